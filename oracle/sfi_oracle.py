@@ -1,0 +1,189 @@
+"""ctypes front end of the C oracle (test infrastructure only; never imported by the product path).
+
+Marshals numpy arrays into oracle/libsfi_oracle.so; no arithmetic happens here.
+bf16 tensors are ``numpy.uint16`` bit patterns, layouts as in sfi_oracle.c.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import math
+import os
+from dataclasses import dataclass
+from typing import Optional, Tuple
+
+import numpy as np
+
+from .build import LIB, build_oracle
+
+_lib = None
+
+
+class _Cfg(C.Structure):
+    _fields_ = [
+        ("B", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("d", C.c_int32),
+        ("n_sink", C.c_int32), ("recent", C.c_int32),
+        ("scale", C.c_double),
+        ("k_stride_b", C.c_int64), ("k_stride_h", C.c_int64), ("k_stride_t", C.c_int64),
+        ("v_stride_b", C.c_int64), ("v_stride_h", C.c_int64), ("v_stride_t", C.c_int64),
+        ("mode", C.c_int32), ("nms_radius", C.c_int32),
+        ("alpha", C.c_double),
+        ("gamma", C.c_double), ("beta", C.c_double), ("p", C.c_double), ("eta", C.c_double),
+        ("lambda_clip", C.c_double), ("alpha_soft", C.c_double), ("alpha_cross", C.c_double),
+        ("temp", C.c_double), ("eps", C.c_double),
+    ]
+
+
+@dataclass
+class SelectorParams:
+    """Selector hyper-parameters.  lambda_clip, alpha_soft, alpha_cross, eps are the paper's defaults
+    (Sec. 5 "Default SFI configuration", Sec. 3.2); the rest are not given by the paper."""
+    mode: int = 0
+    alpha: float = 1.0
+    gamma: float = 0.5
+    beta: float = 1.0
+    p: float = 2.0
+    eta: float = 0.5
+    lambda_clip: float = 0.02
+    alpha_soft: float = 0.5
+    alpha_cross: float = 0.35
+    temp: float = 1.0
+    eps: float = 1e-8
+    nms_radius: int = 2
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB):
+            build_oracle()
+        _lib = C.CDLL(LIB)
+        _lib.sfio_num_threads.restype = C.c_int
+    return _lib
+
+
+def num_threads() -> int:
+    return int(lib().sfio_num_threads())
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _cfg(B, Hq, Hkv, d, n_sink, recent, scale, K=None, V=None, sp: Optional[SelectorParams] = None) -> _Cfg:
+    sp = sp or SelectorParams()
+    c = _Cfg()
+    c.B, c.Hq, c.Hkv, c.d, c.n_sink, c.recent = B, Hq, Hkv, d, n_sink, recent
+    c.scale = (1.0 / math.sqrt(d)) if scale is None else float(scale)
+    if K is not None:
+        assert K.dtype == np.uint16 and K.ndim == 4 and K.strides[3] == 2
+        c.k_stride_b, c.k_stride_h, c.k_stride_t = (s // 2 for s in K.strides[:3])
+    if V is not None:
+        assert V.dtype == np.uint16 and V.ndim == 4 and V.strides[3] == 2
+        c.v_stride_b, c.v_stride_h, c.v_stride_t = (s // 2 for s in V.strides[:3])
+    c.mode, c.nms_radius = sp.mode, sp.nms_radius
+    c.alpha, c.gamma, c.beta, c.p, c.eta = sp.alpha, sp.gamma, sp.beta, sp.p, sp.eta
+    c.lambda_clip, c.alpha_soft, c.alpha_cross, c.temp, c.eps = (
+        sp.lambda_clip, sp.alpha_soft, sp.alpha_cross, sp.temp, sp.eps)
+    return c
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def logits(q: np.ndarray, K: np.ndarray, ctx_len, scale=None) -> np.ndarray:
+    """l[b, g, j] = scale * <q[b, g], K[b, g // G, j]>; float64 [B, Hq, max ctx_len], 0 beyond ctx_len."""
+    B, Hq, d = q.shape
+    Hkv = K.shape[1]
+    ctx_len = _i32(ctx_len)
+    ld = int(max(1, ctx_len.max()))
+    out = np.zeros((B, Hq, ld), dtype=np.float64)
+    c = _cfg(B, Hq, Hkv, d, 0, 0, scale, K=K)
+    q = np.ascontiguousarray(q)
+    rc = lib().sfio_logits(C.byref(c), _p(q), _p(K), _p(ctx_len), _p(out), C.c_int64(ld))
+    assert rc == 0
+    return out
+
+
+def dense(q: np.ndarray, K: np.ndarray, V: np.ndarray, ctx_len, scale=None) -> np.ndarray:
+    """Dense attention over [0, ctx_len[b]): float64 [B, Hq, d]."""
+    B, Hq, d = q.shape
+    Hkv = K.shape[1]
+    ctx_len = _i32(ctx_len)
+    out = np.zeros((B, Hq, d), dtype=np.float64)
+    c = _cfg(B, Hq, Hkv, d, 0, 0, scale, K=K, V=V)
+    q = np.ascontiguousarray(q)
+    rc = lib().sfio_dense(C.byref(c), _p(q), _p(K), _p(V), _p(ctx_len), _p(out))
+    assert rc == 0
+    return out
+
+
+def sparse(q, K, V, sel_idx, n_sel, recent_start, ctx_len, n_sink: int, scale=None) -> np.ndarray:
+    """Sparse attention over [0, n_sink) U sel_idx[b, h, :n_sel] U [recent_start[b], ctx_len[b])."""
+    B, Hq, d = q.shape
+    Hkv = K.shape[1]
+    ctx_len, recent_start = _i32(ctx_len), _i32(recent_start)
+    sel_idx, n_sel = _i32(sel_idx), _i32(n_sel)
+    assert sel_idx.ndim == 3 and sel_idx.shape[:2] == (B, Hkv) and n_sel.shape == (B, Hkv)
+    out = np.zeros((B, Hq, d), dtype=np.float64)
+    c = _cfg(B, Hq, Hkv, d, n_sink, 0, scale, K=K, V=V)
+    q = np.ascontiguousarray(q)
+    rc = lib().sfio_sparse(C.byref(c), _p(q), _p(K), _p(V), _p(sel_idx), _p(n_sel),
+                           C.c_int64(sel_idx.shape[2]), _p(recent_start), _p(ctx_len), _p(out))
+    if rc != 0:
+        raise ValueError("sel_idx entry outside [0, ctx_len)")
+    return out
+
+
+def selector_from_logits(lg: np.ndarray, ctx_len, Hkv: int, budget: int, n_sink: int, recent: int,
+                         sp: Optional[SelectorParams] = None, knorm: Optional[np.ndarray] = None,
+                         debug: bool = False):
+    """Algorithm 2 on given logits float64 [B, Hq, ld].  Returns (sel_idx, n_sel, z[, dbg dict])."""
+    sp = sp or SelectorParams()
+    lg = np.ascontiguousarray(lg, dtype=np.float64)
+    B, Hq, ld = lg.shape
+    ctx_len = _i32(ctx_len)
+    assert int(ctx_len.max()) <= ld
+    if sp.mode != 0:
+        assert knorm is not None and knorm.shape == (B, Hkv, ld)
+        knorm = np.ascontiguousarray(knorm, dtype=np.float64)
+    sel = np.full((B, Hkv, max(budget, 1)), -1, dtype=np.int32)
+    nsel = np.zeros((B, Hkv), dtype=np.int32)
+    z = np.zeros((B, Hkv, ld), dtype=np.float64)
+    dbg = {}
+    if debug:
+        for k in ("f", "r", "s", "zbase", "znms"):
+            dbg[k] = np.zeros((B, Hkv, ld), dtype=np.float64)
+        dbg["lambda"] = np.zeros((B, Hkv), dtype=np.float64)
+    c = _cfg(B, Hq, Hkv, 1, n_sink, recent, 1.0, sp=sp)
+    sel_c = np.ascontiguousarray(sel[:, :, :budget]) if budget > 0 else sel
+    rc = lib().sfio_selector_from_logits(
+        C.byref(c), _p(lg), _p(knorm), C.c_int64(ld), _p(ctx_len), C.c_int32(budget), _p(sel_c), _p(nsel),
+        _p(z), C.c_int64(ld), _p(dbg.get("f")), _p(dbg.get("r")), _p(dbg.get("s")), _p(dbg.get("zbase")),
+        _p(dbg.get("znms")), _p(dbg.get("lambda")))
+    assert rc == 0
+    if budget > 0:
+        sel = sel_c
+    return (sel, nsel, z, dbg) if debug else (sel, nsel, z)
+
+
+def selector(q, K, ctx_len, budget: int, n_sink: int, recent: int, scale=None,
+             sp: Optional[SelectorParams] = None) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Slow-step Selector from q and K: (sel_idx int32 [B,Hkv,budget], n_sel int32 [B,Hkv], z float64 [B,Hkv,ld])."""
+    sp = sp or SelectorParams()
+    B, Hq, d = q.shape
+    Hkv = K.shape[1]
+    ctx_len = _i32(ctx_len)
+    ld = int(max(1, ctx_len.max()))
+    sel = np.full((B, Hkv, max(budget, 1)), -1, dtype=np.int32)
+    nsel = np.zeros((B, Hkv), dtype=np.int32)
+    z = np.zeros((B, Hkv, ld), dtype=np.float64)
+    c = _cfg(B, Hq, Hkv, d, n_sink, recent, scale, K=K, sp=sp)
+    q = np.ascontiguousarray(q)
+    sel_c = np.ascontiguousarray(sel[:, :, :budget]) if budget > 0 else sel
+    rc = lib().sfio_selector(C.byref(c), _p(q), _p(K), _p(ctx_len), C.c_int32(budget), _p(sel_c), _p(nsel),
+                             _p(z), C.c_int64(ld))
+    assert rc == 0
+    if budget > 0:
+        sel = sel_c
+    return sel, nsel, z
