@@ -1,0 +1,171 @@
+/*
+ * libsfi — decode-attention hot path of Slow-Fast Inference for AMD MI355X (gfx950).
+ *
+ * One attention layer, single-query (decode) GQA attention over a bf16 KV cache, done two ways:
+ *
+ *   slow step  dense attention over the whole prefix, plus the Selector that turns the dense
+ *              logits into a refreshed per-KV-head index set (paper Sec. 3.1 "Slow step",
+ *              Sec. 3.2-3.3, Algorithm 2);
+ *   fast step  sparse attention over  I = I_sink U I_sel U I_recent  only
+ *              (paper Eq. index_set, Eq. index_set_head, Sec. 3.1 "Fast step").
+ *
+ * Conventions used by every call
+ * -------------------------------
+ *   B sequences, Hq query heads, Hkv KV heads, G = Hq / Hkv, head_dim d = 128.
+ *   Positions are 0-based.  ctx_len[b] = number of rows of sequence b in the cache, the current
+ *   token's row included.
+ *   I_sink   = [0, min(n_sink, ctx_len))
+ *   I_recent = [recent_start, ctx_len),  normally recent_start = max(n_sink, ctx_len - recent)
+ *   J        = [n_sink, ctx_len - recent)   the allowed candidate set (paper Eq. allowed_set)
+ *   I_sel    = sel_idx[b, h, 0 : n_sel[b, h]]   a subset of J, shared by the G query heads of KV
+ *              head h (paper Sec. 3.1, "maintained per KV head").
+ *
+ *   q        bf16  [B, Hq, 128] contiguous.
+ *   K, V     bf16, element (b, h, t, c) at  base + b*stride_b + h*stride_h + t*stride_t + c
+ *            (strides in elements, given in sfi_config; a row of 128 elements is contiguous;
+ *            row starts must be 16-byte aligned: stride_* multiples of 8, base 16-byte aligned).
+ *   out      fp32  [B, Hq, 128] contiguous.
+ *   sel_idx  int32 [B, Hkv, sel_stride]; n_sel int32 [B, Hkv].
+ *   ctx_len, recent_start int32 [B].
+ *
+ * Every pointer named q, K, V, out, sel_idx, n_sel, ctx_len, recent_start, is_slow and the
+ * workspace is a DEVICE pointer.  sfi_config, sfi_ctx** and the float array of
+ * sfi_stage_times are HOST pointers.
+ *
+ * Ownership: the caller owns every buffer, including the workspace, which must stay alive and
+ * untouched by others until sfi_destroy.  The library allocates no device memory and never
+ * synchronises the device in a hot call: calls enqueue kernels on the given HIP stream
+ * (hipStream_t passed as void*; NULL = the default stream) and return.  Results are valid once
+ * the caller has synchronised that stream.  One context serves one stream at a time: two calls
+ * on the same context must not overlap on the GPU (they share the workspace).
+ *
+ * Errors: every function returning int gives SFI_OK (0) or a negative sfi_status.  Host-checkable
+ * argument errors are reported before anything is launched.  Device-side precondition
+ * violations (an index outside [0, ctx_len), ctx_len > max_ctx) are the caller's
+ * responsibility; they are not detected.
+ */
+#ifndef SFI_H_
+#define SFI_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum sfi_status {
+  SFI_OK = 0,
+  SFI_EINVAL = -1,      /* bad argument: null pointer, value out of range */
+  SFI_EUNSUPPORTED = -2,/* a shape or mode this build does not implement */
+  SFI_EWORKSPACE = -3,  /* workspace too small or misaligned */
+  SFI_EALIGN = -4,      /* pointer or stride alignment violated */
+  SFI_ELAUNCH = -5,     /* the HIP runtime rejected a launch or an event call */
+  SFI_ENOMEM = -6       /* host allocation of the context failed */
+} sfi_status;
+
+typedef struct sfi_config {
+  int32_t batch;        /* B >= 1 */
+  int32_t n_q_heads;    /* Hq, multiple of n_kv_heads, Hq / Hkv <= 16 */
+  int32_t n_kv_heads;   /* Hkv >= 1 */
+  int32_t head_dim;     /* must be 128 */
+  int32_t max_ctx;      /* upper bound of every ctx_len[b] this context will see */
+  int32_t max_budget;   /* upper bound of the Selector budget K */
+  int32_t n_sink;       /* |I_sink|; paper default 4 (Sec. 5 "Default SFI configuration") */
+  int32_t recent;       /* recent window length; paper default 256 */
+  float scale;          /* logit scale; 0 selects 1/sqrt(head_dim) */
+  int32_t selector_mode;/* 0: rank by the evidence f alone (Eqs. selector_pt - selector_f, z_base) */
+  int64_t k_stride_b, k_stride_h, k_stride_t; /* elements */
+  int64_t v_stride_b, v_stride_h, v_stride_t; /* elements */
+} sfi_config;
+
+typedef struct sfi_ctx sfi_ctx; /* opaque; host memory owned by the library */
+
+/* Bytes of device workspace a context of this shape needs (256-byte aligned base expected).
+ * Pure host arithmetic.  Returns 0 if the configuration is invalid. */
+size_t sfi_workspace_bytes(const sfi_config* cfg);
+
+/* Validate cfg, bind the caller's workspace, return a context in *out.
+ * Touches the device only to read its properties and, later, to launch. */
+int sfi_create(const sfi_config* cfg, void* workspace, size_t workspace_bytes, sfi_ctx** out);
+
+/* Frees the host-side context (and its profiling events).  The workspace stays the caller's. */
+int sfi_destroy(sfi_ctx* ctx);
+
+/* Static, human-readable text for a status code. */
+const char* sfi_strerror(int status);
+
+/*
+ * Slow step (paper Algorithm 1 "Slow Step" + Algorithm 2):
+ *   out[b, g, :]     = softmax_j(scale * <q[b,g], K[b,h,j]>) V[b,h,:]  over j in [0, ctx_len[b])
+ *   sel_idx[b, h, :] = the n_sel[b,h] = min(budget, |J|) positions of J with the largest evidence
+ *                      f_h(j) = (1/G) sum_{g in group h} softmax over J of the logits of head g
+ *                      (ranking score z = log(f + 1e-8) is monotone in f); equal scores: the lower
+ *                      position wins; written ascending, entries [n_sel, budget) set to -1.
+ * sel_idx is addressed with row stride `budget`.  max_len: host-side upper bound of ctx_len[]
+ * used only to size the launch (0 = cfg.max_ctx).  1 <= ctx_len[b] <= max_len.
+ */
+int sfi_slow_step(sfi_ctx* ctx, const void* q, const void* K, const void* V, const int32_t* ctx_len,
+                  int32_t max_len, int32_t budget, float* out, int32_t* sel_idx, int32_t* n_sel,
+                  void* stream);
+
+/* Dense attention only (the `out` of a slow step, no Selector).  Same arguments and meaning. */
+int sfi_dense_attn(sfi_ctx* ctx, const void* q, const void* K, const void* V, const int32_t* ctx_len,
+                   int32_t max_len, float* out, void* stream);
+
+/*
+ * Fast step (paper Algorithm 1 "Fast Step"):
+ *   out[b, g, :] = attention of q[b,g] over rows
+ *                  [0, min(n_sink, ctx_len)) U sel_idx[b,h,0:n_sel[b,h]] U [recent_start[b], ctx_len[b]).
+ * Preconditions: the three parts are disjoint; sel entries lie in [n_sink, recent_start[b]);
+ * n_sink <= recent_start[b] <= ctx_len[b] (or recent_start = ctx_len < n_sink);
+ * n_sel[b,h] <= sel_stride <= cfg.max_budget.  sel_idx / n_sel are read-only here.
+ */
+int sfi_fast_step(sfi_ctx* ctx, const void* q, const void* K, const void* V, const int32_t* sel_idx,
+                  const int32_t* n_sel, int32_t sel_stride, const int32_t* recent_start,
+                  const int32_t* ctx_len, float* out, void* stream);
+
+/*
+ * Ragged mix: sequence b takes a slow step if is_slow[b] != 0 (uint8, device) and a fast step
+ * otherwise; slow sequences refresh their rows of sel_idx / n_sel in place (row stride `budget`),
+ * fast sequences read theirs.  No host synchronisation decides the mode.
+ */
+int sfi_mixed_step(sfi_ctx* ctx, const void* q, const void* K, const void* V, const uint8_t* is_slow,
+                   const int32_t* ctx_len, const int32_t* recent_start, int32_t max_len, int32_t budget,
+                   float* out, int32_t* sel_idx, int32_t* n_sel, void* stream);
+
+/* State update between decode steps, on the device (paper Algorithm 1, "update I_recent"):
+ * ctx_len[b] += 1;  recent_start[b] = max(n_sink, ctx_len[b] - recent). */
+int sfi_advance(sfi_ctx* ctx, int32_t* ctx_len, int32_t* recent_start, void* stream);
+
+/*
+ * Per-kernel timing for benchmarks.  With profiling on, each hot call brackets every kernel it
+ * launches with HIP events on the caller's stream; sfi_stage_times waits for the last call's
+ * events and returns their elapsed milliseconds (0 for stages the call did not run).
+ * Not for production loops: event records add launch gaps.
+ */
+enum {
+  SFI_STAGE_ATTN = 0,     /* split attention kernel (dense or gather) */
+  SFI_STAGE_MERGE = 1,    /* split merge */
+  SFI_STAGE_SCORE = 2,    /* evidence + first radix histogram */
+  SFI_STAGE_CAND = 3,     /* threshold-bin candidates */
+  SFI_STAGE_COUNT = 4,    /* exact threshold + per-segment counts */
+  SFI_STAGE_WRITE = 5,    /* ordered index write */
+  SFI_STAGE_ATTN2 = 6,    /* second attention kernel of a mixed step (the gather part) */
+  SFI_N_STAGES = 8
+};
+int sfi_set_profiling(sfi_ctx* ctx, int on);
+int sfi_stage_times(sfi_ctx* ctx, float* ms /* host, [SFI_N_STAGES] */);
+
+/* Launch-geometry knobs for sweeps (values <= 0 keep the current setting):
+ * dense_target_wgs     workgroups the dense launch aims for (default 4 per compute unit);
+ * fast_tiles_per_wave  32-row tiles each wave of the gather launch gets (default 2). */
+int sfi_set_tuning(sfi_ctx* ctx, int32_t dense_target_wgs, int32_t fast_tiles_per_wave);
+
+/* Launch geometry of the last call (for reports): split workgroups per (sequence, KV head). */
+int sfi_query_splits(const sfi_ctx* ctx, int32_t* dense_splits, int32_t* fast_splits);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SFI_H_ */

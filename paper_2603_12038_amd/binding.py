@@ -1,0 +1,199 @@
+"""ctypes binding of libsfi.so: argument marshalling only; every step of the path runs in the HIP kernels.
+
+Functions carry the names of the C entry points declared in include/sfi.h.  Tensors are torch
+tensors on the GPU (torch is used for device memory and streams only); their ``data_ptr()`` goes
+straight to the library.  There is no fallback: if the library is not built, loading fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Tuple
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libsfi.so")
+
+SFI_N_STAGES = 8
+STAGE_NAMES = ("attn", "merge", "score", "cand", "count", "write", "attn_gather_mixed", "unused")
+
+
+class SfiError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {sfi_strerror(code)} ({code})")
+
+
+class SfiConfig(C.Structure):
+    _fields_ = [
+        ("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+        ("max_ctx", C.c_int32), ("max_budget", C.c_int32), ("n_sink", C.c_int32), ("recent", C.c_int32),
+        ("scale", C.c_float), ("selector_mode", C.c_int32),
+        ("k_stride_b", C.c_int64), ("k_stride_h", C.c_int64), ("k_stride_t", C.c_int64),
+        ("v_stride_b", C.c_int64), ("v_stride_h", C.c_int64), ("v_stride_t", C.c_int64),
+    ]
+
+
+_lib: Optional[C.CDLL] = None
+
+EXPORTS = ("sfi_workspace_bytes", "sfi_create", "sfi_destroy", "sfi_strerror", "sfi_slow_step", "sfi_dense_attn",
+           "sfi_fast_step", "sfi_mixed_step", "sfi_advance", "sfi_set_profiling", "sfi_stage_times",
+           "sfi_set_tuning", "sfi_query_splits")
+
+
+def load_library() -> C.CDLL:
+    """Load the in-tree libsfi.so; raises if it has not been built (no fallback path exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(f"{LIB_PATH} is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    lib.sfi_workspace_bytes.restype = C.c_size_t
+    lib.sfi_workspace_bytes.argtypes = [C.POINTER(SfiConfig)]
+    lib.sfi_create.restype = C.c_int
+    lib.sfi_create.argtypes = [C.POINTER(SfiConfig), vp, C.c_size_t, C.POINTER(vp)]
+    lib.sfi_destroy.restype = C.c_int
+    lib.sfi_destroy.argtypes = [vp]
+    lib.sfi_strerror.restype = C.c_char_p
+    lib.sfi_strerror.argtypes = [C.c_int]
+    lib.sfi_slow_step.restype = C.c_int
+    lib.sfi_slow_step.argtypes = [vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
+    lib.sfi_dense_attn.restype = C.c_int
+    lib.sfi_dense_attn.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp]
+    lib.sfi_fast_step.restype = C.c_int
+    lib.sfi_fast_step.argtypes = [vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
+    lib.sfi_mixed_step.restype = C.c_int
+    lib.sfi_mixed_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
+    lib.sfi_advance.restype = C.c_int
+    lib.sfi_advance.argtypes = [vp, vp, vp, vp]
+    lib.sfi_set_profiling.restype = C.c_int
+    lib.sfi_set_profiling.argtypes = [vp, C.c_int]
+    lib.sfi_stage_times.restype = C.c_int
+    lib.sfi_stage_times.argtypes = [vp, C.POINTER(C.c_float)]
+    lib.sfi_set_tuning.restype = C.c_int
+    lib.sfi_set_tuning.argtypes = [vp, i32, i32]
+    lib.sfi_query_splits.restype = C.c_int
+    lib.sfi_query_splits.argtypes = [vp, C.POINTER(i32), C.POINTER(i32)]
+    _lib = lib
+    return lib
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != 0:
+        raise SfiError(rc, where)
+
+
+def sfi_strerror(code: int) -> str:
+    return load_library().sfi_strerror(code).decode()
+
+
+def sfi_workspace_bytes(cfg: SfiConfig) -> int:
+    return int(load_library().sfi_workspace_bytes(C.byref(cfg)))
+
+
+def sfi_create(cfg: SfiConfig, workspace, workspace_bytes: int) -> int:
+    """Returns the opaque context handle (an integer address); raises SfiError on a bad configuration."""
+    h = C.c_void_p()
+    _check(load_library().sfi_create(C.byref(cfg), _ptr(workspace), workspace_bytes, C.byref(h)), "sfi_create")
+    return h.value
+
+
+def sfi_destroy(ctx: int) -> None:
+    _check(load_library().sfi_destroy(ctx), "sfi_destroy")
+
+
+def sfi_slow_step(ctx, q, K, V, ctx_len, max_len, budget, out, sel_idx, n_sel, stream=None) -> None:
+    _check(load_library().sfi_slow_step(ctx, _ptr(q), _ptr(K), _ptr(V), _ptr(ctx_len), max_len, budget, _ptr(out),
+                                        _ptr(sel_idx), _ptr(n_sel), _stream(stream)), "sfi_slow_step")
+
+
+def sfi_dense_attn(ctx, q, K, V, ctx_len, max_len, out, stream=None) -> None:
+    _check(load_library().sfi_dense_attn(ctx, _ptr(q), _ptr(K), _ptr(V), _ptr(ctx_len), max_len, _ptr(out),
+                                         _stream(stream)), "sfi_dense_attn")
+
+
+def sfi_fast_step(ctx, q, K, V, sel_idx, n_sel, sel_stride, recent_start, ctx_len, out, stream=None) -> None:
+    _check(load_library().sfi_fast_step(ctx, _ptr(q), _ptr(K), _ptr(V), _ptr(sel_idx), _ptr(n_sel), sel_stride,
+                                        _ptr(recent_start), _ptr(ctx_len), _ptr(out), _stream(stream)),
+           "sfi_fast_step")
+
+
+def sfi_mixed_step(ctx, q, K, V, is_slow, ctx_len, recent_start, max_len, budget, out, sel_idx, n_sel,
+                   stream=None) -> None:
+    _check(load_library().sfi_mixed_step(ctx, _ptr(q), _ptr(K), _ptr(V), _ptr(is_slow), _ptr(ctx_len),
+                                         _ptr(recent_start), max_len, budget, _ptr(out), _ptr(sel_idx),
+                                         _ptr(n_sel), _stream(stream)), "sfi_mixed_step")
+
+
+def sfi_advance(ctx, ctx_len, recent_start, stream=None) -> None:
+    _check(load_library().sfi_advance(ctx, _ptr(ctx_len), _ptr(recent_start), _stream(stream)), "sfi_advance")
+
+
+def sfi_set_profiling(ctx, on: bool) -> None:
+    _check(load_library().sfi_set_profiling(ctx, 1 if on else 0), "sfi_set_profiling")
+
+
+def sfi_stage_times(ctx):
+    arr = (C.c_float * SFI_N_STAGES)()
+    _check(load_library().sfi_stage_times(ctx, arr), "sfi_stage_times")
+    return [float(x) for x in arr]
+
+
+def sfi_set_tuning(ctx, dense_target_wgs: int = 0, fast_tiles_per_wave: int = 0) -> None:
+    _check(load_library().sfi_set_tuning(ctx, dense_target_wgs, fast_tiles_per_wave), "sfi_set_tuning")
+
+
+def sfi_query_splits(ctx) -> Tuple[int, int]:
+    d, f = C.c_int32(), C.c_int32()
+    _check(load_library().sfi_query_splits(ctx, C.byref(d), C.byref(f)), "sfi_query_splits")
+    return d.value, f.value
+
+
+class SfiContext:
+    """Owns the workspace tensor and the context handle for one (shape, K/V layout)."""
+
+    def __init__(self, B, Hq, Hkv, max_ctx, max_budget, n_sink, recent, K, V, scale: float = 0.0, device="cuda"):
+        import torch
+
+        assert K.dtype == torch.bfloat16 and V.dtype == torch.bfloat16 and K.dim() == 4 and K.stride(3) == 1
+        cfg = SfiConfig()
+        cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim = B, Hq, Hkv, K.shape[3]
+        cfg.max_ctx, cfg.max_budget, cfg.n_sink, cfg.recent = max_ctx, max_budget, n_sink, recent
+        cfg.scale, cfg.selector_mode = scale, 0
+        cfg.k_stride_b, cfg.k_stride_h, cfg.k_stride_t = K.stride(0), K.stride(1), K.stride(2)
+        cfg.v_stride_b, cfg.v_stride_h, cfg.v_stride_t = V.stride(0), V.stride(1), V.stride(2)
+        self.cfg = cfg
+        nbytes = sfi_workspace_bytes(cfg)
+        if nbytes == 0:
+            raise SfiError(-1, "sfi_workspace_bytes")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        self.handle = sfi_create(cfg, self.workspace, nbytes)
+
+    def close(self):
+        if self.handle:
+            sfi_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

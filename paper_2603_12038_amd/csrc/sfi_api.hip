@@ -1,0 +1,397 @@
+// C-ABI of libsfi: argument checks, workspace carving, launch sequencing.  No arithmetic here.
+#include <math.h>
+#include <new>
+#include <string.h>
+
+#include "sfi_internal.h"
+
+using namespace sfi;
+
+struct sfi_ctx {
+  sfi_config cfg;
+  float scale;
+  int G;
+  Workspace ws;
+  int n_cu;
+  int dense_target_wgs;     // workgroups the dense launch aims for
+  int fast_tiles_per_wave;  // 32-row tiles each wave of the gather launch should get
+  int last_dense_splits, last_fast_splits;
+  int profiling;
+  bool events_ready;
+  bool stage_used[SFI_N_STAGES];
+  hipEvent_t ev[SFI_N_STAGES][2];
+};
+
+namespace {
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+int validate(const sfi_config* c) {
+  if (c == nullptr) return SFI_EINVAL;
+  if (c->batch < 1 || c->n_kv_heads < 1 || c->n_q_heads < 1 || c->max_ctx < 1 || c->max_budget < 0 ||
+      c->n_sink < 0 || c->recent < 0 || !(c->scale >= 0.f))
+    return SFI_EINVAL;
+  if (c->n_q_heads % c->n_kv_heads != 0) return SFI_EINVAL;
+  if (c->head_dim != kHeadDim) return SFI_EUNSUPPORTED;
+  if (c->n_q_heads / c->n_kv_heads > 16) return SFI_EUNSUPPORTED;
+  if (c->selector_mode != 0) return SFI_EUNSUPPORTED;
+  if ((int64_t)c->max_ctx > (int64_t)1 << 30) return SFI_EUNSUPPORTED;
+  const int64_t st[6] = {c->k_stride_b, c->k_stride_h, c->k_stride_t, c->v_stride_b, c->v_stride_h, c->v_stride_t};
+  for (int i = 0; i < 6; ++i) {
+    if (st[i] < 0) return SFI_EINVAL;
+    if (st[i] % 8 != 0) return SFI_EALIGN;
+  }
+  if (c->k_stride_t < kHeadDim || c->v_stride_t < kHeadDim) return SFI_EINVAL;
+  return SFI_OK;
+}
+
+// Carves the workspace; base may be null (size computation only).  Returns total bytes.
+size_t carve(const sfi_config* c, char* base, Workspace* ws) {
+  const int64_t B = c->batch, Hq = c->n_q_heads, Hkv = c->n_kv_heads;
+  const int64_t ld = (int64_t)align_up((size_t)c->max_ctx, kSelSeg);
+  const int n_seg = (int)(ld / kSelSeg);
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    char* p = base ? base + off : nullptr;
+    off += align_up(bytes, 256);
+    return p;
+  };
+  ws->part = (float*)take((size_t)(B * Hq) * kSlotCap * kPartStride * sizeof(float));
+  ws->logits = (float*)take((size_t)(B * Hq) * ld * sizeof(float));
+  ws->keys = (uint32_t*)take((size_t)(B * Hkv) * ld * sizeof(uint32_t));
+  ws->cand = (uint32_t*)take((size_t)(B * Hkv) * ld * sizeof(uint32_t));
+  ws->hist1 = (uint32_t*)take((size_t)(B * Hkv) * kHist1Bins * sizeof(uint32_t));
+  ws->state = (uint32_t*)take((size_t)(B * Hkv) * kStateWords * sizeof(uint32_t));
+  ws->segcnt = (uint32_t*)take((size_t)(B * Hkv) * n_seg * 2 * sizeof(uint32_t));
+  ws->ld_pos = ld;
+  ws->n_seg_cap = n_seg;
+  return off;
+}
+
+inline bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+
+int dense_splits_for(const sfi_ctx* x, int max_len) {
+  const int nJ = max_len - x->cfg.recent - x->cfg.n_sink;
+  const int tiles = nJ > 0 ? (nJ + kTile - 1) / kTile : 0;
+  const int pairs = x->cfg.batch * x->cfg.n_kv_heads;
+  int s = (x->dense_target_wgs + pairs - 1) / pairs;
+  const int cap = (tiles + kWaves - 1) / kWaves;
+  if (s > cap) s = cap;
+  if (s > kMaxSplits) s = kMaxSplits;
+  if (s < 1) s = 1;
+  return s;
+}
+
+int fast_splits_for(const sfi_ctx* x, int sel_stride) {
+  const int rows = x->cfg.n_sink + sel_stride + x->cfg.recent;
+  const int tiles = (rows + kTile - 1) / kTile;
+  int s = (tiles + kWaves * x->fast_tiles_per_wave - 1) / (kWaves * x->fast_tiles_per_wave);
+  if (s > kMaxSplits) s = kMaxSplits;
+  if (s < 1) s = 1;
+  return s;
+}
+
+struct StageTimer {
+  sfi_ctx* x;
+  hipStream_t s;
+  int stage;
+  bool ok;
+  StageTimer(sfi_ctx* ctx, hipStream_t st, int stg) : x(ctx), s(st), stage(stg), ok(true) {
+    if (x->profiling) {
+      ok = hipEventRecord(x->ev[stage][0], s) == hipSuccess;
+      x->stage_used[stage] = true;
+    }
+  }
+  bool stop() {
+    if (x->profiling) ok = ok && hipEventRecord(x->ev[stage][1], s) == hipSuccess;
+    return ok;
+  }
+};
+
+void fill_attn(const sfi_ctx* x, AttnArgs* a, const void* q, const void* K, const void* V,
+               const int32_t* ctx_len) {
+  memset(a, 0, sizeof(*a));
+  const sfi_config& c = x->cfg;
+  a->q = (const uint16_t*)q;
+  a->K = (const uint16_t*)K;
+  a->V = (const uint16_t*)V;
+  a->k_sb = c.k_stride_b; a->k_sh = c.k_stride_h; a->k_st = c.k_stride_t;
+  a->v_sb = c.v_stride_b; a->v_sh = c.v_stride_h; a->v_st = c.v_stride_t;
+  a->ctx_len = ctx_len;
+  a->part = x->ws.part;
+  a->ld_pos = x->ws.ld_pos;
+  a->Hq = c.n_q_heads; a->Hkv = c.n_kv_heads; a->G = x->G;
+  a->n_sink = c.n_sink; a->recent = c.recent;
+  a->scale = x->scale;
+}
+
+void fill_sel(const sfi_ctx* x, SelArgs* s, const int32_t* ctx_len, const uint8_t* is_slow, int budget,
+              int n_split, int32_t* sel_idx, int32_t* n_sel) {
+  memset(s, 0, sizeof(*s));
+  const sfi_config& c = x->cfg;
+  s->part = x->ws.part; s->logits = x->ws.logits; s->keys = x->ws.keys; s->cand = x->ws.cand;
+  s->hist1 = x->ws.hist1; s->state = x->ws.state; s->segcnt = x->ws.segcnt;
+  s->ctx_len = ctx_len; s->is_slow = is_slow; s->sel_idx = sel_idx; s->n_sel = n_sel;
+  s->ld_pos = x->ws.ld_pos; s->n_seg_cap = x->ws.n_seg_cap;
+  s->Hq = c.n_q_heads; s->Hkv = c.n_kv_heads; s->G = x->G;
+  s->n_sink = c.n_sink; s->recent = c.recent; s->n_split = n_split; s->budget = budget;
+}
+
+#define SFI_TRY(expr)                         \
+  do {                                        \
+    if ((expr) != hipSuccess) return SFI_ELAUNCH; \
+  } while (0)
+
+// Selector kernels after a dense launch that exposed logits.
+int run_selector(sfi_ctx* x, const SelArgs& sa, int max_len, hipStream_t st) {
+  const int B = x->cfg.batch;
+  const int nJ = max_len - x->cfg.recent - x->cfg.n_sink;
+  int n_seg = nJ > 0 ? (nJ + kSelSeg - 1) / kSelSeg : 1;
+  if (n_seg > x->ws.n_seg_cap) n_seg = x->ws.n_seg_cap;
+  { StageTimer t(x, st, SFI_STAGE_SCORE); SFI_TRY(launch_sel_score(sa, B, n_seg, st)); if (!t.stop()) return SFI_ELAUNCH; }
+  { StageTimer t(x, st, SFI_STAGE_CAND);  SFI_TRY(launch_sel_cand(sa, B, n_seg, st));  if (!t.stop()) return SFI_ELAUNCH; }
+  { StageTimer t(x, st, SFI_STAGE_COUNT); SFI_TRY(launch_sel_count(sa, B, n_seg, st)); if (!t.stop()) return SFI_ELAUNCH; }
+  { StageTimer t(x, st, SFI_STAGE_WRITE); SFI_TRY(launch_sel_write(sa, B, n_seg, st)); if (!t.stop()) return SFI_ELAUNCH; }
+  return SFI_OK;
+}
+
+int check_common(const sfi_ctx* x, const void* q, const void* K, const void* V, const int32_t* ctx_len,
+                 const float* out) {
+  if (x == nullptr || q == nullptr || K == nullptr || V == nullptr || ctx_len == nullptr || out == nullptr)
+    return SFI_EINVAL;
+  if (misaligned(q, 16) || misaligned(K, 16) || misaligned(V, 16) || misaligned(out, 16) || misaligned(ctx_len, 4))
+    return SFI_EALIGN;
+  return SFI_OK;
+}
+
+int resolve_max_len(const sfi_ctx* x, int32_t max_len, int* out) {
+  if (max_len < 0 || max_len > x->cfg.max_ctx) return SFI_EINVAL;
+  *out = max_len == 0 ? x->cfg.max_ctx : max_len;
+  return SFI_OK;
+}
+
+void clear_stage_flags(sfi_ctx* x) {
+  for (int i = 0; i < SFI_N_STAGES; ++i) x->stage_used[i] = false;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t sfi_workspace_bytes(const sfi_config* cfg) {
+  if (validate(cfg) != SFI_OK) return 0;
+  Workspace ws;
+  return carve(cfg, nullptr, &ws);
+}
+
+int sfi_create(const sfi_config* cfg, void* workspace, size_t workspace_bytes, sfi_ctx** out) {
+  if (out == nullptr) return SFI_EINVAL;
+  *out = nullptr;
+  const int v = validate(cfg);
+  if (v != SFI_OK) return v;
+  if (workspace == nullptr) return SFI_EINVAL;
+  if (misaligned(workspace, 256)) return SFI_EWORKSPACE;
+  Workspace ws;
+  const size_t need = carve(cfg, (char*)workspace, &ws);
+  if (workspace_bytes < need) return SFI_EWORKSPACE;
+  sfi_ctx* x = new (std::nothrow) sfi_ctx;
+  if (x == nullptr) return SFI_ENOMEM;
+  memset(x, 0, sizeof(*x));
+  x->cfg = *cfg;
+  x->scale = cfg->scale > 0.f ? cfg->scale : 1.0f / sqrtf((float)cfg->head_dim);
+  x->G = cfg->n_q_heads / cfg->n_kv_heads;
+  x->ws = ws;
+  x->n_cu = 256;
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
+      prop.multiProcessorCount > 0)
+    x->n_cu = prop.multiProcessorCount;
+  else
+    (void)hipGetLastError();  // no device here: keep the MI355X default
+  x->dense_target_wgs = 4 * x->n_cu;
+  x->fast_tiles_per_wave = 2;
+  *out = x;
+  return SFI_OK;
+}
+
+int sfi_destroy(sfi_ctx* x) {
+  if (x == nullptr) return SFI_EINVAL;
+  if (x->events_ready)
+    for (int i = 0; i < SFI_N_STAGES; ++i) {
+      (void)hipEventDestroy(x->ev[i][0]);
+      (void)hipEventDestroy(x->ev[i][1]);
+    }
+  delete x;
+  return SFI_OK;
+}
+
+const char* sfi_strerror(int status) {
+  switch (status) {
+    case SFI_OK: return "ok";
+    case SFI_EINVAL: return "invalid argument";
+    case SFI_EUNSUPPORTED: return "unsupported shape or mode";
+    case SFI_EWORKSPACE: return "workspace too small or misaligned";
+    case SFI_EALIGN: return "pointer or stride alignment violated";
+    case SFI_ELAUNCH: return "HIP launch or event call failed";
+    case SFI_ENOMEM: return "host allocation failed";
+    default: return "unknown status";
+  }
+}
+
+int sfi_dense_attn(sfi_ctx* x, const void* q, const void* K, const void* V, const int32_t* ctx_len,
+                   int32_t max_len, float* out, void* stream) {
+  int rc = check_common(x, q, K, V, ctx_len, out);
+  if (rc != SFI_OK) return rc;
+  int ml;
+  if ((rc = resolve_max_len(x, max_len, &ml)) != SFI_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  clear_stage_flags(x);
+  AttnArgs a;
+  fill_attn(x, &a, q, K, V, ctx_len);
+  a.n_split = dense_splits_for(x, ml);
+  x->last_dense_splits = a.n_split;
+  { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(a, x->cfg.batch, a.n_split + 1, st)); if (!t.stop()) return SFI_ELAUNCH; }
+  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, a.n_split + 1, 0, 0};
+  { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
+  return SFI_OK;
+}
+
+int sfi_slow_step(sfi_ctx* x, const void* q, const void* K, const void* V, const int32_t* ctx_len,
+                  int32_t max_len, int32_t budget, float* out, int32_t* sel_idx, int32_t* n_sel,
+                  void* stream) {
+  int rc = check_common(x, q, K, V, ctx_len, out);
+  if (rc != SFI_OK) return rc;
+  if (sel_idx == nullptr || n_sel == nullptr) return SFI_EINVAL;
+  if (budget < 0 || budget > x->cfg.max_budget) return SFI_EINVAL;
+  if (misaligned(sel_idx, 4) || misaligned(n_sel, 4)) return SFI_EALIGN;
+  int ml;
+  if ((rc = resolve_max_len(x, max_len, &ml)) != SFI_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  clear_stage_flags(x);
+  AttnArgs a;
+  fill_attn(x, &a, q, K, V, ctx_len);
+  a.n_split = dense_splits_for(x, ml);
+  a.logits = x->ws.logits;
+  a.hist1 = x->ws.hist1;
+  a.state = x->ws.state;
+  x->last_dense_splits = a.n_split;
+  { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(a, x->cfg.batch, a.n_split + 1, st)); if (!t.stop()) return SFI_ELAUNCH; }
+  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, a.n_split + 1, 0, 0};
+  { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
+  SelArgs sa;
+  fill_sel(x, &sa, ctx_len, nullptr, budget, a.n_split, sel_idx, n_sel);
+  return run_selector(x, sa, ml, st);
+}
+
+int sfi_fast_step(sfi_ctx* x, const void* q, const void* K, const void* V, const int32_t* sel_idx,
+                  const int32_t* n_sel, int32_t sel_stride, const int32_t* recent_start,
+                  const int32_t* ctx_len, float* out, void* stream) {
+  int rc = check_common(x, q, K, V, ctx_len, out);
+  if (rc != SFI_OK) return rc;
+  if (sel_idx == nullptr || n_sel == nullptr || recent_start == nullptr) return SFI_EINVAL;
+  if (sel_stride < 0 || sel_stride > x->cfg.max_budget) return SFI_EINVAL;
+  if (misaligned(sel_idx, 4) || misaligned(n_sel, 4) || misaligned(recent_start, 4)) return SFI_EALIGN;
+  hipStream_t st = (hipStream_t)stream;
+  clear_stage_flags(x);
+  AttnArgs a;
+  fill_attn(x, &a, q, K, V, ctx_len);
+  a.recent_start = recent_start;
+  a.sel_idx = sel_idx;
+  a.n_sel = n_sel;
+  a.sel_stride = sel_stride;
+  a.n_split = fast_splits_for(x, sel_stride);
+  x->last_fast_splits = a.n_split;
+  { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_gather(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
+  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1};
+  { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
+  return SFI_OK;
+}
+
+int sfi_mixed_step(sfi_ctx* x, const void* q, const void* K, const void* V, const uint8_t* is_slow,
+                   const int32_t* ctx_len, const int32_t* recent_start, int32_t max_len, int32_t budget,
+                   float* out, int32_t* sel_idx, int32_t* n_sel, void* stream) {
+  int rc = check_common(x, q, K, V, ctx_len, out);
+  if (rc != SFI_OK) return rc;
+  if (is_slow == nullptr || sel_idx == nullptr || n_sel == nullptr || recent_start == nullptr) return SFI_EINVAL;
+  if (budget < 0 || budget > x->cfg.max_budget) return SFI_EINVAL;
+  if (misaligned(sel_idx, 4) || misaligned(n_sel, 4) || misaligned(recent_start, 4)) return SFI_EALIGN;
+  int ml;
+  if ((rc = resolve_max_len(x, max_len, &ml)) != SFI_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  clear_stage_flags(x);
+
+  AttnArgs d;
+  fill_attn(x, &d, q, K, V, ctx_len);
+  d.is_slow = is_slow;
+  d.n_split = dense_splits_for(x, ml);
+  d.logits = x->ws.logits;
+  d.hist1 = x->ws.hist1;
+  d.state = x->ws.state;
+  x->last_dense_splits = d.n_split;
+  AttnArgs f;
+  fill_attn(x, &f, q, K, V, ctx_len);
+  f.is_slow = is_slow;
+  f.recent_start = recent_start;
+  f.sel_idx = sel_idx;
+  f.n_sel = n_sel;
+  f.sel_stride = budget;
+  f.n_split = fast_splits_for(x, budget);
+  x->last_fast_splits = f.n_split;
+  // the gather part reads last segment's sel rows of fast sequences; the Selector below only
+  // rewrites rows of slow sequences, so the order of the two attention launches is free.
+  { StageTimer t(x, st, SFI_STAGE_ATTN2); SFI_TRY(launch_attn_gather(f, x->cfg.batch, f.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
+  { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(d, x->cfg.batch, d.n_split + 1, st)); if (!t.stop()) return SFI_ELAUNCH; }
+  MergeArgs m{x->ws.part, out, is_slow, x->cfg.n_q_heads, d.n_split + 1, f.n_split, 2};
+  { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
+  SelArgs sa;
+  fill_sel(x, &sa, ctx_len, is_slow, budget, d.n_split, sel_idx, n_sel);
+  return run_selector(x, sa, ml, st);
+}
+
+int sfi_advance(sfi_ctx* x, int32_t* ctx_len, int32_t* recent_start, void* stream) {
+  if (x == nullptr || ctx_len == nullptr || recent_start == nullptr) return SFI_EINVAL;
+  SFI_TRY(launch_advance(ctx_len, recent_start, x->cfg.batch, x->cfg.n_sink, x->cfg.recent, (hipStream_t)stream));
+  return SFI_OK;
+}
+
+int sfi_set_profiling(sfi_ctx* x, int on) {
+  if (x == nullptr) return SFI_EINVAL;
+  if (on && !x->events_ready) {
+    for (int i = 0; i < SFI_N_STAGES; ++i)
+      for (int j = 0; j < 2; ++j)
+        if (hipEventCreate(&x->ev[i][j]) != hipSuccess) return SFI_ELAUNCH;
+    x->events_ready = true;
+  }
+  x->profiling = on ? 1 : 0;
+  clear_stage_flags(x);
+  return SFI_OK;
+}
+
+int sfi_stage_times(sfi_ctx* x, float* ms) {
+  if (x == nullptr || ms == nullptr) return SFI_EINVAL;
+  for (int i = 0; i < SFI_N_STAGES; ++i) {
+    ms[i] = 0.f;
+    if (x->profiling && x->stage_used[i]) {
+      if (hipEventSynchronize(x->ev[i][1]) != hipSuccess) return SFI_ELAUNCH;
+      if (hipEventElapsedTime(&ms[i], x->ev[i][0], x->ev[i][1]) != hipSuccess) return SFI_ELAUNCH;
+    }
+  }
+  return SFI_OK;
+}
+
+int sfi_set_tuning(sfi_ctx* x, int32_t dense_target_wgs, int32_t fast_tiles_per_wave) {
+  if (x == nullptr) return SFI_EINVAL;
+  if (dense_target_wgs > 0) x->dense_target_wgs = dense_target_wgs;
+  if (fast_tiles_per_wave > 0) x->fast_tiles_per_wave = fast_tiles_per_wave;
+  return SFI_OK;
+}
+
+int sfi_query_splits(const sfi_ctx* x, int32_t* dense_splits, int32_t* fast_splits) {
+  if (x == nullptr) return SFI_EINVAL;
+  if (dense_splits) *dense_splits = x->last_dense_splits;
+  if (fast_splits) *fast_splits = x->last_fast_splits;
+  return SFI_OK;
+}
+
+}  // extern "C"

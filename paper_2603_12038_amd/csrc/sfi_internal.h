@@ -1,0 +1,96 @@
+// Internal declarations shared by the HIP translation units of libsfi (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sfi.h"
+
+namespace sfi {
+
+constexpr int kHeadDim = 128;
+constexpr int kTile = 32;          // KV positions per wave iteration (two 16-row MFMA blocks)
+constexpr int kWaves = 4;          // waves per attention workgroup
+constexpr int kAttnThreads = 64 * kWaves;
+constexpr int kPartStride = 132;   // floats per split record: m, l, pad, pad, acc[128]
+constexpr int kMaxSplits = 128;    // split workgroups per (sequence, KV head)
+constexpr int kSlotCap = kMaxSplits + 1;  // + one workgroup for the sink and recent rows
+constexpr int kSelSeg = 2048;      // Selector positions per workgroup
+constexpr int kSelThreads = 256;
+constexpr int kHist1Bits = 12;     // first radix pass: bits [30:19] of the fp32 score
+constexpr int kHist1Bins = 1 << kHist1Bits;
+constexpr int kStateWords = 8;     // per (b, h) Selector state, see SelState
+constexpr float kNeg = -1.0e30f;   // "minus infinity" that stays finite under subtraction
+constexpr float kLog2e = 1.4426950408889634f;
+
+// Per (sequence, KV head) Selector state words.
+enum SelState { ST_CAND = 0, ST_BIN1 = 1, ST_K1 = 2, ST_TAU = 3, ST_TAKE = 4, ST_FLAGS = 5, ST_KSEL = 6 };
+constexpr uint32_t kFlagAll = 1u;   // budget >= |J|: take every position of J
+constexpr uint32_t kFlagNone = 2u;  // nothing to select
+
+struct Workspace {
+  float* part;        // [B*Hq][kSlotCap][kPartStride]
+  float* logits;      // [B*Hq][ld_pos]   J-relative positions
+  uint32_t* keys;     // [B*Hkv][ld_pos]  fp32 bit pattern of the evidence f
+  uint32_t* cand;     // [B*Hkv][ld_pos]  keys falling into the threshold bin
+  uint32_t* hist1;    // [B*Hkv][kHist1Bins]
+  uint32_t* state;    // [B*Hkv][kStateWords]
+  uint32_t* segcnt;   // [B*Hkv][n_seg_cap][2]
+  int64_t ld_pos;     // multiple of kSelSeg
+  int32_t n_seg_cap;
+};
+
+struct AttnArgs {
+  const uint16_t* q;
+  const uint16_t* K;
+  const uint16_t* V;
+  int64_t k_sb, k_sh, k_st, v_sb, v_sh, v_st;
+  const int32_t* ctx_len;
+  const int32_t* recent_start;   // gather mode
+  const int32_t* sel_idx;        // gather mode
+  const int32_t* n_sel;          // gather mode
+  int64_t sel_stride;
+  const uint8_t* is_slow;        // nullptr: every sequence takes part
+  float* part;
+  float* logits;                 // dense mode, nullptr: do not expose logits
+  uint32_t* hist1;               // dense mode with Selector: cleared by the sink/recent workgroup
+  uint32_t* state;
+  int64_t ld_pos;
+  int32_t Hq, Hkv, G, n_sink, recent, n_split;
+  float scale;
+};
+
+struct MergeArgs {
+  const float* part;
+  float* out;
+  const uint8_t* is_slow;
+  int32_t Hq, slots_slow, slots_fast;  // slot counts for slow / fast sequences
+  int32_t mode;                        // 0: all sequences use slots_slow, 1: all use slots_fast, 2: per is_slow
+};
+
+struct SelArgs {
+  const float* part;
+  const float* logits;
+  uint32_t* keys;
+  uint32_t* cand;
+  uint32_t* hist1;
+  uint32_t* state;
+  uint32_t* segcnt;
+  const int32_t* ctx_len;
+  const uint8_t* is_slow;
+  int32_t* sel_idx;
+  int32_t* n_sel;
+  int64_t ld_pos;
+  int32_t n_seg_cap;
+  int32_t Hq, Hkv, G, n_sink, recent, n_split, budget;
+};
+
+hipError_t launch_attn_dense(const AttnArgs& a, int B, int n_slots, hipStream_t s);
+hipError_t launch_attn_gather(const AttnArgs& a, int B, int n_slots, hipStream_t s);
+hipError_t launch_merge(const MergeArgs& a, int B, hipStream_t s);
+hipError_t launch_sel_score(const SelArgs& a, int B, int n_seg, hipStream_t s);
+hipError_t launch_sel_cand(const SelArgs& a, int B, int n_seg, hipStream_t s);
+hipError_t launch_sel_count(const SelArgs& a, int B, int n_seg, hipStream_t s);
+hipError_t launch_sel_write(const SelArgs& a, int B, int n_seg, hipStream_t s);
+hipError_t launch_advance(int32_t* ctx_len, int32_t* recent_start, int B, int n_sink, int recent, hipStream_t s);
+
+}  // namespace sfi

@@ -1,0 +1,362 @@
+// Selector on the GPU (paper Algorithm 2, evidence-only ranking) for gfx950.
+//
+// Per (sequence b, KV head h), over the allowed set J (Eq. allowed_set), positions p = j - n_sink:
+//   p_g(j) = softmax over J of the logits of query head g          (Eq. selector_pt)
+//   f(j)   = (1/G) sum_g p_g(j)      (Eqs. selector_mu, selector_f with alpha = 1; the G heads of
+//            the group are the observation window)
+//   z(j)   = log(f(j) + eps)  is monotone in f, so the Top-K of Eq. topk_out is taken on f itself.
+// Top-K is a radix select on the fp32 bit pattern of f (non-negative floats order like unsigned
+// integers): a 12-bit histogram over all of J, then an exact 19-bit refinement among the few
+// keys of the threshold bin, then an index-ordered compaction that takes every key above the
+// threshold and the lowest-index keys equal to it.  Integer atomics only count, so the result
+// does not depend on scheduling.
+#include "sfi_internal.h"
+
+namespace sfi {
+
+__device__ __forceinline__ float fast_exp2s(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Exclusive prefix sum of one value per thread over a 256-thread block; returns the exclusive
+// prefix and leaves the block total in *total.  scratch: 8 words of LDS.
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* scratch, uint32_t* total) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  uint32_t inc = v;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const uint32_t t = __shfl_up(inc, d);
+    if (lane >= d) inc += t;
+  }
+  __syncthreads();  // scratch may still be read from a previous call
+  if (lane == 63) scratch[w] = inc;
+  __syncthreads();
+  uint32_t base = 0, tot = 0;
+#pragma unroll
+  for (int i = 0; i < kSelThreads / 64; ++i) {
+    const uint32_t s = scratch[i];
+    if (i < w) base += s;
+    tot += s;
+  }
+  *total = tot;
+  return base + inc - v;
+}
+
+// Finds, scanning bins from the highest down, the bin holding the k-th largest key (1-based k,
+// k <= total count).  Writes res[0] = bin, res[1] = how many keys of that bin are still needed.
+// hist may live in LDS or global memory; nbins is a multiple of 256.
+__device__ __forceinline__ void find_kth_desc(const uint32_t* hist, int nbins, uint32_t k, uint32_t* res,
+                                              uint32_t* scratch) {
+  const int per = nbins / kSelThreads;
+  const int hi = nbins - (int)threadIdx.x * per;  // exclusive upper bin of this thread
+  if (threadIdx.x == 0) res[0] = res[1] = 0u;      // defined result even if k exceeds the total
+  uint32_t c = 0;
+  for (int i = 1; i <= per; ++i) c += hist[hi - i];
+  uint32_t total;
+  const uint32_t above = block_excl_scan(c, scratch, &total);
+  if (above < k && k <= above + c) {
+    uint32_t cum = above;
+    for (int i = 1; i <= per; ++i) {
+      const uint32_t hv = hist[hi - i];
+      if (cum + hv >= k) {
+        res[0] = (uint32_t)(hi - i);
+        res[1] = k - cum;
+        break;
+      }
+      cum += hv;
+    }
+  }
+  __syncthreads();
+}
+
+struct Problem {
+  int nJ;        // |J|
+  uint32_t ksel; // min(budget, |J|)
+};
+
+__device__ __forceinline__ Problem problem_of(const SelArgs& a, int b) {
+  Problem p;
+  p.nJ = max(0, a.ctx_len[b] - a.recent - a.n_sink);
+  p.ksel = (uint32_t)min(a.budget, p.nJ);
+  return p;
+}
+
+// ---- stage 1: evidence f, its key, and the 12-bit histogram ------------------------------------
+__global__ __launch_bounds__(kSelThreads) void sel_score_kernel(const SelArgs a) {
+  const int seg = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
+  const Problem pb = problem_of(a, b);
+  const int p_lo = seg * kSelSeg;
+  if (p_lo >= pb.nJ) return;
+  const int tid = threadIdx.x;
+  const int bh = b * a.Hkv + h;
+  const int G = a.G;
+
+  __shared__ uint32_t s_hist[kHist1Bins];
+  __shared__ float s_M[16], s_c[16];
+  for (int i = tid; i < kHist1Bins; i += kSelThreads) s_hist[i] = 0u;
+
+  // J-only softmax statistics of each head of the group, from the split records of J
+  // (records 0 .. n_split-1 of the dense kernel hold m and sum e^{l-m} over their share of J).
+  if (tid < 64) {
+    for (int g = 0; g < G; ++g) {
+      const float* P = a.part + ((int64_t)(b * a.Hq + h * G + g) * kSlotCap) * kPartStride;
+      float m = kNeg;
+      for (int s = tid; s < a.n_split; s += 64) m = fmaxf(m, P[s * kPartStride]);
+#pragma unroll
+      for (int d = 32; d >= 1; d >>= 1) m = fmaxf(m, __shfl_xor(m, d));
+      float z = 0.f;
+      for (int s = tid; s < a.n_split; s += 64)
+        z += P[s * kPartStride + 1] * fast_exp2s((P[s * kPartStride] - m) * kLog2e);
+#pragma unroll
+      for (int d = 32; d >= 1; d >>= 1) z += __shfl_xor(z, d);
+      if (tid == 0) {
+        s_M[g] = m;
+        s_c[g] = 1.0f / ((float)G * z);
+      }
+    }
+  }
+  __syncthreads();
+
+  const float* lg = a.logits + ((int64_t)(b * a.Hq + h * G)) * a.ld_pos;
+  uint32_t* keys = a.keys + (int64_t)bh * a.ld_pos;
+  for (int p = p_lo + tid * 4; p < min(p_lo + kSelSeg, pb.nJ); p += kSelThreads * 4) {
+    float f0 = 0.f, f1 = 0.f, f2 = 0.f, f3 = 0.f;
+    for (int g = 0; g < G; ++g) {
+      const float4 l4 = *reinterpret_cast<const float4*>(lg + (int64_t)g * a.ld_pos + p);
+      const float M = s_M[g], c = s_c[g];
+      f0 += c * fast_exp2s((l4.x - M) * kLog2e);
+      f1 += c * fast_exp2s((l4.y - M) * kLog2e);
+      f2 += c * fast_exp2s((l4.z - M) * kLog2e);
+      f3 += c * fast_exp2s((l4.w - M) * kLog2e);
+    }
+    const uint4 k4 = make_uint4(__float_as_uint(f0), __float_as_uint(f1), __float_as_uint(f2), __float_as_uint(f3));
+    *reinterpret_cast<uint4*>(keys + p) = k4;
+    atomicAdd(&s_hist[k4.x >> 19], 1u);
+    if (p + 1 < pb.nJ) atomicAdd(&s_hist[k4.y >> 19], 1u);
+    if (p + 2 < pb.nJ) atomicAdd(&s_hist[k4.z >> 19], 1u);
+    if (p + 3 < pb.nJ) atomicAdd(&s_hist[k4.w >> 19], 1u);
+  }
+  __syncthreads();
+  uint32_t* gh = a.hist1 + (int64_t)bh * kHist1Bins;
+  for (int i = tid; i < kHist1Bins; i += kSelThreads) {
+    const uint32_t c = s_hist[i];
+    if (c) atomicAdd(&gh[i], c);
+  }
+}
+
+// ---- stage 2: find the threshold bin, collect its keys -----------------------------------------
+__global__ __launch_bounds__(kSelThreads) void sel_cand_kernel(const SelArgs a) {
+  const int seg = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
+  const Problem pb = problem_of(a, b);
+  const int p_lo = seg * kSelSeg;
+  const int tid = threadIdx.x;
+  const int bh = b * a.Hkv + h;
+  uint32_t* st = a.state + (int64_t)bh * kStateWords;
+  if (pb.ksel == 0 || pb.ksel == (uint32_t)pb.nJ) {
+    if (seg == 0 && tid == 0) {
+      st[ST_KSEL] = pb.ksel;
+      st[ST_FLAGS] = pb.ksel == 0 ? kFlagNone : kFlagAll;
+    }
+    return;
+  }
+  if (p_lo >= pb.nJ) return;
+
+  __shared__ uint32_t s_res[2];
+  __shared__ uint32_t s_scr[8];
+  find_kth_desc(a.hist1 + (int64_t)bh * kHist1Bins, kHist1Bins, pb.ksel, s_res, s_scr);
+  const uint32_t bin1 = s_res[0];
+  if (seg == 0 && tid == 0) {
+    st[ST_BIN1] = bin1;
+    st[ST_K1] = s_res[1];
+    st[ST_KSEL] = pb.ksel;
+    st[ST_FLAGS] = 0u;
+  }
+  const uint32_t* keys = a.keys + (int64_t)bh * a.ld_pos;
+  uint32_t* cand = a.cand + (int64_t)bh * a.ld_pos;
+  const int lane = tid & 63;
+  const int p_hi = min(p_lo + kSelSeg, pb.nJ);
+  for (int p0 = p_lo; p0 < p_hi; p0 += kSelThreads) {
+    const int p = p0 + tid;
+    uint32_t key = 0;
+    bool is_c = false;
+    if (p < p_hi) {
+      key = keys[p];
+      is_c = (key >> 19) == bin1;
+    }
+    const unsigned long long mask = __ballot(is_c);
+    if (mask != 0ull) {
+      const int leader = __ffsll((long long)mask) - 1;
+      uint32_t base = 0;
+      if (lane == leader) base = atomicAdd(&st[ST_CAND], (uint32_t)__popcll(mask));
+      base = __shfl(base, leader);
+      if (is_c) cand[base + __popcll(mask & ((1ull << lane) - 1ull))] = key;
+    }
+  }
+}
+
+// ---- stage 3: exact threshold among the candidates, then per-segment counts --------------------
+__global__ __launch_bounds__(kSelThreads) void sel_count_kernel(const SelArgs a) {
+  const int seg = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
+  const Problem pb = problem_of(a, b);
+  const int p_lo = seg * kSelSeg;
+  if (p_lo >= pb.nJ) return;
+  const int tid = threadIdx.x;
+  const int bh = b * a.Hkv + h;
+  uint32_t* st = a.state + (int64_t)bh * kStateWords;
+  if (st[ST_FLAGS] != 0u) return;  // take all / take none: no threshold needed
+
+  __shared__ uint32_t s_h[1024];
+  __shared__ uint32_t s_res[2];
+  __shared__ uint32_t s_scr[8];
+  __shared__ uint32_t s_cnt[2];
+  const uint32_t bin1 = st[ST_BIN1], k1 = st[ST_K1], n_cand = st[ST_CAND];
+  const uint32_t* cand = a.cand + (int64_t)bh * a.ld_pos;
+
+  // bits [18:9] of the candidates
+  for (int i = tid; i < 1024; i += kSelThreads) s_h[i] = 0u;
+  __syncthreads();
+  for (uint32_t i = tid; i < n_cand; i += kSelThreads) atomicAdd(&s_h[(cand[i] >> 9) & 1023u], 1u);
+  __syncthreads();
+  find_kth_desc(s_h, 1024, k1, s_res, s_scr);
+  const uint32_t bin2 = s_res[0], k2 = s_res[1];
+  __syncthreads();
+  // bits [8:0] of the candidates that share bin2
+  for (int i = tid; i < 512; i += kSelThreads) s_h[i] = 0u;
+  __syncthreads();
+  for (uint32_t i = tid; i < n_cand; i += kSelThreads) {
+    const uint32_t key = cand[i];
+    if (((key >> 9) & 1023u) == bin2) atomicAdd(&s_h[key & 511u], 1u);
+  }
+  __syncthreads();
+  find_kth_desc(s_h, 512, k2, s_res, s_scr);
+  const uint32_t tau = (bin1 << 19) | (bin2 << 9) | s_res[0];
+  const uint32_t take = s_res[1];
+  if (seg == 0 && tid == 0) {
+    st[ST_TAU] = tau;
+    st[ST_TAKE] = take;
+  }
+
+  if (tid < 2) s_cnt[tid] = 0u;
+  __syncthreads();
+  const uint32_t* keys = a.keys + (int64_t)bh * a.ld_pos;
+  const int p_hi = min(p_lo + kSelSeg, pb.nJ);
+  uint32_t gt = 0, eq = 0;
+  for (int p = p_lo + tid; p < p_hi; p += kSelThreads) {
+    const uint32_t key = keys[p];
+    gt += key > tau;
+    eq += key == tau;
+  }
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) {
+    gt += __shfl_xor(gt, d);
+    eq += __shfl_xor(eq, d);
+  }
+  if ((tid & 63) == 0) {
+    atomicAdd(&s_cnt[0], gt);
+    atomicAdd(&s_cnt[1], eq);
+  }
+  __syncthreads();
+  if (tid < 2) a.segcnt[((int64_t)bh * a.n_seg_cap + seg) * 2 + tid] = s_cnt[tid];
+}
+
+// ---- stage 4: index-ordered write of the selected set ------------------------------------------
+__global__ __launch_bounds__(kSelThreads) void sel_write_kernel(const SelArgs a) {
+  const int seg = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
+  const Problem pb = problem_of(a, b);
+  const int tid = threadIdx.x;
+  const int bh = b * a.Hkv + h;
+  const uint32_t* st = a.state + (int64_t)bh * kStateWords;
+  int32_t* out = a.sel_idx + (int64_t)bh * a.budget;
+  const int n_seg = gridDim.x;
+  // padding and n_sel, spread over the segments' workgroups
+  for (int i = (int)pb.ksel + seg * kSelThreads + tid; i < a.budget; i += n_seg * kSelThreads) out[i] = -1;
+  if (seg == 0 && tid == 0) a.n_sel[bh] = (int32_t)pb.ksel;
+  const int p_lo = seg * kSelSeg;
+  if (pb.ksel == 0 || p_lo >= pb.nJ) return;
+  const int p_hi = min(p_lo + kSelSeg, pb.nJ);
+  if (pb.ksel == (uint32_t)pb.nJ) {  // everything is selected
+    for (int p = p_lo + tid; p < p_hi; p += kSelThreads) out[p] = a.n_sink + p;
+    return;
+  }
+
+  __shared__ uint32_t s_base[2];
+  __shared__ uint32_t s_scr[8];
+  if (tid < 2) s_base[tid] = 0u;
+  __syncthreads();
+  {  // keys selected in the segments before this one
+    uint32_t gt = 0, eq = 0;
+    for (int s = tid; s < seg; s += kSelThreads) {
+      gt += a.segcnt[((int64_t)bh * a.n_seg_cap + s) * 2];
+      eq += a.segcnt[((int64_t)bh * a.n_seg_cap + s) * 2 + 1];
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+      gt += __shfl_xor(gt, d);
+      eq += __shfl_xor(eq, d);
+    }
+    if ((tid & 63) == 0) {
+      atomicAdd(&s_base[0], gt);
+      atomicAdd(&s_base[1], eq);
+    }
+  }
+  __syncthreads();
+  const uint32_t base_gt = s_base[0], base_eq = s_base[1];
+  const uint32_t tau = st[ST_TAU], take = st[ST_TAKE];
+  const uint32_t* keys = a.keys + (int64_t)bh * a.ld_pos;
+
+  constexpr int kPer = kSelSeg / kSelThreads;  // consecutive positions per thread
+  const int p0 = p_lo + tid * kPer;
+  static_assert(kPer == 8, "two 16-byte key loads per thread");
+  uint32_t key[kPer];
+  {  // the key row is padded to a multiple of kSelSeg, so the full 32 bytes are always readable
+    const uint4 k0 = *reinterpret_cast<const uint4*>(keys + p0);
+    const uint4 k1 = *reinterpret_cast<const uint4*>(keys + p0 + 4);
+    key[0] = k0.x; key[1] = k0.y; key[2] = k0.z; key[3] = k0.w;
+    key[4] = k1.x; key[5] = k1.y; key[6] = k1.z; key[7] = k1.w;
+  }
+  uint32_t cg = 0, ce = 0;
+#pragma unroll
+  for (int i = 0; i < kPer; ++i) {
+    if (p0 + i < p_hi) {
+      cg += key[i] > tau;
+      ce += key[i] == tau;
+    }
+  }
+  uint32_t total;
+  const uint32_t ex = block_excl_scan(cg | (ce << 16), s_scr, &total);
+  uint32_t gt_before = base_gt + (ex & 0xffffu);
+  uint32_t eq_before = base_eq + (ex >> 16);
+#pragma unroll
+  for (int i = 0; i < kPer; ++i) {
+    if (p0 + i < p_hi) {
+      const bool g = key[i] > tau, e = key[i] == tau;
+      if (g || (e && eq_before < take)) {
+        const uint32_t pos = gt_before + min(eq_before, take);
+        if (pos < pb.ksel) out[pos] = a.n_sink + p0 + i;  // always true when ctx_len <= max_len held
+      }
+      gt_before += g;
+      eq_before += e;
+    }
+  }
+}
+
+hipError_t launch_sel_score(const SelArgs& a, int B, int n_seg, hipStream_t s) {
+  hipLaunchKernelGGL(sel_score_kernel, dim3(n_seg, a.Hkv, B), dim3(kSelThreads), 0, s, a);
+  return hipGetLastError();
+}
+hipError_t launch_sel_cand(const SelArgs& a, int B, int n_seg, hipStream_t s) {
+  hipLaunchKernelGGL(sel_cand_kernel, dim3(n_seg, a.Hkv, B), dim3(kSelThreads), 0, s, a);
+  return hipGetLastError();
+}
+hipError_t launch_sel_count(const SelArgs& a, int B, int n_seg, hipStream_t s) {
+  hipLaunchKernelGGL(sel_count_kernel, dim3(n_seg, a.Hkv, B), dim3(kSelThreads), 0, s, a);
+  return hipGetLastError();
+}
+hipError_t launch_sel_write(const SelArgs& a, int B, int n_seg, hipStream_t s) {
+  hipLaunchKernelGGL(sel_write_kernel, dim3(n_seg, a.Hkv, B), dim3(kSelThreads), 0, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace sfi

@@ -1,0 +1,115 @@
+"""Shared plumbing of the GPU parity tests: uploads, the comparison rules, one-call wrappers.
+
+No arithmetic of the method lives here: expected values come from the oracle, results from libsfi.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+OUT_TOL = 2e-3       # max relative error of an output row (bf16 in, fp32 accumulate)
+TIE_BAND = 1e-5      # ranking-score gap below which several index sets are acceptable
+
+
+def to_dev(bits: np.ndarray):
+    """bf16 bit patterns (uint16) -> torch.bfloat16 tensor on the GPU, same bits."""
+    import torch
+    return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def i32_dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+
+
+def row_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
+    """max over rows of  max_c |got - ref| / max_c |ref|  (rows = last axis)."""
+    num = np.abs(got.astype(np.float64) - ref).max(axis=-1)
+    den = np.abs(ref).max(axis=-1)
+    return float((num / np.maximum(den, 1e-30)).max())
+
+
+def check_out(got, ref, tol=OUT_TOL):
+    assert np.isfinite(got).all()
+    err = row_rel_err(got, ref)
+    assert err <= tol, f"row-relative error {err:.3e} > {tol}"
+    return err
+
+
+def check_selection(sel, nsel, sel_ref, nsel_ref, z, ctx_len, n_sink, recent, budget):
+    """Selected sets must equal the oracle's wherever the k-th and (k+1)-th ranking scores differ by
+    more than TIE_BAND; inside the band any set whose members sit at or above the threshold (and whose
+    non-members sit at or below it) within the band is valid.  Structure is always checked."""
+    B, Hkv = nsel.shape
+    n_exact = 0
+    for b in range(B):
+        L = int(ctx_len[b])
+        lo, hi = n_sink, L - recent
+        nJ = max(0, hi - lo)
+        for h in range(Hkv):
+            k = int(nsel[b, h])
+            assert k == int(nsel_ref[b, h]) == min(budget, nJ)
+            row = sel[b, h]
+            assert (row[k:budget] == -1).all()
+            got = row[:k]
+            if k == 0:
+                continue
+            assert (np.diff(got) > 0).all(), "not ascending / not unique"
+            assert got[0] >= lo and got[-1] < hi
+            ref = sel_ref[b, h, :k]
+            if k == nJ:
+                assert (got == ref).all()
+                n_exact += 1
+                continue
+            zz = z[b, h, lo:hi]
+            part = np.partition(zz, nJ - k - 1)
+            zk1, zk = part[nJ - k - 1], part[nJ - k:].min()
+            if zk - zk1 > TIE_BAND:
+                assert (got == ref).all(), f"selection differs at (b={b}, h={h}) with gap {zk - zk1:.2e}"
+                n_exact += 1
+            else:
+                mask = np.zeros(nJ, bool)
+                mask[got - lo] = True
+                assert zz[mask].min() >= zk - TIE_BAND
+                assert zz[~mask].max() <= zk + TIE_BAND
+    return n_exact
+
+
+class Runner:
+    """Device copies of one workload's K/V plus an sfi context; thin wrappers over the C-ABI calls."""
+
+    def __init__(self, w, max_budget=None):
+        import torch
+        import paper_2603_12038_amd as sfi
+        self.sfi, self.torch, self.w = sfi, torch, w
+        self.K, self.V = to_dev(w.K), to_dev(w.V)
+        self.max_ctx = int(w.L_alloc)
+        self.ctx = sfi.SfiContext(w.B, w.Hq, w.Hkv, self.max_ctx, w.budget if max_budget is None else max_budget,
+                                  w.n_sink, w.recent, self.K, self.V)
+        self.out = torch.zeros(w.B, w.Hq, w.d, dtype=torch.float32, device="cuda")
+
+    def dense(self, q_bits, ctx_len, max_len=0):
+        self.out.fill_(float("nan"))
+        self.sfi.sfi_dense_attn(self.ctx.handle, to_dev(q_bits), self.K, self.V, i32_dev(ctx_len), max_len, self.out)
+        self.torch.cuda.synchronize()
+        return self.out.cpu().numpy()
+
+    def slow(self, q_bits, ctx_len, budget, max_len=0):
+        t = self.torch
+        self.out.fill_(float("nan"))
+        sel = t.full((self.w.B, self.w.Hkv, max(budget, 1)), -7, dtype=t.int32, device="cuda")
+        nsel = t.full((self.w.B, self.w.Hkv), -7, dtype=t.int32, device="cuda")
+        self.sfi.sfi_slow_step(self.ctx.handle, to_dev(q_bits), self.K, self.V, i32_dev(ctx_len), max_len, budget,
+                               self.out, sel, nsel)
+        t.cuda.synchronize()
+        return self.out.cpu().numpy(), sel.cpu().numpy(), nsel.cpu().numpy()
+
+    def fast(self, q_bits, sel, nsel, recent_start, ctx_len):
+        self.out.fill_(float("nan"))
+        sel_d, nsel_d = i32_dev(sel), i32_dev(nsel)
+        self.sfi.sfi_fast_step(self.ctx.handle, to_dev(q_bits), self.K, self.V, sel_d, nsel_d, sel.shape[2],
+                               i32_dev(recent_start), i32_dev(ctx_len), self.out)
+        self.torch.cuda.synchronize()
+        return self.out.cpu().numpy()
+
+    def close(self):
+        self.ctx.close()
