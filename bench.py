@@ -1,0 +1,250 @@
+#!/usr/bin/env python3
+"""Benchmark of the slow/fast decode-attention path on one MI355X.
+
+Workload (default): the Llama-3-8B-shaped layer of the baseline configs — batch 4, 32 query / 8 KV
+heads, head_dim 128, context 32768 (+1 per decode step), budget K = 2048, recent window 128,
+sink 4, one slow step every 16 decode steps, bf16 K/V ~ N(0,1) with 1 % planted x4 support rows.
+
+A benchmark "step" is one refresh segment = 16 decode steps (1 slow + 15 fast, with the device-side
+state update after each) run over `--layers` virtual layers, every layer with its own K/V buffers
+and its own selected index sets, visited round-robin inside each decode step the way a model's
+layers are.  With 16 layers the fast steps touch ~570 MB between two visits of the same layer, so
+neither L2 nor the 256 MB last-level cache can serve the re-reads (cold-cache numbers).
+The timed region is captured into one HIP graph and replayed once (inputs resident in HBM).
+
+Reported value: decode-attention tokens/s of ONE attention layer for the slow+fast mix
+(batch x decode steps x layers / time).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+HBM_PEAK_GBS = 8000.0
+SEG = 16  # decode steps per refresh segment in this workload
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=8, help="timed refresh segments (16 decode steps each)")
+    ap.add_argument("--warmup", type=int, default=2, help="untimed refresh segments")
+    ap.add_argument("--layers", type=int, default=16, help="virtual layers (distinct K/V buffers)")
+    ap.add_argument("--ctx", type=int, default=32768)
+    ap.add_argument("--batch", type=int, default=4)
+    ap.add_argument("--launch", choices=["graph", "stream"], default="graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--dense-wgs", type=int, default=0)
+    ap.add_argument("--fast-tpw", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (no collectives, no sharding); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2603_12038_amd as sfi
+    import sfi_synth as syn
+    from helpers import check_out, check_selection, i32_dev, to_dev
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    sfi.load_library()  # fails loudly if libsfi.so is not built
+    dev = torch.device("cuda:0")
+    K_seg, W_seg, NL = args.steps, args.warmup, args.layers
+    n_dec = SEG * (K_seg + W_seg)
+
+    t0 = time.time()
+    w = syn.make_llama8b(L0=args.ctx, steps=n_dec + SEG, B=args.batch)
+    log(f"generated workload in {time.time() - t0:.1f}s: B={w.B} Hq={w.Hq} Hkv={w.Hkv} L0={args.ctx} "
+        f"K={w.budget} R={w.recent} layers={NL}")
+    B, Hq, Hkv, d, L0 = w.B, w.Hq, w.Hkv, w.d, args.ctx
+
+    # ---- device state: NL virtual layers = base K/V with rows [0, L0) rolled by a layer-specific shift
+    K0, V0 = to_dev(w.K), to_dev(w.V)
+    shift = lambda l: (l * 4099) % L0
+    Ks, Vs = [K0], [V0]
+    for l in range(1, NL):
+        k = K0.clone()
+        v = V0.clone()
+        k[:, :, :L0] = torch.roll(K0[:, :, :L0], shift(l), dims=2)
+        v[:, :, :L0] = torch.roll(V0[:, :, :L0], shift(l), dims=2)
+        Ks.append(k)
+        Vs.append(v)
+    max_ctx = int(w.L_alloc)
+    ctx = sfi.SfiContext(B, Hq, Hkv, max_ctx, w.budget, w.n_sink, w.recent, K0, V0)
+    h = ctx.handle
+    if args.dense_wgs or args.fast_tpw:
+        sfi.sfi_set_tuning(h, args.dense_wgs, args.fast_tpw)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1234)
+    q_all = torch.randn(n_dec + SEG, NL, B, Hq, d, device=dev, generator=gen).to(torch.bfloat16)
+    outs = [torch.zeros(B, Hq, d, dtype=torch.float32, device=dev) for _ in range(NL)]
+    sels = [torch.full((B, Hkv, w.budget), -1, dtype=torch.int32, device=dev) for _ in range(NL)]
+    nsels = [torch.zeros(B, Hkv, dtype=torch.int32, device=dev) for _ in range(NL)]
+    ctx_d, rs_d = i32_dev(w.ctx_len(0)), i32_dev(w.recent_start(0))
+    torch.cuda.synchronize()
+    log(f"device state ready ({torch.cuda.memory_allocated() / 1e9:.1f} GB)")
+
+    def slow(l, step):
+        sfi.sfi_slow_step(h, q_all[step, l], Ks[l], Vs[l], ctx_d, max_ctx, w.budget, outs[l], sels[l], nsels[l])
+
+    def fast(l, step):
+        sfi.sfi_fast_step(h, q_all[step, l], Ks[l], Vs[l], sels[l], nsels[l], w.budget, rs_d, ctx_d, outs[l])
+
+    def segment(step0):
+        for t in range(SEG):
+            for l in range(NL):
+                (slow if t == 0 else fast)(l, step0 + t)
+            sfi.sfi_advance(h, ctx_d, rs_d)
+
+    # ---- parity sample + CPU baseline: 1 slow + 2 fast steps of layer 0 at step 0 ---------------------
+    cpu_baseline = None
+    parity = {}
+    if not args.no_cpu_baseline:
+        from oracle import sfi_oracle as oracle
+
+        qs = [q_all[t, 0].view(torch.int16).cpu().numpy().view(np.uint16) for t in range(3)]
+        c0 = w.ctx_len(0)
+        slow(0, 0)
+        torch.cuda.synchronize()
+        g_out, g_sel, g_nsel = outs[0].cpu().numpy(), sels[0].cpu().numpy(), nsels[0].cpu().numpy()
+        t1 = time.time()
+        o_dense = oracle.dense(qs[0], w.K, w.V, c0)
+        o_sel, o_nsel, o_z = oracle.selector(qs[0], w.K, c0, w.budget, w.n_sink, w.recent)
+        t_slow = time.time() - t1
+        parity["slow_out_row_rel_err"] = check_out(g_out, o_dense)
+        n_exact = check_selection(g_sel, g_nsel, o_sel, o_nsel, o_z, c0, w.n_sink, w.recent, w.budget)
+        parity["selection_sets_exact"] = f"{n_exact}/{B * Hkv}"
+        t_fast = 0.0
+        for t in (1, 2):
+            ct, rt = w.ctx_len(t), w.recent_start(t)
+            sfi.sfi_fast_step(h, q_all[t, 0], K0, V0, sels[0], nsels[0], w.budget, i32_dev(rt), i32_dev(ct), outs[0])
+            torch.cuda.synchronize()
+            t1 = time.time()
+            o_sp = oracle.sparse(qs[t], w.K, w.V, g_sel, g_nsel, rt, ct, w.n_sink)
+            t_fast += time.time() - t1
+            parity[f"fast{t}_out_row_rel_err"] = check_out(outs[0].cpu().numpy(), o_sp)
+        t_fast /= 2
+        cpu_baseline = {
+            "value": B * SEG / (t_slow + (SEG - 1) * t_fast), "unit": "tokens/s per attention layer",
+            "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "1 slow step (dense + Selector) + 2 fast steps of layer 0, extrapolated to 1 slow + 15 fast",
+            "slow_step_s": t_slow, "fast_step_s": t_fast,
+        }
+        log(f"parity sample ok {parity}; oracle slow {t_slow:.2f}s fast {t_fast:.3f}s on {oracle.num_threads()} threads")
+
+    # ---- warm-up (eager), then the timed region ---------------------------------------------------------
+    for s in range(W_seg):
+        segment(s * SEG)
+    torch.cuda.synchronize()
+    step0 = W_seg * SEG
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    if args.launch == "graph":
+        state = [ctx_d.clone(), rs_d.clone()]
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            graph.capture_begin()
+            for s in range(K_seg):
+                segment(step0 + s * SEG)
+            graph.capture_end()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        assert (ctx_d == state[0]).all(), "capture must not have executed anything"
+        t1 = time.perf_counter()
+        ev0.record()
+        graph.replay()
+        ev1.record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t1
+    else:
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ev0.record()
+        for s in range(K_seg):
+            segment(step0 + s * SEG)
+        ev1.record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t1
+    gpu_ms = ev0.elapsed_time(ev1)
+    assert int(ctx_d[0]) == L0 + n_dec, "state did not advance as scheduled"
+    total_s = wall
+    tokens = B * SEG * K_seg * NL
+    value = tokens / total_s
+
+    # ---- per-kernel times with HIP events on the launch stream (separate instrumented pass) -----------
+    sfi.sfi_set_profiling(h, True)
+    acc = {"slow": np.zeros(8), "fast": np.zeros(8)}
+    cnt = {"slow": 0, "fast": 0}
+    step_p = step0 + K_seg * SEG
+    for rep in range(1):
+        for t in range(SEG):
+            for l in range(NL):
+                kind = "slow" if t == 0 else "fast"
+                (slow if t == 0 else fast)(l, step_p + t)
+                acc[kind] += np.array(sfi.sfi_stage_times(h))
+                cnt[kind] += 1
+            sfi.sfi_advance(h, ctx_d, rs_d)
+    sfi.sfi_set_profiling(h, False)
+    torch.cuda.synchronize()
+    slow_ms = acc["slow"] / max(cnt["slow"], 1)
+    fast_ms = acc["fast"] / max(cnt["fast"], 1)
+    L_mid = L0 + step_p
+    dense_bytes = B * Hkv * L_mid * d * 2 * 2
+    nsel_mean = float(torch.stack(nsels).float().mean())
+    fast_rows = w.n_sink + nsel_mean + w.recent
+    fast_bytes = B * Hkv * fast_rows * d * 2 * 2
+    dense_gbs = dense_bytes / (slow_ms[0] * 1e-3) / 1e9
+    fast_gbs = fast_bytes / (fast_ms[0] * 1e-3) / 1e9
+    seg_dense_ms = slow_ms[0]
+    seg_fast_ms = fast_ms[0] * (SEG - 1)
+    dominant = "gather" if seg_fast_ms > seg_dense_ms else "dense"
+    roof = {
+        "bound": "hbm", "kernel": f"attn_split_kernel<{'1' if dominant == 'gather' else '0'}> ({dominant})",
+        "achieved": fast_gbs if dominant == "gather" else dense_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": (fast_gbs if dominant == "gather" else dense_gbs) / HBM_PEAK_GBS, "traffic": None,
+    }
+    dsp, fsp = sfi.sfi_query_splits(h)
+    res = {
+        "metric": "decode attn tokens/s (slow+fast mix)", "value": value, "unit": "tokens/s per attention layer",
+        "n_gpus": 1, "steps": K_seg, "warmup": W_seg, "ms_per_step": total_s * 1e3 / K_seg,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"llama8b-shaped layer: B{B} Hq{Hq} Hkv{Hkv} d{d} ctx{L0} k{w.budget} R{w.recent} "
+                               f"sink{w.n_sink} slow every {SEG}",
+                   "step": f"{SEG} decode steps (1 slow + {SEG - 1} fast) x {NL} virtual layers",
+                   "virtual_layers": NL, "launch": args.launch, "dense_splits": dsp, "fast_splits": fsp},
+        "roofline": roof,
+        "kernels": {
+            "dense_attn": {"us": slow_ms[0] * 1e3, "kv_bytes": dense_bytes, "GBps": dense_gbs,
+                           "frac_of_8TBps": dense_gbs / HBM_PEAK_GBS},
+            "gather_attn": {"us": fast_ms[0] * 1e3, "kv_bytes": fast_bytes, "GBps": fast_gbs,
+                            "frac_of_8TBps": fast_gbs / HBM_PEAK_GBS},
+            "slow_step_stage_us": {n: float(slow_ms[i] * 1e3) for i, n in enumerate(sfi.binding.STAGE_NAMES[:6])},
+            "fast_step_stage_us": {n: float(fast_ms[i] * 1e3) for i, n in enumerate(sfi.binding.STAGE_NAMES[:2])},
+        },
+        "us_per_decode_step_per_layer": total_s * 1e6 / (K_seg * SEG * NL),
+        "gpu_event_ms": gpu_ms,
+        "parity_sample": parity,
+        "cpu_baseline": cpu_baseline,
+    }
+    print(json.dumps(res))
+    ctx.close()
+
+
+if __name__ == "__main__":
+    main()
