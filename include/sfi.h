@@ -103,7 +103,9 @@ const char* sfi_strerror(int status);
  *                      (ranking score z = log(f + 1e-8) is monotone in f); equal scores: the lower
  *                      position wins; written ascending, entries [n_sel, budget) set to -1.
  * sel_idx is addressed with row stride `budget`.  max_len: host-side upper bound of ctx_len[]
- * used only to size the launch (0 = cfg.max_ctx).  1 <= ctx_len[b] <= max_len.
+ * (0 = cfg.max_ctx); it sizes the launch, and rows [0, max_len) of every (b, h) of K and V must be
+ * readable memory (their contents beyond ctx_len[b] are never used): the kernel issues a tile's
+ * row loads before ctx_len[b] has arrived.  1 <= ctx_len[b] <= max_len.
  */
 int sfi_slow_step(sfi_ctx* ctx, const void* q, const void* K, const void* V, const int32_t* ctx_len,
                   int32_t max_len, int32_t budget, float* out, int32_t* sel_idx, int32_t* n_sel,
@@ -158,8 +160,8 @@ int sfi_set_profiling(sfi_ctx* ctx, int on);
 int sfi_stage_times(sfi_ctx* ctx, float* ms /* host, [SFI_N_STAGES] */);
 
 /* Launch-geometry knobs for sweeps (values <= 0 keep the current setting):
- * dense_target_wgs     workgroups the dense launch aims for (default 4 per compute unit);
- * fast_tiles_per_wave  32-row tiles each wave of the gather launch gets (default 2). */
+ * dense_target_wgs     workgroups the dense launch aims for (default 2 per compute unit: all resident at once);
+ * fast_tiles_per_wave  32-row tiles each wave of the gather launch gets (default 1). */
 int sfi_set_tuning(sfi_ctx* ctx, int32_t dense_target_wgs, int32_t fast_tiles_per_wave);
 
 /* Launch geometry of the last call (for reports): split workgroups per (sequence, KV head). */

@@ -42,6 +42,10 @@ int validate(const sfi_config* c) {
     if (st[i] % 8 != 0) return SFI_EALIGN;
   }
   if (c->k_stride_t < kHeadDim || c->v_stride_t < kHeadDim) return SFI_EINVAL;
+  // row offsets inside one (sequence, KV head) are 32-bit byte offsets in the kernels
+  if ((int64_t)c->max_ctx * c->k_stride_t * 2 >= ((int64_t)1 << 32) ||
+      (int64_t)c->max_ctx * c->v_stride_t * 2 >= ((int64_t)1 << 32))
+    return SFI_EUNSUPPORTED;
   return SFI_OK;
 }
 
@@ -80,6 +84,12 @@ int dense_splits_for(const sfi_ctx* x, int max_len) {
   if (s > kMaxSplits) s = kMaxSplits;
   if (s < 1) s = 1;
   return s;
+}
+
+void set_dense_bounds(const sfi_ctx* x, AttnArgs* a, int max_len) {
+  const int nJ = max_len - x->cfg.recent - x->cfg.n_sink;
+  a->max_tiles = nJ > 0 ? (nJ + kTile - 1) / kTile : 0;
+  a->row_cap = max_len - 1;
 }
 
 int fast_splits_for(const sfi_ctx* x, int sel_stride) {
@@ -122,7 +132,7 @@ void fill_attn(const sfi_ctx* x, AttnArgs* a, const void* q, const void* K, cons
   a->ld_pos = x->ws.ld_pos;
   a->Hq = c.n_q_heads; a->Hkv = c.n_kv_heads; a->G = x->G;
   a->n_sink = c.n_sink; a->recent = c.recent;
-  a->scale = x->scale;
+  a->scale_log2 = (float)((double)x->scale * 1.4426950408889634);
 }
 
 void fill_sel(const sfi_ctx* x, SelArgs* s, const int32_t* ctx_len, const uint8_t* is_slow, int budget,
@@ -134,7 +144,7 @@ void fill_sel(const sfi_ctx* x, SelArgs* s, const int32_t* ctx_len, const uint8_
   s->ctx_len = ctx_len; s->is_slow = is_slow; s->sel_idx = sel_idx; s->n_sel = n_sel;
   s->ld_pos = x->ws.ld_pos; s->n_seg_cap = x->ws.n_seg_cap;
   s->Hq = c.n_q_heads; s->Hkv = c.n_kv_heads; s->G = x->G;
-  s->n_sink = c.n_sink; s->recent = c.recent; s->n_split = n_split; s->budget = budget;
+  s->n_sink = c.n_sink; s->recent = c.recent; s->n_split = n_split * kWaves; s->budget = budget;
 }
 
 #define SFI_TRY(expr)                         \
@@ -209,8 +219,8 @@ int sfi_create(const sfi_config* cfg, void* workspace, size_t workspace_bytes, s
     x->n_cu = prop.multiProcessorCount;
   else
     (void)hipGetLastError();  // no device here: keep the MI355X default
-  x->dense_target_wgs = 4 * x->n_cu;
-  x->fast_tiles_per_wave = 2;
+  x->dense_target_wgs = 2 * x->n_cu;
+  x->fast_tiles_per_wave = 1;
   *out = x;
   return SFI_OK;
 }
@@ -250,9 +260,10 @@ int sfi_dense_attn(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   AttnArgs a;
   fill_attn(x, &a, q, K, V, ctx_len);
   a.n_split = dense_splits_for(x, ml);
+  set_dense_bounds(x, &a, ml);
   x->last_dense_splits = a.n_split;
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(a, x->cfg.batch, a.n_split + 1, st)); if (!t.stop()) return SFI_ELAUNCH; }
-  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, a.n_split + 1, 0, 0};
+  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, (a.n_split + 1) * kWaves, 0, 0};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
 }
@@ -272,12 +283,13 @@ int sfi_slow_step(sfi_ctx* x, const void* q, const void* K, const void* V, const
   AttnArgs a;
   fill_attn(x, &a, q, K, V, ctx_len);
   a.n_split = dense_splits_for(x, ml);
+  set_dense_bounds(x, &a, ml);
   a.logits = x->ws.logits;
   a.hist1 = x->ws.hist1;
   a.state = x->ws.state;
   x->last_dense_splits = a.n_split;
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(a, x->cfg.batch, a.n_split + 1, st)); if (!t.stop()) return SFI_ELAUNCH; }
-  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, a.n_split + 1, 0, 0};
+  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, (a.n_split + 1) * kWaves, 0, 0};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   SelArgs sa;
   fill_sel(x, &sa, ctx_len, nullptr, budget, a.n_split, sel_idx, n_sel);
@@ -325,6 +337,7 @@ int sfi_mixed_step(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   fill_attn(x, &d, q, K, V, ctx_len);
   d.is_slow = is_slow;
   d.n_split = dense_splits_for(x, ml);
+  set_dense_bounds(x, &d, ml);
   d.logits = x->ws.logits;
   d.hist1 = x->ws.hist1;
   d.state = x->ws.state;
@@ -342,7 +355,7 @@ int sfi_mixed_step(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   // rewrites rows of slow sequences, so the order of the two attention launches is free.
   { StageTimer t(x, st, SFI_STAGE_ATTN2); SFI_TRY(launch_attn_gather(f, x->cfg.batch, f.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(d, x->cfg.batch, d.n_split + 1, st)); if (!t.stop()) return SFI_ELAUNCH; }
-  MergeArgs m{x->ws.part, out, is_slow, x->cfg.n_q_heads, d.n_split + 1, f.n_split, 2};
+  MergeArgs m{x->ws.part, out, is_slow, x->cfg.n_q_heads, (d.n_split + 1) * kWaves, f.n_split, 2};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   SelArgs sa;
   fill_sel(x, &sa, ctx_len, is_slow, budget, d.n_split, sel_idx, n_sel);

@@ -2,14 +2,16 @@
 //
 // What it computes (paper Sec. 3.1): for one (sequence b, KV head h) and the G query heads that
 // share it, logits l_g(j) = scale * <q_g, k_j> over a list of positions, and the flash-style
-// partial  (m, sum_j e^{l-m}, sum_j e^{l-m} v_j)  of every workgroup's share of that list.
-//   dense  mode (slow step): workgroups 0..n_split-1 cover the allowed set J = [n_sink, L - recent)
-//          and also expose the fp32 logits for the Selector (Eq. window_logits, W = 1);
-//          workgroup n_split covers the sink and recent rows, which the Selector never ranks
-//          (Eq. allowed_set).  Keeping J apart means the J-only softmax normaliser of
-//          Eq. selector_pt is just the merge of the first n_split partials.
-//   gather mode (fast step): the list is  sink ++ sel_idx[0:n_sel] ++ [recent_start, L)
-//          (Eq. index_set_head), strided over n_split workgroups.
+// partial  (m, sum_j e^{l-m}, sum_j e^{l-m} v_j)  of a share of that list, in the log2 domain
+// (y = log2(e) * l, weights 2^(y - m)).
+//   dense  kernel (slow step): workgroups 0..n_split-1 cover the allowed set J = [n_sink, L - recent)
+//          and also expose y over J for the Selector (Eq. window_logits, W = 1); workgroup n_split
+//          covers the sink and recent rows, which the Selector never ranks (Eq. allowed_set).
+//          Keeping J apart means the J-only softmax normaliser of Eq. selector_pt is just the merge
+//          of the J records.  Every wave writes its own record: waves never wait for each other.
+//   gather kernel (fast step): the list is  sink ++ sel_idx[0:n_sel] ++ [recent_start, L)
+//          (Eq. index_set_head), strided over n_split workgroups; the four waves of a workgroup
+//          are combined into one record (fewer records for the merge that follows).
 //
 // Mapping to the matrix cores.  A wave owns 32 positions per iteration, as two 16-row blocks.
 //   S^T = K_blk (16 rows x 128) . Q^T (128 x 16 heads, heads >= G are zero): 4 x mfma 16x16x32 bf16
@@ -39,150 +41,135 @@ __device__ __forceinline__ uint32_t pack_hi16(float a, float b) {
   return (__float_as_uint(a) >> 16) | (__float_as_uint(b) & 0xffff0000u);
 }
 
-template <int MODE>  // 0: dense (slow step), 1: gather (fast step)
-__global__ __launch_bounds__(kAttnThreads) void attn_split_kernel(const AttnArgs a) {
-  const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  if (a.is_slow != nullptr && ((a.is_slow[b] != 0) != (MODE == 0))) return;
+// K and V rows are read once per step: stream them past the caches.  base is uniform over the
+// workgroup, off a 32-bit byte offset (the API rejects layouts whose per-head extent exceeds 4 GiB).
+__device__ __forceinline__ uint4 load_row16(const char* base, uint32_t off) {
+  typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + off));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
 
-  const int tid = threadIdx.x;
-  const int lane = tid & 63, w = tid >> 6;
-  const int jg = lane >> 4, n = lane & 15;
-  const int G = a.G;
-  const int L = a.ctx_len[b];
-  const int bh = b * a.Hkv + h;
+struct Tile {
+  uint4 ka[4], kb[4];  // K rows of blocks A / B: row n, dims kblk*32 + 8*jg .. +8
+  uint4 v[8];          // V rows 4*jg + i of block A (i < 4) and block B (i >= 4), dims 8n .. 8n+7
+};
 
-  // ---- the position list of this workgroup -------------------------------------------------
-  int N;          // number of positions
-  int first, step;  // tile stride of this wave
-  int nS = 0, nSel = 0, rs = 0;
-  const int32_t* sel = nullptr;
-  bool j_range = false;
-  if (MODE == 0) {
-    if (slot < a.n_split) {
-      N = max(0, L - a.recent - a.n_sink);
-      first = slot * kWaves + w;
-      step = a.n_split * kWaves;
-      j_range = true;
-    } else {
-      nS = min(a.n_sink, L);
-      rs = min(max(a.n_sink, L - a.recent), L);
-      N = nS + (L - rs);
-      first = w;
-      step = kWaves;
-      if (a.hist1 != nullptr) {  // fresh Selector state for this (b, h)
-        uint32_t* hh = a.hist1 + (int64_t)bh * kHist1Bins;
-        for (int i = tid; i < kHist1Bins; i += kAttnThreads) hh[i] = 0u;
-        if (tid < kStateWords) a.state[(int64_t)bh * kStateWords + tid] = 0u;
-      }
-    }
-  } else {
-    nS = min(a.n_sink, L);
-    nSel = a.n_sel[bh];
-    rs = min(max(a.recent_start[b], nS), L);
-    N = nS + nSel + (L - rs);
-    sel = a.sel_idx + (int64_t)bh * a.sel_stride;
-    first = slot * kWaves + w;
-    step = a.n_split * kWaves;
+// Per-wave addressing of one (sequence, KV head): uniform bases, per-lane byte offsets.
+struct Rows {
+  const char* Kb;
+  const char* Vb;
+  uint32_t k_st, v_st;    // row strides in bytes
+  uint32_t k_lane, v_lane;  // jg * 16, n * 16
+  int jg, n;
+};
+
+// Row loads of a tile whose positions map to consecutive cache rows: block A row n is cache row
+// r0 + n; rows above r_max are replaced by r_max (they carry no weight).  K and V separately, so
+// that each half of the tile buffer can be refilled as soon as its consumer is done with it.
+__device__ __forceinline__ void issue_k_affine(Tile& T, const Rows& R, int r0, int r_max) {
+  const uint32_t oa = (uint32_t)min(r0 + R.n, r_max) * R.k_st + R.k_lane;
+  const uint32_t ob = (uint32_t)min(r0 + 16 + R.n, r_max) * R.k_st + R.k_lane;
+#pragma unroll
+  for (int kb = 0; kb < 4; ++kb) {
+    T.ka[kb] = load_row16(R.Kb, oa + kb * 64);
+    T.kb[kb] = load_row16(R.Kb, ob + kb * 64);
   }
-  auto row_of = [&](int p) -> int64_t {
-    if (MODE == 0) return j_range ? (int64_t)(a.n_sink + p) : (int64_t)(p < nS ? p : rs + (p - nS));
-    if (p < nS) return p;
-    if (p < nS + nSel) return sel[p - nS];
-    return rs + (p - nS - nSel);
-  };
-
-  const uint16_t* Kb = a.K + b * a.k_sb + h * a.k_sh;
-  const uint16_t* Vb = a.V + b * a.v_sb + h * a.v_sh;
-
-  // ---- Q^T operand: head n, dims kblk*32 + 8*jg .. +8 ----------------------------------------
-  bf16x8 qreg[4];
-  {
-    const uint16_t* qp = a.q + ((int64_t)b * a.Hq + h * G + (n < G ? n : 0)) * kHeadDim + jg * 8;
+}
+__device__ __forceinline__ void issue_v_affine(Tile& T, const Rows& R, int r0, int r_max) {
 #pragma unroll
-    for (int kb = 0; kb < 4; ++kb) {
-      uint4 t = *reinterpret_cast<const uint4*>(qp + kb * 32);
-      if (n >= G) t = make_uint4(0u, 0u, 0u, 0u);
-      qreg[kb] = as_bf16x8(t);
-    }
+  for (int i = 0; i < 4; ++i) {
+    T.v[i] = load_row16(R.Vb, (uint32_t)min(r0 + 4 * R.jg + i, r_max) * R.v_st + R.v_lane);
+    T.v[4 + i] = load_row16(R.Vb, (uint32_t)min(r0 + 16 + 4 * R.jg + i, r_max) * R.v_st + R.v_lane);
   }
+}
+__device__ __forceinline__ void issue_affine(Tile& T, const Rows& R, int r0, int r_max) {
+  issue_k_affine(T, R, r0, r_max);
+  issue_v_affine(T, R, r0, r_max);
+}
 
-  float m_run = kNeg, l_run = 0.f;
-  f32x4 acc[8];
+// Row loads of a tile with arbitrary rows: ra / rb are the cache rows of this lane's K rows in
+// blocks A / B; the V rows 4*jg + i are the ones lanes 4*jg + i resolved for K.
+__device__ __forceinline__ void issue_rows(Tile& T, const Rows& R, int ra, int rb) {
+  const uint32_t oa = (uint32_t)ra * R.k_st + R.k_lane, ob = (uint32_t)rb * R.k_st + R.k_lane;
 #pragma unroll
-  for (int e = 0; e < 8; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int kb = 0; kb < 4; ++kb) {
+    T.ka[kb] = load_row16(R.Kb, oa + kb * 64);
+    T.kb[kb] = load_row16(R.Kb, ob + kb * 64);
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    T.v[i] = load_row16(R.Vb, (uint32_t)__shfl(ra, 4 * R.jg + i) * R.v_st + R.v_lane);
+    T.v[4 + i] = load_row16(R.Vb, (uint32_t)__shfl(rb, 4 * R.jg + i) * R.v_st + R.v_lane);
+  }
+}
 
-  const int nT = (N + kTile - 1) / kTile;
-  const bool head_ok = n < G;
-  const float c_scale = a.scale;
-  float* lg_row = (MODE == 0 && j_range && a.logits != nullptr && head_ok)
-                      ? a.logits + ((int64_t)b * a.Hq + h * G + n) * a.ld_pos
-                      : nullptr;
+// Q^T operand: head n, dims kblk*32 + 8*jg .. +8; zero for heads >= G (no branch around the loads).
+__device__ __forceinline__ void load_q(bf16x8 (&qreg)[4], const uint16_t* q, int64_t head0, int G, int jg, int n) {
+  const uint16_t* qp = q + (head0 + (n < G ? n : 0)) * kHeadDim + jg * 8;
+  const uint32_t keep = n < G ? 0xffffffffu : 0u;
+#pragma unroll
+  for (int kb = 0; kb < 4; ++kb) {
+    uint4 t = *reinterpret_cast<const uint4*>(qp + kb * 32);
+    t.x &= keep; t.y &= keep; t.z &= keep; t.w &= keep;
+    qreg[kb] = as_bf16x8(t);
+  }
+}
 
-  for (int t = first; t < nT; t += step) {
-    const int p0 = t * kTile;
-    // K rows (A operand of S^T): block A row n, block B row n
-    uint4 ka[4], kb4[4], v[8];
-    {
-      const int64_t ra = row_of(min(p0 + n, N - 1));
-      const int64_t rb = row_of(min(p0 + 16 + n, N - 1));
-      const uint16_t* pa = Kb + ra * a.k_st + jg * 8;
-      const uint16_t* pb = Kb + rb * a.k_st + jg * 8;
-#pragma unroll
-      for (int kb = 0; kb < 4; ++kb) {
-        ka[kb] = *reinterpret_cast<const uint4*>(pa + kb * 32);
-        kb4[kb] = *reinterpret_cast<const uint4*>(pb + kb * 32);
-      }
-    }
-    // V rows (B operand of O): rows 4*jg + i of block A, then of block B; dims 8n .. 8n+7
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int64_t r0 = row_of(min(p0 + 4 * jg + i, N - 1));
-      const int64_t r1 = row_of(min(p0 + 16 + 4 * jg + i, N - 1));
-      v[i] = *reinterpret_cast<const uint4*>(Vb + r0 * a.v_st + n * 8);
-      v[4 + i] = *reinterpret_cast<const uint4*>(Vb + r1 * a.v_st + n * 8);
-    }
+// One 32-position tile in three phases: S^T = K Q^T, online softmax in the log2 domain, O += P V.
+// y = c2 * <q, k> with c2 = scale * log2(e); m_run / l_run are the running max of y and the running
+// sum of 2^(y - m_run) of this lane's rows; acc[e][i] is O[head 4*jg+i][dim 8n+e].
+// Lanes of heads >= G see q = 0; their state stays finite and is never written out: no mask needed.
 
-    // ---- S^T = K . Q^T ------------------------------------------------------------------------
-    f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+// Phase 1: y[i] = logit (log2 domain) of head n, row 4*jg+i of block A (i < 4) / block B (i >= 4).
+__device__ __forceinline__ void qk_phase(const Tile& T, const bf16x8 (&qreg)[4], float c2, float (&y)[8]) {
+  f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int kb = 0; kb < 4; ++kb) {
-      sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ka[kb]), qreg[kb], sa, 0, 0, 0);
-      sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kb4[kb]), qreg[kb], sb, 0, 0, 0);
-    }
-    float x[8];
+  for (int kb = 0; kb < 4; ++kb) {
+    sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(T.ka[kb]), qreg[kb], sa, 0, 0, 0);
+    sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(T.kb[kb]), qreg[kb], sb, 0, 0, 0);
+  }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      x[i] = sa[i] * c_scale;
-      x[4 + i] = sb[i] * c_scale;
-    }
-    if (lg_row != nullptr) {  // expose logits of J (rows past N land in the padded tail, never read)
-      *reinterpret_cast<float4*>(lg_row + p0 + 4 * jg) = make_float4(x[0], x[1], x[2], x[3]);
-      *reinterpret_cast<float4*>(lg_row + p0 + 16 + 4 * jg) = make_float4(x[4], x[5], x[6], x[7]);
-    }
-    bool ok[8];
-    float mt = kNeg;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int p = p0 + (i < 4 ? 4 * jg + i : 16 + 4 * jg + (i - 4));
-      ok[i] = head_ok && (p < N);
-      x[i] = ok[i] ? x[i] : kNeg;
-      mt = fmaxf(mt, x[i]);
-    }
-    mt = fmaxf(mt, __shfl_xor(mt, 16));
-    mt = fmaxf(mt, __shfl_xor(mt, 32));
-    const float m_new = fmaxf(m_run, mt);
-    const float alpha = fast_exp2((m_run - m_new) * kLog2e);
-    m_run = m_new;
-    float pr[8], ps = 0.f;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      pr[i] = ok[i] ? fast_exp2((x[i] - m_new) * kLog2e) : 0.f;
-      ps += pr[i];
-    }
-    l_run = l_run * alpha + ps;
+  for (int i = 0; i < 4; ++i) {
+    y[i] = sa[i] * c2;
+    y[4 + i] = sb[i] * c2;
+  }
+}
 
-    // ---- rescale O: this lane's accumulators belong to heads 4*jg + i ---------------------------
-    float al[4];
+// y of head n, rows 0..31 of the tile, goes to stage[n * 32 ..] (this wave's LDS patch).
+__device__ __forceinline__ void stage_logits(float* stage, const float (&y)[8], int jg, int n, int G) {
+  if (n < G) {
+    *reinterpret_cast<float4*>(stage + n * kTile + 4 * jg) = make_float4(y[0], y[1], y[2], y[3]);
+    *reinterpret_cast<float4*>(stage + n * kTile + 16 + 4 * jg) = make_float4(y[4], y[5], y[6], y[7]);
+  }
+}
+
+// Ragged last tile: positions >= N carry no weight; their V rows may hold anything, so zero them
+// to keep 0 * v finite.
+__device__ __forceinline__ void mask_tail(Tile& T, float (&y)[8], int jg, int p0, int N) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const bool oka = p0 + 4 * jg + i < N, okb = p0 + 16 + 4 * jg + i < N;
+    y[i] = oka ? y[i] : kNeg;
+    y[4 + i] = okb ? y[4 + i] : kNeg;
+    if (!oka) T.v[i] = make_uint4(0u, 0u, 0u, 0u);
+    if (!okb) T.v[4 + i] = make_uint4(0u, 0u, 0u, 0u);
+  }
+}
+
+// Phase 2: running max / sum update (accumulators rescaled only when some head's maximum moved,
+// which is rare after the first tiles) and the weights as two bf16 terms, hi + lo ~ 16 bits.
+// Masked rows carry y = kNeg; every tile handed in has at least one unmasked row, so each head's
+// maximum is finite and 2^(kNeg - max) is exactly 0.
+__device__ __forceinline__ void softmax_phase(const float (&y)[8], f32x4 (&acc)[8], float& m_run, float& l_run, int jg,
+                                              bf16x8& a_hi, bf16x8& a_lo) {
+  float mt = fmaxf(fmaxf(fmaxf(y[0], y[1]), fmaxf(y[2], y[3])), fmaxf(fmaxf(y[4], y[5]), fmaxf(y[6], y[7])));
+  mt = fmaxf(mt, __shfl_xor(mt, 16));
+  mt = fmaxf(mt, __shfl_xor(mt, 32));
+  const float m_new = fmaxf(m_run, mt);
+  if (__ballot(m_new > m_run) != 0ull) {
+    const float alpha = fast_exp2(m_run - m_new);
+    l_run *= alpha;
+    float al[4];  // this lane's accumulators belong to heads 4*jg + i
 #pragma unroll
     for (int i = 0; i < 4; ++i) al[i] = __shfl(alpha, 4 * jg + i);
 #pragma unroll
@@ -190,47 +177,267 @@ __global__ __launch_bounds__(kAttnThreads) void attn_split_kernel(const AttnArgs
 #pragma unroll
       for (int i = 0; i < 4; ++i) acc[e][i] *= al[i];
     }
-
-    // ---- P as two bf16 terms -------------------------------------------------------------------
-    uint4 phi, plo;
-    {
-      float lo[8];
+    m_run = m_new;
+  }
+  float pr[8], lo[8], ps = 0.f;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) lo[i] = pr[i] - __uint_as_float(__float_as_uint(pr[i]) & 0xffff0000u);
-      phi = make_uint4(pack_hi16(pr[0], pr[1]), pack_hi16(pr[2], pr[3]), pack_hi16(pr[4], pr[5]),
-                       pack_hi16(pr[6], pr[7]));
-      plo = make_uint4(pack_hi16(lo[0], lo[1]), pack_hi16(lo[2], lo[3]), pack_hi16(lo[4], lo[5]),
-                       pack_hi16(lo[6], lo[7]));
+  for (int i = 0; i < 8; ++i) {
+    pr[i] = fast_exp2(y[i] - m_run);
+    ps += pr[i];
+    lo[i] = pr[i] - __uint_as_float(__float_as_uint(pr[i]) & 0xffff0000u);
+  }
+  l_run += ps;
+  a_hi = as_bf16x8(make_uint4(pack_hi16(pr[0], pr[1]), pack_hi16(pr[2], pr[3]), pack_hi16(pr[4], pr[5]),
+                              pack_hi16(pr[6], pr[7])));
+  a_lo = as_bf16x8(make_uint4(pack_hi16(lo[0], lo[1]), pack_hi16(lo[2], lo[3]), pack_hi16(lo[4], lo[5]),
+                              pack_hi16(lo[6], lo[7])));
+}
+
+// Phase 3: O += P V, one product per dim offset e: element e of each of the 8 rows this lane holds.
+__device__ __forceinline__ void pv_phase(const Tile& T, const bf16x8& a_hi, const bf16x8& a_lo, f32x4 (&acc)[8]) {
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    uint32_t c[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      c[i] = (e >> 1) == 0 ? T.v[i].x : (e >> 1) == 1 ? T.v[i].y : (e >> 1) == 2 ? T.v[i].z : T.v[i].w;
+    uint4 bv;
+    if ((e & 1) == 0) {
+      bv = make_uint4((c[0] & 0xffffu) | (c[1] << 16), (c[2] & 0xffffu) | (c[3] << 16),
+                      (c[4] & 0xffffu) | (c[5] << 16), (c[6] & 0xffffu) | (c[7] << 16));
+    } else {
+      bv = make_uint4((c[0] >> 16) | (c[1] & 0xffff0000u), (c[2] >> 16) | (c[3] & 0xffff0000u),
+                      (c[4] >> 16) | (c[5] & 0xffff0000u), (c[6] >> 16) | (c[7] & 0xffff0000u));
     }
-    const bf16x8 a_hi = as_bf16x8(phi), a_lo = as_bf16x8(plo);
+    const bf16x8 b_e = as_bf16x8(bv);
+    acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi, b_e, acc[e], 0, 0, 0);
+    acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_lo, b_e, acc[e], 0, 0, 0);
+  }
+}
 
-    // ---- O += P . V, one product per dim offset e ------------------------------------------------
+// All three phases on a tile that is already in registers.  MASKED: ragged last tile of a list.
+template <bool MASKED>
+__device__ __forceinline__ void tile_math(Tile& T, const bf16x8 (&qreg)[4], float c2, f32x4 (&acc)[8],
+                                          float& m_run, float& l_run, int jg, int p0, int N) {
+  float y[8];
+  qk_phase(T, qreg, c2, y);
+  if (MASKED) mask_tail(T, y, jg, p0, N);
+  bf16x8 a_hi, a_lo;
+  softmax_phase(y, acc, m_run, l_run, jg, a_hi, a_lo);
+  pv_phase(T, a_hi, a_lo, acc);
+}
+
+// record of (b, head, slot): { max of y, sum 2^(y - max), -, -, O[128] }, written by one wave
+__device__ __forceinline__ void write_wave_record(float* part, int64_t head0, int G, int wslot, const f32x4 (&acc)[8],
+                                                  float m_run, float l_run, int lane) {
+  const int jg = lane >> 4, n = lane & 15;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      uint32_t c[8];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const uint32_t d = (e >> 1) == 0 ? v[i].x : (e >> 1) == 1 ? v[i].y : (e >> 1) == 2 ? v[i].z : v[i].w;
-        c[i] = d;
-      }
-      uint4 bv;
-      if ((e & 1) == 0) {
-        bv = make_uint4((c[0] & 0xffffu) | (c[1] << 16), (c[2] & 0xffffu) | (c[3] << 16),
-                        (c[4] & 0xffffu) | (c[5] << 16), (c[6] & 0xffffu) | (c[7] << 16));
-      } else {
-        bv = make_uint4((c[0] >> 16) | (c[1] & 0xffff0000u), (c[2] >> 16) | (c[3] & 0xffff0000u),
-                        (c[4] >> 16) | (c[5] & 0xffff0000u), (c[6] >> 16) | (c[7] & 0xffff0000u));
-      }
-      const bf16x8 b_e = as_bf16x8(bv);
-      acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi, b_e, acc[e], 0, 0, 0);
-      acc[e] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_lo, b_e, acc[e], 0, 0, 0);
+  for (int i = 0; i < 4; ++i) {
+    const int hh = 4 * jg + i;
+    if (hh < G) {
+      float* dst = part + ((head0 + hh) * kSlotCap + wslot) * kPartStride + 4 + n * 8;
+      *reinterpret_cast<float4*>(dst) = make_float4(acc[0][i], acc[1][i], acc[2][i], acc[3][i]);
+      *reinterpret_cast<float4*>(dst + 4) = make_float4(acc[4][i], acc[5][i], acc[6][i], acc[7][i]);
     }
   }
+  if (lane < G) {
+    float* r = part + ((head0 + lane) * kSlotCap + wslot) * kPartStride;
+    *reinterpret_cast<float2*>(r) = make_float2(m_run, l_run);
+  }
+}
 
-  // ---- combine the four waves and write this workgroup's partial ----------------------------------
+// Walks a position list whose rows are not consecutive: sink ++ sel ++ recent (gather), or
+// sink ++ recent (the dense kernel's last workgroup, n_sel = 0).  Position p < nS is row p, then
+// nSel selected rows, then rows rs, rs + 1, ...; positions past the list read row 0 with weight 0.
+struct ListWalk {
+  const int32_t* sel;  // row of sel_idx of this (b, h), or nullptr
+  int sel_cap;         // sel_stride - 1
+  int n_sink;
+  int nS, nSel, rs, N;
+  __device__ __forceinline__ int sel_at(int p) const {  // index stored for list position p (valid inside the sel part)
+    return sel_cap >= 0 ? sel[min(max(p - n_sink, 0), sel_cap)] : 0;
+  }
+  __device__ __forceinline__ int row_of(int p, int s) const {
+    const int i = p - nS;
+    int r = i < nSel ? s : rs + (i - nSel);
+    r = p < nS ? p : r;
+    return p < N ? r : 0;
+  }
+};
+
+// ------------------------------------------------------------------------------------------------
+// dense kernel
+// ------------------------------------------------------------------------------------------------
+template <bool EXPOSE>  // EXPOSE: also write y over J for the Selector
+__global__ __launch_bounds__(kAttnThreads, 3) void attn_dense_kernel(const AttnArgs a) {
+  __shared__ float s_patch[kWaves][16 * kTile];  // per-wave transpose patch for the logits of one tile
+  const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, w = tid >> 6;
+  const int jg = lane >> 4, n = lane & 15;
+  const int G = a.G;
+  const int bh = b * a.Hkv + h;
+  const int64_t head0 = (int64_t)b * a.Hq + h * G;
+  Rows R;
+  R.Kb = reinterpret_cast<const char*>(a.K + b * a.k_sb + h * a.k_sh);
+  R.Vb = reinterpret_cast<const char*>(a.V + b * a.v_sb + h * a.v_sh);
+  R.k_st = (uint32_t)a.k_st * 2u;
+  R.v_st = (uint32_t)a.v_st * 2u;
+  R.k_lane = jg * 16;
+  R.v_lane = n * 16;
+  R.jg = jg;
+  R.n = n;
+
+  Tile T;
+  bf16x8 qreg[4];
+  float m_run = kNeg, l_run = 0.f;
+  f32x4 acc[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  if (slot == a.n_split) {
+    // ---- the sink and recent rows (never ranked by the Selector) ------------------------------------
+    load_q(qreg, a.q, head0, G, jg, n);
+    const int L = a.ctx_len[b];
+    if (a.hist1 != nullptr) {  // fresh Selector state for this (b, h)
+      uint32_t* hh = a.hist1 + (int64_t)bh * kHist1Bins;
+      for (int i = tid; i < kHist1Bins; i += kAttnThreads) hh[i] = 0u;
+      if (tid < kStateWords) a.state[(int64_t)bh * kStateWords + tid] = 0u;
+    }
+    ListWalk W;
+    W.sel = nullptr;
+    W.sel_cap = -1;
+    W.n_sink = a.n_sink;
+    W.nS = min(a.n_sink, L);
+    W.nSel = 0;
+    W.rs = min(max(a.n_sink, L - a.recent), L);
+    W.N = W.nS + (L - W.rs);
+    const int nT = (W.N + kTile - 1) / kTile;
+    for (int t = w; t < nT; t += kWaves) {
+      const int p0 = t * kTile;
+      issue_rows(T, R, W.row_of(p0 + n, 0), W.row_of(p0 + 16 + n, 0));
+      tile_math<true>(T, qreg, a.scale_log2, acc, m_run, l_run, jg, p0, W.N);
+    }
+  } else {
+    // ---- a share of J: position p is cache row n_sink + p ---------------------------------------------
+    // This wave owns tiles first, first + step, ...  The rows of its first tile follow from the
+    // block index alone: their loads go out before ctx_len arrives (clamped to the launch's row
+    // bound; masked later if they turn out to lie past the list).
+    const int first = slot * kWaves + w, step = a.n_split * kWaves;
+    if (first < a.max_tiles) issue_affine(T, R, a.n_sink + first * kTile, a.row_cap);
+    load_q(qreg, a.q, head0, G, jg, n);
+    const int L = a.ctx_len[b];
+    const int N = max(0, L - a.recent - a.n_sink);
+    const int nFull = N / kTile, nT = (N + kTile - 1) / kTile;
+    const int r_max = a.n_sink + N - 1;
+    const int K = first < nT ? (nT - first + step - 1) / step : 0;  // tiles of this wave, ragged one included
+    // Exposing y.  The logits of (b, h) are stored tile-major, [tile][G heads][32 positions], so a
+    // tile's G x 128 bytes are one contiguous run.  The tile's values are transposed through this
+    // wave's LDS patch so that 8 lanes write each 128-byte line whole.  Every lane stores (lanes
+    // beyond the G heads repeat a line already written by another lane): the number of memory
+    // instructions per tile is then fixed, which the load waits below rely on.
+    float* patch = &s_patch[w][0];
+    float* lg_base = EXPOSE ? a.logits + head0 * a.ld_pos : nullptr;
+    auto write_logits = [&](const float (&y)[8], int t) {
+      stage_logits(patch, y, jg, n, G);
+      __builtin_amdgcn_wave_barrier();
+      float* dst = lg_base + (int64_t)t * G * kTile;
+      const int hd = (lane >> 3) % G, qd = lane & 7;
+      *reinterpret_cast<float4*>(dst + hd * kTile + 4 * qd) = *reinterpret_cast<const float4*>(patch + hd * kTile + 4 * qd);
+      if (G > 8) {
+        const int hd2 = 8 + (lane >> 3) % (G - 8);
+        *reinterpret_cast<float4*>(dst + hd2 * kTile + 4 * qd) = *reinterpret_cast<const float4*>(patch + hd2 * kTile + 4 * qd);
+      }
+      __builtin_amdgcn_wave_barrier();
+    };
+
+    // One loop for all of the wave's tiles, one tile buffer: the K half is refilled with the next
+    // tile's rows as soon as the logits are out, the V half as soon as P V is done, so rows are on
+    // their way during most of a tile's math.  The refill is unconditional -- past the wave's last
+    // tile it degenerates to re-reading row r_max -- so that no branch surrounds a load and every
+    // wait can name exactly the loads it needs.
+    constexpr int kNoTile = 1 << 28;
+    for (int k = 0; k < K; ++k) {
+      const int t = first + k * step;
+      const int r_next = (k + 1 < K) ? a.n_sink + (t + step) * kTile : kNoTile;
+      float y[8];
+      qk_phase(T, qreg, a.scale_log2, y);
+      issue_k_affine(T, R, r_next, r_max);
+      if (EXPOSE) write_logits(y, t);  // positions past N land in the padding of the last tile, never used
+      if (t >= nFull) mask_tail(T, y, jg, t * kTile, N);
+      bf16x8 a_hi, a_lo;
+      softmax_phase(y, acc, m_run, l_run, jg, a_hi, a_lo);
+      pv_phase(T, a_hi, a_lo, acc);
+      issue_v_affine(T, R, r_next, r_max);
+    }
+  }
+  l_run += __shfl_xor(l_run, 16);
+  l_run += __shfl_xor(l_run, 32);
+  write_wave_record(a.part, head0, G, slot * kWaves + w, acc, m_run, l_run, lane);
+}
+
+// ------------------------------------------------------------------------------------------------
+// gather kernel
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_kernel(const AttnArgs a) {
+  const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  if (a.is_slow != nullptr && a.is_slow[b] != 0) return;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, w = tid >> 6;
+  const int jg = lane >> 4, n = lane & 15;
+  const int G = a.G;
+  const int bh = b * a.Hkv + h;
+  const int64_t head0 = (int64_t)b * a.Hq + h * G;
+  const int first = slot * kWaves + w, step = a.n_split * kWaves;
+
+  // ---- first round of loads, none depending on another: the selected indices of this wave's first
+  // tile (read before the list length is known, clamped to the row of sel_idx), q, the scalars.
+  ListWalk W;
+  W.sel = a.sel_idx + (int64_t)bh * a.sel_stride;
+  W.sel_cap = (int)a.sel_stride - 1;
+  W.n_sink = a.n_sink;
+  int sA = W.sel_at(first * kTile + n);
+  int sB = W.sel_at(first * kTile + 16 + n);
+  bf16x8 qreg[4];
+  load_q(qreg, a.q, head0, G, jg, n);
+  const int L = a.ctx_len[b];
+  W.nS = min(a.n_sink, L);
+  W.nSel = a.n_sel[bh];
+  W.rs = min(max(a.recent_start[b], W.nS), L);
+  W.N = W.nS + W.nSel + (L - W.rs);
+
+  Rows R;
+  R.Kb = reinterpret_cast<const char*>(a.K + b * a.k_sb + h * a.k_sh);
+  R.Vb = reinterpret_cast<const char*>(a.V + b * a.v_sb + h * a.v_sh);
+  R.k_st = (uint32_t)a.k_st * 2u;
+  R.v_st = (uint32_t)a.v_st * 2u;
+  R.k_lane = jg * 16;
+  R.v_lane = n * 16;
+  R.jg = jg;
+  R.n = n;
+
+  Tile T;
+  float m_run = kNeg, l_run = 0.f;
+  f32x4 acc[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const int nT = (W.N + kTile - 1) / kTile;
+  for (int t = first; t < nT; t += step) {  // normally a single trip
+    const int p0 = t * kTile;
+    if (t != first) {
+      sA = W.sel_at(p0 + n);
+      sB = W.sel_at(p0 + 16 + n);
+    }
+    issue_rows(T, R, W.row_of(p0 + n, sA), W.row_of(p0 + 16 + n, sB));
+    if (p0 + kTile <= W.N) tile_math<false>(T, qreg, a.scale_log2, acc, m_run, l_run, jg, p0, W.N);
+    else tile_math<true>(T, qreg, a.scale_log2, acc, m_run, l_run, jg, p0, W.N);
+  }
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
 
+  // ---- combine the four waves, one record per workgroup ------------------------------------------------
   __shared__ float s_m[kWaves][16];
   __shared__ float s_l[kWaves][16];
   __shared__ float s_red[kWaves][16][kHeadDim];
@@ -246,14 +453,14 @@ __global__ __launch_bounds__(kAttnThreads) void attn_split_kernel(const AttnArgs
       float M = s_m[0][hh];
 #pragma unroll
       for (int ww = 1; ww < kWaves; ++ww) M = fmaxf(M, s_m[ww][hh]);
-      const float f = fast_exp2((s_m[w][hh] - M) * kLog2e);
+      const float f = fast_exp2(s_m[w][hh] - M);
       float* dst = &s_red[w][hh][n * 8];
       *reinterpret_cast<float4*>(dst) = make_float4(acc[0][i] * f, acc[1][i] * f, acc[2][i] * f, acc[3][i] * f);
       *reinterpret_cast<float4*>(dst + 4) = make_float4(acc[4][i] * f, acc[5][i] * f, acc[6][i] * f, acc[7][i] * f);
     }
   }
   __syncthreads();
-  const int64_t rec0 = (((int64_t)b * a.Hq + h * G) * kSlotCap + slot) * kPartStride;
+  const int64_t rec0 = (head0 * kSlotCap + slot) * kPartStride;
   for (int idx = tid; idx < G * kHeadDim; idx += kAttnThreads) {
     const int hh = idx >> 7, dim = idx & 127;
     float s = s_red[0][hh][dim];
@@ -267,15 +474,19 @@ __global__ __launch_bounds__(kAttnThreads) void attn_split_kernel(const AttnArgs
     for (int ww = 1; ww < kWaves; ++ww) M = fmaxf(M, s_m[ww][tid]);
     float ls = 0.f;
 #pragma unroll
-    for (int ww = 0; ww < kWaves; ++ww) ls += s_l[ww][tid] * fast_exp2((s_m[ww][tid] - M) * kLog2e);
+    for (int ww = 0; ww < kWaves; ++ww) ls += s_l[ww][tid] * fast_exp2(s_m[ww][tid] - M);
     float* r = a.part + rec0 + (int64_t)tid * kSlotCap * kPartStride;
-    r[0] = M;
-    r[1] = ls;
+    *reinterpret_cast<float2*>(r) = make_float2(M, ls);
   }
 }
 
-// out[b, g, :] = sum_s e^{m_s - M} acc_s / sum_s e^{m_s - M} l_s over the split records of (b, g).
-__global__ __launch_bounds__(kHeadDim) void merge_kernel(const MergeArgs a) {
+// out[b, g, :] = sum_s 2^{m_s - M} acc_s / sum_s 2^{m_s - M} l_s over the split records of (b, g).
+// 256 threads = 8 record lanes x 32 dim quads: every thread owns four output dims of every eighth
+// record, so all of a thread's loads are independent and in flight together.
+constexpr int kMergeThreads = 256;
+constexpr int kMergeLanes = 8;
+static_assert(kSlotCap <= kMergeThreads, "one record header per thread");
+__global__ __launch_bounds__(kMergeThreads) void merge_kernel(const MergeArgs a) {
   const int bg = blockIdx.x;
   const int b = bg / a.Hq;
   int n_slots;
@@ -283,17 +494,68 @@ __global__ __launch_bounds__(kHeadDim) void merge_kernel(const MergeArgs a) {
   else if (a.mode == 1) n_slots = a.slots_fast;
   else n_slots = a.is_slow[b] ? a.slots_slow : a.slots_fast;
   const float* P = a.part + (int64_t)bg * kSlotCap * kPartStride;
-  const int dim = threadIdx.x;
-  float M = kNeg;
-  for (int s = 0; s < n_slots; ++s) M = fmaxf(M, P[s * kPartStride]);
-  float Z = 0.f, o = 0.f;
-#pragma unroll 8
-  for (int s = 0; s < n_slots; ++s) {
-    const float wgt = fast_exp2((P[s * kPartStride] - M) * kLog2e);
-    Z += wgt * P[s * kPartStride + 1];
-    o += wgt * P[s * kPartStride + 4 + dim];
+  const int tid = threadIdx.x;
+  const int sl = tid >> 5, c = tid & 31;
+
+  __shared__ float s_w[kSlotCap];          // 2^{m_s - M}
+  __shared__ float s_wl[kSlotCap];         // 2^{m_s - M} l_s
+  __shared__ float s_max[kMergeThreads / 64];
+  __shared__ float4 s_acc[kMergeLanes][32];
+
+  // the record headers: one per thread (kSlotCap <= kMergeThreads)
+  float m = kNeg, l = 0.f;
+  if (tid < n_slots) {
+    const float2 ml = *reinterpret_cast<const float2*>(P + tid * kPartStride);
+    m = ml.x;
+    l = ml.y;
   }
-  a.out[(int64_t)bg * kHeadDim + dim] = Z > 0.f ? o / Z : 0.f;
+  float M = m;
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) M = fmaxf(M, __shfl_xor(M, d));
+  if ((tid & 63) == 0) s_max[tid >> 6] = M;
+  // meanwhile the accumulator loads of this thread's records
+  constexpr int kPer = (kSlotCap + kMergeLanes - 1) / kMergeLanes;
+  float4 r[kPer];
+#pragma unroll
+  for (int i = 0; i < kPer; ++i) {
+    const int s = sl + i * kMergeLanes;
+    r[i] = s < n_slots ? *reinterpret_cast<const float4*>(P + s * kPartStride + 4 + 4 * c) : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  __syncthreads();
+  M = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
+  if (tid < n_slots) {
+    const float wgt = fast_exp2(m - M);
+    s_w[tid] = wgt;
+    s_wl[tid] = wgt * l;
+  }
+  __syncthreads();
+  float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+  for (int i = 0; i < kPer; ++i) {
+    const int s = sl + i * kMergeLanes;
+    if (s < n_slots) {
+      const float wgt = s_w[s];
+      o.x += wgt * r[i].x;
+      o.y += wgt * r[i].y;
+      o.z += wgt * r[i].z;
+      o.w += wgt * r[i].w;
+    }
+  }
+  s_acc[sl][c] = o;
+  __syncthreads();
+  if (tid < 32) {
+    float Z = 0.f;
+    for (int s = 0; s < n_slots; ++s) Z += s_wl[s];
+    float4 t = s_acc[0][tid];
+#pragma unroll
+    for (int j = 1; j < kMergeLanes; ++j) {
+      const float4 u = s_acc[j][tid];
+      t.x += u.x; t.y += u.y; t.z += u.z; t.w += u.w;
+    }
+    const float inv = Z > 0.f ? 1.0f / Z : 0.f;
+    *reinterpret_cast<float4*>(a.out + (int64_t)bg * kHeadDim + 4 * tid) =
+        make_float4(t.x * inv, t.y * inv, t.z * inv, t.w * inv);
+  }
 }
 
 __global__ void advance_kernel(int32_t* ctx_len, int32_t* recent_start, int B, int n_sink, int recent) {
@@ -306,15 +568,18 @@ __global__ void advance_kernel(int32_t* ctx_len, int32_t* recent_start, int B, i
 }
 
 hipError_t launch_attn_dense(const AttnArgs& a, int B, int n_slots, hipStream_t s) {
-  hipLaunchKernelGGL(attn_split_kernel<0>, dim3(n_slots, a.Hkv, B), dim3(kAttnThreads), 0, s, a);
+  if (a.logits != nullptr)
+    hipLaunchKernelGGL(attn_dense_kernel<true>, dim3(n_slots, a.Hkv, B), dim3(kAttnThreads), 0, s, a);
+  else
+    hipLaunchKernelGGL(attn_dense_kernel<false>, dim3(n_slots, a.Hkv, B), dim3(kAttnThreads), 0, s, a);
   return hipGetLastError();
 }
 hipError_t launch_attn_gather(const AttnArgs& a, int B, int n_slots, hipStream_t s) {
-  hipLaunchKernelGGL(attn_split_kernel<1>, dim3(n_slots, a.Hkv, B), dim3(kAttnThreads), 0, s, a);
+  hipLaunchKernelGGL(attn_gather_kernel, dim3(n_slots, a.Hkv, B), dim3(kAttnThreads), 0, s, a);
   return hipGetLastError();
 }
 hipError_t launch_merge(const MergeArgs& a, int B, hipStream_t s) {
-  hipLaunchKernelGGL(merge_kernel, dim3(B * a.Hq), dim3(kHeadDim), 0, s, a);
+  hipLaunchKernelGGL(merge_kernel, dim3(B * a.Hq), dim3(kMergeThreads), 0, s, a);
   return hipGetLastError();
 }
 hipError_t launch_advance(int32_t* ctx_len, int32_t* recent_start, int B, int n_sink, int recent, hipStream_t s) {

@@ -12,8 +12,10 @@ constexpr int kTile = 32;          // KV positions per wave iteration (two 16-ro
 constexpr int kWaves = 4;          // waves per attention workgroup
 constexpr int kAttnThreads = 64 * kWaves;
 constexpr int kPartStride = 132;   // floats per split record: m, l, pad, pad, acc[128]
-constexpr int kMaxSplits = 128;    // split workgroups per (sequence, KV head)
-constexpr int kSlotCap = kMaxSplits + 1;  // + one workgroup for the sink and recent rows
+constexpr int kMaxSplits = 63;     // split workgroups per (sequence, KV head)
+// records per (sequence, query head): the dense kernel writes one per wave, (splits + 1 sink/recent
+// workgroup) x 4 waves; the gather kernel one per workgroup
+constexpr int kSlotCap = (kMaxSplits + 1) * kWaves;
 constexpr int kSelSeg = 2048;      // Selector positions per workgroup
 constexpr int kSelThreads = 256;
 constexpr int kHist1Bits = 12;     // first radix pass: bits [30:19] of the fp32 score
@@ -56,7 +58,9 @@ struct AttnArgs {
   uint32_t* state;
   int64_t ld_pos;
   int32_t Hq, Hkv, G, n_sink, recent, n_split;
-  float scale;
+  int32_t max_tiles;             // dense mode: tiles of J the launch covers at most (from the host's max_len)
+  int32_t row_cap;               // dense mode: max_len - 1, the last row the launch may touch
+  float scale_log2;              // logit scale times log2(e): the kernels work on y = log2(e) * logit
 };
 
 struct MergeArgs {

@@ -1,7 +1,8 @@
 // Selector on the GPU (paper Algorithm 2, evidence-only ranking) for gfx950.
 //
 // Per (sequence b, KV head h), over the allowed set J (Eq. allowed_set), positions p = j - n_sink:
-//   p_g(j) = softmax over J of the logits of query head g          (Eq. selector_pt)
+//   p_g(j) = softmax over J of the logits of query head g          (Eq. selector_pt); the dense
+//            kernel left y = log2(e) * logit, so e^{l - M} is 2^{y - M_y}
 //   f(j)   = (1/G) sum_g p_g(j)      (Eqs. selector_mu, selector_f with alpha = 1; the G heads of
 //            the group are the observation window)
 //   z(j)   = log(f(j) + eps)  is monotone in f, so the Top-K of Eq. topk_out is taken on f itself.
@@ -95,7 +96,8 @@ __global__ __launch_bounds__(kSelThreads) void sel_score_kernel(const SelArgs a)
   for (int i = tid; i < kHist1Bins; i += kSelThreads) s_hist[i] = 0u;
 
   // J-only softmax statistics of each head of the group, from the split records of J
-  // (records 0 .. n_split-1 of the dense kernel hold m and sum e^{l-m} over their share of J).
+  // (the first n_split records of the dense kernel, one per wave that covered J, hold the
+  // maximum and the sum of 2^(y - max) over their share of J).
   if (tid < 64) {
     for (int g = 0; g < G; ++g) {
       const float* P = a.part + ((int64_t)(b * a.Hq + h * G + g) * kSlotCap) * kPartStride;
@@ -105,7 +107,7 @@ __global__ __launch_bounds__(kSelThreads) void sel_score_kernel(const SelArgs a)
       for (int d = 32; d >= 1; d >>= 1) m = fmaxf(m, __shfl_xor(m, d));
       float z = 0.f;
       for (int s = tid; s < a.n_split; s += 64)
-        z += P[s * kPartStride + 1] * fast_exp2s((P[s * kPartStride] - m) * kLog2e);
+        z += P[s * kPartStride + 1] * fast_exp2s(P[s * kPartStride] - m);
 #pragma unroll
       for (int d = 32; d >= 1; d >>= 1) z += __shfl_xor(z, d);
       if (tid == 0) {
@@ -116,17 +118,19 @@ __global__ __launch_bounds__(kSelThreads) void sel_score_kernel(const SelArgs a)
   }
   __syncthreads();
 
+  // logits of (b, h): tile-major, [tile of 32 positions][G heads][32]
   const float* lg = a.logits + ((int64_t)(b * a.Hq + h * G)) * a.ld_pos;
   uint32_t* keys = a.keys + (int64_t)bh * a.ld_pos;
   for (int p = p_lo + tid * 4; p < min(p_lo + kSelSeg, pb.nJ); p += kSelThreads * 4) {
     float f0 = 0.f, f1 = 0.f, f2 = 0.f, f3 = 0.f;
+    const float* lt = lg + (int64_t)(p >> 5) * G * kTile + (p & 31);
     for (int g = 0; g < G; ++g) {
-      const float4 l4 = *reinterpret_cast<const float4*>(lg + (int64_t)g * a.ld_pos + p);
+      const float4 l4 = *reinterpret_cast<const float4*>(lt + g * kTile);
       const float M = s_M[g], c = s_c[g];
-      f0 += c * fast_exp2s((l4.x - M) * kLog2e);
-      f1 += c * fast_exp2s((l4.y - M) * kLog2e);
-      f2 += c * fast_exp2s((l4.z - M) * kLog2e);
-      f3 += c * fast_exp2s((l4.w - M) * kLog2e);
+      f0 += c * fast_exp2s(l4.x - M);
+      f1 += c * fast_exp2s(l4.y - M);
+      f2 += c * fast_exp2s(l4.z - M);
+      f3 += c * fast_exp2s(l4.w - M);
     }
     const uint4 k4 = make_uint4(__float_as_uint(f0), __float_as_uint(f1), __float_as_uint(f2), __float_as_uint(f3));
     *reinterpret_cast<uint4*>(keys + p) = k4;
