@@ -289,10 +289,10 @@ int sfi_slow_step(sfi_ctx* x, const void* q, const void* K, const void* V, const
   a.state = x->ws.state;
   x->last_dense_splits = a.n_split;
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(a, x->cfg.batch, a.n_split + 1, st)); if (!t.stop()) return SFI_ELAUNCH; }
-  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, (a.n_split + 1) * kWaves, 0, 0};
-  { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   SelArgs sa;
   fill_sel(x, &sa, ctx_len, nullptr, budget, a.n_split, sel_idx, n_sel);
+  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, (a.n_split + 1) * kWaves, 0, 0};
+  { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return run_selector(x, sa, ml, st);
 }
 

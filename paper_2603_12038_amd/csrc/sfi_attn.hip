@@ -26,6 +26,7 @@
 // bf16 x bf16 products are exact in fp32, so logits differ from an fp64 evaluation only by the
 // fp32 accumulation inside the matrix core.
 #include "sfi_internal.h"
+#include "sfi_merge.h"
 
 namespace sfi {
 
@@ -480,12 +481,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_kernel(const Attn
   }
 }
 
-// out[b, g, :] = sum_s 2^{m_s - M} acc_s / sum_s 2^{m_s - M} l_s over the split records of (b, g).
-// 256 threads = 8 record lanes x 32 dim quads: every thread owns four output dims of every eighth
-// record, so all of a thread's loads are independent and in flight together.
-constexpr int kMergeThreads = 256;
-constexpr int kMergeLanes = 8;
-static_assert(kSlotCap <= kMergeThreads, "one record header per thread");
+// Stand-alone merge: one workgroup per (sequence, query head).
 __global__ __launch_bounds__(kMergeThreads) void merge_kernel(const MergeArgs a) {
   const int bg = blockIdx.x;
   const int b = bg / a.Hq;
@@ -493,69 +489,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(const MergeArgs a)
   if (a.mode == 0) n_slots = a.slots_slow;
   else if (a.mode == 1) n_slots = a.slots_fast;
   else n_slots = a.is_slow[b] ? a.slots_slow : a.slots_fast;
-  const float* P = a.part + (int64_t)bg * kSlotCap * kPartStride;
-  const int tid = threadIdx.x;
-  const int sl = tid >> 5, c = tid & 31;
-
-  __shared__ float s_w[kSlotCap];          // 2^{m_s - M}
-  __shared__ float s_wl[kSlotCap];         // 2^{m_s - M} l_s
-  __shared__ float s_max[kMergeThreads / 64];
-  __shared__ float4 s_acc[kMergeLanes][32];
-
-  // the record headers: one per thread (kSlotCap <= kMergeThreads)
-  float m = kNeg, l = 0.f;
-  if (tid < n_slots) {
-    const float2 ml = *reinterpret_cast<const float2*>(P + tid * kPartStride);
-    m = ml.x;
-    l = ml.y;
-  }
-  float M = m;
-#pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) M = fmaxf(M, __shfl_xor(M, d));
-  if ((tid & 63) == 0) s_max[tid >> 6] = M;
-  // meanwhile the accumulator loads of this thread's records
-  constexpr int kPer = (kSlotCap + kMergeLanes - 1) / kMergeLanes;
-  float4 r[kPer];
-#pragma unroll
-  for (int i = 0; i < kPer; ++i) {
-    const int s = sl + i * kMergeLanes;
-    r[i] = s < n_slots ? *reinterpret_cast<const float4*>(P + s * kPartStride + 4 + 4 * c) : make_float4(0.f, 0.f, 0.f, 0.f);
-  }
-  __syncthreads();
-  M = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
-  if (tid < n_slots) {
-    const float wgt = fast_exp2(m - M);
-    s_w[tid] = wgt;
-    s_wl[tid] = wgt * l;
-  }
-  __syncthreads();
-  float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-  for (int i = 0; i < kPer; ++i) {
-    const int s = sl + i * kMergeLanes;
-    if (s < n_slots) {
-      const float wgt = s_w[s];
-      o.x += wgt * r[i].x;
-      o.y += wgt * r[i].y;
-      o.z += wgt * r[i].z;
-      o.w += wgt * r[i].w;
-    }
-  }
-  s_acc[sl][c] = o;
-  __syncthreads();
-  if (tid < 32) {
-    float Z = 0.f;
-    for (int s = 0; s < n_slots; ++s) Z += s_wl[s];
-    float4 t = s_acc[0][tid];
-#pragma unroll
-    for (int j = 1; j < kMergeLanes; ++j) {
-      const float4 u = s_acc[j][tid];
-      t.x += u.x; t.y += u.y; t.z += u.z; t.w += u.w;
-    }
-    const float inv = Z > 0.f ? 1.0f / Z : 0.f;
-    *reinterpret_cast<float4*>(a.out + (int64_t)bg * kHeadDim + 4 * tid) =
-        make_float4(t.x * inv, t.y * inv, t.z * inv, t.w * inv);
-  }
+  merge_records(a.part, a.out, bg, n_slots);
 }
 
 __global__ void advance_kernel(int32_t* ctx_len, int32_t* recent_start, int B, int n_sink, int recent) {

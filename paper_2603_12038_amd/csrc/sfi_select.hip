@@ -95,25 +95,49 @@ __global__ __launch_bounds__(kSelThreads) void sel_score_kernel(const SelArgs a)
   __shared__ float s_M[16], s_c[16];
   for (int i = tid; i < kHist1Bins; i += kSelThreads) s_hist[i] = 0u;
 
-  // J-only softmax statistics of each head of the group, from the split records of J
-  // (the first n_split records of the dense kernel, one per wave that covered J, hold the
-  // maximum and the sum of 2^(y - max) over their share of J).
-  if (tid < 64) {
-    for (int g = 0; g < G; ++g) {
-      const float* P = a.part + ((int64_t)(b * a.Hq + h * G + g) * kSlotCap) * kPartStride;
-      float m = kNeg;
-      for (int s = tid; s < a.n_split; s += 64) m = fmaxf(m, P[s * kPartStride]);
+  // J-only softmax statistics of each head of the group, from the split records of J (the first
+  // n_split records of the dense kernel, one per wave that covered J, hold the maximum and the sum
+  // of 2^(y - max) over their share of J).  Thread s reads record s of every head at once.
+  __shared__ float s_wm[kSelThreads / 64][16], s_wz[kSelThreads / 64][16];
+  static_assert(kSlotCap <= kSelThreads, "one record per thread");
+  {
+    float rm[16], rl[16];
 #pragma unroll
-      for (int d = 32; d >= 1; d >>= 1) m = fmaxf(m, __shfl_xor(m, d));
-      float z = 0.f;
-      for (int s = tid; s < a.n_split; s += 64)
-        z += P[s * kPartStride + 1] * fast_exp2s(P[s * kPartStride] - m);
-#pragma unroll
-      for (int d = 32; d >= 1; d >>= 1) z += __shfl_xor(z, d);
-      if (tid == 0) {
-        s_M[g] = m;
-        s_c[g] = 1.0f / ((float)G * z);
+    for (int g = 0; g < 16; ++g) {
+      rm[g] = kNeg;
+      rl[g] = 0.f;
+      if (g < G && tid < a.n_split) {
+        const float2 ml = *reinterpret_cast<const float2*>(
+            a.part + ((int64_t)(b * a.Hq + h * G + g) * kSlotCap + tid) * kPartStride);
+        rm[g] = ml.x;
+        rl[g] = ml.y;
       }
+    }
+    const int wv = tid >> 6;
+#pragma unroll
+    for (int g = 0; g < 16; ++g) {
+      if (g < G) {
+        float m = rm[g];
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) m = fmaxf(m, __shfl_xor(m, d));
+        if ((tid & 63) == 0) s_wm[wv][g] = m;
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int g = 0; g < 16; ++g) {
+      if (g < G) {
+        const float M = fmaxf(fmaxf(s_wm[0][g], s_wm[1][g]), fmaxf(s_wm[2][g], s_wm[3][g]));
+        float z = rl[g] * fast_exp2s(rm[g] - M);
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) z += __shfl_xor(z, d);
+        if ((tid & 63) == 0) s_wz[wv][g] = z;
+      }
+    }
+    __syncthreads();
+    if (tid < G) {
+      s_M[tid] = fmaxf(fmaxf(s_wm[0][tid], s_wm[1][tid]), fmaxf(s_wm[2][tid], s_wm[3][tid]));
+      s_c[tid] = 1.0f / ((float)G * (s_wz[0][tid] + s_wz[1][tid] + s_wz[2][tid] + s_wz[3][tid]));
     }
   }
   __syncthreads();
@@ -165,6 +189,21 @@ __global__ __launch_bounds__(kSelThreads) void sel_cand_kernel(const SelArgs a) 
   }
   if (p_lo >= pb.nJ) return;
 
+  const uint32_t* keys = a.keys + (int64_t)bh * a.ld_pos;
+  uint32_t* cand = a.cand + (int64_t)bh * a.ld_pos;
+  const int lane = tid & 63;
+  // a thread owns 8 consecutive keys (the key row is padded to a whole segment, so both 16-byte
+  // loads are always readable); they are fetched while the threshold bin is being found
+  constexpr int kPer = kSelSeg / kSelThreads;
+  static_assert(kPer == 8, "two 16-byte key loads per thread");
+  const int p0 = p_lo + tid * kPer;
+  uint32_t key[kPer];
+  {
+    const uint4 k0 = *reinterpret_cast<const uint4*>(keys + p0);
+    const uint4 k1 = *reinterpret_cast<const uint4*>(keys + p0 + 4);
+    key[0] = k0.x; key[1] = k0.y; key[2] = k0.z; key[3] = k0.w;
+    key[4] = k1.x; key[5] = k1.y; key[6] = k1.z; key[7] = k1.w;
+  }
   __shared__ uint32_t s_res[2];
   __shared__ uint32_t s_scr[8];
   find_kth_desc(a.hist1 + (int64_t)bh * kHist1Bins, kHist1Bins, pb.ksel, s_res, s_scr);
@@ -175,26 +214,26 @@ __global__ __launch_bounds__(kSelThreads) void sel_cand_kernel(const SelArgs a) 
     st[ST_KSEL] = pb.ksel;
     st[ST_FLAGS] = 0u;
   }
-  const uint32_t* keys = a.keys + (int64_t)bh * a.ld_pos;
-  uint32_t* cand = a.cand + (int64_t)bh * a.ld_pos;
-  const int lane = tid & 63;
-  const int p_hi = min(p_lo + kSelSeg, pb.nJ);
-  for (int p0 = p_lo; p0 < p_hi; p0 += kSelThreads) {
-    const int p = p0 + tid;
-    uint32_t key = 0;
-    bool is_c = false;
-    if (p < p_hi) {
-      key = keys[p];
-      is_c = (key >> 19) == bin1;
-    }
-    const unsigned long long mask = __ballot(is_c);
-    if (mask != 0ull) {
-      const int leader = __ffsll((long long)mask) - 1;
-      uint32_t base = 0;
-      if (lane == leader) base = atomicAdd(&st[ST_CAND], (uint32_t)__popcll(mask));
-      base = __shfl(base, leader);
-      if (is_c) cand[base + __popcll(mask & ((1ull << lane) - 1ull))] = key;
-    }
+  uint32_t mine = 0;  // bit i: key i falls into the threshold bin
+#pragma unroll
+  for (int i = 0; i < kPer; ++i)
+    if (p0 + i < pb.nJ && (key[i] >> 19) == bin1) mine |= 1u << i;
+  // one atomic per wave: lanes get consecutive runs of the reserved range
+  const uint32_t cnt = __popc(mine);
+  uint32_t incl = cnt;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const uint32_t t = __shfl_up(incl, d);
+    if (lane >= d) incl += t;
+  }
+  const uint32_t wave_total = __shfl(incl, 63);
+  uint32_t base = 0;
+  if (wave_total != 0u) {
+    if (lane == 63) base = atomicAdd(&st[ST_CAND], wave_total);
+    base = __shfl(base, 63) + incl - cnt;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i)
+      if (mine & (1u << i)) cand[base++] = key[i];
   }
 }
 
@@ -244,12 +283,19 @@ __global__ __launch_bounds__(kSelThreads) void sel_count_kernel(const SelArgs a)
   if (tid < 2) s_cnt[tid] = 0u;
   __syncthreads();
   const uint32_t* keys = a.keys + (int64_t)bh * a.ld_pos;
-  const int p_hi = min(p_lo + kSelSeg, pb.nJ);
   uint32_t gt = 0, eq = 0;
-  for (int p = p_lo + tid; p < p_hi; p += kSelThreads) {
-    const uint32_t key = keys[p];
-    gt += key > tau;
-    eq += key == tau;
+  {
+    const int p0 = p_lo + tid * 8;
+    const uint4 k0 = *reinterpret_cast<const uint4*>(keys + p0);
+    const uint4 k1 = *reinterpret_cast<const uint4*>(keys + p0 + 4);
+    const uint32_t key[8] = {k0.x, k0.y, k0.z, k0.w, k1.x, k1.y, k1.z, k1.w};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      if (p0 + i < pb.nJ) {
+        gt += key[i] > tau;
+        eq += key[i] == tau;
+      }
+    }
   }
 #pragma unroll
   for (int d = 32; d >= 1; d >>= 1) {
