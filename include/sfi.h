@@ -160,7 +160,8 @@ int sfi_set_profiling(sfi_ctx* ctx, int on);
 int sfi_stage_times(sfi_ctx* ctx, float* ms /* host, [SFI_N_STAGES] */);
 
 /* Launch-geometry knobs for sweeps (values <= 0 keep the current setting):
- * dense_target_wgs     workgroups the dense launch aims for (default 2 per compute unit: all resident at once);
+ * dense_target_wgs     workgroups a dense launch aims for in total (default 2 per compute unit: all
+ *                      resident at once, one round of equal shares);
  * fast_tiles_per_wave  32-row tiles each wave of the gather launch gets (default 1). */
 int sfi_set_tuning(sfi_ctx* ctx, int32_t dense_target_wgs, int32_t fast_tiles_per_wave);
 

@@ -74,11 +74,16 @@ size_t carve(const sfi_config* c, char* base, Workspace* ws) {
 
 inline bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
 
-int dense_splits_for(const sfi_ctx* x, int max_len) {
+// Split workgroups per (sequence, KV head) of a dense launch.  All sequences dense: aim at
+// dense_target_wgs workgroups in total, the sink/recent workgroup of each pair included (two per
+// compute unit by default: every workgroup resident at once, one round, equal shares).  Mixed step:
+// the host cannot know how many sequences are slow, so take the finest split; workgroups of fast
+// sequences exit at once.
+int dense_splits_for(const sfi_ctx* x, int max_len, bool mixed) {
   const int nJ = max_len - x->cfg.recent - x->cfg.n_sink;
   const int tiles = nJ > 0 ? (nJ + kTile - 1) / kTile : 0;
   const int pairs = x->cfg.batch * x->cfg.n_kv_heads;
-  int s = (x->dense_target_wgs + pairs - 1) / pairs;
+  int s = mixed ? kMaxSplits : x->dense_target_wgs / pairs - 1;
   const int cap = (tiles + kWaves - 1) / kWaves;
   if (s > cap) s = cap;
   if (s > kMaxSplits) s = kMaxSplits;
@@ -259,7 +264,7 @@ int sfi_dense_attn(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   clear_stage_flags(x);
   AttnArgs a;
   fill_attn(x, &a, q, K, V, ctx_len);
-  a.n_split = dense_splits_for(x, ml);
+  a.n_split = dense_splits_for(x, ml, false);
   set_dense_bounds(x, &a, ml);
   x->last_dense_splits = a.n_split;
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(a, x->cfg.batch, a.n_split + 1, st)); if (!t.stop()) return SFI_ELAUNCH; }
@@ -282,7 +287,7 @@ int sfi_slow_step(sfi_ctx* x, const void* q, const void* K, const void* V, const
   clear_stage_flags(x);
   AttnArgs a;
   fill_attn(x, &a, q, K, V, ctx_len);
-  a.n_split = dense_splits_for(x, ml);
+  a.n_split = dense_splits_for(x, ml, false);
   set_dense_bounds(x, &a, ml);
   a.logits = x->ws.logits;
   a.hist1 = x->ws.hist1;
@@ -336,7 +341,7 @@ int sfi_mixed_step(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   AttnArgs d;
   fill_attn(x, &d, q, K, V, ctx_len);
   d.is_slow = is_slow;
-  d.n_split = dense_splits_for(x, ml);
+  d.n_split = dense_splits_for(x, ml, true);
   set_dense_bounds(x, &d, ml);
   d.logits = x->ws.logits;
   d.hist1 = x->ws.hist1;

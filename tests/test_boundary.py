@@ -1,0 +1,110 @@
+"""The C-ABI boundary on the host (no GPU): the library loads, exports what include/sfi.h declares,
+and rejects bad arguments with error codes before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2603_12038_amd as sfi
+from paper_2603_12038_amd.binding import SfiConfig
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EALIGN = 0, -1, -2, -3, -4
+
+
+def good_cfg(**over):
+    c = SfiConfig()
+    c.batch, c.n_q_heads, c.n_kv_heads, c.head_dim = 2, 8, 2, 128
+    c.max_ctx, c.max_budget, c.n_sink, c.recent = 4096, 256, 4, 64
+    c.scale, c.selector_mode = 0.0, 0
+    c.k_stride_t, c.k_stride_h, c.k_stride_b = 128, 128 * 4096, 2 * 128 * 4096
+    c.v_stride_t, c.v_stride_h, c.v_stride_b = 128, 128 * 4096, 2 * 128 * 4096
+    for k, v in over.items():
+        setattr(c, k, v)
+    return c
+
+
+def test_library_exports_every_declared_symbol():
+    lib = sfi.load_library()
+    header = open(os.path.join(ROOT, "include", "sfi.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(sfi_[a-z_]+)\s*\(", header))
+    assert {"sfi_slow_step", "sfi_fast_step", "sfi_mixed_step", "sfi_create", "sfi_workspace_bytes"} <= declared
+    for name in sorted(declared):
+        assert hasattr(lib, name), f"{name} declared in sfi.h but not exported"
+    assert declared == set(sfi.binding.EXPORTS), "binding and header disagree on the entry points"
+
+
+def test_workspace_bytes_and_config_validation():
+    assert sfi.sfi_workspace_bytes(good_cfg()) > 0
+    assert sfi.sfi_workspace_bytes(good_cfg()) % 256 == 0
+    bigger = sfi.sfi_workspace_bytes(good_cfg(max_ctx=8192))
+    assert bigger > sfi.sfi_workspace_bytes(good_cfg())
+    for bad in (dict(batch=0), dict(n_kv_heads=0), dict(n_q_heads=7), dict(head_dim=64), dict(max_ctx=0),
+                dict(max_budget=-1), dict(n_sink=-1), dict(recent=-1), dict(k_stride_t=100), dict(v_stride_h=12),
+                dict(selector_mode=1), dict(n_q_heads=64, n_kv_heads=2), dict(scale=-1.0),
+                dict(max_ctx=1 << 24, k_stride_t=128 * 8)):
+        assert sfi.sfi_workspace_bytes(good_cfg(**bad)) == 0, bad
+
+
+def test_create_rejects_bad_arguments_without_touching_a_device():
+    lib = sfi.load_library()
+    need = sfi.sfi_workspace_bytes(good_cfg())
+    h = C.c_void_p()
+    fake = 0x10000  # never dereferenced: creation only records the address
+    assert lib.sfi_create(None, fake, need, C.byref(h)) == EINVAL
+    assert lib.sfi_create(C.byref(good_cfg()), None, need, C.byref(h)) == EINVAL
+    assert lib.sfi_create(C.byref(good_cfg()), fake, need, None) == EINVAL
+    assert lib.sfi_create(C.byref(good_cfg()), fake + 8, need, C.byref(h)) == EWORKSPACE
+    assert lib.sfi_create(C.byref(good_cfg()), fake, need - 1, C.byref(h)) == EWORKSPACE
+    assert lib.sfi_create(C.byref(good_cfg(head_dim=96)), fake, need, C.byref(h)) == EUNSUPPORTED
+    assert lib.sfi_create(C.byref(good_cfg(k_stride_t=132)), fake, need, C.byref(h)) == EALIGN
+    assert h.value is None
+
+
+def test_status_texts():
+    for code in (0, -1, -2, -3, -4, -5, -6):
+        assert sfi.sfi_strerror(code) and sfi.sfi_strerror(code) != "unknown status"
+    assert sfi.sfi_strerror(-99) == "unknown status"
+    assert sfi.sfi_destroy is not None
+    with pytest.raises(sfi.SfiError):
+        sfi.sfi_destroy(None)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in r.stderr
+
+
+def test_hot_calls_reject_bad_arguments_before_any_launch():
+    """A context over a never-dereferenced workspace address: every call below returns an error code
+    from the host-side checks, so nothing is launched (this runs without a GPU)."""
+    lib = sfi.load_library()
+    cfg = good_cfg()
+    need = sfi.sfi_workspace_bytes(cfg)
+    h = C.c_void_p()
+    assert lib.sfi_create(C.byref(cfg), 0x10000, need, C.byref(h)) == OK and h.value
+    p = 0x20000  # stands for any 16-byte aligned device pointer; never used by a failing call
+    try:
+        assert lib.sfi_slow_step(h, None, p, p, p, 0, 64, p, p, p, None) == EINVAL
+        assert lib.sfi_slow_step(h, p, p, p, p, 0, 64, p, None, p, None) == EINVAL
+        assert lib.sfi_slow_step(h, p, p, p, p, 0, cfg.max_budget + 1, p, p, p, None) == EINVAL
+        assert lib.sfi_slow_step(h, p, p, p, p, 0, -1, p, p, p, None) == EINVAL
+        assert lib.sfi_slow_step(h, p, p, p, p, cfg.max_ctx + 1, 64, p, p, p, None) == EINVAL
+        assert lib.sfi_slow_step(h, p + 2, p, p, p, 0, 64, p, p, p, None) == EALIGN
+        assert lib.sfi_slow_step(h, p, p, p, p, 0, 64, p + 4, p, p, None) == EALIGN
+        assert lib.sfi_dense_attn(h, p, p, None, p, 0, p, None) == EINVAL
+        assert lib.sfi_fast_step(h, p, p, p, None, p, 64, p, p, p, None) == EINVAL
+        assert lib.sfi_fast_step(h, p, p, p, p, p, cfg.max_budget + 1, p, p, p, None) == EINVAL
+        assert lib.sfi_fast_step(h, p, p, p, p, p, 64, p + 1, p, p, None) == EALIGN
+        assert lib.sfi_mixed_step(h, p, p, p, None, p, p, 0, 64, p, p, p, None) == EINVAL
+        assert lib.sfi_advance(h, None, p, None) == EINVAL
+        assert lib.sfi_stage_times(h, None) == EINVAL
+        assert lib.sfi_set_tuning(None, 1, 1) == EINVAL
+        d, f = C.c_int32(-1), C.c_int32(-1)
+        assert lib.sfi_query_splits(h, C.byref(d), C.byref(f)) == OK and d.value == 0 and f.value == 0
+    finally:
+        assert lib.sfi_destroy(h) == OK

@@ -1,0 +1,130 @@
+"""GPU parity at the baseline configurations' full sizes, in the launch configuration bench.py times.
+
+The oracle finishes these sizes in well under a second per step on the GPU machine's host cores, so
+every output element and every index set is compared (not a sample)."""
+import numpy as np
+import pytest
+
+import sfi_synth as syn
+from helpers import Runner, check_out, check_selection, i32_dev, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _step(msg):
+    print(f"[gpu-full] {msg}", flush=True)
+
+
+def _slow_then_fast(oracle, w, n_fast=2):
+    r = Runner(w)
+    try:
+        q0, c0 = w.q(0), w.ctx_len(0)
+        _step(f"{w.name}: slow step B={w.B} Hq={w.Hq} Hkv={w.Hkv} ctx={int(c0.max())} K={w.budget}")
+        out, sel, nsel = r.slow(q0, c0, w.budget)
+        e = check_out(out, oracle.dense(q0, w.K, w.V, c0))
+        sel_ref, nsel_ref, z = oracle.selector(q0, w.K, c0, w.budget, w.n_sink, w.recent)
+        n_exact = check_selection(sel, nsel, sel_ref, nsel_ref, z, c0, w.n_sink, w.recent, w.budget)
+        _step(f"  slow out err {e:.2e}; index sets identical to the oracle's: {n_exact}/{w.B * w.Hkv}")
+        assert n_exact >= (w.B * w.Hkv) // 2
+        for t in range(1, 1 + n_fast):
+            q, ct, rt = w.q(t), w.ctx_len(t), w.recent_start(t)
+            got = r.fast(q, sel, nsel, rt, ct)
+            e = check_out(got, oracle.sparse(q, w.K, w.V, sel, nsel, rt, ct, w.n_sink))
+            _step(f"  fast step {t} out err {e:.2e}")
+        return r
+    except Exception:
+        r.close()
+        raise
+
+
+def test_llama8b_shaped_layer(oracle):
+    """Config 2: B4, 32/8 heads, ctx 32768, K = 2048, recent 128 — the workload bench.py times."""
+    w = syn.make_llama8b(steps=8)
+    r = _slow_then_fast(oracle, w)
+    try:
+        # support drift: 10 % of the planted rows move, then the next slow step must follow them
+        patches = syn.drift_support(w, epoch=1)
+        Kd = to_dev(w.K)
+        r.K.copy_(Kd)
+        q, c = w.q(3), w.ctx_len(3)
+        out, sel, nsel = r.slow(q, c, w.budget)
+        check_out(out, oracle.dense(q, w.K, w.V, c))
+        sel_ref, nsel_ref, z = oracle.selector(q, w.K, c, w.budget, w.n_sink, w.recent)
+        check_selection(sel, nsel, sel_ref, nsel_ref, z, c, w.n_sink, w.recent, w.budget)
+        assert len(patches) == w.B * w.Hkv
+    finally:
+        r.close()
+
+
+def test_long_single_stream(oracle):
+    """Config 3: B1, 32/8 heads, ctx 131072, clustered support, K = 4096, recent 256."""
+    w = syn.make_long(steps=4)
+    _slow_then_fast(oracle, w).close()
+
+
+def test_long_cot_window(oracle):
+    """Config 4 at the 24K sample point: B8, 40/8 heads (G = 5), K = 1024, recent 128."""
+    w = syn.make_cot(L0=24576, steps=4)
+    _slow_then_fast(oracle, w).close()
+
+
+def test_serving_mix_ragged(oracle):
+    """Config 5 shape at a quarter of the batch: B8, 64/8 heads (G = 8), ragged ctx in [16384, 65536],
+    K = 2048: first step all slow, then a mixed step with per-sequence modes."""
+    import torch
+    import paper_2603_12038_amd as sfi
+
+    w = syn.make_serving(steps=4, B=8)
+    r = Runner(w)
+    try:
+        B = w.B
+        ctx_d, rs_d = i32_dev(w.ctx_len(0)), i32_dev(w.recent_start(0))
+        sel_d = torch.full((B, w.Hkv, w.budget), -7, dtype=torch.int32, device="cuda")
+        nsel_d = torch.full((B, w.Hkv), -7, dtype=torch.int32, device="cuda")
+        q0, c0 = w.q(0), w.ctx_len(0)
+        _step(f"serving mix: all-slow mixed step, ctx {c0.tolist()}")
+        sfi.sfi_mixed_step(r.ctx.handle, to_dev(q0), r.K, r.V, torch.ones(B, dtype=torch.uint8, device="cuda"), ctx_d,
+                           rs_d, 0, w.budget, r.out, sel_d, nsel_d)
+        torch.cuda.synchronize()
+        check_out(r.out.cpu().numpy(), oracle.dense(q0, w.K, w.V, c0))
+        sel_ref, nsel_ref, z = oracle.selector(q0, w.K, c0, w.budget, w.n_sink, w.recent)
+        sel0, nsel0 = sel_d.cpu().numpy(), nsel_d.cpu().numpy()
+        check_selection(sel0, nsel0, sel_ref, nsel_ref, z, c0, w.n_sink, w.recent, w.budget)
+        sfi.sfi_advance(r.ctx.handle, ctx_d, rs_d)
+        slow1 = np.zeros(B, np.uint8)
+        slow1[[2, 5]] = 1
+        q1, c1, rs1 = w.q(1), w.ctx_len(1), w.recent_start(1)
+        _step("serving mix: 2 slow + 6 fast sequences in one call")
+        sfi.sfi_mixed_step(r.ctx.handle, to_dev(q1), r.K, r.V, torch.from_numpy(slow1).cuda(), ctx_d, rs_d, 0,
+                           w.budget, r.out, sel_d, nsel_d)
+        torch.cuda.synchronize()
+        got = r.out.cpu().numpy()
+        ref_d = oracle.dense(q1, w.K, w.V, c1)
+        ref_s = oracle.sparse(q1, w.K, w.V, sel0, nsel0, rs1, c1, w.n_sink)
+        sel1, nsel1 = sel_d.cpu().numpy(), nsel_d.cpu().numpy()
+        sel_ref1, nsel_ref1, z1 = oracle.selector(q1, w.K, c1, w.budget, w.n_sink, w.recent)
+        for b in range(B):
+            if slow1[b]:
+                check_out(got[b], ref_d[b])
+                check_selection(sel1[b:b + 1], nsel1[b:b + 1], sel_ref1[b:b + 1], nsel_ref1[b:b + 1], z1[b:b + 1],
+                                c1[b:b + 1], w.n_sink, w.recent, w.budget)
+            else:
+                check_out(got[b], ref_s[b])
+                assert (sel1[b] == sel0[b]).all()
+    finally:
+        r.close()
+
+
+def test_retention_sweep_shape(oracle):
+    """Shape of the paper's kernel-speedup table: KV length 16K, batch 16, retention 25 %."""
+    w = syn.make_retention_sweep(0.25)
+    r = Runner(w)
+    try:
+        _step("retention sweep shape, 25 %")
+        q, c = w.q(0), w.ctx_len(0)
+        out, sel, nsel = r.slow(q, c, w.budget)
+        check_out(out, oracle.dense(q, w.K, w.V, c))
+        got = r.fast(q, sel, nsel, w.recent_start(0), c)
+        check_out(got, oracle.sparse(q, w.K, w.V, sel, nsel, w.recent_start(0), c, w.n_sink))
+    finally:
+        r.close()
