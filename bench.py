@@ -67,7 +67,7 @@ def main():
     n_dec = SEG * (K_seg + W_seg)
 
     t0 = time.time()
-    w = syn.make_llama8b(L0=args.ctx, steps=n_dec + SEG, B=args.batch)
+    w = syn.make_llama8b(L0=args.ctx, steps=n_dec + SEG, B=args.batch)  # rows for the schedule + a spare segment
     log(f"generated workload in {time.time() - t0:.1f}s: B={w.B} Hq={w.Hq} Hkv={w.Hkv} L0={args.ctx} "
         f"K={w.budget} R={w.recent} layers={NL}")
     B, Hq, Hkv, d, L0 = w.B, w.Hq, w.Hkv, w.d, args.ctx
@@ -186,23 +186,24 @@ def main():
     tokens = B * SEG * K_seg * NL
     value = tokens / total_s
 
-    # ---- per-kernel times with HIP events on the launch stream (separate instrumented pass) -----------
-    sfi.sfi_set_profiling(h, True)
-    acc = {"slow": np.zeros(8), "fast": np.zeros(8)}
-    cnt = {"slow": 0, "fast": 0}
+    # ---- per-kernel times: every kernel bracketed by HIP events on the launch stream (recorded by the
+    # library into a ring, read back after the pass: no host sync between the profiled calls).  Slow and
+    # fast calls are recorded in separate passes over all virtual layers, at the context the timed
+    # region ended on.
     step_p = step0 + K_seg * SEG
-    for rep in range(1):
-        for t in range(SEG):
+
+    def stage_avg_ms(fn, reps):
+        sfi.sfi_set_profiling(h, reps * NL)
+        for r in range(reps):
             for l in range(NL):
-                kind = "slow" if t == 0 else "fast"
-                (slow if t == 0 else fast)(l, step_p + t)
-                acc[kind] += np.array(sfi.sfi_stage_times(h))
-                cnt[kind] += 1
-            sfi.sfi_advance(h, ctx_d, rs_d)
-    sfi.sfi_set_profiling(h, False)
-    torch.cuda.synchronize()
-    slow_ms = acc["slow"] / max(cnt["slow"], 1)
-    fast_ms = acc["fast"] / max(cnt["fast"], 1)
+                fn(l, step_p + r)
+        torch.cuda.synchronize()
+        ms_sum, cnt = sfi.sfi_stage_times(h)
+        sfi.sfi_set_profiling(h, 0)
+        return np.array(ms_sum) / np.maximum(np.array(cnt), 1)
+
+    slow_ms = stage_avg_ms(slow, 2)
+    fast_ms = stage_avg_ms(fast, 8)
     L_mid = L0 + step_p
     dense_bytes = B * Hkv * L_mid * d * 2 * 2
     nsel_mean = float(torch.stack(nsels).float().mean())
@@ -210,13 +211,20 @@ def main():
     fast_bytes = B * Hkv * fast_rows * d * 2 * 2
     dense_gbs = dense_bytes / (slow_ms[0] * 1e-3) / 1e9
     fast_gbs = fast_bytes / (fast_ms[0] * 1e-3) / 1e9
+    # the kernel with the largest share of a segment's time is the one the roofline object describes
     seg_dense_ms = slow_ms[0]
     seg_fast_ms = fast_ms[0] * (SEG - 1)
     dominant = "gather" if seg_fast_ms > seg_dense_ms else "dense"
+    traffic = None  # HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one
+    pmc_path = os.path.join(ROOT, "profiles", "hbm_traffic_llama8b.json")
+    if os.path.exists(pmc_path) and args.ctx == 32768 and args.batch == 4:
+        traffic = json.load(open(pmc_path)).get(f"attn_{dominant}_kernel", {}).get("hbm_bytes_per_launch")
     roof = {
-        "bound": "hbm", "kernel": f"attn_split_kernel<{'1' if dominant == 'gather' else '0'}> ({dominant})",
+        "bound": "hbm", "kernel": f"sfi::attn_{dominant}_kernel",
         "achieved": fast_gbs if dominant == "gather" else dense_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": (fast_gbs if dominant == "gather" else dense_gbs) / HBM_PEAK_GBS, "traffic": None,
+        "frac": (fast_gbs if dominant == "gather" else dense_gbs) / HBM_PEAK_GBS, "traffic": traffic,
+        "algorithmic_bytes_per_launch": fast_bytes if dominant == "gather" else dense_bytes,
+        "us_per_launch": float((fast_ms[0] if dominant == "gather" else slow_ms[0]) * 1e3),
     }
     dsp, fsp = sfi.sfi_query_splits(h)
     res = {

@@ -141,23 +141,25 @@ int sfi_mixed_step(sfi_ctx* ctx, const void* q, const void* K, const void* V, co
 int sfi_advance(sfi_ctx* ctx, int32_t* ctx_len, int32_t* recent_start, void* stream);
 
 /*
- * Per-kernel timing for benchmarks.  With profiling on, each hot call brackets every kernel it
- * launches with HIP events on the caller's stream; sfi_stage_times waits for the last call's
- * events and returns their elapsed milliseconds (0 for stages the call did not run).
- * Not for production loops: event records add launch gaps.
+ * Per-kernel timing for benchmarks.  sfi_set_profiling(ctx, max_calls) with max_calls > 0 makes each
+ * of the next max_calls hot calls bracket every kernel it launches with a pair of HIP events on the
+ * caller's stream (no host synchronisation in between); max_calls = 0 switches it off.
+ * sfi_stage_times waits for the recorded events and returns, per stage, the sum of elapsed
+ * milliseconds and the number of launches over the calls recorded since profiling was switched on.
+ * Not for production loops: event records add a gap of a few microseconds around every kernel.
  */
 enum {
-  SFI_STAGE_ATTN = 0,     /* split attention kernel (dense or gather) */
+  SFI_STAGE_ATTN = 0,     /* split attention kernel (dense; or gather in a fast step) */
   SFI_STAGE_MERGE = 1,    /* split merge */
   SFI_STAGE_SCORE = 2,    /* evidence + first radix histogram */
   SFI_STAGE_CAND = 3,     /* threshold-bin candidates */
   SFI_STAGE_COUNT = 4,    /* exact threshold + per-segment counts */
   SFI_STAGE_WRITE = 5,    /* ordered index write */
-  SFI_STAGE_ATTN2 = 6,    /* second attention kernel of a mixed step (the gather part) */
+  SFI_STAGE_ATTN2 = 6,    /* the gather attention kernel of a mixed step */
   SFI_N_STAGES = 8
 };
-int sfi_set_profiling(sfi_ctx* ctx, int on);
-int sfi_stage_times(sfi_ctx* ctx, float* ms /* host, [SFI_N_STAGES] */);
+int sfi_set_profiling(sfi_ctx* ctx, int max_calls);
+int sfi_stage_times(sfi_ctx* ctx, float* ms_sum /* host, [SFI_N_STAGES] */, int32_t* count /* host, [SFI_N_STAGES] */);
 
 /* Launch-geometry knobs for sweeps (values <= 0 keep the current setting):
  * dense_target_wgs     workgroups a dense launch aims for in total (default 2 per compute unit: all

@@ -70,7 +70,7 @@ def load_library() -> C.CDLL:
     lib.sfi_set_profiling.restype = C.c_int
     lib.sfi_set_profiling.argtypes = [vp, C.c_int]
     lib.sfi_stage_times.restype = C.c_int
-    lib.sfi_stage_times.argtypes = [vp, C.POINTER(C.c_float)]
+    lib.sfi_stage_times.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
     lib.sfi_set_tuning.restype = C.c_int
     lib.sfi_set_tuning.argtypes = [vp, i32, i32]
     lib.sfi_query_splits.restype = C.c_int
@@ -147,14 +147,16 @@ def sfi_advance(ctx, ctx_len, recent_start, stream=None) -> None:
     _check(load_library().sfi_advance(ctx, _ptr(ctx_len), _ptr(recent_start), _stream(stream)), "sfi_advance")
 
 
-def sfi_set_profiling(ctx, on: bool) -> None:
-    _check(load_library().sfi_set_profiling(ctx, 1 if on else 0), "sfi_set_profiling")
+def sfi_set_profiling(ctx, max_calls: int) -> None:
+    _check(load_library().sfi_set_profiling(ctx, int(max_calls)), "sfi_set_profiling")
 
 
 def sfi_stage_times(ctx):
-    arr = (C.c_float * SFI_N_STAGES)()
-    _check(load_library().sfi_stage_times(ctx, arr), "sfi_stage_times")
-    return [float(x) for x in arr]
+    """(sum of elapsed ms per stage, launches per stage) over the calls recorded since profiling was switched on."""
+    ms = (C.c_float * SFI_N_STAGES)()
+    cnt = (C.c_int32 * SFI_N_STAGES)()
+    _check(load_library().sfi_stage_times(ctx, ms, cnt), "sfi_stage_times")
+    return [float(x) for x in ms], [int(x) for x in cnt]
 
 
 def sfi_set_tuning(ctx, dense_target_wgs: int = 0, fast_tiles_per_wave: int = 0) -> None:

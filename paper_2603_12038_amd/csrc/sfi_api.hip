@@ -16,10 +16,13 @@ struct sfi_ctx {
   int dense_target_wgs;     // workgroups the dense launch aims for
   int fast_tiles_per_wave;  // 32-row tiles each wave of the gather launch should get
   int last_dense_splits, last_fast_splits;
+  // profiling: a ring of event pairs, one set of stages per hot call, read back in one go so that
+  // no host synchronisation sits between the profiled calls
   int profiling;
-  bool events_ready;
-  bool stage_used[SFI_N_STAGES];
-  hipEvent_t ev[SFI_N_STAGES][2];
+  int prof_calls;                     // hot calls recorded since profiling was switched on
+  int prof_cap;                       // calls the ring holds
+  hipEvent_t* ev;                     // [prof_cap][SFI_N_STAGES][2]
+  unsigned char* ev_used;             // [prof_cap][SFI_N_STAGES]
 };
 
 namespace {
@@ -112,13 +115,15 @@ struct StageTimer {
   int stage;
   bool ok;
   StageTimer(sfi_ctx* ctx, hipStream_t st, int stg) : x(ctx), s(st), stage(stg), ok(true) {
-    if (x->profiling) {
-      ok = hipEventRecord(x->ev[stage][0], s) == hipSuccess;
-      x->stage_used[stage] = true;
+    if (recording()) {
+      ok = hipEventRecord(slot()[0], s) == hipSuccess;
+      x->ev_used[(size_t)x->prof_calls * SFI_N_STAGES + stage] = 1;
     }
   }
+  bool recording() const { return x->profiling && x->prof_calls < x->prof_cap; }
+  hipEvent_t* slot() const { return x->ev + ((size_t)x->prof_calls * SFI_N_STAGES + stage) * 2; }
   bool stop() {
-    if (x->profiling) ok = ok && hipEventRecord(x->ev[stage][1], s) == hipSuccess;
+    if (recording()) ok = ok && hipEventRecord(slot()[1], s) == hipSuccess;
     return ok;
   }
 };
@@ -185,9 +190,14 @@ int resolve_max_len(const sfi_ctx* x, int32_t max_len, int* out) {
   return SFI_OK;
 }
 
-void clear_stage_flags(sfi_ctx* x) {
-  for (int i = 0; i < SFI_N_STAGES; ++i) x->stage_used[i] = false;
-}
+// Closes the profiling record of one hot call (its stages were bracketed by StageTimer).
+struct CallRecord {
+  sfi_ctx* x;
+  explicit CallRecord(sfi_ctx* ctx) : x(ctx) {}
+  ~CallRecord() {
+    if (x->profiling && x->prof_calls < x->prof_cap) ++x->prof_calls;
+  }
+};
 
 }  // namespace
 
@@ -232,11 +242,11 @@ int sfi_create(const sfi_config* cfg, void* workspace, size_t workspace_bytes, s
 
 int sfi_destroy(sfi_ctx* x) {
   if (x == nullptr) return SFI_EINVAL;
-  if (x->events_ready)
-    for (int i = 0; i < SFI_N_STAGES; ++i) {
-      (void)hipEventDestroy(x->ev[i][0]);
-      (void)hipEventDestroy(x->ev[i][1]);
-    }
+  if (x->ev != nullptr) {
+    for (size_t i = 0; i < (size_t)x->prof_cap * SFI_N_STAGES * 2; ++i) (void)hipEventDestroy(x->ev[i]);
+    delete[] x->ev;
+    delete[] x->ev_used;
+  }
   delete x;
   return SFI_OK;
 }
@@ -261,7 +271,7 @@ int sfi_dense_attn(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   int ml;
   if ((rc = resolve_max_len(x, max_len, &ml)) != SFI_OK) return rc;
   hipStream_t st = (hipStream_t)stream;
-  clear_stage_flags(x);
+  CallRecord call_record(x);
   AttnArgs a;
   fill_attn(x, &a, q, K, V, ctx_len);
   a.n_split = dense_splits_for(x, ml, false);
@@ -284,7 +294,7 @@ int sfi_slow_step(sfi_ctx* x, const void* q, const void* K, const void* V, const
   int ml;
   if ((rc = resolve_max_len(x, max_len, &ml)) != SFI_OK) return rc;
   hipStream_t st = (hipStream_t)stream;
-  clear_stage_flags(x);
+  CallRecord call_record(x);
   AttnArgs a;
   fill_attn(x, &a, q, K, V, ctx_len);
   a.n_split = dense_splits_for(x, ml, false);
@@ -310,7 +320,7 @@ int sfi_fast_step(sfi_ctx* x, const void* q, const void* K, const void* V, const
   if (sel_stride < 0 || sel_stride > x->cfg.max_budget) return SFI_EINVAL;
   if (misaligned(sel_idx, 4) || misaligned(n_sel, 4) || misaligned(recent_start, 4)) return SFI_EALIGN;
   hipStream_t st = (hipStream_t)stream;
-  clear_stage_flags(x);
+  CallRecord call_record(x);
   AttnArgs a;
   fill_attn(x, &a, q, K, V, ctx_len);
   a.recent_start = recent_start;
@@ -336,7 +346,7 @@ int sfi_mixed_step(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   int ml;
   if ((rc = resolve_max_len(x, max_len, &ml)) != SFI_OK) return rc;
   hipStream_t st = (hipStream_t)stream;
-  clear_stage_flags(x);
+  CallRecord call_record(x);
 
   AttnArgs d;
   fill_attn(x, &d, q, K, V, ctx_len);
@@ -373,28 +383,47 @@ int sfi_advance(sfi_ctx* x, int32_t* ctx_len, int32_t* recent_start, void* strea
   return SFI_OK;
 }
 
-int sfi_set_profiling(sfi_ctx* x, int on) {
-  if (x == nullptr) return SFI_EINVAL;
-  if (on && !x->events_ready) {
-    for (int i = 0; i < SFI_N_STAGES; ++i)
-      for (int j = 0; j < 2; ++j)
-        if (hipEventCreate(&x->ev[i][j]) != hipSuccess) return SFI_ELAUNCH;
-    x->events_ready = true;
+int sfi_set_profiling(sfi_ctx* x, int max_calls) {
+  if (x == nullptr || max_calls < 0 || max_calls > (1 << 16)) return SFI_EINVAL;
+  if (max_calls > x->prof_cap) {  // (re)build the ring
+    if (x->ev != nullptr) {
+      for (size_t i = 0; i < (size_t)x->prof_cap * SFI_N_STAGES * 2; ++i) (void)hipEventDestroy(x->ev[i]);
+      delete[] x->ev;
+      delete[] x->ev_used;
+      x->ev = nullptr;
+      x->ev_used = nullptr;
+      x->prof_cap = 0;
+    }
+    const size_t n = (size_t)max_calls * SFI_N_STAGES * 2;
+    x->ev = new (std::nothrow) hipEvent_t[n];
+    x->ev_used = new (std::nothrow) unsigned char[(size_t)max_calls * SFI_N_STAGES];
+    if (x->ev == nullptr || x->ev_used == nullptr) return SFI_ENOMEM;
+    for (size_t i = 0; i < n; ++i)
+      if (hipEventCreate(&x->ev[i]) != hipSuccess) return SFI_ELAUNCH;
+    x->prof_cap = max_calls;
   }
-  x->profiling = on ? 1 : 0;
-  clear_stage_flags(x);
+  x->profiling = max_calls > 0 ? 1 : 0;
+  x->prof_calls = 0;
+  if (x->ev_used != nullptr) memset(x->ev_used, 0, (size_t)x->prof_cap * SFI_N_STAGES);
   return SFI_OK;
 }
 
-int sfi_stage_times(sfi_ctx* x, float* ms) {
-  if (x == nullptr || ms == nullptr) return SFI_EINVAL;
+int sfi_stage_times(sfi_ctx* x, float* ms_sum, int32_t* count) {
+  if (x == nullptr || ms_sum == nullptr || count == nullptr) return SFI_EINVAL;
   for (int i = 0; i < SFI_N_STAGES; ++i) {
-    ms[i] = 0.f;
-    if (x->profiling && x->stage_used[i]) {
-      if (hipEventSynchronize(x->ev[i][1]) != hipSuccess) return SFI_ELAUNCH;
-      if (hipEventElapsedTime(&ms[i], x->ev[i][0], x->ev[i][1]) != hipSuccess) return SFI_ELAUNCH;
-    }
+    ms_sum[i] = 0.f;
+    count[i] = 0;
   }
+  for (int c = 0; c < x->prof_calls; ++c)
+    for (int i = 0; i < SFI_N_STAGES; ++i) {
+      if (!x->ev_used[(size_t)c * SFI_N_STAGES + i]) continue;
+      hipEvent_t* e = x->ev + ((size_t)c * SFI_N_STAGES + i) * 2;
+      float ms = 0.f;
+      if (hipEventSynchronize(e[1]) != hipSuccess) return SFI_ELAUNCH;
+      if (hipEventElapsedTime(&ms, e[0], e[1]) != hipSuccess) return SFI_ELAUNCH;
+      ms_sum[i] += ms;
+      ++count[i];
+    }
   return SFI_OK;
 }
 

@@ -102,7 +102,8 @@ def test_hot_calls_reject_bad_arguments_before_any_launch():
         assert lib.sfi_fast_step(h, p, p, p, p, p, 64, p + 1, p, p, None) == EALIGN
         assert lib.sfi_mixed_step(h, p, p, p, None, p, p, 0, 64, p, p, p, None) == EINVAL
         assert lib.sfi_advance(h, None, p, None) == EINVAL
-        assert lib.sfi_stage_times(h, None) == EINVAL
+        assert lib.sfi_stage_times(h, None, None) == EINVAL
+        assert lib.sfi_set_profiling(h, -1) == EINVAL
         assert lib.sfi_set_tuning(None, 1, 1) == EINVAL
         d, f = C.c_int32(-1), C.c_int32(-1)
         assert lib.sfi_query_splits(h, C.byref(d), C.byref(f)) == OK and d.value == 0 and f.value == 0
