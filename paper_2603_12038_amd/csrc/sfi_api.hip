@@ -70,6 +70,7 @@ size_t carve(const sfi_config* c, char* base, Workspace* ws) {
   ws->hist1 = (uint32_t*)take((size_t)(B * Hkv) * kHist1Bins * sizeof(uint32_t));
   ws->state = (uint32_t*)take((size_t)(B * Hkv) * kStateWords * sizeof(uint32_t));
   ws->segcnt = (uint32_t*)take((size_t)(B * Hkv) * n_seg * 2 * sizeof(uint32_t));
+  ws->jstat = (float2*)take((size_t)(B * Hq) * sizeof(float2));
   ws->ld_pos = ld;
   ws->n_seg_cap = n_seg;
   return off;
@@ -149,7 +150,7 @@ void fill_sel(const sfi_ctx* x, SelArgs* s, const int32_t* ctx_len, const uint8_
               int n_split, int32_t* sel_idx, int32_t* n_sel) {
   memset(s, 0, sizeof(*s));
   const sfi_config& c = x->cfg;
-  s->part = x->ws.part; s->logits = x->ws.logits; s->keys = x->ws.keys; s->cand = x->ws.cand;
+  s->jstat = x->ws.jstat; s->logits = x->ws.logits; s->keys = x->ws.keys; s->cand = x->ws.cand;
   s->hist1 = x->ws.hist1; s->state = x->ws.state; s->segcnt = x->ws.segcnt;
   s->ctx_len = ctx_len; s->is_slow = is_slow; s->sel_idx = sel_idx; s->n_sel = n_sel;
   s->ld_pos = x->ws.ld_pos; s->n_seg_cap = x->ws.n_seg_cap;
@@ -278,7 +279,7 @@ int sfi_dense_attn(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   set_dense_bounds(x, &a, ml);
   x->last_dense_splits = a.n_split;
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(a, x->cfg.batch, a.n_split + 1, st)); if (!t.stop()) return SFI_ELAUNCH; }
-  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, (a.n_split + 1) * kWaves, 0, 0};
+  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, (a.n_split + 1) * kWaves, 0, 0, nullptr, 0, x->G};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
 }
@@ -306,7 +307,7 @@ int sfi_slow_step(sfi_ctx* x, const void* q, const void* K, const void* V, const
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(a, x->cfg.batch, a.n_split + 1, st)); if (!t.stop()) return SFI_ELAUNCH; }
   SelArgs sa;
   fill_sel(x, &sa, ctx_len, nullptr, budget, a.n_split, sel_idx, n_sel);
-  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, (a.n_split + 1) * kWaves, 0, 0};
+  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, (a.n_split + 1) * kWaves, 0, 0, x->ws.jstat, a.n_split * kWaves, x->G};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return run_selector(x, sa, ml, st);
 }
@@ -330,7 +331,7 @@ int sfi_fast_step(sfi_ctx* x, const void* q, const void* K, const void* V, const
   a.n_split = fast_splits_for(x, sel_stride);
   x->last_fast_splits = a.n_split;
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_gather(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
-  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1};
+  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1, nullptr, 0, x->G};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
 }
@@ -370,7 +371,7 @@ int sfi_mixed_step(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   // rewrites rows of slow sequences, so the order of the two attention launches is free.
   { StageTimer t(x, st, SFI_STAGE_ATTN2); SFI_TRY(launch_attn_gather(f, x->cfg.batch, f.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(d, x->cfg.batch, d.n_split + 1, st)); if (!t.stop()) return SFI_ELAUNCH; }
-  MergeArgs m{x->ws.part, out, is_slow, x->cfg.n_q_heads, (d.n_split + 1) * kWaves, f.n_split, 2};
+  MergeArgs m{x->ws.part, out, is_slow, x->cfg.n_q_heads, (d.n_split + 1) * kWaves, f.n_split, 2, x->ws.jstat, d.n_split * kWaves, x->G};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   SelArgs sa;
   fill_sel(x, &sa, ctx_len, is_slow, budget, d.n_split, sel_idx, n_sel);

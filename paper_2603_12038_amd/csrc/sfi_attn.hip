@@ -489,7 +489,8 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(const MergeArgs a)
   if (a.mode == 0) n_slots = a.slots_slow;
   else if (a.mode == 1) n_slots = a.slots_fast;
   else n_slots = a.is_slow[b] ? a.slots_slow : a.slots_fast;
-  merge_records(a.part, a.out, bg, n_slots);
+  const bool dense = a.mode == 0 || (a.mode == 2 && a.is_slow[b]);
+  merge_records(a.part, a.out, bg, n_slots, dense ? a.jstat : nullptr, a.n_j, a.G);
 }
 
 __global__ void advance_kernel(int32_t* ctx_len, int32_t* recent_start, int B, int n_sink, int recent) {

@@ -37,6 +37,7 @@ struct Workspace {
   uint32_t* hist1;    // [B*Hkv][kHist1Bins]
   uint32_t* state;    // [B*Hkv][kStateWords]
   uint32_t* segcnt;   // [B*Hkv][n_seg_cap][2]
+  float2* jstat;      // [B*Hq]  J-only softmax statistics of each query head (slow step)
   int64_t ld_pos;     // multiple of kSelSeg
   int32_t n_seg_cap;
 };
@@ -69,10 +70,12 @@ struct MergeArgs {
   const uint8_t* is_slow;
   int32_t Hq, slots_slow, slots_fast;  // slot counts for slow / fast sequences
   int32_t mode;                        // 0: all sequences use slots_slow, 1: all use slots_fast, 2: per is_slow
+  float2* jstat;                       // dense records: also leave the J-only softmax statistics here (may be null)
+  int32_t n_j, G;                      // records that cover J; query heads per KV head
 };
 
 struct SelArgs {
-  const float* part;
+  const float2* jstat;
   const float* logits;
   uint32_t* keys;
   uint32_t* cand;

@@ -12,7 +12,11 @@ static_assert(kSlotCap <= kMergeThreads, "one record header per thread");
 // (sequence, query head) bg.  One workgroup of 256 threads = 8 record lanes x 32 dim quads: every
 // thread owns four output dims of every eighth record, so all of a thread's loads are independent
 // and in flight together.
-__device__ __forceinline__ void merge_records(const float* part, float* out, int bg, int n_slots) {
+// If jstat != nullptr the first n_j records are the ones that cover the allowed set J (dense kernel):
+// their merge gives the J-only softmax statistics of this head for the Selector (Eq. selector_pt),
+// stored as jstat[bg] = { M = max of y over J, 1 / (G * sum over J of 2^(y - M)) }.
+__device__ __forceinline__ void merge_records(const float* part, float* out, int bg, int n_slots, float2* jstat,
+                                              int n_j, int G) {
   const float* P = part + (int64_t)bg * kSlotCap * kPartStride;
   const int tid = threadIdx.x;
   const int sl = tid >> 5, c = tid & 31;
@@ -40,6 +44,21 @@ __device__ __forceinline__ void merge_records(const float* part, float* out, int
   for (int i = 0; i < kPer; ++i) {
     const int s = sl + i * kMergeLanes;
     r[i] = s < n_slots ? *reinterpret_cast<const float4*>(P + s * kPartStride + 4 + 4 * c) : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  if (jstat != nullptr) {  // block-uniform
+    __shared__ float s_jm[kMergeThreads / 64], s_jz[kMergeThreads / 64];
+    float mj = tid < n_j ? m : kNeg;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) mj = fmaxf(mj, __shfl_xor(mj, d));
+    if ((tid & 63) == 0) s_jm[tid >> 6] = mj;
+    __syncthreads();
+    const float MJ = fmaxf(fmaxf(s_jm[0], s_jm[1]), fmaxf(s_jm[2], s_jm[3]));
+    float zj = tid < n_j ? l * __builtin_amdgcn_exp2f(m - MJ) : 0.f;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) zj += __shfl_xor(zj, d);
+    if ((tid & 63) == 0) s_jz[tid >> 6] = zj;
+    __syncthreads();
+    if (tid == 0) jstat[bg] = make_float2(MJ, 1.0f / ((float)G * (s_jz[0] + s_jz[1] + s_jz[2] + s_jz[3])));
   }
   __syncthreads();
   M = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));

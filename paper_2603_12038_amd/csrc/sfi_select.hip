@@ -92,69 +92,61 @@ __global__ __launch_bounds__(kSelThreads) void sel_score_kernel(const SelArgs a)
   const int G = a.G;
 
   __shared__ uint32_t s_hist[kHist1Bins];
-  __shared__ float s_M[16], s_c[16];
   for (int i = tid; i < kHist1Bins; i += kSelThreads) s_hist[i] = 0u;
 
-  // J-only softmax statistics of each head of the group, from the split records of J (the first
-  // n_split records of the dense kernel, one per wave that covered J, hold the maximum and the sum
-  // of 2^(y - max) over their share of J).  Thread s reads record s of every head at once.
-  __shared__ float s_wm[kSelThreads / 64][16], s_wz[kSelThreads / 64][16];
-  static_assert(kSlotCap <= kSelThreads, "one record per thread");
-  {
-    float rm[16], rl[16];
-#pragma unroll
-    for (int g = 0; g < 16; ++g) {
-      rm[g] = kNeg;
-      rl[g] = 0.f;
-      if (g < G && tid < a.n_split) {
-        const float2 ml = *reinterpret_cast<const float2*>(
-            a.part + ((int64_t)(b * a.Hq + h * G + g) * kSlotCap + tid) * kPartStride);
-        rm[g] = ml.x;
-        rl[g] = ml.y;
-      }
-    }
-    const int wv = tid >> 6;
-#pragma unroll
-    for (int g = 0; g < 16; ++g) {
-      if (g < G) {
-        float m = rm[g];
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) m = fmaxf(m, __shfl_xor(m, d));
-        if ((tid & 63) == 0) s_wm[wv][g] = m;
-      }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int g = 0; g < 16; ++g) {
-      if (g < G) {
-        const float M = fmaxf(fmaxf(s_wm[0][g], s_wm[1][g]), fmaxf(s_wm[2][g], s_wm[3][g]));
-        float z = rl[g] * fast_exp2s(rm[g] - M);
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) z += __shfl_xor(z, d);
-        if ((tid & 63) == 0) s_wz[wv][g] = z;
-      }
-    }
-    __syncthreads();
-    if (tid < G) {
-      s_M[tid] = fmaxf(fmaxf(s_wm[0][tid], s_wm[1][tid]), fmaxf(s_wm[2][tid], s_wm[3][tid]));
-      s_c[tid] = 1.0f / ((float)G * (s_wz[0][tid] + s_wz[1][tid] + s_wz[2][tid] + s_wz[3][tid]));
-    }
-  }
-  __syncthreads();
-
-  // logits of (b, h): tile-major, [tile of 32 positions][G heads][32]
+  // logits of (b, h): tile-major, [tile of 32 positions][G heads][32].  A thread owns two quads of
+  // positions, half a segment apart; for G <= 8 all its loads are issued before any is used.
   const float* lg = a.logits + ((int64_t)(b * a.Hq + h * G)) * a.ld_pos;
   uint32_t* keys = a.keys + (int64_t)bh * a.ld_pos;
-  for (int p = p_lo + tid * 4; p < min(p_lo + kSelSeg, pb.nJ); p += kSelThreads * 4) {
+  constexpr int kHalf = kSelSeg / 2;
+  const int pq[2] = {p_lo + tid * 4, p_lo + kHalf + tid * 4};
+  float4 lq[2][8];
+  if (G <= 8) {
+#pragma unroll
+    for (int r = 0; r < 2; ++r)
+#pragma unroll
+      for (int g = 0; g < 8; ++g)
+        lq[r][g] = (pq[r] < pb.nJ && g < G)
+                       ? *reinterpret_cast<const float4*>(lg + (int64_t)(pq[r] >> 5) * G * kTile + g * kTile + (pq[r] & 31))
+                       : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  // J-only softmax statistics of the heads of this group, left by the merge kernel:
+  // f(j) = sum_g c_g 2^(y_g(j) - M_g) with (M_g, c_g) = jstat[head g]
+  float sM[16], sc[16];
+#pragma unroll
+  for (int g = 0; g < 16; ++g) {
+    const float2 t = g < G ? a.jstat[b * a.Hq + h * G + g] : make_float2(0.f, 0.f);
+    sM[g] = t.x;
+    sc[g] = t.y;
+  }
+  __syncthreads();  // histogram cleared
+#pragma unroll
+  for (int r = 0; r < 2; ++r) {
+    const int p = pq[r];
+    if (p >= pb.nJ) continue;
     float f0 = 0.f, f1 = 0.f, f2 = 0.f, f3 = 0.f;
-    const float* lt = lg + (int64_t)(p >> 5) * G * kTile + (p & 31);
-    for (int g = 0; g < G; ++g) {
-      const float4 l4 = *reinterpret_cast<const float4*>(lt + g * kTile);
-      const float M = s_M[g], c = s_c[g];
-      f0 += c * fast_exp2s(l4.x - M);
-      f1 += c * fast_exp2s(l4.y - M);
-      f2 += c * fast_exp2s(l4.z - M);
-      f3 += c * fast_exp2s(l4.w - M);
+    if (G <= 8) {
+#pragma unroll
+      for (int g = 0; g < 8; ++g) {
+        if (g < G) {
+          f0 += sc[g] * fast_exp2s(lq[r][g].x - sM[g]);
+          f1 += sc[g] * fast_exp2s(lq[r][g].y - sM[g]);
+          f2 += sc[g] * fast_exp2s(lq[r][g].z - sM[g]);
+          f3 += sc[g] * fast_exp2s(lq[r][g].w - sM[g]);
+        }
+      }
+    } else {
+      const float* lt = lg + (int64_t)(p >> 5) * G * kTile + (p & 31);
+#pragma unroll
+      for (int g = 0; g < 16; ++g) {
+        if (g < G) {
+          const float4 l4 = *reinterpret_cast<const float4*>(lt + g * kTile);
+          f0 += sc[g] * fast_exp2s(l4.x - sM[g]);
+          f1 += sc[g] * fast_exp2s(l4.y - sM[g]);
+          f2 += sc[g] * fast_exp2s(l4.z - sM[g]);
+          f3 += sc[g] * fast_exp2s(l4.w - sM[g]);
+        }
+      }
     }
     const uint4 k4 = make_uint4(__float_as_uint(f0), __float_as_uint(f1), __float_as_uint(f2), __float_as_uint(f3));
     *reinterpret_cast<uint4*>(keys + p) = k4;
