@@ -270,8 +270,8 @@ struct ListWalk {
 // dense kernel
 // ------------------------------------------------------------------------------------------------
 template <bool EXPOSE>  // EXPOSE: also write y over J for the Selector
-__global__ __launch_bounds__(kAttnThreads, 3) void attn_dense_kernel(const AttnArgs a) {
-  __shared__ float s_patch[kWaves][16 * kTile];  // per-wave transpose patch for the logits of one tile
+__global__ __launch_bounds__(kAttnThreads, EXPOSE ? 2 : 3) void attn_dense_kernel(const AttnArgs a) {
+  __shared__ float s_stash[EXPOSE ? kWaves : 1][EXPOSE ? kStashFloats : 1];  // per-wave logits stash
   const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
   const int tid = threadIdx.x;
@@ -334,23 +334,27 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_dense_kernel(const AttnA
     const int r_max = a.n_sink + N - 1;
     const int K = first < nT ? (nT - first + step - 1) / step : 0;  // tiles of this wave, ragged one included
     // Exposing y.  The logits of (b, h) are stored tile-major, [tile][G heads][32 positions], so a
-    // tile's G x 128 bytes are one contiguous run.  The tile's values are transposed through this
-    // wave's LDS patch so that 8 lanes write each 128-byte line whole.  Every lane stores (lanes
-    // beyond the G heads repeat a line already written by another lane): the number of memory
-    // instructions per tile is then fixed, which the load waits below rely on.
-    float* patch = &s_patch[w][0];
+    // tile's G x 128 bytes are one contiguous run.  A wave does not store a tile's logits when it
+    // has them: a store acknowledged late would sit in front of the next rows in the in-order
+    // memory counter.  It parks them in its LDS stash, laid out as they go to memory, and writes the
+    // stash out in one burst when it is full and once more after its last tile, when nothing is
+    // left to wait for.
+    float* stash = EXPOSE ? &s_stash[w][0] : nullptr;
     float* lg_base = EXPOSE ? a.logits + head0 * a.ld_pos : nullptr;
-    auto write_logits = [&](const float (&y)[8], int t) {
-      stage_logits(patch, y, jg, n, G);
+    const int tile_f4 = G * (kTile / 4);        // float4 per tile
+    const int stash_cap = kStashFloats / (G * kTile);  // tiles the stash holds
+    int n_stashed = 0, k_flushed = 0;
+    auto flush_stash = [&]() {
       __builtin_amdgcn_wave_barrier();
-      float* dst = lg_base + (int64_t)t * G * kTile;
-      const int hd = (lane >> 3) % G, qd = lane & 7;
-      *reinterpret_cast<float4*>(dst + hd * kTile + 4 * qd) = *reinterpret_cast<const float4*>(patch + hd * kTile + 4 * qd);
-      if (G > 8) {
-        const int hd2 = 8 + (lane >> 3) % (G - 8);
-        *reinterpret_cast<float4*>(dst + hd2 * kTile + 4 * qd) = *reinterpret_cast<const float4*>(patch + hd2 * kTile + 4 * qd);
+      const int n_f4 = n_stashed * tile_f4;
+      for (int f = lane; f < n_f4; f += 64) {
+        const int i = f / tile_f4, rem = f - i * tile_f4;
+        const int t = first + (k_flushed + i) * step;
+        *reinterpret_cast<float4*>(lg_base + ((int64_t)t * tile_f4 + rem) * 4) = *reinterpret_cast<const float4*>(stash + f * 4);
       }
       __builtin_amdgcn_wave_barrier();
+      k_flushed += n_stashed;
+      n_stashed = 0;
     };
 
     // One loop for all of the wave's tiles, one tile buffer: the K half is refilled with the next
@@ -365,13 +369,17 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_dense_kernel(const AttnA
       float y[8];
       qk_phase(T, qreg, a.scale_log2, y);
       issue_k_affine(T, R, r_next, r_max);
-      if (EXPOSE) write_logits(y, t);  // positions past N land in the padding of the last tile, never used
+      if (EXPOSE) {  // positions past N land in the padding of the last tile, never used
+        stage_logits(stash + n_stashed * (G * kTile), y, jg, n, G);
+        if (++n_stashed == stash_cap) flush_stash();
+      }
       if (t >= nFull) mask_tail(T, y, jg, t * kTile, N);
       bf16x8 a_hi, a_lo;
       softmax_phase(y, acc, m_run, l_run, jg, a_hi, a_lo);
       pv_phase(T, a_hi, a_lo, acc);
       issue_v_affine(T, R, r_next, r_max);
     }
+    if (EXPOSE) flush_stash();
   }
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);

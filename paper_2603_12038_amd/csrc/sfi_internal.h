@@ -11,6 +11,7 @@ constexpr int kHeadDim = 128;
 constexpr int kTile = 32;          // KV positions per wave iteration (two 16-row MFMA blocks)
 constexpr int kWaves = 4;          // waves per attention workgroup
 constexpr int kAttnThreads = 64 * kWaves;
+constexpr int kStashFloats = 4096;  // per-wave LDS stash for exposed logits (16 KB): 128 / G tiles
 constexpr int kPartStride = 132;   // floats per split record: m, l, pad, pad, acc[128]
 constexpr int kMaxSplits = 63;     // split workgroups per (sequence, KV head)
 // records per (sequence, query head): the dense kernel writes one per wave, (splits + 1 sink/recent

@@ -300,3 +300,22 @@ def test_strided_kv_layout(oracle):
         check_out(out.cpu().numpy(), oracle.dense(q, w.K, w.V, w.ctx_len(0)))
     finally:
         ctx.close()
+
+
+@pytest.mark.parametrize("Hq,Hkv,L0", [(16, 2, 5000), (16, 1, 3000), (8, 2, 9000)])
+def test_slow_step_with_few_splits(oracle, Hq, Hkv, L0):
+    """One split per (sequence, KV head): a wave owns far more tiles than its logits stash holds
+    (G = 8: 16 tiles, G = 16: 8, G = 4: 32), so the stash is written out several times on the way."""
+    w = syn.make_tiny(L0=L0, steps=1, budget=96, recent=40, n_support=8, B=1, Hq=Hq, Hkv=Hkv)
+    r = Runner(w)
+    try:
+        _step(f"few splits G={Hq // Hkv} L={L0}")
+        r.sfi.sfi_set_tuning(r.ctx.handle, 1, 1)
+        q, ctx = w.q(0), w.ctx_len(0)
+        out, sel, nsel = r.slow(q, ctx, w.budget)
+        assert r.sfi.sfi_query_splits(r.ctx.handle)[0] == 1
+        check_out(out, oracle.dense(q, w.K, w.V, ctx))
+        sel_ref, nsel_ref, z = oracle.selector(q, w.K, ctx, w.budget, w.n_sink, w.recent)
+        check_selection(sel, nsel, sel_ref, nsel_ref, z, ctx, w.n_sink, w.recent, w.budget)
+    finally:
+        r.close()
