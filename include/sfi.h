@@ -128,6 +128,35 @@ int sfi_fast_step(sfi_ctx* ctx, const void* q, const void* K, const void* V, con
                   const int32_t* ctx_len, float* out, void* stream);
 
 /*
+ * Reorg (paper Sec. "Hiding Slow-step Overhead via Layer-wise Asynchronous Execution", Reorg_i, and
+ * Sec. "Memory-coalesced Kernel Design and Selector Maintenance", two-segment KV layout): after a
+ * slow step, copy the sink rows and the selected rows of every (b, h) into caller-owned compact
+ * buffers, rows of 128 bf16 back to back:
+ *   Kc[b, h, i, :]          = K[b, h, i, :]              i <  min(n_sink, ctx_len[b])
+ *   Kc[b, h, n_sink + i, :] = K[b, h, sel_idx[b,h,i], :] i <  n_sel[b,h]
+ * and the same for Vc from V.  Other rows of the buffers are left as they are.
+ * Kc / Vc: device, bf16, addressed as base + b * c_stride_b + h * c_stride_h + i * 128 (strides in
+ * elements, multiples of 8); every (b, h) slice holds c_rows >= n_sink + sel_stride rows, all of them
+ * readable memory.  is_slow: nullptr, or device uint8 [B]: only sequences with is_slow[b] != 0 are
+ * reorganised (the companion of sfi_mixed_step).  Other arguments as in sfi_fast_step.
+ */
+int sfi_reorg(sfi_ctx* ctx, const void* K, const void* V, const int32_t* sel_idx, const int32_t* n_sel,
+              int32_t sel_stride, const int32_t* ctx_len, const uint8_t* is_slow, void* Kc, void* Vc,
+              int64_t c_stride_b, int64_t c_stride_h, int32_t c_rows, void* stream);
+
+/*
+ * Fast step over the two-segment layout (same sections): the sink and selected rows are read as one
+ * run of consecutive rows from the compact buffers sfi_reorg filled, the recent window
+ * [recent_start[b], ctx_len[b]) in place from K / V.  Same result as sfi_fast_step on the sel_idx
+ * the buffers were built from.  Preconditions as for sfi_fast_step; n_sel[b,h] <= sel_stride and
+ * c_rows >= n_sink + sel_stride; n_sel[b,h] > 0 only where ctx_len[b] > n_sink.
+ */
+int sfi_fast_step_compact(sfi_ctx* ctx, const void* q, const void* Kc, const void* Vc, int64_t c_stride_b,
+                          int64_t c_stride_h, int32_t c_rows, const int32_t* n_sel, int32_t sel_stride,
+                          const void* K, const void* V, const int32_t* recent_start, const int32_t* ctx_len,
+                          float* out, void* stream);
+
+/*
  * Ragged mix: sequence b takes a slow step if is_slow[b] != 0 (uint8, device) and a fast step
  * otherwise; slow sequences refresh their rows of sel_idx / n_sel in place (row stride `budget`),
  * fast sequences read theirs.  No host synchronisation decides the mode.
@@ -149,13 +178,14 @@ int sfi_advance(sfi_ctx* ctx, int32_t* ctx_len, int32_t* recent_start, void* str
  * Not for production loops: event records add a gap of a few microseconds around every kernel.
  */
 enum {
-  SFI_STAGE_ATTN = 0,     /* split attention kernel (dense; or gather in a fast step) */
+  SFI_STAGE_ATTN = 0,     /* split attention kernel (dense; gather or compact in a fast step) */
   SFI_STAGE_MERGE = 1,    /* split merge */
   SFI_STAGE_SCORE = 2,    /* evidence + first radix histogram */
   SFI_STAGE_CAND = 3,     /* threshold-bin candidates */
   SFI_STAGE_COUNT = 4,    /* exact threshold + per-segment counts */
   SFI_STAGE_WRITE = 5,    /* ordered index write */
   SFI_STAGE_ATTN2 = 6,    /* the gather attention kernel of a mixed step */
+  SFI_STAGE_REORG = 7,    /* compact-buffer gather */
   SFI_N_STAGES = 8
 };
 int sfi_set_profiling(sfi_ctx* ctx, int max_calls);

@@ -17,6 +17,9 @@
  *   sfio_sparse    the same attention restricted to the index set
  *                  I = I_sink U I_recent U I_sel  (Eq. index_set, Eq. index_set_head,
  *                  Sec. 3.1 "Fast step").
+ *   sfio_reorg     cache reorganisation Reorg_i: the sink rows and the selected rows
+ *                  copied into a contiguous compact buffer (Sec. 4.1 dependency
+ *                  structure and Sec. 4.2 two-segment KV layout).
  *   sfio_selector_from_logits / sfio_selector
  *                  Algorithm 2 step by step: allowed set J (Eq. allowed_set),
  *                  evidence p, mu, f (Eqs. selector_pt, selector_mu, selector_f),
@@ -380,6 +383,32 @@ int sfio_selector(const sfio_cfg* c, const uint16_t* q, const uint16_t* K, const
   free(logits);
   free(knorm);
   return rc;
+}
+
+/* Reorg: Kc[b][h][i] = K[b][h][i] for i < min(n_sink, L_b);  Kc[b][h][n_sink + i] = K[b][h][sel_idx[b][h][i]]
+ * for i < n_sel[b][h]; likewise Vc.  Kc, Vc: [B, Hkv, c_rows, d], rows not named here are left untouched.
+ * Returns -1 if a selected index lies outside [0, L_b) or the buffer is too small. */
+int sfio_reorg(const sfio_cfg* c, const uint16_t* K, const uint16_t* V, const int32_t* sel_idx, const int32_t* n_sel,
+               int64_t sel_stride, const int32_t* ctx_len, uint16_t* Kc, uint16_t* Vc, int64_t c_rows) {
+  for (int b = 0; b < c->B; ++b)
+    for (int h = 0; h < c->Hkv; ++h) {
+      const int64_t bh = (int64_t)b * c->Hkv + h;
+      const int64_t L = ctx_len[b];
+      uint16_t* kc = Kc + bh * c_rows * c->d;
+      uint16_t* vc = Vc + bh * c_rows * c->d;
+      if (c->n_sink + (int64_t)n_sel[bh] > c_rows) return -1;
+      for (int64_t i = 0; i < c->n_sink && i < L; ++i) {
+        memcpy(kc + i * c->d, k_row(c, K, b, h, i), sizeof(uint16_t) * (size_t)c->d);
+        memcpy(vc + i * c->d, v_row(c, V, b, h, i), sizeof(uint16_t) * (size_t)c->d);
+      }
+      for (int64_t i = 0; i < n_sel[bh]; ++i) {
+        const int64_t j = sel_idx[bh * sel_stride + i];
+        if (j < 0 || j >= L) return -1;
+        memcpy(kc + (c->n_sink + i) * c->d, k_row(c, K, b, h, j), sizeof(uint16_t) * (size_t)c->d);
+        memcpy(vc + (c->n_sink + i) * c->d, v_row(c, V, b, h, j), sizeof(uint16_t) * (size_t)c->d);
+      }
+    }
+  return 0;
 }
 
 int sfio_num_threads(void) {

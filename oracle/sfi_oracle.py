@@ -135,6 +135,21 @@ def sparse(q, K, V, sel_idx, n_sel, recent_start, ctx_len, n_sink: int, scale=No
     return out
 
 
+def reorg(K, V, sel_idx, n_sel, ctx_len, n_sink: int, Kc: np.ndarray, Vc: np.ndarray) -> None:
+    """Reorg: fills rows [0, min(n_sink, L)) and [n_sink, n_sink + n_sel) of the uint16 compact buffers
+    Kc, Vc [B, Hkv, c_rows, d] in place; every other row keeps its contents."""
+    B, Hkv = K.shape[0], K.shape[1]
+    d = K.shape[3]
+    sel_idx, n_sel, ctx_len = _i32(sel_idx), _i32(n_sel), _i32(ctx_len)
+    assert Kc.dtype == np.uint16 and Vc.dtype == np.uint16 and Kc.flags.c_contiguous and Vc.flags.c_contiguous
+    assert Kc.shape == Vc.shape and Kc.shape[:2] == (B, Hkv) and Kc.shape[3] == d
+    c = _cfg(B, Hkv, Hkv, d, n_sink, 0, None, K=K, V=V)
+    rc = lib().sfio_reorg(C.byref(c), _p(K), _p(V), _p(sel_idx), _p(n_sel), C.c_int64(sel_idx.shape[2]), _p(ctx_len),
+                          _p(Kc), _p(Vc), C.c_int64(Kc.shape[2]))
+    if rc != 0:
+        raise ValueError("selected index outside [0, ctx_len) or compact buffer too small")
+
+
 def selector_from_logits(lg: np.ndarray, ctx_len, Hkv: int, budget: int, n_sink: int, recent: int,
                          sp: Optional[SelectorParams] = None, knorm: Optional[np.ndarray] = None,
                          debug: bool = False):

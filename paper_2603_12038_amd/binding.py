@@ -36,7 +36,7 @@ class SfiConfig(C.Structure):
 _lib: Optional[C.CDLL] = None
 
 EXPORTS = ("sfi_workspace_bytes", "sfi_create", "sfi_destroy", "sfi_strerror", "sfi_slow_step", "sfi_dense_attn",
-           "sfi_fast_step", "sfi_mixed_step", "sfi_advance", "sfi_set_profiling", "sfi_stage_times",
+           "sfi_fast_step", "sfi_reorg", "sfi_fast_step_compact", "sfi_mixed_step", "sfi_advance", "sfi_set_profiling", "sfi_stage_times",
            "sfi_set_tuning", "sfi_query_splits")
 
 
@@ -63,6 +63,10 @@ def load_library() -> C.CDLL:
     lib.sfi_dense_attn.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp]
     lib.sfi_fast_step.restype = C.c_int
     lib.sfi_fast_step.argtypes = [vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
+    lib.sfi_reorg.restype = C.c_int
+    lib.sfi_reorg.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, i64, i64, i32, vp]
+    lib.sfi_fast_step_compact.restype = C.c_int
+    lib.sfi_fast_step_compact.argtypes = [vp, vp, vp, vp, i64, i64, i32, vp, i32, vp, vp, vp, vp, vp, vp]
     lib.sfi_mixed_step.restype = C.c_int
     lib.sfi_mixed_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
     lib.sfi_advance.restype = C.c_int
@@ -134,6 +138,22 @@ def sfi_fast_step(ctx, q, K, V, sel_idx, n_sel, sel_stride, recent_start, ctx_le
     _check(load_library().sfi_fast_step(ctx, _ptr(q), _ptr(K), _ptr(V), _ptr(sel_idx), _ptr(n_sel), sel_stride,
                                         _ptr(recent_start), _ptr(ctx_len), _ptr(out), _stream(stream)),
            "sfi_fast_step")
+
+
+def sfi_reorg(ctx, K, V, sel_idx, n_sel, sel_stride, ctx_len, is_slow, Kc, Vc, stream=None) -> None:
+    """Kc / Vc: bf16 tensors [B, Hkv, c_rows, 128] with contiguous rows; strides are taken from them."""
+    assert Kc.stride() == Vc.stride() and Kc.stride(3) == 1 and Kc.stride(2) == Kc.shape[3]
+    _check(load_library().sfi_reorg(ctx, _ptr(K), _ptr(V), _ptr(sel_idx), _ptr(n_sel), sel_stride, _ptr(ctx_len),
+                                    _ptr(is_slow), _ptr(Kc), _ptr(Vc), Kc.stride(0), Kc.stride(1), Kc.shape[2],
+                                    _stream(stream)), "sfi_reorg")
+
+
+def sfi_fast_step_compact(ctx, q, Kc, Vc, n_sel, sel_stride, K, V, recent_start, ctx_len, out, stream=None) -> None:
+    assert Kc.stride() == Vc.stride() and Kc.stride(3) == 1 and Kc.stride(2) == Kc.shape[3]
+    _check(load_library().sfi_fast_step_compact(ctx, _ptr(q), _ptr(Kc), _ptr(Vc), Kc.stride(0), Kc.stride(1),
+                                                Kc.shape[2], _ptr(n_sel), sel_stride, _ptr(K), _ptr(V),
+                                                _ptr(recent_start), _ptr(ctx_len), _ptr(out), _stream(stream)),
+           "sfi_fast_step_compact")
 
 
 def sfi_mixed_step(ctx, q, K, V, is_slow, ctx_len, recent_start, max_len, budget, out, sel_idx, n_sel,

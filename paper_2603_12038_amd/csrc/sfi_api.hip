@@ -110,6 +110,15 @@ int fast_splits_for(const sfi_ctx* x, int sel_stride) {
   return s;
 }
 
+// The compact segment and the recent window are tiled separately (no tile straddles them).
+int compact_splits_for(const sfi_ctx* x, int sel_stride) {
+  const int tiles = (x->cfg.n_sink + sel_stride + kTile - 1) / kTile + (x->cfg.recent + kTile - 1) / kTile;
+  int s = (tiles + kWaves * x->fast_tiles_per_wave - 1) / (kWaves * x->fast_tiles_per_wave);
+  if (s > kMaxSplits) s = kMaxSplits;
+  if (s < 1) s = 1;
+  return s;
+}
+
 struct StageTimer {
   sfi_ctx* x;
   hipStream_t s;
@@ -331,6 +340,71 @@ int sfi_fast_step(sfi_ctx* x, const void* q, const void* K, const void* V, const
   a.n_split = fast_splits_for(x, sel_stride);
   x->last_fast_splits = a.n_split;
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_gather(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
+  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1, nullptr, 0, x->G};
+  { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
+  return SFI_OK;
+}
+
+namespace {
+// Compact-buffer geometry shared by sfi_reorg and sfi_fast_step_compact.
+int check_compact(const sfi_ctx* x, const void* Kc, const void* Vc, int64_t c_stride_b, int64_t c_stride_h,
+                  int32_t c_rows, int32_t sel_stride) {
+  if (Kc == nullptr || Vc == nullptr) return SFI_EINVAL;
+  if (misaligned(Kc, 16) || misaligned(Vc, 16)) return SFI_EALIGN;
+  if (sel_stride < 0 || sel_stride > x->cfg.max_budget) return SFI_EINVAL;
+  if (c_rows < x->cfg.n_sink + sel_stride || c_rows < 1) return SFI_EINVAL;
+  if (c_stride_h < (int64_t)c_rows * kHeadDim || c_stride_b < c_stride_h * x->cfg.n_kv_heads) return SFI_EINVAL;
+  if (c_stride_h % 8 != 0 || c_stride_b % 8 != 0) return SFI_EALIGN;
+  if ((int64_t)c_rows * kHeadDim * 2 > 0xffffffffll) return SFI_EUNSUPPORTED;
+  return SFI_OK;
+}
+}  // namespace
+
+int sfi_reorg(sfi_ctx* x, const void* K, const void* V, const int32_t* sel_idx, const int32_t* n_sel,
+              int32_t sel_stride, const int32_t* ctx_len, const uint8_t* is_slow, void* Kc, void* Vc,
+              int64_t c_stride_b, int64_t c_stride_h, int32_t c_rows, void* stream) {
+  if (x == nullptr || K == nullptr || V == nullptr || sel_idx == nullptr || n_sel == nullptr || ctx_len == nullptr)
+    return SFI_EINVAL;
+  if (misaligned(K, 16) || misaligned(V, 16) || misaligned(sel_idx, 4) || misaligned(n_sel, 4) || misaligned(ctx_len, 4))
+    return SFI_EALIGN;
+  int rc = check_compact(x, Kc, Vc, c_stride_b, c_stride_h, c_rows, sel_stride);
+  if (rc != SFI_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  CallRecord call_record(x);
+  const sfi_config& c = x->cfg;
+  ReorgArgs r;
+  memset(&r, 0, sizeof(r));
+  r.K = (const uint16_t*)K; r.V = (const uint16_t*)V;
+  r.k_sb = c.k_stride_b; r.k_sh = c.k_stride_h; r.k_st = c.k_stride_t;
+  r.v_sb = c.v_stride_b; r.v_sh = c.v_stride_h; r.v_st = c.v_stride_t;
+  r.sel_idx = sel_idx; r.n_sel = n_sel; r.ctx_len = ctx_len; r.is_slow = is_slow; r.sel_stride = sel_stride;
+  r.Kc = (uint16_t*)Kc; r.Vc = (uint16_t*)Vc; r.c_sb = c_stride_b; r.c_sh = c_stride_h;
+  r.Hkv = c.n_kv_heads; r.n_sink = c.n_sink;
+  { StageTimer t(x, st, SFI_STAGE_REORG); SFI_TRY(launch_reorg(r, c.batch, c.n_sink + sel_stride, st)); if (!t.stop()) return SFI_ELAUNCH; }
+  return SFI_OK;
+}
+
+int sfi_fast_step_compact(sfi_ctx* x, const void* q, const void* Kc, const void* Vc, int64_t c_stride_b,
+                          int64_t c_stride_h, int32_t c_rows, const int32_t* n_sel, int32_t sel_stride,
+                          const void* K, const void* V, const int32_t* recent_start, const int32_t* ctx_len,
+                          float* out, void* stream) {
+  int rc = check_common(x, q, K, V, ctx_len, out);
+  if (rc != SFI_OK) return rc;
+  if (n_sel == nullptr || recent_start == nullptr) return SFI_EINVAL;
+  if (misaligned(n_sel, 4) || misaligned(recent_start, 4)) return SFI_EALIGN;
+  if ((rc = check_compact(x, Kc, Vc, c_stride_b, c_stride_h, c_rows, sel_stride)) != SFI_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  CallRecord call_record(x);
+  AttnArgs a;
+  fill_attn(x, &a, q, K, V, ctx_len);
+  a.recent_start = recent_start;
+  a.n_sel = n_sel;
+  a.sel_stride = sel_stride;
+  a.Kc = (const uint16_t*)Kc; a.Vc = (const uint16_t*)Vc;
+  a.c_sb = c_stride_b; a.c_sh = c_stride_h; a.c_rows = c_rows;
+  a.n_split = compact_splits_for(x, sel_stride);
+  x->last_fast_splits = a.n_split;
+  { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_compact(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
   MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1, nullptr, 0, x->G};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;

@@ -386,6 +386,55 @@ __global__ __launch_bounds__(kAttnThreads, EXPOSE ? 2 : 3) void attn_dense_kerne
   write_wave_record(a.part, head0, G, slot * kWaves + w, acc, m_run, l_run, lane);
 }
 
+// The four waves of a workgroup fold their running states into one record (b, head, slot):
+// { max of y, sum 2^(y - max), -, -, O[128] }.  l_run must already be summed over the row groups.
+__device__ __forceinline__ void write_wg_record(float* part, int64_t head0, int G, int slot, const f32x4 (&acc)[8],
+                                                float m_run, float l_run) {
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, w = tid >> 6;
+  const int jg = lane >> 4, n = lane & 15;
+  __shared__ float s_m[kWaves][16];
+  __shared__ float s_l[kWaves][16];
+  __shared__ float s_red[kWaves][16][kHeadDim];
+  if (lane < 16) {
+    s_m[w][lane] = m_run;
+    s_l[w][lane] = l_run;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int hh = 4 * jg + i;
+    if (hh < G) {
+      float M = s_m[0][hh];
+#pragma unroll
+      for (int ww = 1; ww < kWaves; ++ww) M = fmaxf(M, s_m[ww][hh]);
+      const float f = fast_exp2(s_m[w][hh] - M);
+      float* dst = &s_red[w][hh][n * 8];
+      *reinterpret_cast<float4*>(dst) = make_float4(acc[0][i] * f, acc[1][i] * f, acc[2][i] * f, acc[3][i] * f);
+      *reinterpret_cast<float4*>(dst + 4) = make_float4(acc[4][i] * f, acc[5][i] * f, acc[6][i] * f, acc[7][i] * f);
+    }
+  }
+  __syncthreads();
+  const int64_t rec0 = (head0 * kSlotCap + slot) * kPartStride;
+  for (int idx = tid; idx < G * kHeadDim; idx += kAttnThreads) {
+    const int hh = idx >> 7, dim = idx & 127;
+    float s = s_red[0][hh][dim];
+#pragma unroll
+    for (int ww = 1; ww < kWaves; ++ww) s += s_red[ww][hh][dim];
+    part[rec0 + (int64_t)hh * kSlotCap * kPartStride + 4 + dim] = s;
+  }
+  if (tid < G) {
+    float M = s_m[0][tid];
+#pragma unroll
+    for (int ww = 1; ww < kWaves; ++ww) M = fmaxf(M, s_m[ww][tid]);
+    float ls = 0.f;
+#pragma unroll
+    for (int ww = 0; ww < kWaves; ++ww) ls += s_l[ww][tid] * fast_exp2(s_m[ww][tid] - M);
+    float* r = part + rec0 + (int64_t)tid * kSlotCap * kPartStride;
+    *reinterpret_cast<float2*>(r) = make_float2(M, ls);
+  }
+}
+
 // ------------------------------------------------------------------------------------------------
 // gather kernel
 // ------------------------------------------------------------------------------------------------
@@ -445,47 +494,126 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_kernel(const Attn
   }
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
+  write_wg_record(a.part, head0, G, slot, acc, m_run, l_run);
+}
 
-  // ---- combine the four waves, one record per workgroup ------------------------------------------------
-  __shared__ float s_m[kWaves][16];
-  __shared__ float s_l[kWaves][16];
-  __shared__ float s_red[kWaves][16][kHeadDim];
-  if (lane < 16) {
-    s_m[w][lane] = m_run;
-    s_l[w][lane] = l_run;
+// ------------------------------------------------------------------------------------------------
+// compact kernel: the fast step over the two-segment layout (Sec. "Memory-coalesced Kernel Design
+// and Selector Maintenance"): sink ++ selected rows from the compact buffers the Reorg kernel filled,
+// the recent window in place from the cache.  Both segments are runs of consecutive rows, so no
+// index is read: a wave's first tile is on its way before any scalar of the step has arrived.
+// Tiles never straddle the two segments: the compact segment ends with a ragged tile of its own.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kAttnThreads, 3) void attn_compact_kernel(const AttnArgs a) {
+  const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  if (a.is_slow != nullptr && a.is_slow[b] != 0) return;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, w = tid >> 6;
+  const int jg = lane >> 4, n = lane & 15;
+  const int G = a.G;
+  const int bh = b * a.Hkv + h;
+  const int64_t head0 = (int64_t)b * a.Hq + h * G;
+  const int first = slot * kWaves + w, step = a.n_split * kWaves;
+
+  Rows Rc;  // compact segment
+  Rc.Kb = reinterpret_cast<const char*>(a.Kc + b * a.c_sb + h * a.c_sh);
+  Rc.Vb = reinterpret_cast<const char*>(a.Vc + b * a.c_sb + h * a.c_sh);
+  Rc.k_st = Rc.v_st = kHeadDim * 2u;
+  Rc.k_lane = jg * 16;
+  Rc.v_lane = n * 16;
+  Rc.jg = jg;
+  Rc.n = n;
+  Rows R = Rc;  // recent segment, in the cache
+  R.Kb = reinterpret_cast<const char*>(a.K + b * a.k_sb + h * a.k_sh);
+  R.Vb = reinterpret_cast<const char*>(a.V + b * a.v_sb + h * a.v_sh);
+  R.k_st = (uint32_t)a.k_st * 2u;
+  R.v_st = (uint32_t)a.v_st * 2u;
+
+  Tile T;
+  const bool spec = first * kTile < a.c_rows;  // almost every wave's tile lies in the compact segment
+  if (spec) issue_affine(T, Rc, first * kTile, a.c_rows - 1);
+  bf16x8 qreg[4];
+  load_q(qreg, a.q, head0, G, jg, n);
+  const int L = a.ctx_len[b];
+  const int nSel = a.n_sel[bh];
+  const int nS = min(a.n_sink, L);
+  const int rs = min(max(a.recent_start[b], nS), L);
+  const int Nc = nSel > 0 ? a.n_sink + nSel : nS;  // compact rows in use (selected rows exist only past a full sink)
+  const int Tc = (Nc + kTile - 1) / kTile;
+  const int Nr = L - rs;
+  const int nT = Tc + (Nr + kTile - 1) / kTile;
+
+  float m_run = kNeg, l_run = 0.f;
+  f32x4 acc[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  for (int t = first; t < nT; t += step) {  // normally a single trip
+    int p0, N;
+    if (t < Tc) {
+      p0 = t * kTile;
+      N = Nc;
+      if (t != first || !spec) issue_affine(T, Rc, p0, a.c_rows - 1);
+    } else {
+      p0 = (t - Tc) * kTile;
+      N = Nr;
+      issue_affine(T, R, rs + p0, L - 1);
+    }
+    if (p0 + kTile <= N) tile_math<false>(T, qreg, a.scale_log2, acc, m_run, l_run, jg, p0, N);
+    else tile_math<true>(T, qreg, a.scale_log2, acc, m_run, l_run, jg, p0, N);
   }
-  __syncthreads();
+  l_run += __shfl_xor(l_run, 16);
+  l_run += __shfl_xor(l_run, 32);
+  write_wg_record(a.part, head0, G, slot, acc, m_run, l_run);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Reorg (Sec. "Hiding Slow-step Overhead via Layer-wise Asynchronous Execution": Reorg_i): compact row
+// i < n_sink is cache row i, compact row n_sink + i is cache row sel_idx[i], i < n_sel.  A workgroup
+// moves kReorgRows compact rows of one (b, h), 16 lanes x 16 bytes per row, K and V; the indices
+// are read before the list length is known, and all of a thread's row loads precede its stores.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kAttnThreads) void reorg_kernel(const ReorgArgs a) {
+  const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
+  const int bh = b * a.Hkv + h;
+  const int tid = threadIdx.x;
+  const int sub = tid & 15, r = tid >> 4;
+  constexpr int kPass = kReorgRows / 16;
+  const int32_t* sel = a.sel_idx + (int64_t)bh * a.sel_stride;
+  const int sel_cap = (int)a.sel_stride - 1;
+  int src[kPass];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int hh = 4 * jg + i;
-    if (hh < G) {
-      float M = s_m[0][hh];
+  for (int p = 0; p < kPass; ++p) {
+    const int i = chunk * kReorgRows + p * 16 + r;
+    src[p] = sel_cap >= 0 ? sel[min(max(i - a.n_sink, 0), sel_cap)] : 0;
+  }
+  const int L = a.ctx_len[b];
+  const int nSel = min(a.n_sel[bh], (int)a.sel_stride);
+  const int nS = min(a.n_sink, L);
+  const char* Kb = reinterpret_cast<const char*>(a.K + b * a.k_sb + h * a.k_sh);
+  const char* Vb = reinterpret_cast<const char*>(a.V + b * a.v_sb + h * a.v_sh);
+  char* Kc = reinterpret_cast<char*>(a.Kc + b * a.c_sb + h * a.c_sh);
+  char* Vc = reinterpret_cast<char*>(a.Vc + b * a.c_sb + h * a.c_sh);
+  uint4 kr[kPass], vr[kPass];
+  bool ok[kPass];
 #pragma unroll
-      for (int ww = 1; ww < kWaves; ++ww) M = fmaxf(M, s_m[ww][hh]);
-      const float f = fast_exp2(s_m[w][hh] - M);
-      float* dst = &s_red[w][hh][n * 8];
-      *reinterpret_cast<float4*>(dst) = make_float4(acc[0][i] * f, acc[1][i] * f, acc[2][i] * f, acc[3][i] * f);
-      *reinterpret_cast<float4*>(dst + 4) = make_float4(acc[4][i] * f, acc[5][i] * f, acc[6][i] * f, acc[7][i] * f);
+  for (int p = 0; p < kPass; ++p) {
+    const int i = chunk * kReorgRows + p * 16 + r;
+    ok[p] = i < nS || (i >= a.n_sink && i < a.n_sink + nSel);
+    const int row = i < a.n_sink ? i : src[p];
+    if (ok[p]) {
+      kr[p] = load_row16(Kb, (uint32_t)row * ((uint32_t)a.k_st * 2u) + sub * 16);
+      vr[p] = load_row16(Vb, (uint32_t)row * ((uint32_t)a.v_st * 2u) + sub * 16);
     }
   }
-  __syncthreads();
-  const int64_t rec0 = (head0 * kSlotCap + slot) * kPartStride;
-  for (int idx = tid; idx < G * kHeadDim; idx += kAttnThreads) {
-    const int hh = idx >> 7, dim = idx & 127;
-    float s = s_red[0][hh][dim];
 #pragma unroll
-    for (int ww = 1; ww < kWaves; ++ww) s += s_red[ww][hh][dim];
-    a.part[rec0 + (int64_t)hh * kSlotCap * kPartStride + 4 + dim] = s;
-  }
-  if (tid < G) {
-    float M = s_m[0][tid];
-#pragma unroll
-    for (int ww = 1; ww < kWaves; ++ww) M = fmaxf(M, s_m[ww][tid]);
-    float ls = 0.f;
-#pragma unroll
-    for (int ww = 0; ww < kWaves; ++ww) ls += s_l[ww][tid] * fast_exp2(s_m[ww][tid] - M);
-    float* r = a.part + rec0 + (int64_t)tid * kSlotCap * kPartStride;
-    *reinterpret_cast<float2*>(r) = make_float2(M, ls);
+  for (int p = 0; p < kPass; ++p) {
+    const int i = chunk * kReorgRows + p * 16 + r;
+    if (ok[p]) {
+      *reinterpret_cast<uint4*>(Kc + (int64_t)i * (kHeadDim * 2) + sub * 16) = kr[p];
+      *reinterpret_cast<uint4*>(Vc + (int64_t)i * (kHeadDim * 2) + sub * 16) = vr[p];
+    }
   }
 }
 
@@ -515,6 +643,14 @@ hipError_t launch_attn_dense(const AttnArgs& a, int B, int n_slots, hipStream_t 
     hipLaunchKernelGGL(attn_dense_kernel<true>, dim3(n_slots, a.Hkv, B), dim3(kAttnThreads), 0, s, a);
   else
     hipLaunchKernelGGL(attn_dense_kernel<false>, dim3(n_slots, a.Hkv, B), dim3(kAttnThreads), 0, s, a);
+  return hipGetLastError();
+}
+hipError_t launch_attn_compact(const AttnArgs& a, int B, int n_slots, hipStream_t s) {
+  hipLaunchKernelGGL(attn_compact_kernel, dim3(n_slots, a.Hkv, B), dim3(kAttnThreads), 0, s, a);
+  return hipGetLastError();
+}
+hipError_t launch_reorg(const ReorgArgs& a, int B, int rows, hipStream_t s) {
+  hipLaunchKernelGGL(reorg_kernel, dim3((rows + kReorgRows - 1) / kReorgRows, a.Hkv, B), dim3(kAttnThreads), 0, s, a);
   return hipGetLastError();
 }
 hipError_t launch_attn_gather(const AttnArgs& a, int B, int n_slots, hipStream_t s) {

@@ -63,7 +63,28 @@ struct AttnArgs {
   int32_t max_tiles;             // dense mode: tiles of J the launch covers at most (from the host's max_len)
   int32_t row_cap;               // dense mode: max_len - 1, the last row the launch may touch
   float scale_log2;              // logit scale times log2(e): the kernels work on y = log2(e) * logit
+  const uint16_t* Kc;            // compact mode: sink ++ selected rows of each (b, h), rows back to back
+  const uint16_t* Vc;
+  int64_t c_sb, c_sh;            // compact mode: strides between sequences / KV heads, in elements
+  int32_t c_rows;                // compact mode: rows every (b, h) slice of Kc / Vc holds (all readable)
 };
+
+// Reorg: gather the sink and the selected rows of every (b, h) into the compact buffers.
+struct ReorgArgs {
+  const uint16_t* K;
+  const uint16_t* V;
+  int64_t k_sb, k_sh, k_st, v_sb, v_sh, v_st;
+  const int32_t* sel_idx;
+  const int32_t* n_sel;
+  const int32_t* ctx_len;
+  const uint8_t* is_slow;        // nullptr: every sequence takes part
+  int64_t sel_stride;
+  uint16_t* Kc;
+  uint16_t* Vc;
+  int64_t c_sb, c_sh;
+  int32_t Hkv, n_sink;
+};
+constexpr int kReorgRows = 64;   // compact rows per workgroup of the Reorg kernel
 
 struct MergeArgs {
   const float* part;
@@ -93,6 +114,8 @@ struct SelArgs {
 };
 
 hipError_t launch_attn_dense(const AttnArgs& a, int B, int n_slots, hipStream_t s);
+hipError_t launch_attn_compact(const AttnArgs& a, int B, int n_slots, hipStream_t s);
+hipError_t launch_reorg(const ReorgArgs& a, int B, int rows, hipStream_t s);
 hipError_t launch_attn_gather(const AttnArgs& a, int B, int n_slots, hipStream_t s);
 hipError_t launch_merge(const MergeArgs& a, int B, hipStream_t s);
 hipError_t launch_sel_score(const SelArgs& a, int B, int n_seg, hipStream_t s);

@@ -111,5 +111,26 @@ class Runner:
         self.torch.cuda.synchronize()
         return self.out.cpu().numpy()
 
+    def reorg(self, sel, nsel, ctx_len, c_rows=None, is_slow=None, poison=0x7FC1):
+        """Compact buffers (uint16 views of bf16 device tensors) after sfi_reorg; unfilled rows keep `poison`."""
+        t = self.torch
+        c_rows = self.w.n_sink + sel.shape[2] if c_rows is None else c_rows
+        shape = (self.w.B, self.w.Hkv, c_rows, self.w.d)
+        self.Kc = to_dev(np.full(shape, poison, np.uint16))
+        self.Vc = to_dev(np.full(shape, poison, np.uint16))
+        self.sfi.sfi_reorg(self.ctx.handle, self.K, self.V, i32_dev(sel), i32_dev(nsel), sel.shape[2], i32_dev(ctx_len),
+                           None if is_slow is None else t.from_numpy(np.asarray(is_slow, np.uint8)).cuda(),
+                           self.Kc, self.Vc)
+        t.cuda.synchronize()
+        return self.Kc.view(t.int16).cpu().numpy().view(np.uint16), self.Vc.view(t.int16).cpu().numpy().view(np.uint16)
+
+    def fast_compact(self, q_bits, nsel, sel_stride, recent_start, ctx_len):
+        """Fast step over the compact buffers of the last reorg() call."""
+        self.out.fill_(float("nan"))
+        self.sfi.sfi_fast_step_compact(self.ctx.handle, to_dev(q_bits), self.Kc, self.Vc, i32_dev(nsel), sel_stride,
+                                       self.K, self.V, i32_dev(recent_start), i32_dev(ctx_len), self.out)
+        self.torch.cuda.synchronize()
+        return self.out.cpu().numpy()
+
     def close(self):
         self.ctx.close()

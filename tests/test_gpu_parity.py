@@ -319,3 +319,83 @@ def test_slow_step_with_few_splits(oracle, Hq, Hkv, L0):
         check_selection(sel, nsel, sel_ref, nsel_ref, z, ctx, w.n_sink, w.recent, w.budget)
     finally:
         r.close()
+
+
+def test_reorg_and_compact_fast_step(oracle, tiny):
+    """Reorg is a byte copy: compact buffers bit-exact against the oracle's, untouched rows keep their
+    poison (a NaN pattern, which the compact kernel must mask).  The two-segment fast step then matches
+    the oracle's sparse attention on the original cache, over several steps of a sliding recent window."""
+    w, r = tiny
+    _step("reorg + compact fast step, Selector's own selection")
+    q0, ctx = w.q(0), w.ctx_len(0)
+    _, sel, nsel = r.slow(q0, ctx, w.budget)
+    Kc, Vc = r.reorg(sel, nsel, ctx)
+    Kc_ref, Vc_ref = np.full_like(Kc, 0x7FC1), np.full_like(Vc, 0x7FC1)
+    oracle.reorg(w.K, w.V, sel, nsel, ctx, w.n_sink, Kc_ref, Vc_ref)
+    assert (Kc == Kc_ref).all() and (Vc == Vc_ref).all()
+    for t in range(1, 4):
+        q = w.q(t)
+        ctx_t, rs = w.ctx_len(t), w.recent_start(t)
+        got = r.fast_compact(q, nsel, sel.shape[2], rs, ctx_t)
+        check_out(got, oracle.sparse(q, w.K, w.V, sel, nsel, rs, ctx_t, w.n_sink))
+
+
+def test_compact_random_sets_and_edges(oracle, tiny):
+    """Arbitrary valid index sets, ragged n_sel (full budget, tile multiples, 0, 1), contexts down to one row,
+    compact buffers larger than needed."""
+    w, r = tiny
+    q = w.q(5)
+    cases = [(1500, 96), (1500, 0), (1500, 1), (1500, 28), (1500, 60), (300, 33), (70, 2), (68, 0), (5, 0), (3, 0), (1, 0)]
+    for case, (L, ns) in enumerate(cases):
+        _step(f"compact random sets L={L} n_sel={ns}")
+        ctx = np.array([L, max(1, L - 2)], np.int32)
+        rs = np.maximum(np.minimum(w.n_sink, ctx), ctx - w.recent).astype(np.int32)
+        room = np.maximum(0, rs - w.n_sink)
+        nsel = np.minimum(ns, room)[:, None].repeat(w.Hkv, axis=1).astype(np.int32)
+        nsel[1, 0] = max(0, nsel[1, 0] - 1)
+        sel = syn.random_sel(200 + case, w.B, w.Hkv, w.budget, nsel, w.n_sink, rs)
+        Kc, Vc = r.reorg(sel, nsel, ctx, c_rows=w.n_sink + w.budget + (case % 3) * 7)
+        Kc_ref, Vc_ref = np.full_like(Kc, 0x7FC1), np.full_like(Vc, 0x7FC1)
+        oracle.reorg(w.K, w.V, sel, nsel, ctx, w.n_sink, Kc_ref, Vc_ref)
+        assert (Kc == Kc_ref).all() and (Vc == Vc_ref).all()
+        got = r.fast_compact(q, nsel, w.budget, rs, ctx)
+        check_out(got, oracle.sparse(q, w.K, w.V, sel, nsel, rs, ctx, w.n_sink))
+
+
+def test_compact_long_recent_window_and_groups(oracle):
+    """G = 8 and a caller-chosen recent window longer than cfg.recent (extra trips of the tile loop)."""
+    w = syn.make_tiny(L0=900, steps=2, budget=64, recent=32, n_support=8, B=1, Hq=16, Hkv=2)
+    r = Runner(w)
+    try:
+        _step("compact: long recent window, G=8")
+        q, ctx = w.q(0), w.ctx_len(0)
+        _, sel, nsel = r.slow(q, ctx, w.budget)
+        r.reorg(sel, nsel, ctx)
+        q1, ctx1 = w.q(1), w.ctx_len(1)
+        for rs in (w.recent_start(1), ctx1 - 700, ctx1 - 1, ctx1):
+            rs = np.asarray(rs, np.int32).reshape(1)
+            keep = [sel[0, h, :nsel[0, h]][sel[0, h, :nsel[0, h]] < rs[0]] for h in range(w.Hkv)]
+            n2 = np.array([[len(k) for k in keep]], np.int32)
+            s2 = np.full_like(sel, -1)
+            for h, k in enumerate(keep):
+                s2[0, h, :len(k)] = k
+            r.reorg(s2, n2, ctx1)
+            got = r.fast_compact(q1, n2, sel.shape[2], rs, ctx1)
+            check_out(got, oracle.sparse(q1, w.K, w.V, s2, n2, rs, ctx1, w.n_sink))
+    finally:
+        r.close()
+
+
+def test_reorg_only_slow_sequences(oracle, tiny):
+    """With is_slow given, sequences whose flag is 0 keep their compact rows."""
+    w, r = tiny
+    _step("reorg predicate")
+    ctx = w.ctx_len(0)
+    rs = w.recent_start(0)
+    nsel = np.full((w.B, w.Hkv), 40, np.int32)
+    sel = syn.random_sel(77, w.B, w.Hkv, w.budget, nsel, w.n_sink, rs)
+    Kc, Vc = r.reorg(sel, nsel, ctx, is_slow=[0, 1])
+    Kc_ref, Vc_ref = np.full_like(Kc, 0x7FC1), np.full_like(Vc, 0x7FC1)
+    oracle.reorg(w.K, w.V, sel, nsel, ctx, w.n_sink, Kc_ref, Vc_ref)
+    assert (Kc[0] == 0x7FC1).all() and (Vc[0] == 0x7FC1).all()
+    assert (Kc[1] == Kc_ref[1]).all() and (Vc[1] == Vc_ref[1]).all()

@@ -211,3 +211,46 @@ def test_sparse_short_context(oracle):
         rs = max(4, ctx - 64)
         out = oracle.sparse(q, K, V, sel, np.zeros((1, 1), np.int32), [min(rs, ctx)], [ctx], 4)
         np.testing.assert_allclose(out, oracle.dense(q, K, V, [ctx]), rtol=1e-13, atol=1e-15)
+
+
+def test_reorg_is_a_row_gather(oracle):
+    """Reorg against numpy fancy indexing written here; untouched rows keep their poison; and the
+    two-segment reading of a fast step -- dense attention over the compact rows followed by the recent
+    rows, as one cache -- equals sparse attention on the original cache."""
+    B, Hkv, Hq, L, d, n_sink, R = 2, 2, 4, 300, 128, 4, 16
+    K, V = rand_bf16(1, (B, Hkv, L, d)), rand_bf16(2, (B, Hkv, L, d))
+    q = rand_bf16(3, (B, Hq, d))
+    ctx = np.array([300, 211], np.int32)
+    rs = (ctx - R).astype(np.int32)
+    nsel = np.array([[40, 17], [0, 33]], np.int32)
+    sel = syn.random_sel(5, B, Hkv, 48, nsel, n_sink, rs)
+    c_rows = n_sink + 48
+    Kc = np.full((B, Hkv, c_rows, d), 0x7FC1, np.uint16)  # a NaN pattern
+    Vc = np.full((B, Hkv, c_rows, d), 0x7FC1, np.uint16)
+    oracle.reorg(K, V, sel, nsel, ctx, n_sink, Kc, Vc)
+    for b in range(B):
+        for h in range(Hkv):
+            n = int(nsel[b, h])
+            rows = np.concatenate([np.arange(n_sink), sel[b, h, :n]])
+            assert (Kc[b, h, :n_sink + n] == K[b, h][rows]).all() and (Vc[b, h, :n_sink + n] == V[b, h][rows]).all()
+            assert (Kc[b, h, n_sink + n:] == 0x7FC1).all() and (Vc[b, h, n_sink + n:] == 0x7FC1).all()
+    ref = oracle.sparse(q, K, V, sel, nsel, rs, ctx, n_sink)
+    for b in range(B):
+        for h in range(Hkv):
+            n = int(nsel[b, h])
+            K2 = np.concatenate([Kc[b, h, :n_sink + n], K[b, h, rs[b]:ctx[b]]])[None, None]
+            V2 = np.concatenate([Vc[b, h, :n_sink + n], V[b, h, rs[b]:ctx[b]]])[None, None]
+            G = Hq // Hkv
+            got = oracle.dense(q[b:b + 1, h * G:(h + 1) * G], K2, V2, np.array([K2.shape[2]], np.int32))
+            assert np.abs(got[0] - ref[b, h * G:(h + 1) * G]).max() < 1e-12
+
+
+def test_reorg_rejects_bad_input(oracle):
+    K, V = rand_bf16(1, (1, 1, 40, 128)), rand_bf16(2, (1, 1, 40, 128))
+    Kc = np.zeros((1, 1, 12, 128), np.uint16)
+    Vc = np.zeros_like(Kc)
+    with pytest.raises(ValueError):
+        oracle.reorg(K, V, np.array([[[5, 41]]], np.int32), np.array([[2]], np.int32), np.array([40], np.int32), 4, Kc, Vc)
+    with pytest.raises(ValueError):
+        oracle.reorg(K, V, np.arange(4, 13, dtype=np.int32)[None, None], np.array([[9]], np.int32),
+                     np.array([40], np.int32), 4, Kc, Vc)
