@@ -44,6 +44,9 @@ def main():
     ap.add_argument("--ctx", type=int, default=32768)
     ap.add_argument("--batch", type=int, default=4)
     ap.add_argument("--launch", choices=["graph", "stream"], default="graph")
+    ap.add_argument("--fast-path", choices=["gather", "compact"], default="gather",
+                    help="gather: fast steps read the selected rows in place through sel_idx; compact: every slow "
+                         "step is followed by Reorg into a compact buffer and fast steps read the two-segment layout")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--dense-wgs", type=int, default=0)
     ap.add_argument("--fast-tpw", type=int, default=0)
@@ -98,11 +101,22 @@ def main():
     torch.cuda.synchronize()
     log(f"device state ready ({torch.cuda.memory_allocated() / 1e9:.1f} GB)")
 
+    compact = args.fast_path == "compact"
+    if compact:
+        Kcs = [torch.zeros(B, Hkv, w.n_sink + w.budget, d, dtype=torch.bfloat16, device=dev) for _ in range(NL)]
+        Vcs = [torch.zeros(B, Hkv, w.n_sink + w.budget, d, dtype=torch.bfloat16, device=dev) for _ in range(NL)]
+
     def slow(l, step):
         sfi.sfi_slow_step(h, q_all[step, l], Ks[l], Vs[l], ctx_d, max_ctx, w.budget, outs[l], sels[l], nsels[l])
+        if compact:
+            sfi.sfi_reorg(h, Ks[l], Vs[l], sels[l], nsels[l], w.budget, ctx_d, None, Kcs[l], Vcs[l])
 
     def fast(l, step):
-        sfi.sfi_fast_step(h, q_all[step, l], Ks[l], Vs[l], sels[l], nsels[l], w.budget, rs_d, ctx_d, outs[l])
+        if compact:
+            sfi.sfi_fast_step_compact(h, q_all[step, l], Kcs[l], Vcs[l], nsels[l], w.budget, Ks[l], Vs[l], rs_d, ctx_d,
+                                      outs[l])
+        else:
+            sfi.sfi_fast_step(h, q_all[step, l], Ks[l], Vs[l], sels[l], nsels[l], w.budget, rs_d, ctx_d, outs[l])
 
     def segment(step0):
         for t in range(SEG):
@@ -193,7 +207,7 @@ def main():
     step_p = step0 + K_seg * SEG
 
     def stage_avg_ms(fn, reps):
-        sfi.sfi_set_profiling(h, reps * NL)
+        sfi.sfi_set_profiling(h, 2 * reps * NL)
         for r in range(reps):
             for l in range(NL):
                 fn(l, step_p + r)
@@ -214,17 +228,18 @@ def main():
     # the kernel with the largest share of a segment's time is the one the roofline object describes
     seg_dense_ms = slow_ms[0]
     seg_fast_ms = fast_ms[0] * (SEG - 1)
-    dominant = "gather" if seg_fast_ms > seg_dense_ms else "dense"
+    fast_kernel = "compact" if compact else "gather"
+    dominant = fast_kernel if seg_fast_ms > seg_dense_ms else "dense"
     traffic = None  # HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one
     pmc_path = os.path.join(ROOT, "profiles", "hbm_traffic_llama8b.json")
     if os.path.exists(pmc_path) and args.ctx == 32768 and args.batch == 4:
         traffic = json.load(open(pmc_path)).get(f"attn_{dominant}_kernel", {}).get("hbm_bytes_per_launch")
     roof = {
         "bound": "hbm", "kernel": f"sfi::attn_{dominant}_kernel",
-        "achieved": fast_gbs if dominant == "gather" else dense_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": (fast_gbs if dominant == "gather" else dense_gbs) / HBM_PEAK_GBS, "traffic": traffic,
-        "algorithmic_bytes_per_launch": fast_bytes if dominant == "gather" else dense_bytes,
-        "us_per_launch": float((fast_ms[0] if dominant == "gather" else slow_ms[0]) * 1e3),
+        "achieved": fast_gbs if dominant != "dense" else dense_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": (fast_gbs if dominant != "dense" else dense_gbs) / HBM_PEAK_GBS, "traffic": traffic,
+        "algorithmic_bytes_per_launch": fast_bytes if dominant != "dense" else dense_bytes,
+        "us_per_launch": float((fast_ms[0] if dominant != "dense" else slow_ms[0]) * 1e3),
     }
     dsp, fsp = sfi.sfi_query_splits(h)
     res = {
@@ -235,14 +250,16 @@ def main():
         "config": {"workload": f"llama8b-shaped layer: B{B} Hq{Hq} Hkv{Hkv} d{d} ctx{L0} k{w.budget} R{w.recent} "
                                f"sink{w.n_sink} slow every {SEG}",
                    "step": f"{SEG} decode steps (1 slow + {SEG - 1} fast) x {NL} virtual layers",
-                   "virtual_layers": NL, "launch": args.launch, "dense_splits": dsp, "fast_splits": fsp},
+                   "virtual_layers": NL, "launch": args.launch, "fast_path": args.fast_path,
+                   "dense_splits": dsp, "fast_splits": fsp},
         "roofline": roof,
         "kernels": {
             "dense_attn": {"us": slow_ms[0] * 1e3, "kv_bytes": dense_bytes, "GBps": dense_gbs,
                            "frac_of_8TBps": dense_gbs / HBM_PEAK_GBS},
-            "gather_attn": {"us": fast_ms[0] * 1e3, "kv_bytes": fast_bytes, "GBps": fast_gbs,
+            f"{fast_kernel}_attn": {"us": fast_ms[0] * 1e3, "kv_bytes": fast_bytes, "GBps": fast_gbs,
                             "frac_of_8TBps": fast_gbs / HBM_PEAK_GBS},
-            "slow_step_stage_us": {n: float(slow_ms[i] * 1e3) for i, n in enumerate(sfi.binding.STAGE_NAMES[:6])},
+            "slow_step_stage_us": {n: float(slow_ms[i] * 1e3) for i, n in enumerate(sfi.binding.STAGE_NAMES)
+                                   if i < 6 or (compact and n == "reorg")},
             "fast_step_stage_us": {n: float(fast_ms[i] * 1e3) for i, n in enumerate(sfi.binding.STAGE_NAMES[:2])},
         },
         "us_per_decode_step_per_layer": total_s * 1e6 / (K_seg * SEG * NL),

@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libsfi.so")
 
 SFI_N_STAGES = 8
-STAGE_NAMES = ("attn", "merge", "score", "cand", "count", "write", "attn_gather_mixed", "unused")
+STAGE_NAMES = ("attn", "merge", "score", "cand", "count", "write", "attn_gather_mixed", "reorg")
 
 
 class SfiError(RuntimeError):
