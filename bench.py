@@ -47,6 +47,8 @@ def main():
     ap.add_argument("--fast-path", choices=["gather", "compact"], default="gather",
                     help="gather: fast steps read the selected rows in place through sel_idx; compact: every slow "
                          "step is followed by Reorg into a compact buffer and fast steps read the two-segment layout")
+    ap.add_argument("--selector-mode", type=int, choices=[0, 1], default=0,
+                    help="0: evidence-only ranking (the measured baseline); 1: Algorithm 2 in full, oracle defaults")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--dense-wgs", type=int, default=0)
     ap.add_argument("--fast-tpw", type=int, default=0)
@@ -87,7 +89,11 @@ def main():
         Ks.append(k)
         Vs.append(v)
     max_ctx = int(w.L_alloc)
-    ctx = sfi.SfiContext(B, Hq, Hkv, max_ctx, w.budget, w.n_sink, w.recent, K0, V0)
+    sel_params = None
+    if args.selector_mode == 1:
+        sel_params = dict(gamma=0.5, beta=1.0, p=2.0, eta=0.5, lambda_clip=0.02, alpha_soft=0.5, alpha_cross=0.35,
+                          temp=1.0, eps=1e-8, nms_radius=2)
+    ctx = sfi.SfiContext(B, Hq, Hkv, max_ctx, w.budget, w.n_sink, w.recent, K0, V0, selector=sel_params)
     h = ctx.handle
     if args.dense_wgs or args.fast_tpw:
         sfi.sfi_set_tuning(h, args.dense_wgs, args.fast_tpw)
@@ -137,7 +143,8 @@ def main():
         g_out, g_sel, g_nsel = outs[0].cpu().numpy(), sels[0].cpu().numpy(), nsels[0].cpu().numpy()
         t1 = time.time()
         o_dense = oracle.dense(qs[0], w.K, w.V, c0)
-        o_sel, o_nsel, o_z = oracle.selector(qs[0], w.K, c0, w.budget, w.n_sink, w.recent)
+        o_sp = oracle.SelectorParams(mode=1, **sel_params) if sel_params else None
+        o_sel, o_nsel, o_z = oracle.selector(qs[0], w.K, c0, w.budget, w.n_sink, w.recent, sp=o_sp)
         t_slow = time.time() - t1
         parity["slow_out_row_rel_err"] = check_out(g_out, o_dense)
         n_exact = check_selection(g_sel, g_nsel, o_sel, o_nsel, o_z, c0, w.n_sink, w.recent, w.budget)
@@ -250,7 +257,7 @@ def main():
         "config": {"workload": f"llama8b-shaped layer: B{B} Hq{Hq} Hkv{Hkv} d{d} ctx{L0} k{w.budget} R{w.recent} "
                                f"sink{w.n_sink} slow every {SEG}",
                    "step": f"{SEG} decode steps (1 slow + {SEG - 1} fast) x {NL} virtual layers",
-                   "virtual_layers": NL, "launch": args.launch, "fast_path": args.fast_path,
+                   "virtual_layers": NL, "launch": args.launch, "fast_path": args.fast_path, "selector_mode": args.selector_mode,
                    "dense_splits": dsp, "fast_splits": fsp},
         "roofline": roof,
         "kernels": {

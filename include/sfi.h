@@ -74,9 +74,22 @@ typedef struct sfi_config {
   int32_t n_sink;       /* |I_sink|; paper default 4 (Sec. 5 "Default SFI configuration") */
   int32_t recent;       /* recent window length; paper default 256 */
   float scale;          /* logit scale; 0 selects 1/sqrt(head_dim) */
-  int32_t selector_mode;/* 0: rank by the evidence f alone (Eqs. selector_pt - selector_f, z_base) */
+  int32_t selector_mode;/* 0: rank by the evidence f alone (Eqs. selector_pt - selector_f, z_base);
+                           1: Algorithm 2 in full: cache-aware prior, reverse-KL fusion with lambda*,
+                              Soft-NMS and cross-head exclusivity before the Top-K */
   int64_t k_stride_b, k_stride_h, k_stride_t; /* elements */
   int64_t v_stride_b, v_stride_h, v_stride_t; /* elements */
+  /* Selector mode 1 only (ignored in mode 0).  The power-mean exponent of Eq. selector_mu is 1. */
+  float gamma;          /* key-norm exponent, >= 0 (Eq. selector_prior_kn) */
+  float beta, p, eta;   /* position prior: beta >= 0, p >= 1, eta >= 0 (Eq. selector_prior_pos) */
+  float lambda_clip;    /* upper clip of lambda*, in [0, 1] (Eq. selector_lambda_closed) */
+  float alpha_soft;     /* Soft-NMS strength, >= 0 (Eq. nms) */
+  float alpha_cross;    /* cross-head exclusivity strength, >= 0 (Eq. head_mutex) */
+  float temp;           /* T > 0 of Eq. head_softmax */
+  float eps;            /* epsilon of Eqs. selector_prior_kn, selector_u, selector_prior_pos, z_base and
+                           head_mutex; 0 selects 1e-8.  (1 + alpha_soft + alpha_cross) * log2(1/eps) must
+                           stay below 120: the ranking key is exp(z) held in fp32 */
+  int32_t nms_radius;   /* N(j) = { i in J : |i - j| <= nms_radius }, 0 .. 64 (Eq. nms_pool) */
 } sfi_config;
 
 typedef struct sfi_ctx sfi_ctx; /* opaque; host memory owned by the library */
@@ -180,7 +193,7 @@ int sfi_advance(sfi_ctx* ctx, int32_t* ctx_len, int32_t* recent_start, void* str
 enum {
   SFI_STAGE_ATTN = 0,     /* split attention kernel (dense; gather or compact in a fast step) */
   SFI_STAGE_MERGE = 1,    /* split merge */
-  SFI_STAGE_SCORE = 2,    /* evidence + first radix histogram */
+  SFI_STAGE_SCORE = 2,    /* evidence + first radix histogram (mode 1: the three scoring kernels together) */
   SFI_STAGE_CAND = 3,     /* threshold-bin candidates */
   SFI_STAGE_COUNT = 4,    /* exact threshold + per-segment counts */
   SFI_STAGE_WRITE = 5,    /* ordered index write */

@@ -30,6 +30,9 @@ class SfiConfig(C.Structure):
         ("scale", C.c_float), ("selector_mode", C.c_int32),
         ("k_stride_b", C.c_int64), ("k_stride_h", C.c_int64), ("k_stride_t", C.c_int64),
         ("v_stride_b", C.c_int64), ("v_stride_h", C.c_int64), ("v_stride_t", C.c_int64),
+        ("gamma", C.c_float), ("beta", C.c_float), ("p", C.c_float), ("eta", C.c_float),
+        ("lambda_clip", C.c_float), ("alpha_soft", C.c_float), ("alpha_cross", C.c_float), ("temp", C.c_float),
+        ("eps", C.c_float), ("nms_radius", C.c_int32),
     ]
 
 
@@ -192,14 +195,22 @@ def sfi_query_splits(ctx) -> Tuple[int, int]:
 class SfiContext:
     """Owns the workspace tensor and the context handle for one (shape, K/V layout)."""
 
-    def __init__(self, B, Hq, Hkv, max_ctx, max_budget, n_sink, recent, K, V, scale: float = 0.0, device="cuda"):
+    def __init__(self, B, Hq, Hkv, max_ctx, max_budget, n_sink, recent, K, V, scale: float = 0.0, device="cuda",
+                 selector: Optional[dict] = None):
+        """selector: None for mode 0, or the mode-1 hyper-parameters as a dict with the keys gamma, beta, p,
+        eta, lambda_clip, alpha_soft, alpha_cross, temp, eps, nms_radius (all required: the paper fixes none
+        of the prior's)."""
         import torch
 
         assert K.dtype == torch.bfloat16 and V.dtype == torch.bfloat16 and K.dim() == 4 and K.stride(3) == 1
         cfg = SfiConfig()
         cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim = B, Hq, Hkv, K.shape[3]
         cfg.max_ctx, cfg.max_budget, cfg.n_sink, cfg.recent = max_ctx, max_budget, n_sink, recent
-        cfg.scale, cfg.selector_mode = scale, 0
+        cfg.scale, cfg.selector_mode = scale, 0 if selector is None else 1
+        if selector is not None:
+            for k in ("gamma", "beta", "p", "eta", "lambda_clip", "alpha_soft", "alpha_cross", "temp", "eps"):
+                setattr(cfg, k, float(selector[k]))
+            cfg.nms_radius = int(selector["nms_radius"])
         cfg.k_stride_b, cfg.k_stride_h, cfg.k_stride_t = K.stride(0), K.stride(1), K.stride(2)
         cfg.v_stride_b, cfg.v_stride_h, cfg.v_stride_t = V.stride(0), V.stride(1), V.stride(2)
         self.cfg = cfg

@@ -37,7 +37,17 @@ int validate(const sfi_config* c) {
   if (c->n_q_heads % c->n_kv_heads != 0) return SFI_EINVAL;
   if (c->head_dim != kHeadDim) return SFI_EUNSUPPORTED;
   if (c->n_q_heads / c->n_kv_heads > 16) return SFI_EUNSUPPORTED;
-  if (c->selector_mode != 0) return SFI_EUNSUPPORTED;
+  if (c->selector_mode != 0 && c->selector_mode != 1) return SFI_EUNSUPPORTED;
+  if (c->selector_mode == 1) {
+    if (!(c->gamma >= 0.f) || !(c->beta >= 0.f) || !(c->p >= 1.f) || !(c->eta >= 0.f) || !(c->lambda_clip >= 0.f) ||
+        !(c->lambda_clip <= 1.f) || !(c->alpha_soft >= 0.f) || !(c->alpha_cross >= 0.f) || !(c->temp > 0.f) ||
+        !(c->eps >= 0.f) || c->nms_radius < 0)
+      return SFI_EINVAL;
+    if (c->nms_radius > kMaxNmsRadius) return SFI_EUNSUPPORTED;
+    const float eps = c->eps > 0.f ? c->eps : 1e-8f;
+    // the ranking key exp(z) must stay a normal fp32 number: z >= (1 + alpha_soft + alpha_cross) * log(eps)
+    if (!(eps < 1.f) || (1.f + c->alpha_soft + c->alpha_cross) * -log2f(eps) >= 120.f) return SFI_EUNSUPPORTED;
+  }
   if ((int64_t)c->max_ctx > (int64_t)1 << 30) return SFI_EUNSUPPORTED;
   const int64_t st[6] = {c->k_stride_b, c->k_stride_h, c->k_stride_t, c->v_stride_b, c->v_stride_h, c->v_stride_t};
   for (int i = 0; i < 6; ++i) {
@@ -64,13 +74,18 @@ size_t carve(const sfi_config* c, char* base, Workspace* ws) {
     return p;
   };
   ws->part = (float*)take((size_t)(B * Hq) * kSlotCap * kPartStride * sizeof(float));
-  ws->logits = (float*)take((size_t)(B * Hq) * ld * sizeof(float));
+  const bool full = c->selector_mode == 1;
+  // exposed rows per (b, h): the G heads' y and, for the full Selector, the squared key norms
+  ws->logits = (float*)take((size_t)(B * Hq + (full ? B * Hkv : 0)) * ld * sizeof(float));
   ws->keys = (uint32_t*)take((size_t)(B * Hkv) * ld * sizeof(uint32_t));
   ws->cand = (uint32_t*)take((size_t)(B * Hkv) * ld * sizeof(uint32_t));
   ws->hist1 = (uint32_t*)take((size_t)(B * Hkv) * kHist1Bins * sizeof(uint32_t));
   ws->state = (uint32_t*)take((size_t)(B * Hkv) * kStateWords * sizeof(uint32_t));
   ws->segcnt = (uint32_t*)take((size_t)(B * Hkv) * n_seg * 2 * sizeof(uint32_t));
   ws->jstat = (float2*)take((size_t)(B * Hq) * sizeof(float2));
+  ws->prior = full ? (float*)take((size_t)(B * Hkv) * ld * sizeof(float)) : nullptr;
+  ws->znms = full ? (float*)take((size_t)(B * Hkv) * ld * sizeof(float)) : nullptr;
+  ws->segstat = full ? (double*)take((size_t)(B * Hkv) * n_seg * kSegStats * sizeof(double)) : nullptr;
   ws->ld_pos = ld;
   ws->n_seg_cap = n_seg;
   return off;
@@ -165,6 +180,12 @@ void fill_sel(const sfi_ctx* x, SelArgs* s, const int32_t* ctx_len, const uint8_
   s->ld_pos = x->ws.ld_pos; s->n_seg_cap = x->ws.n_seg_cap;
   s->Hq = c.n_q_heads; s->Hkv = c.n_kv_heads; s->G = x->G;
   s->n_sink = c.n_sink; s->recent = c.recent; s->n_split = n_split * kWaves; s->budget = budget;
+  s->prior = x->ws.prior; s->znms = x->ws.znms; s->segstat = x->ws.segstat;
+  s->gamma = c.gamma; s->beta = c.beta; s->p = c.p; s->eta = c.eta; s->lambda_clip = c.lambda_clip;
+  s->alpha_soft = c.alpha_soft; s->alpha_cross = c.alpha_cross;
+  s->inv_temp = c.temp > 0.f ? 1.0f / c.temp : 1.0f;
+  s->eps = c.eps > 0.f ? c.eps : 1e-8f;
+  s->nms_radius = c.nms_radius;
 }
 
 #define SFI_TRY(expr)                         \
@@ -178,7 +199,12 @@ int run_selector(sfi_ctx* x, const SelArgs& sa, int max_len, hipStream_t st) {
   const int nJ = max_len - x->cfg.recent - x->cfg.n_sink;
   int n_seg = nJ > 0 ? (nJ + kSelSeg - 1) / kSelSeg : 1;
   if (n_seg > x->ws.n_seg_cap) n_seg = x->ws.n_seg_cap;
-  { StageTimer t(x, st, SFI_STAGE_SCORE); SFI_TRY(launch_sel_score(sa, B, n_seg, st)); if (!t.stop()) return SFI_ELAUNCH; }
+  {
+    StageTimer t(x, st, SFI_STAGE_SCORE);
+    if (x->cfg.selector_mode == 1) SFI_TRY(launch_sel_full(sa, B, n_seg, st));
+    else SFI_TRY(launch_sel_score(sa, B, n_seg, st));
+    if (!t.stop()) return SFI_ELAUNCH;
+  }
   { StageTimer t(x, st, SFI_STAGE_CAND);  SFI_TRY(launch_sel_cand(sa, B, n_seg, st));  if (!t.stop()) return SFI_ELAUNCH; }
   { StageTimer t(x, st, SFI_STAGE_COUNT); SFI_TRY(launch_sel_count(sa, B, n_seg, st)); if (!t.stop()) return SFI_ELAUNCH; }
   { StageTimer t(x, st, SFI_STAGE_WRITE); SFI_TRY(launch_sel_write(sa, B, n_seg, st)); if (!t.stop()) return SFI_ELAUNCH; }
@@ -310,6 +336,7 @@ int sfi_slow_step(sfi_ctx* x, const void* q, const void* K, const void* V, const
   a.n_split = dense_splits_for(x, ml, false);
   set_dense_bounds(x, &a, ml);
   a.logits = x->ws.logits;
+  a.with_knorm = x->cfg.selector_mode == 1;
   a.hist1 = x->ws.hist1;
   a.state = x->ws.state;
   x->last_dense_splits = a.n_split;
@@ -429,6 +456,7 @@ int sfi_mixed_step(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   d.n_split = dense_splits_for(x, ml, true);
   set_dense_bounds(x, &d, ml);
   d.logits = x->ws.logits;
+  d.with_knorm = x->cfg.selector_mode == 1;
   d.hist1 = x->ws.hist1;
   d.state = x->ws.state;
   x->last_dense_splits = d.n_split;

@@ -136,6 +136,22 @@ __device__ __forceinline__ void qk_phase(const Tile& T, const bf16x8 (&qreg)[4],
   }
 }
 
+// Squared norms of the tile's K rows from the matrix cores: K K^T of block A (B), whose diagonal
+// element (row m, row m) sits in lane (jg, n) = (m / 4, m), slot m % 4.  Products of bf16 pairs are
+// exact in fp32.  The lane with jg == n / 4 gets ||row n||^2 of block A in k2a and of block B in k2b.
+__device__ __forceinline__ void knorm_phase(const Tile& T, int jg, int n, float& k2a, float& k2b) {
+  f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int kb = 0; kb < 4; ++kb) {
+    sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(T.ka[kb]), as_bf16x8(T.ka[kb]), sa, 0, 0, 0);
+    sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(T.kb[kb]), as_bf16x8(T.kb[kb]), sb, 0, 0, 0);
+  }
+  const int i = n & 3;
+  k2a = i == 0 ? sa[0] : i == 1 ? sa[1] : i == 2 ? sa[2] : sa[3];
+  k2b = i == 0 ? sb[0] : i == 1 ? sb[1] : i == 2 ? sb[2] : sb[3];
+  (void)jg;
+}
+
 // y of head n, rows 0..31 of the tile, goes to stage[n * 32 ..] (this wave's LDS patch).
 __device__ __forceinline__ void stage_logits(float* stage, const float (&y)[8], int jg, int n, int G) {
   if (n < G) {
@@ -269,9 +285,9 @@ struct ListWalk {
 // ------------------------------------------------------------------------------------------------
 // dense kernel
 // ------------------------------------------------------------------------------------------------
-template <bool EXPOSE>  // EXPOSE: also write y over J for the Selector
-__global__ __launch_bounds__(kAttnThreads, EXPOSE ? 2 : 3) void attn_dense_kernel(const AttnArgs a) {
-  __shared__ float s_stash[EXPOSE ? kWaves : 1][EXPOSE ? kStashFloats : 1];  // per-wave logits stash
+template <int EXPOSE>  // 1: also write y over J for the Selector; 2: y and the squared key norms
+__global__ __launch_bounds__(kAttnThreads, EXPOSE != 0 ? 2 : 3) void attn_dense_kernel(const AttnArgs a) {
+  __shared__ float s_stash[EXPOSE != 0 ? kWaves : 1][EXPOSE != 0 ? kStashFloats : 1];  // per-wave logits stash
   const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
   const int tid = threadIdx.x;
@@ -339,10 +355,13 @@ __global__ __launch_bounds__(kAttnThreads, EXPOSE ? 2 : 3) void attn_dense_kerne
     // memory counter.  It parks them in its LDS stash, laid out as they go to memory, and writes the
     // stash out in one burst when it is full and once more after its last tile, when nothing is
     // left to wait for.
-    float* stash = EXPOSE ? &s_stash[w][0] : nullptr;
-    float* lg_base = EXPOSE ? a.logits + head0 * a.ld_pos : nullptr;
-    const int tile_f4 = G * (kTile / 4);        // float4 per tile
-    const int stash_cap = kStashFloats / (G * kTile);  // tiles the stash holds
+    // With EXPOSE == 2 a tile has one more row: ||k_j||^2 of its 32 positions, for the key-norm factor of
+    // the Selector's prior (Eq. selector_prior_kn).
+    const int rows_exp = G + (EXPOSE == 2 ? 1 : 0);
+    float* stash = EXPOSE != 0 ? &s_stash[w][0] : nullptr;
+    float* lg_base = EXPOSE != 0 ? a.logits + (int64_t)bh * rows_exp * a.ld_pos : nullptr;
+    const int tile_f4 = rows_exp * (kTile / 4);        // float4 per tile
+    const int stash_cap = kStashFloats / (rows_exp * kTile);  // tiles the stash holds
     int n_stashed = 0, k_flushed = 0;
     auto flush_stash = [&]() {
       __builtin_amdgcn_wave_barrier();
@@ -368,9 +387,16 @@ __global__ __launch_bounds__(kAttnThreads, EXPOSE ? 2 : 3) void attn_dense_kerne
       const int r_next = (k + 1 < K) ? a.n_sink + (t + step) * kTile : kNoTile;
       float y[8];
       qk_phase(T, qreg, a.scale_log2, y);
+      float k2a = 0.f, k2b = 0.f;
+      if (EXPOSE == 2) knorm_phase(T, jg, n, k2a, k2b);
       issue_k_affine(T, R, r_next, r_max);
-      if (EXPOSE) {  // positions past N land in the padding of the last tile, never used
-        stage_logits(stash + n_stashed * (G * kTile), y, jg, n, G);
+      if (EXPOSE != 0) {  // positions past N land in the padding of the last tile, never used
+        float* st = stash + n_stashed * (rows_exp * kTile);
+        stage_logits(st, y, jg, n, G);
+        if (EXPOSE == 2 && jg == (n >> 2)) {
+          st[G * kTile + n] = k2a;
+          st[G * kTile + 16 + n] = k2b;
+        }
         if (++n_stashed == stash_cap) flush_stash();
       }
       if (t >= nFull) mask_tail(T, y, jg, t * kTile, N);
@@ -379,7 +405,7 @@ __global__ __launch_bounds__(kAttnThreads, EXPOSE ? 2 : 3) void attn_dense_kerne
       pv_phase(T, a_hi, a_lo, acc);
       issue_v_affine(T, R, r_next, r_max);
     }
-    if (EXPOSE) flush_stash();
+    if (EXPOSE != 0) flush_stash();
   }
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
@@ -639,10 +665,12 @@ __global__ void advance_kernel(int32_t* ctx_len, int32_t* recent_start, int B, i
 }
 
 hipError_t launch_attn_dense(const AttnArgs& a, int B, int n_slots, hipStream_t s) {
-  if (a.logits != nullptr)
-    hipLaunchKernelGGL(attn_dense_kernel<true>, dim3(n_slots, a.Hkv, B), dim3(kAttnThreads), 0, s, a);
+  if (a.logits != nullptr && a.with_knorm)
+    hipLaunchKernelGGL(attn_dense_kernel<2>, dim3(n_slots, a.Hkv, B), dim3(kAttnThreads), 0, s, a);
+  else if (a.logits != nullptr)
+    hipLaunchKernelGGL(attn_dense_kernel<1>, dim3(n_slots, a.Hkv, B), dim3(kAttnThreads), 0, s, a);
   else
-    hipLaunchKernelGGL(attn_dense_kernel<false>, dim3(n_slots, a.Hkv, B), dim3(kAttnThreads), 0, s, a);
+    hipLaunchKernelGGL(attn_dense_kernel<0>, dim3(n_slots, a.Hkv, B), dim3(kAttnThreads), 0, s, a);
   return hipGetLastError();
 }
 hipError_t launch_attn_compact(const AttnArgs& a, int B, int n_slots, hipStream_t s) {

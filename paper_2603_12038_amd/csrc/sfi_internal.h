@@ -12,6 +12,8 @@ constexpr int kTile = 32;          // KV positions per wave iteration (two 16-ro
 constexpr int kWaves = 4;          // waves per attention workgroup
 constexpr int kAttnThreads = 64 * kWaves;
 constexpr int kStashFloats = 4096;  // per-wave LDS stash for exposed logits (16 KB): 128 / G tiles
+constexpr int kMaxNmsRadius = 64;
+constexpr int kSegStats = 5;        // sum f, sum r, sum f^2, sum f r, sum r^2 of one segment
 constexpr int kPartStride = 132;   // floats per split record: m, l, pad, pad, acc[128]
 constexpr int kMaxSplits = 63;     // split workgroups per (sequence, KV head)
 // records per (sequence, query head): the dense kernel writes one per wave, (splits + 1 sink/recent
@@ -39,6 +41,9 @@ struct Workspace {
   uint32_t* state;    // [B*Hkv][kStateWords]
   uint32_t* segcnt;   // [B*Hkv][n_seg_cap][2]
   float2* jstat;      // [B*Hq]  J-only softmax statistics of each query head (slow step)
+  float* prior;       // [B*Hkv][ld]  full Selector: unnormalised prior pi_kn * pi_pos
+  float* znms;        // [B*Hkv][ld]  full Selector: log2-domain score after Soft-NMS
+  double* segstat;    // [B*Hkv][n_seg_cap][kSegStats]  full Selector: per-segment sums for lambda*
   int64_t ld_pos;     // multiple of kSelSeg
   int32_t n_seg_cap;
 };
@@ -56,6 +61,7 @@ struct AttnArgs {
   const uint8_t* is_slow;        // nullptr: every sequence takes part
   float* part;
   float* logits;                 // dense mode, nullptr: do not expose logits
+  int32_t with_knorm;            // dense mode: also expose the squared key norms (full Selector)
   uint32_t* hist1;               // dense mode with Selector: cleared by the sink/recent workgroup
   uint32_t* state;
   int64_t ld_pos;
@@ -111,6 +117,12 @@ struct SelArgs {
   int64_t ld_pos;
   int32_t n_seg_cap;
   int32_t Hq, Hkv, G, n_sink, recent, n_split, budget;
+  // full Selector (mode 1)
+  float* prior;
+  float* znms;
+  double* segstat;
+  float gamma, beta, p, eta, lambda_clip, alpha_soft, alpha_cross, inv_temp, eps;
+  int32_t nms_radius;
 };
 
 hipError_t launch_attn_dense(const AttnArgs& a, int B, int n_slots, hipStream_t s);
@@ -119,6 +131,7 @@ hipError_t launch_reorg(const ReorgArgs& a, int B, int rows, hipStream_t s);
 hipError_t launch_attn_gather(const AttnArgs& a, int B, int n_slots, hipStream_t s);
 hipError_t launch_merge(const MergeArgs& a, int B, hipStream_t s);
 hipError_t launch_sel_score(const SelArgs& a, int B, int n_seg, hipStream_t s);
+hipError_t launch_sel_full(const SelArgs& a, int B, int n_seg, hipStream_t s);
 hipError_t launch_sel_cand(const SelArgs& a, int B, int n_seg, hipStream_t s);
 hipError_t launch_sel_count(const SelArgs& a, int B, int n_seg, hipStream_t s);
 hipError_t launch_sel_write(const SelArgs& a, int B, int n_seg, hipStream_t s);

@@ -163,6 +163,201 @@ __global__ __launch_bounds__(kSelThreads) void sel_score_kernel(const SelArgs a)
   }
 }
 
+// ---- full Selector (mode 1): three kernels in place of stage 1 -------------------------------------
+// All scores of this part live in the log2 domain, Z = log2(s + eps) = z / ln 2: Soft-NMS is
+// homogeneous of degree one in z, the head softmax of z / T is 2^(Z / T) normalised, and the
+// adjustment alpha_cross * log(r) becomes alpha_cross * log2(r); the ranking key is 2^Z_adj = e^z_adj,
+// a positive fp32 whose bit pattern orders like z_adj, so stages 2-4 are shared with mode 0.
+__device__ __forceinline__ float fast_log2s(float x) { return __builtin_amdgcn_logf(x); }
+
+// Deterministic block sum of one double per thread (fixed tree); result valid in every thread.
+__device__ __forceinline__ double block_sum_f64(double v, double* scratch) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return (scratch[0] + scratch[1]) + (scratch[2] + scratch[3]);
+}
+
+// (1a) evidence f (as in mode 0) and the unnormalised prior pi_kn * pi_pos (Eqs. selector_prior_kn,
+// selector_u, selector_prior_pos) of one segment, and the segment's sums for lambda*.
+__global__ __launch_bounds__(kSelThreads) void sel_prior_kernel(const SelArgs a) {
+  const int seg = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
+  const Problem pb = problem_of(a, b);
+  const int p_lo = seg * kSelSeg;
+  if (p_lo >= pb.nJ) return;
+  const int tid = threadIdx.x;
+  const int bh = b * a.Hkv + h;
+  const int G = a.G, rows = G + 1;
+  const float* lg = a.logits + (int64_t)bh * rows * a.ld_pos;  // [tile][G heads + key norms][32]
+  float* fbuf = reinterpret_cast<float*>(a.keys) + (int64_t)bh * a.ld_pos;
+  float* prior = a.prior + (int64_t)bh * a.ld_pos;
+  float sM[16], sc[16];
+#pragma unroll
+  for (int g = 0; g < 16; ++g) {
+    const float2 t = g < G ? a.jstat[b * a.Hq + h * G + g] : make_float2(0.f, 0.f);
+    sM[g] = t.x;
+    sc[g] = t.y;
+  }
+  // u(j) = p / D, 1 - u(j) + eps = ((|J| - 1 - p) + eps) / D + eps with D = |J| - 1 + eps: the second
+  // form keeps full relative precision near the tail, where 1 - u cancels.
+  const float D = (float)(pb.nJ - 1) + a.eps;
+  const float inv_D = 1.0f / D;
+  const float beta2 = a.beta * 1.4426950408889634f;
+  double sums[kSegStats] = {0.0, 0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+  for (int r = 0; r < 2; ++r) {
+    const int p = p_lo + r * (kSelSeg / 2) + tid * 4;
+    if (p >= pb.nJ) continue;
+    const float* lt = lg + (int64_t)(p >> 5) * rows * kTile + (p & 31);
+    float f[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int g = 0; g < 16; ++g) {
+      if (g < G) {
+        const float4 l4 = *reinterpret_cast<const float4*>(lt + g * kTile);
+        f[0] += sc[g] * fast_exp2s(l4.x - sM[g]);
+        f[1] += sc[g] * fast_exp2s(l4.y - sM[g]);
+        f[2] += sc[g] * fast_exp2s(l4.z - sM[g]);
+        f[3] += sc[g] * fast_exp2s(l4.w - sM[g]);
+      }
+    }
+    const float4 k4 = *reinterpret_cast<const float4*>(lt + G * kTile);
+    const float k2[4] = {k4.x, k4.y, k4.z, k4.w};
+    float rr[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int pc = p + c;
+      const float pi_kn = fast_exp2s(-a.gamma * fast_log2s(sqrtf(k2[c]) + a.eps));
+      const float u = (float)pc * inv_D;
+      const float omu = ((float)(pb.nJ - 1 - pc) + a.eps) * inv_D + a.eps;
+      const float up = u > 0.f ? fast_exp2s(a.p * fast_log2s(u)) : 0.f;
+      const float pi_pos = fast_exp2s(-beta2 * up + a.eta * fast_log2s(omu));
+      const bool ok = pc < pb.nJ;
+      rr[c] = ok ? pi_kn * pi_pos : 0.f;
+      f[c] = ok ? f[c] : 0.f;
+      sums[0] += (double)f[c];
+      sums[1] += (double)rr[c];
+      sums[2] += (double)f[c] * (double)f[c];
+      sums[3] += (double)f[c] * (double)rr[c];
+      sums[4] += (double)rr[c] * (double)rr[c];
+    }
+    *reinterpret_cast<float4*>(fbuf + p) = make_float4(f[0], f[1], f[2], f[3]);
+    *reinterpret_cast<float4*>(prior + p) = make_float4(rr[0], rr[1], rr[2], rr[3]);
+  }
+  __shared__ double s_scr[4];
+  double* out = a.segstat + ((int64_t)bh * a.n_seg_cap + seg) * kSegStats;
+#pragma unroll
+  for (int i = 0; i < kSegStats; ++i) {
+    const double t = block_sum_f64(sums[i], s_scr);
+    if (tid == 0) out[i] = t;
+  }
+}
+
+// (1b) lambda* (Eq. selector_lambda_closed) from the segment sums, the fused score (Eq. selector_closed),
+// Z = log2(s + eps) (Eq. z_base) over the segment and a halo of nms_radius positions on either side,
+// then Soft-NMS on the un-updated scores with the neighbourhood clipped to J (Eqs. nms_pool, nms).
+__global__ __launch_bounds__(kSelThreads) void sel_fuse_kernel(const SelArgs a) {
+  const int seg = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
+  const Problem pb = problem_of(a, b);
+  const int p_lo = seg * kSelSeg;
+  if (p_lo >= pb.nJ) return;
+  const int tid = threadIdx.x;
+  const int bh = b * a.Hkv + h;
+  const float* fbuf = reinterpret_cast<const float*>(a.keys) + (int64_t)bh * a.ld_pos;
+  const float* prior = a.prior + (int64_t)bh * a.ld_pos;
+  float* zn = a.znms + (int64_t)bh * a.ld_pos;
+  __shared__ double s_scr[4];
+  __shared__ float s_z[kSelSeg + 2 * kMaxNmsRadius];
+  const int n_seg = (pb.nJ + kSelSeg - 1) / kSelSeg;
+  const double* st = a.segstat + (int64_t)bh * a.n_seg_cap * kSegStats;
+  double tot[kSegStats];
+#pragma unroll
+  for (int i = 0; i < kSegStats; ++i) {
+    double v = 0.0;
+    for (int s = tid; s < n_seg; s += kSelThreads) v += st[(int64_t)s * kSegStats + i];
+    tot[i] = block_sum_f64(v, s_scr);
+  }
+  // f and r normalised to sum 1: |f|^2 = tot2 / F^2, f.r = tot3 / (F R), |r|^2 = tot4 / R^2
+  const double F = tot[0], Rs = tot[1];
+  const double ff = tot[2] / (F * F), fr = tot[3] / (F * Rs), rr = tot[4] / (Rs * Rs);
+  const double den = ff - 2.0 * fr + rr;
+  double lambda = den > 1e-300 ? (ff - fr) / den : 0.0;
+  lambda = fmin(fmax(lambda, 0.0), (double)a.lambda_clip);
+  const float wf = (float)((1.0 - lambda) / F), wr = (float)(lambda / Rs);
+  const int rad = a.nms_radius;
+  const int n_here = min(kSelSeg, pb.nJ - p_lo);
+  for (int i = tid; i < n_here + 2 * rad; i += kSelThreads) {
+    const int p = p_lo - rad + i;
+    s_z[i] = (p >= 0 && p < pb.nJ) ? fast_log2s(wf * fbuf[p] + wr * prior[p] + a.eps) : -INFINITY;
+  }
+  __syncthreads();
+  for (int i = tid; i < n_here; i += kSelThreads) {
+    const float z = s_z[i + rad];
+    float m = z;
+    for (int d = 0; d <= 2 * rad; ++d) m = fmaxf(m, s_z[i + d]);
+    zn[p_lo + i] = z - a.alpha_soft * fmaxf(m - z, 0.f);
+  }
+}
+
+// (1c) cross-head exclusivity at each position over the Hkv heads of the sequence (Eqs. head_softmax,
+// head_mutex), then the ranking key and the 12-bit histogram exactly as stage 1 of mode 0.
+__global__ __launch_bounds__(kSelThreads) void sel_cross_kernel(const SelArgs a) {
+  const int seg = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
+  const Problem pb = problem_of(a, b);
+  const int p_lo = seg * kSelSeg;
+  if (p_lo >= pb.nJ) return;
+  const int tid = threadIdx.x;
+  const int bh = b * a.Hkv + h;
+  __shared__ uint32_t s_hist[kHist1Bins];
+  for (int i = tid; i < kHist1Bins; i += kSelThreads) s_hist[i] = 0u;
+  __syncthreads();
+  const float* zb = a.znms + (int64_t)b * a.Hkv * a.ld_pos;
+  uint32_t* keys = a.keys + (int64_t)bh * a.ld_pos;
+  const float log2_eps = fast_log2s(a.eps);
+#pragma unroll
+  for (int r = 0; r < 2; ++r) {
+    const int p = p_lo + r * (kSelSeg / 2) + tid * 4;
+    if (p >= pb.nJ) continue;
+    const float4 own4 = *reinterpret_cast<const float4*>(zb + (int64_t)h * a.ld_pos + p);
+    const float own[4] = {own4.x, own4.y, own4.z, own4.w};
+    float mx[4] = {own[0], own[1], own[2], own[3]};
+    for (int hh = 0; hh < a.Hkv; ++hh) {
+      const float4 t = *reinterpret_cast<const float4*>(zb + (int64_t)hh * a.ld_pos + p);
+      mx[0] = fmaxf(mx[0], t.x); mx[1] = fmaxf(mx[1], t.y); mx[2] = fmaxf(mx[2], t.z); mx[3] = fmaxf(mx[3], t.w);
+    }
+    float zs[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int hh = 0; hh < a.Hkv; ++hh) {
+      const float4 t = *reinterpret_cast<const float4*>(zb + (int64_t)hh * a.ld_pos + p);
+      zs[0] += fast_exp2s((t.x - mx[0]) * a.inv_temp);
+      zs[1] += fast_exp2s((t.y - mx[1]) * a.inv_temp);
+      zs[2] += fast_exp2s((t.z - mx[2]) * a.inv_temp);
+      zs[3] += fast_exp2s((t.w - mx[3]) * a.inv_temp);
+    }
+    uint32_t k[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      // log2 of the responsibility, floored at log2(eps)
+      const float lr = fmaxf((own[c] - mx[c]) * a.inv_temp - fast_log2s(zs[c]), log2_eps);
+      k[c] = __float_as_uint(fast_exp2s(own[c] + a.alpha_cross * lr));
+    }
+    *reinterpret_cast<uint4*>(keys + p) = make_uint4(k[0], k[1], k[2], k[3]);
+    atomicAdd(&s_hist[k[0] >> 19], 1u);
+    if (p + 1 < pb.nJ) atomicAdd(&s_hist[k[1] >> 19], 1u);
+    if (p + 2 < pb.nJ) atomicAdd(&s_hist[k[2] >> 19], 1u);
+    if (p + 3 < pb.nJ) atomicAdd(&s_hist[k[3] >> 19], 1u);
+  }
+  __syncthreads();
+  uint32_t* gh = a.hist1 + (int64_t)bh * kHist1Bins;
+  for (int i = tid; i < kHist1Bins; i += kSelThreads) {
+    const uint32_t c = s_hist[i];
+    if (c) atomicAdd(&gh[i], c);
+  }
+}
+
 // ---- stage 2: find the threshold bin, collect its keys -----------------------------------------
 __global__ __launch_bounds__(kSelThreads) void sel_cand_kernel(const SelArgs a) {
   const int seg = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
@@ -386,6 +581,12 @@ __global__ __launch_bounds__(kSelThreads) void sel_write_kernel(const SelArgs a)
 
 hipError_t launch_sel_score(const SelArgs& a, int B, int n_seg, hipStream_t s) {
   hipLaunchKernelGGL(sel_score_kernel, dim3(n_seg, a.Hkv, B), dim3(kSelThreads), 0, s, a);
+  return hipGetLastError();
+}
+hipError_t launch_sel_full(const SelArgs& a, int B, int n_seg, hipStream_t s) {
+  hipLaunchKernelGGL(sel_prior_kernel, dim3(n_seg, a.Hkv, B), dim3(kSelThreads), 0, s, a);
+  hipLaunchKernelGGL(sel_fuse_kernel, dim3(n_seg, a.Hkv, B), dim3(kSelThreads), 0, s, a);
+  hipLaunchKernelGGL(sel_cross_kernel, dim3(n_seg, a.Hkv, B), dim3(kSelThreads), 0, s, a);
   return hipGetLastError();
 }
 hipError_t launch_sel_cand(const SelArgs& a, int B, int n_seg, hipStream_t s) {

@@ -1,0 +1,107 @@
+"""GPU parity of the full Selector (mode 1: prior, lambda*, fusion, Soft-NMS, cross-head exclusivity)
+against the fp64 oracle's Algorithm 2, on the selected index sets.
+
+The GPU ranks in fp32, the oracle in fp64, so the two may differ on positions whose final ranking
+scores z_adj lie within FULL_BAND of the cut; outside that band the sets must be identical.  The band
+is the one of the evidence-only mode.
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+
+import sfi_synth as syn
+from helpers import Runner, check_out, check_selection
+from oracle.sfi_oracle import SelectorParams
+
+pytestmark = pytest.mark.gpu
+
+FULL_BAND = 1e-5
+
+
+def _step(msg):
+    print(f"[gpu-selector-full] {msg}", flush=True)
+
+
+def _params(**kw):
+    sp = dataclasses.replace(SelectorParams(mode=1), **kw)
+    d = {k: getattr(sp, k) for k in ("gamma", "beta", "p", "eta", "lambda_clip", "alpha_soft", "alpha_cross", "temp",
+                                      "eps", "nms_radius")}
+    return sp, d
+
+
+def _run(oracle, w, sp, d, ctx=None, budget=None, band=FULL_BAND):
+    r = Runner(w, selector=d)
+    try:
+        q = w.q(0)
+        ctx = w.ctx_len(0) if ctx is None else np.asarray(ctx, np.int32)
+        budget = w.budget if budget is None else budget
+        out, sel, nsel = r.slow(q, ctx, budget)
+        check_out(out, oracle.dense(q, w.K, w.V, ctx))
+        sel_ref, nsel_ref, z = oracle.selector(q, w.K, ctx, budget, w.n_sink, w.recent, sp=sp)
+        n_exact = check_selection(sel, nsel, sel_ref, nsel_ref, z, ctx, w.n_sink, w.recent, budget, band=band)
+        return n_exact, sel, sel_ref
+    finally:
+        r.close()
+
+
+@pytest.mark.parametrize("kw", [
+    {},                                                      # the defaults
+    {"lambda_clip": 0.5, "gamma": 1.0},                      # strong prior
+    {"lambda_clip": 1.0, "beta": 3.0, "p": 1.0, "eta": 2.0},  # lambda* unclipped; other prior shape
+    {"nms_radius": 0},                                       # Soft-NMS window of one: no change
+    {"nms_radius": 7, "alpha_soft": 1.0},
+    {"nms_radius": 64, "alpha_soft": 0.25},                  # widest window the library takes
+    {"temp": 0.5, "alpha_cross": 1.0},
+    {"temp": 4.0, "alpha_cross": 0.1, "alpha_soft": 0.0},
+])
+def test_full_selector_matches_oracle(oracle, kw):
+    sp, d = _params(**kw)
+    w = syn.make_tiny(L0=4700, steps=1, budget=160, recent=48, n_support=24, B=2, Hq=8, Hkv=2)
+    w.L0 = np.array([4700, 2300], np.int32)
+    _step(f"mode 1 {kw}")
+    n_exact, _, _ = _run(oracle, w, sp, d)
+    assert n_exact >= 2  # most cuts are wider than the band
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(4, 1), (8, 8), (16, 2), (20, 4), (16, 1)])
+def test_full_selector_head_layouts(oracle, Hq, Hkv):
+    """One KV head (the head softmax is the constant 1), eight KV heads, G = 1, 5, 8, 16."""
+    sp, d = _params()
+    w = syn.make_tiny(L0=2500, steps=1, budget=64, recent=32, n_support=12, B=1, Hq=Hq, Hkv=Hkv)
+    _step(f"mode 1 Hq={Hq} Hkv={Hkv}")
+    _run(oracle, w, sp, d)
+
+
+def test_full_selector_without_refinements_is_mode0(oracle):
+    """lambda_clip = 0 and both refinement strengths 0: Alg. 2 reduces to Top-K of f (same sets as mode 0)."""
+    sp, d = _params(lambda_clip=0.0, alpha_soft=0.0, alpha_cross=0.0)
+    w = syn.make_tiny(L0=3000, steps=1, budget=100, recent=64, n_support=16, B=1, Hq=8, Hkv=2)
+    _step("mode 1 reduced to mode 0")
+    _, sel1, _ = _run(oracle, w, sp, d)
+    r0 = Runner(w)
+    try:
+        _, sel0, _ = r0.slow(w.q(0), w.ctx_len(0), w.budget)
+    finally:
+        r0.close()
+    assert (sel0 == sel1).all()
+
+
+@pytest.mark.parametrize("L,budget", [(4 + 32 + 1, 8), (4 + 32 + 5, 8), (4 + 32 + 5, 3), (30, 8), (2048 + 36, 50),
+                                      (2048 + 37, 50), (4096 + 36 + 2, 4096)])
+def test_full_selector_edges(oracle, L, budget):
+    """|J| = 1, |J| < budget, J empty, |J| a whole segment, one past it, budget >= |J| over two segments."""
+    sp, d = _params()
+    w = syn.make_tiny(L0=4200, steps=1, budget=4096, recent=32, n_support=8, B=1, Hq=8, Hkv=2)
+    _step(f"mode 1 edge L={L} budget={budget}")
+    _run(oracle, w, sp, d, ctx=[L], budget=budget)
+
+
+def test_full_selector_at_llama8b_size(oracle):
+    """Config 2's slow step (B4, 32/8 heads, ctx 32768, K = 2048, recent 128) with the full Selector."""
+    sp, d = _params()
+    w = syn.make_llama8b(steps=2)
+    _step("mode 1 at config-2 size")
+    n_exact, _, _ = _run(oracle, w, sp, d)
+    _step(f"  index sets identical to the oracle's: {n_exact}/{w.B * w.Hkv}")
+    assert n_exact >= (w.B * w.Hkv) // 2
