@@ -47,6 +47,11 @@ def main():
     ap.add_argument("--fast-path", choices=["gather", "compact"], default="gather",
                     help="gather: fast steps read the selected rows in place through sel_idx; compact: every slow "
                          "step is followed by Reorg into a compact buffer and fast steps read the two-segment layout")
+    ap.add_argument("--slow-schedule", choices=["sync", "async"], default="sync",
+                    help="sync: each layer's Selector runs on the main stream after its dense attention; async: "
+                         "layer-wise asynchronous execution -- Selector (and Reorg) of layer i on a second stream "
+                         "under the dense attention of layer i+1, ring of --ring workspaces, one barrier at the end")
+    ap.add_argument("--ring", type=int, default=4, help="workspace slots of the asynchronous slow step")
     ap.add_argument("--selector-mode", type=int, choices=[0, 1], default=0,
                     help="0: evidence-only ranking (the measured baseline); 1: Algorithm 2 in full, oracle defaults")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -95,8 +100,13 @@ def main():
                           temp=1.0, eps=1e-8, nms_radius=2)
     ctx = sfi.SfiContext(B, Hq, Hkv, max_ctx, w.budget, w.n_sink, w.recent, K0, V0, selector=sel_params)
     h = ctx.handle
+    use_async = args.slow_schedule == "async"
+    ring = [ctx] + [sfi.SfiContext(B, Hq, Hkv, max_ctx, w.budget, w.n_sink, w.recent, K0, V0, selector=sel_params)
+                    for _ in range(args.ring - 1)] if use_async else [ctx]
+    aux = torch.cuda.Stream() if use_async else None  # default priority
     if args.dense_wgs or args.fast_tpw:
-        sfi.sfi_set_tuning(h, args.dense_wgs, args.fast_tpw)
+        for c in ring:
+            sfi.sfi_set_tuning(c.handle, args.dense_wgs, args.fast_tpw)
     gen = torch.Generator(device=dev)
     gen.manual_seed(1234)
     q_all = torch.randn(n_dec + SEG, NL, B, Hq, d, device=dev, generator=gen).to(torch.bfloat16)
@@ -124,10 +134,36 @@ def main():
         else:
             sfi.sfi_fast_step(h, q_all[step, l], Ks[l], Vs[l], sels[l], nsels[l], w.budget, rs_d, ctx_d, outs[l])
 
+    def slow_all_layers_async(step):
+        """Sec. 4.1 schedule: Attn_1 .. Attn_NL back to back on the main stream; Sel_i (+ Reorg_i) on the second
+        stream as soon as Attn_i is done; a ring slot is reused only after the Selector that last used it; one
+        barrier before the fast steps."""
+        main = torch.cuda.current_stream()
+        slot_free = [None] * len(ring)
+        for l in range(NL):
+            slot = l % len(ring)
+            hs = ring[slot].handle
+            if slot_free[slot] is not None:
+                main.wait_event(slot_free[slot])
+            sfi.sfi_slow_attn(hs, q_all[step, l], Ks[l], Vs[l], ctx_d, max_ctx, outs[l])
+            done = torch.cuda.Event()
+            done.record(main)
+            aux.wait_event(done)
+            with torch.cuda.stream(aux):
+                sfi.sfi_slow_select(hs, ctx_d, max_ctx, w.budget, sels[l], nsels[l])
+                if compact:
+                    sfi.sfi_reorg(hs, Ks[l], Vs[l], sels[l], nsels[l], w.budget, ctx_d, None, Kcs[l], Vcs[l])
+                slot_free[slot] = torch.cuda.Event()
+                slot_free[slot].record(aux)
+        main.wait_stream(aux)
+
     def segment(step0):
         for t in range(SEG):
-            for l in range(NL):
-                (slow if t == 0 else fast)(l, step0 + t)
+            if t == 0 and use_async:
+                slow_all_layers_async(step0)
+            else:
+                for l in range(NL):
+                    (slow if t == 0 else fast)(l, step0 + t)
             sfi.sfi_advance(h, ctx_d, rs_d)
 
     # ---- parity sample + CPU baseline: 1 slow + 2 fast steps of layer 0 at step 0 ---------------------
@@ -258,6 +294,7 @@ def main():
                                f"sink{w.n_sink} slow every {SEG}",
                    "step": f"{SEG} decode steps (1 slow + {SEG - 1} fast) x {NL} virtual layers",
                    "virtual_layers": NL, "launch": args.launch, "fast_path": args.fast_path, "selector_mode": args.selector_mode,
+                   "slow_schedule": args.slow_schedule + (f" (ring {len(ring)})" if use_async else ""),
                    "dense_splits": dsp, "fast_splits": fsp},
         "roofline": roof,
         "kernels": {
@@ -275,7 +312,8 @@ def main():
         "cpu_baseline": cpu_baseline,
     }
     print(json.dumps(res))
-    ctx.close()
+    for c in ring:
+        c.close()
 
 
 if __name__ == "__main__":

@@ -124,6 +124,24 @@ int sfi_slow_step(sfi_ctx* ctx, const void* q, const void* K, const void* V, con
                   int32_t max_len, int32_t budget, float* out, int32_t* sel_idx, int32_t* n_sel,
                   void* stream);
 
+/*
+ * The two halves of a slow step, for layer-wise asynchronous execution (paper Sec. "Hiding Slow-step
+ * Overhead via Layer-wise Asynchronous Execution": Attn_i -> Sel_i, Attn_{i+1} independent of Sel_i):
+ *   sfi_slow_attn    dense attention -> out; the evidence (logits over J and their softmax statistics)
+ *                    stays in this context's workspace;
+ *   sfi_slow_select  the Selector on that evidence -> sel_idx, n_sel.  ctx_len, max_len must be the ones
+ *                    given to the sfi_slow_attn call it follows.
+ * sfi_slow_step is the two in a row on one stream.  To overlap Sel_i with Attn_{i+1}, give the layers
+ * in flight a context (and workspace) each -- a ring of a few -- run sfi_slow_attn on the main stream and
+ * sfi_slow_select on a second stream that waits for an event recorded after it; before a context is
+ * reused, the main stream must wait for the event recorded after that context's last sfi_slow_select.
+ * The library creates no stream and no cross-stream dependency of its own.
+ */
+int sfi_slow_attn(sfi_ctx* ctx, const void* q, const void* K, const void* V, const int32_t* ctx_len,
+                  int32_t max_len, float* out, void* stream);
+int sfi_slow_select(sfi_ctx* ctx, const int32_t* ctx_len, int32_t max_len, int32_t budget, int32_t* sel_idx,
+                    int32_t* n_sel, void* stream);
+
 /* Dense attention only (the `out` of a slow step, no Selector).  Same arguments and meaning. */
 int sfi_dense_attn(sfi_ctx* ctx, const void* q, const void* K, const void* V, const int32_t* ctx_len,
                    int32_t max_len, float* out, void* stream);

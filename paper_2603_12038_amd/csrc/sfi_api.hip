@@ -319,18 +319,11 @@ int sfi_dense_attn(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   return SFI_OK;
 }
 
-int sfi_slow_step(sfi_ctx* x, const void* q, const void* K, const void* V, const int32_t* ctx_len,
-                  int32_t max_len, int32_t budget, float* out, int32_t* sel_idx, int32_t* n_sel,
-                  void* stream) {
-  int rc = check_common(x, q, K, V, ctx_len, out);
-  if (rc != SFI_OK) return rc;
-  if (sel_idx == nullptr || n_sel == nullptr) return SFI_EINVAL;
-  if (budget < 0 || budget > x->cfg.max_budget) return SFI_EINVAL;
-  if (misaligned(sel_idx, 4) || misaligned(n_sel, 4)) return SFI_EALIGN;
-  int ml;
-  if ((rc = resolve_max_len(x, max_len, &ml)) != SFI_OK) return rc;
-  hipStream_t st = (hipStream_t)stream;
-  CallRecord call_record(x);
+namespace {
+// First half of a slow step: dense attention with the evidence (y over J, Selector state cleared,
+// J-only softmax statistics) left in the workspace.
+int slow_attn_impl(sfi_ctx* x, const void* q, const void* K, const void* V, const int32_t* ctx_len, int ml,
+                   float* out, hipStream_t st) {
   AttnArgs a;
   fill_attn(x, &a, q, K, V, ctx_len);
   a.n_split = dense_splits_for(x, ml, false);
@@ -341,11 +334,55 @@ int sfi_slow_step(sfi_ctx* x, const void* q, const void* K, const void* V, const
   a.state = x->ws.state;
   x->last_dense_splits = a.n_split;
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(a, x->cfg.batch, a.n_split + 1, st)); if (!t.stop()) return SFI_ELAUNCH; }
-  SelArgs sa;
-  fill_sel(x, &sa, ctx_len, nullptr, budget, a.n_split, sel_idx, n_sel);
   MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, (a.n_split + 1) * kWaves, 0, 0, x->ws.jstat, a.n_split * kWaves, x->G};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
+  return SFI_OK;
+}
+
+int check_select(const sfi_ctx* x, const int32_t* ctx_len, int32_t budget, const int32_t* sel_idx, const int32_t* n_sel) {
+  if (x == nullptr || ctx_len == nullptr || sel_idx == nullptr || n_sel == nullptr) return SFI_EINVAL;
+  if (budget < 0 || budget > x->cfg.max_budget) return SFI_EINVAL;
+  if (misaligned(ctx_len, 4) || misaligned(sel_idx, 4) || misaligned(n_sel, 4)) return SFI_EALIGN;
+  return SFI_OK;
+}
+}  // namespace
+
+int sfi_slow_step(sfi_ctx* x, const void* q, const void* K, const void* V, const int32_t* ctx_len,
+                  int32_t max_len, int32_t budget, float* out, int32_t* sel_idx, int32_t* n_sel,
+                  void* stream) {
+  int rc = check_common(x, q, K, V, ctx_len, out);
+  if (rc != SFI_OK) return rc;
+  if ((rc = check_select(x, ctx_len, budget, sel_idx, n_sel)) != SFI_OK) return rc;
+  int ml;
+  if ((rc = resolve_max_len(x, max_len, &ml)) != SFI_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  CallRecord call_record(x);
+  if ((rc = slow_attn_impl(x, q, K, V, ctx_len, ml, out, st)) != SFI_OK) return rc;
+  SelArgs sa;
+  fill_sel(x, &sa, ctx_len, nullptr, budget, x->last_dense_splits, sel_idx, n_sel);
   return run_selector(x, sa, ml, st);
+}
+
+int sfi_slow_attn(sfi_ctx* x, const void* q, const void* K, const void* V, const int32_t* ctx_len,
+                  int32_t max_len, float* out, void* stream) {
+  int rc = check_common(x, q, K, V, ctx_len, out);
+  if (rc != SFI_OK) return rc;
+  int ml;
+  if ((rc = resolve_max_len(x, max_len, &ml)) != SFI_OK) return rc;
+  CallRecord call_record(x);
+  return slow_attn_impl(x, q, K, V, ctx_len, ml, out, (hipStream_t)stream);
+}
+
+int sfi_slow_select(sfi_ctx* x, const int32_t* ctx_len, int32_t max_len, int32_t budget, int32_t* sel_idx,
+                    int32_t* n_sel, void* stream) {
+  int rc = check_select(x, ctx_len, budget, sel_idx, n_sel);
+  if (rc != SFI_OK) return rc;
+  int ml;
+  if ((rc = resolve_max_len(x, max_len, &ml)) != SFI_OK) return rc;
+  CallRecord call_record(x);
+  SelArgs sa;
+  fill_sel(x, &sa, ctx_len, nullptr, budget, x->last_dense_splits, sel_idx, n_sel);
+  return run_selector(x, sa, ml, (hipStream_t)stream);
 }
 
 int sfi_fast_step(sfi_ctx* x, const void* q, const void* K, const void* V, const int32_t* sel_idx,

@@ -399,3 +399,45 @@ def test_reorg_only_slow_sequences(oracle, tiny):
     oracle.reorg(w.K, w.V, sel, nsel, ctx, w.n_sink, Kc_ref, Vc_ref)
     assert (Kc[0] == 0x7FC1).all() and (Vc[0] == 0x7FC1).all()
     assert (Kc[1] == Kc_ref[1]).all() and (Vc[1] == Vc_ref[1]).all()
+
+
+def test_slow_step_halves_on_two_streams(oracle, tiny):
+    """sfi_slow_attn on one stream and sfi_slow_select on another, a ring of two contexts over four
+    'layers' (different queries), ordered by events only: same bits as sfi_slow_step layer by layer."""
+    import torch
+    import paper_2603_12038_amd as sfi
+
+    w, r = tiny
+    _step("slow step halves on two streams")
+    ctx = w.ctx_len(0)
+    ctx_d = i32_dev(ctx)
+    qs = [w.q(t) for t in range(4)]
+    ref = [r.slow(q, ctx, w.budget) for q in qs]
+    ring = [sfi.SfiContext(w.B, w.Hq, w.Hkv, r.max_ctx, w.budget, w.n_sink, w.recent, r.K, r.V) for _ in range(2)]
+    try:
+        main, aux = torch.cuda.Stream(), torch.cuda.Stream()
+        outs = [torch.zeros(w.B, w.Hq, w.d, dtype=torch.float32, device="cuda") for _ in qs]
+        sels = [torch.full((w.B, w.Hkv, w.budget), -7, dtype=torch.int32, device="cuda") for _ in qs]
+        nsels = [torch.full((w.B, w.Hkv), -7, dtype=torch.int32, device="cuda") for _ in qs]
+        q_d = [to_dev(q) for q in qs]
+        torch.cuda.synchronize()
+        free = [None, None]
+        for l in range(4):
+            slot = l % 2
+            if free[slot] is not None:
+                main.wait_event(free[slot])
+            sfi.sfi_slow_attn(ring[slot].handle, q_d[l], r.K, r.V, ctx_d, 0, outs[l], stream=main)
+            done = torch.cuda.Event()
+            done.record(main)
+            aux.wait_event(done)
+            sfi.sfi_slow_select(ring[slot].handle, ctx_d, 0, w.budget, sels[l], nsels[l], stream=aux)
+            free[slot] = torch.cuda.Event()
+            free[slot].record(aux)
+        torch.cuda.synchronize()
+        for l in range(4):
+            o, s, n = ref[l]
+            assert (outs[l].cpu().numpy().view(np.uint32) == o.view(np.uint32)).all()
+            assert (sels[l].cpu().numpy() == s).all() and (nsels[l].cpu().numpy() == n).all()
+    finally:
+        for c in ring:
+            c.close()
