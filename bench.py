@@ -28,11 +28,220 @@ sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBS = 8000.0
-SEG = 16  # decode steps per refresh segment in this workload
+
+# Fixed-schedule workloads (one slow step every `seg` decode steps).  Default: the Llama-3-8B-shaped layer.
+# layers: virtual layers, chosen so that one round of fast steps over all layers moves more than the 256 MB
+# last-level cache holds.
+WORKLOADS = {
+    "llama8b": dict(make="make_llama8b", ctx=32768, batch=4, seg=16, layers=16,
+                    label="llama8b-shaped layer"),
+    "long": dict(make="make_long", ctx=131072, batch=1, seg=32, layers=32,
+                 label="long single stream"),
+    "cot": dict(make="make_cot", ctx=24576, batch=8, seg=24, layers=16,
+                label="long-CoT window (G=5)"),
+}
 
 
 def log(msg):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def _emit(res):
+    print(json.dumps(res))
+
+
+def _event_us(torch, fn, reps):
+    """Mean microseconds of fn() over reps back-to-back calls (HIP events on the current stream)."""
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for r in range(reps):
+        fn(r)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / reps
+
+
+def bench_serving(args):
+    """Config 5: batch 32, 64 query / 8 KV heads (G = 8), ragged contexts U{16384..65536}, K = 2048, recent 128;
+    every sequence draws its slow-step gaps from Geometric(1/20); each decode step is one sfi_mixed_step per layer
+    (per-sequence mode flags on the device).  K/V ~ N(0,1) bf16 generated on the device (8.6 GB per layer), 0.5 %
+    support rows scaled x4 in K.  A benchmark step is 16 decode steps over the virtual layers."""
+    import numpy as np
+    import torch
+
+    import paper_2603_12038_amd as sfi
+    import sfi_synth as syn
+    from helpers import i32_dev
+
+    SEG = 16
+    NL = args.layers or 4
+    B = args.batch or 32
+    n_dec = SEG * (args.steps + args.warmup)
+    w = syn.make_serving(steps=n_dec + SEG, B=B, alloc=False)
+    Hq, Hkv, d = w.Hq, w.Hkv, w.d
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(77)
+    Ks, Vs = [], []
+    for l in range(NL):
+        k = torch.empty(B, Hkv, w.L_alloc, d, dtype=torch.bfloat16, device=dev)
+        v = torch.empty_like(k)
+        for b in range(B):
+            k[b] = torch.randn(Hkv, w.L_alloc, d, device=dev, generator=gen).to(torch.bfloat16)
+            v[b] = torch.randn(Hkv, w.L_alloc, d, device=dev, generator=gen).to(torch.bfloat16)
+        sup = torch.from_numpy(w.support).to(dev)  # [B, Hkv, n]
+        rows = (sup + l * 13) % int(w.L0.min() - w.recent)
+        for b in range(B):
+            for hh in range(Hkv):
+                k[b, hh, rows[b, hh]] *= 4.0
+        Ks.append(k)
+        Vs.append(v)
+    log(f"serving workload on device: B={B} Hq={Hq} Hkv={Hkv} ctx {int(w.L0.min())}..{int(w.L0.max())} layers={NL} "
+        f"({torch.cuda.memory_allocated() / 1e9:.1f} GB)")
+    max_ctx = int(w.L_alloc)
+    ctx = sfi.SfiContext(B, Hq, Hkv, max_ctx, w.budget, w.n_sink, w.recent, Ks[0], Vs[0])
+    h = ctx.handle
+    q_all = torch.randn(n_dec + SEG, NL, B, Hq, d, device=dev, generator=gen).to(torch.bfloat16)
+    outs = [torch.zeros(B, Hq, d, dtype=torch.float32, device=dev) for _ in range(NL)]
+    sels = [torch.full((B, Hkv, w.budget), -1, dtype=torch.int32, device=dev) for _ in range(NL)]
+    nsels = [torch.zeros(B, Hkv, dtype=torch.int32, device=dev) for _ in range(NL)]
+    flags = torch.from_numpy(w.slow.astype(np.uint8)).to(dev)  # [steps, B]
+    ctx_d, rs_d = i32_dev(w.ctx_len(0)), i32_dev(w.recent_start(0))
+
+    def decode_step(t):
+        for l in range(NL):
+            sfi.sfi_mixed_step(h, q_all[t, l], Ks[l], Vs[l], flags[t], ctx_d, rs_d, max_ctx, w.budget, outs[l], sels[l],
+                               nsels[l])
+        sfi.sfi_advance(h, ctx_d, rs_d)
+
+    for t in range(args.warmup * SEG):
+        decode_step(t)
+    torch.cuda.synchronize()
+    t0 = args.warmup * SEG
+    n_t = args.steps * SEG
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        for t in range(t0, t0 + n_t):
+            decode_step(t)
+        graph.capture_end()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    graph.replay()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t1
+    # KV bytes the timed steps had to read: whole prefix for slow sequences, sink + selected + recent otherwise
+    kv = 0
+    n_slow = 0
+    for t in range(t0, t0 + n_t):
+        L = w.ctx_len(t).astype(np.int64)
+        slow = w.slow[t]
+        rows = np.where(slow, L, w.n_sink + w.budget + (L - w.recent_start(t)))
+        kv += int(rows.sum()) * Hkv * d * 2 * 2 * NL
+        n_slow += int(slow.sum())
+    # per-kernel times of an all-fast step and of the mixed steps as scheduled (events around every kernel)
+    t_p = t0 + n_t
+    none = torch.zeros(B, dtype=torch.uint8, device=dev)
+    sfi.sfi_set_profiling(h, 4 * NL)
+    for r in range(4):
+        for l in range(NL):
+            sfi.sfi_mixed_step(h, q_all[t_p + r, l], Ks[l], Vs[l], none, ctx_d, rs_d, max_ctx, w.budget, outs[l], sels[l],
+                               nsels[l])
+    torch.cuda.synchronize()
+    ms, cnt = sfi.sfi_stage_times(h)
+    sfi.sfi_set_profiling(h, 0)
+    gather_us = ms[6] / max(cnt[6], 1) * 1e3
+    L_p = w.ctx_len(t_p).astype(np.int64)
+    fast_bytes = int((w.n_sink + w.budget + (L_p - w.recent_start(t_p))).sum()) * Hkv * d * 2 * 2
+    fast_gbs = fast_bytes / (gather_us * 1e-6) / 1e9
+    tokens = B * n_t * NL
+    res = {
+        "metric": "decode attn tokens/s (slow+fast mix)", "value": tokens / wall, "unit": "tokens/s per attention layer",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall * 1e3 / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"serving mix: B{B} Hq{Hq} Hkv{Hkv} d{d} ragged ctx {int(w.L0.min())}..{int(w.L0.max())} "
+                               f"k{w.budget} R{w.recent} sink{w.n_sink}, per-sequence slow gaps ~ Geometric(1/20)",
+                   "step": f"{SEG} decode steps (sfi_mixed_step) x {NL} virtual layers", "virtual_layers": NL,
+                   "launch": "graph", "slow_sequence_steps_in_timed_region": n_slow},
+        "roofline": {"bound": "hbm", "kernel": "sfi::attn_gather_kernel (all-fast step)", "achieved": fast_gbs,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": fast_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": fast_bytes, "us_per_launch": gather_us},
+        "whole_run_kv_GBps": kv / wall / 1e9, "whole_run_frac_of_8TBps": kv / wall / 1e9 / HBM_PEAK_GBS,
+        "all_fast_step_stage_us": {"gather": gather_us, "merge": ms[1] / max(cnt[1], 1) * 1e3},
+        "us_per_decode_step_per_layer": wall * 1e6 / (n_t * NL),
+        "cpu_baseline": None,
+    }
+    _emit(res)
+    ctx.close()
+
+
+def bench_retention(args):
+    """Shape of the paper's kernel table (Table "kernel_speedup": KV length 16K, batch 16, bf16): latency of the
+    sparse attention (gather kernel + merge) over the dense attention (dense kernel + merge) at the table's
+    retention ratios, each timed with HIP events around back-to-back launches cycling over virtual layers."""
+    import numpy as np
+    import torch
+
+    import paper_2603_12038_amd as sfi
+    import sfi_synth as syn
+    from helpers import i32_dev
+
+    B, Hq, Hkv, d, L, R, n_sink = args.batch or 16, 32, 8, 128, args.ctx or 16384, 128, 4
+    NL = args.layers or 4
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(5)
+    Ks = [torch.randn(B, Hkv, L, d, device=dev, generator=gen).to(torch.bfloat16) for _ in range(NL)]
+    Vs = [torch.randn(B, Hkv, L, d, device=dev, generator=gen).to(torch.bfloat16) for _ in range(NL)]
+    max_budget = L - R - n_sink
+    ctx = sfi.SfiContext(B, Hq, Hkv, L, max_budget, n_sink, R, Ks[0], Vs[0])
+    h = ctx.handle
+    q = torch.randn(B, Hq, d, device=dev, generator=gen).to(torch.bfloat16)
+    out = torch.zeros(B, Hq, d, dtype=torch.float32, device=dev)
+    ctx_d = i32_dev(np.full(B, L))
+    rs_d = i32_dev(np.full(B, L - R))
+    reps = 6 * NL
+    dense_us = _event_us(torch, lambda r: sfi.sfi_dense_attn(h, q, Ks[r % NL], Vs[r % NL], ctx_d, L, out), NL)
+    dense_us = _event_us(torch, lambda r: sfi.sfi_dense_attn(h, q, Ks[r % NL], Vs[r % NL], ctx_d, L, out), reps)
+    paper = {1.6: 10.67, 6.3: 9.56, 12.5: 7.15, 25.0: 3.96, 37.5: 2.75, 50.0: 2.10, 75.0: 1.43, 98.4: 1.10, 100.0: 1.00}
+    rows = []
+    for pct, paper_x in paper.items():
+        budget = max(0, min(max_budget, int(round(pct / 100.0 * L)) - R - n_sink))  # rows kept = sink + budget + recent
+        sel = torch.full((NL, B, Hkv, max(budget, 1)), -1, dtype=torch.int32, device=dev)
+        for l in range(NL):
+            for b in range(B):
+                for hh in range(Hkv):
+                    if budget > 0:
+                        perm = torch.randperm(max_budget, device=dev, generator=gen)[:budget].sort().values
+                        sel[l, b, hh, :budget] = (perm + n_sink).to(torch.int32)
+        nsel = torch.full((B, Hkv), budget, dtype=torch.int32, device=dev)
+        fn = lambda r: sfi.sfi_fast_step(h, q, Ks[r % NL], Vs[r % NL], sel[r % NL], nsel, max(budget, 1), rs_d, ctx_d, out)
+        _event_us(torch, fn, NL)
+        sparse_us = _event_us(torch, fn, reps)
+        kept = n_sink + budget + R
+        rows.append({"retention_pct": pct, "rows_kept": kept, "sparse_us": sparse_us, "dense_us": dense_us,
+                     "speedup": dense_us / sparse_us, "paper_speedup_b200": paper_x,
+                     "sparse_GBps": B * Hkv * kept * d * 4 / (sparse_us * 1e-6) / 1e9})
+        log(f"retention {pct:5.1f}%: sparse {sparse_us:7.1f} us, dense {dense_us:7.1f} us, x{dense_us / sparse_us:5.2f} "
+            f"(paper, B200: x{paper_x})")
+    dense_bytes = B * Hkv * L * d * 4
+    res = {
+        "metric": "sparse over dense attention latency ratio", "value": rows[0]["speedup"], "unit": "x at 1.6 % retention",
+        "n_gpus": 1, "steps": reps, "warmup": NL, "ms_per_step": dense_us * 1e-3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"kernel table shape: B{B} Hq{Hq} Hkv{Hkv} d{d} KV length {L}, recent {R}, sink {n_sink}",
+                   "virtual_layers": NL, "timing": "dense kernel + merge vs gather kernel + merge, HIP events"},
+        "roofline": {"bound": "hbm", "kernel": "sfi::attn_dense_kernel<0> + merge", "achieved": dense_bytes / (dense_us * 1e-6) / 1e9,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dense_bytes / (dense_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                     "traffic": None},
+        "table": rows, "cpu_baseline": None,
+    }
+    _emit(res)
+    ctx.close()
 
 
 def main():
@@ -40,9 +249,13 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=8, help="timed refresh segments (16 decode steps each)")
     ap.add_argument("--warmup", type=int, default=2, help="untimed refresh segments")
-    ap.add_argument("--layers", type=int, default=16, help="virtual layers (distinct K/V buffers)")
-    ap.add_argument("--ctx", type=int, default=32768)
-    ap.add_argument("--batch", type=int, default=4)
+    ap.add_argument("--workload", choices=sorted(WORKLOADS) + ["serving", "retention"], default="llama8b",
+                    help="llama8b (the baseline's metric workload), long, cot: slow+fast mix on a fixed schedule; "
+                         "serving: ragged batch-32 mix with per-sequence modes; retention: sparse vs dense kernel "
+                         "latency at KV length 16K")
+    ap.add_argument("--layers", type=int, default=0, help="virtual layers (distinct K/V buffers); 0 = workload default")
+    ap.add_argument("--ctx", type=int, default=0, help="context length at step 0; 0 = workload default")
+    ap.add_argument("--batch", type=int, default=0, help="sequences; 0 = workload default")
     ap.add_argument("--launch", choices=["graph", "stream"], default="graph")
     ap.add_argument("--fast-path", choices=["gather", "compact"], default="gather",
                     help="gather: fast steps read the selected rows in place through sel_idx; compact: every slow "
@@ -63,6 +276,16 @@ def main():
               file=sys.stderr)
         sys.exit(2)
 
+    if args.workload == "serving":
+        return bench_serving(args)
+    if args.workload == "retention":
+        return bench_retention(args)
+    wl = WORKLOADS[args.workload]
+    SEG = wl["seg"]
+    args.ctx = args.ctx or wl["ctx"]
+    args.batch = args.batch or wl["batch"]
+    args.layers = args.layers or wl["layers"]
+
     import numpy as np
     import torch
 
@@ -77,7 +300,7 @@ def main():
     n_dec = SEG * (K_seg + W_seg)
 
     t0 = time.time()
-    w = syn.make_llama8b(L0=args.ctx, steps=n_dec + SEG, B=args.batch)  # rows for the schedule + a spare segment
+    w = getattr(syn, wl["make"])(L0=args.ctx, steps=n_dec + SEG, B=args.batch)  # rows for the schedule + a spare segment
     log(f"generated workload in {time.time() - t0:.1f}s: B={w.B} Hq={w.Hq} Hkv={w.Hkv} L0={args.ctx} "
         f"K={w.budget} R={w.recent} layers={NL}")
     B, Hq, Hkv, d, L0 = w.B, w.Hq, w.Hkv, w.d, args.ctx
@@ -198,7 +421,7 @@ def main():
         cpu_baseline = {
             "value": B * SEG / (t_slow + (SEG - 1) * t_fast), "unit": "tokens/s per attention layer",
             "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": "1 slow step (dense + Selector) + 2 fast steps of layer 0, extrapolated to 1 slow + 15 fast",
+            "sample": f"1 slow step (dense + Selector) + 2 fast steps of layer 0, extrapolated to 1 slow + {SEG - 1} fast",
             "slow_step_s": t_slow, "fast_step_s": t_fast,
         }
         log(f"parity sample ok {parity}; oracle slow {t_slow:.2f}s fast {t_fast:.3f}s on {oracle.num_threads()} threads")
@@ -275,7 +498,7 @@ def main():
     dominant = fast_kernel if seg_fast_ms > seg_dense_ms else "dense"
     traffic = None  # HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one
     pmc_path = os.path.join(ROOT, "profiles", "hbm_traffic_llama8b.json")
-    if os.path.exists(pmc_path) and args.ctx == 32768 and args.batch == 4:
+    if os.path.exists(pmc_path) and args.workload == "llama8b" and args.ctx == 32768 and args.batch == 4:
         traffic = json.load(open(pmc_path)).get(f"attn_{dominant}_kernel", {}).get("hbm_bytes_per_launch")
     roof = {
         "bound": "hbm", "kernel": f"sfi::attn_{dominant}_kernel",
@@ -290,7 +513,7 @@ def main():
         "n_gpus": 1, "steps": K_seg, "warmup": W_seg, "ms_per_step": total_s * 1e3 / K_seg,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": f"llama8b-shaped layer: B{B} Hq{Hq} Hkv{Hkv} d{d} ctx{L0} k{w.budget} R{w.recent} "
+        "config": {"workload": f"{wl['label']}: B{B} Hq{Hq} Hkv{Hkv} d{d} ctx{L0} k{w.budget} R{w.recent} "
                                f"sink{w.n_sink} slow every {SEG}",
                    "step": f"{SEG} decode steps (1 slow + {SEG - 1} fast) x {NL} virtual layers",
                    "virtual_layers": NL, "launch": args.launch, "fast_path": args.fast_path, "selector_mode": args.selector_mode,

@@ -233,19 +233,22 @@ def make_cot(L0: int = 8192, steps: int = 2048, seed: int = 0, B: int = 8, Hq: i
 
 def make_serving(steps: int = 256, seed: int = 0, B: int = 32, Hq: int = 64, Hkv: int = 8, budget: int = 2048,
                  recent: int = 128, len_lo: int = 16384, len_hi: int = 65536, mean_gap: float = 20.0,
-                 support_frac: float = 0.005) -> Workload:
-    """Config 5: ragged high-batch mix; per-sequence slow steps at geometric gaps (first step slow)."""
+                 support_frac: float = 0.005, alloc: bool = True) -> Workload:
+    """Config 5: ragged high-batch mix; per-sequence slow steps at geometric gaps (first step slow).
+    alloc=False leaves K / V unset (lengths, support positions and schedule only), for callers that
+    fill the cache on the device."""
     r = rng_for(seed, _TID_LEN)
     L0 = r.integers(len_lo, len_hi + 1, size=B).astype(np.int32)
     w = Workload("serving", B, Hq, Hkv, L0, steps, budget, recent, seed=seed)
     w.L_alloc = int(L0.max()) + steps
     n_support = max(1, int(round(support_frac * float(L0.min()))))
     w.support = _uniform_support(w, n_support, w.n_sink, (L0 - recent))
-    scale = np.ones((B, Hkv, w.L_alloc), dtype=np.float32)
-    for b in range(B):
-        for h in range(Hkv):
-            scale[b, h, w.support[b, h]] = 4.0
-    _alloc_kv(w, scale)
+    if alloc:
+        scale = np.ones((B, Hkv, w.L_alloc), dtype=np.float32)
+        for b in range(B):
+            for h in range(Hkv):
+                scale[b, h, w.support[b, h]] = 4.0
+        _alloc_kv(w, scale)
     rs = rng_for(seed, _TID_SCHED)
     slow = np.zeros((steps, B), dtype=bool)
     for b in range(B):
