@@ -225,7 +225,10 @@ int sfi_stage_times(sfi_ctx* ctx, float* ms_sum /* host, [SFI_N_STAGES] */, int3
 /* Launch-geometry knobs for sweeps (values <= 0 keep the current setting):
  * dense_target_wgs     workgroups a dense launch aims for in total (default 2 per compute unit: all
  *                      resident at once, one round of equal shares);
- * fast_tiles_per_wave  32-row tiles each wave of the gather launch gets (default 1). */
+ * fast_tiles_per_wave  32-row tiles each wave of the gather launch gets.  Default: decided per launch --
+ *                      one tile per wave while that fits the chip in about one round of workgroups,
+ *                      otherwise few workgroups per (sequence, KV head) and a pipelined loop over
+ *                      several tiles per wave. */
 int sfi_set_tuning(sfi_ctx* ctx, int32_t dense_target_wgs, int32_t fast_tiles_per_wave);
 
 /* Launch geometry of the last call (for reports): split workgroups per (sequence, KV head). */

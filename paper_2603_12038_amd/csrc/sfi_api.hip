@@ -14,7 +14,8 @@ struct sfi_ctx {
   Workspace ws;
   int n_cu;
   int dense_target_wgs;     // workgroups the dense launch aims for
-  int fast_tiles_per_wave;  // 32-row tiles each wave of the gather launch should get
+  int fast_tiles_per_wave;  // 32-row tiles each wave of the gather launch should get; 0 = decided per launch
+  int fast_target_wgs;      // gather launches larger than this many one-tile workgroups use the pipelined kernel
   int last_dense_splits, last_fast_splits;
   // profiling: a ring of event pairs, one set of stages per hot call, read back in one go so that
   // no host synchronisation sits between the profiled calls
@@ -116,10 +117,28 @@ void set_dense_bounds(const sfi_ctx* x, AttnArgs* a, int max_len) {
   a->row_cap = max_len - 1;
 }
 
-int fast_splits_for(const sfi_ctx* x, int sel_stride) {
+// Gather launch geometry.  One tile per wave while all workgroups fit on the chip in about one round
+// (3 resident per compute unit); beyond that, few workgroups per (b, h) walking several tiles each
+// with the pipelined kernel.  fast_tiles_per_wave > 0 overrides: 1 = one tile per wave, t > 1 =
+// pipelined with about t tiles per wave.
+int fast_splits_for(const sfi_ctx* x, int sel_stride, int* pipelined) {
   const int rows = x->cfg.n_sink + sel_stride + x->cfg.recent;
   const int tiles = (rows + kTile - 1) / kTile;
-  int s = (tiles + kWaves * x->fast_tiles_per_wave - 1) / (kWaves * x->fast_tiles_per_wave);
+  const int pairs = x->cfg.batch * x->cfg.n_kv_heads;
+  const int one = (tiles + kWaves - 1) / kWaves;
+  int s;
+  if (x->fast_tiles_per_wave > 0) {
+    s = (tiles + kWaves * x->fast_tiles_per_wave - 1) / (kWaves * x->fast_tiles_per_wave);
+    *pipelined = x->fast_tiles_per_wave > 1;
+  } else if ((int64_t)pairs * one <= (int64_t)x->fast_target_wgs) {
+    s = one;
+    *pipelined = 0;
+  } else {
+    s = x->fast_target_wgs / pairs;
+    if (s > one) s = one;
+    *pipelined = 1;
+  }
+  if (sel_stride < 1) *pipelined = 0;  // the pipelined kernel reads sel_idx unconditionally
   if (s > kMaxSplits) s = kMaxSplits;
   if (s < 1) s = 1;
   return s;
@@ -128,7 +147,8 @@ int fast_splits_for(const sfi_ctx* x, int sel_stride) {
 // The compact segment and the recent window are tiled separately (no tile straddles them).
 int compact_splits_for(const sfi_ctx* x, int sel_stride) {
   const int tiles = (x->cfg.n_sink + sel_stride + kTile - 1) / kTile + (x->cfg.recent + kTile - 1) / kTile;
-  int s = (tiles + kWaves * x->fast_tiles_per_wave - 1) / (kWaves * x->fast_tiles_per_wave);
+  const int tpw = x->fast_tiles_per_wave > 0 ? x->fast_tiles_per_wave : 1;
+  int s = (tiles + kWaves * tpw - 1) / (kWaves * tpw);
   if (s > kMaxSplits) s = kMaxSplits;
   if (s < 1) s = 1;
   return s;
@@ -271,7 +291,8 @@ int sfi_create(const sfi_config* cfg, void* workspace, size_t workspace_bytes, s
   else
     (void)hipGetLastError();  // no device here: keep the MI355X default
   x->dense_target_wgs = 2 * x->n_cu;
-  x->fast_tiles_per_wave = 1;
+  x->fast_tiles_per_wave = 0;
+  x->fast_target_wgs = 3 * x->n_cu;
   *out = x;
   return SFI_OK;
 }
@@ -401,7 +422,7 @@ int sfi_fast_step(sfi_ctx* x, const void* q, const void* K, const void* V, const
   a.sel_idx = sel_idx;
   a.n_sel = n_sel;
   a.sel_stride = sel_stride;
-  a.n_split = fast_splits_for(x, sel_stride);
+  a.n_split = fast_splits_for(x, sel_stride, &a.pipelined);
   x->last_fast_splits = a.n_split;
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_gather(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
   MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1, nullptr, 0, x->G};
@@ -504,7 +525,7 @@ int sfi_mixed_step(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   f.sel_idx = sel_idx;
   f.n_sel = n_sel;
   f.sel_stride = budget;
-  f.n_split = fast_splits_for(x, budget);
+  f.n_split = fast_splits_for(x, budget, &f.pipelined);
   x->last_fast_splits = f.n_split;
   // the gather part reads last segment's sel rows of fast sequences; the Selector below only
   // rewrites rows of slow sequences, so the order of the two attention launches is free.

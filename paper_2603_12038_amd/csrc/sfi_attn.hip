@@ -104,6 +104,23 @@ __device__ __forceinline__ void issue_rows(Tile& T, const Rows& R, int ra, int r
   }
 }
 
+// The same in two halves, for the pipelined gather loop.
+__device__ __forceinline__ void issue_k_rows(Tile& T, const Rows& R, int ra, int rb) {
+  const uint32_t oa = (uint32_t)ra * R.k_st + R.k_lane, ob = (uint32_t)rb * R.k_st + R.k_lane;
+#pragma unroll
+  for (int kb = 0; kb < 4; ++kb) {
+    T.ka[kb] = load_row16(R.Kb, oa + kb * 64);
+    T.kb[kb] = load_row16(R.Kb, ob + kb * 64);
+  }
+}
+__device__ __forceinline__ void issue_v_rows(Tile& T, const Rows& R, int ra, int rb) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    T.v[i] = load_row16(R.Vb, (uint32_t)__shfl(ra, 4 * R.jg + i) * R.v_st + R.v_lane);
+    T.v[4 + i] = load_row16(R.Vb, (uint32_t)__shfl(rb, 4 * R.jg + i) * R.v_st + R.v_lane);
+  }
+}
+
 // Q^T operand: head n, dims kblk*32 + 8*jg .. +8; zero for heads >= G (no branch around the loads).
 __device__ __forceinline__ void load_q(bf16x8 (&qreg)[4], const uint16_t* q, int64_t head0, int G, int jg, int n) {
   const uint16_t* qp = q + (head0 + (n < G ? n : 0)) * kHeadDim + jg * 8;
@@ -273,6 +290,9 @@ struct ListWalk {
   int nS, nSel, rs, N;
   __device__ __forceinline__ int sel_at(int p) const {  // index stored for list position p (valid inside the sel part)
     return sel_cap >= 0 ? sel[min(max(p - n_sink, 0), sel_cap)] : 0;
+  }
+  __device__ __forceinline__ int sel_at_nonempty(int p) const {  // the same without the branch; needs sel_cap >= 0
+    return sel[min(max(p - n_sink, 0), sel_cap)];
   }
   __device__ __forceinline__ int row_of(int p, int s) const {
     const int i = p - nS;
@@ -524,6 +544,93 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_kernel(const Attn
 }
 
 // ------------------------------------------------------------------------------------------------
+// gather kernel, pipelined: for launches whose index lists are long or many enough that one tile
+// per wave would take several rounds of workgroups (large batches, large budgets).  Few workgroups
+// per (b, h), each wave walks tiles first, first + step, ... with the dense kernel's loop: one tile
+// buffer whose K half is refilled with the next tile's rows right after S^T, the V half right
+// after P V; the selected indices are read two tiles ahead.  Loads past the wave's last tile fall
+// on row 0 (no branch around a load, so every wait names exactly the loads it needs).
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(const AttnArgs a) {
+  const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  if (a.is_slow != nullptr && a.is_slow[b] != 0) return;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, w = tid >> 6;
+  const int jg = lane >> 4, n = lane & 15;
+  const int G = a.G;
+  const int bh = b * a.Hkv + h;
+  const int64_t head0 = (int64_t)b * a.Hq + h * G;
+  const int first = slot * kWaves + w, step = a.n_split * kWaves;
+  const int pstep = step * kTile;
+
+  ListWalk W;
+  W.sel = a.sel_idx + (int64_t)bh * a.sel_stride;
+  W.sel_cap = (int)a.sel_stride - 1;
+  W.n_sink = a.n_sink;
+  const int p_first = first * kTile;
+  const int sA = W.sel_at_nonempty(p_first + n), sB = W.sel_at_nonempty(p_first + 16 + n);
+  bf16x8 qreg[4];
+  load_q(qreg, a.q, head0, G, jg, n);
+  const int L = a.ctx_len[b];
+  W.nS = min(a.n_sink, L);
+  W.nSel = a.n_sel[bh];
+  W.rs = min(max(a.recent_start[b], W.nS), L);
+  W.N = W.nS + W.nSel + (L - W.rs);
+
+  Rows R;
+  R.Kb = reinterpret_cast<const char*>(a.K + b * a.k_sb + h * a.k_sh);
+  R.Vb = reinterpret_cast<const char*>(a.V + b * a.v_sb + h * a.v_sh);
+  R.k_st = (uint32_t)a.k_st * 2u;
+  R.v_st = (uint32_t)a.v_st * 2u;
+  R.k_lane = jg * 16;
+  R.v_lane = n * 16;
+  R.jg = jg;
+  R.n = n;
+
+  Tile T;
+  float m_run = kNeg, l_run = 0.f;
+  f32x4 acc[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const int nT = (W.N + kTile - 1) / kTile;
+  const int K = first < nT ? (nT - first + step - 1) / step : 0;
+  // Memory instructions go out in the same order here as in an iteration of the loop below -- K rows,
+  // the indices of the tile after, V rows -- so the in-order load counter reads the same on both ways
+  // into the loop.  A wave without tiles reads row 0 and skips the loop.
+  int sAn, sBn;
+  {
+    const int ra = W.row_of(p_first + n, sA), rb = W.row_of(p_first + 16 + n, sB);
+    __builtin_amdgcn_sched_barrier(0);  // the compiler's scheduler must not reorder the three groups
+    issue_k_rows(T, R, ra, rb);
+    __builtin_amdgcn_sched_barrier(0);
+    sAn = W.sel_at_nonempty(p_first + pstep + n);
+    sBn = W.sel_at_nonempty(p_first + pstep + 16 + n);
+    __builtin_amdgcn_sched_barrier(0);
+    issue_v_rows(T, R, ra, rb);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  for (int k = 0; k < K; ++k) {
+    const int p0 = p_first + k * pstep;
+    const int pn = p0 + pstep;
+    float y[8];
+    qk_phase(T, qreg, a.scale_log2, y);
+    const int ra = W.row_of(pn + n, sAn), rb = W.row_of(pn + 16 + n, sBn);  // row 0 past the list
+    issue_k_rows(T, R, ra, rb);
+    sAn = W.sel_at_nonempty(pn + pstep + n);
+    sBn = W.sel_at_nonempty(pn + pstep + 16 + n);
+    if (p0 + kTile > W.N) mask_tail(T, y, jg, p0, W.N);
+    bf16x8 a_hi, a_lo;
+    softmax_phase(y, acc, m_run, l_run, jg, a_hi, a_lo);
+    pv_phase(T, a_hi, a_lo, acc);
+    issue_v_rows(T, R, ra, rb);
+  }
+  l_run += __shfl_xor(l_run, 16);
+  l_run += __shfl_xor(l_run, 32);
+  write_wg_record(a.part, head0, G, slot, acc, m_run, l_run);
+}
+
+// ------------------------------------------------------------------------------------------------
 // compact kernel: the fast step over the two-segment layout (Sec. "Memory-coalesced Kernel Design
 // and Selector Maintenance"): sink ++ selected rows from the compact buffers the Reorg kernel filled,
 // the recent window in place from the cache.  Both segments are runs of consecutive rows, so no
@@ -682,6 +789,10 @@ hipError_t launch_reorg(const ReorgArgs& a, int B, int rows, hipStream_t s) {
   return hipGetLastError();
 }
 hipError_t launch_attn_gather(const AttnArgs& a, int B, int n_slots, hipStream_t s) {
+  if (a.pipelined) {
+    hipLaunchKernelGGL(attn_gather_stream_kernel, dim3(n_slots, a.Hkv, B), dim3(kAttnThreads), 0, s, a);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(attn_gather_kernel, dim3(n_slots, a.Hkv, B), dim3(kAttnThreads), 0, s, a);
   return hipGetLastError();
 }

@@ -441,3 +441,31 @@ def test_slow_step_halves_on_two_streams(oracle, tiny):
     finally:
         for c in ring:
             c.close()
+
+
+@pytest.mark.parametrize("tpw", [2, 3, 7, 40])
+def test_fast_step_pipelined_gather(oracle, tiny, tpw):
+    """The pipelined gather kernel (several tiles per wave, forced through the tuning knob): the Selector's
+    own sets, arbitrary sets, ragged n_sel, and lists shorter than one tile."""
+    w, r = tiny
+    _step(f"pipelined gather, {tpw} tiles per wave")
+    r.sfi.sfi_set_tuning(r.ctx.handle, 0, tpw)
+    try:
+        q0, ctx = w.q(0), w.ctx_len(0)
+        _, sel, nsel = r.slow(q0, ctx, w.budget)
+        for t in range(1, 3):
+            q, ctx_t, rs = w.q(t), w.ctx_len(t), w.recent_start(t)
+            got = r.fast(q, sel, nsel, rs, ctx_t)
+            check_out(got, oracle.sparse(q, w.K, w.V, sel, nsel, rs, ctx_t, w.n_sink))
+        q = w.q(5)
+        for case, (L, ns) in enumerate([(1500, 96), (1500, 0), (1500, 1), (300, 33), (70, 2), (5, 0), (1, 0)]):
+            ctx = np.array([L, max(1, L - 2)], np.int32)
+            rs = np.maximum(np.minimum(w.n_sink, ctx), ctx - w.recent).astype(np.int32)
+            room = np.maximum(0, rs - w.n_sink)
+            nsel2 = np.minimum(ns, room)[:, None].repeat(w.Hkv, axis=1).astype(np.int32)
+            nsel2[1, 0] = max(0, nsel2[1, 0] - 1)
+            sel2 = syn.random_sel(300 + case, w.B, w.Hkv, w.budget, nsel2, w.n_sink, rs)
+            got = r.fast(q, sel2, nsel2, rs, ctx)
+            check_out(got, oracle.sparse(q, w.K, w.V, sel2, nsel2, rs, ctx, w.n_sink))
+    finally:
+        r.sfi.sfi_set_tuning(r.ctx.handle, 0, 1)
