@@ -200,6 +200,8 @@ def bench_retention(args):
     max_budget = L - R - n_sink
     ctx = sfi.SfiContext(B, Hq, Hkv, L, max_budget, n_sink, R, Ks[0], Vs[0])
     h = ctx.handle
+    if args.dense_wgs or args.fast_tpw:
+        sfi.sfi_set_tuning(h, args.dense_wgs, args.fast_tpw)
     q = torch.randn(B, Hq, d, device=dev, generator=gen).to(torch.bfloat16)
     out = torch.zeros(B, Hq, d, dtype=torch.float32, device=dev)
     ctx_d = i32_dev(np.full(B, L))

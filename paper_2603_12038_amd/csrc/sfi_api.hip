@@ -95,18 +95,21 @@ size_t carve(const sfi_config* c, char* base, Workspace* ws) {
 inline bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
 
 // Split workgroups per (sequence, KV head) of a dense launch.  All sequences dense: aim at
-// dense_target_wgs workgroups in total, the sink/recent workgroup of each pair included (two per
-// compute unit by default: every workgroup resident at once, one round, equal shares).  Mixed step:
+// dense_target_wgs workgroups in total (two per compute unit by default: every workgroup resident at
+// once, one round, equal shares of the prefix, sink and recent rows included).  Mixed step:
 // the host cannot know how many sequences are slow, so take the finest split; workgroups of fast
 // sequences exit at once.
 int dense_splits_for(const sfi_ctx* x, int max_len, bool mixed) {
   const int nJ = max_len - x->cfg.recent - x->cfg.n_sink;
-  const int tiles = nJ > 0 ? (nJ + kTile - 1) / kTile : 0;
+  const int tiles_sr = (x->cfg.n_sink + x->cfg.recent + kTile - 1) / kTile;
+  const int tiles = (nJ > 0 ? (nJ + kTile - 1) / kTile : 0) + tiles_sr;
   const int pairs = x->cfg.batch * x->cfg.n_kv_heads;
-  int s = mixed ? kMaxSplits : x->dense_target_wgs / pairs - 1;
+  int s = mixed ? kMaxSplits : x->dense_target_wgs / pairs;
   const int cap = (tiles + kWaves - 1) / kWaves;
   if (s > cap) s = cap;
   if (s > kMaxSplits) s = kMaxSplits;
+  // records per query head: one per wave for J plus one per wave that owns sink / recent tiles
+  while (s > 1 && s * kWaves + (s * kWaves < tiles_sr ? s * kWaves : tiles_sr) > kSlotCap) --s;
   if (s < 1) s = 1;
   return s;
 }
@@ -334,8 +337,8 @@ int sfi_dense_attn(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   a.n_split = dense_splits_for(x, ml, false);
   set_dense_bounds(x, &a, ml);
   x->last_dense_splits = a.n_split;
-  { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(a, x->cfg.batch, a.n_split + 1, st)); if (!t.stop()) return SFI_ELAUNCH; }
-  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, (a.n_split + 1) * kWaves, 0, 0, nullptr, 0, x->G};
+  { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
+  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, a.n_split * kWaves, 0, 0, nullptr, 0, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
 }
@@ -354,8 +357,8 @@ int slow_attn_impl(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   a.hist1 = x->ws.hist1;
   a.state = x->ws.state;
   x->last_dense_splits = a.n_split;
-  { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(a, x->cfg.batch, a.n_split + 1, st)); if (!t.stop()) return SFI_ELAUNCH; }
-  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, (a.n_split + 1) * kWaves, 0, 0, x->ws.jstat, a.n_split * kWaves, x->G};
+  { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
+  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, a.n_split * kWaves, 0, 0, x->ws.jstat, a.n_split * kWaves, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
 }
@@ -425,7 +428,7 @@ int sfi_fast_step(sfi_ctx* x, const void* q, const void* K, const void* V, const
   a.n_split = fast_splits_for(x, sel_stride, &a.pipelined);
   x->last_fast_splits = a.n_split;
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_gather(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
-  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1, nullptr, 0, x->G};
+  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1, nullptr, 0, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
 }
@@ -490,7 +493,7 @@ int sfi_fast_step_compact(sfi_ctx* x, const void* q, const void* Kc, const void*
   a.n_split = compact_splits_for(x, sel_stride);
   x->last_fast_splits = a.n_split;
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_compact(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
-  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1, nullptr, 0, x->G};
+  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1, nullptr, 0, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
 }
@@ -530,8 +533,8 @@ int sfi_mixed_step(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   // the gather part reads last segment's sel rows of fast sequences; the Selector below only
   // rewrites rows of slow sequences, so the order of the two attention launches is free.
   { StageTimer t(x, st, SFI_STAGE_ATTN2); SFI_TRY(launch_attn_gather(f, x->cfg.batch, f.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
-  { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(d, x->cfg.batch, d.n_split + 1, st)); if (!t.stop()) return SFI_ELAUNCH; }
-  MergeArgs m{x->ws.part, out, is_slow, x->cfg.n_q_heads, (d.n_split + 1) * kWaves, f.n_split, 2, x->ws.jstat, d.n_split * kWaves, x->G};
+  { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(d, x->cfg.batch, d.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
+  MergeArgs m{x->ws.part, out, is_slow, x->cfg.n_q_heads, d.n_split * kWaves, f.n_split, 2, x->ws.jstat, d.n_split * kWaves, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   SelArgs sa;
   fill_sel(x, &sa, ctx_len, is_slow, budget, d.n_split, sel_idx, n_sel);

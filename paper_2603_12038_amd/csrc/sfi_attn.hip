@@ -306,7 +306,7 @@ struct ListWalk {
 // dense kernel
 // ------------------------------------------------------------------------------------------------
 template <int EXPOSE>  // 1: also write y over J for the Selector; 2: y and the squared key norms
-__global__ __launch_bounds__(kAttnThreads, EXPOSE != 0 ? 2 : 3) void attn_dense_kernel(const AttnArgs a) {
+__global__ __launch_bounds__(kAttnThreads, 2) void attn_dense_kernel(const AttnArgs a) {
   __shared__ float s_stash[EXPOSE != 0 ? kWaves : 1][EXPOSE != 0 ? kStashFloats : 1];  // per-wave logits stash
   const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
@@ -326,110 +326,144 @@ __global__ __launch_bounds__(kAttnThreads, EXPOSE != 0 ? 2 : 3) void attn_dense_
   R.jg = jg;
   R.n = n;
 
+  // The prefix of (b, h) is cut into 32-row tiles in two runs: tiles [0, nTJ) cover the allowed set J
+  // (tile t, position i is cache row n_sink + 32 t + i), tiles [nTJ, nTJ + nTS) cover the sink rows
+  // followed by the recent window, which the Selector never ranks.  The n_split * 4 waves of the
+  // (b, h) pair own tiles first, first + step, ... of that sequence, so every wave of every workgroup
+  // carries an equal share.  A wave's J tiles come first; it keeps two records, one for each run
+  // (the J-only softmax statistics the Selector needs are merged from the J records alone).
+  // The rows of the wave's first tile follow from the block index alone (almost always a J tile):
+  // their loads go out before ctx_len arrives, clamped to the launch's row bound.
+  const int n_waves = a.n_split * kWaves;
+  const int first = slot * kWaves + w, step = n_waves;
   Tile T;
+  if (first < a.max_tiles) issue_affine(T, R, a.n_sink + first * kTile, a.row_cap);
   bf16x8 qreg[4];
+  load_q(qreg, a.q, head0, G, jg, n);
+  const int L = a.ctx_len[b];
+  if (slot == 0 && a.hist1 != nullptr) {  // fresh Selector state for this (b, h)
+    uint32_t* hh = a.hist1 + (int64_t)bh * kHist1Bins;
+    for (int i = tid; i < kHist1Bins; i += kAttnThreads) hh[i] = 0u;
+    if (tid < kStateWords) a.state[(int64_t)bh * kStateWords + tid] = 0u;
+  }
+  const int NJ = max(0, L - a.recent - a.n_sink);
+  const int nTJ = (NJ + kTile - 1) / kTile;
+  const int rJ_max = a.n_sink + NJ - 1;
+  const int nS = min(a.n_sink, L);
+  const int rs = min(max(a.n_sink, L - a.recent), L);
+  const int NS = nS + (L - rs);
+  const int nTS = (NS + kTile - 1) / kTile;
+  const int nT = nTJ + nTS;
+  const int K = first < nT ? (nT - first + step - 1) / step : 0;      // tiles of this wave
+  const int KJ = first < nTJ ? (nTJ - first + step - 1) / step : 0;   // ... of which in J
+  const int d_rs = rs - nS, r_last = L - 1;
+  // cache row of position i of tile t; tiles past the end (the refill after the last tile) read row L - 1
+  auto row_for = [&](int t, int i) -> int {
+    const int xj = a.n_sink + t * kTile + i;
+    const int xs = (t - nTJ) * kTile + i;
+    const int r_s = min(xs < nS ? xs : xs + d_rs, r_last);
+    return t < nTJ ? min(xj, rJ_max) : r_s;
+  };
+  auto issue_k_tile = [&](int t) {
+    const uint32_t oa = (uint32_t)row_for(t, n) * R.k_st + R.k_lane;
+    const uint32_t ob = (uint32_t)row_for(t, 16 + n) * R.k_st + R.k_lane;
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb) {
+      T.ka[kb] = load_row16(R.Kb, oa + kb * 64);
+      T.kb[kb] = load_row16(R.Kb, ob + kb * 64);
+    }
+  };
+  auto issue_v_tile = [&](int t) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      T.v[i] = load_row16(R.Vb, (uint32_t)row_for(t, 4 * jg + i) * R.v_st + R.v_lane);
+      T.v[4 + i] = load_row16(R.Vb, (uint32_t)row_for(t, 16 + 4 * jg + i) * R.v_st + R.v_lane);
+    }
+  };
+  if (K > 0 && first >= nTJ) {  // short context: the first tile is a sink / recent tile after all
+    issue_k_tile(first);
+    issue_v_tile(first);
+  }
+
   float m_run = kNeg, l_run = 0.f;
   f32x4 acc[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  if (slot == a.n_split) {
-    // ---- the sink and recent rows (never ranked by the Selector) ------------------------------------
-    load_q(qreg, a.q, head0, G, jg, n);
-    const int L = a.ctx_len[b];
-    if (a.hist1 != nullptr) {  // fresh Selector state for this (b, h)
-      uint32_t* hh = a.hist1 + (int64_t)bh * kHist1Bins;
-      for (int i = tid; i < kHist1Bins; i += kAttnThreads) hh[i] = 0u;
-      if (tid < kStateWords) a.state[(int64_t)bh * kStateWords + tid] = 0u;
+  // Exposing y.  The logits of (b, h) are stored tile-major, [tile][G heads][32 positions], so a
+  // tile's G x 128 bytes are one contiguous run.  A wave does not store a tile's logits when it
+  // has them: a store acknowledged late would sit in front of the next rows in the in-order
+  // memory counter.  It parks them in its LDS stash, laid out as they go to memory, and writes the
+  // stash out in one burst when it is full and once more after its last tile, when nothing is
+  // left to wait for.
+  // With EXPOSE == 2 a tile has one more row: ||k_j||^2 of its 32 positions, for the key-norm factor of
+  // the Selector's prior (Eq. selector_prior_kn).
+  const int rows_exp = G + (EXPOSE == 2 ? 1 : 0);
+  float* stash = EXPOSE != 0 ? &s_stash[w][0] : nullptr;
+  float* lg_base = EXPOSE != 0 ? a.logits + (int64_t)bh * rows_exp * a.ld_pos : nullptr;
+  const int tile_f4 = rows_exp * (kTile / 4);        // float4 per tile
+  const int stash_cap = kStashFloats / (rows_exp * kTile);  // tiles the stash holds
+  int n_stashed = 0, k_flushed = 0;
+  auto flush_stash = [&]() {
+    __builtin_amdgcn_wave_barrier();
+    const int n_f4 = n_stashed * tile_f4;
+    for (int f = lane; f < n_f4; f += 64) {
+      const int i = f / tile_f4, rem = f - i * tile_f4;
+      const int t = first + (k_flushed + i) * step;
+      *reinterpret_cast<float4*>(lg_base + ((int64_t)t * tile_f4 + rem) * 4) = *reinterpret_cast<const float4*>(stash + f * 4);
     }
-    ListWalk W;
-    W.sel = nullptr;
-    W.sel_cap = -1;
-    W.n_sink = a.n_sink;
-    W.nS = min(a.n_sink, L);
-    W.nSel = 0;
-    W.rs = min(max(a.n_sink, L - a.recent), L);
-    W.N = W.nS + (L - W.rs);
-    const int nT = (W.N + kTile - 1) / kTile;
-    for (int t = w; t < nT; t += kWaves) {
-      const int p0 = t * kTile;
-      issue_rows(T, R, W.row_of(p0 + n, 0), W.row_of(p0 + 16 + n, 0));
-      tile_math<true>(T, qreg, a.scale_log2, acc, m_run, l_run, jg, p0, W.N);
-    }
-  } else {
-    // ---- a share of J: position p is cache row n_sink + p ---------------------------------------------
-    // This wave owns tiles first, first + step, ...  The rows of its first tile follow from the
-    // block index alone: their loads go out before ctx_len arrives (clamped to the launch's row
-    // bound; masked later if they turn out to lie past the list).
-    const int first = slot * kWaves + w, step = a.n_split * kWaves;
-    if (first < a.max_tiles) issue_affine(T, R, a.n_sink + first * kTile, a.row_cap);
-    load_q(qreg, a.q, head0, G, jg, n);
-    const int L = a.ctx_len[b];
-    const int N = max(0, L - a.recent - a.n_sink);
-    const int nFull = N / kTile, nT = (N + kTile - 1) / kTile;
-    const int r_max = a.n_sink + N - 1;
-    const int K = first < nT ? (nT - first + step - 1) / step : 0;  // tiles of this wave, ragged one included
-    // Exposing y.  The logits of (b, h) are stored tile-major, [tile][G heads][32 positions], so a
-    // tile's G x 128 bytes are one contiguous run.  A wave does not store a tile's logits when it
-    // has them: a store acknowledged late would sit in front of the next rows in the in-order
-    // memory counter.  It parks them in its LDS stash, laid out as they go to memory, and writes the
-    // stash out in one burst when it is full and once more after its last tile, when nothing is
-    // left to wait for.
-    // With EXPOSE == 2 a tile has one more row: ||k_j||^2 of its 32 positions, for the key-norm factor of
-    // the Selector's prior (Eq. selector_prior_kn).
-    const int rows_exp = G + (EXPOSE == 2 ? 1 : 0);
-    float* stash = EXPOSE != 0 ? &s_stash[w][0] : nullptr;
-    float* lg_base = EXPOSE != 0 ? a.logits + (int64_t)bh * rows_exp * a.ld_pos : nullptr;
-    const int tile_f4 = rows_exp * (kTile / 4);        // float4 per tile
-    const int stash_cap = kStashFloats / (rows_exp * kTile);  // tiles the stash holds
-    int n_stashed = 0, k_flushed = 0;
-    auto flush_stash = [&]() {
-      __builtin_amdgcn_wave_barrier();
-      const int n_f4 = n_stashed * tile_f4;
-      for (int f = lane; f < n_f4; f += 64) {
-        const int i = f / tile_f4, rem = f - i * tile_f4;
-        const int t = first + (k_flushed + i) * step;
-        *reinterpret_cast<float4*>(lg_base + ((int64_t)t * tile_f4 + rem) * 4) = *reinterpret_cast<const float4*>(stash + f * 4);
-      }
-      __builtin_amdgcn_wave_barrier();
-      k_flushed += n_stashed;
-      n_stashed = 0;
-    };
+    __builtin_amdgcn_wave_barrier();
+    k_flushed += n_stashed;
+    n_stashed = 0;
+  };
+  auto write_record = [&](int wslot) {
+    float lr = l_run;
+    lr += __shfl_xor(lr, 16);
+    lr += __shfl_xor(lr, 32);
+    write_wave_record(a.part, head0, G, wslot, acc, m_run, lr, lane);
+  };
 
-    // One loop for all of the wave's tiles, one tile buffer: the K half is refilled with the next
-    // tile's rows as soon as the logits are out, the V half as soon as P V is done, so rows are on
-    // their way during most of a tile's math.  The refill is unconditional -- past the wave's last
-    // tile it degenerates to re-reading row r_max -- so that no branch surrounds a load and every
-    // wait can name exactly the loads it needs.
-    constexpr int kNoTile = 1 << 28;
-    for (int k = 0; k < K; ++k) {
-      const int t = first + k * step;
-      const int r_next = (k + 1 < K) ? a.n_sink + (t + step) * kTile : kNoTile;
-      float y[8];
-      qk_phase(T, qreg, a.scale_log2, y);
-      float k2a = 0.f, k2b = 0.f;
-      if (EXPOSE == 2) knorm_phase(T, jg, n, k2a, k2b);
-      issue_k_affine(T, R, r_next, r_max);
-      if (EXPOSE != 0) {  // positions past N land in the padding of the last tile, never used
-        float* st = stash + n_stashed * (rows_exp * kTile);
-        stage_logits(st, y, jg, n, G);
-        if (EXPOSE == 2 && jg == (n >> 2)) {
-          st[G * kTile + n] = k2a;
-          st[G * kTile + 16 + n] = k2b;
-        }
-        if (++n_stashed == stash_cap) flush_stash();
-      }
-      if (t >= nFull) mask_tail(T, y, jg, t * kTile, N);
-      bf16x8 a_hi, a_lo;
-      softmax_phase(y, acc, m_run, l_run, jg, a_hi, a_lo);
-      pv_phase(T, a_hi, a_lo, acc);
-      issue_v_affine(T, R, r_next, r_max);
+  // One loop for all of the wave's tiles, one tile buffer: the K half is refilled with the next
+  // tile's rows as soon as the logits are out, the V half as soon as P V is done, so rows are on
+  // their way during most of a tile's math.  The refill is unconditional -- past the wave's last
+  // tile it degenerates to re-reading row L - 1 -- so that no branch surrounds a load and every
+  // wait can name exactly the loads it needs.
+  for (int k = 0; k < K; ++k) {
+    const int t = first + k * step;
+    const bool inJ = k < KJ;
+    if (k == KJ) {  // the J tiles are done (or there were none): close the J record, start the other one
+      write_record(first);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+      m_run = kNeg;
+      l_run = 0.f;
     }
-    if (EXPOSE != 0) flush_stash();
+    float y[8];
+    qk_phase(T, qreg, a.scale_log2, y);
+    float k2a = 0.f, k2b = 0.f;
+    if (EXPOSE == 2) knorm_phase(T, jg, n, k2a, k2b);
+    issue_k_tile(t + step);
+    if (EXPOSE != 0 && inJ) {  // positions past |J| land in the padding of the last tile, never used
+      float* st = stash + n_stashed * (rows_exp * kTile);
+      stage_logits(st, y, jg, n, G);
+      if (EXPOSE == 2 && jg == (n >> 2)) {
+        st[G * kTile + n] = k2a;
+        st[G * kTile + 16 + n] = k2b;
+      }
+      if (++n_stashed == stash_cap) flush_stash();
+    }
+    const int p0 = (inJ ? t : t - nTJ) * kTile;
+    const int N = inJ ? NJ : NS;
+    if (p0 + kTile > N) mask_tail(T, y, jg, p0, N);
+    bf16x8 a_hi, a_lo;
+    softmax_phase(y, acc, m_run, l_run, jg, a_hi, a_lo);
+    pv_phase(T, a_hi, a_lo, acc);
+    issue_v_tile(t + step);
   }
-  l_run += __shfl_xor(l_run, 16);
-  l_run += __shfl_xor(l_run, 32);
-  write_wave_record(a.part, head0, G, slot * kWaves + w, acc, m_run, l_run, lane);
+  if (EXPOSE != 0) flush_stash();
+  // the record still open: the J record if the wave had no other tile (slot first), else the record of
+  // its sink / recent tiles, slot n_waves + e with e the rank of its first such tile among them
+  write_record(K == KJ ? first : n_waves + (first + KJ * step - nTJ));
 }
 
 // The four waves of a workgroup fold their running states into one record (b, head, slot):
@@ -759,6 +793,14 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(const MergeArgs a)
   else if (a.mode == 1) n_slots = a.slots_fast;
   else n_slots = a.is_slow[b] ? a.slots_slow : a.slots_fast;
   const bool dense = a.mode == 0 || (a.mode == 2 && a.is_slow[b]);
+  if (dense) {
+    // dense records: slots_slow waves' J records, then one record per wave that owned sink / recent tiles
+    const int L = a.ctx_len[b];
+    const int nS = min(a.n_sink, L);
+    const int rs = min(max(a.n_sink, L - a.recent), L);
+    const int nTS = (nS + (L - rs) + kTile - 1) / kTile;
+    n_slots = a.slots_slow + min(a.slots_slow, nTS);
+  }
   merge_records(a.part, a.out, bg, n_slots, dense ? a.jstat : nullptr, a.n_j, a.G);
 }
 

@@ -101,6 +101,8 @@ struct MergeArgs {
   int32_t mode;                        // 0: all sequences use slots_slow, 1: all use slots_fast, 2: per is_slow
   float2* jstat;                       // dense records: also leave the J-only softmax statistics here (may be null)
   int32_t n_j, G;                      // records that cover J; query heads per KV head
+  const int32_t* ctx_len;              // dense records: the number of sink / recent records follows from it
+  int32_t n_sink, recent;
 };
 
 struct SelArgs {
