@@ -79,7 +79,7 @@ typedef struct sfi_config {
                               Soft-NMS and cross-head exclusivity before the Top-K */
   int64_t k_stride_b, k_stride_h, k_stride_t; /* elements */
   int64_t v_stride_b, v_stride_h, v_stride_t; /* elements */
-  /* Selector mode 1 only (ignored in mode 0).  The power-mean exponent of Eq. selector_mu is 1. */
+  /* Selector mode 1 only (ignored in mode 0). */
   float gamma;          /* key-norm exponent, >= 0 (Eq. selector_prior_kn) */
   float beta, p, eta;   /* position prior: beta >= 0, p >= 1, eta >= 0 (Eq. selector_prior_pos) */
   float lambda_clip;    /* upper clip of lambda*, in [0, 1] (Eq. selector_lambda_closed) */
@@ -90,6 +90,9 @@ typedef struct sfi_config {
                            head_mutex; 0 selects 1e-8.  (1 + alpha_soft + alpha_cross) * log2(1/eps) must
                            stay below 120: the ranking key is exp(z) held in fp32 */
   int32_t nms_radius;   /* N(j) = { i in J : |i - j| <= nms_radius }, 0 .. 64 (Eq. nms_pool) */
+  /* Both modes: power-mean exponent of Eq. selector_mu over the G query heads of a KV head, in (0, 1];
+   * 0 selects 1 (f = the arithmetic mean of the heads' softmaxes over J). */
+  float alpha;
 } sfi_config;
 
 typedef struct sfi_ctx sfi_ctx; /* opaque; host memory owned by the library */
@@ -113,6 +116,7 @@ const char* sfi_strerror(int status);
  *   out[b, g, :]     = softmax_j(scale * <q[b,g], K[b,h,j]>) V[b,h,:]  over j in [0, ctx_len[b])
  *   sel_idx[b, h, :] = the n_sel[b,h] = min(budget, |J|) positions of J with the largest evidence
  *                      f_h(j) = (1/G) sum_{g in group h} softmax over J of the logits of head g
+ *                      (cfg.alpha = 1; in general the power mean of Eqs. selector_mu, selector_f)
  *                      (ranking score z = log(f + 1e-8) is monotone in f); equal scores: the lower
  *                      position wins; written ascending, entries [n_sel, budget) set to -1.
  * sel_idx is addressed with row stride `budget`.  max_len: host-side upper bound of ctx_len[]

@@ -32,7 +32,7 @@ class SfiConfig(C.Structure):
         ("v_stride_b", C.c_int64), ("v_stride_h", C.c_int64), ("v_stride_t", C.c_int64),
         ("gamma", C.c_float), ("beta", C.c_float), ("p", C.c_float), ("eta", C.c_float),
         ("lambda_clip", C.c_float), ("alpha_soft", C.c_float), ("alpha_cross", C.c_float), ("temp", C.c_float),
-        ("eps", C.c_float), ("nms_radius", C.c_int32),
+        ("eps", C.c_float), ("nms_radius", C.c_int32), ("alpha", C.c_float),
     ]
 
 
@@ -211,7 +211,7 @@ class SfiContext:
     """Owns the workspace tensor and the context handle for one (shape, K/V layout)."""
 
     def __init__(self, B, Hq, Hkv, max_ctx, max_budget, n_sink, recent, K, V, scale: float = 0.0, device="cuda",
-                 selector: Optional[dict] = None):
+                 selector: Optional[dict] = None, alpha: float = 0.0):
         """selector: None for mode 0, or the mode-1 hyper-parameters as a dict with the keys gamma, beta, p,
         eta, lambda_clip, alpha_soft, alpha_cross, temp, eps, nms_radius (all required: the paper fixes none
         of the prior's)."""
@@ -222,6 +222,7 @@ class SfiContext:
         cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim = B, Hq, Hkv, K.shape[3]
         cfg.max_ctx, cfg.max_budget, cfg.n_sink, cfg.recent = max_ctx, max_budget, n_sink, recent
         cfg.scale, cfg.selector_mode = scale, 0 if selector is None else 1
+        cfg.alpha = alpha
         if selector is not None:
             for k in ("gamma", "beta", "p", "eta", "lambda_clip", "alpha_soft", "alpha_cross", "temp", "eps"):
                 setattr(cfg, k, float(selector[k]))

@@ -13,6 +13,7 @@ struct sfi_ctx {
   int G;
   Workspace ws;
   int n_cu;
+  float alpha;              // power-mean exponent of the evidence, in (0, 1]
   int dense_target_wgs;     // workgroups the dense launch aims for
   int fast_tiles_per_wave;  // 32-row tiles each wave of the gather launch should get; 0 = decided per launch
   int fast_target_wgs;      // gather launches larger than this many one-tile workgroups use the pipelined kernel
@@ -39,6 +40,7 @@ int validate(const sfi_config* c) {
   if (c->head_dim != kHeadDim) return SFI_EUNSUPPORTED;
   if (c->n_q_heads / c->n_kv_heads > 16) return SFI_EUNSUPPORTED;
   if (c->selector_mode != 0 && c->selector_mode != 1) return SFI_EUNSUPPORTED;
+  if (!(c->alpha >= 0.f) || c->alpha > 1.f) return SFI_EINVAL;
   if (c->selector_mode == 1) {
     if (!(c->gamma >= 0.f) || !(c->beta >= 0.f) || !(c->p >= 1.f) || !(c->eta >= 0.f) || !(c->lambda_clip >= 0.f) ||
         !(c->lambda_clip <= 1.f) || !(c->alpha_soft >= 0.f) || !(c->alpha_cross >= 0.f) || !(c->temp > 0.f) ||
@@ -209,6 +211,8 @@ void fill_sel(const sfi_ctx* x, SelArgs* s, const int32_t* ctx_len, const uint8_
   s->inv_temp = c.temp > 0.f ? 1.0f / c.temp : 1.0f;
   s->eps = c.eps > 0.f ? c.eps : 1e-8f;
   s->nms_radius = c.nms_radius;
+  s->alpha = x->alpha;
+  s->inv_alpha = 1.0f / x->alpha;
 }
 
 #define SFI_TRY(expr)                         \
@@ -284,6 +288,7 @@ int sfi_create(const sfi_config* cfg, void* workspace, size_t workspace_bytes, s
   x->cfg = *cfg;
   x->scale = cfg->scale > 0.f ? cfg->scale : 1.0f / sqrtf((float)cfg->head_dim);
   x->G = cfg->n_q_heads / cfg->n_kv_heads;
+  x->alpha = cfg->alpha > 0.f ? cfg->alpha : 1.0f;
   x->ws = ws;
   x->n_cu = 256;
   int dev = 0;
@@ -338,7 +343,7 @@ int sfi_dense_attn(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   set_dense_bounds(x, &a, ml);
   x->last_dense_splits = a.n_split;
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
-  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, a.n_split * kWaves, 0, 0, nullptr, 0, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent};
+  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, a.n_split * kWaves, 0, 0, nullptr, 0, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
 }
@@ -358,7 +363,7 @@ int slow_attn_impl(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   a.state = x->ws.state;
   x->last_dense_splits = a.n_split;
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
-  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, a.n_split * kWaves, 0, 0, x->ws.jstat, a.n_split * kWaves, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent};
+  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, a.n_split * kWaves, 0, 0, x->ws.jstat, a.n_split * kWaves, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
 }
@@ -428,7 +433,7 @@ int sfi_fast_step(sfi_ctx* x, const void* q, const void* K, const void* V, const
   a.n_split = fast_splits_for(x, sel_stride, &a.pipelined);
   x->last_fast_splits = a.n_split;
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_gather(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
-  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1, nullptr, 0, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent};
+  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1, nullptr, 0, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
 }
@@ -493,7 +498,7 @@ int sfi_fast_step_compact(sfi_ctx* x, const void* q, const void* Kc, const void*
   a.n_split = compact_splits_for(x, sel_stride);
   x->last_fast_splits = a.n_split;
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_compact(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
-  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1, nullptr, 0, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent};
+  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1, nullptr, 0, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
 }
@@ -534,7 +539,7 @@ int sfi_mixed_step(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   // rewrites rows of slow sequences, so the order of the two attention launches is free.
   { StageTimer t(x, st, SFI_STAGE_ATTN2); SFI_TRY(launch_attn_gather(f, x->cfg.batch, f.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(d, x->cfg.batch, d.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
-  MergeArgs m{x->ws.part, out, is_slow, x->cfg.n_q_heads, d.n_split * kWaves, f.n_split, 2, x->ws.jstat, d.n_split * kWaves, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent};
+  MergeArgs m{x->ws.part, out, is_slow, x->cfg.n_q_heads, d.n_split * kWaves, f.n_split, 2, x->ws.jstat, d.n_split * kWaves, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   SelArgs sa;
   fill_sel(x, &sa, ctx_len, is_slow, budget, d.n_split, sel_idx, n_sel);

@@ -801,7 +801,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(const MergeArgs a)
     const int nTS = (nS + (L - rs) + kTile - 1) / kTile;
     n_slots = a.slots_slow + min(a.slots_slow, nTS);
   }
-  merge_records(a.part, a.out, bg, n_slots, dense ? a.jstat : nullptr, a.n_j, a.G);
+  merge_records(a.part, a.out, bg, n_slots, dense ? a.jstat : nullptr, a.n_j, a.G, a.alpha);
 }
 
 __global__ void advance_kernel(int32_t* ctx_len, int32_t* recent_start, int B, int n_sink, int recent) {

@@ -103,6 +103,7 @@ struct MergeArgs {
   int32_t n_j, G;                      // records that cover J; query heads per KV head
   const int32_t* ctx_len;              // dense records: the number of sink / recent records follows from it
   int32_t n_sink, recent;
+  float alpha;                         // power-mean exponent of the evidence (Eq. selector_mu)
 };
 
 struct SelArgs {
@@ -126,6 +127,7 @@ struct SelArgs {
   double* segstat;
   float gamma, beta, p, eta, lambda_clip, alpha_soft, alpha_cross, inv_temp, eps;
   int32_t nms_radius;
+  float alpha, inv_alpha;  // power-mean exponent of the evidence and its reciprocal
 };
 
 hipError_t launch_attn_dense(const AttnArgs& a, int B, int n_slots, hipStream_t s);

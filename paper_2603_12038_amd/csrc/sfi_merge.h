@@ -14,9 +14,10 @@ static_assert(kSlotCap <= kMergeThreads, "one record header per thread");
 // and in flight together.
 // If jstat != nullptr the first n_j records are the ones that cover the allowed set J (dense kernel):
 // their merge gives the J-only softmax statistics of this head for the Selector (Eq. selector_pt),
-// stored as jstat[bg] = { M = max of y over J, 1 / (G * sum over J of 2^(y - M)) }.
+// stored as jstat[bg] = { M = max of y over J, Z^(-alpha) / G } with Z = sum over J of 2^(y - M): the
+// head's term of Eq. selector_mu is then p^alpha / G = (Z^(-alpha) / G) * 2^(alpha (y - M)).
 __device__ __forceinline__ void merge_records(const float* part, float* out, int bg, int n_slots, float2* jstat,
-                                              int n_j, int G) {
+                                              int n_j, int G, float alpha) {
   const float* P = part + (int64_t)bg * kSlotCap * kPartStride;
   const int tid = threadIdx.x;
   const int sl = tid >> 5, c = tid & 31;
@@ -58,7 +59,11 @@ __device__ __forceinline__ void merge_records(const float* part, float* out, int
     for (int d = 32; d >= 1; d >>= 1) zj += __shfl_xor(zj, d);
     if ((tid & 63) == 0) s_jz[tid >> 6] = zj;
     __syncthreads();
-    if (tid == 0) jstat[bg] = make_float2(MJ, 1.0f / ((float)G * (s_jz[0] + s_jz[1] + s_jz[2] + s_jz[3])));
+    if (tid == 0) {
+      const float Z = s_jz[0] + s_jz[1] + s_jz[2] + s_jz[3];
+      const float zpow = alpha == 1.0f ? Z : __builtin_amdgcn_exp2f(alpha * __builtin_amdgcn_logf(Z));
+      jstat[bg] = make_float2(MJ, 1.0f / ((float)G * zpow));
+    }
   }
   __syncthreads();
   M = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));

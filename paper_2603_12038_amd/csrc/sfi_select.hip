@@ -112,6 +112,7 @@ __global__ __launch_bounds__(kSelThreads) void sel_score_kernel(const SelArgs a)
   }
   // J-only softmax statistics of the heads of this group, left by the merge kernel:
   // f(j) = sum_g c_g 2^(y_g(j) - M_g) with (M_g, c_g) = jstat[head g]
+  const float al = a.alpha;  // mu(j) = sum_g sc[g] 2^(alpha (y_g(j) - sM[g]))  (Eq. selector_mu)
   float sM[16], sc[16];
 #pragma unroll
   for (int g = 0; g < 16; ++g) {
@@ -129,10 +130,10 @@ __global__ __launch_bounds__(kSelThreads) void sel_score_kernel(const SelArgs a)
 #pragma unroll
       for (int g = 0; g < 8; ++g) {
         if (g < G) {
-          f0 += sc[g] * fast_exp2s(lq[r][g].x - sM[g]);
-          f1 += sc[g] * fast_exp2s(lq[r][g].y - sM[g]);
-          f2 += sc[g] * fast_exp2s(lq[r][g].z - sM[g]);
-          f3 += sc[g] * fast_exp2s(lq[r][g].w - sM[g]);
+          f0 += sc[g] * fast_exp2s(al * (lq[r][g].x - sM[g]));
+          f1 += sc[g] * fast_exp2s(al * (lq[r][g].y - sM[g]));
+          f2 += sc[g] * fast_exp2s(al * (lq[r][g].z - sM[g]));
+          f3 += sc[g] * fast_exp2s(al * (lq[r][g].w - sM[g]));
         }
       }
     } else {
@@ -141,10 +142,10 @@ __global__ __launch_bounds__(kSelThreads) void sel_score_kernel(const SelArgs a)
       for (int g = 0; g < 16; ++g) {
         if (g < G) {
           const float4 l4 = *reinterpret_cast<const float4*>(lt + g * kTile);
-          f0 += sc[g] * fast_exp2s(l4.x - sM[g]);
-          f1 += sc[g] * fast_exp2s(l4.y - sM[g]);
-          f2 += sc[g] * fast_exp2s(l4.z - sM[g]);
-          f3 += sc[g] * fast_exp2s(l4.w - sM[g]);
+          f0 += sc[g] * fast_exp2s(al * (l4.x - sM[g]));
+          f1 += sc[g] * fast_exp2s(al * (l4.y - sM[g]));
+          f2 += sc[g] * fast_exp2s(al * (l4.z - sM[g]));
+          f3 += sc[g] * fast_exp2s(al * (l4.w - sM[g]));
         }
       }
     }
@@ -194,6 +195,7 @@ __global__ __launch_bounds__(kSelThreads) void sel_prior_kernel(const SelArgs a)
   const float* lg = a.logits + (int64_t)bh * rows * a.ld_pos;  // [tile][G heads + key norms][32]
   float* fbuf = reinterpret_cast<float*>(a.keys) + (int64_t)bh * a.ld_pos;
   float* prior = a.prior + (int64_t)bh * a.ld_pos;
+  const float al = a.alpha;  // mu(j) = sum_g sc[g] 2^(alpha (y_g(j) - sM[g]))  (Eq. selector_mu)
   float sM[16], sc[16];
 #pragma unroll
   for (int g = 0; g < 16; ++g) {
@@ -217,11 +219,15 @@ __global__ __launch_bounds__(kSelThreads) void sel_prior_kernel(const SelArgs a)
     for (int g = 0; g < 16; ++g) {
       if (g < G) {
         const float4 l4 = *reinterpret_cast<const float4*>(lt + g * kTile);
-        f[0] += sc[g] * fast_exp2s(l4.x - sM[g]);
-        f[1] += sc[g] * fast_exp2s(l4.y - sM[g]);
-        f[2] += sc[g] * fast_exp2s(l4.z - sM[g]);
-        f[3] += sc[g] * fast_exp2s(l4.w - sM[g]);
+        f[0] += sc[g] * fast_exp2s(al * (l4.x - sM[g]));
+        f[1] += sc[g] * fast_exp2s(al * (l4.y - sM[g]));
+        f[2] += sc[g] * fast_exp2s(al * (l4.z - sM[g]));
+        f[3] += sc[g] * fast_exp2s(al * (l4.w - sM[g]));
       }
+    }
+    if (al != 1.0f) {  // f = mu^(1/alpha) up to the normalisation done with the segment sums (Eq. selector_f)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) f[c] = fast_exp2s(a.inv_alpha * fast_log2s(f[c]));
     }
     const float4 k4 = *reinterpret_cast<const float4*>(lt + G * kTile);
     const float k2[4] = {k4.x, k4.y, k4.z, k4.w};

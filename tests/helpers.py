@@ -78,14 +78,14 @@ def check_selection(sel, nsel, sel_ref, nsel_ref, z, ctx_len, n_sink, recent, bu
 class Runner:
     """Device copies of one workload's K/V plus an sfi context; thin wrappers over the C-ABI calls."""
 
-    def __init__(self, w, max_budget=None, selector=None):
+    def __init__(self, w, max_budget=None, selector=None, alpha=0.0):
         import torch
         import paper_2603_12038_amd as sfi
         self.sfi, self.torch, self.w = sfi, torch, w
         self.K, self.V = to_dev(w.K), to_dev(w.V)
         self.max_ctx = int(w.L_alloc)
         self.ctx = sfi.SfiContext(w.B, w.Hq, w.Hkv, self.max_ctx, w.budget if max_budget is None else max_budget,
-                                  w.n_sink, w.recent, self.K, self.V, selector=selector)
+                                  w.n_sink, w.recent, self.K, self.V, selector=selector, alpha=alpha)
         self.out = torch.zeros(w.B, w.Hq, w.d, dtype=torch.float32, device="cuda")
 
     def dense(self, q_bits, ctx_len, max_len=0):

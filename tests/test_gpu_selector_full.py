@@ -31,7 +31,7 @@ def _params(**kw):
 
 
 def _run(oracle, w, sp, d, ctx=None, budget=None, band=FULL_BAND):
-    r = Runner(w, selector=d)
+    r = Runner(w, selector=d, alpha=sp.alpha)
     try:
         q = w.q(0)
         ctx = w.ctx_len(0) if ctx is None else np.asarray(ctx, np.int32)
@@ -105,3 +105,32 @@ def test_full_selector_at_llama8b_size(oracle):
     n_exact, _, _ = _run(oracle, w, sp, d)
     _step(f"  index sets identical to the oracle's: {n_exact}/{w.B * w.Hkv}")
     assert n_exact >= (w.B * w.Hkv) // 2
+
+
+@pytest.mark.parametrize("alpha", [0.5, 0.25, 0.9])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_power_mean_evidence(oracle, mode, alpha):
+    """Eq. selector_mu with alpha < 1 (the G heads of a KV head are the window), in both Selector modes."""
+    sp, d = _params(alpha=alpha)
+    if mode == 0:
+        sp, d = dataclasses.replace(sp, mode=0), None
+    w = syn.make_tiny(L0=3900, steps=1, budget=128, recent=48, n_support=24, B=2, Hq=8, Hkv=2)
+    _step(f"power mean alpha={alpha} mode={mode}")
+    _run(oracle, w, sp, d)
+
+
+def test_power_mean_single_head_is_alpha_free(oracle):
+    """G = 1: f = p_1 whatever alpha is (Eq. selector_f), so the selection equals the alpha = 1 one."""
+    w = syn.make_tiny(L0=2100, steps=1, budget=64, recent=32, n_support=12, B=1, Hq=2, Hkv=2)
+    _step("power mean with G = 1")
+    sels = []
+    for alpha in (1.0, 0.4):
+        r = Runner(w, alpha=alpha)
+        try:
+            _, sel, _ = r.slow(w.q(0), w.ctx_len(0), w.budget)
+            sels.append(sel)
+        finally:
+            r.close()
+    sel_ref, nsel_ref, z = oracle.selector(w.q(0), w.K, w.ctx_len(0), w.budget, w.n_sink, w.recent,
+                                           sp=SelectorParams(alpha=0.4))
+    assert (sels[0] == sels[1]).all() and (sels[1] == sel_ref).all()
