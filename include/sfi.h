@@ -200,6 +200,21 @@ int sfi_mixed_step(sfi_ctx* ctx, const void* q, const void* K, const void* V, co
                    const int32_t* ctx_len, const int32_t* recent_start, int32_t max_len, int32_t budget,
                    float* out, int32_t* sel_idx, int32_t* n_sel, void* stream);
 
+/*
+ * Trigger policy on the device (paper Sec. "Training-free trigger policy", Eq. trigger, and the last lines
+ * of Algorithm 1), so that a decode loop needs no host decision between steps:
+ *   is_slow[b]    = 1 if last_token[b] is in the trigger set, or since_slow[b] >= t_max; else 0
+ *   since_slow[b] = 0 if is_slow[b], else since_slow[b] + 1
+ * i.e. the step after a trigger token is slow, and so is the step after t_max fast steps in a row.
+ * last_token: device int32 [B], the token generated by the previous step; ids outside [0, vocab_size)
+ * never trigger.  trigger_bitmap: device uint32 [(vocab_size + 31) / 32], bit (id % 32) of word id / 32 set
+ * iff id is in the trigger set (built once, offline, from the tokenizer).  since_slow: device int32 [B],
+ * read and updated; initialise it to t_max to make the first step slow (Algorithm 1: g_0 = 1).
+ * is_slow: device uint8 [B], written; the flags sfi_mixed_step and sfi_reorg take.
+ */
+int sfi_trigger(sfi_ctx* ctx, const int32_t* last_token, const uint32_t* trigger_bitmap, int32_t vocab_size,
+                int32_t t_max, int32_t* since_slow, uint8_t* is_slow, void* stream);
+
 /* State update between decode steps, on the device (paper Algorithm 1, "update I_recent"):
  * ctx_len[b] += 1;  recent_start[b] = max(n_sink, ctx_len[b] - recent). */
 int sfi_advance(sfi_ctx* ctx, int32_t* ctx_len, int32_t* recent_start, void* stream);

@@ -20,6 +20,10 @@
  *   sfio_reorg     cache reorganisation Reorg_i: the sink rows and the selected rows
  *                  copied into a contiguous compact buffer (Sec. 4.1 dependency
  *                  structure and Sec. 4.2 two-segment KV layout).
+ *   sfio_trigger_schedule
+ *                  the slow/fast indicator g_t of one request (Sec. 3.1 "Training-free
+ *                  trigger policy", Eq. trigger, with the forced refresh after T_max fast
+ *                  steps; Algorithm 1: g_0 = 1).
  *   sfio_selector_from_logits / sfio_selector
  *                  Algorithm 2 step by step: allowed set J (Eq. allowed_set),
  *                  evidence p, mu, f (Eqs. selector_pt, selector_mu, selector_f),
@@ -408,6 +412,26 @@ int sfio_reorg(const sfio_cfg* c, const uint16_t* K, const uint16_t* V, const in
         memcpy(vc + (c->n_sink + i) * c->d, v_row(c, V, b, h, j), sizeof(uint16_t) * (size_t)c->d);
       }
     }
+  return 0;
+}
+
+/* g[t] for t = 0 .. n_steps-1.  x[t] is the token generated at step t; trig[0..n_trig) the trigger ids.
+ * g[0] = 1; for t >= 1: g[t] = 1 if x[t-1] is a trigger token, or if the T_max steps before t were all fast. */
+int sfio_trigger_schedule(const int32_t* x, int32_t n_steps, const int32_t* trig, int32_t n_trig, int32_t t_max,
+                          uint8_t* g) {
+  int32_t fast_run = 0; /* fast steps since the last slow step */
+  for (int32_t t = 0; t < n_steps; ++t) {
+    int slow = 0;
+    if (t == 0) {
+      slow = 1;
+    } else {
+      for (int32_t i = 0; i < n_trig; ++i)
+        if (trig[i] == x[t - 1]) slow = 1;
+      if (fast_run >= t_max) slow = 1;
+    }
+    g[t] = (uint8_t)slow;
+    fast_run = slow ? 0 : fast_run + 1;
+  }
   return 0;
 }
 

@@ -150,6 +150,15 @@ def reorg(K, V, sel_idx, n_sel, ctx_len, n_sink: int, Kc: np.ndarray, Vc: np.nda
         raise ValueError("selected index outside [0, ctx_len) or compact buffer too small")
 
 
+def trigger_schedule(tokens, trigger_ids, t_max: int) -> np.ndarray:
+    """g_t of one request: uint8 [len(tokens)]; tokens[t] is the token generated at step t."""
+    x = _i32(tokens)
+    trig = _i32(sorted(set(int(i) for i in trigger_ids)))
+    g = np.zeros(x.shape[0], dtype=np.uint8)
+    lib().sfio_trigger_schedule(_p(x), C.c_int32(x.shape[0]), _p(trig), C.c_int32(trig.shape[0]), C.c_int32(t_max), _p(g))
+    return g
+
+
 def selector_from_logits(lg: np.ndarray, ctx_len, Hkv: int, budget: int, n_sink: int, recent: int,
                          sp: Optional[SelectorParams] = None, knorm: Optional[np.ndarray] = None,
                          debug: bool = False):

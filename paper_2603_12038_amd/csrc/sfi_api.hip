@@ -546,6 +546,17 @@ int sfi_mixed_step(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   return run_selector(x, sa, ml, st);
 }
 
+int sfi_trigger(sfi_ctx* x, const int32_t* last_token, const uint32_t* trigger_bitmap, int32_t vocab_size,
+                int32_t t_max, int32_t* since_slow, uint8_t* is_slow, void* stream) {
+  if (x == nullptr || last_token == nullptr || trigger_bitmap == nullptr || since_slow == nullptr || is_slow == nullptr)
+    return SFI_EINVAL;
+  if (vocab_size < 1 || t_max < 0) return SFI_EINVAL;
+  if (misaligned(last_token, 4) || misaligned(trigger_bitmap, 4) || misaligned(since_slow, 4)) return SFI_EALIGN;
+  SFI_TRY(launch_trigger(last_token, trigger_bitmap, vocab_size, t_max, since_slow, is_slow, x->cfg.batch,
+                         (hipStream_t)stream));
+  return SFI_OK;
+}
+
 int sfi_advance(sfi_ctx* x, int32_t* ctx_len, int32_t* recent_start, void* stream) {
   if (x == nullptr || ctx_len == nullptr || recent_start == nullptr) return SFI_EINVAL;
   SFI_TRY(launch_advance(ctx_len, recent_start, x->cfg.batch, x->cfg.n_sink, x->cfg.recent, (hipStream_t)stream));

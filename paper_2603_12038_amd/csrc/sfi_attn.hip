@@ -813,6 +813,26 @@ __global__ void advance_kernel(int32_t* ctx_len, int32_t* recent_start, int B, i
   }
 }
 
+__global__ void trigger_kernel(const int32_t* last_token, const uint32_t* bitmap, int vocab, int t_max, int32_t* since_slow,
+                               uint8_t* is_slow, int B) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b < B) {
+    const int tok = last_token[b];
+    const int c = since_slow[b];
+    const bool hit = tok >= 0 && tok < vocab && ((bitmap[tok >> 5] >> (tok & 31)) & 1u) != 0u;
+    const bool slow = hit || c >= t_max;
+    is_slow[b] = slow ? 1 : 0;
+    since_slow[b] = slow ? 0 : c + 1;
+  }
+}
+
+hipError_t launch_trigger(const int32_t* last_token, const uint32_t* bitmap, int vocab, int t_max, int32_t* since_slow,
+                          uint8_t* is_slow, int B, hipStream_t s) {
+  hipLaunchKernelGGL(trigger_kernel, dim3((B + 63) / 64), dim3(64), 0, s, last_token, bitmap, vocab, t_max, since_slow,
+                     is_slow, B);
+  return hipGetLastError();
+}
+
 hipError_t launch_attn_dense(const AttnArgs& a, int B, int n_slots, hipStream_t s) {
   if (a.logits != nullptr && a.with_knorm)
     hipLaunchKernelGGL(attn_dense_kernel<2>, dim3(n_slots, a.Hkv, B), dim3(kAttnThreads), 0, s, a);

@@ -140,6 +140,8 @@ hipError_t launch_sel_full(const SelArgs& a, int B, int n_seg, hipStream_t s);
 hipError_t launch_sel_cand(const SelArgs& a, int B, int n_seg, hipStream_t s);
 hipError_t launch_sel_count(const SelArgs& a, int B, int n_seg, hipStream_t s);
 hipError_t launch_sel_write(const SelArgs& a, int B, int n_seg, hipStream_t s);
+hipError_t launch_trigger(const int32_t* last_token, const uint32_t* bitmap, int vocab, int t_max, int32_t* since_slow,
+                          uint8_t* is_slow, int B, hipStream_t s);
 hipError_t launch_advance(int32_t* ctx_len, int32_t* recent_start, int B, int n_sink, int recent, hipStream_t s);
 
 }  // namespace sfi

@@ -469,3 +469,31 @@ def test_fast_step_pipelined_gather(oracle, tiny, tpw):
             check_out(got, oracle.sparse(q, w.K, w.V, sel2, nsel2, rs, ctx, w.n_sink))
     finally:
         r.sfi.sfi_set_tuning(r.ctx.handle, 0, 1)
+
+
+def test_trigger_policy_on_device(oracle, tiny):
+    """sfi_trigger step by step against the oracle's schedule, one request per batch row (different
+    token streams), tokens outside the vocabulary included."""
+    import torch
+
+    w, r = tiny
+    _step("trigger policy")
+    vocab, t_max, n = 1000, 9, 120
+    trig = [3, 64, 65, 999]
+    bitmap = np.zeros((vocab + 31) // 32, np.uint32)
+    for i in trig:
+        bitmap[i >> 5] |= np.uint32(1 << (i & 31))
+    rng = syn.rng_for(11, 555)
+    toks = rng.integers(-2, vocab + 40, size=(n, w.B)).astype(np.int32)
+    toks[rng.random((n, w.B)) < 0.08] = 64
+    ref = np.stack([oracle.trigger_schedule(toks[:, b], trig, t_max) for b in range(w.B)], axis=1)
+    bm_d = torch.from_numpy(bitmap.view(np.int32)).cuda()
+    since = torch.full((w.B,), t_max, dtype=torch.int32, device="cuda")
+    flag = torch.zeros(w.B, dtype=torch.uint8, device="cuda")
+    got = np.zeros((n, w.B), np.uint8)
+    last = torch.zeros(w.B, dtype=torch.int32, device="cuda")  # step 0 is slow through since_slow = t_max
+    for t in range(n):
+        r.sfi.sfi_trigger(r.ctx.handle, last, bm_d, vocab, t_max, since, flag)
+        got[t] = flag.cpu().numpy()
+        last = torch.from_numpy(toks[t]).cuda()
+    assert (got == ref).all()
