@@ -43,9 +43,24 @@ def test_workspace_bytes_and_config_validation():
     assert bigger > sfi.sfi_workspace_bytes(good_cfg())
     for bad in (dict(batch=0), dict(n_kv_heads=0), dict(n_q_heads=7), dict(head_dim=64), dict(max_ctx=0),
                 dict(max_budget=-1), dict(n_sink=-1), dict(recent=-1), dict(k_stride_t=100), dict(v_stride_h=12),
-                dict(selector_mode=1), dict(n_q_heads=64, n_kv_heads=2), dict(scale=-1.0),
-                dict(max_ctx=1 << 24, k_stride_t=128 * 8)):
+                dict(selector_mode=2), dict(n_q_heads=64, n_kv_heads=2), dict(scale=-1.0), dict(alpha=1.5),
+                dict(alpha=-0.1), dict(max_ctx=1 << 24, k_stride_t=128 * 8)):
         assert sfi.sfi_workspace_bytes(good_cfg(**bad)) == 0, bad
+    assert sfi.sfi_workspace_bytes(good_cfg(alpha=0.5)) == sfi.sfi_workspace_bytes(good_cfg())
+
+
+FULL = dict(selector_mode=1, gamma=0.5, beta=1.0, p=2.0, eta=0.5, lambda_clip=0.02, alpha_soft=0.5, alpha_cross=0.35,
+            temp=1.0, eps=1e-8, nms_radius=2)
+
+
+def test_full_selector_config_validation():
+    """Mode 1 needs its hyper-parameters in range; its workspace is larger (prior, Soft-NMS scores, key norms)."""
+    assert sfi.sfi_workspace_bytes(good_cfg(**FULL)) > sfi.sfi_workspace_bytes(good_cfg())
+    for bad in (dict(temp=0.0), dict(gamma=-1.0), dict(p=0.5), dict(eta=-0.1), dict(lambda_clip=1.5), dict(lambda_clip=-0.1),
+                dict(alpha_soft=-1.0), dict(alpha_cross=-1.0), dict(nms_radius=-1), dict(nms_radius=65), dict(eps=-1e-8),
+                dict(eps=2.0), dict(alpha_soft=3.0, alpha_cross=1.0)):
+        assert sfi.sfi_workspace_bytes(good_cfg(**{**FULL, **bad})) == 0, bad
+    assert sfi.sfi_workspace_bytes(good_cfg(**{**FULL, "eps": 0.0})) > 0  # 0 selects 1e-8
 
 
 def test_create_rejects_bad_arguments_without_touching_a_device():
@@ -101,6 +116,30 @@ def test_hot_calls_reject_bad_arguments_before_any_launch():
         assert lib.sfi_fast_step(h, p, p, p, p, p, cfg.max_budget + 1, p, p, p, None) == EINVAL
         assert lib.sfi_fast_step(h, p, p, p, p, p, 64, p + 1, p, p, None) == EALIGN
         assert lib.sfi_mixed_step(h, p, p, p, None, p, p, 0, 64, p, p, p, None) == EINVAL
+        assert lib.sfi_slow_attn(h, p, p, p, None, 0, p, None) == EINVAL
+        assert lib.sfi_slow_attn(h, p, p, p, p, -1, p, None) == EINVAL
+        assert lib.sfi_slow_select(h, p, 0, 64, None, p, None) == EINVAL
+        assert lib.sfi_slow_select(h, p, 0, cfg.max_budget + 1, p, p, None) == EINVAL
+        assert lib.sfi_slow_select(h, p + 2, 0, 64, p, p, None) == EALIGN
+        # compact buffers: c_rows >= n_sink + sel_stride, strides cover the rows, 16-byte aligned bases
+        rows = cfg.n_sink + 64
+        sb, sh = 2 * rows * 128, rows * 128
+        i64 = C.c_int64
+        assert lib.sfi_reorg(h, p, p, p, p, 64, p, None, None, p, i64(sb), i64(sh), rows, None) == EINVAL
+        assert lib.sfi_reorg(h, p, p, p, p, 64, p, None, p, p, i64(sb), i64(sh), rows - 1, None) == EINVAL
+        assert lib.sfi_reorg(h, p, p, p, p, 64, p, None, p, p, i64(sb), i64(sh - 8), rows, None) == EINVAL
+        assert lib.sfi_reorg(h, p, p, p, p, 64, p, None, p, p, i64(sh), i64(sh), rows, None) == EINVAL
+        assert lib.sfi_reorg(h, p, p, p, p, cfg.max_budget + 1, p, None, p, p, i64(8 * sb), i64(4 * sh), 4 * rows, None) == EINVAL
+        assert lib.sfi_reorg(h, p, p, p, p, 64, p, None, p + 8, p, i64(sb), i64(sh), rows, None) == EALIGN
+        assert lib.sfi_reorg(h, p, p, None, p, 64, p, None, p, p, i64(sb), i64(sh), rows, None) == EINVAL
+        assert lib.sfi_fast_step_compact(h, p, p, p, i64(sb), i64(sh), rows - 1, p, 64, p, p, p, p, p, None) == EINVAL
+        assert lib.sfi_fast_step_compact(h, p, None, p, i64(sb), i64(sh), rows, p, 64, p, p, p, p, p, None) == EINVAL
+        assert lib.sfi_fast_step_compact(h, p, p, p, i64(sb), i64(sh), rows, None, 64, p, p, p, p, p, None) == EINVAL
+        assert lib.sfi_fast_step_compact(h, p, p, p, i64(4 * sb), i64(sh + 4), rows, p, 64, p, p, p, p, p, None) == EALIGN
+        assert lib.sfi_trigger(h, None, p, 100, 8, p, p, None) == EINVAL
+        assert lib.sfi_trigger(h, p, p, 0, 8, p, p, None) == EINVAL
+        assert lib.sfi_trigger(h, p, p, 100, -1, p, p, None) == EINVAL
+        assert lib.sfi_trigger(h, p, p + 2, 100, 8, p, p, None) == EALIGN
         assert lib.sfi_advance(h, None, p, None) == EINVAL
         assert lib.sfi_stage_times(h, None, None) == EINVAL
         assert lib.sfi_set_profiling(h, -1) == EINVAL
