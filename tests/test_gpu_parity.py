@@ -497,3 +497,30 @@ def test_trigger_policy_on_device(oracle, tiny):
         got[t] = flag.cpu().numpy()
         last = torch.from_numpy(toks[t]).cuda()
     assert (got == ref).all()
+
+
+@pytest.mark.parametrize("recent,n_sink,splits", [(1500, 4, 1), (1500, 70, 0), (700, 33, 1), (2900, 4, 0)])
+def test_long_recent_window_and_sink(oracle, recent, n_sink, splits):
+    """Sink + recent rows spanning many tiles (several such tiles per wave when the split is forced to one
+    workgroup per pair), a sink longer than a tile, and a recent window that leaves almost no J."""
+    w = syn.make_tiny(L0=3000, steps=2, budget=80, recent=recent, n_support=8, B=2, Hq=8, Hkv=2)
+    w.n_sink = n_sink
+    w.L0 = np.array([3000, 1777], np.int32)
+    r = Runner(w)
+    try:
+        _step(f"long recent window R={recent} sink={n_sink} splits={'forced 1' if splits else 'default'}")
+        if splits:
+            r.sfi.sfi_set_tuning(r.ctx.handle, 1, 1)
+        q, ctx = w.q(0), w.ctx_len(0)
+        out, sel, nsel = r.slow(q, ctx, w.budget)
+        check_out(out, oracle.dense(q, w.K, w.V, ctx))
+        sel_ref, nsel_ref, z = oracle.selector(q, w.K, ctx, w.budget, w.n_sink, w.recent)
+        check_selection(sel, nsel, sel_ref, nsel_ref, z, ctx, w.n_sink, w.recent, w.budget)
+        q1, ctx1, rs1 = w.q(1), w.ctx_len(1), w.recent_start(1)
+        got = r.fast(q1, sel, nsel, rs1, ctx1)
+        check_out(got, oracle.sparse(q1, w.K, w.V, sel, nsel, rs1, ctx1, w.n_sink))
+        Kc, Vc = r.reorg(sel, nsel, ctx)
+        got = r.fast_compact(q1, nsel, sel.shape[2], rs1, ctx1)
+        check_out(got, oracle.sparse(q1, w.K, w.V, sel, nsel, rs1, ctx1, w.n_sink))
+    finally:
+        r.close()
