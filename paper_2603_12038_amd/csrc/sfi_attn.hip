@@ -4,14 +4,17 @@
 // share it, logits l_g(j) = scale * <q_g, k_j> over a list of positions, and the flash-style
 // partial  (m, sum_j e^{l-m}, sum_j e^{l-m} v_j)  of a share of that list, in the log2 domain
 // (y = log2(e) * l, weights 2^(y - m)).
-//   dense  kernel (slow step): workgroups 0..n_split-1 cover the allowed set J = [n_sink, L - recent)
-//          and also expose y over J for the Selector (Eq. window_logits, W = 1); workgroup n_split
-//          covers the sink and recent rows, which the Selector never ranks (Eq. allowed_set).
-//          Keeping J apart means the J-only softmax normaliser of Eq. selector_pt is just the merge
-//          of the J records.  Every wave writes its own record: waves never wait for each other.
-//   gather kernel (fast step): the list is  sink ++ sel_idx[0:n_sel] ++ [recent_start, L)
+//   dense  kernel (slow step): the waves of n_split workgroups share the tiles of the allowed set
+//          J = [n_sink, L - recent), for which y is also exposed to the Selector (Eq. window_logits,
+//          W = 1), followed by the tiles of the sink and recent rows, which the Selector never ranks
+//          (Eq. allowed_set).  A wave keeps the two kinds in separate records, so the J-only softmax
+//          normaliser of Eq. selector_pt is just the merge of the J records.  Every wave writes its
+//          own records: waves never wait for each other.
+//   gather kernels (fast step): the list is  sink ++ sel_idx[0:n_sel] ++ [recent_start, L)
 //          (Eq. index_set_head), strided over n_split workgroups; the four waves of a workgroup
-//          are combined into one record (fewer records for the merge that follows).
+//          are combined into one record (fewer records for the merge that follows).  One tile per
+//          wave, or a pipelined walk over several for large launches.
+//   compact kernel (fast step, two-segment layout of Sec. 4.2) and the Reorg copy that feeds it.
 //
 // Mapping to the matrix cores.  A wave owns 32 positions per iteration, as two 16-row blocks.
 //   S^T = K_blk (16 rows x 128) . Q^T (128 x 16 heads, heads >= G are zero): 4 x mfma 16x16x32 bf16

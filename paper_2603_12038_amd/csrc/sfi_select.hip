@@ -1,13 +1,15 @@
-// Selector on the GPU (paper Algorithm 2, evidence-only ranking) for gfx950.
+// Selector on the GPU (paper Algorithm 2) for gfx950.
 //
 // Per (sequence b, KV head h), over the allowed set J (Eq. allowed_set), positions p = j - n_sink:
 //   p_g(j) = softmax over J of the logits of query head g          (Eq. selector_pt); the dense
 //            kernel left y = log2(e) * logit, so e^{l - M} is 2^{y - M_y}
-//   f(j)   = (1/G) sum_g p_g(j)      (Eqs. selector_mu, selector_f with alpha = 1; the G heads of
-//            the group are the observation window)
-//   z(j)   = log(f(j) + eps)  is monotone in f, so the Top-K of Eq. topk_out is taken on f itself.
-// Top-K is a radix select on the fp32 bit pattern of f (non-negative floats order like unsigned
-// integers): a 12-bit histogram over all of J, then an exact 19-bit refinement among the few
+//   mu(j)  = (1/G) sum_g p_g(j)^alpha, f = mu^(1/alpha) / sum      (Eqs. selector_mu, selector_f; the G
+//            heads of the group are the observation window; alpha = 1: f is the mean of the p_g)
+// Mode 0 ranks by f alone: z = log(f + eps) is monotone in mu, so the Top-K of Eq. topk_out is taken
+// on mu itself.  Mode 1 goes through the prior, the reverse-KL fusion with lambda*, Soft-NMS and the
+// cross-head exclusivity first (three kernels further down) and ranks by e^z_adj.
+// Top-K is a radix select on the fp32 bit pattern of the ranking value (positive floats order like
+// unsigned integers): a 12-bit histogram over all of J, then an exact 19-bit refinement among the few
 // keys of the threshold bin, then an index-ordered compaction that takes every key above the
 // threshold and the lowest-index keys equal to it.  Integer atomics only count, so the result
 // does not depend on scheduling.
