@@ -102,6 +102,8 @@ def bench_serving(args):
     max_ctx = int(w.L_alloc)
     ctx = sfi.SfiContext(B, Hq, Hkv, max_ctx, w.budget, w.n_sink, w.recent, Ks[0], Vs[0])
     h = ctx.handle
+    if args.dense_wgs or args.fast_tpw:
+        sfi.sfi_set_tuning(h, args.dense_wgs, args.fast_tpw)
     q_all = torch.randn(n_dec + SEG, NL, B, Hq, d, device=dev, generator=gen).to(torch.bfloat16)
     outs = [torch.zeros(B, Hq, d, dtype=torch.float32, device=dev) for _ in range(NL)]
     sels = [torch.full((B, Hkv, w.budget), -1, dtype=torch.int32, device=dev) for _ in range(NL)]

@@ -139,7 +139,8 @@ int fast_splits_for(const sfi_ctx* x, int sel_stride, int* pipelined) {
     s = one;
     *pipelined = 0;
   } else {
-    s = x->fast_target_wgs / pairs;
+    // at least one workgroup per compute unit from the pairs alone: one per pair, which then needs no merge
+    s = pairs >= x->n_cu ? 1 : x->fast_target_wgs / pairs;
     if (s > one) s = one;
     *pipelined = 1;
   }
@@ -432,7 +433,9 @@ int sfi_fast_step(sfi_ctx* x, const void* q, const void* K, const void* V, const
   a.sel_stride = sel_stride;
   a.n_split = fast_splits_for(x, sel_stride, &a.pipelined);
   x->last_fast_splits = a.n_split;
+  if (a.n_split == 1) a.out_direct = out;  // one workgroup per pair finishes the softmax itself
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_gather(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
+  if (a.n_split == 1) return SFI_OK;
   MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1, nullptr, 0, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
@@ -497,7 +500,9 @@ int sfi_fast_step_compact(sfi_ctx* x, const void* q, const void* Kc, const void*
   a.c_sb = c_stride_b; a.c_sh = c_stride_h; a.c_rows = c_rows;
   a.n_split = compact_splits_for(x, sel_stride);
   x->last_fast_splits = a.n_split;
+  if (a.n_split == 1) a.out_direct = out;
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_compact(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
+  if (a.n_split == 1) return SFI_OK;
   MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1, nullptr, 0, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
@@ -534,12 +539,13 @@ int sfi_mixed_step(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   f.n_sel = n_sel;
   f.sel_stride = budget;
   f.n_split = fast_splits_for(x, budget, &f.pipelined);
+  if (f.n_split == 1) f.out_direct = out;
   x->last_fast_splits = f.n_split;
   // the gather part reads last segment's sel rows of fast sequences; the Selector below only
   // rewrites rows of slow sequences, so the order of the two attention launches is free.
   { StageTimer t(x, st, SFI_STAGE_ATTN2); SFI_TRY(launch_attn_gather(f, x->cfg.batch, f.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(d, x->cfg.batch, d.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
-  MergeArgs m{x->ws.part, out, is_slow, x->cfg.n_q_heads, d.n_split * kWaves, f.n_split, 2, x->ws.jstat, d.n_split * kWaves, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha};
+  MergeArgs m{x->ws.part, out, is_slow, x->cfg.n_q_heads, d.n_split * kWaves, f.n_split == 1 ? 0 : f.n_split, 2, x->ws.jstat, d.n_split * kWaves, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   SelArgs sa;
   fill_sel(x, &sa, ctx_len, is_slow, budget, d.n_split, sel_idx, n_sel);

@@ -471,8 +471,10 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_dense_kernel(const AttnA
 
 // The four waves of a workgroup fold their running states into one record (b, head, slot):
 // { max of y, sum 2^(y - max), -, -, O[128] }.  l_run must already be summed over the row groups.
+// With out != nullptr the workgroup is the only one of its (b, h) pair: it writes the normalised
+// attention output O / l straight to out[b, head, :] and no record (no merge kernel follows).
 __device__ __forceinline__ void write_wg_record(float* part, int64_t head0, int G, int slot, const f32x4 (&acc)[8],
-                                                float m_run, float l_run) {
+                                                float m_run, float l_run, float* out) {
   const int tid = threadIdx.x;
   const int lane = tid & 63, w = tid >> 6;
   const int jg = lane >> 4, n = lane & 15;
@@ -498,6 +500,22 @@ __device__ __forceinline__ void write_wg_record(float* part, int64_t head0, int 
     }
   }
   __syncthreads();
+  if (out != nullptr) {  // block-uniform
+    for (int idx = tid; idx < G * kHeadDim; idx += kAttnThreads) {
+      const int hh = idx >> 7, dim = idx & 127;
+      float M = s_m[0][hh];
+#pragma unroll
+      for (int ww = 1; ww < kWaves; ++ww) M = fmaxf(M, s_m[ww][hh]);
+      float ls = 0.f, sum = 0.f;
+#pragma unroll
+      for (int ww = 0; ww < kWaves; ++ww) {
+        ls += s_l[ww][hh] * fast_exp2(s_m[ww][hh] - M);
+        sum += s_red[ww][hh][dim];
+      }
+      out[(head0 + hh) * kHeadDim + dim] = ls > 0.f ? sum / ls : 0.f;
+    }
+    return;
+  }
   const int64_t rec0 = (head0 * kSlotCap + slot) * kPartStride;
   for (int idx = tid; idx < G * kHeadDim; idx += kAttnThreads) {
     const int hh = idx >> 7, dim = idx & 127;
@@ -577,7 +595,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_kernel(const Attn
   }
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
-  write_wg_record(a.part, head0, G, slot, acc, m_run, l_run);
+  write_wg_record(a.part, head0, G, slot, acc, m_run, l_run, a.out_direct);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -664,7 +682,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(con
   }
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
-  write_wg_record(a.part, head0, G, slot, acc, m_run, l_run);
+  write_wg_record(a.part, head0, G, slot, acc, m_run, l_run, a.out_direct);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -734,7 +752,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_compact_kernel(const Att
   }
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
-  write_wg_record(a.part, head0, G, slot, acc, m_run, l_run);
+  write_wg_record(a.part, head0, G, slot, acc, m_run, l_run, a.out_direct);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -792,6 +810,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(const MergeArgs a)
   const int bg = blockIdx.x;
   const int b = bg / a.Hq;
   int n_slots;
+  if (a.mode == 2 && a.slots_fast == 0 && a.is_slow[b] == 0) return;  // fast sequences wrote their output themselves
   if (a.mode == 0) n_slots = a.slots_slow;
   else if (a.mode == 1) n_slots = a.slots_fast;
   else n_slots = a.is_slow[b] ? a.slots_slow : a.slots_fast;

@@ -63,6 +63,7 @@ struct AttnArgs {
   float* logits;                 // dense mode, nullptr: do not expose logits
   int32_t with_knorm;            // dense mode: also expose the squared key norms (full Selector)
   int32_t pipelined;             // gather mode: few workgroups per (b, h), each wave walks several tiles
+  float* out_direct;             // gather / compact mode with n_split == 1: write the output here, no record
   uint32_t* hist1;               // dense mode with Selector: cleared by the sink/recent workgroup
   uint32_t* state;
   int64_t ld_pos;
