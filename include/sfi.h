@@ -93,6 +93,13 @@ typedef struct sfi_config {
   /* Both modes: power-mean exponent of Eq. selector_mu over the G query heads of a KV head, in (0, 1];
    * 0 selects 1 (f = the arithmetic mean of the heads' softmaxes over J). */
   float alpha;
+  /* Paged cache: 0 = K and V are flat strided tensors (above); a power of two in [16, 65536] = K and V are
+   * pools of blocks of page_size consecutive rows, row r of block p of KV head h at element offset
+   * (p * page_size + r) * k_stride_t + h * k_stride_h from the pool base (so k_stride_t is the row stride
+   * inside and across blocks, e.g. Hkv * 128 for a [blocks][page_size][Hkv][128] pool); k_stride_b and
+   * v_stride_b must be 0.  Sequences find their blocks through the block table set with
+   * sfi_set_block_table.  max_ctx still bounds every ctx_len[b]. */
+  int32_t page_size;
 } sfi_config;
 
 typedef struct sfi_ctx sfi_ctx; /* opaque; host memory owned by the library */
@@ -104,6 +111,19 @@ size_t sfi_workspace_bytes(const sfi_config* cfg);
 /* Validate cfg, bind the caller's workspace, return a context in *out.
  * Touches the device only to read its properties and, later, to launch. */
 int sfi_create(const sfi_config* cfg, void* workspace, size_t workspace_bytes, sfi_ctx** out);
+
+/*
+ * Paged cache (cfg.page_size > 0; paper Sec. 4.2: recent tokens "remain in paged KV", and the packed
+ * per-step descriptor carries block-table pointers): block_table is a DEVICE int32 array
+ * [batch][table_stride]; entry [b][i] is the block of the pools that holds rows
+ * [i * page_size, (i + 1) * page_size) of sequence b.  Entries that cover rows [0, ctx_len[b]) must be valid
+ * at every hot call (later ones are never read); block ids lie in [0, n_blocks), and
+ * n_blocks * page_size * row stride must stay below 4 GiB for K and for V (32-bit row offsets inside the
+ * kernels).  The pointer is kept until the next call of this function; the table's contents may change
+ * between hot calls.  With a paged cache the K and V arguments of the hot calls are the pool bases and the
+ * kernels never read rows before ctx_len[b] is known.  Passing NULL detaches the table.
+ */
+int sfi_set_block_table(sfi_ctx* ctx, const int32_t* block_table, int32_t table_stride, int32_t n_blocks);
 
 /* Frees the host-side context (and its profiling events).  The workspace stays the caller's. */
 int sfi_destroy(sfi_ctx* ctx);

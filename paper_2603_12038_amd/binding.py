@@ -33,12 +33,13 @@ class SfiConfig(C.Structure):
         ("gamma", C.c_float), ("beta", C.c_float), ("p", C.c_float), ("eta", C.c_float),
         ("lambda_clip", C.c_float), ("alpha_soft", C.c_float), ("alpha_cross", C.c_float), ("temp", C.c_float),
         ("eps", C.c_float), ("nms_radius", C.c_int32), ("alpha", C.c_float),
+        ("page_size", C.c_int32),
     ]
 
 
 _lib: Optional[C.CDLL] = None
 
-EXPORTS = ("sfi_workspace_bytes", "sfi_create", "sfi_destroy", "sfi_strerror", "sfi_slow_step", "sfi_slow_attn",
+EXPORTS = ("sfi_workspace_bytes", "sfi_create", "sfi_set_block_table", "sfi_destroy", "sfi_strerror", "sfi_slow_step", "sfi_slow_attn",
            "sfi_slow_select", "sfi_dense_attn",
            "sfi_fast_step", "sfi_reorg", "sfi_fast_step_compact", "sfi_mixed_step", "sfi_trigger", "sfi_advance", "sfi_set_profiling", "sfi_stage_times",
            "sfi_set_tuning", "sfi_query_splits")
@@ -57,6 +58,8 @@ def load_library() -> C.CDLL:
     lib.sfi_workspace_bytes.argtypes = [C.POINTER(SfiConfig)]
     lib.sfi_create.restype = C.c_int
     lib.sfi_create.argtypes = [C.POINTER(SfiConfig), vp, C.c_size_t, C.POINTER(vp)]
+    lib.sfi_set_block_table.restype = C.c_int
+    lib.sfi_set_block_table.argtypes = [vp, vp, i32, i32]
     lib.sfi_destroy.restype = C.c_int
     lib.sfi_destroy.argtypes = [vp]
     lib.sfi_strerror.restype = C.c_char_p
@@ -128,6 +131,12 @@ def sfi_create(cfg: SfiConfig, workspace, workspace_bytes: int) -> int:
     h = C.c_void_p()
     _check(load_library().sfi_create(C.byref(cfg), _ptr(workspace), workspace_bytes, C.byref(h)), "sfi_create")
     return h.value
+
+
+def sfi_set_block_table(ctx, block_table, n_blocks: int) -> None:
+    """block_table: int32 device tensor [B, pages per sequence] (or None to detach)."""
+    stride = 0 if block_table is None else block_table.stride(0)
+    _check(load_library().sfi_set_block_table(ctx, _ptr(block_table), stride, n_blocks), "sfi_set_block_table")
 
 
 def sfi_destroy(ctx: int) -> None:
@@ -218,7 +227,7 @@ class SfiContext:
     """Owns the workspace tensor and the context handle for one (shape, K/V layout)."""
 
     def __init__(self, B, Hq, Hkv, max_ctx, max_budget, n_sink, recent, K, V, scale: float = 0.0, device="cuda",
-                 selector: Optional[dict] = None, alpha: float = 0.0):
+                 selector: Optional[dict] = None, alpha: float = 0.0, page_size: int = 0):
         """selector: None for mode 0, or the mode-1 hyper-parameters as a dict with the keys gamma, beta, p,
         eta, lambda_clip, alpha_soft, alpha_cross, temp, eps, nms_radius (all required: the paper fixes none
         of the prior's)."""
@@ -226,6 +235,7 @@ class SfiContext:
 
         assert K.dtype == torch.bfloat16 and V.dtype == torch.bfloat16 and K.dim() == 4 and K.stride(3) == 1
         cfg = SfiConfig()
+        cfg.page_size = page_size
         cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim = B, Hq, Hkv, K.shape[3]
         cfg.max_ctx, cfg.max_budget, cfg.n_sink, cfg.recent = max_ctx, max_budget, n_sink, recent
         cfg.scale, cfg.selector_mode = scale, 0 if selector is None else 1
@@ -234,8 +244,14 @@ class SfiContext:
             for k in ("gamma", "beta", "p", "eta", "lambda_clip", "alpha_soft", "alpha_cross", "temp", "eps"):
                 setattr(cfg, k, float(selector[k]))
             cfg.nms_radius = int(selector["nms_radius"])
-        cfg.k_stride_b, cfg.k_stride_h, cfg.k_stride_t = K.stride(0), K.stride(1), K.stride(2)
-        cfg.v_stride_b, cfg.v_stride_h, cfg.v_stride_t = V.stride(0), V.stride(1), V.stride(2)
+        if page_size:
+            # K, V: block pools [n_blocks, page_size, Hkv, d]; rows of all blocks are one run with stride K.stride(1)
+            assert K.shape[1] == page_size and K.stride(0) == page_size * K.stride(1)
+            cfg.k_stride_b, cfg.k_stride_h, cfg.k_stride_t = 0, K.stride(2), K.stride(1)
+            cfg.v_stride_b, cfg.v_stride_h, cfg.v_stride_t = 0, V.stride(2), V.stride(1)
+        else:
+            cfg.k_stride_b, cfg.k_stride_h, cfg.k_stride_t = K.stride(0), K.stride(1), K.stride(2)
+            cfg.v_stride_b, cfg.v_stride_h, cfg.v_stride_t = V.stride(0), V.stride(1), V.stride(2)
         self.cfg = cfg
         nbytes = sfi_workspace_bytes(cfg)
         if nbytes == 0:

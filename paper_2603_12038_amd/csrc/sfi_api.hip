@@ -14,6 +14,8 @@ struct sfi_ctx {
   Workspace ws;
   int n_cu;
   float alpha;              // power-mean exponent of the evidence, in (0, 1]
+  const int32_t* table;     // paged cache: device block table, nullptr until sfi_set_block_table
+  int table_stride, page_lg;
   int dense_target_wgs;     // workgroups the dense launch aims for
   int fast_tiles_per_wave;  // 32-row tiles each wave of the gather launch should get; 0 = decided per launch
   int fast_target_wgs;      // gather launches larger than this many one-tile workgroups use the pipelined kernel
@@ -41,6 +43,10 @@ int validate(const sfi_config* c) {
   if (c->n_q_heads / c->n_kv_heads > 16) return SFI_EUNSUPPORTED;
   if (c->selector_mode != 0 && c->selector_mode != 1) return SFI_EUNSUPPORTED;
   if (!(c->alpha >= 0.f) || c->alpha > 1.f) return SFI_EINVAL;
+  if (c->page_size != 0) {
+    if (c->page_size < 16 || c->page_size > 65536 || (c->page_size & (c->page_size - 1)) != 0) return SFI_EINVAL;
+    if (c->k_stride_b != 0 || c->v_stride_b != 0) return SFI_EINVAL;
+  }
   if (c->selector_mode == 1) {
     if (!(c->gamma >= 0.f) || !(c->beta >= 0.f) || !(c->p >= 1.f) || !(c->eta >= 0.f) || !(c->lambda_clip >= 0.f) ||
         !(c->lambda_clip <= 1.f) || !(c->alpha_soft >= 0.f) || !(c->alpha_cross >= 0.f) || !(c->temp > 0.f) ||
@@ -59,8 +65,8 @@ int validate(const sfi_config* c) {
   }
   if (c->k_stride_t < kHeadDim || c->v_stride_t < kHeadDim) return SFI_EINVAL;
   // row offsets inside one (sequence, KV head) are 32-bit byte offsets in the kernels
-  if ((int64_t)c->max_ctx * c->k_stride_t * 2 >= ((int64_t)1 << 32) ||
-      (int64_t)c->max_ctx * c->v_stride_t * 2 >= ((int64_t)1 << 32))
+  if (c->page_size == 0 && ((int64_t)c->max_ctx * c->k_stride_t * 2 >= ((int64_t)1 << 32) ||
+                            (int64_t)c->max_ctx * c->v_stride_t * 2 >= ((int64_t)1 << 32)))
     return SFI_EUNSUPPORTED;
   return SFI_OK;
 }
@@ -194,6 +200,7 @@ void fill_attn(const sfi_ctx* x, AttnArgs* a, const void* q, const void* K, cons
   a->Hq = c.n_q_heads; a->Hkv = c.n_kv_heads; a->G = x->G;
   a->n_sink = c.n_sink; a->recent = c.recent;
   a->scale_log2 = (float)((double)x->scale * 1.4426950408889634);
+  a->table = x->table; a->table_stride = x->table_stride; a->page_lg = x->page_lg;
 }
 
 void fill_sel(const sfi_ctx* x, SelArgs* s, const int32_t* ctx_len, const uint8_t* is_slow, int budget,
@@ -245,6 +252,7 @@ int check_common(const sfi_ctx* x, const void* q, const void* K, const void* V, 
     return SFI_EINVAL;
   if (misaligned(q, 16) || misaligned(K, 16) || misaligned(V, 16) || misaligned(out, 16) || misaligned(ctx_len, 4))
     return SFI_EALIGN;
+  if (x->cfg.page_size != 0 && x->table == nullptr) return SFI_EINVAL;  // paged cache without a block table
   return SFI_OK;
 }
 
@@ -290,6 +298,7 @@ int sfi_create(const sfi_config* cfg, void* workspace, size_t workspace_bytes, s
   x->scale = cfg->scale > 0.f ? cfg->scale : 1.0f / sqrtf((float)cfg->head_dim);
   x->G = cfg->n_q_heads / cfg->n_kv_heads;
   x->alpha = cfg->alpha > 0.f ? cfg->alpha : 1.0f;
+  for (int p = cfg->page_size; p > 1; p >>= 1) ++x->page_lg;
   x->ws = ws;
   x->n_cu = 256;
   int dev = 0;
@@ -303,6 +312,25 @@ int sfi_create(const sfi_config* cfg, void* workspace, size_t workspace_bytes, s
   x->fast_tiles_per_wave = 0;
   x->fast_target_wgs = 3 * x->n_cu;
   *out = x;
+  return SFI_OK;
+}
+
+int sfi_set_block_table(sfi_ctx* x, const int32_t* block_table, int32_t table_stride, int32_t n_blocks) {
+  if (x == nullptr) return SFI_EINVAL;
+  if (block_table == nullptr) {
+    x->table = nullptr;
+    return SFI_OK;
+  }
+  const sfi_config& c = x->cfg;
+  if (c.page_size == 0) return SFI_EINVAL;  // the context was created for a flat cache
+  if (misaligned(block_table, 4)) return SFI_EALIGN;
+  const int64_t pages = ((int64_t)c.max_ctx + c.page_size - 1) / c.page_size;
+  if (table_stride < pages || n_blocks < 1) return SFI_EINVAL;
+  if ((int64_t)n_blocks * c.page_size * c.k_stride_t * 2 >= ((int64_t)1 << 32) ||
+      (int64_t)n_blocks * c.page_size * c.v_stride_t * 2 >= ((int64_t)1 << 32))
+    return SFI_EUNSUPPORTED;
+  x->table = block_table;
+  x->table_stride = table_stride;
   return SFI_OK;
 }
 
@@ -463,6 +491,7 @@ int sfi_reorg(sfi_ctx* x, const void* K, const void* V, const int32_t* sel_idx, 
     return SFI_EINVAL;
   if (misaligned(K, 16) || misaligned(V, 16) || misaligned(sel_idx, 4) || misaligned(n_sel, 4) || misaligned(ctx_len, 4))
     return SFI_EALIGN;
+  if (x->cfg.page_size != 0 && x->table == nullptr) return SFI_EINVAL;
   int rc = check_compact(x, Kc, Vc, c_stride_b, c_stride_h, c_rows, sel_stride);
   if (rc != SFI_OK) return rc;
   hipStream_t st = (hipStream_t)stream;
@@ -476,6 +505,7 @@ int sfi_reorg(sfi_ctx* x, const void* K, const void* V, const int32_t* sel_idx, 
   r.sel_idx = sel_idx; r.n_sel = n_sel; r.ctx_len = ctx_len; r.is_slow = is_slow; r.sel_stride = sel_stride;
   r.Kc = (uint16_t*)Kc; r.Vc = (uint16_t*)Vc; r.c_sb = c_stride_b; r.c_sh = c_stride_h;
   r.Hkv = c.n_kv_heads; r.n_sink = c.n_sink;
+  r.table = x->table; r.table_stride = x->table_stride; r.page_lg = x->page_lg;
   { StageTimer t(x, st, SFI_STAGE_REORG); SFI_TRY(launch_reorg(r, c.batch, c.n_sink + sel_stride, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
 }

@@ -67,6 +67,24 @@ struct Rows {
   int jg, n;
 };
 
+// Paged cache: K and V are pools of blocks of 2^lg consecutive rows (row stride as in Rows), and a
+// sequence's logical row r lives in block tbl[r >> lg] at row r & mask of that block, i.e. at
+// physical row (tbl[r >> lg] << lg) + (r & mask) of the pool.  Everything downstream of a row number
+// is unchanged: kernels translate logical rows to physical ones and hand those to the same loads.
+struct Pages {
+  const int32_t* tbl;  // this sequence's row of the block table
+  int lg, mask;
+  __device__ __forceinline__ int page_of(int row) const { return tbl[row >> lg]; }
+  __device__ __forceinline__ int phys(int row, int page) const { return (page << lg) + (row & mask); }
+};
+__device__ __forceinline__ Pages pages_of(const AttnArgs& a, int b) {
+  Pages P;
+  P.tbl = a.table + (int64_t)b * a.table_stride;
+  P.lg = a.page_lg;
+  P.mask = (1 << a.page_lg) - 1;
+  return P;
+}
+
 // Row loads of a tile whose positions map to consecutive cache rows: block A row n is cache row
 // r0 + n; rows above r_max are replaced by r_max (they carry no weight).  K and V separately, so
 // that each half of the tile buffer can be refilled as soon as its consumer is done with it.
@@ -308,7 +326,8 @@ struct ListWalk {
 // ------------------------------------------------------------------------------------------------
 // dense kernel
 // ------------------------------------------------------------------------------------------------
-template <int EXPOSE>  // 1: also write y over J for the Selector; 2: y and the squared key norms
+// PAGED: K / V are block pools addressed through the sequence's block table.
+template <int EXPOSE, bool PAGED>  // EXPOSE 1: also write y over J for the Selector; 2: y and the squared key norms
 __global__ __launch_bounds__(kAttnThreads, 2) void attn_dense_kernel(const AttnArgs a) {
   __shared__ float s_stash[EXPOSE != 0 ? kWaves : 1][EXPOSE != 0 ? kStashFloats : 1];  // per-wave logits stash
   const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
@@ -340,7 +359,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_dense_kernel(const AttnA
   const int n_waves = a.n_split * kWaves;
   const int first = slot * kWaves + w, step = n_waves;
   Tile T;
-  if (first < a.max_tiles) issue_affine(T, R, a.n_sink + first * kTile, a.row_cap);
+  // (a paged cache has valid blocks only up to ctx_len: no load before ctx_len is known)
+  if (!PAGED && first < a.max_tiles) issue_affine(T, R, a.n_sink + first * kTile, a.row_cap);
   bf16x8 qreg[4];
   load_q(qreg, a.q, head0, G, jg, n);
   const int L = a.ctx_len[b];
@@ -383,7 +403,23 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_dense_kernel(const AttnA
       T.v[4 + i] = load_row16(R.Vb, (uint32_t)row_for(t, 16 + 4 * jg + i) * R.v_st + R.v_lane);
     }
   };
-  if (K > 0 && first >= nTJ) {  // short context: the first tile is a sink / recent tile after all
+  Pages P;
+  int pa_n = 0, pb_n = 0;  // PAGED: block-table entries of the next tile's K rows (this lane's rows n and 16 + n)
+  if (PAGED) {
+    // Same order of memory instructions as an iteration of the loop: K rows, the table entries of the
+    // tile after, V rows.  Waves without tiles read row L - 1.
+    P = pages_of(a, b);
+    const int ra = row_for(first, n), rb = row_for(first, 16 + n);
+    const int pra = P.phys(ra, P.page_of(ra)), prb = P.phys(rb, P.page_of(rb));
+    __builtin_amdgcn_sched_barrier(0);
+    issue_k_rows(T, R, pra, prb);
+    __builtin_amdgcn_sched_barrier(0);
+    pa_n = P.page_of(row_for(first + step, n));
+    pb_n = P.page_of(row_for(first + step, 16 + n));
+    __builtin_amdgcn_sched_barrier(0);
+    issue_v_rows(T, R, pra, prb);
+    __builtin_amdgcn_sched_barrier(0);
+  } else if (K > 0 && first >= nTJ) {  // short context: the first tile is a sink / recent tile after all
     issue_k_tile(first);
     issue_v_tile(first);
   }
@@ -445,7 +481,16 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_dense_kernel(const AttnA
     qk_phase(T, qreg, a.scale_log2, y);
     float k2a = 0.f, k2b = 0.f;
     if (EXPOSE == 2) knorm_phase(T, jg, n, k2a, k2b);
-    issue_k_tile(t + step);
+    int pra = 0, prb = 0;
+    if (PAGED) {
+      pra = P.phys(row_for(t + step, n), pa_n);
+      prb = P.phys(row_for(t + step, 16 + n), pb_n);
+      issue_k_rows(T, R, pra, prb);
+      pa_n = P.page_of(row_for(t + 2 * step, n));
+      pb_n = P.page_of(row_for(t + 2 * step, 16 + n));
+    } else {
+      issue_k_tile(t + step);
+    }
     if (EXPOSE != 0 && inJ) {  // positions past |J| land in the padding of the last tile, never used
       float* st = stash + n_stashed * (rows_exp * kTile);
       stage_logits(st, y, jg, n, G);
@@ -461,7 +506,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_dense_kernel(const AttnA
     bf16x8 a_hi, a_lo;
     softmax_phase(y, acc, m_run, l_run, jg, a_hi, a_lo);
     pv_phase(T, a_hi, a_lo, acc);
-    issue_v_tile(t + step);
+    if (PAGED) issue_v_rows(T, R, pra, prb);
+    else issue_v_tile(t + step);
   }
   if (EXPOSE != 0) flush_stash();
   // the record still open: the J record if the wave had no other tile (slot first), else the record of
@@ -539,6 +585,7 @@ __device__ __forceinline__ void write_wg_record(float* part, int64_t head0, int 
 // ------------------------------------------------------------------------------------------------
 // gather kernel
 // ------------------------------------------------------------------------------------------------
+template <bool PAGED>
 __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_kernel(const AttnArgs a) {
   const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   if (a.is_slow != nullptr && a.is_slow[b] != 0) return;
@@ -589,7 +636,13 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_kernel(const Attn
       sA = W.sel_at(p0 + n);
       sB = W.sel_at(p0 + 16 + n);
     }
-    issue_rows(T, R, W.row_of(p0 + n, sA), W.row_of(p0 + 16 + n, sB));
+    int ra = W.row_of(p0 + n, sA), rb = W.row_of(p0 + 16 + n, sB);
+    if (PAGED) {  // one more dependent round: row -> block-table entry -> physical row
+      const Pages P = pages_of(a, b);
+      ra = P.phys(ra, P.page_of(ra));
+      rb = P.phys(rb, P.page_of(rb));
+    }
+    issue_rows(T, R, ra, rb);
     if (p0 + kTile <= W.N) tile_math<false>(T, qreg, a.scale_log2, acc, m_run, l_run, jg, p0, W.N);
     else tile_math<true>(T, qreg, a.scale_log2, acc, m_run, l_run, jg, p0, W.N);
   }
@@ -606,6 +659,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_kernel(const Attn
 // after P V; the selected indices are read two tiles ahead.  Loads past the wave's last tile fall
 // on row 0 (no branch around a load, so every wait names exactly the loads it needs).
 // ------------------------------------------------------------------------------------------------
+template <bool PAGED>
 __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(const AttnArgs a) {
   const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   if (a.is_slow != nullptr && a.is_slow[b] != 0) return;
@@ -653,8 +707,32 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(con
   // Memory instructions go out in the same order here as in an iteration of the loop below -- K rows,
   // the indices of the tile after, V rows -- so the in-order load counter reads the same on both ways
   // into the loop.  A wave without tiles reads row 0 and skips the loop.
-  int sAn, sBn;
-  {
+  // PAGED adds one stage to the pipeline: indices are read two tiles ahead, the block-table entries
+  // of the rows they name one tile ahead (order: K rows, table entries, indices, V rows).
+  int sAn, sBn;            // !PAGED: indices of the next tile; PAGED: of the tile after the next
+  int ra_n = 0, rb_n = 0;  // PAGED: logical rows of the next tile and their block-table entries
+  int pa_n = 0, pb_n = 0;
+  Pages P;
+  if (PAGED) {
+    P = pages_of(a, b);
+    const int sA1 = W.sel_at_nonempty(p_first + pstep + n), sB1 = W.sel_at_nonempty(p_first + pstep + 16 + n);
+    int ra = W.row_of(p_first + n, sA), rb = W.row_of(p_first + 16 + n, sB);
+    ra = P.phys(ra, P.page_of(ra));
+    rb = P.phys(rb, P.page_of(rb));
+    __builtin_amdgcn_sched_barrier(0);
+    issue_k_rows(T, R, ra, rb);
+    __builtin_amdgcn_sched_barrier(0);
+    ra_n = W.row_of(p_first + pstep + n, sA1);
+    rb_n = W.row_of(p_first + pstep + 16 + n, sB1);
+    pa_n = P.page_of(ra_n);
+    pb_n = P.page_of(rb_n);
+    __builtin_amdgcn_sched_barrier(0);
+    sAn = W.sel_at_nonempty(p_first + 2 * pstep + n);
+    sBn = W.sel_at_nonempty(p_first + 2 * pstep + 16 + n);
+    __builtin_amdgcn_sched_barrier(0);
+    issue_v_rows(T, R, ra, rb);
+    __builtin_amdgcn_sched_barrier(0);
+  } else {
     const int ra = W.row_of(p_first + n, sA), rb = W.row_of(p_first + 16 + n, sB);
     __builtin_amdgcn_sched_barrier(0);  // the compiler's scheduler must not reorder the three groups
     issue_k_rows(T, R, ra, rb);
@@ -670,10 +748,24 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(con
     const int pn = p0 + pstep;
     float y[8];
     qk_phase(T, qreg, a.scale_log2, y);
-    const int ra = W.row_of(pn + n, sAn), rb = W.row_of(pn + 16 + n, sBn);  // row 0 past the list
-    issue_k_rows(T, R, ra, rb);
-    sAn = W.sel_at_nonempty(pn + pstep + n);
-    sBn = W.sel_at_nonempty(pn + pstep + 16 + n);
+    int ra, rb;
+    if (PAGED) {
+      ra = P.phys(ra_n, pa_n);
+      rb = P.phys(rb_n, pb_n);
+      issue_k_rows(T, R, ra, rb);
+      ra_n = W.row_of(pn + pstep + n, sAn);  // row 0 past the list
+      rb_n = W.row_of(pn + pstep + 16 + n, sBn);
+      pa_n = P.page_of(ra_n);
+      pb_n = P.page_of(rb_n);
+      sAn = W.sel_at_nonempty(pn + 2 * pstep + n);
+      sBn = W.sel_at_nonempty(pn + 2 * pstep + 16 + n);
+    } else {
+      ra = W.row_of(pn + n, sAn);  // row 0 past the list
+      rb = W.row_of(pn + 16 + n, sBn);
+      issue_k_rows(T, R, ra, rb);
+      sAn = W.sel_at_nonempty(pn + pstep + n);
+      sBn = W.sel_at_nonempty(pn + pstep + 16 + n);
+    }
     if (p0 + kTile > W.N) mask_tail(T, y, jg, p0, W.N);
     bf16x8 a_hi, a_lo;
     softmax_phase(y, acc, m_run, l_run, jg, a_hi, a_lo);
@@ -692,6 +784,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(con
 // index is read: a wave's first tile is on its way before any scalar of the step has arrived.
 // Tiles never straddle the two segments: the compact segment ends with a ragged tile of its own.
 // ------------------------------------------------------------------------------------------------
+template <bool PAGED>  // PAGED: the recent window is read from a paged cache (the compact buffers are always flat)
 __global__ __launch_bounds__(kAttnThreads, 3) void attn_compact_kernel(const AttnArgs a) {
   const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   if (a.is_slow != nullptr && a.is_slow[b] != 0) return;
@@ -745,7 +838,13 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_compact_kernel(const Att
     } else {
       p0 = (t - Tc) * kTile;
       N = Nr;
-      issue_affine(T, R, rs + p0, L - 1);
+      if (PAGED) {
+        const Pages P = pages_of(a, b);
+        const int ra = min(rs + p0 + n, L - 1), rb = min(rs + p0 + 16 + n, L - 1);
+        issue_rows(T, R, P.phys(ra, P.page_of(ra)), P.phys(rb, P.page_of(rb)));
+      } else {
+        issue_affine(T, R, rs + p0, L - 1);
+      }
     }
     if (p0 + kTile <= N) tile_math<false>(T, qreg, a.scale_log2, acc, m_run, l_run, jg, p0, N);
     else tile_math<true>(T, qreg, a.scale_log2, acc, m_run, l_run, jg, p0, N);
@@ -761,6 +860,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_compact_kernel(const Att
 // moves kReorgRows compact rows of one (b, h), 16 lanes x 16 bytes per row, K and V; the indices
 // are read before the list length is known, and all of a thread's row loads precede its stores.
 // ------------------------------------------------------------------------------------------------
+template <bool PAGED>
 __global__ __launch_bounds__(kAttnThreads) void reorg_kernel(const ReorgArgs a) {
   const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
@@ -789,7 +889,11 @@ __global__ __launch_bounds__(kAttnThreads) void reorg_kernel(const ReorgArgs a) 
   for (int p = 0; p < kPass; ++p) {
     const int i = chunk * kReorgRows + p * 16 + r;
     ok[p] = i < nS || (i >= a.n_sink && i < a.n_sink + nSel);
-    const int row = i < a.n_sink ? i : src[p];
+    int row = i < a.n_sink ? i : src[p];
+    if (PAGED && ok[p]) {
+      const int32_t* tbl = a.table + (int64_t)b * a.table_stride;
+      row = (tbl[row >> a.page_lg] << a.page_lg) + (row & ((1 << a.page_lg) - 1));
+    }
     if (ok[p]) {
       kr[p] = load_row16(Kb, (uint32_t)row * ((uint32_t)a.k_st * 2u) + sub * 16);
       vr[p] = load_row16(Vb, (uint32_t)row * ((uint32_t)a.v_st * 2u) + sub * 16);
@@ -855,29 +959,43 @@ hipError_t launch_trigger(const int32_t* last_token, const uint32_t* bitmap, int
   return hipGetLastError();
 }
 
-hipError_t launch_attn_dense(const AttnArgs& a, int B, int n_slots, hipStream_t s) {
+template <bool PAGED>
+static void launch_dense_t(const AttnArgs& a, dim3 grid, hipStream_t s) {
   if (a.logits != nullptr && a.with_knorm)
-    hipLaunchKernelGGL(attn_dense_kernel<2>, dim3(n_slots, a.Hkv, B), dim3(kAttnThreads), 0, s, a);
+    hipLaunchKernelGGL((attn_dense_kernel<2, PAGED>), grid, dim3(kAttnThreads), 0, s, a);
   else if (a.logits != nullptr)
-    hipLaunchKernelGGL(attn_dense_kernel<1>, dim3(n_slots, a.Hkv, B), dim3(kAttnThreads), 0, s, a);
+    hipLaunchKernelGGL((attn_dense_kernel<1, PAGED>), grid, dim3(kAttnThreads), 0, s, a);
   else
-    hipLaunchKernelGGL(attn_dense_kernel<0>, dim3(n_slots, a.Hkv, B), dim3(kAttnThreads), 0, s, a);
+    hipLaunchKernelGGL((attn_dense_kernel<0, PAGED>), grid, dim3(kAttnThreads), 0, s, a);
+}
+hipError_t launch_attn_dense(const AttnArgs& a, int B, int n_slots, hipStream_t s) {
+  const dim3 grid(n_slots, a.Hkv, B);
+  if (a.table != nullptr) launch_dense_t<true>(a, grid, s);
+  else launch_dense_t<false>(a, grid, s);
   return hipGetLastError();
 }
 hipError_t launch_attn_compact(const AttnArgs& a, int B, int n_slots, hipStream_t s) {
-  hipLaunchKernelGGL(attn_compact_kernel, dim3(n_slots, a.Hkv, B), dim3(kAttnThreads), 0, s, a);
+  if (a.table != nullptr)
+    hipLaunchKernelGGL(attn_compact_kernel<true>, dim3(n_slots, a.Hkv, B), dim3(kAttnThreads), 0, s, a);
+  else
+    hipLaunchKernelGGL(attn_compact_kernel<false>, dim3(n_slots, a.Hkv, B), dim3(kAttnThreads), 0, s, a);
   return hipGetLastError();
 }
 hipError_t launch_reorg(const ReorgArgs& a, int B, int rows, hipStream_t s) {
-  hipLaunchKernelGGL(reorg_kernel, dim3((rows + kReorgRows - 1) / kReorgRows, a.Hkv, B), dim3(kAttnThreads), 0, s, a);
+  const dim3 grid((rows + kReorgRows - 1) / kReorgRows, a.Hkv, B);
+  if (a.table != nullptr) hipLaunchKernelGGL(reorg_kernel<true>, grid, dim3(kAttnThreads), 0, s, a);
+  else hipLaunchKernelGGL(reorg_kernel<false>, grid, dim3(kAttnThreads), 0, s, a);
   return hipGetLastError();
 }
 hipError_t launch_attn_gather(const AttnArgs& a, int B, int n_slots, hipStream_t s) {
+  const dim3 grid(n_slots, a.Hkv, B);
   if (a.pipelined) {
-    hipLaunchKernelGGL(attn_gather_stream_kernel, dim3(n_slots, a.Hkv, B), dim3(kAttnThreads), 0, s, a);
-    return hipGetLastError();
+    if (a.table != nullptr) hipLaunchKernelGGL(attn_gather_stream_kernel<true>, grid, dim3(kAttnThreads), 0, s, a);
+    else hipLaunchKernelGGL(attn_gather_stream_kernel<false>, grid, dim3(kAttnThreads), 0, s, a);
+  } else {
+    if (a.table != nullptr) hipLaunchKernelGGL(attn_gather_kernel<true>, grid, dim3(kAttnThreads), 0, s, a);
+    else hipLaunchKernelGGL(attn_gather_kernel<false>, grid, dim3(kAttnThreads), 0, s, a);
   }
-  hipLaunchKernelGGL(attn_gather_kernel, dim3(n_slots, a.Hkv, B), dim3(kAttnThreads), 0, s, a);
   return hipGetLastError();
 }
 hipError_t launch_merge(const MergeArgs& a, int B, hipStream_t s) {

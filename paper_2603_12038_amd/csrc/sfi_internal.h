@@ -64,6 +64,9 @@ struct AttnArgs {
   int32_t with_knorm;            // dense mode: also expose the squared key norms (full Selector)
   int32_t pipelined;             // gather mode: few workgroups per (b, h), each wave walks several tiles
   float* out_direct;             // gather / compact mode with n_split == 1: write the output here, no record
+  const int32_t* table;          // paged cache: block table [B][table_stride], logical page -> block of the pool
+  int64_t table_stride;
+  int32_t page_lg;               // log2 of the page size in rows
   uint32_t* hist1;               // dense mode with Selector: cleared by the sink/recent workgroup
   uint32_t* state;
   int64_t ld_pos;
@@ -91,6 +94,9 @@ struct ReorgArgs {
   uint16_t* Vc;
   int64_t c_sb, c_sh;
   int32_t Hkv, n_sink;
+  const int32_t* table;          // paged cache (see AttnArgs)
+  int64_t table_stride;
+  int32_t page_lg;
 };
 constexpr int kReorgRows = 64;   // compact rows per workgroup of the Reorg kernel
 
