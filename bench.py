@@ -269,6 +269,11 @@ def main():
                          "layer-wise asynchronous execution -- Selector (and Reorg) of layer i on a second stream "
                          "under the dense attention of layer i+1, ring of --ring workspaces, one barrier at the end")
     ap.add_argument("--ring", type=int, default=4, help="workspace slots of the asynchronous slow step")
+    ap.add_argument("--page-size", type=int, default=0,
+                    help="0: flat K/V tensors; a power of two >= 16: K/V handed over as block pools of that many rows "
+                         "with one randomly permuted block table shared by the layers (fixed-schedule workloads)")
+    ap.add_argument("--page-layout", choices=["thd", "htd"], default="htd",
+                    help="block layout of a paged cache: [blocks][page][Hkv][d] or [blocks][Hkv][page][d]")
     ap.add_argument("--selector-mode", type=int, choices=[0, 1], default=0,
                     help="0: evidence-only ranking (the measured baseline); 1: Algorithm 2 in full, oracle defaults")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -321,15 +326,46 @@ def main():
         Ks.append(k)
         Vs.append(v)
     max_ctx = int(w.L_alloc)
+    n_blocks = 0
+    if args.page_size:
+        # scatter every layer's flat cache into a block pool [n_blocks, page, Hkv, d] through one block table
+        P = args.page_size
+        pages = (max_ctx + P - 1) // P
+        n_blocks = B * pages
+        gperm = torch.Generator(device="cpu")
+        gperm.manual_seed(99)
+        perm = torch.randperm(n_blocks, generator=gperm).to(dev)
+        table_d = perm.view(B, pages).to(torch.int32).contiguous()
+
+        def to_pool(x):
+            pad = pages * P - x.shape[2]
+            if pad:
+                x = torch.cat([x, torch.zeros(B, Hkv, pad, d, dtype=x.dtype, device=dev)], dim=2)
+            if args.page_layout == "thd":
+                blocks = x.view(B, Hkv, pages, P, d).permute(0, 2, 3, 1, 4).reshape(n_blocks, P, Hkv, d)
+            else:
+                blocks = x.view(B, Hkv, pages, P, d).permute(0, 2, 1, 3, 4).reshape(n_blocks, Hkv, P, d)
+            pool = torch.empty_like(blocks)
+            pool[perm] = blocks
+            return pool
+
+        Ks = [to_pool(k) for k in Ks]
+        Vs = [to_pool(v) for v in Vs]
+        K0, V0 = Ks[0], Vs[0]
+        torch.cuda.synchronize()
     sel_params = None
     if args.selector_mode == 1:
         sel_params = dict(gamma=0.5, beta=1.0, p=2.0, eta=0.5, lambda_clip=0.02, alpha_soft=0.5, alpha_cross=0.35,
                           temp=1.0, eps=1e-8, nms_radius=2)
-    ctx = sfi.SfiContext(B, Hq, Hkv, max_ctx, w.budget, w.n_sink, w.recent, K0, V0, selector=sel_params)
+    mk = lambda: sfi.SfiContext(B, Hq, Hkv, max_ctx, w.budget, w.n_sink, w.recent, K0, V0, selector=sel_params,
+                                page_size=args.page_size, page_layout=args.page_layout)
+    ctx = mk()
     h = ctx.handle
     use_async = args.slow_schedule == "async"
-    ring = [ctx] + [sfi.SfiContext(B, Hq, Hkv, max_ctx, w.budget, w.n_sink, w.recent, K0, V0, selector=sel_params)
-                    for _ in range(args.ring - 1)] if use_async else [ctx]
+    ring = [ctx] + [mk() for _ in range(args.ring - 1)] if use_async else [ctx]
+    if args.page_size:
+        for c in ring:
+            sfi.sfi_set_block_table(c.handle, table_d, n_blocks)
     aux = torch.cuda.Stream() if use_async else None  # default priority
     if args.dense_wgs or args.fast_tpw:
         for c in ring:
@@ -520,7 +556,7 @@ def main():
         "config": {"workload": f"{wl['label']}: B{B} Hq{Hq} Hkv{Hkv} d{d} ctx{L0} k{w.budget} R{w.recent} "
                                f"sink{w.n_sink} slow every {SEG}",
                    "step": f"{SEG} decode steps (1 slow + {SEG - 1} fast) x {NL} virtual layers",
-                   "virtual_layers": NL, "launch": args.launch, "fast_path": args.fast_path, "selector_mode": args.selector_mode,
+                   "virtual_layers": NL, "launch": args.launch, "fast_path": args.fast_path, "selector_mode": args.selector_mode, "page_size": args.page_size, "page_layout": args.page_layout if args.page_size else None,
                    "slow_schedule": args.slow_schedule + (f" (ring {len(ring)})" if use_async else ""),
                    "dense_splits": dsp, "fast_splits": fsp},
         "roofline": roof,

@@ -95,11 +95,17 @@ typedef struct sfi_config {
   float alpha;
   /* Paged cache: 0 = K and V are flat strided tensors (above); a power of two in [16, 65536] = K and V are
    * pools of blocks of page_size consecutive rows, row r of block p of KV head h at element offset
-   * (p * page_size + r) * k_stride_t + h * k_stride_h from the pool base (so k_stride_t is the row stride
-   * inside and across blocks, e.g. Hkv * 128 for a [blocks][page_size][Hkv][128] pool); k_stride_b and
-   * v_stride_b must be 0.  Sequences find their blocks through the block table set with
+   * p * k_stride_page + r * k_stride_t + h * k_stride_h from the pool base; k_stride_b and v_stride_b must
+   * be 0.  Sequences find their blocks through the block table set with
    * sfi_set_block_table.  max_ctx still bounds every ctx_len[b]. */
   int32_t page_size;
+  /* Paged cache: element offset between consecutive blocks of the K / V pool; 0 selects
+   * page_size * k_stride_t (blocks back to back in one run of rows, as in [blocks][page_size][Hkv][128]).
+   * A [blocks][Hkv][page_size][128] pool, which keeps each head's rows of a block contiguous (the faster
+   * layout for the dense kernel), has k_stride_t = 128, k_stride_h = page_size * 128 and
+   * k_stride_page = Hkv * page_size * 128.  Must be a multiple of the row stride, with the same ratio for
+   * K and V. */
+  int64_t k_stride_page, v_stride_page;
 } sfi_config;
 
 typedef struct sfi_ctx sfi_ctx; /* opaque; host memory owned by the library */
@@ -118,8 +124,7 @@ int sfi_create(const sfi_config* cfg, void* workspace, size_t workspace_bytes, s
  * [batch][table_stride]; entry [b][i] is the block of the pools that holds rows
  * [i * page_size, (i + 1) * page_size) of sequence b.  Entries that cover rows [0, ctx_len[b]) must be valid
  * at every hot call (later ones are never read); block ids lie in [0, n_blocks), and
- * n_blocks * page_size * row stride must stay below 4 GiB for K and for V (32-bit row offsets inside the
- * kernels).  The pointer is kept until the next call of this function; the table's contents may change
+ * n_blocks * block stride must stay below 4 GiB for K and for V (32-bit row offsets inside the kernels).  The pointer is kept until the next call of this function; the table's contents may change
  * between hot calls.  With a paged cache the K and V arguments of the hot calls are the pool bases and the
  * kernels never read rows before ctx_len[b] is known.  Passing NULL detaches the table.
  */

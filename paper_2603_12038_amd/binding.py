@@ -33,7 +33,7 @@ class SfiConfig(C.Structure):
         ("gamma", C.c_float), ("beta", C.c_float), ("p", C.c_float), ("eta", C.c_float),
         ("lambda_clip", C.c_float), ("alpha_soft", C.c_float), ("alpha_cross", C.c_float), ("temp", C.c_float),
         ("eps", C.c_float), ("nms_radius", C.c_int32), ("alpha", C.c_float),
-        ("page_size", C.c_int32),
+        ("page_size", C.c_int32), ("k_stride_page", C.c_int64), ("v_stride_page", C.c_int64),
     ]
 
 
@@ -227,7 +227,7 @@ class SfiContext:
     """Owns the workspace tensor and the context handle for one (shape, K/V layout)."""
 
     def __init__(self, B, Hq, Hkv, max_ctx, max_budget, n_sink, recent, K, V, scale: float = 0.0, device="cuda",
-                 selector: Optional[dict] = None, alpha: float = 0.0, page_size: int = 0):
+                 selector: Optional[dict] = None, alpha: float = 0.0, page_size: int = 0, page_layout: str = "thd"):
         """selector: None for mode 0, or the mode-1 hyper-parameters as a dict with the keys gamma, beta, p,
         eta, lambda_clip, alpha_soft, alpha_cross, temp, eps, nms_radius (all required: the paper fixes none
         of the prior's)."""
@@ -245,10 +245,11 @@ class SfiContext:
                 setattr(cfg, k, float(selector[k]))
             cfg.nms_radius = int(selector["nms_radius"])
         if page_size:
-            # K, V: block pools [n_blocks, page_size, Hkv, d]; rows of all blocks are one run with stride K.stride(1)
-            assert K.shape[1] == page_size and K.stride(0) == page_size * K.stride(1)
-            cfg.k_stride_b, cfg.k_stride_h, cfg.k_stride_t = 0, K.stride(2), K.stride(1)
-            cfg.v_stride_b, cfg.v_stride_h, cfg.v_stride_t = 0, V.stride(2), V.stride(1)
+            # K, V: block pools, [n_blocks, page_size, Hkv, d] ("thd") or [n_blocks, Hkv, page_size, d] ("htd")
+            t, hd = (1, 2) if page_layout == "thd" else (2, 1)
+            assert K.shape[t] == page_size and K.shape[hd] == Hkv and V.shape == K.shape
+            cfg.k_stride_b, cfg.k_stride_h, cfg.k_stride_t, cfg.k_stride_page = 0, K.stride(hd), K.stride(t), K.stride(0)
+            cfg.v_stride_b, cfg.v_stride_h, cfg.v_stride_t, cfg.v_stride_page = 0, V.stride(hd), V.stride(t), V.stride(0)
         else:
             cfg.k_stride_b, cfg.k_stride_h, cfg.k_stride_t = K.stride(0), K.stride(1), K.stride(2)
             cfg.v_stride_b, cfg.v_stride_h, cfg.v_stride_t = V.stride(0), V.stride(1), V.stride(2)

@@ -15,7 +15,7 @@ struct sfi_ctx {
   int n_cu;
   float alpha;              // power-mean exponent of the evidence, in (0, 1]
   const int32_t* table;     // paged cache: device block table, nullptr until sfi_set_block_table
-  int table_stride, page_lg;
+  int table_stride, page_lg, page_rpb;
   int dense_target_wgs;     // workgroups the dense launch aims for
   int fast_tiles_per_wave;  // 32-row tiles each wave of the gather launch should get; 0 = decided per launch
   int fast_target_wgs;      // gather launches larger than this many one-tile workgroups use the pipelined kernel
@@ -46,6 +46,13 @@ int validate(const sfi_config* c) {
   if (c->page_size != 0) {
     if (c->page_size < 16 || c->page_size > 65536 || (c->page_size & (c->page_size - 1)) != 0) return SFI_EINVAL;
     if (c->k_stride_b != 0 || c->v_stride_b != 0) return SFI_EINVAL;
+    if (c->k_stride_page < 0 || c->v_stride_page < 0 || (c->k_stride_page == 0) != (c->v_stride_page == 0)) return SFI_EINVAL;
+    if (c->k_stride_page != 0) {  // whole row strides, enough for a block, the same count for K and V
+      if (c->k_stride_t == 0 || c->v_stride_t == 0 || c->k_stride_page % c->k_stride_t != 0 ||
+          c->v_stride_page % c->v_stride_t != 0 || c->k_stride_page / c->k_stride_t != c->v_stride_page / c->v_stride_t ||
+          c->k_stride_page / c->k_stride_t < c->page_size || c->k_stride_page / c->k_stride_t > (1 << 24))
+        return SFI_EINVAL;
+    }
   }
   if (c->selector_mode == 1) {
     if (!(c->gamma >= 0.f) || !(c->beta >= 0.f) || !(c->p >= 1.f) || !(c->eta >= 0.f) || !(c->lambda_clip >= 0.f) ||
@@ -200,7 +207,7 @@ void fill_attn(const sfi_ctx* x, AttnArgs* a, const void* q, const void* K, cons
   a->Hq = c.n_q_heads; a->Hkv = c.n_kv_heads; a->G = x->G;
   a->n_sink = c.n_sink; a->recent = c.recent;
   a->scale_log2 = (float)((double)x->scale * 1.4426950408889634);
-  a->table = x->table; a->table_stride = x->table_stride; a->page_lg = x->page_lg;
+  a->table = x->table; a->table_stride = x->table_stride; a->page_lg = x->page_lg; a->page_rpb = x->page_rpb;
 }
 
 void fill_sel(const sfi_ctx* x, SelArgs* s, const int32_t* ctx_len, const uint8_t* is_slow, int budget,
@@ -299,6 +306,7 @@ int sfi_create(const sfi_config* cfg, void* workspace, size_t workspace_bytes, s
   x->G = cfg->n_q_heads / cfg->n_kv_heads;
   x->alpha = cfg->alpha > 0.f ? cfg->alpha : 1.0f;
   for (int p = cfg->page_size; p > 1; p >>= 1) ++x->page_lg;
+  x->page_rpb = cfg->k_stride_page != 0 ? (int)(cfg->k_stride_page / cfg->k_stride_t) : cfg->page_size;
   x->ws = ws;
   x->n_cu = 256;
   int dev = 0;
@@ -326,8 +334,8 @@ int sfi_set_block_table(sfi_ctx* x, const int32_t* block_table, int32_t table_st
   if (misaligned(block_table, 4)) return SFI_EALIGN;
   const int64_t pages = ((int64_t)c.max_ctx + c.page_size - 1) / c.page_size;
   if (table_stride < pages || n_blocks < 1) return SFI_EINVAL;
-  if ((int64_t)n_blocks * c.page_size * c.k_stride_t * 2 >= ((int64_t)1 << 32) ||
-      (int64_t)n_blocks * c.page_size * c.v_stride_t * 2 >= ((int64_t)1 << 32))
+  if ((int64_t)n_blocks * x->page_rpb * c.k_stride_t * 2 >= ((int64_t)1 << 32) ||
+      (int64_t)n_blocks * x->page_rpb * c.v_stride_t * 2 >= ((int64_t)1 << 32))
     return SFI_EUNSUPPORTED;
   x->table = block_table;
   x->table_stride = table_stride;
@@ -505,7 +513,7 @@ int sfi_reorg(sfi_ctx* x, const void* K, const void* V, const int32_t* sel_idx, 
   r.sel_idx = sel_idx; r.n_sel = n_sel; r.ctx_len = ctx_len; r.is_slow = is_slow; r.sel_stride = sel_stride;
   r.Kc = (uint16_t*)Kc; r.Vc = (uint16_t*)Vc; r.c_sb = c_stride_b; r.c_sh = c_stride_h;
   r.Hkv = c.n_kv_heads; r.n_sink = c.n_sink;
-  r.table = x->table; r.table_stride = x->table_stride; r.page_lg = x->page_lg;
+  r.table = x->table; r.table_stride = x->table_stride; r.page_lg = x->page_lg; r.page_rpb = x->page_rpb;
   { StageTimer t(x, st, SFI_STAGE_REORG); SFI_TRY(launch_reorg(r, c.batch, c.n_sink + sel_stride, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
 }

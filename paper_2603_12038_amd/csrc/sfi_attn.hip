@@ -67,21 +67,23 @@ struct Rows {
   int jg, n;
 };
 
-// Paged cache: K and V are pools of blocks of 2^lg consecutive rows (row stride as in Rows), and a
-// sequence's logical row r lives in block tbl[r >> lg] at row r & mask of that block, i.e. at
-// physical row (tbl[r >> lg] << lg) + (r & mask) of the pool.  Everything downstream of a row number
+// Paged cache: K and V are pools of blocks of 2^lg consecutive rows (row stride as in Rows); blocks
+// start every rpb row strides (rpb = 2^lg when the blocks lie back to back).  A sequence's logical
+// row r lives in block tbl[r >> lg] at row r & mask of that block, i.e. at row number
+// tbl[r >> lg] * rpb + (r & mask) of the pool's row space.  Everything downstream of a row number
 // is unchanged: kernels translate logical rows to physical ones and hand those to the same loads.
 struct Pages {
   const int32_t* tbl;  // this sequence's row of the block table
-  int lg, mask;
+  int lg, mask, rpb;
   __device__ __forceinline__ int page_of(int row) const { return tbl[row >> lg]; }
-  __device__ __forceinline__ int phys(int row, int page) const { return (page << lg) + (row & mask); }
+  __device__ __forceinline__ int phys(int row, int page) const { return page * rpb + (row & mask); }
 };
 __device__ __forceinline__ Pages pages_of(const AttnArgs& a, int b) {
   Pages P;
   P.tbl = a.table + (int64_t)b * a.table_stride;
   P.lg = a.page_lg;
   P.mask = (1 << a.page_lg) - 1;
+  P.rpb = a.page_rpb;
   return P;
 }
 
@@ -892,7 +894,7 @@ __global__ __launch_bounds__(kAttnThreads) void reorg_kernel(const ReorgArgs a) 
     int row = i < a.n_sink ? i : src[p];
     if (PAGED && ok[p]) {
       const int32_t* tbl = a.table + (int64_t)b * a.table_stride;
-      row = (tbl[row >> a.page_lg] << a.page_lg) + (row & ((1 << a.page_lg) - 1));
+      row = tbl[row >> a.page_lg] * a.page_rpb + (row & ((1 << a.page_lg) - 1));
     }
     if (ok[p]) {
       kr[p] = load_row16(Kb, (uint32_t)row * ((uint32_t)a.k_st * 2u) + sub * 16);

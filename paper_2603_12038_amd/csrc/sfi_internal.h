@@ -67,6 +67,7 @@ struct AttnArgs {
   const int32_t* table;          // paged cache: block table [B][table_stride], logical page -> block of the pool
   int64_t table_stride;
   int32_t page_lg;               // log2 of the page size in rows
+  int32_t page_rpb;              // row numbers a block spans in the pool's row space (block stride / row stride)
   uint32_t* hist1;               // dense mode with Selector: cleared by the sink/recent workgroup
   uint32_t* state;
   int64_t ld_pos;
@@ -96,7 +97,7 @@ struct ReorgArgs {
   int32_t Hkv, n_sink;
   const int32_t* table;          // paged cache (see AttnArgs)
   int64_t table_stride;
-  int32_t page_lg;
+  int32_t page_lg, page_rpb;
 };
 constexpr int kReorgRows = 64;   // compact rows per workgroup of the Reorg kernel
 

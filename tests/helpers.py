@@ -75,7 +75,7 @@ def check_selection(sel, nsel, sel_ref, nsel_ref, z, ctx_len, n_sink, recent, bu
     return n_exact
 
 
-def make_paged(K: np.ndarray, V: np.ndarray, ctx_max: np.ndarray, page: int, seed: int, spare: int = 3):
+def make_paged(K: np.ndarray, V: np.ndarray, ctx_max: np.ndarray, page: int, seed: int, spare: int = 3, layout: str = "thd"):
     """Scatter flat caches [B, Hkv, L, d] into block pools [n_blocks, page, Hkv, d] through a random block
     table [B, pages].  Spare blocks, and the blocks of table entries wholly beyond ctx_max[b], hold a NaN
     pattern (a valid address, so a wrong lookup shows up as a wrong result, never as a fault)."""
@@ -96,13 +96,15 @@ def make_paged(K: np.ndarray, V: np.ndarray, ctx_max: np.ndarray, page: int, see
                 continue
             Kp[table[b, i], :hi - lo] = K[b, :, lo:hi].transpose(1, 0, 2)
             Vp[table[b, i], :hi - lo] = V[b, :, lo:hi].transpose(1, 0, 2)
+    if layout == "htd":  # [n_blocks, Hkv, page, d]: a head's rows of a block are contiguous
+        Kp, Vp = np.ascontiguousarray(Kp.transpose(0, 2, 1, 3)), np.ascontiguousarray(Vp.transpose(0, 2, 1, 3))
     return Kp, Vp, table
 
 
 class Runner:
     """Device copies of one workload's K/V plus an sfi context; thin wrappers over the C-ABI calls."""
 
-    def __init__(self, w, max_budget=None, selector=None, alpha=0.0, page_size=0, ctx_max=None):
+    def __init__(self, w, max_budget=None, selector=None, alpha=0.0, page_size=0, ctx_max=None, page_layout="thd"):
         """page_size > 0: the cache is handed over as block pools + block table (valid up to ctx_max[b] rows,
         default every allocated row); self.K / self.V are then the pools."""
         import torch
@@ -111,13 +113,14 @@ class Runner:
         self.max_ctx = int(w.L_alloc)
         if page_size:
             cm = np.full(w.B, w.L_alloc) if ctx_max is None else np.asarray(ctx_max)
-            Kp, Vp, table = make_paged(w.K, w.V, cm, page_size, seed=page_size + 17)
+            Kp, Vp, table = make_paged(w.K, w.V, cm, page_size, seed=page_size + 17, layout=page_layout)
             self.K, self.V = to_dev(Kp), to_dev(Vp)
             self.table = torch.from_numpy(table).cuda()
         else:
             self.K, self.V = to_dev(w.K), to_dev(w.V)
         self.ctx = sfi.SfiContext(w.B, w.Hq, w.Hkv, self.max_ctx, w.budget if max_budget is None else max_budget,
-                                  w.n_sink, w.recent, self.K, self.V, selector=selector, alpha=alpha, page_size=page_size)
+                                  w.n_sink, w.recent, self.K, self.V, selector=selector, alpha=alpha, page_size=page_size,
+                                  page_layout=page_layout)
         if page_size:
             sfi.sfi_set_block_table(self.ctx.handle, self.table, self.K.shape[0])
         self.out = torch.zeros(w.B, w.Hq, w.d, dtype=torch.float32, device="cuda")

@@ -148,3 +148,39 @@ def test_hot_calls_reject_bad_arguments_before_any_launch():
         assert lib.sfi_query_splits(h, C.byref(d), C.byref(f)) == OK and d.value == 0 and f.value == 0
     finally:
         assert lib.sfi_destroy(h) == OK
+
+
+def paged_cfg(**over):
+    """[blocks][Hkv][page][128] pools of 64-row blocks."""
+    c = good_cfg(page_size=64, k_stride_b=0, v_stride_b=0, k_stride_t=128, v_stride_t=128, k_stride_h=64 * 128,
+                 v_stride_h=64 * 128, k_stride_page=2 * 64 * 128, v_stride_page=2 * 64 * 128)
+    for k, v in over.items():
+        setattr(c, k, v)
+    return c
+
+
+def test_paged_config_and_block_table_validation():
+    assert sfi.sfi_workspace_bytes(paged_cfg()) == sfi.sfi_workspace_bytes(good_cfg())
+    assert sfi.sfi_workspace_bytes(paged_cfg(k_stride_page=0, v_stride_page=0, k_stride_t=256, v_stride_t=256,
+                                             k_stride_h=128, v_stride_h=128)) > 0  # [blocks][page][Hkv][128]
+    for bad in (dict(page_size=8), dict(page_size=48), dict(page_size=1 << 17), dict(k_stride_b=4096),
+                dict(k_stride_page=64 * 128 + 8), dict(v_stride_page=0), dict(v_stride_page=4 * 64 * 128),
+                dict(k_stride_page=32 * 128, v_stride_page=32 * 128), dict(k_stride_page=-128)):
+        assert sfi.sfi_workspace_bytes(paged_cfg(**bad)) == 0, bad
+    lib = sfi.load_library()
+    p = 0x20000
+    for cfg, cases in ((good_cfg(), [((p, 64, 10), EINVAL)]),          # a flat context takes no table
+                       (paged_cfg(), [((p, 63, 10), EINVAL),           # 4096 rows need 64 entries per sequence
+                                      ((p, 64, 0), EINVAL), ((p + 2, 64, 10), EALIGN),
+                                      ((p, 64, 1 << 17), EUNSUPPORTED),  # pool beyond 32-bit row offsets
+                                      ((p, 64, 1000), OK), ((None, 0, 0), OK)])):
+        h = C.c_void_p()
+        assert lib.sfi_create(C.byref(cfg), 0x10000, sfi.sfi_workspace_bytes(cfg), C.byref(h)) == OK
+        try:
+            for (tbl, stride, n_blocks), want in cases:
+                assert lib.sfi_set_block_table(h, tbl, stride, n_blocks) == want, (tbl, stride, n_blocks)
+            if cfg.page_size:  # detached: hot calls refuse to run
+                assert lib.sfi_dense_attn(h, p, p, p, p, 0, p, None) == EINVAL
+                assert lib.sfi_reorg(h, p, p, p, p, 64, p, None, p, p, C.c_int64(2 * 68 * 128), C.c_int64(68 * 128), 68, None) == EINVAL
+        finally:
+            assert lib.sfi_destroy(h) == OK

@@ -14,15 +14,15 @@ def _step(msg):
     print(f"[gpu-paged] {msg}", flush=True)
 
 
-@pytest.mark.parametrize("page", [16, 64, 512])
-def test_paged_slow_and_fast_steps(oracle, page):
+@pytest.mark.parametrize("page,layout", [(16, "thd"), (64, "thd"), (512, "thd"), (16, "htd"), (128, "htd")])
+def test_paged_slow_and_fast_steps(oracle, page, layout):
     """Slow step (dense output + Selector) and fast steps (one tile per wave and the pipelined walk) through
     the block table, ragged contexts, table entries past each context pointing at a poison block."""
     w = syn.make_tiny(L0=2500, steps=4, budget=96, recent=64, n_support=16, B=2)
     w.L0 = np.array([2500, 1203], np.int32)
-    r = Runner(w, page_size=page, ctx_max=w.L0 + 4)
+    r = Runner(w, page_size=page, ctx_max=w.L0 + 4, page_layout=layout)
     try:
-        _step(f"page {page}: slow step")
+        _step(f"page {page} {layout}: slow step")
         q0, ctx = w.q(0), w.ctx_len(0)
         out, sel, nsel = r.slow(q0, ctx, w.budget)
         check_out(out, oracle.dense(q0, w.K, w.V, ctx))
