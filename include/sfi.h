@@ -124,7 +124,8 @@ int sfi_create(const sfi_config* cfg, void* workspace, size_t workspace_bytes, s
  * [batch][table_stride]; entry [b][i] is the block of the pools that holds rows
  * [i * page_size, (i + 1) * page_size) of sequence b.  Entries that cover rows [0, ctx_len[b]) must be valid
  * at every hot call (later ones are never read); block ids lie in [0, n_blocks), and
- * n_blocks * block stride must stay below 4 GiB for K and for V (32-bit row offsets inside the kernels).  The pointer is kept until the next call of this function; the table's contents may change
+ * n_blocks * (block stride / row stride) must stay below 2^31 (row numbers are 32-bit; byte offsets into the
+ * pools are 64-bit).  The pointer is kept until the next call of this function; the table's contents may change
  * between hot calls.  With a paged cache the K and V arguments of the hot calls are the pool bases and the
  * kernels never read rows before ctx_len[b] is known.  Passing NULL detaches the table.
  */

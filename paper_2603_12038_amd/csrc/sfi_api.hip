@@ -334,9 +334,7 @@ int sfi_set_block_table(sfi_ctx* x, const int32_t* block_table, int32_t table_st
   if (misaligned(block_table, 4)) return SFI_EALIGN;
   const int64_t pages = ((int64_t)c.max_ctx + c.page_size - 1) / c.page_size;
   if (table_stride < pages || n_blocks < 1) return SFI_EINVAL;
-  if ((int64_t)n_blocks * x->page_rpb * c.k_stride_t * 2 >= ((int64_t)1 << 32) ||
-      (int64_t)n_blocks * x->page_rpb * c.v_stride_t * 2 >= ((int64_t)1 << 32))
-    return SFI_EUNSUPPORTED;
+  if ((int64_t)n_blocks * x->page_rpb >= ((int64_t)1 << 31)) return SFI_EUNSUPPORTED;  // row numbers are 32-bit
   x->table = block_table;
   x->table_stride = table_stride;
   return SFI_OK;

@@ -52,6 +52,15 @@ __device__ __forceinline__ uint4 load_row16(const char* base, uint32_t off) {
   const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + off));
   return make_uint4(v.x, v.y, v.z, v.w);
 }
+// The same with a 64-bit byte offset: block pools of a paged cache may exceed 4 GiB.
+__device__ __forceinline__ uint4 load_row16(const char* base, uint64_t off) {
+  typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + off));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+// Offset type of a row address: 32 bits for a flat cache, 64 for a paged one.
+template <bool PAGED> struct RowOff { typedef uint32_t type; };
+template <> struct RowOff<true> { typedef uint64_t type; };
 
 struct Tile {
   uint4 ka[4], kb[4];  // K rows of blocks A / B: row n, dims kblk*32 + 8*jg .. +8
@@ -112,36 +121,28 @@ __device__ __forceinline__ void issue_affine(Tile& T, const Rows& R, int r0, int
 }
 
 // Row loads of a tile with arbitrary rows: ra / rb are the cache rows of this lane's K rows in
-// blocks A / B; the V rows 4*jg + i are the ones lanes 4*jg + i resolved for K.
-__device__ __forceinline__ void issue_rows(Tile& T, const Rows& R, int ra, int rb) {
-  const uint32_t oa = (uint32_t)ra * R.k_st + R.k_lane, ob = (uint32_t)rb * R.k_st + R.k_lane;
-#pragma unroll
-  for (int kb = 0; kb < 4; ++kb) {
-    T.ka[kb] = load_row16(R.Kb, oa + kb * 64);
-    T.kb[kb] = load_row16(R.Kb, ob + kb * 64);
-  }
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    T.v[i] = load_row16(R.Vb, (uint32_t)__shfl(ra, 4 * R.jg + i) * R.v_st + R.v_lane);
-    T.v[4 + i] = load_row16(R.Vb, (uint32_t)__shfl(rb, 4 * R.jg + i) * R.v_st + R.v_lane);
-  }
-}
-
-// The same in two halves, for the pipelined gather loop.
+// blocks A / B; the V rows 4*jg + i are the ones lanes 4*jg + i resolved for K.  OffT: RowOff<>::type.
+template <typename OffT = uint32_t>
 __device__ __forceinline__ void issue_k_rows(Tile& T, const Rows& R, int ra, int rb) {
-  const uint32_t oa = (uint32_t)ra * R.k_st + R.k_lane, ob = (uint32_t)rb * R.k_st + R.k_lane;
+  const OffT oa = (OffT)(uint32_t)ra * R.k_st + R.k_lane, ob = (OffT)(uint32_t)rb * R.k_st + R.k_lane;
 #pragma unroll
   for (int kb = 0; kb < 4; ++kb) {
-    T.ka[kb] = load_row16(R.Kb, oa + kb * 64);
-    T.kb[kb] = load_row16(R.Kb, ob + kb * 64);
+    T.ka[kb] = load_row16(R.Kb, (OffT)(oa + kb * 64));
+    T.kb[kb] = load_row16(R.Kb, (OffT)(ob + kb * 64));
   }
 }
+template <typename OffT = uint32_t>
 __device__ __forceinline__ void issue_v_rows(Tile& T, const Rows& R, int ra, int rb) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    T.v[i] = load_row16(R.Vb, (uint32_t)__shfl(ra, 4 * R.jg + i) * R.v_st + R.v_lane);
-    T.v[4 + i] = load_row16(R.Vb, (uint32_t)__shfl(rb, 4 * R.jg + i) * R.v_st + R.v_lane);
+    T.v[i] = load_row16(R.Vb, (OffT)((OffT)(uint32_t)__shfl(ra, 4 * R.jg + i) * R.v_st + R.v_lane));
+    T.v[4 + i] = load_row16(R.Vb, (OffT)((OffT)(uint32_t)__shfl(rb, 4 * R.jg + i) * R.v_st + R.v_lane));
   }
+}
+template <typename OffT = uint32_t>
+__device__ __forceinline__ void issue_rows(Tile& T, const Rows& R, int ra, int rb) {
+  issue_k_rows<OffT>(T, R, ra, rb);
+  issue_v_rows<OffT>(T, R, ra, rb);
 }
 
 // Q^T operand: head n, dims kblk*32 + 8*jg .. +8; zero for heads >= G (no branch around the loads).
@@ -414,12 +415,12 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_dense_kernel(const AttnA
     const int ra = row_for(first, n), rb = row_for(first, 16 + n);
     const int pra = P.phys(ra, P.page_of(ra)), prb = P.phys(rb, P.page_of(rb));
     __builtin_amdgcn_sched_barrier(0);
-    issue_k_rows(T, R, pra, prb);
+    issue_k_rows<uint64_t>(T, R, pra, prb);
     __builtin_amdgcn_sched_barrier(0);
     pa_n = P.page_of(row_for(first + step, n));
     pb_n = P.page_of(row_for(first + step, 16 + n));
     __builtin_amdgcn_sched_barrier(0);
-    issue_v_rows(T, R, pra, prb);
+    issue_v_rows<uint64_t>(T, R, pra, prb);
     __builtin_amdgcn_sched_barrier(0);
   } else if (K > 0 && first >= nTJ) {  // short context: the first tile is a sink / recent tile after all
     issue_k_tile(first);
@@ -487,7 +488,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_dense_kernel(const AttnA
     if (PAGED) {
       pra = P.phys(row_for(t + step, n), pa_n);
       prb = P.phys(row_for(t + step, 16 + n), pb_n);
-      issue_k_rows(T, R, pra, prb);
+      issue_k_rows<uint64_t>(T, R, pra, prb);
       pa_n = P.page_of(row_for(t + 2 * step, n));
       pb_n = P.page_of(row_for(t + 2 * step, 16 + n));
     } else {
@@ -508,7 +509,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_dense_kernel(const AttnA
     bf16x8 a_hi, a_lo;
     softmax_phase(y, acc, m_run, l_run, jg, a_hi, a_lo);
     pv_phase(T, a_hi, a_lo, acc);
-    if (PAGED) issue_v_rows(T, R, pra, prb);
+    if (PAGED) issue_v_rows<uint64_t>(T, R, pra, prb);
     else issue_v_tile(t + step);
   }
   if (EXPOSE != 0) flush_stash();
@@ -644,7 +645,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_kernel(const Attn
       ra = P.phys(ra, P.page_of(ra));
       rb = P.phys(rb, P.page_of(rb));
     }
-    issue_rows(T, R, ra, rb);
+    issue_rows<typename RowOff<PAGED>::type>(T, R, ra, rb);
     if (p0 + kTile <= W.N) tile_math<false>(T, qreg, a.scale_log2, acc, m_run, l_run, jg, p0, W.N);
     else tile_math<true>(T, qreg, a.scale_log2, acc, m_run, l_run, jg, p0, W.N);
   }
@@ -722,7 +723,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(con
     ra = P.phys(ra, P.page_of(ra));
     rb = P.phys(rb, P.page_of(rb));
     __builtin_amdgcn_sched_barrier(0);
-    issue_k_rows(T, R, ra, rb);
+    issue_k_rows<typename RowOff<PAGED>::type>(T, R, ra, rb);
     __builtin_amdgcn_sched_barrier(0);
     ra_n = W.row_of(p_first + pstep + n, sA1);
     rb_n = W.row_of(p_first + pstep + 16 + n, sB1);
@@ -732,17 +733,17 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(con
     sAn = W.sel_at_nonempty(p_first + 2 * pstep + n);
     sBn = W.sel_at_nonempty(p_first + 2 * pstep + 16 + n);
     __builtin_amdgcn_sched_barrier(0);
-    issue_v_rows(T, R, ra, rb);
+    issue_v_rows<typename RowOff<PAGED>::type>(T, R, ra, rb);
     __builtin_amdgcn_sched_barrier(0);
   } else {
     const int ra = W.row_of(p_first + n, sA), rb = W.row_of(p_first + 16 + n, sB);
     __builtin_amdgcn_sched_barrier(0);  // the compiler's scheduler must not reorder the three groups
-    issue_k_rows(T, R, ra, rb);
+    issue_k_rows<typename RowOff<PAGED>::type>(T, R, ra, rb);
     __builtin_amdgcn_sched_barrier(0);
     sAn = W.sel_at_nonempty(p_first + pstep + n);
     sBn = W.sel_at_nonempty(p_first + pstep + 16 + n);
     __builtin_amdgcn_sched_barrier(0);
-    issue_v_rows(T, R, ra, rb);
+    issue_v_rows<typename RowOff<PAGED>::type>(T, R, ra, rb);
     __builtin_amdgcn_sched_barrier(0);
   }
   for (int k = 0; k < K; ++k) {
@@ -754,7 +755,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(con
     if (PAGED) {
       ra = P.phys(ra_n, pa_n);
       rb = P.phys(rb_n, pb_n);
-      issue_k_rows(T, R, ra, rb);
+      issue_k_rows<typename RowOff<PAGED>::type>(T, R, ra, rb);
       ra_n = W.row_of(pn + pstep + n, sAn);  // row 0 past the list
       rb_n = W.row_of(pn + pstep + 16 + n, sBn);
       pa_n = P.page_of(ra_n);
@@ -764,7 +765,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(con
     } else {
       ra = W.row_of(pn + n, sAn);  // row 0 past the list
       rb = W.row_of(pn + 16 + n, sBn);
-      issue_k_rows(T, R, ra, rb);
+      issue_k_rows<typename RowOff<PAGED>::type>(T, R, ra, rb);
       sAn = W.sel_at_nonempty(pn + pstep + n);
       sBn = W.sel_at_nonempty(pn + pstep + 16 + n);
     }
@@ -772,7 +773,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(con
     bf16x8 a_hi, a_lo;
     softmax_phase(y, acc, m_run, l_run, jg, a_hi, a_lo);
     pv_phase(T, a_hi, a_lo, acc);
-    issue_v_rows(T, R, ra, rb);
+    issue_v_rows<typename RowOff<PAGED>::type>(T, R, ra, rb);
   }
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
@@ -843,7 +844,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_compact_kernel(const Att
       if (PAGED) {
         const Pages P = pages_of(a, b);
         const int ra = min(rs + p0 + n, L - 1), rb = min(rs + p0 + 16 + n, L - 1);
-        issue_rows(T, R, P.phys(ra, P.page_of(ra)), P.phys(rb, P.page_of(rb)));
+        issue_rows<uint64_t>(T, R, P.phys(ra, P.page_of(ra)), P.phys(rb, P.page_of(rb)));
       } else {
         issue_affine(T, R, rs + p0, L - 1);
       }
@@ -897,8 +898,9 @@ __global__ __launch_bounds__(kAttnThreads) void reorg_kernel(const ReorgArgs a) 
       row = tbl[row >> a.page_lg] * a.page_rpb + (row & ((1 << a.page_lg) - 1));
     }
     if (ok[p]) {
-      kr[p] = load_row16(Kb, (uint32_t)row * ((uint32_t)a.k_st * 2u) + sub * 16);
-      vr[p] = load_row16(Vb, (uint32_t)row * ((uint32_t)a.v_st * 2u) + sub * 16);
+      typedef typename RowOff<PAGED>::type OffT;
+      kr[p] = load_row16(Kb, (OffT)((OffT)(uint32_t)row * ((uint32_t)a.k_st * 2u) + sub * 16));
+      vr[p] = load_row16(Vb, (OffT)((OffT)(uint32_t)row * ((uint32_t)a.v_st * 2u) + sub * 16));
     }
   }
 #pragma unroll

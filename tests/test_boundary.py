@@ -172,7 +172,7 @@ def test_paged_config_and_block_table_validation():
     for cfg, cases in ((good_cfg(), [((p, 64, 10), EINVAL)]),          # a flat context takes no table
                        (paged_cfg(), [((p, 63, 10), EINVAL),           # 4096 rows need 64 entries per sequence
                                       ((p, 64, 0), EINVAL), ((p + 2, 64, 10), EALIGN),
-                                      ((p, 64, 1 << 17), EUNSUPPORTED),  # pool beyond 32-bit row offsets
+                                      ((p, 64, 1 << 25), EUNSUPPORTED),  # more rows than a 32-bit row number addresses
                                       ((p, 64, 1000), OK), ((None, 0, 0), OK)])):
         h = C.c_void_p()
         assert lib.sfi_create(C.byref(cfg), 0x10000, sfi.sfi_workspace_bytes(cfg), C.byref(h)) == OK
