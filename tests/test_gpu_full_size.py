@@ -128,3 +128,10 @@ def test_retention_sweep_shape(oracle):
         check_out(got, oracle.sparse(q, w.K, w.V, sel, nsel, w.recent_start(0), c, w.n_sink))
     finally:
         r.close()
+
+
+def test_million_token_context(oracle):
+    """One sequence of 2^20 cached rows (B1, 4/1 heads, K = 4096, recent 512): 512 Selector segments, the
+    finest dense split, 32-bit row offsets close to their limit for this row stride."""
+    w = syn.make_long(L0=(1 << 20) - 2, steps=2, B=1, Hq=4, Hkv=1, budget=4096, recent=512, n_clusters=256)
+    _slow_then_fast(oracle, w, n_fast=1).close()
