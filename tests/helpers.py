@@ -104,7 +104,8 @@ def make_paged(K: np.ndarray, V: np.ndarray, ctx_max: np.ndarray, page: int, see
 class Runner:
     """Device copies of one workload's K/V plus an sfi context; thin wrappers over the C-ABI calls."""
 
-    def __init__(self, w, max_budget=None, selector=None, alpha=0.0, page_size=0, ctx_max=None, page_layout="thd"):
+    def __init__(self, w, max_budget=None, selector=None, alpha=0.0, page_size=0, ctx_max=None, page_layout="thd",
+                 scale=0.0):
         """page_size > 0: the cache is handed over as block pools + block table (valid up to ctx_max[b] rows,
         default every allocated row); self.K / self.V are then the pools."""
         import torch
@@ -119,8 +120,8 @@ class Runner:
         else:
             self.K, self.V = to_dev(w.K), to_dev(w.V)
         self.ctx = sfi.SfiContext(w.B, w.Hq, w.Hkv, self.max_ctx, w.budget if max_budget is None else max_budget,
-                                  w.n_sink, w.recent, self.K, self.V, selector=selector, alpha=alpha, page_size=page_size,
-                                  page_layout=page_layout)
+                                  w.n_sink, w.recent, self.K, self.V, scale=scale, selector=selector, alpha=alpha,
+                                  page_size=page_size, page_layout=page_layout)
         if page_size:
             sfi.sfi_set_block_table(self.ctx.handle, self.table, self.K.shape[0])
         self.out = torch.zeros(w.B, w.Hq, w.d, dtype=torch.float32, device="cuda")

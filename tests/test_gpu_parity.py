@@ -524,3 +524,23 @@ def test_long_recent_window_and_sink(oracle, recent, n_sink, splits):
         check_out(got, oracle.sparse(q1, w.K, w.V, sel, nsel, rs1, ctx1, w.n_sink))
     finally:
         r.close()
+
+
+@pytest.mark.parametrize("scale", [1.0, 0.35, 0.004])
+def test_logit_scales_far_from_default(oracle, scale):
+    """The config's logit scale: 1.0 makes the softmax nearly one-hot (logits of several hundred in the log2
+    domain, most weights underflow to 0), 0.004 makes it nearly uniform."""
+    w = syn.make_tiny(L0=2200, steps=2, budget=64, recent=48, n_support=12, B=2, Hq=8, Hkv=2)
+    r = Runner(w, scale=scale)
+    try:
+        _step(f"logit scale {scale}")
+        q, ctx = w.q(0), w.ctx_len(0)
+        out, sel, nsel = r.slow(q, ctx, w.budget)
+        check_out(out, oracle.dense(q, w.K, w.V, ctx, scale=scale))
+        sel_ref, nsel_ref, z = oracle.selector(q, w.K, ctx, w.budget, w.n_sink, w.recent, scale=scale)
+        check_selection(sel, nsel, sel_ref, nsel_ref, z, ctx, w.n_sink, w.recent, w.budget)
+        q1, ctx1, rs1 = w.q(1), w.ctx_len(1), w.recent_start(1)
+        got = r.fast(q1, sel, nsel, rs1, ctx1)
+        check_out(got, oracle.sparse(q1, w.K, w.V, sel, nsel, rs1, ctx1, w.n_sink, scale=scale))
+    finally:
+        r.close()
