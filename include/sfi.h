@@ -172,6 +172,23 @@ int sfi_slow_attn(sfi_ctx* ctx, const void* q, const void* K, const void* V, con
 int sfi_slow_select(sfi_ctx* ctx, const int32_t* ctx_len, int32_t max_len, int32_t budget, int32_t* sel_idx,
                     int32_t* n_sel, void* stream);
 
+/*
+ * Windowed evidence (paper Eq. window_logits and Eq. selector_mu with a window of W > 1 queries, e.g. the last
+ * W queries of a prefill block; Sec. 5 "Default SFI configuration" uses W = 1 in decode):
+ *   sfi_evidence_add     dense attention of one window query (-> out, as sfi_slow_attn) and its head-mean
+ *                        evidence (1/G) sum_g p_g^alpha over J added to this context's accumulator
+ *                        (first != 0 starts the accumulator);
+ *   sfi_evidence_select  the Selector on the accumulated evidence mu = (1/W) * sum over the n_added queries:
+ *                        mode 0 ranks mu, mode 1 takes f = mu^(1/alpha) through prior, fusion and refinements
+ *                        (key norms from the last sfi_evidence_add).  -> sel_idx, n_sel.
+ * Every added query must see the same allowed set J, i.e. the same ctx_len[] / max_len in every call (for the
+ * tail of a causal prefill block: recent >= W, so that no window query is masked anywhere in J).
+ */
+int sfi_evidence_add(sfi_ctx* ctx, const void* q, const void* K, const void* V, const int32_t* ctx_len,
+                     int32_t max_len, float* out, int32_t first, void* stream);
+int sfi_evidence_select(sfi_ctx* ctx, int32_t n_added, const int32_t* ctx_len, int32_t max_len, int32_t budget,
+                        int32_t* sel_idx, int32_t* n_sel, void* stream);
+
 /* Dense attention only (the `out` of a slow step, no Selector).  Same arguments and meaning. */
 int sfi_dense_attn(sfi_ctx* ctx, const void* q, const void* K, const void* V, const int32_t* ctx_len,
                    int32_t max_len, float* out, void* stream);

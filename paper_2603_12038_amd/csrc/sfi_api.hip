@@ -99,6 +99,7 @@ size_t carve(const sfi_config* c, char* base, Workspace* ws) {
   ws->state = (uint32_t*)take((size_t)(B * Hkv) * kStateWords * sizeof(uint32_t));
   ws->segcnt = (uint32_t*)take((size_t)(B * Hkv) * n_seg * 2 * sizeof(uint32_t));
   ws->jstat = (float2*)take((size_t)(B * Hq) * sizeof(float2));
+  ws->mu = (float*)take((size_t)(B * Hkv) * ld * sizeof(float));
   ws->prior = full ? (float*)take((size_t)(B * Hkv) * ld * sizeof(float)) : nullptr;
   ws->znms = full ? (float*)take((size_t)(B * Hkv) * ld * sizeof(float)) : nullptr;
   ws->segstat = full ? (double*)take((size_t)(B * Hkv) * n_seg * kSegStats * sizeof(double)) : nullptr;
@@ -228,6 +229,8 @@ void fill_sel(const sfi_ctx* x, SelArgs* s, const int32_t* ctx_len, const uint8_
   s->nms_radius = c.nms_radius;
   s->alpha = x->alpha;
   s->inv_alpha = 1.0f / x->alpha;
+  s->mu = x->ws.mu; s->mu_scale = 1.0f;
+  s->lg_rows = x->G + (c.selector_mode == 1 ? 1 : 0);
 }
 
 #define SFI_TRY(expr)                         \
@@ -236,7 +239,8 @@ void fill_sel(const sfi_ctx* x, SelArgs* s, const int32_t* ctx_len, const uint8_
   } while (0)
 
 // Selector kernels after a dense launch that exposed logits.
-int run_selector(sfi_ctx* x, const SelArgs& sa, int max_len, hipStream_t st) {
+// windowed: rank the accumulated evidence (sa.mu_scale set) instead of the last query's.
+int run_selector(sfi_ctx* x, const SelArgs& sa, int max_len, hipStream_t st, bool windowed = false) {
   const int B = x->cfg.batch;
   const int nJ = max_len - x->cfg.recent - x->cfg.n_sink;
   int n_seg = nJ > 0 ? (nJ + kSelSeg - 1) / kSelSeg : 1;
@@ -244,6 +248,7 @@ int run_selector(sfi_ctx* x, const SelArgs& sa, int max_len, hipStream_t st) {
   {
     StageTimer t(x, st, SFI_STAGE_SCORE);
     if (x->cfg.selector_mode == 1) SFI_TRY(launch_sel_full(sa, B, n_seg, st));
+    else if (windowed) SFI_TRY(launch_sel_finalize(sa, B, n_seg, st));
     else SFI_TRY(launch_sel_score(sa, B, n_seg, st));
     if (!t.stop()) return SFI_ELAUNCH;
   }
@@ -447,6 +452,40 @@ int sfi_slow_select(sfi_ctx* x, const int32_t* ctx_len, int32_t max_len, int32_t
   SelArgs sa;
   fill_sel(x, &sa, ctx_len, nullptr, budget, x->last_dense_splits, sel_idx, n_sel);
   return run_selector(x, sa, ml, (hipStream_t)stream);
+}
+
+int sfi_evidence_add(sfi_ctx* x, const void* q, const void* K, const void* V, const int32_t* ctx_len,
+                     int32_t max_len, float* out, int32_t first, void* stream) {
+  int rc = check_common(x, q, K, V, ctx_len, out);
+  if (rc != SFI_OK) return rc;
+  int ml;
+  if ((rc = resolve_max_len(x, max_len, &ml)) != SFI_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  CallRecord call_record(x);
+  if ((rc = slow_attn_impl(x, q, K, V, ctx_len, ml, out, st)) != SFI_OK) return rc;
+  SelArgs sa;
+  fill_sel(x, &sa, ctx_len, nullptr, 0, x->last_dense_splits, nullptr, nullptr);
+  sa.accum_first = first != 0;
+  const int nJ = ml - x->cfg.recent - x->cfg.n_sink;
+  int n_seg = nJ > 0 ? (nJ + kSelSeg - 1) / kSelSeg : 1;
+  if (n_seg > x->ws.n_seg_cap) n_seg = x->ws.n_seg_cap;
+  { StageTimer t(x, st, SFI_STAGE_SCORE); SFI_TRY(launch_sel_accum(sa, x->cfg.batch, n_seg, st)); if (!t.stop()) return SFI_ELAUNCH; }
+  return SFI_OK;
+}
+
+int sfi_evidence_select(sfi_ctx* x, int32_t n_added, const int32_t* ctx_len, int32_t max_len, int32_t budget,
+                        int32_t* sel_idx, int32_t* n_sel, void* stream) {
+  int rc = check_select(x, ctx_len, budget, sel_idx, n_sel);
+  if (rc != SFI_OK) return rc;
+  if (n_added < 1) return SFI_EINVAL;
+  int ml;
+  if ((rc = resolve_max_len(x, max_len, &ml)) != SFI_OK) return rc;
+  CallRecord call_record(x);
+  SelArgs sa;
+  fill_sel(x, &sa, ctx_len, nullptr, budget, x->last_dense_splits, sel_idx, n_sel);
+  sa.mu_scale = 1.0f / (float)n_added;
+  sa.f_from_mu = 1;
+  return run_selector(x, sa, ml, (hipStream_t)stream, true);
 }
 
 int sfi_fast_step(sfi_ctx* x, const void* q, const void* K, const void* V, const int32_t* sel_idx,

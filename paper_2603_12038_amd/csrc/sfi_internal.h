@@ -44,6 +44,7 @@ struct Workspace {
   float* prior;       // [B*Hkv][ld]  full Selector: unnormalised prior pi_kn * pi_pos
   float* znms;        // [B*Hkv][ld]  full Selector: log2-domain score after Soft-NMS
   double* segstat;    // [B*Hkv][n_seg_cap][kSegStats]  full Selector: per-segment sums for lambda*
+  float* mu;          // [B*Hkv][ld]  windowed evidence: accumulator over the window's queries
   int64_t ld_pos;     // multiple of kSelSeg
   int32_t n_seg_cap;
 };
@@ -136,6 +137,12 @@ struct SelArgs {
   float gamma, beta, p, eta, lambda_clip, alpha_soft, alpha_cross, inv_temp, eps;
   int32_t nms_radius;
   float alpha, inv_alpha;  // power-mean exponent of the evidence and its reciprocal
+  // windowed evidence
+  float* mu;               // [B*Hkv][ld] accumulator of the head-means of the window's queries
+  float mu_scale;          // 1 / number of queries added
+  int32_t accum_first;     // this query starts the accumulator
+  int32_t f_from_mu;       // full Selector: take the evidence from the accumulator
+  int32_t lg_rows;         // rows per tile of the exposed logits: G, or G + 1 with key norms
 };
 
 hipError_t launch_attn_dense(const AttnArgs& a, int B, int n_slots, hipStream_t s);
@@ -144,6 +151,8 @@ hipError_t launch_reorg(const ReorgArgs& a, int B, int rows, hipStream_t s);
 hipError_t launch_attn_gather(const AttnArgs& a, int B, int n_slots, hipStream_t s);
 hipError_t launch_merge(const MergeArgs& a, int B, hipStream_t s);
 hipError_t launch_sel_score(const SelArgs& a, int B, int n_seg, hipStream_t s);
+hipError_t launch_sel_accum(const SelArgs& a, int B, int n_seg, hipStream_t s);
+hipError_t launch_sel_finalize(const SelArgs& a, int B, int n_seg, hipStream_t s);
 hipError_t launch_sel_full(const SelArgs& a, int B, int n_seg, hipStream_t s);
 hipError_t launch_sel_cand(const SelArgs& a, int B, int n_seg, hipStream_t s);
 hipError_t launch_sel_count(const SelArgs& a, int B, int n_seg, hipStream_t s);

@@ -83,6 +83,9 @@ __device__ __forceinline__ Problem problem_of(const SelArgs& a, int b) {
 }
 
 // ---- stage 1: evidence f, its key, and the 12-bit histogram ------------------------------------
+// ACCUM: windowed evidence (Eq. selector_mu over several queries): instead of ranking, add this
+// query's head-mean to the accumulator mu (or start it, a.accum_first); sel_finalize_kernel ranks later.
+template <bool ACCUM>
 __global__ __launch_bounds__(kSelThreads) void sel_score_kernel(const SelArgs a) {
   const int seg = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
@@ -98,7 +101,8 @@ __global__ __launch_bounds__(kSelThreads) void sel_score_kernel(const SelArgs a)
 
   // logits of (b, h): tile-major, [tile of 32 positions][G heads][32].  A thread owns two quads of
   // positions, half a segment apart; for G <= 8 all its loads are issued before any is used.
-  const float* lg = a.logits + ((int64_t)(b * a.Hq + h * G)) * a.ld_pos;
+  const int rows = a.lg_rows;  // G, or G + 1 when the dense kernel also exposed the key norms
+  const float* lg = a.logits + (int64_t)bh * rows * a.ld_pos;
   uint32_t* keys = a.keys + (int64_t)bh * a.ld_pos;
   constexpr int kHalf = kSelSeg / 2;
   const int pq[2] = {p_lo + tid * 4, p_lo + kHalf + tid * 4};
@@ -109,7 +113,7 @@ __global__ __launch_bounds__(kSelThreads) void sel_score_kernel(const SelArgs a)
 #pragma unroll
       for (int g = 0; g < 8; ++g)
         lq[r][g] = (pq[r] < pb.nJ && g < G)
-                       ? *reinterpret_cast<const float4*>(lg + (int64_t)(pq[r] >> 5) * G * kTile + g * kTile + (pq[r] & 31))
+                       ? *reinterpret_cast<const float4*>(lg + (int64_t)(pq[r] >> 5) * rows * kTile + g * kTile + (pq[r] & 31))
                        : make_float4(0.f, 0.f, 0.f, 0.f);
   }
   // J-only softmax statistics of the heads of this group, left by the merge kernel:
@@ -139,7 +143,7 @@ __global__ __launch_bounds__(kSelThreads) void sel_score_kernel(const SelArgs a)
         }
       }
     } else {
-      const float* lt = lg + (int64_t)(p >> 5) * G * kTile + (p & 31);
+      const float* lt = lg + (int64_t)(p >> 5) * rows * kTile + (p & 31);
 #pragma unroll
       for (int g = 0; g < 16; ++g) {
         if (g < G) {
@@ -151,7 +155,50 @@ __global__ __launch_bounds__(kSelThreads) void sel_score_kernel(const SelArgs a)
         }
       }
     }
+    if (ACCUM) {
+      float4* mp = reinterpret_cast<float4*>(a.mu + (int64_t)bh * a.ld_pos + p);
+      float4 m4 = a.accum_first ? make_float4(0.f, 0.f, 0.f, 0.f) : *mp;
+      m4.x += f0; m4.y += f1; m4.z += f2; m4.w += f3;
+      *mp = m4;
+      continue;
+    }
     const uint4 k4 = make_uint4(__float_as_uint(f0), __float_as_uint(f1), __float_as_uint(f2), __float_as_uint(f3));
+    *reinterpret_cast<uint4*>(keys + p) = k4;
+    atomicAdd(&s_hist[k4.x >> 19], 1u);
+    if (p + 1 < pb.nJ) atomicAdd(&s_hist[k4.y >> 19], 1u);
+    if (p + 2 < pb.nJ) atomicAdd(&s_hist[k4.z >> 19], 1u);
+    if (p + 3 < pb.nJ) atomicAdd(&s_hist[k4.w >> 19], 1u);
+  }
+  if (ACCUM) return;
+  __syncthreads();
+  uint32_t* gh = a.hist1 + (int64_t)bh * kHist1Bins;
+  for (int i = tid; i < kHist1Bins; i += kSelThreads) {
+    const uint32_t c = s_hist[i];
+    if (c) atomicAdd(&gh[i], c);
+  }
+}
+
+// Windowed evidence, mode 0: the accumulated mu times 1 / (number of queries added) is the ranking value.
+__global__ __launch_bounds__(kSelThreads) void sel_finalize_kernel(const SelArgs a) {
+  const int seg = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
+  const Problem pb = problem_of(a, b);
+  const int p_lo = seg * kSelSeg;
+  if (p_lo >= pb.nJ) return;
+  const int tid = threadIdx.x;
+  const int bh = b * a.Hkv + h;
+  __shared__ uint32_t s_hist[kHist1Bins];
+  for (int i = tid; i < kHist1Bins; i += kSelThreads) s_hist[i] = 0u;
+  __syncthreads();
+  uint32_t* keys = a.keys + (int64_t)bh * a.ld_pos;
+  const float* mu = a.mu + (int64_t)bh * a.ld_pos;
+#pragma unroll
+  for (int r = 0; r < 2; ++r) {
+    const int p = p_lo + r * (kSelSeg / 2) + tid * 4;
+    if (p >= pb.nJ) continue;
+    const float4 m4 = *reinterpret_cast<const float4*>(mu + p);
+    const uint4 k4 = make_uint4(__float_as_uint(m4.x * a.mu_scale), __float_as_uint(m4.y * a.mu_scale),
+                                __float_as_uint(m4.z * a.mu_scale), __float_as_uint(m4.w * a.mu_scale));
     *reinterpret_cast<uint4*>(keys + p) = k4;
     atomicAdd(&s_hist[k4.x >> 19], 1u);
     if (p + 1 < pb.nJ) atomicAdd(&s_hist[k4.y >> 19], 1u);
@@ -226,6 +273,10 @@ __global__ __launch_bounds__(kSelThreads) void sel_prior_kernel(const SelArgs a)
         f[2] += sc[g] * fast_exp2s(al * (l4.z - sM[g]));
         f[3] += sc[g] * fast_exp2s(al * (l4.w - sM[g]));
       }
+    }
+    if (a.f_from_mu) {  // windowed evidence: mu was accumulated over the window's queries
+      const float4 m4 = *reinterpret_cast<const float4*>(a.mu + (int64_t)bh * a.ld_pos + p);
+      f[0] = m4.x * a.mu_scale; f[1] = m4.y * a.mu_scale; f[2] = m4.z * a.mu_scale; f[3] = m4.w * a.mu_scale;
     }
     if (al != 1.0f) {  // f = mu^(1/alpha) up to the normalisation done with the segment sums (Eq. selector_f)
 #pragma unroll
@@ -588,7 +639,15 @@ __global__ __launch_bounds__(kSelThreads) void sel_write_kernel(const SelArgs a)
 }
 
 hipError_t launch_sel_score(const SelArgs& a, int B, int n_seg, hipStream_t s) {
-  hipLaunchKernelGGL(sel_score_kernel, dim3(n_seg, a.Hkv, B), dim3(kSelThreads), 0, s, a);
+  hipLaunchKernelGGL(sel_score_kernel<false>, dim3(n_seg, a.Hkv, B), dim3(kSelThreads), 0, s, a);
+  return hipGetLastError();
+}
+hipError_t launch_sel_accum(const SelArgs& a, int B, int n_seg, hipStream_t s) {
+  hipLaunchKernelGGL(sel_score_kernel<true>, dim3(n_seg, a.Hkv, B), dim3(kSelThreads), 0, s, a);
+  return hipGetLastError();
+}
+hipError_t launch_sel_finalize(const SelArgs& a, int B, int n_seg, hipStream_t s) {
+  hipLaunchKernelGGL(sel_finalize_kernel, dim3(n_seg, a.Hkv, B), dim3(kSelThreads), 0, s, a);
   return hipGetLastError();
 }
 hipError_t launch_sel_full(const SelArgs& a, int B, int n_seg, hipStream_t s) {

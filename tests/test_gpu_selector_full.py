@@ -134,3 +134,44 @@ def test_power_mean_single_head_is_alpha_free(oracle):
     sel_ref, nsel_ref, z = oracle.selector(w.q(0), w.K, w.ctx_len(0), w.budget, w.n_sink, w.recent,
                                            sp=SelectorParams(alpha=0.4))
     assert (sels[0] == sels[1]).all() and (sels[1] == sel_ref).all()
+
+
+@pytest.mark.parametrize("mode,alpha,W", [(0, 1.0, 5), (0, 0.5, 3), (1, 1.0, 4), (1, 0.5, 2), (0, 1.0, 1)])
+def test_windowed_evidence(oracle, mode, alpha, W):
+    """Evidence accumulated over W window queries (Eq. selector_mu with a window): W calls of
+    sfi_evidence_add and one sfi_evidence_select against the oracle's Selector on the W * G query vectors
+    of each KV head.  Each call's `out` is that query's dense attention."""
+    import torch
+    import paper_2603_12038_amd as sfi
+    from helpers import i32_dev, to_dev
+
+    sp, d = _params(alpha=alpha)
+    if mode == 0:
+        sp, d = dataclasses.replace(sp, mode=0), None
+    w = syn.make_tiny(L0=3100, steps=8, budget=96, recent=40, n_support=16, B=2, Hq=8, Hkv=2)
+    w.L0 = np.array([3100, 1500], np.int32)
+    G = w.Hq // w.Hkv
+    r = Runner(w, selector=d, alpha=alpha)
+    try:
+        _step(f"windowed evidence mode={mode} alpha={alpha} W={W}")
+        ctx = w.ctx_len(0)
+        ctx_d = i32_dev(ctx)
+        qs = [w.q(t) for t in range(W)]
+        sel = torch.full((w.B, w.Hkv, w.budget), -7, dtype=torch.int32, device="cuda")
+        nsel = torch.full((w.B, w.Hkv), -7, dtype=torch.int32, device="cuda")
+        for t, q in enumerate(qs):
+            r.out.fill_(float("nan"))
+            sfi.sfi_evidence_add(r.ctx.handle, to_dev(q), r.K, r.V, ctx_d, 0, r.out, t == 0)
+            torch.cuda.synchronize()
+            check_out(r.out.cpu().numpy(), oracle.dense(q, w.K, w.V, ctx))
+        sfi.sfi_evidence_select(r.ctx.handle, W, ctx_d, 0, w.budget, sel, nsel)
+        torch.cuda.synchronize()
+        # the oracle's window: per KV head the W * G vectors (query tau, head g)
+        q_cat = np.empty((w.B, w.Hkv * W * G, w.d), np.uint16)
+        for h in range(w.Hkv):
+            for t in range(W):
+                q_cat[:, h * W * G + t * G:h * W * G + (t + 1) * G] = qs[t][:, h * G:(h + 1) * G]
+        sel_ref, nsel_ref, z = oracle.selector(q_cat, w.K, ctx, w.budget, w.n_sink, w.recent, sp=sp)
+        check_selection(sel.cpu().numpy(), nsel.cpu().numpy(), sel_ref, nsel_ref, z, ctx, w.n_sink, w.recent, w.budget)
+    finally:
+        r.close()
