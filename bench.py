@@ -539,7 +539,11 @@ def main():
     traffic = None  # HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one
     pmc_path = os.path.join(ROOT, "profiles", "hbm_traffic_llama8b.json")
     if os.path.exists(pmc_path) and args.workload == "llama8b" and args.ctx == 32768 and args.batch == 4:
-        traffic = json.load(open(pmc_path)).get(f"attn_{dominant}_kernel", {}).get("hbm_bytes_per_launch")
+        prof = json.load(open(pmc_path))
+        for key in (f"attn_{dominant}_stream_kernel", f"attn_{dominant}_kernel"):
+            if key in prof:
+                traffic = prof[key].get("hbm_bytes_per_launch")
+                break
     roof = {
         "bound": "hbm", "kernel": f"sfi::attn_{dominant}_kernel",
         "achieved": fast_gbs if dominant != "dense" else dense_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -548,6 +552,10 @@ def main():
         "us_per_launch": float((fast_ms[0] if dominant != "dense" else slow_ms[0]) * 1e3),
     }
     dsp, fsp = sfi.sfi_query_splits(h)
+    # fewer workgroups per pair than one tile per wave needs: the pipelined gather kernel ran
+    fast_tiles = -(-(w.n_sink + w.budget + w.recent) // 32)
+    if not compact and fsp * 4 < fast_tiles and roof["kernel"] == "sfi::attn_gather_kernel":
+        roof["kernel"] = "sfi::attn_gather_stream_kernel"
     res = {
         "metric": "decode attn tokens/s (slow+fast mix)", "value": value, "unit": "tokens/s per attention layer",
         "n_gpus": 1, "steps": K_seg, "warmup": W_seg, "ms_per_step": total_s * 1e3 / K_seg,
