@@ -171,11 +171,22 @@ int fast_splits_for(const sfi_ctx* x, int sel_stride, int* pipelined) {
   return s;
 }
 
-// The compact segment and the recent window are tiled separately (no tile straddles them).
+// The compact segment and the recent window are tiled separately (no tile straddles them); the kernel walks
+// several tiles per wave with the same pipelined loop, so the gather policy's workgroup counts apply.
 int compact_splits_for(const sfi_ctx* x, int sel_stride) {
   const int tiles = (x->cfg.n_sink + sel_stride + kTile - 1) / kTile + (x->cfg.recent + kTile - 1) / kTile;
-  const int tpw = x->fast_tiles_per_wave > 0 ? x->fast_tiles_per_wave : 1;
-  int s = (tiles + kWaves * tpw - 1) / (kWaves * tpw);
+  const int pairs = x->cfg.batch * x->cfg.n_kv_heads;
+  const int one = (tiles + kWaves - 1) / kWaves;
+  int s;
+  if (x->fast_tiles_per_wave > 0) {
+    s = (tiles + kWaves * x->fast_tiles_per_wave - 1) / (kWaves * x->fast_tiles_per_wave);
+  } else if (pairs >= x->n_cu) {
+    s = 1;
+  } else {
+    const int s1 = x->n_cu / pairs, s3 = 3 * x->n_cu / pairs;
+    s = one <= s1 ? one : (tiles >= 4 * kWaves * s3 ? s3 : s1);
+  }
+  if (s > one) s = one;
   if (s > kMaxSplits) s = kMaxSplits;
   if (s < 1) s = 1;
   return s;

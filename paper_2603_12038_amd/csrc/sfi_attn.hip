@@ -788,7 +788,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(con
 // Tiles never straddle the two segments: the compact segment ends with a ragged tile of its own.
 // ------------------------------------------------------------------------------------------------
 template <bool PAGED>  // PAGED: the recent window is read from a paged cache (the compact buffers are always flat)
-__global__ __launch_bounds__(kAttnThreads, 3) void attn_compact_kernel(const AttnArgs a) {
+__global__ __launch_bounds__(kAttnThreads, PAGED ? 2 : 3) void attn_compact_kernel(const AttnArgs a) {
   const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   if (a.is_slow != nullptr && a.is_slow[b] != 0) return;
   const int tid = threadIdx.x;
@@ -832,25 +832,46 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_compact_kernel(const Att
 #pragma unroll
   for (int e = 0; e < 8; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  for (int t = first; t < nT; t += step) {  // normally a single trip
-    int p0, N;
+  // Tile t < Tc is rows 32 t .. of the compact segment, tile t >= Tc rows rs + 32 (t - Tc) .. of the cache
+  // (clamped to L - 1, which is also what the refill past the wave's last tile reads).  The branch is
+  // wave-uniform and both sides issue the same number of loads.
+  int pra_n = 0, prb_n = 0;  // PAGED: physical rows of the recent tile whose K half was issued last
+  auto issue_k_tile = [&](int t) {
     if (t < Tc) {
-      p0 = t * kTile;
-      N = Nc;
-      if (t != first || !spec) issue_affine(T, Rc, p0, a.c_rows - 1);
+      issue_k_affine(T, Rc, t * kTile, a.c_rows - 1);
+    } else if (PAGED) {
+      const Pages P = pages_of(a, b);
+      const int ra = min(rs + (t - Tc) * kTile + n, L - 1), rb = min(rs + (t - Tc) * kTile + 16 + n, L - 1);
+      pra_n = P.phys(ra, P.page_of(ra));
+      prb_n = P.phys(rb, P.page_of(rb));
+      issue_k_rows<uint64_t>(T, R, pra_n, prb_n);
     } else {
-      p0 = (t - Tc) * kTile;
-      N = Nr;
-      if (PAGED) {
-        const Pages P = pages_of(a, b);
-        const int ra = min(rs + p0 + n, L - 1), rb = min(rs + p0 + 16 + n, L - 1);
-        issue_rows<uint64_t>(T, R, P.phys(ra, P.page_of(ra)), P.phys(rb, P.page_of(rb)));
-      } else {
-        issue_affine(T, R, rs + p0, L - 1);
-      }
+      issue_k_affine(T, R, rs + (t - Tc) * kTile, L - 1);
     }
-    if (p0 + kTile <= N) tile_math<false>(T, qreg, a.scale_log2, acc, m_run, l_run, jg, p0, N);
-    else tile_math<true>(T, qreg, a.scale_log2, acc, m_run, l_run, jg, p0, N);
+  };
+  auto issue_v_tile = [&](int t) {
+    if (t < Tc) issue_v_affine(T, Rc, t * kTile, a.c_rows - 1);
+    else if (PAGED) issue_v_rows<uint64_t>(T, R, pra_n, prb_n);
+    else issue_v_affine(T, R, rs + (t - Tc) * kTile, L - 1);
+  };
+  const int K = first < nT ? (nT - first + step - 1) / step : 0;
+  if (K > 0 && !(spec && first < Tc)) {  // the first tile is not the compact tile requested up front
+    issue_k_tile(first);
+    issue_v_tile(first);
+  }
+  // the dense kernel's loop: K half refilled after S^T, V half after P V
+  for (int k = 0; k < K; ++k) {
+    const int t = first + k * step;
+    const int p0 = (t < Tc ? t : t - Tc) * kTile;
+    const int N = t < Tc ? Nc : Nr;
+    float y[8];
+    qk_phase(T, qreg, a.scale_log2, y);
+    issue_k_tile(t + step);
+    if (p0 + kTile > N) mask_tail(T, y, jg, p0, N);
+    bf16x8 a_hi, a_lo;
+    softmax_phase(y, acc, m_run, l_run, jg, a_hi, a_lo);
+    pv_phase(T, a_hi, a_lo, acc);
+    issue_v_tile(t + step);
   }
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
