@@ -339,7 +339,7 @@ int sfi_create(const sfi_config* cfg, void* workspace, size_t workspace_bytes, s
     x->n_cu = prop.multiProcessorCount;
   else
     (void)hipGetLastError();  // no device here: keep the MI355X default
-  x->dense_target_wgs = 2 * x->n_cu;
+  x->dense_target_wgs = x->n_cu;
   x->fast_tiles_per_wave = 0;
   *out = x;
   return SFI_OK;
