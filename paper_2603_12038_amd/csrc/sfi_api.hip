@@ -135,12 +135,11 @@ void set_dense_bounds(const sfi_ctx* x, AttnArgs* a, int max_len) {
   a->row_cap = max_len - 1;
 }
 
-// Gather launch geometry (found by sweeps).  With at least one (b, h) pair per compute unit: one workgroup
-// per pair, which then finishes the softmax itself (no merge).  Otherwise, if one tile per wave needs no
-// more than one workgroup per compute unit: that, with the one-tile kernel.  Otherwise the pipelined
-// kernel: three workgroups per compute unit when that still leaves every wave four tiles or more (long
-// lists, bandwidth-bound), else one workgroup per compute unit with a few tiles per wave (short lists,
-// latency-bound: 2.7 % faster than one tile per wave at the llama8b-shaped workload).
+// Gather launch geometry (found by sweeps): one workgroup per compute unit is a sharp optimum on this chip,
+// for short lists (latency-bound) and long ones (bandwidth-bound) alike.  With at least one (b, h) pair per
+// compute unit: one workgroup per pair, which then finishes the softmax itself (no merge).  Otherwise, if
+// one tile per wave needs no more than one workgroup per compute unit: that, with the one-tile kernel.
+// Otherwise n_cu / pairs workgroups per pair and the pipelined kernel.
 // fast_tiles_per_wave > 0 overrides: 1 = one tile per wave, t > 1 = pipelined with about t tiles per wave.
 int fast_splits_for(const sfi_ctx* x, int sel_stride, int* pipelined) {
   const int rows = x->cfg.n_sink + sel_stride + x->cfg.recent;
@@ -155,12 +154,12 @@ int fast_splits_for(const sfi_ctx* x, int sel_stride, int* pipelined) {
     s = 1;
     *pipelined = 1;
   } else {
-    const int s1 = x->n_cu / pairs, s3 = 3 * x->n_cu / pairs;
+    const int s1 = x->n_cu / pairs;
     if (one <= s1) {
       s = one;
       *pipelined = 0;
     } else {
-      s = tiles >= 4 * kWaves * s3 ? s3 : s1;
+      s = s1;
       *pipelined = 1;
     }
   }
@@ -183,8 +182,8 @@ int compact_splits_for(const sfi_ctx* x, int sel_stride) {
   } else if (pairs >= x->n_cu) {
     s = 1;
   } else {
-    const int s1 = x->n_cu / pairs, s3 = 3 * x->n_cu / pairs;
-    s = one <= s1 ? one : (tiles >= 4 * kWaves * s3 ? s3 : s1);
+    const int s1 = x->n_cu / pairs;
+    s = one <= s1 ? one : s1;
   }
   if (s > one) s = one;
   if (s > kMaxSplits) s = kMaxSplits;
