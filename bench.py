@@ -28,6 +28,7 @@ sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBS = 8000.0
+FAST_MERGE = {None: 0, "kernel": 1, "launch": 2}  # sfi_set_tuning codes
 
 # Fixed-schedule workloads (one slow step every `seg` decode steps).  Default: the Llama-3-8B-shaped layer.
 # layers: virtual layers, chosen so that one round of fast steps over all layers moves more than the 256 MB
@@ -102,8 +103,8 @@ def bench_serving(args):
     max_ctx = int(w.L_alloc)
     ctx = sfi.SfiContext(B, Hq, Hkv, max_ctx, w.budget, w.n_sink, w.recent, Ks[0], Vs[0])
     h = ctx.handle
-    if args.dense_wgs or args.fast_tpw:
-        sfi.sfi_set_tuning(h, args.dense_wgs, args.fast_tpw)
+    if args.dense_wgs or args.fast_tpw or args.fast_merge:
+        sfi.sfi_set_tuning(h, args.dense_wgs, args.fast_tpw, FAST_MERGE[args.fast_merge])
     q_all = torch.randn(n_dec + SEG, NL, B, Hq, d, device=dev, generator=gen).to(torch.bfloat16)
     outs = [torch.zeros(B, Hq, d, dtype=torch.float32, device=dev) for _ in range(NL)]
     sels = [torch.full((B, Hkv, w.budget), -1, dtype=torch.int32, device=dev) for _ in range(NL)]
@@ -202,8 +203,8 @@ def bench_retention(args):
     max_budget = L - R - n_sink
     ctx = sfi.SfiContext(B, Hq, Hkv, L, max_budget, n_sink, R, Ks[0], Vs[0])
     h = ctx.handle
-    if args.dense_wgs or args.fast_tpw:
-        sfi.sfi_set_tuning(h, args.dense_wgs, args.fast_tpw)
+    if args.dense_wgs or args.fast_tpw or args.fast_merge:
+        sfi.sfi_set_tuning(h, args.dense_wgs, args.fast_tpw, FAST_MERGE[args.fast_merge])
     q = torch.randn(B, Hq, d, device=dev, generator=gen).to(torch.bfloat16)
     out = torch.zeros(B, Hq, d, dtype=torch.float32, device=dev)
     ctx_d = i32_dev(np.full(B, L))
@@ -279,6 +280,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--dense-wgs", type=int, default=0)
     ap.add_argument("--fast-tpw", type=int, default=0)
+    ap.add_argument("--fast-merge", choices=["kernel", "launch"], default=None,
+                    help="merge of a fast step's split records: inside the attention kernel (default) or in a launch of its own")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (no collectives, no sharding); run with --gpus 1",
@@ -367,9 +370,9 @@ def main():
         for c in ring:
             sfi.sfi_set_block_table(c.handle, table_d, n_blocks)
     aux = torch.cuda.Stream() if use_async else None  # default priority
-    if args.dense_wgs or args.fast_tpw:
+    if args.dense_wgs or args.fast_tpw or args.fast_merge:
         for c in ring:
-            sfi.sfi_set_tuning(c.handle, args.dense_wgs, args.fast_tpw)
+            sfi.sfi_set_tuning(c.handle, args.dense_wgs, args.fast_tpw, FAST_MERGE[args.fast_merge])
     gen = torch.Generator(device=dev)
     gen.manual_seed(1234)
     q_all = torch.randn(n_dec + SEG, NL, B, Hq, d, device=dev, generator=gen).to(torch.bfloat16)
@@ -566,7 +569,8 @@ def main():
                    "step": f"{SEG} decode steps (1 slow + {SEG - 1} fast) x {NL} virtual layers",
                    "virtual_layers": NL, "launch": args.launch, "fast_path": args.fast_path, "selector_mode": args.selector_mode, "page_size": args.page_size, "page_layout": args.page_layout if args.page_size else None,
                    "slow_schedule": args.slow_schedule + (f" (ring {len(ring)})" if use_async else ""),
-                   "dense_splits": dsp, "fast_splits": fsp},
+                   "dense_splits": dsp, "fast_splits": fsp,
+                   "fast_merge": args.fast_merge or "kernel"},
         "roofline": roof,
         "kernels": {
             "dense_attn": {"us": slow_ms[0] * 1e3, "kv_bytes": dense_bytes, "GBps": dense_gbs,

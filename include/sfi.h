@@ -284,14 +284,17 @@ enum {
 int sfi_set_profiling(sfi_ctx* ctx, int max_calls);
 int sfi_stage_times(sfi_ctx* ctx, float* ms_sum /* host, [SFI_N_STAGES] */, int32_t* count /* host, [SFI_N_STAGES] */);
 
-/* Launch-geometry knobs for sweeps (values <= 0 keep the current setting):
- * dense_target_wgs     workgroups a dense launch aims for in total (default 2 per compute unit: all
+/* Launch knobs for sweeps (values <= 0 keep the current setting):
+ * dense_target_wgs     workgroups a dense launch aims for in total (default one per compute unit: all
  *                      resident at once, one round of equal shares);
  * fast_tiles_per_wave  32-row tiles each wave of the gather launch gets.  Default: decided per launch --
- *                      one tile per wave while that fits the chip in about one round of workgroups,
- *                      otherwise few workgroups per (sequence, KV head) and a pipelined loop over
- *                      several tiles per wave. */
-int sfi_set_tuning(sfi_ctx* ctx, int32_t dense_target_wgs, int32_t fast_tiles_per_wave);
+ *                      one tile per wave while that fits the chip in one round of workgroups,
+ *                      otherwise one workgroup per compute unit and a pipelined loop over several
+ *                      tiles per wave;
+ * fast_merge           how the split records of a fast step become the output: 1 (default) inside the
+ *                      attention kernel, by the last workgroup of each (sequence, KV head) to finish;
+ *                      2 in a merge launch of its own.  Other values > 2: SFI_EINVAL. */
+int sfi_set_tuning(sfi_ctx* ctx, int32_t dense_target_wgs, int32_t fast_tiles_per_wave, int32_t fast_merge);
 
 /* Launch geometry of the last call (for reports): split workgroups per (sequence, KV head). */
 int sfi_query_splits(const sfi_ctx* ctx, int32_t* dense_splits, int32_t* fast_splits);

@@ -93,7 +93,7 @@ def load_library() -> C.CDLL:
     lib.sfi_stage_times.restype = C.c_int
     lib.sfi_stage_times.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
     lib.sfi_set_tuning.restype = C.c_int
-    lib.sfi_set_tuning.argtypes = [vp, i32, i32]
+    lib.sfi_set_tuning.argtypes = [vp, i32, i32, i32]
     lib.sfi_query_splits.restype = C.c_int
     lib.sfi_query_splits.argtypes = [vp, C.POINTER(i32), C.POINTER(i32)]
     _lib = lib
@@ -227,8 +227,8 @@ def sfi_stage_times(ctx):
     return [float(x) for x in ms], [int(x) for x in cnt]
 
 
-def sfi_set_tuning(ctx, dense_target_wgs: int = 0, fast_tiles_per_wave: int = 0) -> None:
-    _check(load_library().sfi_set_tuning(ctx, dense_target_wgs, fast_tiles_per_wave), "sfi_set_tuning")
+def sfi_set_tuning(ctx, dense_target_wgs: int = 0, fast_tiles_per_wave: int = 0, fast_merge: int = 0) -> None:
+    _check(load_library().sfi_set_tuning(ctx, dense_target_wgs, fast_tiles_per_wave, fast_merge), "sfi_set_tuning")
 
 
 def sfi_query_splits(ctx) -> Tuple[int, int]:

@@ -18,6 +18,7 @@ struct sfi_ctx {
   int table_stride, page_lg, page_rpb;
   int dense_target_wgs;     // workgroups the dense launch aims for
   int fast_tiles_per_wave;  // 32-row tiles each wave of the gather launch should get; 0 = decided per launch
+  int tail_merge;           // split fast-step launches merge in the attention kernel (no merge launch)
   int last_dense_splits, last_fast_splits;
   // profiling: a ring of event pairs, one set of stages per hot call, read back in one go so that
   // no host synchronisation sits between the profiled calls
@@ -99,6 +100,7 @@ size_t carve(const sfi_config* c, char* base, Workspace* ws) {
   ws->segcnt = (uint32_t*)take((size_t)(B * Hkv) * n_seg * 2 * sizeof(uint32_t));
   ws->jstat = (float2*)take((size_t)(B * Hq) * sizeof(float2));
   ws->mu = (float*)take((size_t)(B * Hkv) * ld * sizeof(float));
+  ws->arrive = (uint32_t*)take((size_t)(B * Hkv) * sizeof(uint32_t));
   ws->prior = full ? (float*)take((size_t)(B * Hkv) * ld * sizeof(float)) : nullptr;
   ws->znms = full ? (float*)take((size_t)(B * Hkv) * ld * sizeof(float)) : nullptr;
   ws->segstat = full ? (double*)take((size_t)(B * Hkv) * n_seg * kSegStats * sizeof(double)) : nullptr;
@@ -340,6 +342,11 @@ int sfi_create(const sfi_config* cfg, void* workspace, size_t workspace_bytes, s
     (void)hipGetLastError();  // no device here: keep the MI355X default
   x->dense_target_wgs = x->n_cu;
   x->fast_tiles_per_wave = 0;
+  x->tail_merge = 1;
+  // the arrival counters of split fast-step launches start at zero (and every launch leaves them there)
+  if (hipMemset(ws.arrive, 0, (size_t)cfg->batch * cfg->n_kv_heads * sizeof(uint32_t)) != hipSuccess ||
+      hipDeviceSynchronize() != hipSuccess)
+    (void)hipGetLastError();  // no device here: nothing will be launched either
   *out = x;
   return SFI_OK;
 }
@@ -523,8 +530,9 @@ int sfi_fast_step(sfi_ctx* x, const void* q, const void* K, const void* V, const
   a.n_split = fast_splits_for(x, sel_stride, &a.pipelined);
   x->last_fast_splits = a.n_split;
   if (a.n_split == 1) a.out_direct = out;  // one workgroup per pair finishes the softmax itself
+  else if (x->tail_merge) { a.out_merge = out; a.arrive = x->ws.arrive; }
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_gather(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
-  if (a.n_split == 1) return SFI_OK;
+  if (a.n_split == 1 || a.out_merge != nullptr) return SFI_OK;
   MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1, nullptr, 0, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
@@ -592,8 +600,9 @@ int sfi_fast_step_compact(sfi_ctx* x, const void* q, const void* Kc, const void*
   a.n_split = compact_splits_for(x, sel_stride);
   x->last_fast_splits = a.n_split;
   if (a.n_split == 1) a.out_direct = out;
+  else if (x->tail_merge) { a.out_merge = out; a.arrive = x->ws.arrive; }
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_compact(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
-  if (a.n_split == 1) return SFI_OK;
+  if (a.n_split == 1 || a.out_merge != nullptr) return SFI_OK;
   MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1, nullptr, 0, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
@@ -704,10 +713,11 @@ int sfi_stage_times(sfi_ctx* x, float* ms_sum, int32_t* count) {
   return SFI_OK;
 }
 
-int sfi_set_tuning(sfi_ctx* x, int32_t dense_target_wgs, int32_t fast_tiles_per_wave) {
-  if (x == nullptr) return SFI_EINVAL;
+int sfi_set_tuning(sfi_ctx* x, int32_t dense_target_wgs, int32_t fast_tiles_per_wave, int32_t fast_merge) {
+  if (x == nullptr || fast_merge > 2) return SFI_EINVAL;
   if (dense_target_wgs > 0) x->dense_target_wgs = dense_target_wgs;
   if (fast_tiles_per_wave > 0) x->fast_tiles_per_wave = fast_tiles_per_wave;
+  if (fast_merge > 0) x->tail_merge = fast_merge == 1;
   return SFI_OK;
 }
 

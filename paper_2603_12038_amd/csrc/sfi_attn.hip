@@ -285,6 +285,76 @@ __device__ __forceinline__ void tile_math(Tile& T, const bf16x8 (&qreg)[4], floa
   pv_phase(T, a_hi, a_lo, acc);
 }
 
+// Device-scope accesses: visible to / from every compute unit of the device whatever L2 it sits behind,
+// without a fence (records that one workgroup hands to another inside a launch).
+__device__ __forceinline__ void store_device(float* p, float v) {
+  __hip_atomic_store(reinterpret_cast<uint32_t*>(p), __float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store_device2(float* p, float v0, float v1) {  // 8-byte aligned
+  const uint64_t u = (uint64_t)__float_as_uint(v0) | ((uint64_t)__float_as_uint(v1) << 32);
+  __hip_atomic_store(reinterpret_cast<uint64_t*>(p), u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float2 load_device2(const float* p) {  // 8-byte aligned
+  const uint64_t u = __hip_atomic_load(reinterpret_cast<const uint64_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return make_float2(__uint_as_float((uint32_t)u), __uint_as_float((uint32_t)(u >> 32)));
+}
+
+// Merge inside the attention kernel.  Called by every thread of every workgroup of a (b, h) pair after
+// the workgroup's record went out in device-scope stores.  Every thread waits for its stores to be
+// acknowledged, then one thread counts the workgroup in on *arrive.  The workgroup that finds all
+// n_wgs - 1 others there before it merges the pair's n_wgs records per head with device-scope loads:
+//   out[b, head, :] = sum_s 2^(m_s - M) acc_s / sum_s 2^(m_s - M) l_s,
+// and puts the counter back to zero.  Nothing waits on anything, and no cache is written back or
+// invalidated as a whole (a device-scope fence costs tens of microseconds here).
+// One thread per (head, four output dims); records eight at a time, all loads of the eight in flight.
+__device__ __forceinline__ void finish_pair(const float* part, int64_t head0, int G, int n_wgs, uint32_t* arrive,
+                                            float* out) {
+  const int tid = threadIdx.x;
+  __shared__ uint32_t s_before;
+  // s_waitcnt vmcnt(0): a workgroup barrier by itself only orders the stores within the compute unit
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  __syncthreads();
+  if (tid == 0) s_before = __hip_atomic_fetch_add(arrive, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __syncthreads();
+  if (s_before != (uint32_t)(n_wgs - 1)) return;
+  if (tid == 0) __hip_atomic_store(arrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  for (int idx = tid; idx < G * (kHeadDim / 4); idx += kAttnThreads) {
+    const int hh = idx >> 5, c = idx & 31;
+    const float* P = part + (head0 + hh) * kSlotCap * kPartStride;
+    float M = kNeg, Z = 0.f;
+    float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s0 = 0; s0 < n_wgs; s0 += 8) {
+      float2 ml[8], ra[8], rb[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float* rec = P + (int64_t)min(s0 + i, n_wgs - 1) * kPartStride;
+        ml[i] = load_device2(rec);
+        ra[i] = load_device2(rec + 4 + 4 * c);
+        rb[i] = load_device2(rec + 6 + 4 * c);
+      }
+      float Mn = M;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        if (s0 + i >= n_wgs) ml[i] = make_float2(kNeg, 0.f);
+        Mn = fmaxf(Mn, ml[i].x);
+      }
+      const float f = fast_exp2(M - Mn);
+      Z *= f;
+      o.x *= f; o.y *= f; o.z *= f; o.w *= f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float wgt = fast_exp2(ml[i].x - Mn);
+        Z += wgt * ml[i].y;
+        o.x += wgt * ra[i].x; o.y += wgt * ra[i].y; o.z += wgt * rb[i].x; o.w += wgt * rb[i].y;
+      }
+      M = Mn;
+    }
+    const float inv = Z > 0.f ? 1.0f / Z : 0.f;
+    *reinterpret_cast<float4*>(out + (head0 + hh) * kHeadDim + 4 * c) =
+        make_float4(o.x * inv, o.y * inv, o.z * inv, o.w * inv);
+  }
+}
+
 // record of (b, head, slot): { max of y, sum 2^(y - max), -, -, O[128] }, written by one wave
 __device__ __forceinline__ void write_wave_record(float* part, int64_t head0, int G, int wslot, const f32x4 (&acc)[8],
                                                   float m_run, float l_run, int lane) {
@@ -390,7 +460,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_dense_kernel(const AttnA
     const int r_s = min(xs < nS ? xs : xs + d_rs, r_last);
     return t < nTJ ? min(xj, rJ_max) : r_s;
   };
-  auto issue_k_tile = [&](int t) {
+  auto issue_k_tile = [&](Tile& T, int t) {
     const uint32_t oa = (uint32_t)row_for(t, n) * R.k_st + R.k_lane;
     const uint32_t ob = (uint32_t)row_for(t, 16 + n) * R.k_st + R.k_lane;
 #pragma unroll
@@ -399,7 +469,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_dense_kernel(const AttnA
       T.kb[kb] = load_row16(R.Kb, ob + kb * 64);
     }
   };
-  auto issue_v_tile = [&](int t) {
+  auto issue_v_tile = [&](Tile& T, int t) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       T.v[i] = load_row16(R.Vb, (uint32_t)row_for(t, 4 * jg + i) * R.v_st + R.v_lane);
@@ -423,8 +493,17 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_dense_kernel(const AttnA
     issue_v_rows<uint64_t>(T, R, pra, prb);
     __builtin_amdgcn_sched_barrier(0);
   } else if (K > 0 && first >= nTJ) {  // short context: the first tile is a sink / recent tile after all
-    issue_k_tile(first);
-    issue_v_tile(first);
+    issue_k_tile(T, first);
+    issue_v_tile(T, first);
+  }
+  // A flat cache keeps two tiles in flight per wave: the second buffer takes the wave's second tile now.
+  Tile T2;
+  constexpr int NB = PAGED ? 1 : 2;  // tile buffers; a tile's refill is the wave's tile NB further on
+  if (!PAGED) {
+    __builtin_amdgcn_sched_barrier(0);
+    issue_k_tile(T2, first + step);
+    issue_v_tile(T2, first + step);
+    __builtin_amdgcn_sched_barrier(0);
   }
 
   float m_run = kNeg, l_run = 0.f;
@@ -465,12 +544,12 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_dense_kernel(const AttnA
     write_wave_record(a.part, head0, G, wslot, acc, m_run, lr, lane);
   };
 
-  // One loop for all of the wave's tiles, one tile buffer: the K half is refilled with the next
-  // tile's rows as soon as the logits are out, the V half as soon as P V is done, so rows are on
-  // their way during most of a tile's math.  The refill is unconditional -- past the wave's last
-  // tile it degenerates to re-reading row L - 1 -- so that no branch surrounds a load and every
-  // wait can name exactly the loads it needs.
-  for (int k = 0; k < K; ++k) {
+  // One loop for all of the wave's tiles.  A tile buffer's K half is refilled with the rows of the
+  // tile that uses the buffer next as soon as the logits are out, its V half as soon as P V is done,
+  // so rows are on their way during all of the math (with two buffers, a whole tile more than with
+  // one).  The refill is unconditional -- past the wave's last tile it degenerates to re-reading row
+  // L - 1 -- so that no branch surrounds a load and every wait can name exactly the loads it needs.
+  auto tile_step = [&](Tile& T, int k) {
     const int t = first + k * step;
     const bool inJ = k < KJ;
     if (k == KJ) {  // the J tiles are done (or there were none): close the J record, start the other one
@@ -492,7 +571,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_dense_kernel(const AttnA
       pa_n = P.page_of(row_for(t + 2 * step, n));
       pb_n = P.page_of(row_for(t + 2 * step, 16 + n));
     } else {
-      issue_k_tile(t + step);
+      issue_k_tile(T, t + NB * step);
     }
     if (EXPOSE != 0 && inJ) {  // positions past |J| land in the padding of the last tile, never used
       float* st = stash + n_stashed * (rows_exp * kTile);
@@ -510,7 +589,20 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_dense_kernel(const AttnA
     softmax_phase(y, acc, m_run, l_run, jg, a_hi, a_lo);
     pv_phase(T, a_hi, a_lo, acc);
     if (PAGED) issue_v_rows<uint64_t>(T, R, pra, prb);
-    else issue_v_tile(t + step);
+    else issue_v_tile(T, t + NB * step);
+  };
+  if (PAGED) {
+    for (int k = 0; k < K; ++k) tile_step(T, k);
+  } else {
+    // (an odd last tile is taken after the loop: a way out of the middle of the loop body would put a
+    // path from the first buffer's refill straight to its next use into the flow graph, and the waits
+    // would be placed for that path)
+    int k = 0;
+    for (; k + 1 < K; k += 2) {
+      tile_step(T, k);
+      tile_step(T2, k + 1);
+    }
+    if (k < K) tile_step(T, k);
   }
   if (EXPOSE != 0) flush_stash();
   // the record still open: the J record if the wave had no other tile (slot first), else the record of
@@ -518,12 +610,13 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_dense_kernel(const AttnA
   write_record(K == KJ ? first : n_waves + (first + KJ * step - nTJ));
 }
 
-// The four waves of a workgroup fold their running states into one record (b, head, slot):
-// { max of y, sum 2^(y - max), -, -, O[128] }.  l_run must already be summed over the row groups.
 // With out != nullptr the workgroup is the only one of its (b, h) pair: it writes the normalised
 // attention output O / l straight to out[b, head, :] and no record (no merge kernel follows).
+// With out_merge != nullptr the record goes out in device-scope stores and the pair's last workgroup to
+// finish merges the records into out_merge[b, head, :] (finish_pair; no merge kernel follows).
 __device__ __forceinline__ void write_wg_record(float* part, int64_t head0, int G, int slot, const f32x4 (&acc)[8],
-                                                float m_run, float l_run, float* out) {
+                                                float m_run, float l_run, float* out, float* out_merge = nullptr,
+                                                uint32_t* arrive = nullptr, int n_split = 1) {
   const int tid = threadIdx.x;
   const int lane = tid & 63, w = tid >> 6;
   const int jg = lane >> 4, n = lane & 15;
@@ -566,12 +659,15 @@ __device__ __forceinline__ void write_wg_record(float* part, int64_t head0, int 
     return;
   }
   const int64_t rec0 = (head0 * kSlotCap + slot) * kPartStride;
+  const bool tail = out_merge != nullptr;  // block-uniform
   for (int idx = tid; idx < G * kHeadDim; idx += kAttnThreads) {
     const int hh = idx >> 7, dim = idx & 127;
     float s = s_red[0][hh][dim];
 #pragma unroll
     for (int ww = 1; ww < kWaves; ++ww) s += s_red[ww][hh][dim];
-    part[rec0 + (int64_t)hh * kSlotCap * kPartStride + 4 + dim] = s;
+    float* dst = part + rec0 + (int64_t)hh * kSlotCap * kPartStride + 4 + dim;
+    if (tail) store_device(dst, s);
+    else *dst = s;
   }
   if (tid < G) {
     float M = s_m[0][tid];
@@ -581,8 +677,13 @@ __device__ __forceinline__ void write_wg_record(float* part, int64_t head0, int 
 #pragma unroll
     for (int ww = 0; ww < kWaves; ++ww) ls += s_l[ww][tid] * fast_exp2(s_m[ww][tid] - M);
     float* r = part + rec0 + (int64_t)tid * kSlotCap * kPartStride;
-    *reinterpret_cast<float2*>(r) = make_float2(M, ls);
+    if (tail) {
+      store_device2(r, M, ls);
+    } else {
+      *reinterpret_cast<float2*>(r) = make_float2(M, ls);
+    }
   }
+  if (tail) finish_pair(part, head0, G, n_split, arrive, out_merge);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -651,7 +752,8 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_kernel(const Attn
   }
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
-  write_wg_record(a.part, head0, G, slot, acc, m_run, l_run, a.out_direct);
+  write_wg_record(a.part, head0, G, slot, acc, m_run, l_run, a.out_direct, a.out_merge,
+                  a.arrive != nullptr ? a.arrive + bh : nullptr, a.n_split);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -777,7 +879,8 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(con
   }
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
-  write_wg_record(a.part, head0, G, slot, acc, m_run, l_run, a.out_direct);
+  write_wg_record(a.part, head0, G, slot, acc, m_run, l_run, a.out_direct, a.out_merge,
+                  a.arrive != nullptr ? a.arrive + bh : nullptr, a.n_split);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -875,7 +978,8 @@ __global__ __launch_bounds__(kAttnThreads, PAGED ? 2 : 3) void attn_compact_kern
   }
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
-  write_wg_record(a.part, head0, G, slot, acc, m_run, l_run, a.out_direct);
+  write_wg_record(a.part, head0, G, slot, acc, m_run, l_run, a.out_direct, a.out_merge,
+                  a.arrive != nullptr ? a.arrive + bh : nullptr, a.n_split);
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -45,6 +45,7 @@ struct Workspace {
   float* znms;        // [B*Hkv][ld]  full Selector: log2-domain score after Soft-NMS
   double* segstat;    // [B*Hkv][n_seg_cap][kSegStats]  full Selector: per-segment sums for lambda*
   float* mu;          // [B*Hkv][ld]  windowed evidence: accumulator over the window's queries
+  uint32_t* arrive;   // [B*Hkv]  workgroups of a split fast-step launch that have written their record
   int64_t ld_pos;     // multiple of kSelSeg
   int32_t n_seg_cap;
 };
@@ -65,6 +66,9 @@ struct AttnArgs {
   int32_t with_knorm;            // dense mode: also expose the squared key norms (full Selector)
   int32_t pipelined;             // gather mode: few workgroups per (b, h), each wave walks several tiles
   float* out_direct;             // gather / compact mode with n_split == 1: write the output here, no record
+  float* out_merge;              // gather / compact mode, nullptr or: the pair's last workgroup to finish merges
+  uint32_t* arrive;              //   the pair's records into out_merge; arrive[b * Hkv + h] counts the finished
+                                 //   workgroups of the pair (zero between launches)
   const int32_t* table;          // paged cache: block table [B][table_stride], logical page -> block of the pool
   int64_t table_stride;
   int32_t page_lg;               // log2 of the page size in rows

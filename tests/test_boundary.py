@@ -148,7 +148,9 @@ def test_hot_calls_reject_bad_arguments_before_any_launch():
         assert lib.sfi_advance(h, None, p, None) == EINVAL
         assert lib.sfi_stage_times(h, None, None) == EINVAL
         assert lib.sfi_set_profiling(h, -1) == EINVAL
-        assert lib.sfi_set_tuning(None, 1, 1) == EINVAL
+        assert lib.sfi_set_tuning(None, 1, 1, 0) == EINVAL
+        assert lib.sfi_set_tuning(h, 0, 0, 3) == EINVAL
+        assert lib.sfi_set_tuning(h, 0, 0, 2) == OK
         d, f = C.c_int32(-1), C.c_int32(-1)
         assert lib.sfi_query_splits(h, C.byref(d), C.byref(f)) == OK and d.value == 0 and f.value == 0
     finally:

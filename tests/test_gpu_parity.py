@@ -544,3 +544,34 @@ def test_logit_scales_far_from_default(oracle, scale):
         check_out(got, oracle.sparse(q1, w.K, w.V, sel, nsel, rs1, ctx1, w.n_sink, scale=scale))
     finally:
         r.close()
+
+
+@pytest.mark.parametrize("merge", [1, 2])
+def test_fast_step_merge_in_kernel_and_in_its_own_launch(oracle, tiny, merge):
+    """Both ways of merging a fast step's split records, on calls in a row whose lists differ in length
+    (the number of workgroups per pair changes from call to call; the arrival counters of the in-kernel
+    merge must come back to zero every time)."""
+    w, r = tiny
+    r.sfi.sfi_set_tuning(r.ctx.handle, 0, 0, merge)
+    try:
+        q = w.q(6)
+        for case, (L, ns) in enumerate([(1500, 96), (1500, 3), (700, 40), (1500, 96), (69, 1), (1200, 64)]):
+            _step(f"fast merge mode {merge}: L={L} n_sel={ns}")
+            ctx = np.array([L, max(1, L - 5)], np.int32)
+            rs = np.maximum(np.minimum(w.n_sink, ctx), ctx - w.recent).astype(np.int32)
+            room = np.maximum(0, rs - w.n_sink)
+            nsel = np.minimum(ns, room)[:, None].repeat(w.Hkv, axis=1).astype(np.int32)
+            sel = syn.random_sel(500 + case, w.B, w.Hkv, max(ns, 1), nsel, w.n_sink, rs)
+            got = r.fast(q, sel, nsel, rs, ctx)
+            check_out(got, oracle.sparse(q, w.K, w.V, sel, nsel, rs, ctx, w.n_sink))
+            assert r.sfi.sfi_query_splits(r.ctx.handle)[1] >= 1
+        # the compact path shares the merge
+        q0, ctx0 = w.q(0), w.ctx_len(0)
+        _, sel, nsel = r.slow(q0, ctx0, w.budget)
+        r.reorg(sel, nsel, ctx0)
+        for t in range(1, 3):
+            qt, ctx_t, rs = w.q(t), w.ctx_len(t), w.recent_start(t)
+            got = r.fast_compact(qt, nsel, sel.shape[2], rs, ctx_t)
+            check_out(got, oracle.sparse(qt, w.K, w.V, sel, nsel, rs, ctx_t, w.n_sink))
+    finally:
+        r.sfi.sfi_set_tuning(r.ctx.handle, 0, 0, 1)
