@@ -415,7 +415,7 @@ namespace {
 // First half of a slow step: dense attention with the evidence (y over J, Selector state cleared,
 // J-only softmax statistics) left in the workspace.
 int slow_attn_impl(sfi_ctx* x, const void* q, const void* K, const void* V, const int32_t* ctx_len, int ml,
-                   float* out, hipStream_t st) {
+                   float* out, hipStream_t st, bool merge_later = false) {
   AttnArgs a;
   fill_attn(x, &a, q, K, V, ctx_len);
   a.n_split = dense_splits_for(x, ml, false);
@@ -426,6 +426,7 @@ int slow_attn_impl(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   a.state = x->ws.state;
   x->last_dense_splits = a.n_split;
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
+  if (merge_later) return SFI_OK;  // the Selector's scoring launch merges
   MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, a.n_split * kWaves, 0, 0, x->ws.jstat, a.n_split * kWaves, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
@@ -449,9 +450,16 @@ int sfi_slow_step(sfi_ctx* x, const void* q, const void* K, const void* V, const
   if ((rc = resolve_max_len(x, max_len, &ml)) != SFI_OK) return rc;
   hipStream_t st = (hipStream_t)stream;
   CallRecord call_record(x);
-  if ((rc = slow_attn_impl(x, q, K, V, ctx_len, ml, out, st)) != SFI_OK) return rc;
+  // mode 0: the merge rides in the scoring launch (one launch less on the step's critical path)
+  const bool merge_in_score = x->cfg.selector_mode == 0;
+  if ((rc = slow_attn_impl(x, q, K, V, ctx_len, ml, out, st, merge_in_score)) != SFI_OK) return rc;
   SelArgs sa;
   fill_sel(x, &sa, ctx_len, nullptr, budget, x->last_dense_splits, sel_idx, n_sel);
+  if (merge_in_score) {
+    sa.part = x->ws.part;
+    sa.merge_out = out;
+    sa.n_jrec = x->last_dense_splits * kWaves;
+  }
   return run_selector(x, sa, ml, st);
 }
 

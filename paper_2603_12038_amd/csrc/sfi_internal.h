@@ -147,6 +147,11 @@ struct SelArgs {
   int32_t accum_first;     // this query starts the accumulator
   int32_t f_from_mu;       // full Selector: take the evidence from the accumulator
   int32_t lg_rows;         // rows per tile of the exposed logits: G, or G + 1 with key norms
+  // slow step in one go, mode 0: the scoring launch also merges the dense kernel's records (one more
+  // workgroup per query head) and takes the J-only softmax statistics from the record headers itself
+  const float* part;       // nullptr: a merge launch has run, jstat is valid
+  float* merge_out;
+  int32_t n_jrec;          // dense records that cover J (one per wave of the dense launch)
 };
 
 hipError_t launch_attn_dense(const AttnArgs& a, int B, int n_slots, hipStream_t s);

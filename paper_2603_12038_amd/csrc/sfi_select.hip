@@ -14,6 +14,7 @@
 // threshold and the lowest-index keys equal to it.  Integer atomics only count, so the result
 // does not depend on scheduling.
 #include "sfi_internal.h"
+#include "sfi_merge.h"
 
 namespace sfi {
 
@@ -90,11 +91,52 @@ __global__ __launch_bounds__(kSelThreads) void sel_score_kernel(const SelArgs a)
   const int seg = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
   const Problem pb = problem_of(a, b);
-  const int p_lo = seg * kSelSeg;
-  if (p_lo >= pb.nJ) return;
   const int tid = threadIdx.x;
   const int bh = b * a.Hkv + h;
   const int G = a.G;
+  const bool fused = !ACCUM && a.part != nullptr;  // grid-uniform
+  if (fused && seg >= (int)gridDim.x - G) {
+    // the G extra workgroups of (b, h): each merges the dense kernel's records of one head into the
+    // attention output (J records of all waves, then one record per wave that owned sink / recent tiles)
+    const int L = a.ctx_len[b];
+    const int nS = min(a.n_sink, L);
+    const int rs = min(max(a.n_sink, L - a.recent), L);
+    const int nTS = (nS + (L - rs) + 31) / 32;
+    const int n_slots = a.n_jrec + min(a.n_jrec, nTS);
+    merge_records(a.part, a.merge_out, b * a.Hq + h * G + (seg - ((int)gridDim.x - G)), n_slots, nullptr, 0, G, a.alpha);
+    return;
+  }
+  const int p_lo = seg * kSelSeg;
+  if (p_lo >= pb.nJ) return;
+
+  __shared__ float s_jM[16], s_jc[16];
+  if (fused) {
+    // J-only softmax statistics of the group's heads from the headers of the J records: one wave per
+    // head, a lane takes records lane, lane + 64, ... (at most kSlotCap = 256 of them)
+    const int lane = tid & 63;
+    for (int g = tid >> 6; g < G; g += kSelThreads / 64) {
+      const float* P = a.part + (int64_t)(b * a.Hq + h * G + g) * kSlotCap * kPartStride;
+      float2 ml[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int sl = lane + 64 * i;
+        ml[i] = sl < a.n_jrec ? *reinterpret_cast<const float2*>(P + (int64_t)sl * kPartStride) : make_float2(kNeg, 0.f);
+      }
+      float M = fmaxf(fmaxf(ml[0].x, ml[1].x), fmaxf(ml[2].x, ml[3].x));
+#pragma unroll
+      for (int d = 32; d >= 1; d >>= 1) M = fmaxf(M, __shfl_xor(M, d));
+      float Z = 0.f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) Z += ml[i].y * fast_exp2s(ml[i].x - M);
+#pragma unroll
+      for (int d = 32; d >= 1; d >>= 1) Z += __shfl_xor(Z, d);
+      if (lane == 0) {
+        const float zpow = a.alpha == 1.0f ? Z : fast_exp2s(a.alpha * __builtin_amdgcn_logf(Z));
+        s_jM[g] = M;
+        s_jc[g] = 1.0f / ((float)G * zpow);
+      }
+    }
+  }
 
   __shared__ uint32_t s_hist[kHist1Bins];
   for (int i = tid; i < kHist1Bins; i += kSelThreads) s_hist[i] = 0u;
@@ -120,13 +162,22 @@ __global__ __launch_bounds__(kSelThreads) void sel_score_kernel(const SelArgs a)
   // f(j) = sum_g c_g 2^(y_g(j) - M_g) with (M_g, c_g) = jstat[head g]
   const float al = a.alpha;  // mu(j) = sum_g sc[g] 2^(alpha (y_g(j) - sM[g]))  (Eq. selector_mu)
   float sM[16], sc[16];
+  if (!fused) {
 #pragma unroll
-  for (int g = 0; g < 16; ++g) {
-    const float2 t = g < G ? a.jstat[b * a.Hq + h * G + g] : make_float2(0.f, 0.f);
-    sM[g] = t.x;
-    sc[g] = t.y;
+    for (int g = 0; g < 16; ++g) {
+      const float2 t = g < G ? a.jstat[b * a.Hq + h * G + g] : make_float2(0.f, 0.f);
+      sM[g] = t.x;
+      sc[g] = t.y;
+    }
   }
-  __syncthreads();  // histogram cleared
+  __syncthreads();  // histogram cleared, statistics in place
+  if (fused) {
+#pragma unroll
+    for (int g = 0; g < 16; ++g) {
+      sM[g] = g < G ? s_jM[g] : 0.f;
+      sc[g] = g < G ? s_jc[g] : 0.f;
+    }
+  }
 #pragma unroll
   for (int r = 0; r < 2; ++r) {
     const int p = pq[r];
@@ -639,7 +690,8 @@ __global__ __launch_bounds__(kSelThreads) void sel_write_kernel(const SelArgs a)
 }
 
 hipError_t launch_sel_score(const SelArgs& a, int B, int n_seg, hipStream_t s) {
-  hipLaunchKernelGGL(sel_score_kernel<false>, dim3(n_seg, a.Hkv, B), dim3(kSelThreads), 0, s, a);
+  // with the merge on board: one more workgroup per query head
+  hipLaunchKernelGGL(sel_score_kernel<false>, dim3(n_seg + (a.part != nullptr ? a.G : 0), a.Hkv, B), dim3(kSelThreads), 0, s, a);
   return hipGetLastError();
 }
 hipError_t launch_sel_accum(const SelArgs& a, int B, int n_seg, hipStream_t s) {
