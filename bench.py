@@ -170,7 +170,7 @@ def bench_serving(args):
                                f"k{w.budget} R{w.recent} sink{w.n_sink}, per-sequence slow gaps ~ Geometric(1/20)",
                    "step": f"{SEG} decode steps (sfi_mixed_step) x {NL} virtual layers", "virtual_layers": NL,
                    "launch": "graph", "slow_sequence_steps_in_timed_region": n_slow},
-        "roofline": {"bound": "hbm", "kernel": "sfi::attn_gather_kernel (all-fast step)", "achieved": fast_gbs,
+        "roofline": {"bound": "hbm", "kernel": "sfi::attn_gather_stream_kernel (all-fast step)", "achieved": fast_gbs,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": fast_gbs / HBM_PEAK_GBS, "traffic": None,
                      "algorithmic_bytes_per_launch": fast_bytes, "us_per_launch": gather_us},
         "whole_run_kv_GBps": kv / wall / 1e9, "whole_run_frac_of_8TBps": kv / wall / 1e9 / HBM_PEAK_GBS,
@@ -525,8 +525,25 @@ def main():
         sfi.sfi_set_profiling(h, 0)
         return np.array(ms_sum) / np.maximum(np.array(cnt), 1)
 
+    def stream_avg_ms(fn, reps):
+        """Average duration of a call whose work is one kernel: two events around reps x NL launches in a row
+        on the launch stream (what the kernel costs inside a stream of dependent kernels, as a trace shows it)."""
+        for l in range(NL):
+            fn(l, step_p)
+        ea, eb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ea.record()
+        for r in range(reps):
+            for l in range(NL):
+                fn(l, step_p + r)
+        eb.record()
+        torch.cuda.synchronize()
+        return ea.elapsed_time(eb) / (reps * NL)
+
     slow_ms = stage_avg_ms(slow, 2)
     fast_ms = stage_avg_ms(fast, 8)
+    fast_bracketed_us = float(fast_ms[0] * 1e3)
+    if fast_ms[1] == 0.0:  # the fast step is a single kernel (merge on board): time it without the event pair per launch
+        fast_ms[0] = stream_avg_ms(fast, 8)
     L_mid = L0 + step_p
     dense_bytes = B * Hkv * L_mid * d * 2 * 2
     nsel_mean = float(torch.stack(nsels).float().mean())
@@ -576,7 +593,8 @@ def main():
             "dense_attn": {"us": slow_ms[0] * 1e3, "kv_bytes": dense_bytes, "GBps": dense_gbs,
                            "frac_of_8TBps": dense_gbs / HBM_PEAK_GBS},
             f"{fast_kernel}_attn": {"us": fast_ms[0] * 1e3, "kv_bytes": fast_bytes, "GBps": fast_gbs,
-                            "frac_of_8TBps": fast_gbs / HBM_PEAK_GBS},
+                            "frac_of_8TBps": fast_gbs / HBM_PEAK_GBS,
+                            "us_with_an_event_pair_per_launch": fast_bracketed_us},
             "slow_step_stage_us": {n: float(slow_ms[i] * 1e3) for i, n in enumerate(sfi.binding.STAGE_NAMES)
                                    if i < 6 or (compact and n == "reorg")},
             "fast_step_stage_us": {n: float(fast_ms[i] * 1e3) for i, n in enumerate(sfi.binding.STAGE_NAMES[:2])},
