@@ -648,15 +648,30 @@ int sfi_mixed_step(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   f.sel_stride = budget;
   f.n_split = fast_splits_for(x, budget, &f.pipelined);
   if (f.n_split == 1) f.out_direct = out;
+  else if (x->tail_merge) { f.out_merge = out; f.arrive = x->ws.arrive; }  // slow sequences' workgroups never arrive
   x->last_fast_splits = f.n_split;
+  // Fast sequences finish inside the gather launch unless their split records need the merge launch;
+  // slow sequences are merged by the scoring launch in mode 0 (as in sfi_slow_step).  Only when one
+  // of the two is not so does the merge kernel run (for both kinds: it skips what is already done).
+  const bool fast_done = f.n_split == 1 || f.out_merge != nullptr;
+  const bool merge_in_score = x->cfg.selector_mode == 0 && fast_done;
   // the gather part reads last segment's sel rows of fast sequences; the Selector below only
   // rewrites rows of slow sequences, so the order of the two attention launches is free.
   { StageTimer t(x, st, SFI_STAGE_ATTN2); SFI_TRY(launch_attn_gather(f, x->cfg.batch, f.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(d, x->cfg.batch, d.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
-  MergeArgs m{x->ws.part, out, is_slow, x->cfg.n_q_heads, d.n_split * kWaves, f.n_split == 1 ? 0 : f.n_split, 2, x->ws.jstat, d.n_split * kWaves, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha};
-  { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
+  if (!merge_in_score) {
+    MergeArgs m{x->ws.part, out, is_slow, x->cfg.n_q_heads, d.n_split * kWaves, fast_done ? 0 : f.n_split, 2, x->ws.jstat, d.n_split * kWaves, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha};
+    StageTimer t(x, st, SFI_STAGE_MERGE);
+    SFI_TRY(launch_merge(m, x->cfg.batch, st));
+    if (!t.stop()) return SFI_ELAUNCH;
+  }
   SelArgs sa;
   fill_sel(x, &sa, ctx_len, is_slow, budget, d.n_split, sel_idx, n_sel);
+  if (merge_in_score) {
+    sa.part = x->ws.part;
+    sa.merge_out = out;
+    sa.n_jrec = d.n_split * kWaves;
+  }
   return run_selector(x, sa, ml, st);
 }
 

@@ -575,3 +575,24 @@ def test_fast_step_merge_in_kernel_and_in_its_own_launch(oracle, tiny, merge):
             check_out(got, oracle.sparse(qt, w.K, w.V, sel, nsel, rs, ctx_t, w.n_sink))
     finally:
         r.sfi.sfi_set_tuning(r.ctx.handle, 0, 0, 1)
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(4, 1), (6, 2), (16, 1)])
+def test_fast_step_many_split_workgroups(oracle, Hq, Hkv):
+    """Long index lists over one or two (b, h) pairs: 10, 24, 32 and 63 (the cap) split workgroups per pair, so
+    the in-kernel merge walks its records in several groups of eight, the last one ragged; G = 4, 3 and 16
+    (two rounds of output threads).  The last list is shorter again: the arrival counters must be back at zero."""
+    w = syn.make_tiny(L0=9000, steps=1, budget=8100, recent=64, n_support=8, B=1, Hq=Hq, Hkv=Hkv)
+    r = Runner(w)
+    try:
+        q, ctx, rs = w.q(0), w.ctx_len(0), w.recent_start(0)
+        for case, (ns, want) in enumerate([(1100, 10), (3000, 24), (4000, 32), (8100, 63), (300, 3)]):
+            _step(f"fast step with {want} split workgroups per pair, G={Hq // Hkv}")
+            nsel = np.full((w.B, w.Hkv), ns, np.int32)
+            nsel[0, -1] = ns - 7
+            sel = syn.random_sel(700 + case, w.B, w.Hkv, ns, nsel, w.n_sink, rs)
+            got = r.fast(q, sel, nsel, rs, ctx)
+            assert r.sfi.sfi_query_splits(r.ctx.handle)[1] == want
+            check_out(got, oracle.sparse(q, w.K, w.V, sel, nsel, rs, ctx, w.n_sink))
+    finally:
+        r.close()
