@@ -56,6 +56,38 @@ def test_llama8b_shaped_layer(oracle):
         r.close()
 
 
+def test_in_kernel_merge_never_reads_a_stale_record(oracle):
+    """Config 2 shape, 8 split workgroups per pair on all compute units: 600 fast steps in a row alternating
+    between two queries and two index sets.  Every output must be bit-identical to the first output of its
+    query (checked against the oracle): a record left over from the launch before, read in place of a fresh
+    one, would belong to the other query."""
+    import torch
+    w = syn.make_llama8b(steps=4)
+    r = Runner(w)
+    try:
+        ctx, rs = w.ctx_len(1), w.recent_start(1)
+        ctx_d, rs_d = i32_dev(ctx), i32_dev(rs)
+        cases = []
+        for k in range(2):
+            q = w.q(1 + k)
+            nsel = np.full((w.B, w.Hkv), w.budget - 5 * k, np.int32)
+            sel = syn.random_sel(900 + k, w.B, w.Hkv, w.budget, nsel, w.n_sink, rs)
+            ref = r.fast(q, sel, nsel, rs, ctx)
+            check_out(ref, oracle.sparse(q, w.K, w.V, sel, nsel, rs, ctx, w.n_sink))
+            cases.append((to_dev(q), i32_dev(sel), i32_dev(nsel), torch.from_numpy(ref).cuda()))
+        assert r.sfi.sfi_query_splits(r.ctx.handle)[1] == 8
+        _step("600 alternating fast steps, in-kernel merge")
+        outs = [torch.empty_like(cases[0][3]) for _ in range(600)]
+        for i, o in enumerate(outs):
+            qd, sd, nd, _ = cases[i & 1]
+            r.sfi.sfi_fast_step(r.ctx.handle, qd, r.K, r.V, sd, nd, w.budget, rs_d, ctx_d, o)
+        torch.cuda.synchronize()
+        for i, o in enumerate(outs):
+            assert torch.equal(o, cases[i & 1][3]), f"launch {i} differs from the first output of its query"
+    finally:
+        r.close()
+
+
 def test_long_single_stream(oracle):
     """Config 3: B1, 32/8 heads, ctx 131072, clustered support, K = 4096, recent 256."""
     w = syn.make_long(steps=4)
