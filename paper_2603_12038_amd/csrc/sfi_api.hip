@@ -450,16 +450,13 @@ int sfi_slow_step(sfi_ctx* x, const void* q, const void* K, const void* V, const
   if ((rc = resolve_max_len(x, max_len, &ml)) != SFI_OK) return rc;
   hipStream_t st = (hipStream_t)stream;
   CallRecord call_record(x);
-  // mode 0: the merge rides in the scoring launch (one launch less on the step's critical path)
-  const bool merge_in_score = x->cfg.selector_mode == 0;
-  if ((rc = slow_attn_impl(x, q, K, V, ctx_len, ml, out, st, merge_in_score)) != SFI_OK) return rc;
+  // no merge launch: the merge rides in the Selector's first launch (one launch less on the step's critical path)
+  if ((rc = slow_attn_impl(x, q, K, V, ctx_len, ml, out, st, true)) != SFI_OK) return rc;
   SelArgs sa;
   fill_sel(x, &sa, ctx_len, nullptr, budget, x->last_dense_splits, sel_idx, n_sel);
-  if (merge_in_score) {
-    sa.part = x->ws.part;
-    sa.merge_out = out;
-    sa.n_jrec = x->last_dense_splits * kWaves;
-  }
+  sa.part = x->ws.part;
+  sa.merge_out = out;
+  sa.n_jrec = x->last_dense_splits * kWaves;
   return run_selector(x, sa, ml, st);
 }
 
@@ -651,10 +648,10 @@ int sfi_mixed_step(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   else if (x->tail_merge) { f.out_merge = out; f.arrive = x->ws.arrive; }  // slow sequences' workgroups never arrive
   x->last_fast_splits = f.n_split;
   // Fast sequences finish inside the gather launch unless their split records need the merge launch;
-  // slow sequences are merged by the scoring launch in mode 0 (as in sfi_slow_step).  Only when one
-  // of the two is not so does the merge kernel run (for both kinds: it skips what is already done).
+  // slow sequences are merged by the first scoring launch (as in sfi_slow_step).  The merge kernel only
+  // runs when the in-kernel merge is switched off (for both kinds: it skips what is already done).
   const bool fast_done = f.n_split == 1 || f.out_merge != nullptr;
-  const bool merge_in_score = x->cfg.selector_mode == 0 && fast_done;
+  const bool merge_in_score = fast_done;
   // the gather part reads last segment's sel rows of fast sequences; the Selector below only
   // rewrites rows of slow sequences, so the order of the two attention launches is free.
   { StageTimer t(x, st, SFI_STAGE_ATTN2); SFI_TRY(launch_attn_gather(f, x->cfg.batch, f.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }

@@ -83,6 +83,48 @@ __device__ __forceinline__ Problem problem_of(const SelArgs& a, int b) {
   return p;
 }
 
+// The slow step without a merge launch (SelArgs::part != nullptr).  The launch that reads the exposed
+// logits first carries G extra workgroups per (b, h); each merges the dense kernel's records of one
+// query head into the attention output (J records of all waves, then one record per wave that owned
+// sink / recent tiles).
+__device__ __forceinline__ void merge_head(const SelArgs& a, int b, int h, int g) {
+  const int L = a.ctx_len[b];
+  const int nS = min(a.n_sink, L);
+  const int rs = min(max(a.n_sink, L - a.recent), L);
+  const int nTS = (nS + (L - rs) + 31) / 32;
+  const int n_slots = a.n_jrec + min(a.n_jrec, nTS);
+  merge_records(a.part, a.merge_out, b * a.Hq + h * a.G + g, n_slots, nullptr, 0, a.G, a.alpha);
+}
+
+// ... and every other workgroup takes the J-only softmax statistics of the group's heads from the
+// headers of the J records itself: one wave per head, a lane takes records lane, lane + 64, ... (at
+// most kSlotCap = 256).  sM[g] = max of y over J, sc[g] = Z^(-alpha) / G; valid after the next barrier.
+__device__ __forceinline__ void group_jstat(const SelArgs& a, int b, int h, float* sM, float* sc) {
+  const int lane = threadIdx.x & 63;
+  for (int g = threadIdx.x >> 6; g < a.G; g += kSelThreads / 64) {
+    const float* P = a.part + (int64_t)(b * a.Hq + h * a.G + g) * kSlotCap * kPartStride;
+    float2 ml[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int sl = lane + 64 * i;
+      ml[i] = sl < a.n_jrec ? *reinterpret_cast<const float2*>(P + (int64_t)sl * kPartStride) : make_float2(kNeg, 0.f);
+    }
+    float M = fmaxf(fmaxf(ml[0].x, ml[1].x), fmaxf(ml[2].x, ml[3].x));
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) M = fmaxf(M, __shfl_xor(M, d));
+    float Z = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) Z += ml[i].y * fast_exp2s(ml[i].x - M);
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) Z += __shfl_xor(Z, d);
+    if (lane == 0) {
+      const float zpow = a.alpha == 1.0f ? Z : fast_exp2s(a.alpha * __builtin_amdgcn_logf(Z));
+      sM[g] = M;
+      sc[g] = 1.0f / ((float)a.G * zpow);
+    }
+  }
+}
+
 // ---- stage 1: evidence f, its key, and the 12-bit histogram ------------------------------------
 // ACCUM: windowed evidence (Eq. selector_mu over several queries): instead of ranking, add this
 // query's head-mean to the accumulator mu (or start it, a.accum_first); sel_finalize_kernel ranks later.
@@ -96,47 +138,14 @@ __global__ __launch_bounds__(kSelThreads) void sel_score_kernel(const SelArgs a)
   const int G = a.G;
   const bool fused = !ACCUM && a.part != nullptr;  // grid-uniform
   if (fused && seg >= (int)gridDim.x - G) {
-    // the G extra workgroups of (b, h): each merges the dense kernel's records of one head into the
-    // attention output (J records of all waves, then one record per wave that owned sink / recent tiles)
-    const int L = a.ctx_len[b];
-    const int nS = min(a.n_sink, L);
-    const int rs = min(max(a.n_sink, L - a.recent), L);
-    const int nTS = (nS + (L - rs) + 31) / 32;
-    const int n_slots = a.n_jrec + min(a.n_jrec, nTS);
-    merge_records(a.part, a.merge_out, b * a.Hq + h * G + (seg - ((int)gridDim.x - G)), n_slots, nullptr, 0, G, a.alpha);
+    merge_head(a, b, h, seg - ((int)gridDim.x - G));
     return;
   }
   const int p_lo = seg * kSelSeg;
   if (p_lo >= pb.nJ) return;
 
   __shared__ float s_jM[16], s_jc[16];
-  if (fused) {
-    // J-only softmax statistics of the group's heads from the headers of the J records: one wave per
-    // head, a lane takes records lane, lane + 64, ... (at most kSlotCap = 256 of them)
-    const int lane = tid & 63;
-    for (int g = tid >> 6; g < G; g += kSelThreads / 64) {
-      const float* P = a.part + (int64_t)(b * a.Hq + h * G + g) * kSlotCap * kPartStride;
-      float2 ml[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int sl = lane + 64 * i;
-        ml[i] = sl < a.n_jrec ? *reinterpret_cast<const float2*>(P + (int64_t)sl * kPartStride) : make_float2(kNeg, 0.f);
-      }
-      float M = fmaxf(fmaxf(ml[0].x, ml[1].x), fmaxf(ml[2].x, ml[3].x));
-#pragma unroll
-      for (int d = 32; d >= 1; d >>= 1) M = fmaxf(M, __shfl_xor(M, d));
-      float Z = 0.f;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) Z += ml[i].y * fast_exp2s(ml[i].x - M);
-#pragma unroll
-      for (int d = 32; d >= 1; d >>= 1) Z += __shfl_xor(Z, d);
-      if (lane == 0) {
-        const float zpow = a.alpha == 1.0f ? Z : fast_exp2s(a.alpha * __builtin_amdgcn_logf(Z));
-        s_jM[g] = M;
-        s_jc[g] = 1.0f / ((float)G * zpow);
-      }
-    }
-  }
+  if (fused) group_jstat(a, b, h, s_jM, s_jc);
 
   __shared__ uint32_t s_hist[kHist1Bins];
   for (int i = tid; i < kHist1Bins; i += kSelThreads) s_hist[i] = 0u;
@@ -287,19 +296,29 @@ __global__ __launch_bounds__(kSelThreads) void sel_prior_kernel(const SelArgs a)
   const int seg = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
   const Problem pb = problem_of(a, b);
+  const int G = a.G, rows = G + 1;
+  const bool fused = a.part != nullptr;  // grid-uniform: no merge launch has run
+  if (fused && seg >= (int)gridDim.x - G) {
+    merge_head(a, b, h, seg - ((int)gridDim.x - G));
+    return;
+  }
   const int p_lo = seg * kSelSeg;
   if (p_lo >= pb.nJ) return;
   const int tid = threadIdx.x;
   const int bh = b * a.Hkv + h;
-  const int G = a.G, rows = G + 1;
   const float* lg = a.logits + (int64_t)bh * rows * a.ld_pos;  // [tile][G heads + key norms][32]
   float* fbuf = reinterpret_cast<float*>(a.keys) + (int64_t)bh * a.ld_pos;
   float* prior = a.prior + (int64_t)bh * a.ld_pos;
   const float al = a.alpha;  // mu(j) = sum_g sc[g] 2^(alpha (y_g(j) - sM[g]))  (Eq. selector_mu)
+  __shared__ float s_jM[16], s_jc[16];
+  if (fused) {
+    group_jstat(a, b, h, s_jM, s_jc);
+    __syncthreads();
+  }
   float sM[16], sc[16];
 #pragma unroll
   for (int g = 0; g < 16; ++g) {
-    const float2 t = g < G ? a.jstat[b * a.Hq + h * G + g] : make_float2(0.f, 0.f);
+    const float2 t = g >= G ? make_float2(0.f, 0.f) : fused ? make_float2(s_jM[g], s_jc[g]) : a.jstat[b * a.Hq + h * G + g];
     sM[g] = t.x;
     sc[g] = t.y;
   }
@@ -703,7 +722,7 @@ hipError_t launch_sel_finalize(const SelArgs& a, int B, int n_seg, hipStream_t s
   return hipGetLastError();
 }
 hipError_t launch_sel_full(const SelArgs& a, int B, int n_seg, hipStream_t s) {
-  hipLaunchKernelGGL(sel_prior_kernel, dim3(n_seg, a.Hkv, B), dim3(kSelThreads), 0, s, a);
+  hipLaunchKernelGGL(sel_prior_kernel, dim3(n_seg + (a.part != nullptr ? a.G : 0), a.Hkv, B), dim3(kSelThreads), 0, s, a);
   hipLaunchKernelGGL(sel_fuse_kernel, dim3(n_seg, a.Hkv, B), dim3(kSelThreads), 0, s, a);
   hipLaunchKernelGGL(sel_cross_kernel, dim3(n_seg, a.Hkv, B), dim3(kSelThreads), 0, s, a);
   return hipGetLastError();
