@@ -112,7 +112,7 @@ size_t carve(const sfi_config* c, char* base, Workspace* ws) {
 inline bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
 
 // Split workgroups per (sequence, KV head) of a dense launch.  All sequences dense: aim at
-// dense_target_wgs workgroups in total (two per compute unit by default: every workgroup resident at
+// dense_target_wgs workgroups in total (one per compute unit by default: every workgroup resident at
 // once, one round, equal shares of the prefix, sink and recent rows included).  Mixed step:
 // the host cannot know how many sequences are slow, so take the finest split; workgroups of fast
 // sequences exit at once.
@@ -239,7 +239,7 @@ void fill_sel(const sfi_ctx* x, SelArgs* s, const int32_t* ctx_len, const uint8_
   s->ctx_len = ctx_len; s->is_slow = is_slow; s->sel_idx = sel_idx; s->n_sel = n_sel;
   s->ld_pos = x->ws.ld_pos; s->n_seg_cap = x->ws.n_seg_cap;
   s->Hq = c.n_q_heads; s->Hkv = c.n_kv_heads; s->G = x->G;
-  s->n_sink = c.n_sink; s->recent = c.recent; s->n_split = n_split * kWaves; s->budget = budget;
+  s->n_sink = c.n_sink; s->recent = c.recent; s->n_jrec = n_split * kWaves; s->budget = budget;
   s->prior = x->ws.prior; s->znms = x->ws.znms; s->segstat = x->ws.segstat;
   s->gamma = c.gamma; s->beta = c.beta; s->p = c.p; s->eta = c.eta; s->lambda_clip = c.lambda_clip;
   s->alpha_soft = c.alpha_soft; s->alpha_cross = c.alpha_cross;
@@ -456,7 +456,6 @@ int sfi_slow_step(sfi_ctx* x, const void* q, const void* K, const void* V, const
   fill_sel(x, &sa, ctx_len, nullptr, budget, x->last_dense_splits, sel_idx, n_sel);
   sa.part = x->ws.part;
   sa.merge_out = out;
-  sa.n_jrec = x->last_dense_splits * kWaves;
   return run_selector(x, sa, ml, st);
 }
 
@@ -667,7 +666,6 @@ int sfi_mixed_step(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   if (merge_in_score) {
     sa.part = x->ws.part;
     sa.merge_out = out;
-    sa.n_jrec = d.n_split * kWaves;
   }
   return run_selector(x, sa, ml, st);
 }

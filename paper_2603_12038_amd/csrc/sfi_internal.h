@@ -133,7 +133,8 @@ struct SelArgs {
   int32_t* n_sel;
   int64_t ld_pos;
   int32_t n_seg_cap;
-  int32_t Hq, Hkv, G, n_sink, recent, n_split, budget;
+  int32_t Hq, Hkv, G, n_sink, recent, budget;
+  int32_t n_jrec;          // dense records that cover J (one per wave of the dense launch)
   // full Selector (mode 1)
   float* prior;
   float* znms;
@@ -151,7 +152,6 @@ struct SelArgs {
   // workgroup per query head) and takes the J-only softmax statistics from the record headers itself
   const float* part;       // nullptr: a merge launch has run, jstat is valid
   float* merge_out;
-  int32_t n_jrec;          // dense records that cover J (one per wave of the dense launch)
 };
 
 hipError_t launch_attn_dense(const AttnArgs& a, int B, int n_slots, hipStream_t s);
