@@ -284,17 +284,24 @@ enum {
 int sfi_set_profiling(sfi_ctx* ctx, int max_calls);
 int sfi_stage_times(sfi_ctx* ctx, float* ms_sum /* host, [SFI_N_STAGES] */, int32_t* count /* host, [SFI_N_STAGES] */);
 
-/* Launch knobs for sweeps (values <= 0 keep the current setting):
- * dense_target_wgs     workgroups a dense launch aims for in total (default one per compute unit: all
- *                      resident at once, one round of equal shares);
- * fast_tiles_per_wave  32-row tiles each wave of the gather launch gets.  Default: decided per launch --
- *                      one tile per wave while that fits the chip in one round of workgroups,
- *                      otherwise one workgroup per compute unit and a pipelined loop over several
- *                      tiles per wave;
+/* Launch knobs for sweeps (0 keeps the current setting, a negative value restores the default):
+ * dense_target_wgs     workgroups a dense launch aims for in total.  Default: decided per launch -- the
+ *                      number of workgroups per (sequence, KV head) that loads the compute units most
+ *                      evenly (one workgroup per compute unit, all resident at once, where the pairs
+ *                      divide the compute units);
+ * fast_tiles_per_wave  32-row tiles each wave of the gather launch gets.  Default: decided per launch by
+ *                      the same rule -- one tile per wave (one-tile kernel) or several (pipelined loop);
  * fast_merge           how the split records of a fast step become the output: 1 (default) inside the
  *                      attention kernel, by the last workgroup of each (sequence, KV head) to finish;
  *                      2 in a merge launch of its own.  Other values > 2: SFI_EINVAL. */
 int sfi_set_tuning(sfi_ctx* ctx, int32_t dense_target_wgs, int32_t fast_tiles_per_wave, int32_t fast_merge);
+
+/* Launch geometry the library would choose, without launching anything (host arithmetic only): split
+ * workgroups per (sequence, KV head) of a dense launch bounded by max_len rows (0 = cfg.max_ctx) and
+ * of a fast step whose index lists are sel_stride wide.  Either output may be NULL.  SFI_EINVAL for a
+ * max_len or sel_stride outside the configuration. */
+int sfi_plan_splits(const sfi_ctx* ctx, int32_t max_len, int32_t sel_stride, int32_t* dense_splits,
+                    int32_t* fast_splits);
 
 /* Launch geometry of the last call (for reports): split workgroups per (sequence, KV head). */
 int sfi_query_splits(const sfi_ctx* ctx, int32_t* dense_splits, int32_t* fast_splits);

@@ -151,6 +151,9 @@ def test_hot_calls_reject_bad_arguments_before_any_launch():
         assert lib.sfi_set_tuning(None, 1, 1, 0) == EINVAL
         assert lib.sfi_set_tuning(h, 0, 0, 3) == EINVAL
         assert lib.sfi_set_tuning(h, 0, 0, 2) == OK
+        assert lib.sfi_plan_splits(None, 0, 64, None, None) == EINVAL
+        assert lib.sfi_plan_splits(h, cfg.max_ctx + 1, 64, None, None) == EINVAL
+        assert lib.sfi_plan_splits(h, 0, cfg.max_budget + 1, None, None) == EINVAL
         d, f = C.c_int32(-1), C.c_int32(-1)
         assert lib.sfi_query_splits(h, C.byref(d), C.byref(f)) == OK and d.value == 0 and f.value == 0
     finally:
@@ -191,3 +194,47 @@ def test_paged_config_and_block_table_validation():
                 assert lib.sfi_reorg(h, p, p, p, p, 64, p, None, p, p, C.c_int64(2 * 68 * 128), C.c_int64(68 * 128), 68, None) == EINVAL
         finally:
             assert lib.sfi_destroy(h) == OK
+
+
+def _plan(B, Hkv, ctx, budget, recent=128, tuning=None):
+    """Launch plan (dense splits, fast splits) of a context of this shape; the library assumes 256
+    compute units where there is no device."""
+    lib = sfi.load_library()
+    c = good_cfg(batch=B, n_q_heads=4 * Hkv, n_kv_heads=Hkv, max_ctx=ctx, max_budget=budget, recent=recent,
+                 k_stride_h=128 * ctx, k_stride_b=Hkv * 128 * ctx, v_stride_h=128 * ctx, v_stride_b=Hkv * 128 * ctx)
+    h = C.c_void_p()
+    assert lib.sfi_create(C.byref(c), 0x10000, sfi.sfi_workspace_bytes(c), C.byref(h)) == OK
+    try:
+        if tuning:
+            assert lib.sfi_set_tuning(h, *tuning) == OK
+        d, f = C.c_int32(-1), C.c_int32(-1)
+        assert lib.sfi_plan_splits(h, 0, budget, C.byref(d), C.byref(f)) == OK
+        return d.value, f.value
+    finally:
+        assert lib.sfi_destroy(h) == OK
+
+
+def test_launch_plan_loads_the_compute_units_evenly():
+    """Host logic of the launch policy (256 compute units).  Where the (sequence, KV head) pairs divide the
+    compute units the plan is one workgroup per unit; where they do not, it must not leave a second round
+    that is almost empty (264 pairs: one workgroup per pair would take two shares of time for 1.03 of work)."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("the plan depends on the device's compute-unit count; this test pins the 256-unit default")
+    assert _plan(4, 8, 32768 + 64, 2048) == (8, 8)            # the benchmark's shape: 256 workgroups each
+    assert _plan(1, 8, 131072 + 64, 4096, recent=256) == (32, 32)
+    assert _plan(32, 8, 32768, 2048) == (1, 1)                # one pair per unit: no split, no merge
+    assert _plan(64, 8, 32768, 2048) == (1, 1)                # two full rounds
+    for B in (12, 24, 33, 40, 48):
+        pairs = 8 * B
+        d, f = _plan(B, 8, 32768, 2048)
+        for s, tiles in ((d, 1024 + 5), (f, (4 + 2048 + 128 + 31) // 32)):
+            r = pairs * s / 256
+            assert 1 <= s <= 63 and 4 * s <= tiles + 3
+            assert r / -(-r // 1) >= 0.68, f"B={B}: {s} workgroups per pair load the units {r:.2f} rounds"
+    assert _plan(33, 8, 32768, 2048)[0] in (8, 9)              # 8.25 or 9.28 rounds of workgroups, not 1.03
+    # a tiny problem spreads over as many workgroups as it has tiles for
+    assert _plan(1, 2, 777, 50, recent=32) == (7, 1 + (4 + 50 + 32) // 128)
+    # knobs: a total for the dense launch, tiles per wave for the gather launch; negative restores the default
+    assert _plan(4, 8, 32768, 2048, tuning=(512, 1, 0)) == (16, 18)
+    assert _plan(4, 8, 32768, 2048, tuning=(-1, -1, 0)) == (8, 8)

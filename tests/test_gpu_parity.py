@@ -468,7 +468,7 @@ def test_fast_step_pipelined_gather(oracle, tiny, tpw):
             got = r.fast(q, sel2, nsel2, rs, ctx)
             check_out(got, oracle.sparse(q, w.K, w.V, sel2, nsel2, rs, ctx, w.n_sink))
     finally:
-        r.sfi.sfi_set_tuning(r.ctx.handle, 0, 1)
+        r.sfi.sfi_set_tuning(r.ctx.handle, 0, -1)
 
 
 def test_trigger_policy_on_device(oracle, tiny):
