@@ -433,6 +433,7 @@ int slow_attn_impl(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   set_dense_bounds(x, &a, ml);
   a.logits = x->ws.logits;
   a.with_knorm = x->cfg.selector_mode == 1;
+  a.big_stash = 1;  // every sequence is dense: one workgroup per compute unit, half as many write bursts
   a.hist1 = x->ws.hist1;
   a.state = x->ws.state;
   x->last_dense_splits = a.n_split;

@@ -400,9 +400,13 @@ struct ListWalk {
 // dense kernel
 // ------------------------------------------------------------------------------------------------
 // PAGED: K / V are block pools addressed through the sequence's block table.
-template <int EXPOSE, bool PAGED>  // EXPOSE 1: also write y over J for the Selector; 2: y and the squared key norms
-__global__ __launch_bounds__(kAttnThreads, 2) void attn_dense_kernel(const AttnArgs a) {
-  __shared__ float s_stash[EXPOSE != 0 ? kWaves : 1][EXPOSE != 0 ? kStashFloats : 1];  // per-wave logits stash
+// EXPOSE 1: also write y over J for the Selector; 2: y and the squared key norms.
+// BIG: twice the logits stash per wave, which leaves room for one workgroup per compute unit only
+// (launches where every sequence is dense run one per unit anyway; the mixed step keeps two).
+template <int EXPOSE, bool PAGED, bool BIG = false>
+__global__ __launch_bounds__(kAttnThreads, BIG ? 1 : 2) void attn_dense_kernel(const AttnArgs a) {
+  constexpr int kStash = BIG ? 2 * kStashFloats : kStashFloats;
+  __shared__ float s_stash[EXPOSE != 0 ? kWaves : 1][EXPOSE != 0 ? kStash : 1];  // per-wave logits stash
   const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
   const int tid = threadIdx.x;
@@ -523,7 +527,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void attn_dense_kernel(const AttnA
   float* stash = EXPOSE != 0 ? &s_stash[w][0] : nullptr;
   float* lg_base = EXPOSE != 0 ? a.logits + (int64_t)bh * rows_exp * a.ld_pos : nullptr;
   const int tile_f4 = rows_exp * (kTile / 4);        // float4 per tile
-  const int stash_cap = kStashFloats / (rows_exp * kTile);  // tiles the stash holds
+  const int stash_cap = kStash / (rows_exp * kTile);  // tiles the stash holds
   int n_stashed = 0, k_flushed = 0;
   auto flush_stash = [&]() {
     __builtin_amdgcn_wave_barrier();
@@ -1090,8 +1094,12 @@ hipError_t launch_trigger(const int32_t* last_token, const uint32_t* bitmap, int
 
 template <bool PAGED>
 static void launch_dense_t(const AttnArgs& a, dim3 grid, hipStream_t s) {
-  if (a.logits != nullptr && a.with_knorm)
+  if (a.logits != nullptr && a.with_knorm && a.big_stash)
+    hipLaunchKernelGGL((attn_dense_kernel<2, PAGED, true>), grid, dim3(kAttnThreads), 0, s, a);
+  else if (a.logits != nullptr && a.with_knorm)
     hipLaunchKernelGGL((attn_dense_kernel<2, PAGED>), grid, dim3(kAttnThreads), 0, s, a);
+  else if (a.logits != nullptr && a.big_stash)
+    hipLaunchKernelGGL((attn_dense_kernel<1, PAGED, true>), grid, dim3(kAttnThreads), 0, s, a);
   else if (a.logits != nullptr)
     hipLaunchKernelGGL((attn_dense_kernel<1, PAGED>), grid, dim3(kAttnThreads), 0, s, a);
   else

@@ -11,7 +11,7 @@ constexpr int kHeadDim = 128;
 constexpr int kTile = 32;          // KV positions per wave iteration (two 16-row MFMA blocks)
 constexpr int kWaves = 4;          // waves per attention workgroup
 constexpr int kAttnThreads = 64 * kWaves;
-constexpr int kStashFloats = 4096;  // per-wave LDS stash for exposed logits (16 KB): 128 / G tiles
+constexpr int kStashFloats = 4096;  // per-wave LDS stash for exposed logits (16 KB): 128 / G tiles; big variant: twice that
 constexpr int kMaxNmsRadius = 64;
 constexpr int kSegStats = 5;        // sum f, sum r, sum f^2, sum f r, sum r^2 of one segment
 constexpr int kPartStride = 132;   // floats per split record: m, l, pad, pad, acc[128]
@@ -64,6 +64,7 @@ struct AttnArgs {
   float* part;
   float* logits;                 // dense mode, nullptr: do not expose logits
   int32_t with_knorm;            // dense mode: also expose the squared key norms (full Selector)
+  int32_t big_stash;             // dense mode with logits: the variant with the 32 KB stash per wave (one workgroup per CU)
   int32_t pipelined;             // gather mode: few workgroups per (b, h), each wave walks several tiles
   float* out_direct;             // gather / compact mode with n_split == 1: write the output here, no record
   float* out_merge;              // gather / compact mode, nullptr or: the pair's last workgroup to finish merges
