@@ -94,10 +94,10 @@ size_t carve(const sfi_config* c, char* base, Workspace* ws) {
   // exposed rows per (b, h): the G heads' y and, for the full Selector, the squared key norms
   ws->logits = (float*)take((size_t)(B * Hq + (full ? B * Hkv : 0)) * ld * sizeof(float));
   ws->keys = (uint32_t*)take((size_t)(B * Hkv) * ld * sizeof(uint32_t));
-  ws->cand = (uint32_t*)take((size_t)(B * Hkv) * ld * sizeof(uint32_t));
+  ws->cand = (uint32_t*)take((size_t)(B * Hkv) * ld * 2 * sizeof(uint32_t));
   ws->hist1 = (uint32_t*)take((size_t)(B * Hkv) * kHist1Bins * sizeof(uint32_t));
   ws->state = (uint32_t*)take((size_t)(B * Hkv) * kStateWords * sizeof(uint32_t));
-  ws->segcnt = (uint32_t*)take((size_t)(B * Hkv) * n_seg * 2 * sizeof(uint32_t));
+  ws->segcnt = (uint32_t*)take((size_t)(B * Hkv) * n_seg * sizeof(uint32_t));
   ws->jstat = (float2*)take((size_t)(B * Hq) * sizeof(float2));
   ws->mu = (float*)take((size_t)(B * Hkv) * ld * sizeof(float));
   ws->arrive = (uint32_t*)take((size_t)(B * Hkv) * sizeof(uint32_t));
@@ -283,7 +283,6 @@ int run_selector(sfi_ctx* x, const SelArgs& sa, int max_len, hipStream_t st, boo
     if (!t.stop()) return SFI_ELAUNCH;
   }
   { StageTimer t(x, st, SFI_STAGE_CAND);  SFI_TRY(launch_sel_cand(sa, B, n_seg, st));  if (!t.stop()) return SFI_ELAUNCH; }
-  { StageTimer t(x, st, SFI_STAGE_COUNT); SFI_TRY(launch_sel_count(sa, B, n_seg, st)); if (!t.stop()) return SFI_ELAUNCH; }
   { StageTimer t(x, st, SFI_STAGE_WRITE); SFI_TRY(launch_sel_write(sa, B, n_seg, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
 }

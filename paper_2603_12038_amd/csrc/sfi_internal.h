@@ -36,10 +36,10 @@ struct Workspace {
   float* part;        // [B*Hq][kSlotCap][kPartStride]
   float* logits;      // [B*Hq][ld_pos]   J-relative positions
   uint32_t* keys;     // [B*Hkv][ld_pos]  fp32 bit pattern of the evidence f
-  uint32_t* cand;     // [B*Hkv][ld_pos]  keys falling into the threshold bin
+  uint32_t* cand;     // [B*Hkv][ld_pos][2]  keys falling into the threshold bin, each with its segment
   uint32_t* hist1;    // [B*Hkv][kHist1Bins]
   uint32_t* state;    // [B*Hkv][kStateWords]
-  uint32_t* segcnt;   // [B*Hkv][n_seg_cap][2]
+  uint32_t* segcnt;   // [B*Hkv][n_seg_cap]  keys of each segment above the threshold bin
   float2* jstat;      // [B*Hq]  J-only softmax statistics of each query head (slow step)
   float* prior;       // [B*Hkv][ld]  full Selector: unnormalised prior pi_kn * pi_pos
   float* znms;        // [B*Hkv][ld]  full Selector: log2-domain score after Soft-NMS
@@ -165,7 +165,6 @@ hipError_t launch_sel_accum(const SelArgs& a, int B, int n_seg, hipStream_t s);
 hipError_t launch_sel_finalize(const SelArgs& a, int B, int n_seg, hipStream_t s);
 hipError_t launch_sel_full(const SelArgs& a, int B, int n_seg, hipStream_t s);
 hipError_t launch_sel_cand(const SelArgs& a, int B, int n_seg, hipStream_t s);
-hipError_t launch_sel_count(const SelArgs& a, int B, int n_seg, hipStream_t s);
 hipError_t launch_sel_write(const SelArgs& a, int B, int n_seg, hipStream_t s);
 hipError_t launch_trigger(const int32_t* last_token, const uint32_t* bitmap, int vocab, int t_max, int32_t* since_slow,
                           uint8_t* is_slow, int B, hipStream_t s);

@@ -9,9 +9,10 @@
 // on mu itself.  Mode 1 goes through the prior, the reverse-KL fusion with lambda*, Soft-NMS and the
 // cross-head exclusivity first (three kernels further down) and ranks by e^z_adj.
 // Top-K is a radix select on the fp32 bit pattern of the ranking value (positive floats order like
-// unsigned integers): a 12-bit histogram over all of J, then an exact 19-bit refinement among the few
-// keys of the threshold bin, then an index-ordered compaction that takes every key above the
-// threshold and the lowest-index keys equal to it.  Integer atomics only count, so the result
+// unsigned integers): a 12-bit histogram over all of J (stage 1, with the scoring), the keys of the
+// threshold bin collected with the segment they came from (stage 2), and, in one launch (stage 3), an
+// exact 19-bit refinement among those few keys followed by an index-ordered compaction that takes every
+// key above the threshold and the lowest-index keys equal to it.  Integer atomics only count, so the result
 // does not depend on scheduling.
 #include "sfi_internal.h"
 #include "sfi_merge.h"
@@ -506,7 +507,7 @@ __global__ __launch_bounds__(kSelThreads) void sel_cand_kernel(const SelArgs a) 
   if (p_lo >= pb.nJ) return;
 
   const uint32_t* keys = a.keys + (int64_t)bh * a.ld_pos;
-  uint32_t* cand = a.cand + (int64_t)bh * a.ld_pos;
+  uint2* cand = reinterpret_cast<uint2*>(a.cand) + (int64_t)bh * a.ld_pos;  // (key, segment it came from)
   const int lane = tid & 63;
   // a thread owns 8 consecutive keys (the key row is padded to a whole segment, so both 16-byte
   // loads are always readable); they are fetched while the threshold bin is being found
@@ -531,9 +532,24 @@ __global__ __launch_bounds__(kSelThreads) void sel_cand_kernel(const SelArgs a) 
     st[ST_FLAGS] = 0u;
   }
   uint32_t mine = 0;  // bit i: key i falls into the threshold bin
+  uint32_t above = 0; // keys of this thread in a higher bin: selected whatever the exact threshold is
 #pragma unroll
-  for (int i = 0; i < kPer; ++i)
-    if (p0 + i < pb.nJ && (key[i] >> 19) == bin1) mine |= 1u << i;
+  for (int i = 0; i < kPer; ++i) {
+    if (p0 + i < pb.nJ) {
+      if ((key[i] >> 19) == bin1) mine |= 1u << i;
+      above += (key[i] >> 19) > bin1;
+    }
+  }
+  {  // the segment's count of keys above the threshold bin, for the write stage's prefix
+    __shared__ uint32_t s_above;
+    if (tid == 0) s_above = 0u;
+    __syncthreads();
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) above += __shfl_xor(above, d);
+    if (lane == 0 && above != 0u) atomicAdd(&s_above, above);
+    __syncthreads();
+    if (tid == 0) a.segcnt[(int64_t)bh * a.n_seg_cap + seg] = s_above;
+  }
   // one atomic per wave: lanes get consecutive runs of the reserved range
   const uint32_t cnt = __popc(mine);
   uint32_t incl = cnt;
@@ -549,84 +565,11 @@ __global__ __launch_bounds__(kSelThreads) void sel_cand_kernel(const SelArgs a) 
     base = __shfl(base, 63) + incl - cnt;
 #pragma unroll
     for (int i = 0; i < kPer; ++i)
-      if (mine & (1u << i)) cand[base++] = key[i];
+      if (mine & (1u << i)) cand[base++] = make_uint2(key[i], (uint32_t)seg);
   }
 }
 
-// ---- stage 3: exact threshold among the candidates, then per-segment counts --------------------
-__global__ __launch_bounds__(kSelThreads) void sel_count_kernel(const SelArgs a) {
-  const int seg = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
-  const Problem pb = problem_of(a, b);
-  const int p_lo = seg * kSelSeg;
-  if (p_lo >= pb.nJ) return;
-  const int tid = threadIdx.x;
-  const int bh = b * a.Hkv + h;
-  uint32_t* st = a.state + (int64_t)bh * kStateWords;
-  if (st[ST_FLAGS] != 0u) return;  // take all / take none: no threshold needed
-
-  __shared__ uint32_t s_h[1024];
-  __shared__ uint32_t s_res[2];
-  __shared__ uint32_t s_scr[8];
-  __shared__ uint32_t s_cnt[2];
-  const uint32_t bin1 = st[ST_BIN1], k1 = st[ST_K1], n_cand = st[ST_CAND];
-  const uint32_t* cand = a.cand + (int64_t)bh * a.ld_pos;
-
-  // bits [18:9] of the candidates
-  for (int i = tid; i < 1024; i += kSelThreads) s_h[i] = 0u;
-  __syncthreads();
-  for (uint32_t i = tid; i < n_cand; i += kSelThreads) atomicAdd(&s_h[(cand[i] >> 9) & 1023u], 1u);
-  __syncthreads();
-  find_kth_desc(s_h, 1024, k1, s_res, s_scr);
-  const uint32_t bin2 = s_res[0], k2 = s_res[1];
-  __syncthreads();
-  // bits [8:0] of the candidates that share bin2
-  for (int i = tid; i < 512; i += kSelThreads) s_h[i] = 0u;
-  __syncthreads();
-  for (uint32_t i = tid; i < n_cand; i += kSelThreads) {
-    const uint32_t key = cand[i];
-    if (((key >> 9) & 1023u) == bin2) atomicAdd(&s_h[key & 511u], 1u);
-  }
-  __syncthreads();
-  find_kth_desc(s_h, 512, k2, s_res, s_scr);
-  const uint32_t tau = (bin1 << 19) | (bin2 << 9) | s_res[0];
-  const uint32_t take = s_res[1];
-  if (seg == 0 && tid == 0) {
-    st[ST_TAU] = tau;
-    st[ST_TAKE] = take;
-  }
-
-  if (tid < 2) s_cnt[tid] = 0u;
-  __syncthreads();
-  const uint32_t* keys = a.keys + (int64_t)bh * a.ld_pos;
-  uint32_t gt = 0, eq = 0;
-  {
-    const int p0 = p_lo + tid * 8;
-    const uint4 k0 = *reinterpret_cast<const uint4*>(keys + p0);
-    const uint4 k1 = *reinterpret_cast<const uint4*>(keys + p0 + 4);
-    const uint32_t key[8] = {k0.x, k0.y, k0.z, k0.w, k1.x, k1.y, k1.z, k1.w};
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      if (p0 + i < pb.nJ) {
-        gt += key[i] > tau;
-        eq += key[i] == tau;
-      }
-    }
-  }
-#pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) {
-    gt += __shfl_xor(gt, d);
-    eq += __shfl_xor(eq, d);
-  }
-  if ((tid & 63) == 0) {
-    atomicAdd(&s_cnt[0], gt);
-    atomicAdd(&s_cnt[1], eq);
-  }
-  __syncthreads();
-  if (tid < 2) a.segcnt[((int64_t)bh * a.n_seg_cap + seg) * 2 + tid] = s_cnt[tid];
-}
-
-// ---- stage 4: index-ordered write of the selected set ------------------------------------------
+// ---- stage 3: exact threshold among the candidates, index-ordered write of the selected set ------
 __global__ __launch_bounds__(kSelThreads) void sel_write_kernel(const SelArgs a) {
   const int seg = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
@@ -647,15 +590,54 @@ __global__ __launch_bounds__(kSelThreads) void sel_write_kernel(const SelArgs a)
     return;
   }
 
+  __shared__ uint32_t s_h[1024];
+  __shared__ uint32_t s_res[2];
   __shared__ uint32_t s_base[2];
   __shared__ uint32_t s_scr[8];
+  const uint32_t bin1 = st[ST_BIN1], k1 = st[ST_K1], n_cand = st[ST_CAND];
+  const uint2* cand = reinterpret_cast<const uint2*>(a.cand) + (int64_t)bh * a.ld_pos;
+  const uint32_t* keys = a.keys + (int64_t)bh * a.ld_pos;
+  constexpr int kPer = kSelSeg / kSelThreads;  // consecutive positions per thread
+  const int p0 = p_lo + tid * kPer;
+  static_assert(kPer == 8, "two 16-byte key loads per thread");
+  uint32_t key[kPer];
+  {  // fetched while the threshold is worked out; the key row is padded to a multiple of kSelSeg, so the
+     // full 32 bytes are always readable
+    const uint4 lo4 = *reinterpret_cast<const uint4*>(keys + p0);
+    const uint4 hi4 = *reinterpret_cast<const uint4*>(keys + p0 + 4);
+    key[0] = lo4.x; key[1] = lo4.y; key[2] = lo4.z; key[3] = lo4.w;
+    key[4] = hi4.x; key[5] = hi4.y; key[6] = hi4.z; key[7] = hi4.w;
+  }
+  // Exact threshold tau and tie quota among the keys of the threshold bin (typically a few hundred):
+  // two LDS radix passes, bits [18:9] then [8:0]; every workgroup of the pair does the same.
+  for (int i = tid; i < 1024; i += kSelThreads) s_h[i] = 0u;
   if (tid < 2) s_base[tid] = 0u;
   __syncthreads();
-  {  // keys selected in the segments before this one
+  for (uint32_t i = tid; i < n_cand; i += kSelThreads) atomicAdd(&s_h[(cand[i].x >> 9) & 1023u], 1u);
+  __syncthreads();
+  find_kth_desc(s_h, 1024, k1, s_res, s_scr);
+  const uint32_t bin2 = s_res[0], k2 = s_res[1];
+  __syncthreads();
+  for (int i = tid; i < 512; i += kSelThreads) s_h[i] = 0u;
+  __syncthreads();
+  for (uint32_t i = tid; i < n_cand; i += kSelThreads) {
+    const uint32_t key = cand[i].x;
+    if (((key >> 9) & 1023u) == bin2) atomicAdd(&s_h[key & 511u], 1u);
+  }
+  __syncthreads();
+  find_kth_desc(s_h, 512, k2, s_res, s_scr);
+  const uint32_t tau = (bin1 << 19) | (bin2 << 9) | s_res[0];
+  const uint32_t take = s_res[1];
+  {  // keys selected in the segments before this one: those above the threshold bin (counted by stage 2)
+     // plus the bin's own keys above tau; and the ties before this segment
     uint32_t gt = 0, eq = 0;
-    for (int s = tid; s < seg; s += kSelThreads) {
-      gt += a.segcnt[((int64_t)bh * a.n_seg_cap + s) * 2];
-      eq += a.segcnt[((int64_t)bh * a.n_seg_cap + s) * 2 + 1];
+    for (int sg = tid; sg < seg; sg += kSelThreads) gt += a.segcnt[(int64_t)bh * a.n_seg_cap + sg];
+    for (uint32_t i = tid; i < n_cand; i += kSelThreads) {
+      const uint2 c = cand[i];
+      if ((int)c.y < seg) {
+        gt += c.x > tau;
+        eq += c.x == tau;
+      }
     }
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) {
@@ -669,19 +651,7 @@ __global__ __launch_bounds__(kSelThreads) void sel_write_kernel(const SelArgs a)
   }
   __syncthreads();
   const uint32_t base_gt = s_base[0], base_eq = s_base[1];
-  const uint32_t tau = st[ST_TAU], take = st[ST_TAKE];
-  const uint32_t* keys = a.keys + (int64_t)bh * a.ld_pos;
 
-  constexpr int kPer = kSelSeg / kSelThreads;  // consecutive positions per thread
-  const int p0 = p_lo + tid * kPer;
-  static_assert(kPer == 8, "two 16-byte key loads per thread");
-  uint32_t key[kPer];
-  {  // the key row is padded to a multiple of kSelSeg, so the full 32 bytes are always readable
-    const uint4 k0 = *reinterpret_cast<const uint4*>(keys + p0);
-    const uint4 k1 = *reinterpret_cast<const uint4*>(keys + p0 + 4);
-    key[0] = k0.x; key[1] = k0.y; key[2] = k0.z; key[3] = k0.w;
-    key[4] = k1.x; key[5] = k1.y; key[6] = k1.z; key[7] = k1.w;
-  }
   uint32_t cg = 0, ce = 0;
 #pragma unroll
   for (int i = 0; i < kPer; ++i) {
@@ -729,10 +699,6 @@ hipError_t launch_sel_full(const SelArgs& a, int B, int n_seg, hipStream_t s) {
 }
 hipError_t launch_sel_cand(const SelArgs& a, int B, int n_seg, hipStream_t s) {
   hipLaunchKernelGGL(sel_cand_kernel, dim3(n_seg, a.Hkv, B), dim3(kSelThreads), 0, s, a);
-  return hipGetLastError();
-}
-hipError_t launch_sel_count(const SelArgs& a, int B, int n_seg, hipStream_t s) {
-  hipLaunchKernelGGL(sel_count_kernel, dim3(n_seg, a.Hkv, B), dim3(kSelThreads), 0, s, a);
   return hipGetLastError();
 }
 hipError_t launch_sel_write(const SelArgs& a, int B, int n_seg, hipStream_t s) {
