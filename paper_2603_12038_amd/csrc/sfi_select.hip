@@ -508,7 +508,6 @@ __global__ __launch_bounds__(kSelThreads) void sel_cand_kernel(const SelArgs a) 
 
   const uint32_t* keys = a.keys + (int64_t)bh * a.ld_pos;
   uint2* cand = reinterpret_cast<uint2*>(a.cand) + (int64_t)bh * a.ld_pos;  // (key, segment it came from)
-  const int lane = tid & 63;
   // a thread owns 8 consecutive keys (the key row is padded to a whole segment, so both 16-byte
   // loads are always readable); they are fetched while the threshold bin is being found
   constexpr int kPer = kSelSeg / kSelThreads;
@@ -540,33 +539,22 @@ __global__ __launch_bounds__(kSelThreads) void sel_cand_kernel(const SelArgs a) 
       above += (key[i] >> 19) > bin1;
     }
   }
-  {  // the segment's count of keys above the threshold bin, for the write stage's prefix
-    __shared__ uint32_t s_above;
-    if (tid == 0) s_above = 0u;
-    __syncthreads();
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) above += __shfl_xor(above, d);
-    if (lane == 0 && above != 0u) atomicAdd(&s_above, above);
-    __syncthreads();
-    if (tid == 0) a.segcnt[(int64_t)bh * a.n_seg_cap + seg] = s_above;
+  // One prefix sum over the workgroup gives both the segment's count of keys above the threshold bin (for
+  // the write stage's prefix) and every thread's place in the segment's run of candidates; one atomic per
+  // workgroup reserves the run in the pair's list (one per wave made the long-context launches crawl:
+  // hundreds of atomics on one counter).
+  uint32_t total;
+  const uint32_t ex = block_excl_scan((uint32_t)__popc(mine) | (above << 16), s_scr, &total);
+  __shared__ uint32_t s_base;
+  if (tid == 0) {
+    a.segcnt[(int64_t)bh * a.n_seg_cap + seg] = total >> 16;
+    s_base = (total & 0xffffu) != 0u ? atomicAdd(&st[ST_CAND], total & 0xffffu) : 0u;
   }
-  // one atomic per wave: lanes get consecutive runs of the reserved range
-  const uint32_t cnt = __popc(mine);
-  uint32_t incl = cnt;
+  __syncthreads();
+  uint32_t base = s_base + (ex & 0xffffu);
 #pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    const uint32_t t = __shfl_up(incl, d);
-    if (lane >= d) incl += t;
-  }
-  const uint32_t wave_total = __shfl(incl, 63);
-  uint32_t base = 0;
-  if (wave_total != 0u) {
-    if (lane == 63) base = atomicAdd(&st[ST_CAND], wave_total);
-    base = __shfl(base, 63) + incl - cnt;
-#pragma unroll
-    for (int i = 0; i < kPer; ++i)
-      if (mine & (1u << i)) cand[base++] = make_uint2(key[i], (uint32_t)seg);
-  }
+  for (int i = 0; i < kPer; ++i)
+    if (mine & (1u << i)) cand[base++] = make_uint2(key[i], (uint32_t)seg);
 }
 
 // ---- stage 3: exact threshold among the candidates, index-ordered write of the selected set ------
