@@ -596,3 +596,80 @@ def test_fast_step_many_split_workgroups(oracle, Hq, Hkv):
             check_out(got, oracle.sparse(q, w.K, w.V, sel, nsel, rs, ctx, w.n_sink))
     finally:
         r.close()
+
+
+def test_graph_replays_match_eager_runs(oracle):
+    """One refresh segment (slow step, state update, three fast steps with state updates) captured into
+    a HIP graph and replayed three times, with eager work of the library and synchronisations between the
+    replays: every replay must leave the bits the eager run left (outputs of all four steps, index sets,
+    state), and the eager run matches the oracle.  Sizes give split launches, so the in-kernel merge and
+    its arrival counters are part of what is replayed."""
+    import torch
+    w = syn.make_tiny(L0=6000, steps=4, budget=700, recent=64, n_support=16, B=2)
+    w.L0 = np.array([6000, 4321], np.int32)
+    r = Runner(w)
+    try:
+        sfi, h, t = r.sfi, r.ctx.handle, torch
+        qs = [to_dev(w.q(i)) for i in range(4)]
+        outs = [t.zeros(w.B, w.Hq, w.d, dtype=t.float32, device="cuda") for _ in range(4)]
+        sel = t.full((w.B, w.Hkv, w.budget), -7, dtype=t.int32, device="cuda")
+        nsel = t.full((w.B, w.Hkv), -7, dtype=t.int32, device="cuda")
+        ctx0, rs0 = i32_dev(w.ctx_len(0)), i32_dev(w.recent_start(0))
+        ctx_d, rs_d = ctx0.clone(), rs0.clone()
+
+        def segment():
+            sfi.sfi_slow_step(h, qs[0], r.K, r.V, ctx_d, r.max_ctx, w.budget, outs[0], sel, nsel)
+            sfi.sfi_advance(h, ctx_d, rs_d)
+            for i in range(1, 4):
+                sfi.sfi_fast_step(h, qs[i], r.K, r.V, sel, nsel, w.budget, rs_d, ctx_d, outs[i])
+                sfi.sfi_advance(h, ctx_d, rs_d)
+
+        def reset():
+            ctx_d.copy_(ctx0)
+            rs_d.copy_(rs0)
+            for o in outs:
+                o.fill_(float("nan"))
+            sel.fill_(-7)
+            nsel.fill_(-7)
+
+        _step("graph test: eager segment")
+        reset()
+        segment()
+        t.cuda.synchronize()
+        assert sfi.sfi_query_splits(h)[1] > 1
+        ref = [o.clone() for o in outs] + [sel.clone(), nsel.clone(), ctx_d.clone(), rs_d.clone()]
+        check_out(ref[0].cpu().numpy(), oracle.dense(w.q(0), w.K, w.V, w.ctx_len(0)))
+        sel_np, nsel_np = ref[4].cpu().numpy(), ref[5].cpu().numpy()
+        for i in range(1, 4):
+            check_out(ref[i].cpu().numpy(),
+                      oracle.sparse(w.q(i), w.K, w.V, sel_np, nsel_np, w.recent_start(i), w.ctx_len(i), w.n_sink))
+
+        _step("graph test: capture")
+        reset()
+        t.cuda.synchronize()
+        side = t.cuda.Stream()  # default priority
+        side.wait_stream(t.cuda.current_stream())
+        graph = t.cuda.CUDAGraph()
+        with t.cuda.stream(side):
+            graph.capture_begin()
+            segment()
+            graph.capture_end()
+        t.cuda.current_stream().wait_stream(side)
+        t.cuda.synchronize()
+        assert t.equal(ctx_d, ctx0), "capture must not execute anything"
+
+        other_q = to_dev(w.q(2))
+        for rep in range(3):
+            _step(f"graph test: replay {rep}")
+            reset()
+            graph.replay()
+            t.cuda.synchronize()
+            got = outs + [sel, nsel, ctx_d, rs_d]
+            for k, (g_, r_) in enumerate(zip(got, ref)):
+                assert t.equal(g_, r_), f"replay {rep}: tensor {k} differs from the eager run"
+            # eager work of the library between the replays (same context, same workspace)
+            r.dense(w.q(3), w.ctx_len(1))
+            sfi.sfi_fast_step(h, other_q, r.K, r.V, sel, nsel, w.budget, rs0, ctx0, r.out)
+            t.cuda.synchronize()
+    finally:
+        r.close()
