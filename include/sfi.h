@@ -115,7 +115,10 @@ typedef struct sfi_ctx sfi_ctx; /* opaque; host memory owned by the library */
 size_t sfi_workspace_bytes(const sfi_config* cfg);
 
 /* Validate cfg, bind the caller's workspace, return a context in *out.
- * Touches the device only to read its properties and, later, to launch. */
+ * Touches the device to read its properties and to clear a few hundred bytes of the workspace (the
+ * arrival counters of the fast step's in-kernel merge; a blocking memset followed by a device
+ * synchronisation, so not to be called while a stream of the device is capturing).  SFI_ELAUNCH if the
+ * workspace is device memory and could not be cleared. */
 int sfi_create(const sfi_config* cfg, void* workspace, size_t workspace_bytes, sfi_ctx** out);
 
 /*

@@ -345,18 +345,33 @@ int sfi_create(const sfi_config* cfg, void* workspace, size_t workspace_bytes, s
   x->n_cu = 256;
   int dev = 0;
   hipDeviceProp_t prop;
+  bool have_device = false;
   if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
-      prop.multiProcessorCount > 0)
+      prop.multiProcessorCount > 0) {
     x->n_cu = prop.multiProcessorCount;
-  else
+    have_device = true;
+  } else {
     (void)hipGetLastError();  // no device here: keep the MI355X default
+  }
   x->dense_target_wgs = 0;
   x->fast_tiles_per_wave = 0;
   x->tail_merge = 1;
-  // the arrival counters of split fast-step launches start at zero (and every launch leaves them there)
-  if (hipMemset(ws.arrive, 0, (size_t)cfg->batch * cfg->n_kv_heads * sizeof(uint32_t)) != hipSuccess ||
-      hipDeviceSynchronize() != hipSuccess)
-    (void)hipGetLastError();  // no device here: nothing will be launched either
+  // The arrival counters of split fast-step launches start at zero (and every launch leaves them there).
+  // A workspace that is device memory is cleared here and a failure to do so is an error: with stale
+  // counters no workgroup would ever take itself for the last one.  (Without a device, or with a
+  // pointer the runtime does not know, nothing can be launched on this context anyway.)
+  hipPointerAttribute_t attr;
+  if (have_device && hipPointerGetAttributes(&attr, ws.arrive) == hipSuccess &&
+      attr.type == hipMemoryTypeDevice) {
+    if (hipMemset(ws.arrive, 0, (size_t)cfg->batch * cfg->n_kv_heads * sizeof(uint32_t)) != hipSuccess ||
+        hipDeviceSynchronize() != hipSuccess) {
+      (void)hipGetLastError();
+      delete x;
+      return SFI_ELAUNCH;
+    }
+  } else {
+    (void)hipGetLastError();
+  }
   *out = x;
   return SFI_OK;
 }
