@@ -673,3 +673,33 @@ def test_graph_replays_match_eager_runs(oracle):
             t.cuda.synchronize()
     finally:
         r.close()
+
+
+def test_context_on_a_dirty_workspace(oracle, tiny):
+    """sfi_create must not rely on what the workspace holds: a workspace of 0xFF bytes gives the same split
+    fast step (in-kernel merge, arrival counters) and the same slow step as a fresh one."""
+    import torch
+    w, r = tiny
+    sfi = r.sfi
+    cfg = r.ctx.cfg
+    nbytes = sfi.sfi_workspace_bytes(cfg)
+    ws = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device="cuda")
+    h = sfi.sfi_create(cfg, ws, nbytes)
+    try:
+        q0, ctx0 = w.q(0), w.ctx_len(0)
+        out_ref, sel, nsel = r.slow(q0, ctx0, w.budget)
+        q1, ctx1, rs1 = w.q(1), w.ctx_len(1), w.recent_start(1)
+        fast_ref = r.fast(q1, sel, nsel, rs1, ctx1)
+        assert sfi.sfi_query_splits(r.ctx.handle)[1] > 1
+        out = torch.full((w.B, w.Hq, w.d), float("nan"), dtype=torch.float32, device="cuda")
+        sel_d = torch.full((w.B, w.Hkv, w.budget), -7, dtype=torch.int32, device="cuda")
+        nsel_d = torch.full((w.B, w.Hkv), -7, dtype=torch.int32, device="cuda")
+        sfi.sfi_fast_step(h, to_dev(q1), r.K, r.V, i32_dev(sel), i32_dev(nsel), w.budget, i32_dev(rs1), i32_dev(ctx1), out)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), fast_ref)
+        sfi.sfi_slow_step(h, to_dev(q0), r.K, r.V, i32_dev(ctx0), r.max_ctx, w.budget, out, sel_d, nsel_d)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), out_ref)
+        assert np.array_equal(sel_d.cpu().numpy(), sel) and np.array_equal(nsel_d.cpu().numpy(), nsel)
+    finally:
+        sfi.sfi_destroy(h)
