@@ -201,7 +201,8 @@ int sfi_dense_attn(sfi_ctx* ctx, const void* q, const void* K, const void* V, co
  *   out[b, g, :] = attention of q[b,g] over rows
  *                  [0, min(n_sink, ctx_len)) U sel_idx[b,h,0:n_sel[b,h]] U [recent_start[b], ctx_len[b]).
  * Preconditions: the three parts are disjoint; sel entries lie in [n_sink, recent_start[b]);
- * n_sink <= recent_start[b] <= ctx_len[b] (or recent_start = ctx_len < n_sink);
+ * n_sink <= recent_start[b] <= ctx_len[b]; while ctx_len[b] < n_sink any recent_start[b] >= ctx_len[b] is
+ * read as ctx_len[b] (an empty window: sfi_advance leaves n_sink there);
  * n_sel[b,h] <= sel_stride <= cfg.max_budget.  sel_idx / n_sel are read-only here.
  */
 int sfi_fast_step(sfi_ctx* ctx, const void* q, const void* K, const void* V, const int32_t* sel_idx,
@@ -231,6 +232,10 @@ int sfi_reorg(sfi_ctx* ctx, const void* K, const void* V, const int32_t* sel_idx
  * [recent_start[b], ctx_len[b]) in place from K / V.  Same result as sfi_fast_step on the sel_idx
  * the buffers were built from.  Preconditions as for sfi_fast_step; n_sel[b,h] <= sel_stride and
  * c_rows >= n_sink + sel_stride; n_sel[b,h] > 0 only where ctx_len[b] > n_sink.
+ * While ctx_len[b] <= n_sink the whole context is read in place from K / V (nothing is selected, and
+ * rows appended since sfi_reorg are sink rows the buffers do not hold).  A sequence reorganised at
+ * ctx_len[b] < n_sink must be reorganised again before a compact fast step at ctx_len[b] > n_sink:
+ * the sink rows that did not exist yet are not in the buffers.
  */
 int sfi_fast_step_compact(sfi_ctx* ctx, const void* q, const void* Kc, const void* Vc, int64_t c_stride_b,
                           int64_t c_stride_h, int32_t c_rows, const int32_t* n_sel, int32_t sel_stride,

@@ -928,8 +928,11 @@ __global__ __launch_bounds__(kAttnThreads, PAGED ? 2 : 3) void attn_compact_kern
   const int L = a.ctx_len[b];
   const int nSel = a.n_sel[bh];
   const int nS = min(a.n_sink, L);
-  const int rs = min(max(a.recent_start[b], nS), L);
-  const int Nc = nSel > 0 ? a.n_sink + nSel : nS;  // compact rows in use (selected rows exist only past a full sink)
+  // A context that still lies inside the sink range has nothing selected, and the rows appended since
+  // the reorganisation are sink rows the compact buffers do not hold: all of it is read in place.
+  const bool all_sink = L <= a.n_sink;
+  const int rs = all_sink ? 0 : min(max(a.recent_start[b], nS), L);
+  const int Nc = all_sink ? 0 : a.n_sink + nSel;  // compact rows in use
   const int Tc = (Nc + kTile - 1) / kTile;
   const int Nr = L - rs;
   const int nT = Tc + (Nr + kTile - 1) / kTile;

@@ -703,3 +703,30 @@ def test_context_on_a_dirty_workspace(oracle, tiny):
         assert np.array_equal(sel_d.cpu().numpy(), sel) and np.array_equal(nsel_d.cpu().numpy(), nsel)
     finally:
         sfi.sfi_destroy(h)
+
+
+@pytest.mark.parametrize("n_sink,L", [(33, 23), (70, 10), (70, 69), (33, 33), (4, 2)])
+def test_context_shorter_than_the_sink(oracle, n_sink, L):
+    """ctx_len <= n_sink: every row is a sink row, nothing is selected, the recent window is empty
+    (sfi_advance leaves recent_start = n_sink > ctx_len).  Slow step, fast step and the compact fast step,
+    whose buffers were filled before the last rows were appended."""
+    w = syn.make_tiny(L0=200, steps=3, budget=16, recent=8, n_support=4, B=2, Hq=6, Hkv=2)
+    w.n_sink = n_sink
+    w.L0 = np.array([L, max(1, L - 3)], np.int32)
+    r = Runner(w)
+    try:
+        _step(f"context inside the sink: n_sink={n_sink} L={L}")
+        q0, c0 = w.q(0), w.ctx_len(0)
+        out, sel, nsel = r.slow(q0, c0, w.budget)
+        check_out(out, oracle.dense(q0, w.K, w.V, c0))
+        assert (nsel == 0).all() and (sel == -1).all()
+        r.reorg(sel, nsel, c0)
+        for t in (1, 2):
+            q, ct, rt = w.q(t), w.ctx_len(t), w.recent_start(t)
+            if (ct > n_sink).any():
+                break  # the sink has filled up: the next step has to be a slow one for the compact path
+            ref = oracle.sparse(q, w.K, w.V, sel, nsel, rt, ct, w.n_sink)
+            check_out(r.fast(q, sel, nsel, rt, ct), ref)
+            check_out(r.fast_compact(q, nsel, sel.shape[2], rt, ct), ref)
+    finally:
+        r.close()
