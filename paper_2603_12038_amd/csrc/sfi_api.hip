@@ -114,21 +114,25 @@ inline bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintp
 // Workgroups per (sequence, KV head) pair for a launch whose pairs each hold `tiles` 32-row tiles.
 // A compute unit pulls rows at a fixed rate however many workgroups share it, so a launch takes as
 // long as its busiest compute unit: w = pairs * s workgroups over n_cu units cost ceil(w / n_cu)
-// shares where w / n_cu would do (264 workgroups on 256 units take twice as long as 256).  Against
-// that, every workgroup pays a start and an end worth about three tiles of a wave's time.  Take the s
-// with the best product of the two factors, the smaller s on a tie.  (Measured at 12, 24, 33 and 40
-// sequences of 8 KV heads: 13 to 43 % faster dense launches than one workgroup per compute unit
-// rounded down, and the same choice wherever the pairs divide the compute units.)
-int balanced_splits(int pairs, int tiles, int cap, int n_cu) {
+// shares where w / n_cu would do (264 workgroups on 256 units take twice as long as 256).  A share
+// is a wave's tiles plus a start and an end worth about three tiles; in a single round the waves
+// move in step, one trip to memory per tile, so the wave with the most tiles counts.  A launch that
+// merges its records in the kernel pays about two thirds of a tile for every further group of eight
+// workgroups per pair.  Take the s with the lowest cost, the smaller s on a tie.  (Measured at 12, 24,
+// 33 and 40 sequences of 8 KV heads: 13 to 43 % faster dense launches than one workgroup per compute
+// unit rounded down; one long stream: 18 workgroups per pair instead of 32, 6 % faster fast steps; the
+// same choice as one workgroup per compute unit where the pairs divide the compute units.)
+int balanced_splits(int pairs, int tiles, int cap, int n_cu, bool merges_in_kernel) {
   int best = 1;
-  double best_score = -1.0;
+  double best_cost = 1e300;
   for (int s = 1; s <= cap; ++s) {
     const double r = (double)pairs * s / n_cu;
     const double t = (double)tiles / (kWaves * s);
-    const double score = r / ceil(r) * t / (t + 3.0);
-    if (score > best_score * (1.0 + 1e-9)) {
+    const double share = (r <= 1.0 ? ceil(t) : t) + 3.0;
+    const double cost = ceil(r) * share + (merges_in_kernel ? (2.0 / 3.0) * ((s + 7) / 8 - 1) : 0.0);
+    if (cost < best_cost * (1.0 - 1e-9)) {
       best = s;
-      best_score = score;
+      best_cost = cost;
     }
   }
   return best;
@@ -151,7 +155,7 @@ int dense_splits_for(const sfi_ctx* x, int max_len, bool mixed) {
   int s;
   if (mixed) s = cap;
   else if (x->dense_target_wgs > 0) s = x->dense_target_wgs / pairs;
-  else s = balanced_splits(pairs, tiles, cap, x->n_cu);
+  else s = balanced_splits(pairs, tiles, cap, x->n_cu, false);
   if (s > cap) s = cap;
   if (s < 1) s = 1;
   return s;
@@ -179,7 +183,7 @@ int fast_splits_for(const sfi_ctx* x, int sel_stride, int* pipelined) {
   if (x->fast_tiles_per_wave > 0)
     s = (tiles + kWaves * x->fast_tiles_per_wave - 1) / (kWaves * x->fast_tiles_per_wave);
   else
-    s = balanced_splits(pairs, tiles, one, x->n_cu);
+    s = balanced_splits(pairs, tiles, one, x->n_cu, x->tail_merge != 0);
   if (s > one) s = one;
   if (s < 1) s = 1;
   *pipelined = s * kWaves < tiles;
@@ -198,7 +202,7 @@ int compact_splits_for(const sfi_ctx* x, int sel_stride) {
   if (x->fast_tiles_per_wave > 0)
     s = (tiles + kWaves * x->fast_tiles_per_wave - 1) / (kWaves * x->fast_tiles_per_wave);
   else
-    s = balanced_splits(pairs, tiles, one, x->n_cu);
+    s = balanced_splits(pairs, tiles, one, x->n_cu, x->tail_merge != 0);
   if (s > one) s = one;
   if (s < 1) s = 1;
   return s;

@@ -57,7 +57,7 @@ def test_llama8b_shaped_layer(oracle):
 
 
 def test_in_kernel_merge_never_reads_a_stale_record(oracle):
-    """Config 2 shape, 8 split workgroups per pair on all compute units: 600 fast steps in a row alternating
+    """Config 2 shape, several split workgroups per pair: 600 fast steps in a row alternating
     between two queries and two index sets.  Every output must be bit-identical to the first output of its
     query (checked against the oracle): a record left over from the launch before, read in place of a fresh
     one, would belong to the other query."""
@@ -75,7 +75,7 @@ def test_in_kernel_merge_never_reads_a_stale_record(oracle):
             ref = r.fast(q, sel, nsel, rs, ctx)
             check_out(ref, oracle.sparse(q, w.K, w.V, sel, nsel, rs, ctx, w.n_sink))
             cases.append((to_dev(q), i32_dev(sel), i32_dev(nsel), torch.from_numpy(ref).cuda()))
-        assert r.sfi.sfi_query_splits(r.ctx.handle)[1] == 8
+        assert r.sfi.sfi_query_splits(r.ctx.handle)[1] >= 4
         _step("600 alternating fast steps, in-kernel merge")
         outs = [torch.empty_like(cases[0][3]) for _ in range(600)]
         for i, o in enumerate(outs):

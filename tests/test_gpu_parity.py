@@ -585,6 +585,7 @@ def test_fast_step_many_split_workgroups(oracle, Hq, Hkv):
     w = syn.make_tiny(L0=9000, steps=1, budget=8100, recent=64, n_support=8, B=1, Hq=Hq, Hkv=Hkv)
     r = Runner(w)
     try:
+        r.sfi.sfi_set_tuning(r.ctx.handle, 0, 1)  # one tile per wave: as many workgroups as the list has tiles for
         q, ctx, rs = w.q(0), w.ctx_len(0), w.recent_start(0)
         for case, (ns, want) in enumerate([(1100, 10), (3000, 24), (4000, 32), (8100, 63), (300, 3)]):
             _step(f"fast step with {want} split workgroups per pair, G={Hq // Hkv}")
