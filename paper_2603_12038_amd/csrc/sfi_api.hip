@@ -169,10 +169,10 @@ void set_dense_bounds(const sfi_ctx* x, AttnArgs* a, int max_len) {
 
 // Gather launch geometry: the balanced split above.  With one workgroup per pair the workgroup
 // finishes the softmax itself (no records, no merge).  A split that leaves every wave at most one
-// tile runs the one-tile kernel, any other the pipelined one.  (Config 2: one workgroup per compute
-// unit, 2 - 3 tiles per wave; 33 sequences of 8 KV heads: 3 workgroups per pair instead of 1, 17 %
-// faster.)  fast_tiles_per_wave > 0 overrides: 1 = one tile per wave, t > 1 = pipelined with about t
-// tiles per wave.
+// tile runs the one-tile kernel, any other the pipelined one.  (Config 2: 6 workgroups per pair, up to
+// 3 tiles per wave; 33 sequences of 8 KV heads: 2 workgroups per pair instead of 1, 10 % faster.)
+// fast_tiles_per_wave > 0 overrides: 1 = one tile per wave, t > 1 = pipelined with about t tiles per
+// wave.
 int fast_splits_for(const sfi_ctx* x, int sel_stride, int* pipelined) {
   const int rows = x->cfg.n_sink + sel_stride + x->cfg.recent;
   const int tiles = (rows + kTile - 1) / kTile;
