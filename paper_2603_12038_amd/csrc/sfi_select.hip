@@ -281,14 +281,22 @@ __global__ __launch_bounds__(kSelThreads) void sel_finalize_kernel(const SelArgs
 // a positive fp32 whose bit pattern orders like z_adj, so stages 2-4 are shared with mode 0.
 __device__ __forceinline__ float fast_log2s(float x) { return __builtin_amdgcn_logf(x); }
 
-// Deterministic block sum of one double per thread (fixed tree); result valid in every thread.
-__device__ __forceinline__ double block_sum_f64(double v, double* scratch) {
+// Deterministic block sums of kSegStats doubles per thread (fixed tree, one pair of barriers for all of
+// them); results valid in every thread.  scratch: [kSelThreads / 64][kSegStats] doubles of LDS.
+__device__ __forceinline__ void block_sums_f64(double (&v)[kSegStats], double (*scratch)[kSegStats]) {
 #pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
+  for (int i = 0; i < kSegStats; ++i) {
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v[i] += __shfl_xor(v[i], d);
+  }
   __syncthreads();
-  if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
+  if ((threadIdx.x & 63) == 0) {
+#pragma unroll
+    for (int i = 0; i < kSegStats; ++i) scratch[threadIdx.x >> 6][i] = v[i];
+  }
   __syncthreads();
-  return (scratch[0] + scratch[1]) + (scratch[2] + scratch[3]);
+#pragma unroll
+  for (int i = 0; i < kSegStats; ++i) v[i] = (scratch[0][i] + scratch[1][i]) + (scratch[2][i] + scratch[3][i]);
 }
 
 // (1a) evidence f (as in mode 0) and the unnormalised prior pi_kn * pi_pos (Eqs. selector_prior_kn,
@@ -376,12 +384,12 @@ __global__ __launch_bounds__(kSelThreads) void sel_prior_kernel(const SelArgs a)
     *reinterpret_cast<float4*>(fbuf + p) = make_float4(f[0], f[1], f[2], f[3]);
     *reinterpret_cast<float4*>(prior + p) = make_float4(rr[0], rr[1], rr[2], rr[3]);
   }
-  __shared__ double s_scr[4];
+  __shared__ double s_scr[kSelThreads / 64][kSegStats];
   double* out = a.segstat + ((int64_t)bh * a.n_seg_cap + seg) * kSegStats;
+  block_sums_f64(sums, s_scr);
+  if (tid == 0) {
 #pragma unroll
-  for (int i = 0; i < kSegStats; ++i) {
-    const double t = block_sum_f64(sums[i], s_scr);
-    if (tid == 0) out[i] = t;
+    for (int i = 0; i < kSegStats; ++i) out[i] = sums[i];
   }
 }
 
@@ -399,7 +407,7 @@ __global__ __launch_bounds__(kSelThreads) void sel_fuse_kernel(const SelArgs a) 
   const float* fbuf = reinterpret_cast<const float*>(a.keys) + (int64_t)bh * a.ld_pos;
   const float* prior = a.prior + (int64_t)bh * a.ld_pos;
   float* zn = a.znms + (int64_t)bh * a.ld_pos;
-  __shared__ double s_scr[4];
+  __shared__ double s_scr[kSelThreads / 64][kSegStats];
   __shared__ float s_z[kSelSeg + 2 * kMaxNmsRadius];
   const int n_seg = (pb.nJ + kSelSeg - 1) / kSelSeg;
   const double* st = a.segstat + (int64_t)bh * a.n_seg_cap * kSegStats;
@@ -408,8 +416,9 @@ __global__ __launch_bounds__(kSelThreads) void sel_fuse_kernel(const SelArgs a) 
   for (int i = 0; i < kSegStats; ++i) {
     double v = 0.0;
     for (int s = tid; s < n_seg; s += kSelThreads) v += st[(int64_t)s * kSegStats + i];
-    tot[i] = block_sum_f64(v, s_scr);
+    tot[i] = v;
   }
+  block_sums_f64(tot, s_scr);
   // f and r normalised to sum 1: |f|^2 = tot2 / F^2, f.r = tot3 / (F R), |r|^2 = tot4 / R^2
   const double F = tot[0], Rs = tot[1];
   const double ff = tot[2] / (F * F), fr = tot[3] / (F * Rs), rr = tot[4] / (Rs * Rs);
