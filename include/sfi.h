@@ -186,6 +186,8 @@ int sfi_slow_select(sfi_ctx* ctx, const int32_t* ctx_len, int32_t max_len, int32
  *                        (key norms from the last sfi_evidence_add).  -> sel_idx, n_sel.
  * Every added query must see the same allowed set J, i.e. the same ctx_len[] / max_len in every call (for the
  * tail of a causal prefill block: recent >= W, so that no window query is masked anywhere in J).
+ * sfi_evidence_add with out == NULL is the evidence-only pass: V is not read (and may be NULL), no attention
+ * output is written -- half the cache traffic, for callers whose prefill kernel has the outputs already.
  */
 int sfi_evidence_add(sfi_ctx* ctx, const void* q, const void* K, const void* V, const int32_t* ctx_len,
                      int32_t max_len, float* out, int32_t first, void* stream);

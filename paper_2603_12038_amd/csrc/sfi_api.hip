@@ -452,6 +452,7 @@ int slow_attn_impl(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   a.logits = x->ws.logits;
   a.with_knorm = x->cfg.selector_mode == 1;
   a.big_stash = 1;  // every sequence is dense: one workgroup per compute unit, half as many write bursts
+  a.no_v = out == nullptr;  // evidence only (sfi_evidence_add without an output)
   a.hist1 = x->ws.hist1;
   a.state = x->ws.state;
   x->last_dense_splits = a.n_split;
@@ -513,8 +514,15 @@ int sfi_slow_select(sfi_ctx* x, const int32_t* ctx_len, int32_t max_len, int32_t
 
 int sfi_evidence_add(sfi_ctx* x, const void* q, const void* K, const void* V, const int32_t* ctx_len,
                      int32_t max_len, float* out, int32_t first, void* stream) {
-  int rc = check_common(x, q, K, V, ctx_len, out);
-  if (rc != SFI_OK) return rc;
+  // out == nullptr: evidence only -- V is not read (and may be null), no attention output is produced
+  const bool evidence_only = out == nullptr;
+  if (x == nullptr || q == nullptr || K == nullptr || ctx_len == nullptr || (!evidence_only && V == nullptr))
+    return SFI_EINVAL;
+  if (misaligned(q, 16) || misaligned(K, 16) || misaligned(ctx_len, 4) ||
+      (!evidence_only && (misaligned(V, 16) || misaligned(out, 16))))
+    return SFI_EALIGN;
+  if (x->cfg.page_size != 0 && x->table == nullptr) return SFI_EINVAL;  // paged cache without a block table
+  int rc;
   int ml;
   if ((rc = resolve_max_len(x, max_len, &ml)) != SFI_OK) return rc;
   hipStream_t st = (hipStream_t)stream;

@@ -203,14 +203,15 @@ __device__ __forceinline__ void stage_logits(float* stage, const float (&y)[8], 
 
 // Ragged last tile: positions >= N carry no weight; their V rows may hold anything, so zero them
 // to keep 0 * v finite.
+template <bool WITH_V = true>  // false: the tile holds no V rows (evidence-only pass)
 __device__ __forceinline__ void mask_tail(Tile& T, float (&y)[8], int jg, int p0, int N) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const bool oka = p0 + 4 * jg + i < N, okb = p0 + 16 + 4 * jg + i < N;
     y[i] = oka ? y[i] : kNeg;
     y[4 + i] = okb ? y[4 + i] : kNeg;
-    if (!oka) T.v[i] = make_uint4(0u, 0u, 0u, 0u);
-    if (!okb) T.v[4 + i] = make_uint4(0u, 0u, 0u, 0u);
+    if (WITH_V && !oka) T.v[i] = make_uint4(0u, 0u, 0u, 0u);
+    if (WITH_V && !okb) T.v[4 + i] = make_uint4(0u, 0u, 0u, 0u);
   }
 }
 
@@ -357,12 +358,12 @@ __device__ __forceinline__ void finish_pair(const float* part, int64_t head0, in
 
 // record of (b, head, slot): { max of y, sum 2^(y - max), -, -, O[128] }, written by one wave
 __device__ __forceinline__ void write_wave_record(float* part, int64_t head0, int G, int wslot, const f32x4 (&acc)[8],
-                                                  float m_run, float l_run, int lane) {
+                                                  float m_run, float l_run, int lane, bool with_acc = true) {
   const int jg = lane >> 4, n = lane & 15;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int hh = 4 * jg + i;
-    if (hh < G) {
+    if (with_acc && hh < G) {
       float* dst = part + ((head0 + hh) * kSlotCap + wslot) * kPartStride + 4 + n * 8;
       *reinterpret_cast<float4*>(dst) = make_float4(acc[0][i], acc[1][i], acc[2][i], acc[3][i]);
       *reinterpret_cast<float4*>(dst + 4) = make_float4(acc[4][i], acc[5][i], acc[6][i], acc[7][i]);
@@ -403,7 +404,8 @@ struct ListWalk {
 // EXPOSE 1: also write y over J for the Selector; 2: y and the squared key norms.
 // BIG: twice the logits stash per wave, which leaves room for one workgroup per compute unit only
 // (launches where every sequence is dense run one per unit anyway; the mixed step keeps two).
-template <int EXPOSE, bool PAGED, bool BIG = false>
+// NOV: evidence only -- no V row is read, no P V product, the records carry the softmax statistics alone.
+template <int EXPOSE, bool PAGED, bool BIG = false, bool NOV = false>
 __global__ __launch_bounds__(kAttnThreads, BIG ? 1 : 2) void attn_dense_kernel(const AttnArgs a) {
   constexpr int kStash = BIG ? 2 * kStashFloats : kStashFloats;
   __shared__ float s_stash[EXPOSE != 0 ? kWaves : 1][EXPOSE != 0 ? kStash : 1];  // per-wave logits stash
@@ -437,7 +439,10 @@ __global__ __launch_bounds__(kAttnThreads, BIG ? 1 : 2) void attn_dense_kernel(c
   const int first = slot * kWaves + w, step = n_waves;
   Tile T;
   // (a paged cache has valid blocks only up to ctx_len: no load before ctx_len is known)
-  if (!PAGED && first < a.max_tiles) issue_affine(T, R, a.n_sink + first * kTile, a.row_cap);
+  if (!PAGED && first < a.max_tiles) {
+    issue_k_affine(T, R, a.n_sink + first * kTile, a.row_cap);
+    if (!NOV) issue_v_affine(T, R, a.n_sink + first * kTile, a.row_cap);
+  }
   bf16x8 qreg[4];
   load_q(qreg, a.q, head0, G, jg, n);
   const int L = a.ctx_len[b];
@@ -474,6 +479,7 @@ __global__ __launch_bounds__(kAttnThreads, BIG ? 1 : 2) void attn_dense_kernel(c
     }
   };
   auto issue_v_tile = [&](Tile& T, int t) {
+    if (NOV) return;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       T.v[i] = load_row16(R.Vb, (uint32_t)row_for(t, 4 * jg + i) * R.v_st + R.v_lane);
@@ -494,7 +500,7 @@ __global__ __launch_bounds__(kAttnThreads, BIG ? 1 : 2) void attn_dense_kernel(c
     pa_n = P.page_of(row_for(first + step, n));
     pb_n = P.page_of(row_for(first + step, 16 + n));
     __builtin_amdgcn_sched_barrier(0);
-    issue_v_rows<uint64_t>(T, R, pra, prb);
+    if (!NOV) issue_v_rows<uint64_t>(T, R, pra, prb);
     __builtin_amdgcn_sched_barrier(0);
   } else if (K > 0 && first >= nTJ) {  // short context: the first tile is a sink / recent tile after all
     issue_k_tile(T, first);
@@ -545,7 +551,7 @@ __global__ __launch_bounds__(kAttnThreads, BIG ? 1 : 2) void attn_dense_kernel(c
     float lr = l_run;
     lr += __shfl_xor(lr, 16);
     lr += __shfl_xor(lr, 32);
-    write_wave_record(a.part, head0, G, wslot, acc, m_run, lr, lane);
+    write_wave_record(a.part, head0, G, wslot, acc, m_run, lr, lane, !NOV);
   };
 
   // One loop for all of the wave's tiles.  A tile buffer's K half is refilled with the rows of the
@@ -588,12 +594,12 @@ __global__ __launch_bounds__(kAttnThreads, BIG ? 1 : 2) void attn_dense_kernel(c
     }
     const int p0 = (inJ ? t : t - nTJ) * kTile;
     const int N = inJ ? NJ : NS;
-    if (p0 + kTile > N) mask_tail(T, y, jg, p0, N);
+    if (p0 + kTile > N) mask_tail<!NOV>(T, y, jg, p0, N);
     bf16x8 a_hi, a_lo;
     softmax_phase(y, acc, m_run, l_run, jg, a_hi, a_lo);
-    pv_phase(T, a_hi, a_lo, acc);
-    if (PAGED) issue_v_rows<uint64_t>(T, R, pra, prb);
-    else issue_v_tile(T, t + NB * step);
+    if (!NOV) pv_phase(T, a_hi, a_lo, acc);
+    if (PAGED && !NOV) issue_v_rows<uint64_t>(T, R, pra, prb);
+    else if (!PAGED) issue_v_tile(T, t + NB * step);
   };
   if (PAGED) {
     for (int k = 0; k < K; ++k) tile_step(T, k);
@@ -1097,7 +1103,11 @@ hipError_t launch_trigger(const int32_t* last_token, const uint32_t* bitmap, int
 
 template <bool PAGED>
 static void launch_dense_t(const AttnArgs& a, dim3 grid, hipStream_t s) {
-  if (a.logits != nullptr && a.with_knorm && a.big_stash)
+  if (a.logits != nullptr && a.no_v && a.with_knorm)  // evidence only (always with the big stash)
+    hipLaunchKernelGGL((attn_dense_kernel<2, PAGED, true, true>), grid, dim3(kAttnThreads), 0, s, a);
+  else if (a.logits != nullptr && a.no_v)
+    hipLaunchKernelGGL((attn_dense_kernel<1, PAGED, true, true>), grid, dim3(kAttnThreads), 0, s, a);
+  else if (a.logits != nullptr && a.with_knorm && a.big_stash)
     hipLaunchKernelGGL((attn_dense_kernel<2, PAGED, true>), grid, dim3(kAttnThreads), 0, s, a);
   else if (a.logits != nullptr && a.with_knorm)
     hipLaunchKernelGGL((attn_dense_kernel<2, PAGED>), grid, dim3(kAttnThreads), 0, s, a);

@@ -97,7 +97,8 @@ __device__ __forceinline__ void merge_records(const float* part, float* out, int
       t.x += u.x; t.y += u.y; t.z += u.z; t.w += u.w;
     }
     const float inv = Z > 0.f ? 1.0f / Z : 0.f;
-    *reinterpret_cast<float4*>(out + (int64_t)bg * kHeadDim + 4 * tid) =
+    if (out != nullptr)  // nullptr: only the J statistics were wanted (evidence-only pass)
+      *reinterpret_cast<float4*>(out + (int64_t)bg * kHeadDim + 4 * tid) =
         make_float4(t.x * inv, t.y * inv, t.z * inv, t.w * inv);
   }
 }

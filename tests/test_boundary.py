@@ -121,7 +121,9 @@ def test_hot_calls_reject_bad_arguments_before_any_launch():
         assert lib.sfi_slow_select(h, p, 0, 64, None, p, None) == EINVAL
         assert lib.sfi_slow_select(h, p, 0, cfg.max_budget + 1, p, p, None) == EINVAL
         assert lib.sfi_slow_select(h, p + 2, 0, 64, p, p, None) == EALIGN
-        assert lib.sfi_evidence_add(h, p, p, p, p, 0, None, 1, None) == EINVAL
+        assert lib.sfi_evidence_add(h, p, p, None, p, 0, p, 1, None) == EINVAL   # an output needs V
+        assert lib.sfi_evidence_add(h, p, None, None, p, 0, None, 1, None) == EINVAL
+        assert lib.sfi_evidence_add(h, p, p + 2, None, p, 0, None, 1, None) == EALIGN
         assert lib.sfi_evidence_add(h, p, p, p, p, cfg.max_ctx + 1, p, 1, None) == EINVAL
         assert lib.sfi_evidence_select(h, 0, p, 0, 64, p, p, None) == EINVAL
         assert lib.sfi_evidence_select(h, 4, p, 0, 64, None, p, None) == EINVAL

@@ -135,3 +135,36 @@ def test_paged_calls_need_a_table(oracle):
         check_out(r.dense(w.q(0), w.ctx_len(0)), oracle.dense(w.q(0), w.K, w.V, w.ctx_len(0)))
     finally:
         r.close()
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_paged_evidence_only_pass(oracle, mode):
+    """The evidence-only pass (sfi_evidence_add without V and out) over a paged cache: the windowed selection
+    equals the one of the flat cache, bit for bit, in both Selector modes."""
+    import dataclasses
+    import torch
+    from oracle.sfi_oracle import SelectorParams
+    sp = SelectorParams(mode=1)
+    d = None
+    if mode == 1:
+        d = {k: getattr(sp, k) for k in ("gamma", "beta", "p", "eta", "lambda_clip", "alpha_soft", "alpha_cross", "temp",
+                                          "eps", "nms_radius")}
+    w = syn.make_tiny(L0=3300, steps=4, budget=120, recent=40, n_support=16, B=2, Hq=8, Hkv=2)
+    w.L0 = np.array([3300, 2111], np.int32)
+    got = []
+    for page in (0, 64):
+        r = Runner(w, selector=d, page_size=page)
+        try:
+            _step(f"evidence-only pass, mode {mode}, page size {page}")
+            ctx_d = i32_dev(w.ctx_len(0))
+            sel = torch.full((w.B, w.Hkv, w.budget), -7, dtype=torch.int32, device="cuda")
+            nsel = torch.full((w.B, w.Hkv), -7, dtype=torch.int32, device="cuda")
+            for t in range(3):
+                r.sfi.sfi_evidence_add(r.ctx.handle, to_dev(w.q(t)), r.K, None, ctx_d, 0, None, t == 0)
+            r.sfi.sfi_evidence_select(r.ctx.handle, 3, ctx_d, 0, w.budget, sel, nsel)
+            torch.cuda.synchronize()
+            got.append((sel.cpu().numpy(), nsel.cpu().numpy()))
+        finally:
+            r.close()
+    assert np.array_equal(got[0][0], got[1][0]) and np.array_equal(got[0][1], got[1][1])
+    assert (got[0][1] == w.budget).all()

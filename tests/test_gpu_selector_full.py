@@ -136,11 +136,13 @@ def test_power_mean_single_head_is_alpha_free(oracle):
     assert (sels[0] == sels[1]).all() and (sels[1] == sel_ref).all()
 
 
+@pytest.mark.parametrize("with_out", [True, False])
 @pytest.mark.parametrize("mode,alpha,W", [(0, 1.0, 5), (0, 0.5, 3), (1, 1.0, 4), (1, 0.5, 2), (0, 1.0, 1)])
-def test_windowed_evidence(oracle, mode, alpha, W):
+def test_windowed_evidence(oracle, mode, alpha, W, with_out):
     """Evidence accumulated over W window queries (Eq. selector_mu with a window): W calls of
     sfi_evidence_add and one sfi_evidence_select against the oracle's Selector on the W * G query vectors
-    of each KV head.  Each call's `out` is that query's dense attention."""
+    of each KV head.  Each call's `out` is that query's dense attention; without `out` (and without V) the
+    call is the evidence-only pass and the selection must come out the same."""
     import torch
     import paper_2603_12038_amd as sfi
     from helpers import i32_dev, to_dev
@@ -153,7 +155,7 @@ def test_windowed_evidence(oracle, mode, alpha, W):
     G = w.Hq // w.Hkv
     r = Runner(w, selector=d, alpha=alpha)
     try:
-        _step(f"windowed evidence mode={mode} alpha={alpha} W={W}")
+        _step(f"windowed evidence mode={mode} alpha={alpha} W={W} with_out={with_out}")
         ctx = w.ctx_len(0)
         ctx_d = i32_dev(ctx)
         qs = [w.q(t) for t in range(W)]
@@ -161,9 +163,14 @@ def test_windowed_evidence(oracle, mode, alpha, W):
         nsel = torch.full((w.B, w.Hkv), -7, dtype=torch.int32, device="cuda")
         for t, q in enumerate(qs):
             r.out.fill_(float("nan"))
-            sfi.sfi_evidence_add(r.ctx.handle, to_dev(q), r.K, r.V, ctx_d, 0, r.out, t == 0)
-            torch.cuda.synchronize()
-            check_out(r.out.cpu().numpy(), oracle.dense(q, w.K, w.V, ctx))
+            if with_out:
+                sfi.sfi_evidence_add(r.ctx.handle, to_dev(q), r.K, r.V, ctx_d, 0, r.out, t == 0)
+                torch.cuda.synchronize()
+                check_out(r.out.cpu().numpy(), oracle.dense(q, w.K, w.V, ctx))
+            else:
+                sfi.sfi_evidence_add(r.ctx.handle, to_dev(q), r.K, None, ctx_d, 0, None, t == 0)
+                torch.cuda.synchronize()
+                assert torch.isnan(r.out).all()  # nothing wrote an output
         sfi.sfi_evidence_select(r.ctx.handle, W, ctx_d, 0, w.budget, sel, nsel)
         torch.cuda.synchronize()
         # the oracle's window: per KV head the W * G vectors (query tau, head g)
