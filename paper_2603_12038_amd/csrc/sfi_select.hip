@@ -72,6 +72,33 @@ __device__ __forceinline__ void find_kth_desc(const uint32_t* hist, int nbins, u
   __syncthreads();
 }
 
+// The same with the thread's bins already in registers: hv[i] is bin (nbins - tid * N) - 1 - i.
+template <int N>
+__device__ __forceinline__ void find_kth_desc_regs(const uint32_t (&hv)[N], int nbins, uint32_t k, uint32_t* res,
+                                                   uint32_t* scratch) {
+  const int hi = nbins - (int)threadIdx.x * N;
+  if (threadIdx.x == 0) res[0] = res[1] = 0u;
+  uint32_t c = 0;
+#pragma unroll
+  for (int i = 0; i < N; ++i) c += hv[i];
+  uint32_t total;
+  const uint32_t above = block_excl_scan(c, scratch, &total);
+  if (above < k && k <= above + c) {
+    uint32_t cum = above;
+    bool found = false;
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      if (!found && cum + hv[i] >= k) {
+        res[0] = (uint32_t)(hi - 1 - i);
+        res[1] = k - cum;
+        found = true;
+      }
+      cum += hv[i];
+    }
+  }
+  __syncthreads();
+}
+
 struct Problem {
   int nJ;        // |J|
   uint32_t ksel; // min(budget, |J|)
@@ -501,11 +528,36 @@ __global__ __launch_bounds__(kSelThreads) void sel_cross_kernel(const SelArgs a)
 __global__ __launch_bounds__(kSelThreads) void sel_cand_kernel(const SelArgs a) {
   const int seg = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
-  const Problem pb = problem_of(a, b);
   const int p_lo = seg * kSelSeg;
   const int tid = threadIdx.x;
   const int bh = b * a.Hkv + h;
   uint32_t* st = a.state + (int64_t)bh * kStateWords;
+  // Requested before ctx_len has arrived (all of it readable whatever the context is): the thread's 8
+  // consecutive keys -- the key row is padded to a whole segment, so both 16-byte loads are always in
+  // bounds -- and its 16 bins of the pair's histogram.
+  constexpr int kPer = kSelSeg / kSelThreads;
+  static_assert(kPer == 8, "two 16-byte key loads per thread");
+  const int p0 = p_lo + tid * kPer;
+  uint32_t key[kPer];
+  {
+    const uint32_t* keys = a.keys + (int64_t)bh * a.ld_pos;
+    const uint4 k0 = *reinterpret_cast<const uint4*>(keys + p0);
+    const uint4 k1 = *reinterpret_cast<const uint4*>(keys + p0 + 4);
+    key[0] = k0.x; key[1] = k0.y; key[2] = k0.z; key[3] = k0.w;
+    key[4] = k1.x; key[5] = k1.y; key[6] = k1.z; key[7] = k1.w;
+  }
+  constexpr int kBinsPer = kHist1Bins / kSelThreads;
+  uint32_t hv[kBinsPer];  // bins hi - 1, hi - 2, ... of this thread, hi = kHist1Bins - tid * kBinsPer
+  {
+    const uint4* hq = reinterpret_cast<const uint4*>(a.hist1 + (int64_t)bh * kHist1Bins + (kHist1Bins - (tid + 1) * kBinsPer));
+    static_assert(kBinsPer == 16, "four 16-byte histogram loads per thread");
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint4 q4 = hq[3 - i];
+      hv[4 * i] = q4.w; hv[4 * i + 1] = q4.z; hv[4 * i + 2] = q4.y; hv[4 * i + 3] = q4.x;
+    }
+  }
+  const Problem pb = problem_of(a, b);
   if (pb.ksel == 0 || pb.ksel == (uint32_t)pb.nJ) {
     if (seg == 0 && tid == 0) {
       st[ST_KSEL] = pb.ksel;
@@ -515,23 +567,10 @@ __global__ __launch_bounds__(kSelThreads) void sel_cand_kernel(const SelArgs a) 
   }
   if (p_lo >= pb.nJ) return;
 
-  const uint32_t* keys = a.keys + (int64_t)bh * a.ld_pos;
   uint2* cand = reinterpret_cast<uint2*>(a.cand) + (int64_t)bh * a.ld_pos;  // (key, segment it came from)
-  // a thread owns 8 consecutive keys (the key row is padded to a whole segment, so both 16-byte
-  // loads are always readable); they are fetched while the threshold bin is being found
-  constexpr int kPer = kSelSeg / kSelThreads;
-  static_assert(kPer == 8, "two 16-byte key loads per thread");
-  const int p0 = p_lo + tid * kPer;
-  uint32_t key[kPer];
-  {
-    const uint4 k0 = *reinterpret_cast<const uint4*>(keys + p0);
-    const uint4 k1 = *reinterpret_cast<const uint4*>(keys + p0 + 4);
-    key[0] = k0.x; key[1] = k0.y; key[2] = k0.z; key[3] = k0.w;
-    key[4] = k1.x; key[5] = k1.y; key[6] = k1.z; key[7] = k1.w;
-  }
   __shared__ uint32_t s_res[2];
   __shared__ uint32_t s_scr[8];
-  find_kth_desc(a.hist1 + (int64_t)bh * kHist1Bins, kHist1Bins, pb.ksel, s_res, s_scr);
+  find_kth_desc_regs(hv, kHist1Bins, pb.ksel, s_res, s_scr);
   const uint32_t bin1 = s_res[0];
   if (seg == 0 && tid == 0) {
     st[ST_BIN1] = bin1;
