@@ -572,6 +572,11 @@ def main():
         "us_per_launch": float((fast_ms[0] if dominant != "dense" else slow_ms[0]) * 1e3),
     }
     dsp, fsp = sfi.sfi_query_splits(h)
+    # SFI_GUARD_* bits the kernels raised since the contexts were created: 0 = no length, count, stored index
+    # or block id of the run had to be clamped
+    device_status = 0
+    for c in ring:
+        device_status |= sfi.sfi_device_status(c.handle)
     # fewer workgroups per pair than one tile per wave needs: the pipelined gather kernel ran
     fast_tiles = -(-(w.n_sink + w.budget + w.recent) // 32)
     if not compact and fsp * 4 < fast_tiles and roof["kernel"] == "sfi::attn_gather_kernel":
@@ -602,6 +607,7 @@ def main():
         "us_per_decode_step_per_layer": total_s * 1e6 / (K_seg * SEG * NL),
         "gpu_event_ms": gpu_ms,
         "parity_sample": parity,
+        "device_status": device_status,
         "cpu_baseline": cpu_baseline,
     }
     print(json.dumps(res))

@@ -313,6 +313,30 @@ int sfi_set_tuning(sfi_ctx* ctx, int32_t dense_target_wgs, int32_t fast_tiles_pe
 int sfi_plan_splits(const sfi_ctx* ctx, int32_t max_len, int32_t sel_stride, int32_t* dense_splits,
                     int32_t* fast_splits);
 
+/*
+ * Device-side inputs that were out of range.  ctx_len, recent_start, n_sel, sel_idx and the block table live
+ * in device memory, so no host check can vet them before a launch.  Every kernel therefore brings them into
+ * range before they address memory, so that a launch stays inside the caller's buffers whatever these arrays
+ * hold:
+ *   ctx_len[b]       to [0, max_len] (cfg.max_ctx for calls without a max_len);
+ *   recent_start[b]  to [min(n_sink, ctx_len[b]), ctx_len[b]] (silently: any value is allowed and read this way);
+ *   n_sel[b, h]      to [0, sel_stride];
+ *   a stored index   outside [0, ctx_len[b]) reads as row ctx_len[b] - 1;
+ *   a block id       to [0, n_blocks).
+ * A kernel that changed a value it used ORs the matching bit below into a word of the workspace (padding
+ * entries of sel_idx and table entries past ctx_len[b] are never looked at).  The outputs of a call that raised
+ * a bit are unspecified.
+ *
+ * This call waits for `stream`, copies the word to *flags (HOST int32) and, with clear != 0, zeroes it.
+ * It blocks the host and is not part of the hot path: poll it when debugging, or once in a while.  Not to be
+ * called while a stream of the device is capturing.  The word is also zeroed by sfi_create.
+ */
+#define SFI_GUARD_CTX_LEN 1 /* a ctx_len[b] was negative or above the call's bound */
+#define SFI_GUARD_N_SEL 2   /* an n_sel[b, h] was negative or above sel_stride */
+#define SFI_GUARD_SEL_IDX 4 /* an index among sel_idx[b, h, 0:n_sel] was outside [0, ctx_len[b]) */
+#define SFI_GUARD_BLOCK 8   /* a block-table entry covering rows [0, ctx_len[b]) was outside [0, n_blocks) */
+int sfi_device_status(sfi_ctx* ctx, int32_t* flags, int32_t clear, void* stream);
+
 /* Launch geometry of the last call (for reports): split workgroups per (sequence, KV head). */
 int sfi_query_splits(const sfi_ctx* ctx, int32_t* dense_splits, int32_t* fast_splits);
 

@@ -42,7 +42,7 @@ _lib: Optional[C.CDLL] = None
 EXPORTS = ("sfi_workspace_bytes", "sfi_create", "sfi_set_block_table", "sfi_destroy", "sfi_strerror", "sfi_slow_step", "sfi_slow_attn",
            "sfi_slow_select", "sfi_evidence_add", "sfi_evidence_select", "sfi_dense_attn",
            "sfi_fast_step", "sfi_reorg", "sfi_fast_step_compact", "sfi_mixed_step", "sfi_trigger", "sfi_advance", "sfi_set_profiling", "sfi_stage_times",
-           "sfi_set_tuning", "sfi_plan_splits", "sfi_query_splits")
+           "sfi_set_tuning", "sfi_plan_splits", "sfi_device_status", "sfi_query_splits")
 
 
 def load_library() -> C.CDLL:
@@ -96,6 +96,8 @@ def load_library() -> C.CDLL:
     lib.sfi_set_tuning.argtypes = [vp, i32, i32, i32]
     lib.sfi_plan_splits.restype = C.c_int
     lib.sfi_plan_splits.argtypes = [vp, i32, i32, C.POINTER(i32), C.POINTER(i32)]
+    lib.sfi_device_status.restype = C.c_int
+    lib.sfi_device_status.argtypes = [vp, C.POINTER(i32), i32, vp]
     lib.sfi_query_splits.restype = C.c_int
     lib.sfi_query_splits.argtypes = [vp, C.POINTER(i32), C.POINTER(i32)]
     _lib = lib
@@ -237,6 +239,17 @@ def sfi_plan_splits(ctx, max_len: int, sel_stride: int) -> Tuple[int, int]:
     d, f = C.c_int32(), C.c_int32()
     _check(load_library().sfi_plan_splits(ctx, max_len, sel_stride, C.byref(d), C.byref(f)), "sfi_plan_splits")
     return d.value, f.value
+
+
+GUARD_CTX_LEN, GUARD_N_SEL, GUARD_SEL_IDX, GUARD_BLOCK = 1, 2, 4, 8
+
+
+def sfi_device_status(ctx, clear: bool = True, stream=None) -> int:
+    """SFI_GUARD_* bits of device-side inputs the kernels had to clamp (blocks until `stream` is done)."""
+    flags = C.c_int32()
+    _check(load_library().sfi_device_status(ctx, C.byref(flags), 1 if clear else 0, _stream(stream)),
+           "sfi_device_status")
+    return flags.value
 
 
 def sfi_query_splits(ctx) -> Tuple[int, int]:

@@ -15,7 +15,7 @@ struct sfi_ctx {
   int n_cu;
   float alpha;              // power-mean exponent of the evidence, in (0, 1]
   const int32_t* table;     // paged cache: device block table, nullptr until sfi_set_block_table
-  int table_stride, page_lg, page_rpb;
+  int table_stride, page_lg, page_rpb, n_blocks;
   int dense_target_wgs;     // workgroups the dense launch aims for; 0 = decided per launch
   int fast_tiles_per_wave;  // 32-row tiles each wave of the gather launch should get; 0 = decided per launch
   int tail_merge;           // split fast-step launches merge in the attention kernel (no merge launch)
@@ -101,6 +101,7 @@ size_t carve(const sfi_config* c, char* base, Workspace* ws) {
   ws->jstat = (float2*)take((size_t)(B * Hq) * sizeof(float2));
   ws->mu = (float*)take((size_t)(B * Hkv) * ld * sizeof(float));
   ws->arrive = (uint32_t*)take((size_t)(B * Hkv) * sizeof(uint32_t));
+  ws->guard = (int32_t*)take(sizeof(int32_t));  // directly behind the counters: one memset clears both
   ws->prior = full ? (float*)take((size_t)(B * Hkv) * ld * sizeof(float)) : nullptr;
   ws->znms = full ? (float*)take((size_t)(B * Hkv) * ld * sizeof(float)) : nullptr;
   ws->segstat = full ? (double*)take((size_t)(B * Hkv) * n_seg * kSegStats * sizeof(double)) : nullptr;
@@ -165,6 +166,7 @@ void set_dense_bounds(const sfi_ctx* x, AttnArgs* a, int max_len) {
   const int nJ = max_len - x->cfg.recent - x->cfg.n_sink;
   a->max_tiles = nJ > 0 ? (nJ + kTile - 1) / kTile : 0;
   a->row_cap = max_len - 1;
+  a->len_cap = max_len;
 }
 
 // Gather launch geometry: the balanced split above.  With one workgroup per pair the workgroup
@@ -243,9 +245,12 @@ void fill_attn(const sfi_ctx* x, AttnArgs* a, const void* q, const void* K, cons
   a->n_sink = c.n_sink; a->recent = c.recent;
   a->scale_log2 = (float)((double)x->scale * 1.4426950408889634);
   a->table = x->table; a->table_stride = x->table_stride; a->page_lg = x->page_lg; a->page_rpb = x->page_rpb;
+  a->n_blocks = x->n_blocks;
+  a->len_cap = c.max_ctx;  // calls with a max_len lower it (set_dense_bounds)
+  a->guard = x->ws.guard;
 }
 
-void fill_sel(const sfi_ctx* x, SelArgs* s, const int32_t* ctx_len, const uint8_t* is_slow, int budget,
+void fill_sel(const sfi_ctx* x, SelArgs* s, const int32_t* ctx_len, int max_len, const uint8_t* is_slow, int budget,
               int n_split, int32_t* sel_idx, int32_t* n_sel) {
   memset(s, 0, sizeof(*s));
   const sfi_config& c = x->cfg;
@@ -265,6 +270,7 @@ void fill_sel(const sfi_ctx* x, SelArgs* s, const int32_t* ctx_len, const uint8_
   s->inv_alpha = 1.0f / x->alpha;
   s->mu = x->ws.mu; s->mu_scale = 1.0f;
   s->lg_rows = x->G + (c.selector_mode == 1 ? 1 : 0);
+  s->len_cap = max_len;
 }
 
 #define SFI_TRY(expr)                         \
@@ -367,7 +373,8 @@ int sfi_create(const sfi_config* cfg, void* workspace, size_t workspace_bytes, s
   hipPointerAttribute_t attr;
   if (have_device && hipPointerGetAttributes(&attr, ws.arrive) == hipSuccess &&
       attr.type == hipMemoryTypeDevice) {
-    if (hipMemset(ws.arrive, 0, (size_t)cfg->batch * cfg->n_kv_heads * sizeof(uint32_t)) != hipSuccess ||
+    const size_t n_clear = (size_t)((char*)ws.guard - (char*)ws.arrive) + sizeof(int32_t);  // counters and guard word
+    if (hipMemset(ws.arrive, 0, n_clear) != hipSuccess ||
         hipDeviceSynchronize() != hipSuccess) {
       (void)hipGetLastError();
       delete x;
@@ -394,6 +401,7 @@ int sfi_set_block_table(sfi_ctx* x, const int32_t* block_table, int32_t table_st
   if ((int64_t)n_blocks * x->page_rpb >= ((int64_t)1 << 31)) return SFI_EUNSUPPORTED;  // row numbers are 32-bit
   x->table = block_table;
   x->table_stride = table_stride;
+  x->n_blocks = n_blocks;
   return SFI_OK;
 }
 
@@ -435,7 +443,7 @@ int sfi_dense_attn(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   set_dense_bounds(x, &a, ml);
   x->last_dense_splits = a.n_split;
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
-  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, a.n_split * kWaves, 0, 0, nullptr, 0, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha};
+  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, a.n_split * kWaves, 0, 0, nullptr, 0, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha, ml};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
 }
@@ -458,7 +466,7 @@ int slow_attn_impl(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   x->last_dense_splits = a.n_split;
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
   if (merge_later) return SFI_OK;  // the Selector's scoring launch merges
-  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, a.n_split * kWaves, 0, 0, x->ws.jstat, a.n_split * kWaves, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha};
+  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, a.n_split * kWaves, 0, 0, x->ws.jstat, a.n_split * kWaves, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha, ml};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
 }
@@ -484,7 +492,7 @@ int sfi_slow_step(sfi_ctx* x, const void* q, const void* K, const void* V, const
   // no merge launch: the merge rides in the Selector's first launch (one launch less on the step's critical path)
   if ((rc = slow_attn_impl(x, q, K, V, ctx_len, ml, out, st, true)) != SFI_OK) return rc;
   SelArgs sa;
-  fill_sel(x, &sa, ctx_len, nullptr, budget, x->last_dense_splits, sel_idx, n_sel);
+  fill_sel(x, &sa, ctx_len, ml, nullptr, budget, x->last_dense_splits, sel_idx, n_sel);
   sa.part = x->ws.part;
   sa.merge_out = out;
   return run_selector(x, sa, ml, st);
@@ -508,7 +516,7 @@ int sfi_slow_select(sfi_ctx* x, const int32_t* ctx_len, int32_t max_len, int32_t
   if ((rc = resolve_max_len(x, max_len, &ml)) != SFI_OK) return rc;
   CallRecord call_record(x);
   SelArgs sa;
-  fill_sel(x, &sa, ctx_len, nullptr, budget, x->last_dense_splits, sel_idx, n_sel);
+  fill_sel(x, &sa, ctx_len, ml, nullptr, budget, x->last_dense_splits, sel_idx, n_sel);
   return run_selector(x, sa, ml, (hipStream_t)stream);
 }
 
@@ -529,7 +537,7 @@ int sfi_evidence_add(sfi_ctx* x, const void* q, const void* K, const void* V, co
   CallRecord call_record(x);
   if ((rc = slow_attn_impl(x, q, K, V, ctx_len, ml, out, st)) != SFI_OK) return rc;
   SelArgs sa;
-  fill_sel(x, &sa, ctx_len, nullptr, 0, x->last_dense_splits, nullptr, nullptr);
+  fill_sel(x, &sa, ctx_len, ml, nullptr, 0, x->last_dense_splits, nullptr, nullptr);
   sa.accum_first = first != 0;
   const int nJ = ml - x->cfg.recent - x->cfg.n_sink;
   int n_seg = nJ > 0 ? (nJ + kSelSeg - 1) / kSelSeg : 1;
@@ -547,7 +555,7 @@ int sfi_evidence_select(sfi_ctx* x, int32_t n_added, const int32_t* ctx_len, int
   if ((rc = resolve_max_len(x, max_len, &ml)) != SFI_OK) return rc;
   CallRecord call_record(x);
   SelArgs sa;
-  fill_sel(x, &sa, ctx_len, nullptr, budget, x->last_dense_splits, sel_idx, n_sel);
+  fill_sel(x, &sa, ctx_len, ml, nullptr, budget, x->last_dense_splits, sel_idx, n_sel);
   sa.mu_scale = 1.0f / (float)n_added;
   sa.f_from_mu = 1;
   return run_selector(x, sa, ml, (hipStream_t)stream, true);
@@ -575,7 +583,7 @@ int sfi_fast_step(sfi_ctx* x, const void* q, const void* K, const void* V, const
   else if (x->tail_merge) { a.out_merge = out; a.arrive = x->ws.arrive; }
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_gather(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
   if (a.n_split == 1 || a.out_merge != nullptr) return SFI_OK;
-  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1, nullptr, 0, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha};
+  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1, nullptr, 0, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha, x->cfg.max_ctx};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
 }
@@ -617,6 +625,7 @@ int sfi_reorg(sfi_ctx* x, const void* K, const void* V, const int32_t* sel_idx, 
   r.Kc = (uint16_t*)Kc; r.Vc = (uint16_t*)Vc; r.c_sb = c_stride_b; r.c_sh = c_stride_h;
   r.Hkv = c.n_kv_heads; r.n_sink = c.n_sink;
   r.table = x->table; r.table_stride = x->table_stride; r.page_lg = x->page_lg; r.page_rpb = x->page_rpb;
+  r.len_cap = c.max_ctx; r.n_blocks = x->n_blocks; r.guard = x->ws.guard;
   { StageTimer t(x, st, SFI_STAGE_REORG); SFI_TRY(launch_reorg(r, c.batch, c.n_sink + sel_stride, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
 }
@@ -645,7 +654,7 @@ int sfi_fast_step_compact(sfi_ctx* x, const void* q, const void* Kc, const void*
   else if (x->tail_merge) { a.out_merge = out; a.arrive = x->ws.arrive; }
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_compact(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
   if (a.n_split == 1 || a.out_merge != nullptr) return SFI_OK;
-  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1, nullptr, 0, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha};
+  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1, nullptr, 0, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha, x->cfg.max_ctx};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
 }
@@ -680,6 +689,7 @@ int sfi_mixed_step(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   f.sel_idx = sel_idx;
   f.n_sel = n_sel;
   f.sel_stride = budget;
+  f.len_cap = ml;
   f.n_split = fast_splits_for(x, budget, &f.pipelined);
   if (f.n_split == 1) f.out_direct = out;
   else if (x->tail_merge) { f.out_merge = out; f.arrive = x->ws.arrive; }  // slow sequences' workgroups never arrive
@@ -694,13 +704,13 @@ int sfi_mixed_step(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   { StageTimer t(x, st, SFI_STAGE_ATTN2); SFI_TRY(launch_attn_gather(f, x->cfg.batch, f.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(d, x->cfg.batch, d.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
   if (!merge_in_score) {
-    MergeArgs m{x->ws.part, out, is_slow, x->cfg.n_q_heads, d.n_split * kWaves, fast_done ? 0 : f.n_split, 2, x->ws.jstat, d.n_split * kWaves, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha};
+    MergeArgs m{x->ws.part, out, is_slow, x->cfg.n_q_heads, d.n_split * kWaves, fast_done ? 0 : f.n_split, 2, x->ws.jstat, d.n_split * kWaves, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha, ml};
     StageTimer t(x, st, SFI_STAGE_MERGE);
     SFI_TRY(launch_merge(m, x->cfg.batch, st));
     if (!t.stop()) return SFI_ELAUNCH;
   }
   SelArgs sa;
-  fill_sel(x, &sa, ctx_len, is_slow, budget, d.n_split, sel_idx, n_sel);
+  fill_sel(x, &sa, ctx_len, ml, is_slow, budget, d.n_split, sel_idx, n_sel);
   if (merge_in_score) {
     sa.part = x->ws.part;
     sa.merge_out = out;
@@ -786,6 +796,22 @@ int sfi_plan_splits(const sfi_ctx* x, int32_t max_len, int32_t sel_stride, int32
   int pipelined;
   if (dense_splits) *dense_splits = dense_splits_for(x, ml, false);
   if (fast_splits) *fast_splits = fast_splits_for(x, sel_stride, &pipelined);
+  return SFI_OK;
+}
+
+int sfi_device_status(sfi_ctx* x, int32_t* flags, int32_t clear, void* stream) {
+  if (x == nullptr || flags == nullptr) return SFI_EINVAL;
+  static_assert(kGuardCtxLen == SFI_GUARD_CTX_LEN && kGuardNSel == SFI_GUARD_N_SEL &&
+                kGuardSelIdx == SFI_GUARD_SEL_IDX && kGuardBlock == SFI_GUARD_BLOCK, "guard bits");
+  hipStream_t st = (hipStream_t)stream;
+  int32_t v = 0;
+  SFI_TRY(hipMemcpyAsync(&v, x->ws.guard, sizeof(v), hipMemcpyDeviceToHost, st));
+  SFI_TRY(hipStreamSynchronize(st));
+  if (clear != 0 && v != 0) {
+    SFI_TRY(hipMemsetAsync(x->ws.guard, 0, sizeof(v), st));
+    SFI_TRY(hipStreamSynchronize(st));
+  }
+  *flags = v;
   return SFI_OK;
 }
 

@@ -84,16 +84,38 @@ struct Rows {
 struct Pages {
   const int32_t* tbl;  // this sequence's row of the block table
   int lg, mask, rpb;
+  int last;            // n_blocks - 1: a block id outside [0, last] is clamped and noted in the caller's flags
+  bool live;           // ctx_len > 0 (an empty context has no valid table entry; its padding reads go to row 0 of
+                       // whatever block the clamp yields and are not reported)
   __device__ __forceinline__ int page_of(int row) const { return tbl[row >> lg]; }
-  __device__ __forceinline__ int phys(int row, int page) const { return page * rpb + (row & mask); }
+  __device__ __forceinline__ int phys(int row, int page, int& bad) const {
+    const int pc = min(max(page, 0), last);
+    bad |= (pc != page && live) ? kGuardBlock : 0;
+    return pc * rpb + (row & mask);
+  }
 };
-__device__ __forceinline__ Pages pages_of(const AttnArgs& a, int b) {
+__device__ __forceinline__ Pages pages_of(const AttnArgs& a, int b, int L) {
   Pages P;
   P.tbl = a.table + (int64_t)b * a.table_stride;
   P.lg = a.page_lg;
   P.mask = (1 << a.page_lg) - 1;
   P.rpb = a.page_rpb;
+  P.last = a.n_blocks - 1;
+  P.live = L > 0;
   return P;
+}
+
+// ctx_len[b] clamped to what the launch may touch.
+__device__ __forceinline__ int guarded_len(int L0, int cap, int& bad) {
+  const int L = min(max(L0, 0), cap);
+  bad |= L != L0 ? kGuardCtxLen : 0;
+  return L;
+}
+// A lane that had to clamp an input says so, once, as the last thing the kernel does: a store inside the
+// loop would sit in the in-order memory counter the pipelined loops wait on, and even the untaken branch,
+// placed between the loop and the record write, cost the fast step 0.2 us.
+__device__ __forceinline__ void report_guard(int32_t* guard, int bad) {
+  if (bad != 0 && guard != nullptr) atomicOr(guard, bad);
 }
 
 // Row loads of a tile whose positions map to consecutive cache rows: block A row n is cache row
@@ -383,17 +405,32 @@ struct ListWalk {
   int sel_cap;         // sel_stride - 1
   int n_sink;
   int nS, nSel, rs, N;
+  int r_hi;            // last readable row, max(L, 1) - 1: a stored index outside [0, r_hi] reads as r_hi
+  int bad;
+  __device__ __forceinline__ void set_counts(int L, int n_sel, int recent_start, int sel_stride) {
+    nS = min(n_sink, L);
+    nSel = min(max(n_sel, 0), sel_stride);
+    bad |= nSel != n_sel ? kGuardNSel : 0;
+    rs = min(max(recent_start, nS), L);
+    N = nS + nSel + (L - rs);
+    r_hi = max(L, 1) - 1;
+  }
   __device__ __forceinline__ int sel_at(int p) const {  // index stored for list position p (valid inside the sel part)
     return sel_cap >= 0 ? sel[min(max(p - n_sink, 0), sel_cap)] : 0;
   }
   __device__ __forceinline__ int sel_at_nonempty(int p) const {  // the same without the branch; needs sel_cap >= 0
     return sel[min(max(p - n_sink, 0), sel_cap)];
   }
-  __device__ __forceinline__ int row_of(int p, int s) const {
+  __device__ __forceinline__ int row_of(int p, int s) {
     const int i = p - nS;
     int r = i < nSel ? s : rs + (i - nSel);
     r = p < nS ? p : r;
-    return p < N ? r : 0;
+    r = p < N ? r : 0;
+    // Sink and recent rows are inside the context by construction, so only a stored index can change here.
+    // One clamp for both ends: a negative row reads as a huge one.
+    const int rc = (int)min((uint32_t)r, (uint32_t)r_hi);
+    bad |= rc != r ? kGuardSelIdx : 0;
+    return rc;
   }
 };
 
@@ -445,7 +482,8 @@ __global__ __launch_bounds__(kAttnThreads, BIG ? 1 : 2) void attn_dense_kernel(c
   }
   bf16x8 qreg[4];
   load_q(qreg, a.q, head0, G, jg, n);
-  const int L = a.ctx_len[b];
+  int bad = 0;
+  const int L = guarded_len(a.ctx_len[b], a.len_cap, bad);
   if (slot == 0 && a.hist1 != nullptr) {  // fresh Selector state for this (b, h)
     uint32_t* hh = a.hist1 + (int64_t)bh * kHist1Bins;
     for (int i = tid; i < kHist1Bins; i += kAttnThreads) hh[i] = 0u;
@@ -461,8 +499,9 @@ __global__ __launch_bounds__(kAttnThreads, BIG ? 1 : 2) void attn_dense_kernel(c
   const int nT = nTJ + nTS;
   const int K = first < nT ? (nT - first + step - 1) / step : 0;      // tiles of this wave
   const int KJ = first < nTJ ? (nTJ - first + step - 1) / step : 0;   // ... of which in J
-  const int d_rs = rs - nS, r_last = L - 1;
+  const int d_rs = rs - nS, r_last = max(L, 1) - 1;
   // cache row of position i of tile t; tiles past the end (the refill after the last tile) read row L - 1
+  // (row 0 of an empty context: the cache holds max_ctx >= 1 rows)
   auto row_for = [&](int t, int i) -> int {
     const int xj = a.n_sink + t * kTile + i;
     const int xs = (t - nTJ) * kTile + i;
@@ -491,9 +530,9 @@ __global__ __launch_bounds__(kAttnThreads, BIG ? 1 : 2) void attn_dense_kernel(c
   if (PAGED) {
     // Same order of memory instructions as an iteration of the loop: K rows, the table entries of the
     // tile after, V rows.  Waves without tiles read row L - 1.
-    P = pages_of(a, b);
+    P = pages_of(a, b, L);
     const int ra = row_for(first, n), rb = row_for(first, 16 + n);
-    const int pra = P.phys(ra, P.page_of(ra)), prb = P.phys(rb, P.page_of(rb));
+    const int pra = P.phys(ra, P.page_of(ra), bad), prb = P.phys(rb, P.page_of(rb), bad);
     __builtin_amdgcn_sched_barrier(0);
     issue_k_rows<uint64_t>(T, R, pra, prb);
     __builtin_amdgcn_sched_barrier(0);
@@ -575,8 +614,8 @@ __global__ __launch_bounds__(kAttnThreads, BIG ? 1 : 2) void attn_dense_kernel(c
     if (EXPOSE == 2) knorm_phase(T, jg, n, k2a, k2b);
     int pra = 0, prb = 0;
     if (PAGED) {
-      pra = P.phys(row_for(t + step, n), pa_n);
-      prb = P.phys(row_for(t + step, 16 + n), pb_n);
+      pra = P.phys(row_for(t + step, n), pa_n, bad);
+      prb = P.phys(row_for(t + step, 16 + n), pb_n, bad);
       issue_k_rows<uint64_t>(T, R, pra, prb);
       pa_n = P.page_of(row_for(t + 2 * step, n));
       pb_n = P.page_of(row_for(t + 2 * step, 16 + n));
@@ -618,6 +657,7 @@ __global__ __launch_bounds__(kAttnThreads, BIG ? 1 : 2) void attn_dense_kernel(c
   // the record still open: the J record if the wave had no other tile (slot first), else the record of
   // its sink / recent tiles, slot n_waves + e with e the rank of its first such tile among them
   write_record(K == KJ ? first : n_waves + (first + KJ * step - nTJ));
+  report_guard(a.guard, bad);
 }
 
 // With out != nullptr the workgroup is the only one of its (b, h) pair: it writes the normalised
@@ -710,6 +750,9 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_kernel(const Attn
   const int bh = b * a.Hkv + h;
   const int64_t head0 = (int64_t)b * a.Hq + h * G;
   const int first = slot * kWaves + w, step = a.n_split * kWaves;
+  // The step's three scalars are requested together, ahead of everything else: read one by one where
+  // they are used, the wait for the first would hold back the requests for the others (a round trip each).
+  const int L_in = a.ctx_len[b], n_sel_in = a.n_sel[bh], rs_in = a.recent_start[b];
 
   // ---- first round of loads, none depending on another: the selected indices of this wave's first
   // tile (read before the list length is known, clamped to the row of sel_idx), q, the scalars.
@@ -721,11 +764,9 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_kernel(const Attn
   int sB = W.sel_at(first * kTile + 16 + n);
   bf16x8 qreg[4];
   load_q(qreg, a.q, head0, G, jg, n);
-  const int L = a.ctx_len[b];
-  W.nS = min(a.n_sink, L);
-  W.nSel = a.n_sel[bh];
-  W.rs = min(max(a.recent_start[b], W.nS), L);
-  W.N = W.nS + W.nSel + (L - W.rs);
+  W.bad = 0;
+  const int L = guarded_len(L_in, a.len_cap, W.bad);
+  W.set_counts(L, n_sel_in, rs_in, (int)a.sel_stride);
 
   Rows R;
   R.Kb = reinterpret_cast<const char*>(a.K + b * a.k_sb + h * a.k_sh);
@@ -752,9 +793,9 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_kernel(const Attn
     }
     int ra = W.row_of(p0 + n, sA), rb = W.row_of(p0 + 16 + n, sB);
     if (PAGED) {  // one more dependent round: row -> block-table entry -> physical row
-      const Pages P = pages_of(a, b);
-      ra = P.phys(ra, P.page_of(ra));
-      rb = P.phys(rb, P.page_of(rb));
+      const Pages P = pages_of(a, b, L);
+      ra = P.phys(ra, P.page_of(ra), W.bad);
+      rb = P.phys(rb, P.page_of(rb), W.bad);
     }
     issue_rows<typename RowOff<PAGED>::type>(T, R, ra, rb);
     if (p0 + kTile <= W.N) tile_math<false>(T, qreg, a.scale_log2, acc, m_run, l_run, jg, p0, W.N);
@@ -764,6 +805,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_kernel(const Attn
   l_run += __shfl_xor(l_run, 32);
   write_wg_record(a.part, head0, G, slot, acc, m_run, l_run, a.out_direct, a.out_merge,
                   a.arrive != nullptr ? a.arrive + bh : nullptr, a.n_split);
+  report_guard(a.guard, W.bad);  // last: the way to the record and the merge is the launch's critical path
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -786,6 +828,9 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(con
   const int64_t head0 = (int64_t)b * a.Hq + h * G;
   const int first = slot * kWaves + w, step = a.n_split * kWaves;
   const int pstep = step * kTile;
+  // The step's three scalars are requested together, ahead of everything else: read one by one where
+  // they are used, the wait for the first would hold back the requests for the others (a round trip each).
+  const int L_in = a.ctx_len[b], n_sel_in = a.n_sel[bh], rs_in = a.recent_start[b];
 
   ListWalk W;
   W.sel = a.sel_idx + (int64_t)bh * a.sel_stride;
@@ -795,11 +840,9 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(con
   const int sA = W.sel_at_nonempty(p_first + n), sB = W.sel_at_nonempty(p_first + 16 + n);
   bf16x8 qreg[4];
   load_q(qreg, a.q, head0, G, jg, n);
-  const int L = a.ctx_len[b];
-  W.nS = min(a.n_sink, L);
-  W.nSel = a.n_sel[bh];
-  W.rs = min(max(a.recent_start[b], W.nS), L);
-  W.N = W.nS + W.nSel + (L - W.rs);
+  W.bad = 0;
+  const int L = guarded_len(L_in, a.len_cap, W.bad);
+  W.set_counts(L, n_sel_in, rs_in, (int)a.sel_stride);
 
   Rows R;
   R.Kb = reinterpret_cast<const char*>(a.K + b * a.k_sb + h * a.k_sh);
@@ -829,11 +872,11 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(con
   int pa_n = 0, pb_n = 0;
   Pages P;
   if (PAGED) {
-    P = pages_of(a, b);
+    P = pages_of(a, b, L);
     const int sA1 = W.sel_at_nonempty(p_first + pstep + n), sB1 = W.sel_at_nonempty(p_first + pstep + 16 + n);
     int ra = W.row_of(p_first + n, sA), rb = W.row_of(p_first + 16 + n, sB);
-    ra = P.phys(ra, P.page_of(ra));
-    rb = P.phys(rb, P.page_of(rb));
+    ra = P.phys(ra, P.page_of(ra), W.bad);
+    rb = P.phys(rb, P.page_of(rb), W.bad);
     __builtin_amdgcn_sched_barrier(0);
     issue_k_rows<typename RowOff<PAGED>::type>(T, R, ra, rb);
     __builtin_amdgcn_sched_barrier(0);
@@ -865,8 +908,8 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(con
     qk_phase(T, qreg, a.scale_log2, y);
     int ra, rb;
     if (PAGED) {
-      ra = P.phys(ra_n, pa_n);
-      rb = P.phys(rb_n, pb_n);
+      ra = P.phys(ra_n, pa_n, W.bad);
+      rb = P.phys(rb_n, pb_n, W.bad);
       issue_k_rows<typename RowOff<PAGED>::type>(T, R, ra, rb);
       ra_n = W.row_of(pn + pstep + n, sAn);  // row 0 past the list
       rb_n = W.row_of(pn + pstep + 16 + n, sBn);
@@ -891,6 +934,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(con
   l_run += __shfl_xor(l_run, 32);
   write_wg_record(a.part, head0, G, slot, acc, m_run, l_run, a.out_direct, a.out_merge,
                   a.arrive != nullptr ? a.arrive + bh : nullptr, a.n_split);
+  report_guard(a.guard, W.bad);  // last: the way to the record and the merge is the launch's critical path
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -931,13 +975,16 @@ __global__ __launch_bounds__(kAttnThreads, PAGED ? 2 : 3) void attn_compact_kern
   if (spec) issue_affine(T, Rc, first * kTile, a.c_rows - 1);
   bf16x8 qreg[4];
   load_q(qreg, a.q, head0, G, jg, n);
-  const int L = a.ctx_len[b];
-  const int nSel = a.n_sel[bh];
+  int bad = 0;
+  const int L_in = a.ctx_len[b], nSel0 = a.n_sel[bh], rs_in = a.recent_start[b];  // one round trip for the three
+  const int L = guarded_len(L_in, a.len_cap, bad);
+  const int nSel = min(max(nSel0, 0), (int)a.sel_stride);
+  bad |= nSel != nSel0 ? kGuardNSel : 0;
   const int nS = min(a.n_sink, L);
   // A context that still lies inside the sink range has nothing selected, and the rows appended since
   // the reorganisation are sink rows the compact buffers do not hold: all of it is read in place.
   const bool all_sink = L <= a.n_sink;
-  const int rs = all_sink ? 0 : min(max(a.recent_start[b], nS), L);
+  const int rs = all_sink ? 0 : min(max(rs_in, nS), L);
   const int Nc = all_sink ? 0 : a.n_sink + nSel;  // compact rows in use
   const int Tc = (Nc + kTile - 1) / kTile;
   const int Nr = L - rs;
@@ -956,10 +1003,10 @@ __global__ __launch_bounds__(kAttnThreads, PAGED ? 2 : 3) void attn_compact_kern
     if (t < Tc) {
       issue_k_affine(T, Rc, t * kTile, a.c_rows - 1);
     } else if (PAGED) {
-      const Pages P = pages_of(a, b);
+      const Pages P = pages_of(a, b, L);
       const int ra = min(rs + (t - Tc) * kTile + n, L - 1), rb = min(rs + (t - Tc) * kTile + 16 + n, L - 1);
-      pra_n = P.phys(ra, P.page_of(ra));
-      prb_n = P.phys(rb, P.page_of(rb));
+      pra_n = P.phys(ra, P.page_of(ra), bad);
+      prb_n = P.phys(rb, P.page_of(rb), bad);
       issue_k_rows<uint64_t>(T, R, pra_n, prb_n);
     } else {
       issue_k_affine(T, R, rs + (t - Tc) * kTile, L - 1);
@@ -993,6 +1040,7 @@ __global__ __launch_bounds__(kAttnThreads, PAGED ? 2 : 3) void attn_compact_kern
   l_run += __shfl_xor(l_run, 32);
   write_wg_record(a.part, head0, G, slot, acc, m_run, l_run, a.out_direct, a.out_merge,
                   a.arrive != nullptr ? a.arrive + bh : nullptr, a.n_split);
+  report_guard(a.guard, bad);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1017,9 +1065,13 @@ __global__ __launch_bounds__(kAttnThreads) void reorg_kernel(const ReorgArgs a) 
     const int i = chunk * kReorgRows + p * 16 + r;
     src[p] = sel_cap >= 0 ? sel[min(max(i - a.n_sink, 0), sel_cap)] : 0;
   }
-  const int L = a.ctx_len[b];
-  const int nSel = min(a.n_sel[bh], (int)a.sel_stride);
+  int bad = 0;
+  const int L_in = a.ctx_len[b], nSel0 = a.n_sel[bh];
+  const int L = guarded_len(L_in, a.len_cap, bad);
+  const int nSel = min(max(nSel0, 0), (int)a.sel_stride);
+  bad |= nSel != nSel0 ? kGuardNSel : 0;
   const int nS = min(a.n_sink, L);
+  const int r_hi = max(L, 1) - 1;
   const char* Kb = reinterpret_cast<const char*>(a.K + b * a.k_sb + h * a.k_sh);
   const char* Vb = reinterpret_cast<const char*>(a.V + b * a.v_sb + h * a.v_sh);
   char* Kc = reinterpret_cast<char*>(a.Kc + b * a.c_sb + h * a.c_sh);
@@ -1031,9 +1083,17 @@ __global__ __launch_bounds__(kAttnThreads) void reorg_kernel(const ReorgArgs a) 
     const int i = chunk * kReorgRows + p * 16 + r;
     ok[p] = i < nS || (i >= a.n_sink && i < a.n_sink + nSel);
     int row = i < a.n_sink ? i : src[p];
+    if (ok[p]) {  // a stored index outside the context reads as the context's last row (as in the gather kernels)
+      const int rc = (int)min((uint32_t)row, (uint32_t)r_hi);
+      bad |= rc != row ? kGuardSelIdx : 0;
+      row = rc;
+    }
     if (PAGED && ok[p]) {
       const int32_t* tbl = a.table + (int64_t)b * a.table_stride;
-      row = tbl[row >> a.page_lg] * a.page_rpb + (row & ((1 << a.page_lg) - 1));
+      const int page = tbl[row >> a.page_lg];
+      const int pc = min(max(page, 0), a.n_blocks - 1);
+      bad |= pc != page ? kGuardBlock : 0;
+      row = pc * a.page_rpb + (row & ((1 << a.page_lg) - 1));
     }
     if (ok[p]) {
       typedef typename RowOff<PAGED>::type OffT;
@@ -1049,6 +1109,7 @@ __global__ __launch_bounds__(kAttnThreads) void reorg_kernel(const ReorgArgs a) 
       *reinterpret_cast<uint4*>(Vc + (int64_t)i * (kHeadDim * 2) + sub * 16) = vr[p];
     }
   }
+  report_guard(a.guard, bad);
 }
 
 // Stand-alone merge: one workgroup per (sequence, query head).
@@ -1063,7 +1124,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(const MergeArgs a)
   const bool dense = a.mode == 0 || (a.mode == 2 && a.is_slow[b]);
   if (dense) {
     // dense records: slots_slow waves' J records, then one record per wave that owned sink / recent tiles
-    const int L = a.ctx_len[b];
+    const int L = min(max(a.ctx_len[b], 0), a.len_cap);  // the dense launch's clamp
     const int nS = min(a.n_sink, L);
     const int rs = min(max(a.n_sink, L - a.recent), L);
     const int nTS = (nS + (L - rs) + kTile - 1) / kTile;

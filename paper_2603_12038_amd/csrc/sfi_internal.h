@@ -46,9 +46,15 @@ struct Workspace {
   double* segstat;    // [B*Hkv][n_seg_cap][kSegStats]  full Selector: per-segment sums for lambda*
   float* mu;          // [B*Hkv][ld]  windowed evidence: accumulator over the window's queries
   uint32_t* arrive;   // [B*Hkv]  workgroups of a split fast-step launch that have written their record
+  int32_t* guard;     // [1]  SFI_GUARD_* bits of device-side inputs the kernels found out of range and clamped
   int64_t ld_pos;     // multiple of kSelSeg
   int32_t n_seg_cap;
 };
+
+// Device-side inputs (lengths, counts, row indices, block ids) are clamped into the range the launch may
+// touch before they address memory; a kernel that had to clamp ORs the matching bit into Workspace::guard
+// once, on its way out.  The bit values are the public SFI_GUARD_* ones.
+constexpr int kGuardCtxLen = 1, kGuardNSel = 2, kGuardSelIdx = 4, kGuardBlock = 8;
 
 struct AttnArgs {
   const uint16_t* q;
@@ -86,6 +92,9 @@ struct AttnArgs {
   const uint16_t* Vc;
   int64_t c_sb, c_sh;            // compact mode: strides between sequences / KV heads, in elements
   int32_t c_rows;                // compact mode: rows every (b, h) slice of Kc / Vc holds (all readable)
+  int32_t len_cap;               // ctx_len[b] is clamped to [0, len_cap]: the launch's max_len, else cfg.max_ctx
+  int32_t n_blocks;              // paged cache: block ids are clamped to [0, n_blocks)
+  int32_t* guard;                // Workspace::guard
 };
 
 // Reorg: gather the sink and the selected rows of every (b, h) into the compact buffers.
@@ -105,6 +114,8 @@ struct ReorgArgs {
   const int32_t* table;          // paged cache (see AttnArgs)
   int64_t table_stride;
   int32_t page_lg, page_rpb;
+  int32_t len_cap, n_blocks;     // clamps of ctx_len and of the block ids (see AttnArgs)
+  int32_t* guard;
 };
 constexpr int kReorgRows = 64;   // compact rows per workgroup of the Reorg kernel
 
@@ -119,6 +130,7 @@ struct MergeArgs {
   const int32_t* ctx_len;              // dense records: the number of sink / recent records follows from it
   int32_t n_sink, recent;
   float alpha;                         // power-mean exponent of the evidence (Eq. selector_mu)
+  int32_t len_cap;                     // the clamp the dense launch applied to ctx_len
 };
 
 struct SelArgs {
@@ -154,6 +166,7 @@ struct SelArgs {
   // workgroup per query head) and takes the J-only softmax statistics from the record headers itself
   const float* part;       // nullptr: a merge launch has run, jstat is valid
   float* merge_out;
+  int32_t len_cap;         // the clamp the dense launch applied to ctx_len
 };
 
 hipError_t launch_attn_dense(const AttnArgs& a, int B, int n_slots, hipStream_t s);

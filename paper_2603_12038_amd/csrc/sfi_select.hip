@@ -106,7 +106,7 @@ struct Problem {
 
 __device__ __forceinline__ Problem problem_of(const SelArgs& a, int b) {
   Problem p;
-  p.nJ = max(0, a.ctx_len[b] - a.recent - a.n_sink);
+  p.nJ = max(0, min(a.ctx_len[b], a.len_cap) - a.recent - a.n_sink);  // the dense launch's clamp of ctx_len
   p.ksel = (uint32_t)min(a.budget, p.nJ);
   return p;
 }
@@ -116,7 +116,7 @@ __device__ __forceinline__ Problem problem_of(const SelArgs& a, int b) {
 // query head into the attention output (J records of all waves, then one record per wave that owned
 // sink / recent tiles).
 __device__ __forceinline__ void merge_head(const SelArgs& a, int b, int h, int g) {
-  const int L = a.ctx_len[b];
+  const int L = min(max(a.ctx_len[b], 0), a.len_cap);
   const int nS = min(a.n_sink, L);
   const int rs = min(max(a.n_sink, L - a.recent), L);
   const int nTS = (nS + (L - rs) + 31) / 32;
