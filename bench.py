@@ -176,6 +176,7 @@ def bench_serving(args):
         "whole_run_kv_GBps": kv / wall / 1e9, "whole_run_frac_of_8TBps": kv / wall / 1e9 / HBM_PEAK_GBS,
         "all_fast_step_stage_us": {"gather": gather_us, "merge": ms[1] / max(cnt[1], 1) * 1e3},
         "us_per_decode_step_per_layer": wall * 1e6 / (n_t * NL),
+        "device_status": sfi.sfi_device_status(ctx.handle),  # 0: no device-side input had to be clamped
         "cpu_baseline": None,
     }
     _emit(res)
@@ -243,7 +244,7 @@ def bench_retention(args):
         "roofline": {"bound": "hbm", "kernel": "sfi::attn_dense_kernel<0> + merge", "achieved": dense_bytes / (dense_us * 1e-6) / 1e9,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dense_bytes / (dense_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
                      "traffic": None},
-        "table": rows, "cpu_baseline": None,
+        "table": rows, "device_status": sfi.sfi_device_status(ctx.handle), "cpu_baseline": None,
     }
     _emit(res)
     ctx.close()

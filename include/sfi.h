@@ -40,9 +40,12 @@
  * on the same context must not overlap on the GPU (they share the workspace).
  *
  * Errors: every function returning int gives SFI_OK (0) or a negative sfi_status.  Host-checkable
- * argument errors are reported before anything is launched.  Device-side precondition
- * violations (an index outside [0, ctx_len), ctx_len > max_ctx) are the caller's
- * responsibility; they are not detected.
+ * argument errors are reported before anything is launched.  Values the host cannot see -- the
+ * contents of ctx_len, n_sel, sel_idx, the block table -- are brought into range by the kernels
+ * before they address memory, and what had to be changed is reported by sfi_device_status.
+ *
+ * ctx_len[b] = 0 is a legal input (an unused slot of a batch): out[b] = 0, n_sel[b] = 0, nothing of
+ * K / V of that sequence is used, the other sequences are computed as if the slot were not there.
  */
 #ifndef SFI_H_
 #define SFI_H_
@@ -151,7 +154,7 @@ const char* sfi_strerror(int status);
  * sel_idx is addressed with row stride `budget`.  max_len: host-side upper bound of ctx_len[]
  * (0 = cfg.max_ctx); it sizes the launch, and rows [0, max_len) of every (b, h) of K and V must be
  * readable memory (their contents beyond ctx_len[b] are never used): the kernel issues a tile's
- * row loads before ctx_len[b] has arrived.  1 <= ctx_len[b] <= max_len.
+ * row loads before ctx_len[b] has arrived.  0 <= ctx_len[b] <= max_len.
  */
 int sfi_slow_step(sfi_ctx* ctx, const void* q, const void* K, const void* V, const int32_t* ctx_len,
                   int32_t max_len, int32_t budget, float* out, int32_t* sel_idx, int32_t* n_sel,
