@@ -278,6 +278,9 @@ def main():
                     help="block layout of a paged cache: [blocks][page][Hkv][d] or [blocks][Hkv][page][d]")
     ap.add_argument("--selector-mode", type=int, choices=[0, 1], default=0,
                     help="0: evidence-only ranking (the measured baseline); 1: Algorithm 2 in full, oracle defaults")
+    ap.add_argument("--kv-layout", choices=["separate", "interleaved"], default="separate",
+                    help="flat cache only: K and V as two tensors, or as one [B, Hkv, L, 2, d] tensor whose row t "
+                         "holds k_t then v_t (the library sees two base pointers and a row stride of 2 d either way)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--dense-wgs", type=int, default=0)
     ap.add_argument("--fast-tpw", type=int, default=0)
@@ -330,6 +333,15 @@ def main():
         Ks.append(k)
         Vs.append(v)
     max_ctx = int(w.L_alloc)
+    if args.kv_layout == "interleaved":
+        assert not args.page_size, "--kv-layout interleaved is for the flat cache"
+        for l in range(NL):
+            kv = torch.empty(B, Hkv, Ks[l].shape[2], 2, d, dtype=Ks[l].dtype, device=dev)
+            kv[:, :, :, 0] = Ks[l]
+            kv[:, :, :, 1] = Vs[l]
+            Ks[l], Vs[l] = kv[:, :, :, 0], kv[:, :, :, 1]
+        K0, V0 = Ks[0], Vs[0]
+        torch.cuda.synchronize()
     n_blocks = 0
     if args.page_size:
         # scatter every layer's flat cache into a block pool [n_blocks, page, Hkv, d] through one block table
@@ -590,7 +602,7 @@ def main():
         "config": {"workload": f"{wl['label']}: B{B} Hq{Hq} Hkv{Hkv} d{d} ctx{L0} k{w.budget} R{w.recent} "
                                f"sink{w.n_sink} slow every {SEG}",
                    "step": f"{SEG} decode steps (1 slow + {SEG - 1} fast) x {NL} virtual layers",
-                   "virtual_layers": NL, "launch": args.launch, "fast_path": args.fast_path, "selector_mode": args.selector_mode, "page_size": args.page_size, "page_layout": args.page_layout if args.page_size else None,
+                   "virtual_layers": NL, "launch": args.launch, "kv_layout": args.kv_layout, "fast_path": args.fast_path, "selector_mode": args.selector_mode, "page_size": args.page_size, "page_layout": args.page_layout if args.page_size else None,
                    "slow_schedule": args.slow_schedule + (f" (ring {len(ring)})" if use_async else ""),
                    "dense_splits": dsp, "fast_splits": fsp,
                    "fast_merge": args.fast_merge or "kernel"},

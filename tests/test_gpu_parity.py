@@ -282,6 +282,37 @@ def test_results_are_deterministic(tiny):
         assert (x.view(np.uint32) == y.view(np.uint32)).all() if x.dtype == np.float32 else (x == y).all()
 
 
+def test_interleaved_kv_layout(oracle):
+    """K and V in one tensor [B, Hkv, L, 2, d] (row t: k_t then v_t), handed over as two base pointers 256 bytes
+    apart with a row stride of 2 d: slow step, both fast-step launch shapes, reorg + compact fast step."""
+    import torch
+
+    w = syn.make_tiny(L0=3000, steps=2, budget=96, recent=48, n_support=8, B=2)
+    w.L0 = np.array([3000, 1777], np.int32)
+    r = Runner(w)
+    try:
+        _step("interleaved K/V layout")
+        kv = torch.empty(w.B, w.Hkv, w.L_alloc, 2, w.d, dtype=torch.bfloat16, device="cuda")
+        kv[:, :, :, 0], kv[:, :, :, 1] = r.K, r.V
+        r.ctx.close()
+        r.K, r.V = kv[:, :, :, 0], kv[:, :, :, 1]
+        r.ctx = r.sfi.SfiContext(w.B, w.Hq, w.Hkv, r.max_ctx, w.budget, w.n_sink, w.recent, r.K, r.V)
+        q0, ctx0 = w.q(0), w.ctx_len(0)
+        out, sel, nsel = r.slow(q0, ctx0, w.budget)
+        check_out(out, oracle.dense(q0, w.K, w.V, ctx0))
+        sel_ref, nsel_ref, z = oracle.selector(q0, w.K, ctx0, w.budget, w.n_sink, w.recent)
+        check_selection(sel, nsel, sel_ref, nsel_ref, z, ctx0, w.n_sink, w.recent, w.budget)
+        q1, ctx1, rs1 = w.q(1), w.ctx_len(1), w.recent_start(1)
+        ref = oracle.sparse(q1, w.K, w.V, sel, nsel, rs1, ctx1, w.n_sink)
+        for tpw in (1, 3):
+            r.sfi.sfi_set_tuning(r.ctx.handle, 0, tpw)
+            check_out(r.fast(q1, sel, nsel, rs1, ctx1), ref)
+        r.reorg(sel, nsel, ctx0)
+        check_out(r.fast_compact(q1, nsel, sel.shape[2], rs1, ctx1), ref)
+    finally:
+        r.close()
+
+
 def test_strided_kv_layout(oracle):
     """Token-major K/V storage ([B, L, Hkv, d]) through the stride fields."""
     import torch
