@@ -901,7 +901,10 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(con
     issue_v_rows<typename RowOff<PAGED>::type>(T, R, ra, rb);
     __builtin_amdgcn_sched_barrier(0);
   }
-  for (int k = 0; k < K; ++k) {
+  // The last tile is taken after the loop, without the refill: no rows are requested for a tile that does not
+  // exist, and nothing is in flight when the wave reaches the record write (worth 0.05 us at most: the tail
+  // waits for its own stores far longer than for such rows).
+  for (int k = 0; k + 1 < K; ++k) {
     const int p0 = p_first + k * pstep;
     const int pn = p0 + pstep;
     float y[8];
@@ -929,6 +932,15 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(con
     softmax_phase(y, acc, m_run, l_run, jg, a_hi, a_lo);
     pv_phase(T, a_hi, a_lo, acc);
     issue_v_rows<typename RowOff<PAGED>::type>(T, R, ra, rb);
+  }
+  if (K > 0) {
+    const int p0 = p_first + (K - 1) * pstep;
+    float y[8];
+    qk_phase(T, qreg, a.scale_log2, y);
+    if (p0 + kTile > W.N) mask_tail(T, y, jg, p0, W.N);
+    bf16x8 a_hi, a_lo;
+    softmax_phase(y, acc, m_run, l_run, jg, a_hi, a_lo);
+    pv_phase(T, a_hi, a_lo, acc);
   }
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
