@@ -125,6 +125,8 @@ def test_hot_calls_reject_bad_arguments_before_any_launch():
         assert lib.sfi_evidence_add(h, p, None, None, p, 0, None, 1, None) == EINVAL
         assert lib.sfi_evidence_add(h, p, p + 2, None, p, 0, None, 1, None) == EALIGN
         assert lib.sfi_evidence_add(h, p, p, p, p, cfg.max_ctx + 1, p, 1, None) == EINVAL
+        assert lib.sfi_device_status(h, None, 1, None) == EINVAL
+        assert lib.sfi_device_status(None, C.byref(C.c_int32()), 1, None) == EINVAL
         assert lib.sfi_evidence_select(h, 0, p, 0, 64, p, p, None) == EINVAL
         assert lib.sfi_evidence_select(h, 4, p, 0, 64, None, p, None) == EINVAL
         assert lib.sfi_evidence_select(h, 4, p, 0, cfg.max_budget + 1, p, p, None) == EINVAL
