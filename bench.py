@@ -518,6 +518,25 @@ def main():
         wall = time.perf_counter() - t1
     gpu_ms = ev0.elapsed_time(ev1)
     assert int(ctx_d[0]) == L0 + n_dec, "state did not advance as scheduled"
+    # spread of the timed region: the same graph replayed a few more times from the same state (untimed for
+    # `value`; GPU events around each replay)
+    spread = None
+    if args.launch == "graph":
+        reps_ms = []
+        for _ in range(7):
+            ctx_d.copy_(state[0])
+            rs_d.copy_(state[1])
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            graph.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            reps_ms.append(e0.elapsed_time(e1))
+        assert int(ctx_d[0]) == L0 + n_dec
+        reps_ms = np.sort(np.array(reps_ms))
+        spread = {"n": len(reps_ms), "median_ms": float(np.median(reps_ms)), "min_ms": float(reps_ms[0]),
+                  "max_ms": float(reps_ms[-1]), "p10_ms": float(np.percentile(reps_ms, 10)),
+                  "p90_ms": float(np.percentile(reps_ms, 90))}
     total_s = wall
     tokens = B * SEG * K_seg * NL
     value = tokens / total_s
@@ -619,6 +638,7 @@ def main():
         },
         "us_per_decode_step_per_layer": total_s * 1e6 / (K_seg * SEG * NL),
         "gpu_event_ms": gpu_ms,
+        "timed_region_repeats": spread,
         "parity_sample": parity,
         "device_status": device_status,
         "cpu_baseline": cpu_baseline,
