@@ -208,7 +208,8 @@ int sfi_dense_attn(sfi_ctx* ctx, const void* q, const void* K, const void* V, co
  * Preconditions: the three parts are disjoint; sel entries lie in [n_sink, recent_start[b]);
  * n_sink <= recent_start[b] <= ctx_len[b]; while ctx_len[b] < n_sink any recent_start[b] >= ctx_len[b] is
  * read as ctx_len[b] (an empty window: sfi_advance leaves n_sink there);
- * n_sel[b,h] <= sel_stride <= cfg.max_budget.  sel_idx / n_sel are read-only here.
+ * n_sel[b,h] <= sel_stride <= cfg.max_budget.  sel_idx / n_sel are read-only here.  With sel_stride = 0
+ * (sink and recent window only) sel_idx is not read and may be NULL.
  */
 int sfi_fast_step(sfi_ctx* ctx, const void* q, const void* K, const void* V, const int32_t* sel_idx,
                   const int32_t* n_sel, int32_t sel_stride, const int32_t* recent_start,

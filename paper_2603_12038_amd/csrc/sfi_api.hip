@@ -566,15 +566,16 @@ int sfi_fast_step(sfi_ctx* x, const void* q, const void* K, const void* V, const
                   const int32_t* ctx_len, float* out, void* stream) {
   int rc = check_common(x, q, K, V, ctx_len, out);
   if (rc != SFI_OK) return rc;
-  if (sel_idx == nullptr || n_sel == nullptr || recent_start == nullptr) return SFI_EINVAL;
   if (sel_stride < 0 || sel_stride > x->cfg.max_budget) return SFI_EINVAL;
+  if ((sel_idx == nullptr && sel_stride > 0) || n_sel == nullptr || recent_start == nullptr) return SFI_EINVAL;
   if (misaligned(sel_idx, 4) || misaligned(n_sel, 4) || misaligned(recent_start, 4)) return SFI_EALIGN;
   hipStream_t st = (hipStream_t)stream;
   CallRecord call_record(x);
   AttnArgs a;
   fill_attn(x, &a, q, K, V, ctx_len);
   a.recent_start = recent_start;
-  a.sel_idx = sel_idx;
+  // an index list of width 0: the pipelined kernel still reads one word where the list would start
+  a.sel_idx = sel_stride > 0 ? sel_idx : x->ws.guard;
   a.n_sel = n_sel;
   a.sel_stride = sel_stride;
   a.n_split = fast_splits_for(x, sel_stride, &a.pipelined);
@@ -686,7 +687,7 @@ int sfi_mixed_step(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   fill_attn(x, &f, q, K, V, ctx_len);
   f.is_slow = is_slow;
   f.recent_start = recent_start;
-  f.sel_idx = sel_idx;
+  f.sel_idx = budget > 0 ? sel_idx : x->ws.guard;  // as in sfi_fast_step
   f.n_sel = n_sel;
   f.sel_stride = budget;
   f.len_cap = ml;

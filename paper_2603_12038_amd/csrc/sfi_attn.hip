@@ -834,7 +834,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(con
 
   ListWalk W;
   W.sel = a.sel_idx + (int64_t)bh * a.sel_stride;
-  W.sel_cap = (int)a.sel_stride - 1;
+  W.sel_cap = max((int)a.sel_stride - 1, 0);  // sel_stride = 0: the host points sel_idx at one readable word
   W.n_sink = a.n_sink;
   const int p_first = first * kTile;
   const int sA = W.sel_at_nonempty(p_first + n), sB = W.sel_at_nonempty(p_first + 16 + n);

@@ -282,6 +282,31 @@ def test_results_are_deterministic(tiny):
         assert (x.view(np.uint32) == y.view(np.uint32)).all() if x.dtype == np.float32 else (x == y).all()
 
 
+@pytest.mark.parametrize("recent", [20, 700])
+def test_fast_step_without_selected_rows(oracle, recent):
+    """Index lists of width 0 (sink + recent window only, sel_idx = NULL): the one-tile kernel and, with a long
+    window, the pipelined one, which reads its indices ahead of the list length."""
+    import torch
+    w = syn.make_tiny(L0=2500, steps=2, budget=8, recent=recent, n_support=4, B=2)
+    w.L0 = np.array([2500, 1300], np.int32)
+    r = Runner(w)
+    try:
+        _step(f"fast step with sel_stride 0, recent {recent}")
+        q, ctx, rs = w.q(1), w.ctx_len(1), w.recent_start(1)
+        nsel = np.zeros((w.B, w.Hkv), np.int32)
+        sel = np.zeros((w.B, w.Hkv, 0), np.int32)
+        ref = oracle.sparse(q, w.K, w.V, sel, nsel, rs, ctx, w.n_sink)
+        for tpw in (0, 1, 3):
+            r.sfi.sfi_set_tuning(r.ctx.handle, 0, tpw if tpw else -1)
+            r.out.fill_(float("nan"))
+            r.sfi.sfi_fast_step(r.ctx.handle, to_dev(q), r.K, r.V, None, i32_dev(nsel), 0, i32_dev(rs), i32_dev(ctx), r.out)
+            torch.cuda.synchronize()
+            check_out(r.out.cpu().numpy(), ref)
+        assert r.sfi.sfi_device_status(r.ctx.handle) == 0
+    finally:
+        r.close()
+
+
 def test_interleaved_kv_layout(oracle):
     """K and V in one tensor [B, Hkv, L, 2, d] (row t: k_t then v_t), handed over as two base pointers 256 bytes
     apart with a row stride of 2 d: slow step, both fast-step launch shapes, reorg + compact fast step."""
