@@ -189,7 +189,6 @@ int fast_splits_for(const sfi_ctx* x, int sel_stride, int* pipelined) {
   if (s > one) s = one;
   if (s < 1) s = 1;
   *pipelined = s * kWaves < tiles;
-  if (sel_stride < 1) *pipelined = 0;  // the pipelined kernel reads sel_idx unconditionally
   return s;
 }
 
