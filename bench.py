@@ -589,7 +589,7 @@ def main():
     fast_kernel = "compact" if compact else "gather"
     dominant = fast_kernel if seg_fast_ms > seg_dense_ms else "dense"
     traffic = None  # HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one
-    pmc_path = os.path.join(ROOT, "profiles", "hbm_traffic_llama8b.json")
+    pmc_path = os.path.join(ROOT, "profiles", "hbm_traffic_llama8b.txt")
     if os.path.exists(pmc_path) and args.workload == "llama8b" and args.ctx == 32768 and args.batch == 4:
         prof = json.load(open(pmc_path))
         for key in (f"attn_{dominant}_stream_kernel", f"attn_{dominant}_kernel"):
