@@ -281,6 +281,8 @@ def main():
     ap.add_argument("--kv-layout", choices=["separate", "interleaved"], default="separate",
                     help="flat cache only: K and V as two tensors, or as one [B, Hkv, L, 2, d] tensor whose row t "
                          "holds k_t then v_t (the library sees two base pointers and a row stride of 2 d either way)")
+    ap.add_argument("--out-bf16", action="store_true",
+                    help="outputs stored as bf16 (cfg.out_bf16) instead of fp32; slow+fast mix workloads only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--dense-wgs", type=int, default=0)
     ap.add_argument("--fast-tpw", type=int, default=0)
@@ -307,8 +309,11 @@ def main():
 
     import paper_2603_12038_amd as sfi
     import sfi_synth as syn
-    from helpers import check_out, check_selection, i32_dev, to_dev
+    from helpers import check_out, check_out_bf16, check_selection, i32_dev, to_dev
 
+    if args.out_bf16:  # the parity sample then uses the bf16 rule (an ulp of the element + the fp32 path's error)
+        check_out = check_out_bf16
+    err_key = "out_frac_of_bf16_bound" if args.out_bf16 else "out_row_rel_err"
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     sfi.load_library()  # fails loudly if libsfi.so is not built
     dev = torch.device("cuda:0")
@@ -374,7 +379,7 @@ def main():
         sel_params = dict(gamma=0.5, beta=1.0, p=2.0, eta=0.5, lambda_clip=0.02, alpha_soft=0.5, alpha_cross=0.35,
                           temp=1.0, eps=1e-8, nms_radius=2)
     mk = lambda: sfi.SfiContext(B, Hq, Hkv, max_ctx, w.budget, w.n_sink, w.recent, K0, V0, selector=sel_params,
-                                page_size=args.page_size, page_layout=args.page_layout)
+                                page_size=args.page_size, page_layout=args.page_layout, out_bf16=args.out_bf16)
     ctx = mk()
     h = ctx.handle
     use_async = args.slow_schedule == "async"
@@ -389,7 +394,7 @@ def main():
     gen = torch.Generator(device=dev)
     gen.manual_seed(1234)
     q_all = torch.randn(n_dec + SEG, NL, B, Hq, d, device=dev, generator=gen).to(torch.bfloat16)
-    outs = [torch.zeros(B, Hq, d, dtype=torch.float32, device=dev) for _ in range(NL)]
+    outs = [torch.zeros(B, Hq, d, dtype=torch.bfloat16 if args.out_bf16 else torch.float32, device=dev) for _ in range(NL)]
     sels = [torch.full((B, Hkv, w.budget), -1, dtype=torch.int32, device=dev) for _ in range(NL)]
     nsels = [torch.zeros(B, Hkv, dtype=torch.int32, device=dev) for _ in range(NL)]
     ctx_d, rs_d = i32_dev(w.ctx_len(0)), i32_dev(w.recent_start(0))
@@ -455,13 +460,13 @@ def main():
         c0 = w.ctx_len(0)
         slow(0, 0)
         torch.cuda.synchronize()
-        g_out, g_sel, g_nsel = outs[0].cpu().numpy(), sels[0].cpu().numpy(), nsels[0].cpu().numpy()
+        g_out, g_sel, g_nsel = outs[0].float().cpu().numpy(), sels[0].cpu().numpy(), nsels[0].cpu().numpy()
         t1 = time.time()
         o_dense = oracle.dense(qs[0], w.K, w.V, c0)
         o_sp = oracle.SelectorParams(mode=1, **sel_params) if sel_params else None
         o_sel, o_nsel, o_z = oracle.selector(qs[0], w.K, c0, w.budget, w.n_sink, w.recent, sp=o_sp)
         t_slow = time.time() - t1
-        parity["slow_out_row_rel_err"] = check_out(g_out, o_dense)
+        parity[f"slow_{err_key}"] = check_out(g_out, o_dense)
         n_exact = check_selection(g_sel, g_nsel, o_sel, o_nsel, o_z, c0, w.n_sink, w.recent, w.budget)
         parity["selection_sets_exact"] = f"{n_exact}/{B * Hkv}"
         t_fast = 0.0
@@ -472,7 +477,7 @@ def main():
             t1 = time.time()
             o_sp = oracle.sparse(qs[t], w.K, w.V, g_sel, g_nsel, rt, ct, w.n_sink)
             t_fast += time.time() - t1
-            parity[f"fast{t}_out_row_rel_err"] = check_out(outs[0].cpu().numpy(), o_sp)
+            parity[f"fast{t}_{err_key}"] = check_out(outs[0].float().cpu().numpy(), o_sp)
         t_fast /= 2
         cpu_baseline = {
             "value": B * SEG / (t_slow + (SEG - 1) * t_fast), "unit": "tokens/s per attention layer",
@@ -621,7 +626,7 @@ def main():
         "config": {"workload": f"{wl['label']}: B{B} Hq{Hq} Hkv{Hkv} d{d} ctx{L0} k{w.budget} R{w.recent} "
                                f"sink{w.n_sink} slow every {SEG}",
                    "step": f"{SEG} decode steps (1 slow + {SEG - 1} fast) x {NL} virtual layers",
-                   "virtual_layers": NL, "launch": args.launch, "kv_layout": args.kv_layout, "fast_path": args.fast_path, "selector_mode": args.selector_mode, "page_size": args.page_size, "page_layout": args.page_layout if args.page_size else None,
+                   "virtual_layers": NL, "launch": args.launch, "out_dtype": "bf16" if args.out_bf16 else "fp32", "kv_layout": args.kv_layout, "fast_path": args.fast_path, "selector_mode": args.selector_mode, "page_size": args.page_size, "page_layout": args.page_layout if args.page_size else None,
                    "slow_schedule": args.slow_schedule + (f" (ring {len(ring)})" if use_async else ""),
                    "dense_splits": dsp, "fast_splits": fsp,
                    "fast_merge": args.fast_merge or "kernel"},

@@ -109,6 +109,10 @@ typedef struct sfi_config {
    * k_stride_page = Hkv * page_size * 128.  Must be a multiple of the row stride, with the same ratio for
    * K and V. */
   int64_t k_stride_page, v_stride_page;
+  /* Output type of every `out` argument: 0 = fp32 [B, Hq, 128] (what the error bound of this library is
+   * stated for); 1 = bf16 [B, Hq, 128], the fp32 result rounded to nearest even as it is stored (what a model
+   * that keeps its activations in bf16 hands to the next projection; saves it a conversion pass). */
+  int32_t out_bf16;
 } sfi_config;
 
 typedef struct sfi_ctx sfi_ctx; /* opaque; host memory owned by the library */

@@ -34,6 +34,7 @@ class SfiConfig(C.Structure):
         ("lambda_clip", C.c_float), ("alpha_soft", C.c_float), ("alpha_cross", C.c_float), ("temp", C.c_float),
         ("eps", C.c_float), ("nms_radius", C.c_int32), ("alpha", C.c_float),
         ("page_size", C.c_int32), ("k_stride_page", C.c_int64), ("v_stride_page", C.c_int64),
+        ("out_bf16", C.c_int32),
     ]
 
 
@@ -262,7 +263,8 @@ class SfiContext:
     """Owns the workspace tensor and the context handle for one (shape, K/V layout)."""
 
     def __init__(self, B, Hq, Hkv, max_ctx, max_budget, n_sink, recent, K, V, scale: float = 0.0, device="cuda",
-                 selector: Optional[dict] = None, alpha: float = 0.0, page_size: int = 0, page_layout: str = "thd"):
+                 selector: Optional[dict] = None, alpha: float = 0.0, page_size: int = 0, page_layout: str = "thd",
+                 out_bf16: bool = False):
         """selector: None for mode 0, or the mode-1 hyper-parameters as a dict with the keys gamma, beta, p,
         eta, lambda_clip, alpha_soft, alpha_cross, temp, eps, nms_radius (all required: the paper fixes none
         of the prior's)."""
@@ -275,6 +277,7 @@ class SfiContext:
         cfg.max_ctx, cfg.max_budget, cfg.n_sink, cfg.recent = max_ctx, max_budget, n_sink, recent
         cfg.scale, cfg.selector_mode = scale, 0 if selector is None else 1
         cfg.alpha = alpha
+        cfg.out_bf16 = 1 if out_bf16 else 0
         if selector is not None:
             for k in ("gamma", "beta", "p", "eta", "lambda_clip", "alpha_soft", "alpha_cross", "temp", "eps"):
                 setattr(cfg, k, float(selector[k]))

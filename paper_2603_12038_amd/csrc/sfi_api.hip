@@ -42,6 +42,7 @@ int validate(const sfi_config* c) {
   if (c->head_dim != kHeadDim) return SFI_EUNSUPPORTED;
   if (c->n_q_heads / c->n_kv_heads > 16) return SFI_EUNSUPPORTED;
   if (c->selector_mode != 0 && c->selector_mode != 1) return SFI_EUNSUPPORTED;
+  if (c->out_bf16 != 0 && c->out_bf16 != 1) return SFI_EINVAL;
   if (!(c->alpha >= 0.f) || c->alpha > 1.f) return SFI_EINVAL;
   if (c->page_size != 0) {
     if (c->page_size < 16 || c->page_size > 65536 || (c->page_size & (c->page_size - 1)) != 0) return SFI_EINVAL;
@@ -246,6 +247,7 @@ void fill_attn(const sfi_ctx* x, AttnArgs* a, const void* q, const void* K, cons
   a->table = x->table; a->table_stride = x->table_stride; a->page_lg = x->page_lg; a->page_rpb = x->page_rpb;
   a->n_blocks = x->n_blocks;
   a->len_cap = c.max_ctx;  // calls with a max_len lower it (set_dense_bounds)
+  a->out_bf16 = c.out_bf16;
   a->guard = x->ws.guard;
 }
 
@@ -270,6 +272,7 @@ void fill_sel(const sfi_ctx* x, SelArgs* s, const int32_t* ctx_len, int max_len,
   s->mu = x->ws.mu; s->mu_scale = 1.0f;
   s->lg_rows = x->G + (c.selector_mode == 1 ? 1 : 0);
   s->len_cap = max_len;
+  s->out_bf16 = c.out_bf16;
 }
 
 #define SFI_TRY(expr)                         \
@@ -442,7 +445,7 @@ int sfi_dense_attn(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   set_dense_bounds(x, &a, ml);
   x->last_dense_splits = a.n_split;
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
-  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, a.n_split * kWaves, 0, 0, nullptr, 0, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha, ml};
+  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, a.n_split * kWaves, 0, 0, nullptr, 0, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha, ml, x->cfg.out_bf16};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
 }
@@ -465,7 +468,7 @@ int slow_attn_impl(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   x->last_dense_splits = a.n_split;
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
   if (merge_later) return SFI_OK;  // the Selector's scoring launch merges
-  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, a.n_split * kWaves, 0, 0, x->ws.jstat, a.n_split * kWaves, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha, ml};
+  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, a.n_split * kWaves, 0, 0, x->ws.jstat, a.n_split * kWaves, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha, ml, x->cfg.out_bf16};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
 }
@@ -583,7 +586,7 @@ int sfi_fast_step(sfi_ctx* x, const void* q, const void* K, const void* V, const
   else if (x->tail_merge) { a.out_merge = out; a.arrive = x->ws.arrive; }
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_gather(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
   if (a.n_split == 1 || a.out_merge != nullptr) return SFI_OK;
-  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1, nullptr, 0, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha, x->cfg.max_ctx};
+  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1, nullptr, 0, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha, x->cfg.max_ctx, x->cfg.out_bf16};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
 }
@@ -654,7 +657,7 @@ int sfi_fast_step_compact(sfi_ctx* x, const void* q, const void* Kc, const void*
   else if (x->tail_merge) { a.out_merge = out; a.arrive = x->ws.arrive; }
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_compact(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
   if (a.n_split == 1 || a.out_merge != nullptr) return SFI_OK;
-  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1, nullptr, 0, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha, x->cfg.max_ctx};
+  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1, nullptr, 0, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha, x->cfg.max_ctx, x->cfg.out_bf16};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
 }
@@ -704,7 +707,7 @@ int sfi_mixed_step(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   { StageTimer t(x, st, SFI_STAGE_ATTN2); SFI_TRY(launch_attn_gather(f, x->cfg.batch, f.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(d, x->cfg.batch, d.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
   if (!merge_in_score) {
-    MergeArgs m{x->ws.part, out, is_slow, x->cfg.n_q_heads, d.n_split * kWaves, fast_done ? 0 : f.n_split, 2, x->ws.jstat, d.n_split * kWaves, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha, ml};
+    MergeArgs m{x->ws.part, out, is_slow, x->cfg.n_q_heads, d.n_split * kWaves, fast_done ? 0 : f.n_split, 2, x->ws.jstat, d.n_split * kWaves, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha, ml, x->cfg.out_bf16};
     StageTimer t(x, st, SFI_STAGE_MERGE);
     SFI_TRY(launch_merge(m, x->cfg.batch, st));
     if (!t.stop()) return SFI_ELAUNCH;

@@ -331,7 +331,7 @@ __device__ __forceinline__ float2 load_device2(const float* p) {  // 8-byte alig
 // invalidated as a whole (a device-scope fence costs tens of microseconds here).
 // One thread per (head, four output dims); records eight at a time, all loads of the eight in flight.
 __device__ __forceinline__ void finish_pair(const float* part, int64_t head0, int G, int n_wgs, uint32_t* arrive,
-                                            float* out) {
+                                            float* out, bool out_bf16) {
   const int tid = threadIdx.x;
   __shared__ uint32_t s_before;
   // s_waitcnt vmcnt(0): a workgroup barrier by itself only orders the stores within the compute unit
@@ -373,8 +373,7 @@ __device__ __forceinline__ void finish_pair(const float* part, int64_t head0, in
       M = Mn;
     }
     const float inv = Z > 0.f ? 1.0f / Z : 0.f;
-    *reinterpret_cast<float4*>(out + (head0 + hh) * kHeadDim + 4 * c) =
-        make_float4(o.x * inv, o.y * inv, o.z * inv, o.w * inv);
+    store_out4(out, (head0 + hh) * kHeadDim + 4 * c, make_float4(o.x * inv, o.y * inv, o.z * inv, o.w * inv), out_bf16);
   }
 }
 
@@ -666,7 +665,7 @@ __global__ __launch_bounds__(kAttnThreads, BIG ? 1 : 2) void attn_dense_kernel(c
 // finish merges the records into out_merge[b, head, :] (finish_pair; no merge kernel follows).
 __device__ __forceinline__ void write_wg_record(float* part, int64_t head0, int G, int slot, const f32x4 (&acc)[8],
                                                 float m_run, float l_run, float* out, float* out_merge = nullptr,
-                                                uint32_t* arrive = nullptr, int n_split = 1) {
+                                                uint32_t* arrive = nullptr, int n_split = 1, bool out_bf16 = false) {
   const int tid = threadIdx.x;
   const int lane = tid & 63, w = tid >> 6;
   const int jg = lane >> 4, n = lane & 15;
@@ -704,7 +703,7 @@ __device__ __forceinline__ void write_wg_record(float* part, int64_t head0, int 
         ls += s_l[ww][hh] * fast_exp2(s_m[ww][hh] - M);
         sum += s_red[ww][hh][dim];
       }
-      out[(head0 + hh) * kHeadDim + dim] = ls > 0.f ? sum / ls : 0.f;
+      store_out(out, (head0 + hh) * kHeadDim + dim, ls > 0.f ? sum / ls : 0.f, out_bf16);
     }
     return;
   }
@@ -733,7 +732,7 @@ __device__ __forceinline__ void write_wg_record(float* part, int64_t head0, int 
       *reinterpret_cast<float2*>(r) = make_float2(M, ls);
     }
   }
-  if (tail) finish_pair(part, head0, G, n_split, arrive, out_merge);
+  if (tail) finish_pair(part, head0, G, n_split, arrive, out_merge, out_bf16);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -804,7 +803,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_kernel(const Attn
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
   write_wg_record(a.part, head0, G, slot, acc, m_run, l_run, a.out_direct, a.out_merge,
-                  a.arrive != nullptr ? a.arrive + bh : nullptr, a.n_split);
+                  a.arrive != nullptr ? a.arrive + bh : nullptr, a.n_split, a.out_bf16 != 0);
   report_guard(a.guard, W.bad);  // last: the way to the record and the merge is the launch's critical path
 }
 
@@ -945,7 +944,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(con
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
   write_wg_record(a.part, head0, G, slot, acc, m_run, l_run, a.out_direct, a.out_merge,
-                  a.arrive != nullptr ? a.arrive + bh : nullptr, a.n_split);
+                  a.arrive != nullptr ? a.arrive + bh : nullptr, a.n_split, a.out_bf16 != 0);
   report_guard(a.guard, W.bad);  // last: the way to the record and the merge is the launch's critical path
 }
 
@@ -1051,7 +1050,7 @@ __global__ __launch_bounds__(kAttnThreads, PAGED ? 2 : 3) void attn_compact_kern
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
   write_wg_record(a.part, head0, G, slot, acc, m_run, l_run, a.out_direct, a.out_merge,
-                  a.arrive != nullptr ? a.arrive + bh : nullptr, a.n_split);
+                  a.arrive != nullptr ? a.arrive + bh : nullptr, a.n_split, a.out_bf16 != 0);
   report_guard(a.guard, bad);
 }
 
@@ -1142,7 +1141,7 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(const MergeArgs a)
     const int nTS = (nS + (L - rs) + kTile - 1) / kTile;
     n_slots = a.slots_slow + min(a.slots_slow, nTS);
   }
-  merge_records(a.part, a.out, bg, n_slots, dense ? a.jstat : nullptr, a.n_j, a.G, a.alpha);
+  merge_records(a.part, a.out, bg, n_slots, dense ? a.jstat : nullptr, a.n_j, a.G, a.alpha, a.out_bf16 != 0);
 }
 
 __global__ void advance_kernel(int32_t* ctx_len, int32_t* recent_start, int B, int n_sink, int recent) {

@@ -27,6 +27,23 @@ constexpr int kStateWords = 8;     // per (b, h) Selector state, see SelState
 constexpr float kNeg = -1.0e30f;   // "minus infinity" that stays finite under subtraction
 constexpr float kLog2e = 1.4426950408889634f;
 
+// Output stores: fp32, or bf16 rounded to nearest even (results here are finite: no NaN handling).
+__device__ __forceinline__ uint32_t bf16_rne(float v) {
+  const uint32_t u = __float_as_uint(v);
+  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ void store_out(float* out, int64_t elem, float v, bool as_bf16) {
+  if (as_bf16) reinterpret_cast<uint16_t*>(out)[elem] = (uint16_t)bf16_rne(v);
+  else out[elem] = v;
+}
+__device__ __forceinline__ void store_out4(float* out, int64_t elem, float4 v, bool as_bf16) {  // elem % 4 == 0
+  if (as_bf16)
+    *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(out) + elem) =
+        make_uint2(bf16_rne(v.x) | (bf16_rne(v.y) << 16), bf16_rne(v.z) | (bf16_rne(v.w) << 16));
+  else
+    *reinterpret_cast<float4*>(out + elem) = v;
+}
+
 // Per (sequence, KV head) Selector state words.
 enum SelState { ST_CAND = 0, ST_BIN1 = 1, ST_K1 = 2, ST_TAU = 3, ST_TAKE = 4, ST_FLAGS = 5, ST_KSEL = 6 };
 constexpr uint32_t kFlagAll = 1u;   // budget >= |J|: take every position of J
@@ -92,6 +109,7 @@ struct AttnArgs {
   const uint16_t* Vc;
   int64_t c_sb, c_sh;            // compact mode: strides between sequences / KV heads, in elements
   int32_t c_rows;                // compact mode: rows every (b, h) slice of Kc / Vc holds (all readable)
+  int32_t out_bf16;              // out_direct / out_merge are bf16 (rounded to nearest even as stored), not fp32
   int32_t len_cap;               // ctx_len[b] is clamped to [0, len_cap]: the launch's max_len, else cfg.max_ctx
   int32_t n_blocks;              // paged cache: block ids are clamped to [0, n_blocks)
   int32_t* guard;                // Workspace::guard
@@ -131,6 +149,7 @@ struct MergeArgs {
   int32_t n_sink, recent;
   float alpha;                         // power-mean exponent of the evidence (Eq. selector_mu)
   int32_t len_cap;                     // the clamp the dense launch applied to ctx_len
+  int32_t out_bf16;                    // out is bf16
 };
 
 struct SelArgs {
@@ -167,6 +186,7 @@ struct SelArgs {
   const float* part;       // nullptr: a merge launch has run, jstat is valid
   float* merge_out;
   int32_t len_cap;         // the clamp the dense launch applied to ctx_len
+  int32_t out_bf16;        // merge_out is bf16
 };
 
 hipError_t launch_attn_dense(const AttnArgs& a, int B, int n_slots, hipStream_t s);

@@ -17,7 +17,7 @@ static_assert(kSlotCap <= kMergeThreads, "one record header per thread");
 // stored as jstat[bg] = { M = max of y over J, Z^(-alpha) / G } with Z = sum over J of 2^(y - M): the
 // head's term of Eq. selector_mu is then p^alpha / G = (Z^(-alpha) / G) * 2^(alpha (y - M)).
 __device__ __forceinline__ void merge_records(const float* part, float* out, int bg, int n_slots, float2* jstat,
-                                              int n_j, int G, float alpha) {
+                                              int n_j, int G, float alpha, bool out_bf16) {
   const float* P = part + (int64_t)bg * kSlotCap * kPartStride;
   const int tid = threadIdx.x;
   const int sl = tid >> 5, c = tid & 31;
@@ -98,8 +98,8 @@ __device__ __forceinline__ void merge_records(const float* part, float* out, int
     }
     const float inv = Z > 0.f ? 1.0f / Z : 0.f;
     if (out != nullptr)  // nullptr: only the J statistics were wanted (evidence-only pass)
-      *reinterpret_cast<float4*>(out + (int64_t)bg * kHeadDim + 4 * tid) =
-        make_float4(t.x * inv, t.y * inv, t.z * inv, t.w * inv);
+      store_out4(out, (int64_t)bg * kHeadDim + 4 * tid, make_float4(t.x * inv, t.y * inv, t.z * inv, t.w * inv),
+                 out_bf16);
   }
 }
 

@@ -121,7 +121,7 @@ __device__ __forceinline__ void merge_head(const SelArgs& a, int b, int h, int g
   const int rs = min(max(a.n_sink, L - a.recent), L);
   const int nTS = (nS + (L - rs) + 31) / 32;
   const int n_slots = a.n_jrec + min(a.n_jrec, nTS);
-  merge_records(a.part, a.merge_out, b * a.Hq + h * a.G + g, n_slots, nullptr, 0, a.G, a.alpha);
+  merge_records(a.part, a.merge_out, b * a.Hq + h * a.G + g, n_slots, nullptr, 0, a.G, a.alpha, a.out_bf16 != 0);
 }
 
 // ... and every other workgroup takes the J-only softmax statistics of the group's heads from the

@@ -28,6 +28,20 @@ def row_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
     return float((num / np.maximum(den, 1e-30)).max())
 
 
+def check_out_bf16(got, ref):
+    """Outputs stored as bf16 (handed over widened to fp32): every element within one bf16 ulp of itself (the
+    rounding, plus one ulp where the fp32 result sits next to a rounding boundary) plus 5e-5 of its row's
+    largest magnitude (the fp32 path's own error, three times the largest observed) of the fp64 reference."""
+    assert np.isfinite(got).all()
+    rowmax = np.abs(ref).max(axis=-1, keepdims=True)
+    err = np.abs(got.astype(np.float64) - ref)
+    bound = np.abs(ref) * 2.0 ** -8 + 5e-5 * rowmax + 1e-30
+    worst = float((err / bound).max())
+    assert worst <= 1.0, f"bf16 output off by {worst:.3f} of its bound"
+    assert np.array_equal(got.astype(np.float32).view(np.uint32) & 0xFFFF, np.zeros_like(got, np.uint32)), "not bf16 values"
+    return worst
+
+
 def check_out(got, ref, tol=OUT_TOL):
     assert np.isfinite(got).all()
     err = row_rel_err(got, ref)
@@ -105,7 +119,7 @@ class Runner:
     """Device copies of one workload's K/V plus an sfi context; thin wrappers over the C-ABI calls."""
 
     def __init__(self, w, max_budget=None, selector=None, alpha=0.0, page_size=0, ctx_max=None, page_layout="thd",
-                 scale=0.0):
+                 scale=0.0, out_bf16=False):
         """page_size > 0: the cache is handed over as block pools + block table (valid up to ctx_max[b] rows,
         default every allocated row); self.K / self.V are then the pools."""
         import torch
@@ -121,16 +135,17 @@ class Runner:
             self.K, self.V = to_dev(w.K), to_dev(w.V)
         self.ctx = sfi.SfiContext(w.B, w.Hq, w.Hkv, self.max_ctx, w.budget if max_budget is None else max_budget,
                                   w.n_sink, w.recent, self.K, self.V, scale=scale, selector=selector, alpha=alpha,
-                                  page_size=page_size, page_layout=page_layout)
+                                  page_size=page_size, page_layout=page_layout, out_bf16=out_bf16)
         if page_size:
             sfi.sfi_set_block_table(self.ctx.handle, self.table, self.K.shape[0])
-        self.out = torch.zeros(w.B, w.Hq, w.d, dtype=torch.float32, device="cuda")
+        # with bf16 outputs the wrappers below return the values widened to fp32 (exact)
+        self.out = torch.zeros(w.B, w.Hq, w.d, dtype=torch.bfloat16 if out_bf16 else torch.float32, device="cuda")
 
     def dense(self, q_bits, ctx_len, max_len=0):
         self.out.fill_(float("nan"))
         self.sfi.sfi_dense_attn(self.ctx.handle, to_dev(q_bits), self.K, self.V, i32_dev(ctx_len), max_len, self.out)
         self.torch.cuda.synchronize()
-        return self.out.cpu().numpy()
+        return self.out.float().cpu().numpy()
 
     def slow(self, q_bits, ctx_len, budget, max_len=0):
         t = self.torch
@@ -140,7 +155,7 @@ class Runner:
         self.sfi.sfi_slow_step(self.ctx.handle, to_dev(q_bits), self.K, self.V, i32_dev(ctx_len), max_len, budget,
                                self.out, sel, nsel)
         t.cuda.synchronize()
-        return self.out.cpu().numpy(), sel.cpu().numpy(), nsel.cpu().numpy()
+        return self.out.float().cpu().numpy(), sel.cpu().numpy(), nsel.cpu().numpy()
 
     def fast(self, q_bits, sel, nsel, recent_start, ctx_len):
         self.out.fill_(float("nan"))
@@ -148,7 +163,7 @@ class Runner:
         self.sfi.sfi_fast_step(self.ctx.handle, to_dev(q_bits), self.K, self.V, sel_d, nsel_d, sel.shape[2],
                                i32_dev(recent_start), i32_dev(ctx_len), self.out)
         self.torch.cuda.synchronize()
-        return self.out.cpu().numpy()
+        return self.out.float().cpu().numpy()
 
     def reorg(self, sel, nsel, ctx_len, c_rows=None, is_slow=None, poison=0x7FC1):
         """Compact buffers (uint16 views of bf16 device tensors) after sfi_reorg; unfilled rows keep `poison`."""
@@ -169,7 +184,7 @@ class Runner:
         self.sfi.sfi_fast_step_compact(self.ctx.handle, to_dev(q_bits), self.Kc, self.Vc, i32_dev(nsel), sel_stride,
                                        self.K, self.V, i32_dev(recent_start), i32_dev(ctx_len), self.out)
         self.torch.cuda.synchronize()
-        return self.out.cpu().numpy()
+        return self.out.float().cpu().numpy()
 
     def close(self):
         self.ctx.close()
