@@ -24,7 +24,8 @@
  *   K, V     bf16, element (b, h, t, c) at  base + b*stride_b + h*stride_h + t*stride_t + c
  *            (strides in elements, given in sfi_config; a row of 128 elements is contiguous;
  *            row starts must be 16-byte aligned: stride_* multiples of 8, base 16-byte aligned).
- *   out      fp32  [B, Hq, 128] contiguous.
+ *   out      fp32  [B, Hq, 128] contiguous; with cfg.out_bf16 = 1 the same pointer (declared float* throughout)
+ *            addresses bf16 [B, Hq, 128] instead.
  *   sel_idx  int32 [B, Hkv, sel_stride]; n_sel int32 [B, Hkv].
  *   ctx_len, recent_start int32 [B].
  *
