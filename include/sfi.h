@@ -124,9 +124,10 @@ size_t sfi_workspace_bytes(const sfi_config* cfg);
 
 /* Validate cfg, bind the caller's workspace, return a context in *out.
  * Touches the device to read its properties and to clear a few hundred bytes of the workspace (the
- * arrival counters of the fast step's in-kernel merge; a blocking memset followed by a device
- * synchronisation, so not to be called while a stream of the device is capturing).  SFI_ELAUNCH if the
- * workspace is device memory and could not be cleared. */
+ * arrival counters of the fast step's in-kernel merge and the status word of sfi_device_status; a blocking
+ * memset followed by a device synchronisation, so not to be called while a stream of the device is
+ * capturing).  SFI_ELAUNCH if the workspace is memory the runtime knows (device, managed or pinned host
+ * memory) and could not be cleared. */
 int sfi_create(const sfi_config* cfg, void* workspace, size_t workspace_bytes, sfi_ctx** out);
 
 /*

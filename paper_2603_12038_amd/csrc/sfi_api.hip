@@ -369,12 +369,12 @@ int sfi_create(const sfi_config* cfg, void* workspace, size_t workspace_bytes, s
   x->fast_tiles_per_wave = 0;
   x->tail_merge = 1;
   // The arrival counters of split fast-step launches start at zero (and every launch leaves them there).
-  // A workspace that is device memory is cleared here and a failure to do so is an error: with stale
+  // A workspace the runtime knows (device, managed, pinned) is cleared here and a failure to do so is an error: with stale
   // counters no workgroup would ever take itself for the last one.  (Without a device, or with a
   // pointer the runtime does not know, nothing can be launched on this context anyway.)
   hipPointerAttribute_t attr;
   if (have_device && hipPointerGetAttributes(&attr, ws.arrive) == hipSuccess &&
-      attr.type == hipMemoryTypeDevice) {
+      attr.type != hipMemoryTypeUnregistered) {  // device, managed or pinned host memory: all of it is cleared here
     const size_t n_clear = (size_t)((char*)ws.guard - (char*)ws.arrive) + sizeof(int32_t);  // counters and guard word
     if (hipMemset(ws.arrive, 0, n_clear) != hipSuccess ||
         hipDeviceSynchronize() != hipSuccess) {
