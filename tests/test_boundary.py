@@ -245,3 +245,38 @@ def test_launch_plan_loads_the_compute_units_evenly():
     # knobs: a total for the dense launch, tiles per wave for the gather launch; negative restores the default
     assert _plan(4, 8, 32768, 2048, tuning=(512, 1, 0)) == (16, 18)
     assert _plan(4, 8, 32768, 2048, tuning=(-1, -1, 0)) == (8, 6)
+
+
+def test_header_is_plain_c_and_the_binding_mirrors_its_config_layout(tmp_path):
+    """include/sfi.h compiles as strict C99 on its own, and every field of the ctypes mirror of
+    sfi_config sits at the offset and has the size the C compiler gives it (a field added to one side
+    only would shift everything behind it without any error)."""
+    import subprocess
+
+    lines = ['#include <stddef.h>', '#include <stdio.h>', '#include "sfi.h"', 'int main(void) {',
+             '  printf("sizeof %zu\\n", sizeof(sfi_config));']
+    for name, _ in SfiConfig._fields_:
+        lines.append(f'  printf("{name} %zu %zu\\n", offsetof(sfi_config, {name}), sizeof(((sfi_config*)0)->{name}));')
+    lines += ['  return 0;', '}']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines) + "\n")
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe)], check=True)
+    got = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split("\n")
+    assert got[0] == f"sizeof {C.sizeof(SfiConfig)}"
+    seen = {}
+    for ln in got[1:]:
+        if ln:
+            name, off, size = ln.split()
+            seen[name] = (int(off), int(size))
+    for name, ctype in SfiConfig._fields_:
+        assert seen[name] == (getattr(SfiConfig, name).offset, C.sizeof(ctype)), name
+    # and the header has no field the mirror lacks: its struct body names exactly these identifiers
+    text = open(os.path.join(ROOT, "include", "sfi.h")).read()
+    body = text[text.index("typedef struct sfi_config"):]
+    body = body[:body.index("} sfi_config;")]
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    decl = re.findall(r"\b(?:int32_t|int64_t|float)\s+([^;]+);", body)
+    names = [n.strip() for d in decl for n in d.split(",")]
+    assert names == [n for n, _ in SfiConfig._fields_]
