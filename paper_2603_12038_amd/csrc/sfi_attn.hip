@@ -63,9 +63,29 @@ template <bool PAGED> struct RowOff { typedef uint32_t type; };
 template <> struct RowOff<true> { typedef uint64_t type; };
 
 struct Tile {
-  uint4 ka[4], kb[4];  // K rows of blocks A / B: row n, dims kblk*32 + 8*jg .. +8
+  uint4 ka[4], kb[4];  // K rows of blocks A / B: row n, dims kblk*32 + 8*jg .. +8  (WIDE: see below)
   uint4 v[8];          // V rows 4*jg + i of block A (i < 4) and block B (i >= 4), dims 8n .. 8n+7
 };
+
+// WIDE (the gather kernels, query groups of at most 8 heads): a K row's 256 bytes go out as two requests
+// for whole 128-byte lines instead of four for 64 bytes -- a compute unit's bandwidth is the requests it
+// keeps in flight times their size.  (The dense kernel stays with the plain layout: with one wave per
+// SIMD nothing hides the two rounds of lane exchanges below, and it measured 1-4 % slower.)  The operand layout gives a row of the matrix product to four lanes of 16 bytes, so
+// a row of the product is made half a K row: the tile is four blocks of 8 positions, product row
+// n = 8 * half + r of block blk is position 8 * blk + r, dims 64 * kb + 32 * half + 8 * jg .. + 8 in
+// step kb (two steps), and its column 8 * half' + head is the same half of q[head].  The halves
+// meet where half == half': lane (jg < 2, n < 8) and its mirror (jg + 2, n + 8), 40 lanes up.
+// K registers: ka[2 * blk + kb] for blk < 2, kb[2 * (blk - 2) + kb] above.
+// Position of V slot i (and of logit y[i]) of lane row jg within the tile:
+template <bool WIDE>
+__device__ __forceinline__ int slot_pos(int jg, int i) {
+  return WIDE ? 16 * (jg >> 1) + 8 * (i >> 2) + 4 * (jg & 1) + (i & 3) : 16 * (i >> 2) + 4 * jg + (i & 3);
+}
+__device__ __forceinline__ uint4& wide_k(Tile& T, int blk, int kb) { return blk < 2 ? T.ka[2 * blk + kb] : T.kb[2 * (blk - 2) + kb]; }
+__device__ __forceinline__ const uint4& wide_k(const Tile& T, int blk, int kb) { return blk < 2 ? T.ka[2 * blk + kb] : T.kb[2 * (blk - 2) + kb]; }
+// this lane's byte offset into a K row
+template <bool WIDE>
+__device__ __forceinline__ uint32_t k_lane_of(int jg, int n) { return WIDE ? (uint32_t)((n >> 3) * 64 + jg * 16) : (uint32_t)(jg * 16); }
 
 // Per-wave addressing of one (sequence, KV head): uniform bases, per-lane byte offsets.
 struct Rows {
@@ -121,7 +141,17 @@ __device__ __forceinline__ void report_guard(int32_t* guard, int bad) {
 // Row loads of a tile whose positions map to consecutive cache rows: block A row n is cache row
 // r0 + n; rows above r_max are replaced by r_max (they carry no weight).  K and V separately, so
 // that each half of the tile buffer can be refilled as soon as its consumer is done with it.
+template <bool WIDE = false>
 __device__ __forceinline__ void issue_k_affine(Tile& T, const Rows& R, int r0, int r_max) {
+  if (WIDE) {
+#pragma unroll
+    for (int blk = 0; blk < 4; ++blk) {
+      const uint32_t o = (uint32_t)min(r0 + 8 * blk + (R.n & 7), r_max) * R.k_st + R.k_lane;
+      wide_k(T, blk, 0) = load_row16(R.Kb, o);
+      wide_k(T, blk, 1) = load_row16(R.Kb, o + 128u);
+    }
+    return;
+  }
   const uint32_t oa = (uint32_t)min(r0 + R.n, r_max) * R.k_st + R.k_lane;
   const uint32_t ob = (uint32_t)min(r0 + 16 + R.n, r_max) * R.k_st + R.k_lane;
 #pragma unroll
@@ -130,22 +160,36 @@ __device__ __forceinline__ void issue_k_affine(Tile& T, const Rows& R, int r0, i
     T.kb[kb] = load_row16(R.Kb, ob + kb * 64);
   }
 }
+template <bool WIDE = false>
 __device__ __forceinline__ void issue_v_affine(Tile& T, const Rows& R, int r0, int r_max) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    T.v[i] = load_row16(R.Vb, (uint32_t)min(r0 + 4 * R.jg + i, r_max) * R.v_st + R.v_lane);
-    T.v[4 + i] = load_row16(R.Vb, (uint32_t)min(r0 + 16 + 4 * R.jg + i, r_max) * R.v_st + R.v_lane);
+    T.v[i] = load_row16(R.Vb, (uint32_t)min(r0 + slot_pos<WIDE>(R.jg, i), r_max) * R.v_st + R.v_lane);
+    T.v[4 + i] = load_row16(R.Vb, (uint32_t)min(r0 + slot_pos<WIDE>(R.jg, 4 + i), r_max) * R.v_st + R.v_lane);
   }
 }
+template <bool WIDE = false>
 __device__ __forceinline__ void issue_affine(Tile& T, const Rows& R, int r0, int r_max) {
-  issue_k_affine(T, R, r0, r_max);
-  issue_v_affine(T, R, r0, r_max);
+  issue_k_affine<WIDE>(T, R, r0, r_max);
+  issue_v_affine<WIDE>(T, R, r0, r_max);
 }
 
 // Row loads of a tile with arbitrary rows: ra / rb are the cache rows of this lane's K rows in
 // blocks A / B; the V rows 4*jg + i are the ones lanes 4*jg + i resolved for K.  OffT: RowOff<>::type.
-template <typename OffT = uint32_t>
+template <typename OffT = uint32_t, bool WIDE = false>
 __device__ __forceinline__ void issue_k_rows(Tile& T, const Rows& R, int ra, int rb) {
+  if (WIDE) {  // positions 8 * blk + (n & 7): held by this lane or by the lane 8 further round its row of 16
+    const int xa = __shfl_xor(ra, 8), xb = __shfl_xor(rb, 8);
+    const bool lo = R.n < 8;
+    const int r[4] = {lo ? ra : xa, lo ? xa : ra, lo ? rb : xb, lo ? xb : rb};
+#pragma unroll
+    for (int blk = 0; blk < 4; ++blk) {
+      const OffT o = (OffT)(uint32_t)r[blk] * R.k_st + R.k_lane;
+      wide_k(T, blk, 0) = load_row16(R.Kb, (OffT)o);
+      wide_k(T, blk, 1) = load_row16(R.Kb, (OffT)(o + 128u));
+    }
+    return;
+  }
   const OffT oa = (OffT)(uint32_t)ra * R.k_st + R.k_lane, ob = (OffT)(uint32_t)rb * R.k_st + R.k_lane;
 #pragma unroll
   for (int kb = 0; kb < 4; ++kb) {
@@ -153,22 +197,46 @@ __device__ __forceinline__ void issue_k_rows(Tile& T, const Rows& R, int ra, int
     T.kb[kb] = load_row16(R.Kb, (OffT)(ob + kb * 64));
   }
 }
-template <typename OffT = uint32_t>
+template <typename OffT = uint32_t, bool WIDE = false>
 __device__ __forceinline__ void issue_v_rows(Tile& T, const Rows& R, int ra, int rb) {
+  if (WIDE) {  // slot i is position slot_pos(jg, i): index 4 * (jg & 1) + (i & 3) + 8 * (i >> 2) of ra (jg < 2) or rb,
+               // taken from the lane of this lane's own row of 16 that resolved it
+    const int sel = R.jg < 2 ? ra : rb;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      T.v[i] = load_row16(R.Vb, (OffT)((OffT)(uint32_t)__shfl(sel, 16 * R.jg + 4 * (R.jg & 1) + i) * R.v_st + R.v_lane));
+      T.v[4 + i] = load_row16(R.Vb, (OffT)((OffT)(uint32_t)__shfl(sel, 16 * R.jg + 8 + 4 * (R.jg & 1) + i) * R.v_st + R.v_lane));
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     T.v[i] = load_row16(R.Vb, (OffT)((OffT)(uint32_t)__shfl(ra, 4 * R.jg + i) * R.v_st + R.v_lane));
     T.v[4 + i] = load_row16(R.Vb, (OffT)((OffT)(uint32_t)__shfl(rb, 4 * R.jg + i) * R.v_st + R.v_lane));
   }
 }
-template <typename OffT = uint32_t>
+template <typename OffT = uint32_t, bool WIDE = false>
 __device__ __forceinline__ void issue_rows(Tile& T, const Rows& R, int ra, int rb) {
-  issue_k_rows<OffT>(T, R, ra, rb);
-  issue_v_rows<OffT>(T, R, ra, rb);
+  issue_k_rows<OffT, WIDE>(T, R, ra, rb);
+  issue_v_rows<OffT, WIDE>(T, R, ra, rb);
 }
 
 // Q^T operand: head n, dims kblk*32 + 8*jg .. +8; zero for heads >= G (no branch around the loads).
+template <bool WIDE = false>
 __device__ __forceinline__ void load_q(bf16x8 (&qreg)[4], const uint16_t* q, int64_t head0, int G, int jg, int n) {
+  if (WIDE) {  // column n = 8 * half + head: dims 64 * kb + 32 * half + 8 * jg .. + 8 of q[head]; qreg[2], qreg[3] unused
+    const int head = n & 7;
+    const uint16_t* qw = q + (head0 + (head < G ? head : 0)) * kHeadDim + (n >> 3) * 32 + jg * 8;
+    const uint32_t kp = head < G ? 0xffffffffu : 0u;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      uint4 t = *reinterpret_cast<const uint4*>(qw + kb * 64);
+      t.x &= kp; t.y &= kp; t.z &= kp; t.w &= kp;
+      qreg[kb] = as_bf16x8(t);
+      qreg[2 + kb] = as_bf16x8(make_uint4(0u, 0u, 0u, 0u));
+    }
+    return;
+  }
   const uint16_t* qp = q + (head0 + (n < G ? n : 0)) * kHeadDim + jg * 8;
   const uint32_t keep = n < G ? 0xffffffffu : 0u;
 #pragma unroll
@@ -185,7 +253,33 @@ __device__ __forceinline__ void load_q(bf16x8 (&qreg)[4], const uint16_t* q, int
 // Lanes of heads >= G see q = 0; their state stays finite and is never written out: no mask needed.
 
 // Phase 1: y[i] = logit (log2 domain) of head n, row 4*jg+i of block A (i < 4) / block B (i >= 4).
+template <bool WIDE = false>
 __device__ __forceinline__ void qk_phase(const Tile& T, const bf16x8 (&qreg)[4], float c2, float (&y)[8]) {
+  if (WIDE) {
+    f32x4 s[4];
+#pragma unroll
+    for (int blk = 0; blk < 4; ++blk) {
+      s[blk] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+        s[blk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wide_k(T, blk, kb)), qreg[kb], s[blk], 0, 0, 0);
+    }
+    // s[blk][i] of lane (jg, n): product row 4 * jg + i, column n.  Lane (jg < 2, n < 8) holds the first-half
+    // sums of positions 8 * blk + 4 * jg + i for head n, its mirror 40 lanes up the second-half sums.  The
+    // lower lane keeps blocks 0 and 1, the mirror blocks 2 and 3: each sends the other the half it lacks.
+    // Then lane (jg >= 2, n < 8) fetches its logits from the mirror (jg, n + 8) in its own row of 16.
+    const int lane = threadIdx.x & 63, jg = lane >> 4, n = lane & 15;
+    const bool low = jg < 2;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float u0 = (low ? s[0][i] : s[2][i]) + __shfl_xor(low ? s[2][i] : s[0][i], 40);
+      const float u1 = (low ? s[1][i] : s[3][i]) + __shfl_xor(low ? s[3][i] : s[1][i], 40);
+      const float x0 = __shfl_xor(u0, 8), x1 = __shfl_xor(u1, 8);
+      y[i] = n < 8 ? (low ? u0 : x0) * c2 : 0.f;
+      y[4 + i] = n < 8 ? (low ? u1 : x1) * c2 : 0.f;
+    }
+    return;
+  }
   f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int kb = 0; kb < 4; ++kb) {
@@ -216,20 +310,21 @@ __device__ __forceinline__ void knorm_phase(const Tile& T, int jg, int n, float&
 }
 
 // y of head n, rows 0..31 of the tile, goes to stage[n * 32 ..] (this wave's LDS patch).
+template <bool WIDE = false>
 __device__ __forceinline__ void stage_logits(float* stage, const float (&y)[8], int jg, int n, int G) {
   if (n < G) {
-    *reinterpret_cast<float4*>(stage + n * kTile + 4 * jg) = make_float4(y[0], y[1], y[2], y[3]);
-    *reinterpret_cast<float4*>(stage + n * kTile + 16 + 4 * jg) = make_float4(y[4], y[5], y[6], y[7]);
+    *reinterpret_cast<float4*>(stage + n * kTile + slot_pos<WIDE>(jg, 0)) = make_float4(y[0], y[1], y[2], y[3]);
+    *reinterpret_cast<float4*>(stage + n * kTile + slot_pos<WIDE>(jg, 4)) = make_float4(y[4], y[5], y[6], y[7]);
   }
 }
 
 // Ragged last tile: positions >= N carry no weight; their V rows may hold anything, so zero them
 // to keep 0 * v finite.
-template <bool WITH_V = true>  // false: the tile holds no V rows (evidence-only pass)
+template <bool WITH_V = true, bool WIDE = false>  // WITH_V false: the tile holds no V rows (evidence-only pass)
 __device__ __forceinline__ void mask_tail(Tile& T, float (&y)[8], int jg, int p0, int N) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const bool oka = p0 + 4 * jg + i < N, okb = p0 + 16 + 4 * jg + i < N;
+    const bool oka = p0 + slot_pos<WIDE>(jg, i) < N, okb = p0 + slot_pos<WIDE>(jg, 4 + i) < N;
     y[i] = oka ? y[i] : kNeg;
     y[4 + i] = okb ? y[4 + i] : kNeg;
     if (WITH_V && !oka) T.v[i] = make_uint4(0u, 0u, 0u, 0u);
@@ -297,12 +392,12 @@ __device__ __forceinline__ void pv_phase(const Tile& T, const bf16x8& a_hi, cons
 }
 
 // All three phases on a tile that is already in registers.  MASKED: ragged last tile of a list.
-template <bool MASKED>
+template <bool MASKED, bool WIDE = false>
 __device__ __forceinline__ void tile_math(Tile& T, const bf16x8 (&qreg)[4], float c2, f32x4 (&acc)[8],
                                           float& m_run, float& l_run, int jg, int p0, int N) {
   float y[8];
-  qk_phase(T, qreg, c2, y);
-  if (MASKED) mask_tail(T, y, jg, p0, N);
+  qk_phase<WIDE>(T, qreg, c2, y);
+  if (MASKED) mask_tail<true, WIDE>(T, y, jg, p0, N);
   bf16x8 a_hi, a_lo;
   softmax_phase(y, acc, m_run, l_run, jg, a_hi, a_lo);
   pv_phase(T, a_hi, a_lo, acc);
@@ -738,7 +833,7 @@ __device__ __forceinline__ void write_wg_record(float* part, int64_t head0, int 
 // ------------------------------------------------------------------------------------------------
 // gather kernel
 // ------------------------------------------------------------------------------------------------
-template <bool PAGED>
+template <bool PAGED, bool WIDE>
 __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_kernel(const AttnArgs a) {
   const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   if (a.is_slow != nullptr && a.is_slow[b] != 0) return;
@@ -762,7 +857,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_kernel(const Attn
   int sA = W.sel_at(first * kTile + n);
   int sB = W.sel_at(first * kTile + 16 + n);
   bf16x8 qreg[4];
-  load_q(qreg, a.q, head0, G, jg, n);
+  load_q<WIDE>(qreg, a.q, head0, G, jg, n);
   W.bad = 0;
   const int L = guarded_len(L_in, a.len_cap, W.bad);
   W.set_counts(L, n_sel_in, rs_in, (int)a.sel_stride);
@@ -772,7 +867,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_kernel(const Attn
   R.Vb = reinterpret_cast<const char*>(a.V + b * a.v_sb + h * a.v_sh);
   R.k_st = (uint32_t)a.k_st * 2u;
   R.v_st = (uint32_t)a.v_st * 2u;
-  R.k_lane = jg * 16;
+  R.k_lane = k_lane_of<WIDE>(jg, n);
   R.v_lane = n * 16;
   R.jg = jg;
   R.n = n;
@@ -796,9 +891,9 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_kernel(const Attn
       ra = P.phys(ra, P.page_of(ra), W.bad);
       rb = P.phys(rb, P.page_of(rb), W.bad);
     }
-    issue_rows<typename RowOff<PAGED>::type>(T, R, ra, rb);
-    if (p0 + kTile <= W.N) tile_math<false>(T, qreg, a.scale_log2, acc, m_run, l_run, jg, p0, W.N);
-    else tile_math<true>(T, qreg, a.scale_log2, acc, m_run, l_run, jg, p0, W.N);
+    issue_rows<typename RowOff<PAGED>::type, WIDE>(T, R, ra, rb);
+    if (p0 + kTile <= W.N) tile_math<false, WIDE>(T, qreg, a.scale_log2, acc, m_run, l_run, jg, p0, W.N);
+    else tile_math<true, WIDE>(T, qreg, a.scale_log2, acc, m_run, l_run, jg, p0, W.N);
   }
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
@@ -815,7 +910,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_kernel(const Attn
 // after P V; the selected indices are read two tiles ahead.  Loads past the wave's last tile fall
 // on row 0 (no branch around a load, so every wait names exactly the loads it needs).
 // ------------------------------------------------------------------------------------------------
-template <bool PAGED>
+template <bool PAGED, bool WIDE>
 __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(const AttnArgs a) {
   const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   if (a.is_slow != nullptr && a.is_slow[b] != 0) return;
@@ -838,7 +933,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(con
   const int p_first = first * kTile;
   const int sA = W.sel_at_nonempty(p_first + n), sB = W.sel_at_nonempty(p_first + 16 + n);
   bf16x8 qreg[4];
-  load_q(qreg, a.q, head0, G, jg, n);
+  load_q<WIDE>(qreg, a.q, head0, G, jg, n);
   W.bad = 0;
   const int L = guarded_len(L_in, a.len_cap, W.bad);
   W.set_counts(L, n_sel_in, rs_in, (int)a.sel_stride);
@@ -848,7 +943,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(con
   R.Vb = reinterpret_cast<const char*>(a.V + b * a.v_sb + h * a.v_sh);
   R.k_st = (uint32_t)a.k_st * 2u;
   R.v_st = (uint32_t)a.v_st * 2u;
-  R.k_lane = jg * 16;
+  R.k_lane = k_lane_of<WIDE>(jg, n);
   R.v_lane = n * 16;
   R.jg = jg;
   R.n = n;
@@ -877,7 +972,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(con
     ra = P.phys(ra, P.page_of(ra), W.bad);
     rb = P.phys(rb, P.page_of(rb), W.bad);
     __builtin_amdgcn_sched_barrier(0);
-    issue_k_rows<typename RowOff<PAGED>::type>(T, R, ra, rb);
+    issue_k_rows<typename RowOff<PAGED>::type, WIDE>(T, R, ra, rb);
     __builtin_amdgcn_sched_barrier(0);
     ra_n = W.row_of(p_first + pstep + n, sA1);
     rb_n = W.row_of(p_first + pstep + 16 + n, sB1);
@@ -887,17 +982,17 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(con
     sAn = W.sel_at_nonempty(p_first + 2 * pstep + n);
     sBn = W.sel_at_nonempty(p_first + 2 * pstep + 16 + n);
     __builtin_amdgcn_sched_barrier(0);
-    issue_v_rows<typename RowOff<PAGED>::type>(T, R, ra, rb);
+    issue_v_rows<typename RowOff<PAGED>::type, WIDE>(T, R, ra, rb);
     __builtin_amdgcn_sched_barrier(0);
   } else {
     const int ra = W.row_of(p_first + n, sA), rb = W.row_of(p_first + 16 + n, sB);
     __builtin_amdgcn_sched_barrier(0);  // the compiler's scheduler must not reorder the three groups
-    issue_k_rows<typename RowOff<PAGED>::type>(T, R, ra, rb);
+    issue_k_rows<typename RowOff<PAGED>::type, WIDE>(T, R, ra, rb);
     __builtin_amdgcn_sched_barrier(0);
     sAn = W.sel_at_nonempty(p_first + pstep + n);
     sBn = W.sel_at_nonempty(p_first + pstep + 16 + n);
     __builtin_amdgcn_sched_barrier(0);
-    issue_v_rows<typename RowOff<PAGED>::type>(T, R, ra, rb);
+    issue_v_rows<typename RowOff<PAGED>::type, WIDE>(T, R, ra, rb);
     __builtin_amdgcn_sched_barrier(0);
   }
   // The last tile is taken after the loop, without the refill: no rows are requested for a tile that does not
@@ -907,12 +1002,12 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(con
     const int p0 = p_first + k * pstep;
     const int pn = p0 + pstep;
     float y[8];
-    qk_phase(T, qreg, a.scale_log2, y);
+    qk_phase<WIDE>(T, qreg, a.scale_log2, y);
     int ra, rb;
     if (PAGED) {
       ra = P.phys(ra_n, pa_n, W.bad);
       rb = P.phys(rb_n, pb_n, W.bad);
-      issue_k_rows<typename RowOff<PAGED>::type>(T, R, ra, rb);
+      issue_k_rows<typename RowOff<PAGED>::type, WIDE>(T, R, ra, rb);
       ra_n = W.row_of(pn + pstep + n, sAn);  // row 0 past the list
       rb_n = W.row_of(pn + pstep + 16 + n, sBn);
       pa_n = P.page_of(ra_n);
@@ -922,21 +1017,21 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(con
     } else {
       ra = W.row_of(pn + n, sAn);  // row 0 past the list
       rb = W.row_of(pn + 16 + n, sBn);
-      issue_k_rows<typename RowOff<PAGED>::type>(T, R, ra, rb);
+      issue_k_rows<typename RowOff<PAGED>::type, WIDE>(T, R, ra, rb);
       sAn = W.sel_at_nonempty(pn + pstep + n);
       sBn = W.sel_at_nonempty(pn + pstep + 16 + n);
     }
-    if (p0 + kTile > W.N) mask_tail(T, y, jg, p0, W.N);
+    if (p0 + kTile > W.N) mask_tail<true, WIDE>(T, y, jg, p0, W.N);
     bf16x8 a_hi, a_lo;
     softmax_phase(y, acc, m_run, l_run, jg, a_hi, a_lo);
     pv_phase(T, a_hi, a_lo, acc);
-    issue_v_rows<typename RowOff<PAGED>::type>(T, R, ra, rb);
+    issue_v_rows<typename RowOff<PAGED>::type, WIDE>(T, R, ra, rb);
   }
   if (K > 0) {
     const int p0 = p_first + (K - 1) * pstep;
     float y[8];
-    qk_phase(T, qreg, a.scale_log2, y);
-    if (p0 + kTile > W.N) mask_tail(T, y, jg, p0, W.N);
+    qk_phase<WIDE>(T, qreg, a.scale_log2, y);
+    if (p0 + kTile > W.N) mask_tail<true, WIDE>(T, y, jg, p0, W.N);
     bf16x8 a_hi, a_lo;
     softmax_phase(y, acc, m_run, l_run, jg, a_hi, a_lo);
     pv_phase(T, a_hi, a_lo, acc);
@@ -1209,15 +1304,20 @@ hipError_t launch_reorg(const ReorgArgs& a, int B, int rows, hipStream_t s) {
   else hipLaunchKernelGGL(reorg_kernel<false>, grid, dim3(kAttnThreads), 0, s, a);
   return hipGetLastError();
 }
+template <bool WIDE>
+static void launch_gather_t(const AttnArgs& a, dim3 grid, hipStream_t s) {
+  if (a.pipelined) {
+    if (a.table != nullptr) hipLaunchKernelGGL((attn_gather_stream_kernel<true, WIDE>), grid, dim3(kAttnThreads), 0, s, a);
+    else hipLaunchKernelGGL((attn_gather_stream_kernel<false, WIDE>), grid, dim3(kAttnThreads), 0, s, a);
+  } else {
+    if (a.table != nullptr) hipLaunchKernelGGL((attn_gather_kernel<true, WIDE>), grid, dim3(kAttnThreads), 0, s, a);
+    else hipLaunchKernelGGL((attn_gather_kernel<false, WIDE>), grid, dim3(kAttnThreads), 0, s, a);
+  }
+}
 hipError_t launch_attn_gather(const AttnArgs& a, int B, int n_slots, hipStream_t s) {
   const dim3 grid(n_slots, a.Hkv, B);
-  if (a.pipelined) {
-    if (a.table != nullptr) hipLaunchKernelGGL(attn_gather_stream_kernel<true>, grid, dim3(kAttnThreads), 0, s, a);
-    else hipLaunchKernelGGL(attn_gather_stream_kernel<false>, grid, dim3(kAttnThreads), 0, s, a);
-  } else {
-    if (a.table != nullptr) hipLaunchKernelGGL(attn_gather_kernel<true>, grid, dim3(kAttnThreads), 0, s, a);
-    else hipLaunchKernelGGL(attn_gather_kernel<false>, grid, dim3(kAttnThreads), 0, s, a);
-  }
+  if (a.G <= 8) launch_gather_t<true>(a, grid, s);
+  else launch_gather_t<false>(a, grid, s);
   return hipGetLastError();
 }
 hipError_t launch_merge(const MergeArgs& a, int B, hipStream_t s) {
