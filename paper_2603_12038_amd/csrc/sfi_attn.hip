@@ -83,6 +83,16 @@ __device__ __forceinline__ int slot_pos(int jg, int i) {
 }
 __device__ __forceinline__ uint4& wide_k(Tile& T, int blk, int kb) { return blk < 2 ? T.ka[2 * blk + kb] : T.kb[2 * (blk - 2) + kb]; }
 __device__ __forceinline__ const uint4& wide_k(const Tile& T, int blk, int kb) { return blk < 2 ? T.ka[2 * blk + kb] : T.kb[2 * (blk - 2) + kb]; }
+// Lane exchanges of the WIDE layout on the vector ALU (no trip through the LDS crossbar): the lane 8
+// further round the same row of 16 (row rotate by 8), and the lane 40 up or down (the same, then the
+// two halves of the wave swapped).
+__device__ __forceinline__ int lane_xor8(int v) { return __builtin_amdgcn_update_dpp(0, v, 0x128, 0xf, 0xf, false); }
+__device__ __forceinline__ float lane_xor8(float v) { return __int_as_float(lane_xor8(__float_as_int(v))); }
+__device__ __forceinline__ float lane_xor40(float v) {
+  const unsigned w = (unsigned)lane_xor8(__float_as_int(v));
+  const auto sw = __builtin_amdgcn_permlane32_swap(w, w, false, false);  // [0]: lower half twice, [1]: upper half twice
+  return __uint_as_float((threadIdx.x & 32) != 0 ? sw[0] : sw[1]);
+}
 // this lane's byte offset into a K row
 template <bool WIDE>
 __device__ __forceinline__ uint32_t k_lane_of(int jg, int n) { return WIDE ? (uint32_t)((n >> 3) * 64 + jg * 16) : (uint32_t)(jg * 16); }
@@ -179,7 +189,7 @@ __device__ __forceinline__ void issue_affine(Tile& T, const Rows& R, int r0, int
 template <typename OffT = uint32_t, bool WIDE = false>
 __device__ __forceinline__ void issue_k_rows(Tile& T, const Rows& R, int ra, int rb) {
   if (WIDE) {  // positions 8 * blk + (n & 7): held by this lane or by the lane 8 further round its row of 16
-    const int xa = __shfl_xor(ra, 8), xb = __shfl_xor(rb, 8);
+    const int xa = lane_xor8(ra), xb = lane_xor8(rb);
     const bool lo = R.n < 8;
     const int r[4] = {lo ? ra : xa, lo ? xa : ra, lo ? rb : xb, lo ? xb : rb};
 #pragma unroll
@@ -272,9 +282,9 @@ __device__ __forceinline__ void qk_phase(const Tile& T, const bf16x8 (&qreg)[4],
     const bool low = jg < 2;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const float u0 = (low ? s[0][i] : s[2][i]) + __shfl_xor(low ? s[2][i] : s[0][i], 40);
-      const float u1 = (low ? s[1][i] : s[3][i]) + __shfl_xor(low ? s[3][i] : s[1][i], 40);
-      const float x0 = __shfl_xor(u0, 8), x1 = __shfl_xor(u1, 8);
+      const float u0 = (low ? s[0][i] : s[2][i]) + lane_xor40(low ? s[2][i] : s[0][i]);
+      const float u1 = (low ? s[1][i] : s[3][i]) + lane_xor40(low ? s[3][i] : s[1][i]);
+      const float x0 = lane_xor8(u0), x1 = lane_xor8(u1);
       y[i] = n < 8 ? (low ? u0 : x0) * c2 : 0.f;
       y[4 + i] = n < 8 ? (low ? u1 : x1) * c2 : 0.f;
     }
