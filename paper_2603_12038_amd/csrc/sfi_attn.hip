@@ -69,8 +69,8 @@ struct Tile {
 
 // WIDE (the gather kernels, query groups of at most 8 heads): a K row's 256 bytes go out as two requests
 // for whole 128-byte lines instead of four for 64 bytes -- a compute unit's bandwidth is the requests it
-// keeps in flight times their size.  (The dense kernel stays with the plain layout: with one wave per
-// SIMD nothing hides the two rounds of lane exchanges below, and it measured 1-4 % slower.)  The operand layout gives a row of the matrix product to four lanes of 16 bytes, so
+// keeps in flight times their size.  (The dense kernel stays with the plain layout: it measured 1-4 % slower
+// with this one, whichever way the lanes exchange their halves.)  The operand layout gives a row of the matrix product to four lanes of 16 bytes, so
 // a row of the product is made half a K row: the tile is four blocks of 8 positions, product row
 // n = 8 * half + r of block blk is position 8 * blk + r, dims 64 * kb + 32 * half + 8 * jg .. + 8 in
 // step kb (two steps), and its column 8 * half' + head is the same half of q[head].  The halves
