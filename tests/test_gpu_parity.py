@@ -128,9 +128,10 @@ def test_fast_with_full_index_set_equals_dense(oracle, tiny):
         r2.close()
 
 
-@pytest.mark.parametrize("Hq,Hkv", [(2, 2), (10, 2), (16, 2), (16, 1), (32, 2)])
+@pytest.mark.parametrize("Hq,Hkv", [(2, 2), (10, 2), (14, 2), (16, 2), (18, 2), (12, 1), (16, 1), (32, 2)])
 def test_group_sizes(oracle, Hq, Hkv):
-    """G = 1, 5, 8, 16 (and 16 again with more KV heads)."""
+    """G = 1, 5, 7, 8, 9, 12, 16 (and 16 again with more KV heads): the fast-step kernels change their K-row
+    layout between groups of 8 and 9 heads."""
     w = syn.make_tiny(L0=777, steps=2, budget=50, recent=32, n_support=8, B=1, Hq=Hq, Hkv=Hkv)
     r = Runner(w)
     try:
