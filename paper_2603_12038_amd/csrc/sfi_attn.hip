@@ -67,7 +67,7 @@ struct Tile {
   uint4 v[8];          // V rows 4*jg + i of block A (i < 4) and block B (i >= 4), dims 8n .. 8n+7
 };
 
-// WIDE (the gather kernels, query groups of at most 8 heads): a K row's 256 bytes go out as two requests
+// WIDE (the gather and compact kernels, query groups of at most 8 heads): a K row's 256 bytes go out as two requests
 // for whole 128-byte lines instead of four for 64 bytes -- a compute unit's bandwidth is the requests it
 // keeps in flight times their size.  (The dense kernel stays with the plain layout: it measured 1-4 % slower
 // with this one, whichever way the lanes exchange their halves.)  The operand layout gives a row of the matrix product to four lanes of 16 bytes, so
@@ -1060,7 +1060,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(con
 // index is read: a wave's first tile is on its way before any scalar of the step has arrived.
 // Tiles never straddle the two segments: the compact segment ends with a ragged tile of its own.
 // ------------------------------------------------------------------------------------------------
-template <bool PAGED>  // PAGED: the recent window is read from a paged cache (the compact buffers are always flat)
+template <bool PAGED, bool WIDE>  // PAGED: the recent window is read from a paged cache (the compact buffers are always flat)
 __global__ __launch_bounds__(kAttnThreads, PAGED ? 2 : 3) void attn_compact_kernel(const AttnArgs a) {
   const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   if (a.is_slow != nullptr && a.is_slow[b] != 0) return;
@@ -1076,7 +1076,7 @@ __global__ __launch_bounds__(kAttnThreads, PAGED ? 2 : 3) void attn_compact_kern
   Rc.Kb = reinterpret_cast<const char*>(a.Kc + b * a.c_sb + h * a.c_sh);
   Rc.Vb = reinterpret_cast<const char*>(a.Vc + b * a.c_sb + h * a.c_sh);
   Rc.k_st = Rc.v_st = kHeadDim * 2u;
-  Rc.k_lane = jg * 16;
+  Rc.k_lane = k_lane_of<WIDE>(jg, n);
   Rc.v_lane = n * 16;
   Rc.jg = jg;
   Rc.n = n;
@@ -1088,9 +1088,9 @@ __global__ __launch_bounds__(kAttnThreads, PAGED ? 2 : 3) void attn_compact_kern
 
   Tile T;
   const bool spec = first * kTile < a.c_rows;  // almost every wave's tile lies in the compact segment
-  if (spec) issue_affine(T, Rc, first * kTile, a.c_rows - 1);
+  if (spec) issue_affine<WIDE>(T, Rc, first * kTile, a.c_rows - 1);
   bf16x8 qreg[4];
-  load_q(qreg, a.q, head0, G, jg, n);
+  load_q<WIDE>(qreg, a.q, head0, G, jg, n);
   int bad = 0;
   const int L_in = a.ctx_len[b], nSel0 = a.n_sel[bh], rs_in = a.recent_start[b];  // one round trip for the three
   const int L = guarded_len(L_in, a.len_cap, bad);
@@ -1117,21 +1117,21 @@ __global__ __launch_bounds__(kAttnThreads, PAGED ? 2 : 3) void attn_compact_kern
   int pra_n = 0, prb_n = 0;  // PAGED: physical rows of the recent tile whose K half was issued last
   auto issue_k_tile = [&](int t) {
     if (t < Tc) {
-      issue_k_affine(T, Rc, t * kTile, a.c_rows - 1);
+      issue_k_affine<WIDE>(T, Rc, t * kTile, a.c_rows - 1);
     } else if (PAGED) {
       const Pages P = pages_of(a, b, L);
       const int ra = min(rs + (t - Tc) * kTile + n, L - 1), rb = min(rs + (t - Tc) * kTile + 16 + n, L - 1);
       pra_n = P.phys(ra, P.page_of(ra), bad);
       prb_n = P.phys(rb, P.page_of(rb), bad);
-      issue_k_rows<uint64_t>(T, R, pra_n, prb_n);
+      issue_k_rows<uint64_t, WIDE>(T, R, pra_n, prb_n);
     } else {
-      issue_k_affine(T, R, rs + (t - Tc) * kTile, L - 1);
+      issue_k_affine<WIDE>(T, R, rs + (t - Tc) * kTile, L - 1);
     }
   };
   auto issue_v_tile = [&](int t) {
-    if (t < Tc) issue_v_affine(T, Rc, t * kTile, a.c_rows - 1);
-    else if (PAGED) issue_v_rows<uint64_t>(T, R, pra_n, prb_n);
-    else issue_v_affine(T, R, rs + (t - Tc) * kTile, L - 1);
+    if (t < Tc) issue_v_affine<WIDE>(T, Rc, t * kTile, a.c_rows - 1);
+    else if (PAGED) issue_v_rows<uint64_t, WIDE>(T, R, pra_n, prb_n);
+    else issue_v_affine<WIDE>(T, R, rs + (t - Tc) * kTile, L - 1);
   };
   const int K = first < nT ? (nT - first + step - 1) / step : 0;
   if (K > 0 && !(spec && first < Tc)) {  // the first tile is not the compact tile requested up front
@@ -1144,9 +1144,9 @@ __global__ __launch_bounds__(kAttnThreads, PAGED ? 2 : 3) void attn_compact_kern
     const int p0 = (t < Tc ? t : t - Tc) * kTile;
     const int N = t < Tc ? Nc : Nr;
     float y[8];
-    qk_phase(T, qreg, a.scale_log2, y);
+    qk_phase<WIDE>(T, qreg, a.scale_log2, y);
     issue_k_tile(t + step);
-    if (p0 + kTile > N) mask_tail(T, y, jg, p0, N);
+    if (p0 + kTile > N) mask_tail<true, WIDE>(T, y, jg, p0, N);
     bf16x8 a_hi, a_lo;
     softmax_phase(y, acc, m_run, l_run, jg, a_hi, a_lo);
     pv_phase(T, a_hi, a_lo, acc);
@@ -1302,10 +1302,14 @@ hipError_t launch_attn_dense(const AttnArgs& a, int B, int n_slots, hipStream_t 
   return hipGetLastError();
 }
 hipError_t launch_attn_compact(const AttnArgs& a, int B, int n_slots, hipStream_t s) {
-  if (a.table != nullptr)
-    hipLaunchKernelGGL(attn_compact_kernel<true>, dim3(n_slots, a.Hkv, B), dim3(kAttnThreads), 0, s, a);
-  else
-    hipLaunchKernelGGL(attn_compact_kernel<false>, dim3(n_slots, a.Hkv, B), dim3(kAttnThreads), 0, s, a);
+  const dim3 grid(n_slots, a.Hkv, B);
+  if (a.G <= 8) {
+    if (a.table != nullptr) hipLaunchKernelGGL((attn_compact_kernel<true, true>), grid, dim3(kAttnThreads), 0, s, a);
+    else hipLaunchKernelGGL((attn_compact_kernel<false, true>), grid, dim3(kAttnThreads), 0, s, a);
+  } else {
+    if (a.table != nullptr) hipLaunchKernelGGL((attn_compact_kernel<true, false>), grid, dim3(kAttnThreads), 0, s, a);
+    else hipLaunchKernelGGL((attn_compact_kernel<false, false>), grid, dim3(kAttnThreads), 0, s, a);
+  }
   return hipGetLastError();
 }
 hipError_t launch_reorg(const ReorgArgs& a, int B, int rows, hipStream_t s) {
