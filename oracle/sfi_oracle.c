@@ -24,6 +24,12 @@
  *                  the slow/fast indicator g_t of one request (Sec. 3.1 "Training-free
  *                  trigger policy", Eq. trigger, with the forced refresh after T_max fast
  *                  steps; Algorithm 1: g_0 = 1).
+ *   sfio_advance   the state update between two decode steps: the context grows by one row and the
+ *                  recent window slides with it (Algorithm 1, "Update I_recent"; Sec. 3.1 "Fast step").
+ *   sfio_decode_loop
+ *                  Algorithm 1 for a batch of requests with a scripted indicator g_t: slow steps attend
+ *                  densely and refresh I_sel through the Selector, fast steps attend over
+ *                  I_sink U I_recent U I_sel and keep I_sel (Eq. freeze_sel).
  *   sfio_selector_from_logits / sfio_selector
  *                  Algorithm 2 step by step: allowed set J (Eq. allowed_set),
  *                  evidence p, mu, f (Eqs. selector_pt, selector_mu, selector_f),
@@ -39,7 +45,11 @@
  *   - the G query heads that share one KV head play the role of the W window queries
  *     of Eq. selector_mu (one evidence vector per KV head);
  *   - Top-K orders by (-score, index): equal scores -> lower index first; the selected
- *     set is emitted ascending by index and padded with -1.
+ *     set is emitted ascending by index and padded with -1;
+ *   - a window of W > 1 queries (Eq. window_logits) is handed in as W * G vectors per KV head; a window
+ *     query that sits before the end of the context sees only the rows up to its own ("masked attention
+ *     logit"): its softmax runs over the part of J it sees and it contributes p = 0 elsewhere, while the
+ *     mean of Eq. selector_mu still divides by the full number of window vectors.
  *
  * Pins: tests/test_oracle_*.py (brute force on tiny inputs, closed forms, invariants,
  * library special cases).  The hyper-parameters gamma, beta, p, eta, T and the Soft-NMS
@@ -196,6 +206,8 @@ static int cmp_i32(const void* a, const void* b) {
  * Selector from logits (Algorithm 2).
  *   logits : [B, Hq, ld_l]   l_g(j) for j < ctx_len[b]
  *   knorm  : [B, Hkv, ld_l]  ||k_h(j)||_2 (mode 1 only; may be NULL in mode 0)
+ *   vis    : [B, Hq] or NULL: vector (b, g) sees rows [0, vis[b][g]) only (a window query under the
+ *            causal mask, Eq. window_logits); NULL: every vector sees the whole context
  *   sel_idx: [B, Hkv, budget] out, ascending, padded with -1;  n_sel: [B, Hkv] out
  *   z_out  : [B, Hkv, ld_z]  optional: final ranking score per absolute position j
  *            (-inf outside J)
@@ -203,7 +215,7 @@ static int cmp_i32(const void* a, const void* b) {
  *            (0 outside J); dbg_lambda: optional [B, Hkv].
  */
 int sfio_selector_from_logits(const sfio_cfg* c, const double* logits, const double* knorm, int64_t ld_l,
-                              const int32_t* ctx_len, int32_t budget, int32_t* sel_idx, int32_t* n_sel,
+                              const int32_t* vis, const int32_t* ctx_len, int32_t budget, int32_t* sel_idx, int32_t* n_sel,
                               double* z_out, int64_t ld_z, double* dbg_f, double* dbg_r, double* dbg_s,
                               double* dbg_zbase, double* dbg_znms, double* dbg_lambda) {
   const int G = c->Hq / c->Hkv;
@@ -236,12 +248,15 @@ int sfio_selector_from_logits(const sfio_cfg* c, const double* logits, const dou
       /* Eq. selector_pt: p_g = softmax over J;  Eq. selector_mu: mu = (1/G) sum_g p_g^alpha */
       for (int gg = 0; gg < G; ++gg) {
         const double* l = logits + ((int64_t)b * c->Hq + h * G + gg) * ld_l;
+        /* the part of J this vector sees: all of it, or up to its own row under the causal mask */
+        int64_t j_end = j_hi;
+        if (vis && vis[(int64_t)b * c->Hq + h * G + gg] < j_end) j_end = vis[(int64_t)b * c->Hq + h * G + gg];
         double M = -INFINITY;
-        for (int64_t j = j_lo; j < j_hi; ++j)
+        for (int64_t j = j_lo; j < j_end; ++j)
           if (l[j] > M) M = l[j];
         double Z = 0.0;
-        for (int64_t j = j_lo; j < j_hi; ++j) Z += exp(l[j] - M);
-        for (int64_t j = j_lo; j < j_hi; ++j) {
+        for (int64_t j = j_lo; j < j_end; ++j) Z += exp(l[j] - M);
+        for (int64_t j = j_lo; j < j_end; ++j) {
           double p = exp(l[j] - M) / Z;
           mu[j - j_lo] += pow(p, c->alpha) / (double)G;
         }
@@ -362,7 +377,7 @@ int sfio_selector_from_logits(const sfio_cfg* c, const double* logits, const dou
 }
 
 /* Selector from q and K: computes the logits and (mode 1) key norms, then Algorithm 2. */
-int sfio_selector(const sfio_cfg* c, const uint16_t* q, const uint16_t* K, const int32_t* ctx_len,
+int sfio_selector(const sfio_cfg* c, const uint16_t* q, const uint16_t* K, const int32_t* vis, const int32_t* ctx_len,
                   int32_t budget, int32_t* sel_idx, int32_t* n_sel, double* z_out, int64_t ld_z) {
   int64_t ld = 1;
   for (int b = 0; b < c->B; ++b)
@@ -382,7 +397,7 @@ int sfio_selector(const sfio_cfg* c, const uint16_t* q, const uint16_t* K, const
           knorm[((int64_t)b * c->Hkv + h) * ld + j] = sqrt(s);
         }
   }
-  int rc = sfio_selector_from_logits(c, logits, knorm, ld, ctx_len, budget, sel_idx, n_sel, z_out, ld_z, NULL,
+  int rc = sfio_selector_from_logits(c, logits, knorm, ld, vis, ctx_len, budget, sel_idx, n_sel, z_out, ld_z, NULL,
                                      NULL, NULL, NULL, NULL, NULL);
   free(logits);
   free(knorm);
@@ -433,6 +448,63 @@ int sfio_trigger_schedule(const int32_t* x, int32_t n_steps, const int32_t* trig
     fast_run = slow ? 0 : fast_run + 1;
   }
   return 0;
+}
+
+/* State update between two decode steps (Algorithm 1, "Update I_recent"): the new token's row joins the cache,
+ * L <- L + 1, and the recent window slides: I_recent = [max(n_sink, L - recent), L). */
+int sfio_advance(const sfio_cfg* c, int32_t* ctx_len, int32_t* recent_start) {
+  for (int b = 0; b < c->B; ++b) {
+    const int32_t L = ctx_len[b] + 1;
+    ctx_len[b] = L;
+    recent_start[b] = L - c->recent > c->n_sink ? L - c->recent : c->n_sink;
+  }
+  return 0;
+}
+
+/*
+ * Algorithm 1 for B requests over n_steps decode steps with a scripted indicator g[t][b] (1 = slow step).
+ *   q        : [n_steps, B, Hq, d]  the query of every step
+ *   K, V     : caches that already hold the rows of every step (row L0[b] + t - 1 is step t's own token)
+ *   ctx_len, recent_start : [B] in / out: the state before step 0, left as after the last step
+ *   sel_idx, n_sel : [B, Hkv, budget], [B, Hkv] in / out: I_sel before step 0 (n_sel = 0: empty), left as after
+ *                    the last step
+ *   out      : [n_steps, B, Hq, d]
+ *   sel_hist : optional [n_steps, B, Hkv, budget], nsel_hist optional [n_steps, B, Hkv]: I_sel after each step
+ *   ctx_hist, rs_hist : optional [n_steps, B]: the state each step ran on
+ * Per step and request: fast -> attention over I_sink U I_recent U I_sel, I_sel kept (Eq. freeze_sel);
+ * slow -> dense attention over the prefix, I_sel <- Selector on J (Algorithm 2); then the state update.
+ */
+int sfio_decode_loop(const sfio_cfg* c, const uint16_t* q, const uint16_t* K, const uint16_t* V, int32_t n_steps,
+                     const uint8_t* g, int32_t budget, int32_t* ctx_len, int32_t* recent_start, int32_t* sel_idx,
+                     int32_t* n_sel, double* out, int32_t* sel_hist, int32_t* nsel_hist, int32_t* ctx_hist,
+                     int32_t* rs_hist) {
+  const int64_t q_step = (int64_t)c->B * c->Hq * c->d;
+  int rc = 0;
+  for (int32_t t = 0; t < n_steps; ++t) {
+    for (int b = 0; b < c->B; ++b) {
+      /* request b on its own: a batch of one at the request's offsets */
+      sfio_cfg c1 = *c;
+      c1.B = 1;
+      const uint16_t* qb = q + t * q_step + (int64_t)b * c->Hq * c->d;
+      const uint16_t* Kb = K + b * c->k_stride_b;
+      const uint16_t* Vb = V + b * c->v_stride_b;
+      double* ob = out + t * q_step + (int64_t)b * c->Hq * c->d;
+      int32_t* sel_b = sel_idx + (int64_t)b * c->Hkv * budget;
+      int32_t* nsel_b = n_sel + (int64_t)b * c->Hkv;
+      if (ctx_hist) ctx_hist[(int64_t)t * c->B + b] = ctx_len[b];
+      if (rs_hist) rs_hist[(int64_t)t * c->B + b] = recent_start[b];
+      if (g[(int64_t)t * c->B + b]) {
+        rc |= sfio_dense(&c1, qb, Kb, Vb, ctx_len + b, ob);
+        rc |= sfio_selector(&c1, qb, Kb, NULL, ctx_len + b, budget, sel_b, nsel_b, NULL, 0);
+      } else {
+        rc |= sfio_sparse(&c1, qb, Kb, Vb, sel_b, nsel_b, budget, recent_start + b, ctx_len + b, ob);
+      }
+    }
+    if (sel_hist) memcpy(sel_hist + (int64_t)t * c->B * c->Hkv * budget, sel_idx, sizeof(int32_t) * (size_t)c->B * c->Hkv * budget);
+    if (nsel_hist) memcpy(nsel_hist + (int64_t)t * c->B * c->Hkv, n_sel, sizeof(int32_t) * (size_t)c->B * c->Hkv);
+    sfio_advance(c, ctx_len, recent_start);
+  }
+  return rc;
 }
 
 int sfio_num_threads(void) {

@@ -52,11 +52,14 @@ class SelectorParams:
 
 
 def lib() -> C.CDLL:
+    """The compiled oracle.  SFI_ORACLE_LIB names another build of sfi_oracle.c to load instead (the mutation
+    test runs the pins against deliberately broken copies this way)."""
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB):
+        path = os.environ.get("SFI_ORACLE_LIB") or LIB
+        if path == LIB and not os.path.exists(LIB):
             build_oracle()
-        _lib = C.CDLL(LIB)
+        _lib = C.CDLL(path)
         _lib.sfio_num_threads.restype = C.c_int
     return _lib
 
@@ -161,8 +164,9 @@ def trigger_schedule(tokens, trigger_ids, t_max: int) -> np.ndarray:
 
 def selector_from_logits(lg: np.ndarray, ctx_len, Hkv: int, budget: int, n_sink: int, recent: int,
                          sp: Optional[SelectorParams] = None, knorm: Optional[np.ndarray] = None,
-                         debug: bool = False):
-    """Algorithm 2 on given logits float64 [B, Hq, ld].  Returns (sel_idx, n_sel, z[, dbg dict])."""
+                         debug: bool = False, vis=None):
+    """Algorithm 2 on given logits float64 [B, Hq, ld].  Returns (sel_idx, n_sel, z[, dbg dict]).
+    vis: optional int32 [B, Hq]: vector (b, g) sees rows [0, vis[b, g]) only (causal mask of a window query)."""
     sp = sp or SelectorParams()
     lg = np.ascontiguousarray(lg, dtype=np.float64)
     B, Hq, ld = lg.shape
@@ -181,8 +185,9 @@ def selector_from_logits(lg: np.ndarray, ctx_len, Hkv: int, budget: int, n_sink:
         dbg["lambda"] = np.zeros((B, Hkv), dtype=np.float64)
     c = _cfg(B, Hq, Hkv, 1, n_sink, recent, 1.0, sp=sp)
     sel_c = np.ascontiguousarray(sel[:, :, :budget]) if budget > 0 else sel
+    vis = None if vis is None else _i32(vis).reshape(B, Hq)
     rc = lib().sfio_selector_from_logits(
-        C.byref(c), _p(lg), _p(knorm), C.c_int64(ld), _p(ctx_len), C.c_int32(budget), _p(sel_c), _p(nsel),
+        C.byref(c), _p(lg), _p(knorm), C.c_int64(ld), _p(vis), _p(ctx_len), C.c_int32(budget), _p(sel_c), _p(nsel),
         _p(z), C.c_int64(ld), _p(dbg.get("f")), _p(dbg.get("r")), _p(dbg.get("s")), _p(dbg.get("zbase")),
         _p(dbg.get("znms")), _p(dbg.get("lambda")))
     assert rc == 0
@@ -192,8 +197,9 @@ def selector_from_logits(lg: np.ndarray, ctx_len, Hkv: int, budget: int, n_sink:
 
 
 def selector(q, K, ctx_len, budget: int, n_sink: int, recent: int, scale=None,
-             sp: Optional[SelectorParams] = None) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
-    """Slow-step Selector from q and K: (sel_idx int32 [B,Hkv,budget], n_sel int32 [B,Hkv], z float64 [B,Hkv,ld])."""
+             sp: Optional[SelectorParams] = None, vis=None) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Slow-step Selector from q and K: (sel_idx int32 [B,Hkv,budget], n_sel int32 [B,Hkv], z float64 [B,Hkv,ld]).
+    vis: optional int32 [B, Hq]: vector (b, g) sees rows [0, vis[b, g]) only (causal mask of a window query)."""
     sp = sp or SelectorParams()
     B, Hq, d = q.shape
     Hkv = K.shape[1]
@@ -205,9 +211,49 @@ def selector(q, K, ctx_len, budget: int, n_sink: int, recent: int, scale=None,
     c = _cfg(B, Hq, Hkv, d, n_sink, recent, scale, K=K, sp=sp)
     q = np.ascontiguousarray(q)
     sel_c = np.ascontiguousarray(sel[:, :, :budget]) if budget > 0 else sel
-    rc = lib().sfio_selector(C.byref(c), _p(q), _p(K), _p(ctx_len), C.c_int32(budget), _p(sel_c), _p(nsel),
+    vis = None if vis is None else _i32(vis).reshape(B, Hq)
+    rc = lib().sfio_selector(C.byref(c), _p(q), _p(K), _p(vis), _p(ctx_len), C.c_int32(budget), _p(sel_c), _p(nsel),
                              _p(z), C.c_int64(ld))
     assert rc == 0
     if budget > 0:
         sel = sel_c
     return sel, nsel, z
+
+
+def advance(ctx_len, recent_start, n_sink: int, recent: int) -> Tuple[np.ndarray, np.ndarray]:
+    """State update between two decode steps: returns the new (ctx_len, recent_start), int32 [B]."""
+    ctx_len, recent_start = _i32(ctx_len).copy(), _i32(recent_start).copy()
+    c = _cfg(ctx_len.shape[0], 1, 1, 1, n_sink, recent, 1.0)
+    rc = lib().sfio_advance(C.byref(c), _p(ctx_len), _p(recent_start))
+    assert rc == 0
+    return ctx_len, recent_start
+
+
+def decode_loop(q_steps: np.ndarray, K, V, ctx_len, recent_start, g, budget: int, n_sink: int, recent: int,
+                sel_idx=None, n_sel=None, scale=None, sp: Optional[SelectorParams] = None) -> dict:
+    """Algorithm 1 with a scripted slow/fast indicator g uint8 [n_steps, B] over q_steps uint16 [n_steps, B, Hq, d].
+    ctx_len / recent_start: the state before step 0.  sel_idx / n_sel: I_sel before step 0 (default: empty).
+    Returns a dict: out float64 [n_steps, B, Hq, d]; sel_hist, nsel_hist (I_sel after each step); ctx_hist, rs_hist
+    (the state each step ran on); ctx_len, recent_start, sel_idx, n_sel (the state after the last step)."""
+    sp = sp or SelectorParams()
+    q_steps = np.ascontiguousarray(q_steps)
+    T, B, Hq, d = q_steps.shape
+    Hkv = K.shape[1]
+    g = np.ascontiguousarray(g, dtype=np.uint8).reshape(T, B)
+    ctx_len, recent_start = _i32(ctx_len).copy(), _i32(recent_start).copy()
+    bw = max(budget, 1)
+    sel = np.full((B, Hkv, bw), -1, np.int32) if sel_idx is None else np.ascontiguousarray(sel_idx, np.int32).copy()
+    nsel = np.zeros((B, Hkv), np.int32) if n_sel is None else _i32(n_sel).copy()
+    assert sel.shape == (B, Hkv, bw) and budget > 0
+    out = np.zeros((T, B, Hq, d), np.float64)
+    sel_hist = np.zeros((T, B, Hkv, bw), np.int32)
+    nsel_hist = np.zeros((T, B, Hkv), np.int32)
+    ctx_hist, rs_hist = np.zeros((T, B), np.int32), np.zeros((T, B), np.int32)
+    c = _cfg(B, Hq, Hkv, d, n_sink, recent, scale, K=K, V=V, sp=sp)
+    rc = lib().sfio_decode_loop(C.byref(c), _p(q_steps), _p(K), _p(V), C.c_int32(T), _p(g), C.c_int32(budget),
+                                _p(ctx_len), _p(recent_start), _p(sel), _p(nsel), _p(out), _p(sel_hist), _p(nsel_hist),
+                                _p(ctx_hist), _p(rs_hist))
+    if rc != 0:
+        raise ValueError("decode loop: a selected index left the context")
+    return dict(out=out, sel_hist=sel_hist, nsel_hist=nsel_hist, ctx_hist=ctx_hist, rs_hist=rs_hist, ctx_len=ctx_len,
+                recent_start=recent_start, sel_idx=sel, n_sel=nsel)

@@ -286,6 +286,113 @@ def test_cross_head_properties(oracle):
         np.testing.assert_array_equal(seli[0, h], seli[0, 0])
 
 
+@pytest.mark.parametrize("p", [2.0, 3.0, 1.5])
+def test_position_decay_exponent(oracle, p):
+    """Decay factor alone (gamma = eta = 0): r(j) ~ exp(-beta u(j)^p) with u = (j - j_min) / (j_max - j_min + eps)
+    (Eqs. selector_u, selector_prior_pos), so for ANY two positions
+    log r(j) - log r(j') = -beta (u(j)^p - u(j')^p).  Checked on pairs far apart, where u^p and u differ most."""
+    L, n_sink, R, beta = 75, 4, 7, 2.5
+    lg, kn = _rand_problem(55, L=L)
+    nJ = L - R - n_sink
+    _, _, _, dbg = run(oracle, lg, L, 2, 8, n_sink, R, sp=_mode1(gamma=0, beta=beta, p=p, eta=0), knorm=kn, debug=True)
+    r = dbg["r"][0, 1, n_sink:L - R]
+    u = np.arange(nJ) / (nJ - 1 + EPS)
+    for a, b in [(0, nJ - 1), (3, 40), (17, 60), (nJ // 2, nJ - 2), (1, 2)]:
+        np.testing.assert_allclose(math.log(r[a]) - math.log(r[b]), -beta * (u[a] ** p - u[b] ** p), rtol=1e-11, atol=1e-13)
+    # the first position has u = 0 whatever p is; the last has u^p = 1 up to eps: r(last) / r(first) = exp(-beta)
+    np.testing.assert_allclose(r[-1] / r[0], math.exp(-beta * (1.0 / (1.0 + EPS / (nJ - 1))) ** p), rtol=1e-12)
+    assert abs(r.sum() - 1.0) < 1e-12
+
+
+def test_position_prior_both_factors_closed_form(oracle):
+    """Both position factors and the key-norm factor at once against the equations written out with numpy
+    (Eqs. selector_prior_kn, selector_prior_pos, selector_r)."""
+    L, n_sink, R = 64, 3, 5
+    lg, kn = _rand_problem(56, L=L)
+    nJ = L - R - n_sink
+    g, beta, p, eta = 0.7, 1.3, 3.0, 0.4
+    _, _, _, dbg = run(oracle, lg, L, 2, 8, n_sink, R, sp=_mode1(gamma=g, beta=beta, p=p, eta=eta), knorm=kn, debug=True)
+    u = np.arange(nJ) / (nJ - 1 + EPS)
+    for h in range(2):
+        w = (kn[0, h, n_sink:L - R] + EPS) ** (-g) * np.exp(-beta * u ** p) * (1.0 - u + EPS) ** eta
+        np.testing.assert_allclose(dbg["r"][0, h, n_sink:L - R], w / w.sum(), rtol=1e-12)
+
+
+def test_cross_head_responsibility_floor(oracle):
+    """Eq. head_mutex: z_adj = z_nms + alpha_cross log max(r_h, eps).  Two KV heads, G = 1, prior and Soft-NMS off,
+    so z_nms = log(p_h + eps) with p_h the head's softmax over J.  At one position head 0 carries almost all of
+    its mass and head 1 almost none, so that (z_0 - z_1) / T exceeds ln(1 / eps): head 1's responsibility
+    e^{-(z_0 - z_1)/T} / (1 + ...) is below eps and its adjustment must equal alpha_cross * ln(eps) exactly.
+    At a second position the gap stays just inside ln(1 / eps): no floor, adjustment = alpha_cross * log r_h."""
+    L, n_sink, R, T, ac = 40, 2, 3, 0.5, 0.35
+    nJ = L - R - n_sink
+    J = slice(n_sink, L - R)
+    lg = np.zeros((1, 2, L))
+    lg[0, 0, 10] = 18.0     # head 0: p(10) ~ 1
+    lg[0, 1, 10] = -18.0    # head 1: p(10) ~ e^-18 / nJ, far below eps -> z_1 = log(eps-ish)
+    lg[0, 0, 20] = 12.0     # p_0(20) = e^-6: a mild gap to head 1's 1 / |J| there
+    kn = np.ones((1, 2, L))
+    sp = _mode1(lambda_clip=0.0, alpha_soft=0.0, alpha_cross=ac, temp=T, nms_radius=0)
+    _, _, z, dbg = run(oracle, lg, L, 2, 4, n_sink, R, sp=sp, knorm=kn, debug=True)
+    p0, p1 = softmax(lg[0, 0, J]), softmax(lg[0, 1, J])
+    z0, z1 = np.log(p0 + EPS), np.log(p1 + EPS)
+    np.testing.assert_allclose(dbg["znms"][0, 0, J], z0, rtol=1e-13, atol=1e-14)
+    np.testing.assert_allclose(dbg["znms"][0, 1, J], z1, rtol=1e-13, atol=1e-14)
+    i = 10 - n_sink
+    gap = (z0[i] - z1[i]) / T
+    assert gap > math.log(1.0 / EPS) + 5.0                       # the floor is what decides here
+    np.testing.assert_allclose(z[0, 1, 10] - z1[i], ac * math.log(EPS), rtol=1e-13)
+    np.testing.assert_allclose(z[0, 0, 10] - z0[i], ac * math.log(1.0 / (1.0 + math.exp(-gap))), rtol=1e-9, atol=1e-14)
+    # without the floor the adjustment would have been alpha_cross * (-gap - log(1 + e^-gap)): far lower
+    assert ac * (-gap) < ac * math.log(EPS) - 1.0
+    k = 20 - n_sink                                              # a position where no head drops below the floor
+    gap2 = (z1[k] - z0[k]) / T                                   # here head 1 leads
+    assert 0 < gap2 < math.log(1.0 / EPS) - 5.0
+    np.testing.assert_allclose(z[0, 0, 20] - z0[k], ac * (-gap2 - math.log1p(math.exp(-gap2))), rtol=1e-12)
+    np.testing.assert_allclose(z[0, 1, 20] - z1[k], -ac * math.log1p(math.exp(-gap2)), rtol=1e-9)
+    # Either side of the floor, planted exactly.  Head 0 uniform over J (z_0 = log(1 / |J| + eps) everywhere); head 1
+    # uniform except one low logit x at position 12, chosen so that its responsibility there,
+    # 1 / (1 + e^{(z_0 - z_1) / T}), is 2 eps (untouched by the floor) or eps / 2 (lifted to eps).
+    for resp, want in [(2.0 * EPS, 2.0 * EPS), (0.5 * EPS, EPS)]:
+        g2 = math.log((1.0 - resp) / resp) * T                   # the z_0 - z_1 that gives head 1 this responsibility
+        target = (1.0 / nJ + EPS) * math.exp(-g2) - EPS          # p_1(12) with log(p_1 + eps) = z_0 - g2
+        assert target > 0
+        x = math.log(target * (nJ - 1) / (1.0 - target))         # p_1(12) = e^x / (|J| - 1 + e^x)
+        lg2 = np.zeros((1, 2, L))
+        lg2[0, 1, 12] = x
+        _, _, zz, dd = run(oracle, lg2, L, 2, 4, n_sink, R, sp=sp, knorm=kn, debug=True)
+        adj = zz[0, 1, 12] - dd["znms"][0, 1, 12]
+        np.testing.assert_allclose(adj, ac * math.log(want), rtol=1e-7)
+
+
+def test_degenerate_prior_and_fusion_cases(oracle):
+    """Where the epsilons and guards of Sec. 3.2 decide: |J| = 1 (u = 0 / eps, Eq. selector_u), f = r (the
+    denominator of Eq. selector_lambda_closed vanishes: lambda* = 0) and an unclipped lambda* below 0."""
+    kn1 = np.full((1, 1, 20), 3.0)
+    # |J| = 1: the only position has u = 0, r = s = f = 1, z = log(1 + eps); nothing is NaN
+    lg = syn.rng_for(57, 1).standard_normal((1, 2, 20))
+    sel, nsel, z, dbg = run(oracle, lg[:, :, :9], 9, 1, 3, 4, 4, sp=_mode1(), knorm=kn1[:, :, :9], debug=True)
+    assert nsel[0, 0] == 1 and sel[0, 0, 0] == 4
+    assert dbg["r"][0, 0, 4] == 1.0 and dbg["f"][0, 0, 4] == 1.0 and dbg["s"][0, 0, 4] == 1.0
+    np.testing.assert_allclose(z[0, 0, 4], math.log(1.0 + EPS), rtol=1e-12)
+    # f = r = uniform: denominator 0 -> lambda* = 0, s = f, everything finite
+    lgu = np.zeros((1, 2, 20))
+    _, _, zu, du = run(oracle, lgu, 20, 1, 3, 4, 4, sp=_mode1(gamma=0, beta=0, eta=0, lambda_clip=1.0), knorm=kn1, debug=True)
+    assert du["lambda"][0, 0] == 0.0 and np.isfinite(zu[0, 0, 4:16]).all()
+    np.testing.assert_allclose(du["s"][0, 0, 4:16], 1.0 / 12, rtol=1e-14)
+    # f mildly peaked, r sharply peaked at the same position: |f|^2 < f.r, so the unclipped minimiser is negative
+    # and lambda* = 0 (Eq. selector_lambda_closed clips to [0, lambda_clip])
+    lgp = np.zeros((1, 2, 20))
+    lgp[0, :, 8] = 0.3
+    knp = np.full((1, 1, 20), 50.0)
+    knp[0, 0, 8] = 0.5
+    _, _, _, dp = run(oracle, lgp, 20, 1, 3, 4, 4, sp=_mode1(gamma=2.0, beta=0, eta=0, lambda_clip=1.0), knorm=knp, debug=True)
+    f, r = dp["f"][0, 0, 4:16], dp["r"][0, 0, 4:16]
+    assert (f * f).sum() < (f * r).sum()
+    assert dp["lambda"][0, 0] == 0.0
+    np.testing.assert_array_equal(dp["s"][0, 0, 4:16], f)
+
+
 def test_mode1_from_qk_uses_key_norms(oracle):
     """sfio_selector computes ||k||_2 from K: scaling one key row changes its prior mass as (norm)^-gamma."""
     w = syn.make_tiny(L0=200, steps=1, budget=8, recent=16, n_support=2)
