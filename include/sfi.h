@@ -24,8 +24,8 @@
  *   K, V     bf16, element (b, h, t, c) at  base + b*stride_b + h*stride_h + t*stride_t + c
  *            (strides in elements, given in sfi_config; a row of 128 elements is contiguous;
  *            row starts must be 16-byte aligned: stride_* multiples of 8, base 16-byte aligned).
- *   out      fp32  [B, Hq, 128] contiguous; with cfg.out_bf16 = 1 the same pointer (declared float* throughout)
- *            addresses bf16 [B, Hq, 128] instead.
+ *   out      fp32  [B, Hq, 128] contiguous, or with cfg.out_bf16 = 1 bf16 [B, Hq, 128] (hence void*);
+ *            16-byte aligned.
  *   sel_idx  int32 [B, Hkv, sel_stride]; n_sel int32 [B, Hkv].
  *   ctx_len, recent_start int32 [B].
  *
@@ -163,7 +163,7 @@ const char* sfi_strerror(int status);
  * row loads before ctx_len[b] has arrived.  0 <= ctx_len[b] <= max_len.
  */
 int sfi_slow_step(sfi_ctx* ctx, const void* q, const void* K, const void* V, const int32_t* ctx_len,
-                  int32_t max_len, int32_t budget, float* out, int32_t* sel_idx, int32_t* n_sel,
+                  int32_t max_len, int32_t budget, void* out, int32_t* sel_idx, int32_t* n_sel,
                   void* stream);
 
 /*
@@ -180,7 +180,7 @@ int sfi_slow_step(sfi_ctx* ctx, const void* q, const void* K, const void* V, con
  * The library creates no stream and no cross-stream dependency of its own.
  */
 int sfi_slow_attn(sfi_ctx* ctx, const void* q, const void* K, const void* V, const int32_t* ctx_len,
-                  int32_t max_len, float* out, void* stream);
+                  int32_t max_len, void* out, void* stream);
 int sfi_slow_select(sfi_ctx* ctx, const int32_t* ctx_len, int32_t max_len, int32_t budget, int32_t* sel_idx,
                     int32_t* n_sel, void* stream);
 
@@ -199,13 +199,13 @@ int sfi_slow_select(sfi_ctx* ctx, const int32_t* ctx_len, int32_t max_len, int32
  * output is written -- half the cache traffic, for callers whose prefill kernel has the outputs already.
  */
 int sfi_evidence_add(sfi_ctx* ctx, const void* q, const void* K, const void* V, const int32_t* ctx_len,
-                     int32_t max_len, float* out, int32_t first, void* stream);
+                     int32_t max_len, void* out, int32_t first, void* stream);
 int sfi_evidence_select(sfi_ctx* ctx, int32_t n_added, const int32_t* ctx_len, int32_t max_len, int32_t budget,
                         int32_t* sel_idx, int32_t* n_sel, void* stream);
 
 /* Dense attention only (the `out` of a slow step, no Selector).  Same arguments and meaning. */
 int sfi_dense_attn(sfi_ctx* ctx, const void* q, const void* K, const void* V, const int32_t* ctx_len,
-                   int32_t max_len, float* out, void* stream);
+                   int32_t max_len, void* out, void* stream);
 
 /*
  * Fast step (paper Algorithm 1 "Fast Step"):
@@ -219,7 +219,28 @@ int sfi_dense_attn(sfi_ctx* ctx, const void* q, const void* K, const void* V, co
  */
 int sfi_fast_step(sfi_ctx* ctx, const void* q, const void* K, const void* V, const int32_t* sel_idx,
                   const int32_t* n_sel, int32_t sel_stride, const int32_t* recent_start,
-                  const int32_t* ctx_len, float* out, void* stream);
+                  const int32_t* ctx_len, void* out, void* stream);
+
+/*
+ * The fast step for callers that cannot allocate device memory or hold a workspace: code under HIP graph
+ * capture that owns no buffers of its own, tight serving loops, harnesses that forbid hipMalloc.  Same result
+ * as sfi_fast_step on a context created from *cfg (HOST pointer; read during the call only), same argument
+ * meaning and preconditions; no sfi_ctx and no workspace are involved.  The split records and arrival counters
+ * of the in-kernel merge live in a file-scope device array of the library instead (4.2 MiB, held by every GPU
+ * the library runs on until the process ends), which sets the limits:
+ *   batch * n_q_heads <= 8192  and  batch * n_kv_heads <= 4096, else SFI_EUNSUPPORTED;
+ *   at most 8192 / (batch * n_q_heads) workgroups per (sequence, KV head): larger shapes run with a coarser split
+ *   than sfi_fast_step would pick (same result up to the rounding of the split merge);
+ *   flat caches only (cfg->page_size != 0: SFI_EUNSUPPORTED).
+ * Calls no allocating routine.  Every call on one GPU uses that GPU's one array: calls that overlap on a GPU
+ * (two streams, two threads' launches in flight together) race and give undefined outputs; calls on one stream,
+ * or otherwise ordered, are fine.  The counters are zeroed by a small kernel on `stream` in a device's first call
+ * and after a call whose launch failed; every completed launch leaves them at zero.  Device-side inputs out of
+ * range are clamped as everywhere, but not reported (there is no context whose status word could take the bits).
+ */
+int sfi_fast_step_static(const sfi_config* cfg, const void* q, const void* K, const void* V, const int32_t* sel_idx,
+                         const int32_t* n_sel, int32_t sel_stride, const int32_t* recent_start,
+                         const int32_t* ctx_len, void* out, void* stream);
 
 /*
  * Reorg (paper Sec. "Hiding Slow-step Overhead via Layer-wise Asynchronous Execution", Reorg_i, and
@@ -252,7 +273,7 @@ int sfi_reorg(sfi_ctx* ctx, const void* K, const void* V, const int32_t* sel_idx
 int sfi_fast_step_compact(sfi_ctx* ctx, const void* q, const void* Kc, const void* Vc, int64_t c_stride_b,
                           int64_t c_stride_h, int32_t c_rows, const int32_t* n_sel, int32_t sel_stride,
                           const void* K, const void* V, const int32_t* recent_start, const int32_t* ctx_len,
-                          float* out, void* stream);
+                          void* out, void* stream);
 
 /*
  * Ragged mix: sequence b takes a slow step if is_slow[b] != 0 (uint8, device) and a fast step
@@ -261,7 +282,7 @@ int sfi_fast_step_compact(sfi_ctx* ctx, const void* q, const void* Kc, const voi
  */
 int sfi_mixed_step(sfi_ctx* ctx, const void* q, const void* K, const void* V, const uint8_t* is_slow,
                    const int32_t* ctx_len, const int32_t* recent_start, int32_t max_len, int32_t budget,
-                   float* out, int32_t* sel_idx, int32_t* n_sel, void* stream);
+                   void* out, int32_t* sel_idx, int32_t* n_sel, void* stream);
 
 /*
  * Trigger policy on the device (paper Sec. "Training-free trigger policy", Eq. trigger, and the last lines

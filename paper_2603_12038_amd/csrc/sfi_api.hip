@@ -1,5 +1,6 @@
 // C-ABI of libsfi: argument checks, workspace carving, launch sequencing.  No arithmetic here.
 #include <math.h>
+#include <mutex>
 #include <new>
 #include <string.h>
 
@@ -176,12 +177,13 @@ void set_dense_bounds(const sfi_ctx* x, AttnArgs* a, int max_len) {
 // 3 tiles per wave; 33 sequences of 8 KV heads: 2 workgroups per pair instead of 1, 10 % faster.)
 // fast_tiles_per_wave > 0 overrides: 1 = one tile per wave, t > 1 = pipelined with about t tiles per
 // wave.
-int fast_splits_for(const sfi_ctx* x, int sel_stride, int* pipelined) {
+int fast_splits_for(const sfi_ctx* x, int sel_stride, int* pipelined, int max_splits = kMaxSplits) {
   const int rows = x->cfg.n_sink + sel_stride + x->cfg.recent;
   const int tiles = (rows + kTile - 1) / kTile;
   const int pairs = x->cfg.batch * x->cfg.n_kv_heads;
   int one = (tiles + kWaves - 1) / kWaves;
   if (one > kMaxSplits) one = kMaxSplits;
+  if (one > max_splits) one = max_splits;  // records the buffer has room for
   int s;
   if (x->fast_tiles_per_wave > 0)
     s = (tiles + kWaves * x->fast_tiles_per_wave - 1) / (kWaves * x->fast_tiles_per_wave);
@@ -240,6 +242,7 @@ void fill_attn(const sfi_ctx* x, AttnArgs* a, const void* q, const void* K, cons
   a->v_sb = c.v_stride_b; a->v_sh = c.v_stride_h; a->v_st = c.v_stride_t;
   a->ctx_len = ctx_len;
   a->part = x->ws.part;
+  a->slot_cap = kSlotCap;
   a->ld_pos = x->ws.ld_pos;
   a->Hq = c.n_q_heads; a->Hkv = c.n_kv_heads; a->G = x->G;
   a->n_sink = c.n_sink; a->recent = c.recent;
@@ -300,7 +303,7 @@ int run_selector(sfi_ctx* x, const SelArgs& sa, int max_len, hipStream_t st, boo
 }
 
 int check_common(const sfi_ctx* x, const void* q, const void* K, const void* V, const int32_t* ctx_len,
-                 const float* out) {
+                 const void* out) {
   if (x == nullptr || q == nullptr || K == nullptr || V == nullptr || ctx_len == nullptr || out == nullptr)
     return SFI_EINVAL;
   if (misaligned(q, 16) || misaligned(K, 16) || misaligned(V, 16) || misaligned(out, 16) || misaligned(ctx_len, 4))
@@ -432,7 +435,8 @@ const char* sfi_strerror(int status) {
 }
 
 int sfi_dense_attn(sfi_ctx* x, const void* q, const void* K, const void* V, const int32_t* ctx_len,
-                   int32_t max_len, float* out, void* stream) {
+                   int32_t max_len, void* out_, void* stream) {
+  float* out = (float*)out_;
   int rc = check_common(x, q, K, V, ctx_len, out);
   if (rc != SFI_OK) return rc;
   int ml;
@@ -482,8 +486,9 @@ int check_select(const sfi_ctx* x, const int32_t* ctx_len, int32_t budget, const
 }  // namespace
 
 int sfi_slow_step(sfi_ctx* x, const void* q, const void* K, const void* V, const int32_t* ctx_len,
-                  int32_t max_len, int32_t budget, float* out, int32_t* sel_idx, int32_t* n_sel,
+                  int32_t max_len, int32_t budget, void* out_, int32_t* sel_idx, int32_t* n_sel,
                   void* stream) {
+  float* out = (float*)out_;
   int rc = check_common(x, q, K, V, ctx_len, out);
   if (rc != SFI_OK) return rc;
   if ((rc = check_select(x, ctx_len, budget, sel_idx, n_sel)) != SFI_OK) return rc;
@@ -501,7 +506,8 @@ int sfi_slow_step(sfi_ctx* x, const void* q, const void* K, const void* V, const
 }
 
 int sfi_slow_attn(sfi_ctx* x, const void* q, const void* K, const void* V, const int32_t* ctx_len,
-                  int32_t max_len, float* out, void* stream) {
+                  int32_t max_len, void* out_, void* stream) {
+  float* out = (float*)out_;
   int rc = check_common(x, q, K, V, ctx_len, out);
   if (rc != SFI_OK) return rc;
   int ml;
@@ -523,7 +529,8 @@ int sfi_slow_select(sfi_ctx* x, const int32_t* ctx_len, int32_t max_len, int32_t
 }
 
 int sfi_evidence_add(sfi_ctx* x, const void* q, const void* K, const void* V, const int32_t* ctx_len,
-                     int32_t max_len, float* out, int32_t first, void* stream) {
+                     int32_t max_len, void* out_, int32_t first, void* stream) {
+  float* out = (float*)out_;
   // out == nullptr: evidence only -- V is not read (and may be null), no attention output is produced
   const bool evidence_only = out == nullptr;
   if (x == nullptr || q == nullptr || K == nullptr || ctx_len == nullptr || (!evidence_only && V == nullptr))
@@ -563,32 +570,131 @@ int sfi_evidence_select(sfi_ctx* x, int32_t n_added, const int32_t* ctx_len, int
   return run_selector(x, sa, ml, (hipStream_t)stream, true);
 }
 
-int sfi_fast_step(sfi_ctx* x, const void* q, const void* K, const void* V, const int32_t* sel_idx,
-                  const int32_t* n_sel, int32_t sel_stride, const int32_t* recent_start,
-                  const int32_t* ctx_len, float* out, void* stream) {
+namespace {
+// The fast step's launches on records / counters / status word given by the caller of this function: the
+// context's workspace (sfi_fast_step) or the library's static scratch (sfi_fast_step_static).  max_splits bounds
+// the workgroups per pair by the records the buffer has room for.
+int fast_step_on(sfi_ctx* x, const void* q, const void* K, const void* V, const int32_t* sel_idx, const int32_t* n_sel,
+                 int32_t sel_stride, const int32_t* recent_start, const int32_t* ctx_len, float* out, hipStream_t st,
+                 float* part, int slot_cap, uint32_t* arrive, int32_t* guard, const int32_t* one_word, int max_splits) {
+  AttnArgs a;
+  fill_attn(x, &a, q, K, V, ctx_len);
+  a.part = part;
+  a.slot_cap = slot_cap;
+  a.guard = guard;
+  a.recent_start = recent_start;
+  // an index list of width 0: the pipelined kernel still reads one word where the list would start
+  a.sel_idx = sel_stride > 0 ? sel_idx : one_word;
+  a.n_sel = n_sel;
+  a.sel_stride = sel_stride;
+  a.n_split = fast_splits_for(x, sel_stride, &a.pipelined, max_splits);
+  x->last_fast_splits = a.n_split;
+  if (a.n_split == 1) a.out_direct = out;  // one workgroup per pair finishes the softmax itself
+  else if (x->tail_merge) { a.out_merge = out; a.arrive = arrive; }
+  { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_gather(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
+  if (a.n_split == 1 || a.out_merge != nullptr) return SFI_OK;
+  MergeArgs m{part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1, nullptr, 0, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha, x->cfg.max_ctx, x->cfg.out_bf16};
+  { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
+  return SFI_OK;
+}
+
+int check_fast(const sfi_ctx* x, const void* q, const void* K, const void* V, const int32_t* sel_idx, const int32_t* n_sel,
+               int32_t sel_stride, const int32_t* recent_start, const int32_t* ctx_len, const void* out) {
   int rc = check_common(x, q, K, V, ctx_len, out);
   if (rc != SFI_OK) return rc;
   if (sel_stride < 0 || sel_stride > x->cfg.max_budget) return SFI_EINVAL;
   if ((sel_idx == nullptr && sel_stride > 0) || n_sel == nullptr || recent_start == nullptr) return SFI_EINVAL;
   if (misaligned(sel_idx, 4) || misaligned(n_sel, 4) || misaligned(recent_start, 4)) return SFI_EALIGN;
-  hipStream_t st = (hipStream_t)stream;
-  CallRecord call_record(x);
-  AttnArgs a;
-  fill_attn(x, &a, q, K, V, ctx_len);
-  a.recent_start = recent_start;
-  // an index list of width 0: the pipelined kernel still reads one word where the list would start
-  a.sel_idx = sel_stride > 0 ? sel_idx : x->ws.guard;
-  a.n_sel = n_sel;
-  a.sel_stride = sel_stride;
-  a.n_split = fast_splits_for(x, sel_stride, &a.pipelined);
-  x->last_fast_splits = a.n_split;
-  if (a.n_split == 1) a.out_direct = out;  // one workgroup per pair finishes the softmax itself
-  else if (x->tail_merge) { a.out_merge = out; a.arrive = x->ws.arrive; }
-  { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_gather(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
-  if (a.n_split == 1 || a.out_merge != nullptr) return SFI_OK;
-  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1, nullptr, 0, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha, x->cfg.max_ctx, x->cfg.out_bf16};
-  { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
+}
+}  // namespace
+
+int sfi_fast_step(sfi_ctx* x, const void* q, const void* K, const void* V, const int32_t* sel_idx,
+                  const int32_t* n_sel, int32_t sel_stride, const int32_t* recent_start,
+                  const int32_t* ctx_len, void* out, void* stream) {
+  const int rc = check_fast(x, q, K, V, sel_idx, n_sel, sel_stride, recent_start, ctx_len, out);
+  if (rc != SFI_OK) return rc;
+  CallRecord call_record(x);
+  return fast_step_on(x, q, K, V, sel_idx, n_sel, sel_stride, recent_start, ctx_len, (float*)out, (hipStream_t)stream,
+                      x->ws.part, kSlotCap, x->ws.arrive, x->ws.guard, x->ws.guard, kMaxSplits);
+}
+
+// ---- the fast step for callers that cannot allocate ------------------------------------------------------
+// Split records and arrival counters live in a file-scope device array instead of a caller's workspace.
+namespace {
+constexpr int kStaticRecords = 8192;   // split records the scratch holds: batch * n_q_heads * splits per pair
+constexpr int kStaticPairs = 4096;     // arrival counters: batch * n_kv_heads
+constexpr size_t kStaticRecordBytes = (size_t)kStaticRecords * kPartStride * sizeof(float);
+constexpr size_t kStaticBytes = kStaticRecordBytes + (size_t)kStaticPairs * sizeof(uint32_t) + 256;
+constexpr int kMaxDevices = 64;
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+namespace {
+struct StaticScratch {
+  unsigned char* ptr;   // this device's copy of `scratch` (hipGetSymbolAddress), nullptr until its first call
+  int n_cu;
+  bool counters_clean;  // the arrival counters are known to be zero (every completed launch leaves them so)
+};
+StaticScratch g_static[kMaxDevices];
+std::mutex g_static_mutex;
+
+__global__ void clear_words_kernel(uint32_t* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+}  // namespace
+
+int sfi_fast_step_static(const sfi_config* cfg, const void* q, const void* K, const void* V, const int32_t* sel_idx,
+                         const int32_t* n_sel, int32_t sel_stride, const int32_t* recent_start,
+                         const int32_t* ctx_len, void* out, void* stream) {
+  int rc = validate(cfg);
+  if (rc != SFI_OK) return rc;
+  if (cfg->page_size != 0) return SFI_EUNSUPPORTED;  // no context to hold a block table
+  const int64_t heads = (int64_t)cfg->batch * cfg->n_q_heads, pairs = (int64_t)cfg->batch * cfg->n_kv_heads;
+  if (heads > kStaticRecords || pairs > kStaticPairs) return SFI_EUNSUPPORTED;  // beyond the static scratch
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return SFI_ELAUNCH; }
+  if (dev < 0 || dev >= kMaxDevices) return SFI_EUNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_static_mutex);  // calls that share a device's scratch must not overlap anyway
+  StaticScratch& S = g_static[dev];
+  if (S.ptr == nullptr) {  // once per device, with that device current: its own copy of the array
+    unsigned char* p = nullptr;
+    if (hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+      (void)hipGetLastError();
+      return SFI_ELAUNCH;
+    }
+    int n_cu = 0;
+    if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0) {
+      (void)hipGetLastError();
+      return SFI_ELAUNCH;
+    }
+    S.n_cu = n_cu;
+    S.counters_clean = false;
+    S.ptr = p;
+  }
+  sfi_ctx x;  // a context for this call only: no workspace, no profiling, default launch policy
+  memset(&x, 0, sizeof(x));
+  x.cfg = *cfg;
+  x.scale = cfg->scale > 0.f ? cfg->scale : 1.0f / sqrtf((float)cfg->head_dim);
+  x.G = cfg->n_q_heads / cfg->n_kv_heads;
+  x.alpha = cfg->alpha > 0.f ? cfg->alpha : 1.0f;
+  x.n_cu = S.n_cu;
+  x.tail_merge = 1;
+  if ((rc = check_fast(&x, q, K, V, sel_idx, n_sel, sel_stride, recent_start, ctx_len, out)) != SFI_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  float* part = reinterpret_cast<float*>(S.ptr);
+  uint32_t* arrive = reinterpret_cast<uint32_t*>(S.ptr + kStaticRecordBytes);
+  const int32_t* one_word = reinterpret_cast<const int32_t*>(arrive + kStaticPairs);  // readable, never written
+  const int max_splits = (int)(kStaticRecords / heads);  // >= 1
+  if (!S.counters_clean) {  // first call on this device, or the call before did not get its launch out
+    hipLaunchKernelGGL(clear_words_kernel, dim3((kStaticPairs + 255) / 256), dim3(256), 0, st, arrive, kStaticPairs);
+    if (hipGetLastError() != hipSuccess) return SFI_ELAUNCH;
+  }
+  S.counters_clean = false;
+  rc = fast_step_on(&x, q, K, V, sel_idx, n_sel, sel_stride, recent_start, ctx_len, (float*)out, st, part,
+                    max_splits < kMaxSplits ? max_splits : kMaxSplits, arrive, nullptr, one_word, max_splits);
+  S.counters_clean = rc == SFI_OK;
+  return rc;
 }
 
 namespace {
@@ -636,7 +742,8 @@ int sfi_reorg(sfi_ctx* x, const void* K, const void* V, const int32_t* sel_idx, 
 int sfi_fast_step_compact(sfi_ctx* x, const void* q, const void* Kc, const void* Vc, int64_t c_stride_b,
                           int64_t c_stride_h, int32_t c_rows, const int32_t* n_sel, int32_t sel_stride,
                           const void* K, const void* V, const int32_t* recent_start, const int32_t* ctx_len,
-                          float* out, void* stream) {
+                          void* out_, void* stream) {
+  float* out = (float*)out_;
   int rc = check_common(x, q, K, V, ctx_len, out);
   if (rc != SFI_OK) return rc;
   if (n_sel == nullptr || recent_start == nullptr) return SFI_EINVAL;
@@ -664,7 +771,8 @@ int sfi_fast_step_compact(sfi_ctx* x, const void* q, const void* Kc, const void*
 
 int sfi_mixed_step(sfi_ctx* x, const void* q, const void* K, const void* V, const uint8_t* is_slow,
                    const int32_t* ctx_len, const int32_t* recent_start, int32_t max_len, int32_t budget,
-                   float* out, int32_t* sel_idx, int32_t* n_sel, void* stream) {
+                   void* out_, int32_t* sel_idx, int32_t* n_sel, void* stream) {
+  float* out = (float*)out_;
   int rc = check_common(x, q, K, V, ctx_len, out);
   if (rc != SFI_OK) return rc;
   if (is_slow == nullptr || sel_idx == nullptr || n_sel == nullptr || recent_start == nullptr) return SFI_EINVAL;

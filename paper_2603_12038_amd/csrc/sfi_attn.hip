@@ -436,7 +436,7 @@ __device__ __forceinline__ float2 load_device2(const float* p) {  // 8-byte alig
 // invalidated as a whole (a device-scope fence costs tens of microseconds here).
 // One thread per (head, four output dims); records eight at a time, all loads of the eight in flight.
 __device__ __forceinline__ void finish_pair(const float* part, int64_t head0, int G, int n_wgs, uint32_t* arrive,
-                                            float* out, bool out_bf16) {
+                                            float* out, bool out_bf16, int slot_cap) {
   const int tid = threadIdx.x;
   __shared__ uint32_t s_before;
   // s_waitcnt vmcnt(0): a workgroup barrier by itself only orders the stores within the compute unit
@@ -448,7 +448,7 @@ __device__ __forceinline__ void finish_pair(const float* part, int64_t head0, in
   if (tid == 0) __hip_atomic_store(arrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   for (int idx = tid; idx < G * (kHeadDim / 4); idx += kAttnThreads) {
     const int hh = idx >> 5, c = idx & 31;
-    const float* P = part + (head0 + hh) * kSlotCap * kPartStride;
+    const float* P = part + (head0 + hh) * slot_cap * kPartStride;
     float M = kNeg, Z = 0.f;
     float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int s0 = 0; s0 < n_wgs; s0 += 8) {
@@ -770,7 +770,8 @@ __global__ __launch_bounds__(kAttnThreads, BIG ? 1 : 2) void attn_dense_kernel(c
 // finish merges the records into out_merge[b, head, :] (finish_pair; no merge kernel follows).
 __device__ __forceinline__ void write_wg_record(float* part, int64_t head0, int G, int slot, const f32x4 (&acc)[8],
                                                 float m_run, float l_run, float* out, float* out_merge = nullptr,
-                                                uint32_t* arrive = nullptr, int n_split = 1, bool out_bf16 = false) {
+                                                uint32_t* arrive = nullptr, int n_split = 1, bool out_bf16 = false,
+                                                int slot_cap = kSlotCap) {
   const int tid = threadIdx.x;
   const int lane = tid & 63, w = tid >> 6;
   const int jg = lane >> 4, n = lane & 15;
@@ -812,14 +813,15 @@ __device__ __forceinline__ void write_wg_record(float* part, int64_t head0, int 
     }
     return;
   }
-  const int64_t rec0 = (head0 * kSlotCap + slot) * kPartStride;
+  // slot_cap: records each query head has room for (kSlotCap in a caller's workspace, fewer in the static scratch)
+  const int64_t rec0 = (head0 * slot_cap + slot) * kPartStride;
   const bool tail = out_merge != nullptr;  // block-uniform
   for (int idx = tid; idx < G * kHeadDim; idx += kAttnThreads) {
     const int hh = idx >> 7, dim = idx & 127;
     float s = s_red[0][hh][dim];
 #pragma unroll
     for (int ww = 1; ww < kWaves; ++ww) s += s_red[ww][hh][dim];
-    float* dst = part + rec0 + (int64_t)hh * kSlotCap * kPartStride + 4 + dim;
+    float* dst = part + rec0 + (int64_t)hh * slot_cap * kPartStride + 4 + dim;
     if (tail) store_device(dst, s);
     else *dst = s;
   }
@@ -830,14 +832,14 @@ __device__ __forceinline__ void write_wg_record(float* part, int64_t head0, int 
     float ls = 0.f;
 #pragma unroll
     for (int ww = 0; ww < kWaves; ++ww) ls += s_l[ww][tid] * fast_exp2(s_m[ww][tid] - M);
-    float* r = part + rec0 + (int64_t)tid * kSlotCap * kPartStride;
+    float* r = part + rec0 + (int64_t)tid * slot_cap * kPartStride;
     if (tail) {
       store_device2(r, M, ls);
     } else {
       *reinterpret_cast<float2*>(r) = make_float2(M, ls);
     }
   }
-  if (tail) finish_pair(part, head0, G, n_split, arrive, out_merge, out_bf16);
+  if (tail) finish_pair(part, head0, G, n_split, arrive, out_merge, out_bf16, slot_cap);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -908,7 +910,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_kernel(const Attn
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
   write_wg_record(a.part, head0, G, slot, acc, m_run, l_run, a.out_direct, a.out_merge,
-                  a.arrive != nullptr ? a.arrive + bh : nullptr, a.n_split, a.out_bf16 != 0);
+                  a.arrive != nullptr ? a.arrive + bh : nullptr, a.n_split, a.out_bf16 != 0, a.slot_cap);
   report_guard(a.guard, W.bad);  // last: the way to the record and the merge is the launch's critical path
 }
 
@@ -1049,7 +1051,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(con
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
   write_wg_record(a.part, head0, G, slot, acc, m_run, l_run, a.out_direct, a.out_merge,
-                  a.arrive != nullptr ? a.arrive + bh : nullptr, a.n_split, a.out_bf16 != 0);
+                  a.arrive != nullptr ? a.arrive + bh : nullptr, a.n_split, a.out_bf16 != 0, a.slot_cap);
   report_guard(a.guard, W.bad);  // last: the way to the record and the merge is the launch's critical path
 }
 
@@ -1155,7 +1157,7 @@ __global__ __launch_bounds__(kAttnThreads, PAGED ? 2 : 3) void attn_compact_kern
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
   write_wg_record(a.part, head0, G, slot, acc, m_run, l_run, a.out_direct, a.out_merge,
-                  a.arrive != nullptr ? a.arrive + bh : nullptr, a.n_split, a.out_bf16 != 0);
+                  a.arrive != nullptr ? a.arrive + bh : nullptr, a.n_split, a.out_bf16 != 0, a.slot_cap);
   report_guard(a.guard, bad);
 }
 

@@ -85,6 +85,8 @@ struct AttnArgs {
   int64_t sel_stride;
   const uint8_t* is_slow;        // nullptr: every sequence takes part
   float* part;
+  int32_t slot_cap;              // gather / compact mode: records each query head has room for in part (kSlotCap in a
+                                 //   caller's workspace)
   float* logits;                 // dense mode, nullptr: do not expose logits
   int32_t with_knorm;            // dense mode: also expose the squared key norms (full Selector)
   int32_t no_v;                  // dense mode with logits: evidence only -- V is not read, the records hold no output
