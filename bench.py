@@ -25,7 +25,6 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBS = 8000.0
 FAST_MERGE = {None: 0, "kernel": 1, "launch": 2}  # sfi_set_tuning codes
@@ -73,7 +72,7 @@ def bench_serving(args):
 
     import paper_2603_12038_amd as sfi
     import sfi_synth as syn
-    from helpers import i32_dev
+    from sfi_check import i32_dev
 
     SEG = 16
     NL = args.layers or 4
@@ -192,7 +191,7 @@ def bench_retention(args):
 
     import paper_2603_12038_amd as sfi
     import sfi_synth as syn
-    from helpers import i32_dev
+    from sfi_check import i32_dev
 
     B, Hq, Hkv, d, L, R, n_sink = args.batch or 16, 32, 8, 128, args.ctx or 16384, 128, 4
     NL = args.layers or 4
@@ -309,7 +308,7 @@ def main():
 
     import paper_2603_12038_amd as sfi
     import sfi_synth as syn
-    from helpers import check_out, check_out_bf16, check_selection, i32_dev, to_dev
+    from sfi_check import check_out, check_out_bf16, check_selection, i32_dev, to_dev
 
     if args.out_bf16:  # the parity sample then uses the bf16 rule (an ulp of the element + the fp32 path's error)
         check_out = check_out_bf16

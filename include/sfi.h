@@ -172,7 +172,9 @@ int sfi_slow_step(sfi_ctx* ctx, const void* q, const void* K, const void* V, con
  *   sfi_slow_attn    dense attention -> out; the evidence (logits over J and their softmax statistics)
  *                    stays in this context's workspace;
  *   sfi_slow_select  the Selector on that evidence -> sel_idx, n_sel.  ctx_len, max_len must be the ones
- *                    given to the sfi_slow_attn call it follows.
+ *                    given to the sfi_slow_attn call it follows.  It may be called again on the same evidence
+ *                    (another budget): a repeat starts with one more small launch that resets the Selector's
+ *                    counters.
  * sfi_slow_step is the two in a row on one stream.  To overlap Sel_i with Attn_{i+1}, give the layers
  * in flight a context (and workspace) each -- a ring of a few -- run sfi_slow_attn on the main stream and
  * sfi_slow_select on a second stream that waits for an event recorded after it; before a context is

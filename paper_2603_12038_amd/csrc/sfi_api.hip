@@ -21,6 +21,8 @@ struct sfi_ctx {
   int fast_tiles_per_wave;  // 32-row tiles each wave of the gather launch should get; 0 = decided per launch
   int tail_merge;           // split fast-step launches merge in the attention kernel (no merge launch)
   int last_dense_splits, last_fast_splits;
+  int selector_ran;         // a Selector pass has used the evidence now in the workspace: its histogram and state
+                            // words are no longer the cleared ones the dense kernel left
   // profiling: a ring of event pairs, one set of stages per hot call, read back in one go so that
   // no host synchronisation sits between the profiled calls
   int profiling;
@@ -290,6 +292,8 @@ int run_selector(sfi_ctx* x, const SelArgs& sa, int max_len, hipStream_t st, boo
   const int nJ = max_len - x->cfg.recent - x->cfg.n_sink;
   int n_seg = nJ > 0 ? (nJ + kSelSeg - 1) / kSelSeg : 1;
   if (n_seg > x->ws.n_seg_cap) n_seg = x->ws.n_seg_cap;
+  if (x->selector_ran) SFI_TRY(launch_sel_clear(sa, B, st));  // a second pass over the same evidence
+  x->selector_ran = 1;
   {
     StageTimer t(x, st, SFI_STAGE_SCORE);
     if (x->cfg.selector_mode == 1) SFI_TRY(launch_sel_full(sa, B, n_seg, st));
@@ -471,6 +475,7 @@ int slow_attn_impl(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   a.state = x->ws.state;
   x->last_dense_splits = a.n_split;
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
+  x->selector_ran = 0;  // fresh evidence, Selector state cleared by the launch above
   if (merge_later) return SFI_OK;  // the Selector's scoring launch merges
   MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, a.n_split * kWaves, 0, 0, x->ws.jstat, a.n_split * kWaves, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha, ml, x->cfg.out_bf16};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
@@ -814,6 +819,7 @@ int sfi_mixed_step(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   // rewrites rows of slow sequences, so the order of the two attention launches is free.
   { StageTimer t(x, st, SFI_STAGE_ATTN2); SFI_TRY(launch_attn_gather(f, x->cfg.batch, f.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(d, x->cfg.batch, d.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
+  x->selector_ran = 0;
   if (!merge_in_score) {
     MergeArgs m{x->ws.part, out, is_slow, x->cfg.n_q_heads, d.n_split * kWaves, fast_done ? 0 : f.n_split, 2, x->ws.jstat, d.n_split * kWaves, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha, ml, x->cfg.out_bf16};
     StageTimer t(x, st, SFI_STAGE_MERGE);
@@ -860,9 +866,20 @@ int sfi_set_profiling(sfi_ctx* x, int max_calls) {
     const size_t n = (size_t)max_calls * SFI_N_STAGES * 2;
     x->ev = new (std::nothrow) hipEvent_t[n];
     x->ev_used = new (std::nothrow) unsigned char[(size_t)max_calls * SFI_N_STAGES];
-    if (x->ev == nullptr || x->ev_used == nullptr) return SFI_ENOMEM;
-    for (size_t i = 0; i < n; ++i)
-      if (hipEventCreate(&x->ev[i]) != hipSuccess) return SFI_ELAUNCH;
+    size_t made = 0;
+    int rc = (x->ev == nullptr || x->ev_used == nullptr) ? SFI_ENOMEM : SFI_OK;
+    for (; rc == SFI_OK && made < n; ++made)
+      if (hipEventCreate(&x->ev[made]) != hipSuccess) { rc = SFI_ELAUNCH; break; }
+    if (rc != SFI_OK) {  // leave the context without a ring rather than with half of one
+      (void)hipGetLastError();
+      for (size_t i = 0; i < made; ++i) (void)hipEventDestroy(x->ev[i]);
+      delete[] x->ev;
+      delete[] x->ev_used;
+      x->ev = nullptr;
+      x->ev_used = nullptr;
+      x->profiling = 0;
+      return rc;
+    }
     x->prof_cap = max_calls;
   }
   x->profiling = max_calls > 0 ? 1 : 0;

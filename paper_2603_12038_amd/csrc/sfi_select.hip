@@ -714,6 +714,22 @@ __global__ __launch_bounds__(kSelThreads) void sel_write_kernel(const SelArgs a)
   }
 }
 
+// Fresh Selector state (histogram, state words) for every (b, h) of the sequences taking part.  The dense
+// kernel does this for the evidence it writes; a Selector pass that runs a second time on the same evidence
+// (another budget, say) starts with this launch instead, or it would count into the first pass's histogram.
+__global__ __launch_bounds__(kSelThreads) void sel_clear_kernel(const SelArgs a) {
+  const int h = blockIdx.y, b = blockIdx.z;
+  if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
+  const int bh = b * a.Hkv + h;
+  uint32_t* hh = a.hist1 + (int64_t)bh * kHist1Bins;
+  for (int i = threadIdx.x; i < kHist1Bins; i += kSelThreads) hh[i] = 0u;
+  if (threadIdx.x < kStateWords) a.state[(int64_t)bh * kStateWords + threadIdx.x] = 0u;
+}
+hipError_t launch_sel_clear(const SelArgs& a, int B, hipStream_t s) {
+  hipLaunchKernelGGL(sel_clear_kernel, dim3(1, a.Hkv, B), dim3(kSelThreads), 0, s, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_sel_score(const SelArgs& a, int B, int n_seg, hipStream_t s) {
   // with the merge on board: one more workgroup per query head
   hipLaunchKernelGGL(sel_score_kernel<false>, dim3(n_seg + (a.part != nullptr ? a.G : 0), a.Hkv, B), dim3(kSelThreads), 0, s, a);

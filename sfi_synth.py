@@ -46,7 +46,16 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
 
 
 def normal_bf16(rng: np.random.Generator, shape, row_scale: Optional[np.ndarray] = None) -> np.ndarray:
-    """N(0,1) samples, optionally scaled per row (second-to-last axis) before rounding."""
+    """N(0,1) samples, optionally scaled per row (second-to-last axis) before rounding.  Large 2-D requests are
+    drawn a block of rows at a time (the generator's stream, hence every bit, is the same as in one draw; the
+    temporaries then stay cache-sized, which is what lets several threads fill slices side by side)."""
+    if len(shape) == 2 and shape[0] * shape[1] > (1 << 20):
+        out = np.empty(shape, dtype=np.uint16)
+        step = max(1, (1 << 18) // shape[1])
+        for r0 in range(0, shape[0], step):
+            r1 = min(shape[0], r0 + step)
+            out[r0:r1] = normal_bf16(rng, (r1 - r0, shape[1]), None if row_scale is None else row_scale[r0:r1])
+        return out
     x = rng.standard_normal(size=shape, dtype=np.float32)
     if row_scale is not None:
         x *= row_scale[..., None].astype(np.float32)
@@ -103,15 +112,27 @@ class Workload:
 
 
 def _alloc_kv(w: Workload, row_scale: Optional[np.ndarray]) -> None:
+    """Every (b, h) slice comes from its own Philox stream, so the slices can be filled by a few threads at once
+    (numpy's generators release the interpreter lock) and the bits do not depend on how many."""
+    from concurrent.futures import ThreadPoolExecutor
+
     shape = (w.B, w.Hkv, w.L_alloc, w.d)
     w.K = np.empty(shape, dtype=np.uint16)
     w.V = np.empty(shape, dtype=np.uint16)
-    for b in range(w.B):
-        for h in range(w.Hkv):
-            sub = b * w.Hkv + h
-            rs = None if row_scale is None else row_scale[b, h]
-            w.K[b, h] = normal_bf16(rng_for(w.seed, _TID_K, sub), (w.L_alloc, w.d), rs)
-            w.V[b, h] = normal_bf16(rng_for(w.seed, _TID_V, sub), (w.L_alloc, w.d))
+
+    def fill(sub: int) -> None:
+        b, h = divmod(sub, w.Hkv)
+        rs = None if row_scale is None else row_scale[b, h]
+        w.K[b, h] = normal_bf16(rng_for(w.seed, _TID_K, sub), (w.L_alloc, w.d), rs)
+        w.V[b, h] = normal_bf16(rng_for(w.seed, _TID_V, sub), (w.L_alloc, w.d))
+
+    n = w.B * w.Hkv
+    if n * w.L_alloc * w.d < (1 << 22):
+        for sub in range(n):
+            fill(sub)
+    else:
+        with ThreadPoolExecutor(max_workers=8) as ex:
+            list(ex.map(fill, range(n)))
 
 
 def _fixed_schedule(steps: int, B: int, every: int) -> np.ndarray:

@@ -1,7 +1,9 @@
 """GPU parity at the baseline configurations' full sizes, in the launch configuration bench.py times.
 
-The oracle finishes these sizes in well under a second per step on the GPU machine's host cores, so
-every output element and every index set is compared (not a sample)."""
+The oracle finishes most of these sizes in about a second per step on the GPU machine's host cores, so every
+output element and every index set is compared; the full serving batch (32 ragged sequences of up to 65536
+rows) is the exception: the GPU computes all of it, the oracle checks every sequence's fast steps and a sample
+of the dense ones, named in the test."""
 import numpy as np
 import pytest
 
@@ -94,9 +96,11 @@ def test_long_single_stream(oracle):
     _slow_then_fast(oracle, w).close()
 
 
-def test_long_cot_window(oracle):
-    """Config 4 at the 24K sample point: B8, 40/8 heads (G = 5), K = 1024, recent 128."""
-    w = syn.make_cot(L0=24576, steps=4)
+@pytest.mark.parametrize("L0", [8192, 24576, 38912])
+def test_long_cot_window(oracle, L0):
+    """Config 4 at its three sample points (start of the windows at 8K, 24K and 40K): B8, 40/8 heads (G = 5),
+    K = 1024, recent 128."""
+    w = syn.make_cot(L0=L0, steps=4)
     _slow_then_fast(oracle, w).close()
 
 
@@ -143,6 +147,81 @@ def test_serving_mix_ragged(oracle):
             else:
                 check_out(got[b], ref_s[b])
                 assert (sel1[b] == sel0[b]).all()
+    finally:
+        r.close()
+
+
+def test_serving_mix_full_batch(oracle):
+    """Config 5 at its full batch: B32, 64/8 heads (G = 8), ragged ctx in [16384, 65536], K = 2048 -- the launch
+    plan bench.py's serving workload times (256 pairs: one workgroup per pair in the fast part, output written
+    directly).  An all-slow step, a mixed step and an all-fast step.  The GPU computes all 32 sequences every time;
+    the oracle checks every sequence on the fast side (cheap) and, on the dense side, the longest, the shortest
+    and four more (a dense sequence costs it seconds)."""
+    import torch
+    import paper_2603_12038_amd as sfi
+
+    w = syn.make_serving(steps=4)
+    assert w.B == 32
+    _step(f"serving mix at full batch: generated, ctx {int(w.L0.min())}..{int(w.L0.max())}")
+    r = Runner(w)
+    try:
+        B = w.B
+        one = lambda x, b: x[b:b + 1]
+        ctx_d, rs_d = i32_dev(w.ctx_len(0)), i32_dev(w.recent_start(0))
+        sel_d = torch.full((B, w.Hkv, w.budget), -7, dtype=torch.int32, device="cuda")
+        nsel_d = torch.full((B, w.Hkv), -7, dtype=torch.int32, device="cuda")
+        order = np.argsort(w.L0)
+        sample = sorted({int(order[0]), int(order[-1]), 3, 11, 19, 27})
+        # ---- all slow
+        q0, c0 = w.q(0), w.ctx_len(0)
+        sfi.sfi_mixed_step(r.ctx.handle, to_dev(q0), r.K, r.V, torch.ones(B, dtype=torch.uint8, device="cuda"), ctx_d,
+                           rs_d, 0, w.budget, r.out, sel_d, nsel_d)
+        torch.cuda.synchronize()
+        got0, sel0, nsel0 = r.out.cpu().numpy(), sel_d.cpu().numpy(), nsel_d.cpu().numpy()
+        assert np.isfinite(got0).all()
+        for b in sample:
+            e = check_out(got0[b:b + 1], oracle.dense(one(q0, b), one(w.K, b), one(w.V, b), one(c0, b)))
+            sr, nr, z = oracle.selector(one(q0, b), one(w.K, b), one(c0, b), w.budget, w.n_sink, w.recent)
+            n_exact = check_selection(one(sel0, b), one(nsel0, b), sr, nr, z, one(c0, b), w.n_sink, w.recent, w.budget)
+            _step(f"  all-slow step, sequence {b} (ctx {int(c0[b])}): out err {e:.2e}, sets identical {n_exact}/{w.Hkv}")
+        for b in range(B):  # structure of every sequence's sets
+            for h in range(w.Hkv):
+                k = int(nsel0[b, h])
+                assert k == min(w.budget, int(c0[b]) - w.recent - w.n_sink) and (np.diff(sel0[b, h, :k]) > 0).all()
+                assert sel0[b, h, 0] >= w.n_sink and sel0[b, h, k - 1] < int(c0[b]) - w.recent
+        # ---- mixed: three slow sequences, one of them checked densely by the oracle
+        sfi.sfi_advance(r.ctx.handle, ctx_d, rs_d)
+        slow1 = np.zeros(B, np.uint8)
+        slow1[[sample[1], 17, 30]] = 1
+        q1, c1, rs1 = w.q(1), w.ctx_len(1), w.recent_start(1)
+        sfi.sfi_mixed_step(r.ctx.handle, to_dev(q1), r.K, r.V, torch.from_numpy(slow1).cuda(), ctx_d, rs_d, 0,
+                           w.budget, r.out, sel_d, nsel_d)
+        torch.cuda.synchronize()
+        got1, sel1, nsel1 = r.out.cpu().numpy(), sel_d.cpu().numpy(), nsel_d.cpu().numpy()
+        ref_s = oracle.sparse(q1, w.K, w.V, sel0, nsel0, rs1, c1, w.n_sink)
+        for b in range(B):
+            if slow1[b]:
+                if b in (sample[1], 17):
+                    check_out(got1[b:b + 1], oracle.dense(one(q1, b), one(w.K, b), one(w.V, b), one(c1, b)))
+                    sr, nr, z = oracle.selector(one(q1, b), one(w.K, b), one(c1, b), w.budget, w.n_sink, w.recent)
+                    check_selection(one(sel1, b), one(nsel1, b), sr, nr, z, one(c1, b), w.n_sink, w.recent, w.budget)
+            else:
+                check_out(got1[b], ref_s[b])
+                assert (sel1[b] == sel0[b]).all()
+        _step("  mixed step (3 slow + 29 fast sequences) ok")
+        # ---- all fast
+        sfi.sfi_advance(r.ctx.handle, ctx_d, rs_d)
+        q2, c2, rs2 = w.q(2), w.ctx_len(2), w.recent_start(2)
+        sfi.sfi_mixed_step(r.ctx.handle, to_dev(q2), r.K, r.V, torch.zeros(B, dtype=torch.uint8, device="cuda"), ctx_d,
+                           rs_d, 0, w.budget, r.out, sel_d, nsel_d)
+        torch.cuda.synchronize()
+        e = check_out(r.out.cpu().numpy(), oracle.sparse(q2, w.K, w.V, sel1, nsel1, rs2, c2, w.n_sink))
+        assert (sel_d.cpu().numpy() == sel1).all()
+        assert sfi.sfi_query_splits(r.ctx.handle)[1] == 1, "256 pairs: one workgroup per pair, output written directly"
+        got = r.fast(q2, sel1, nsel1, rs2, c2)     # the same step through sfi_fast_step
+        check_out(got, oracle.sparse(q2, w.K, w.V, sel1, nsel1, rs2, c2, w.n_sink))
+        _step(f"  all-fast step ok, out err {e:.2e}")
+        assert sfi.sfi_device_status(r.ctx.handle) == 0
     finally:
         r.close()
 

@@ -213,7 +213,8 @@ def test_mixed_step_and_advance(oracle):
 
         sfi.sfi_advance(r.ctx.handle, ctx_d, rs_d)
         torch.cuda.synchronize()
-        assert (ctx_d.cpu().numpy() == w.ctx_len(1)).all() and (rs_d.cpu().numpy() == w.recent_start(1)).all()
+        ctx_o, rs_o = oracle.advance(ctx0, w.recent_start(0), w.n_sink, w.recent)   # the oracle's state update
+        assert (ctx_d.cpu().numpy() == ctx_o).all() and (rs_d.cpu().numpy() == rs_o).all()
 
         slow1 = np.array([0, 1, 0, 0, 1], np.uint8)
         q1 = w.q(1)
@@ -239,36 +240,42 @@ def test_mixed_step_and_advance(oracle):
 
 
 def test_tiny_config_all_steps(oracle):
-    """Config 1 as stated: 16 steps, slow at t = 0 and 8, every step checked (Algorithm 1 with a scripted g_t)."""
+    """Config 1 as stated: 16 steps, slow at t = 0 and 8, the state carried on the device from step to step
+    (sfi_advance), every step checked against the oracle's Algorithm 1 driver: outputs, the state each step ran
+    on and the index sets after it."""
     import torch
     import paper_2603_12038_amd as sfi
 
     w = syn.make_tiny()
+    qs = np.stack([w.q(t) for t in range(w.steps)])
+    ref = oracle.decode_loop(qs, w.K, w.V, w.ctx_len(0), w.recent_start(0), w.slow.astype(np.uint8), w.budget, w.n_sink,
+                             w.recent)
     r = Runner(w)
     try:
         ctx_d, rs_d = i32_dev(w.ctx_len(0)), i32_dev(w.recent_start(0))
         sel_d = torch.full((w.B, w.Hkv, w.budget), -7, dtype=torch.int32, device="cuda")
         nsel_d = torch.zeros((w.B, w.Hkv), dtype=torch.int32, device="cuda")
-        sel_o = nsel_o = None
         for t in range(w.steps):
             _step(f"tiny config step {t} ({'slow' if w.slow[t, 0] else 'fast'})")
-            q = w.q(t)
-            ctx, rs = w.ctx_len(t), w.recent_start(t)
+            q = qs[t]
+            assert (ctx_d.cpu().numpy() == ref["ctx_hist"][t]).all() and (rs_d.cpu().numpy() == ref["rs_hist"][t]).all()
             if w.slow[t, 0]:
                 sfi.sfi_slow_step(r.ctx.handle, to_dev(q), r.K, r.V, ctx_d, 0, w.budget, r.out, sel_d, nsel_d)
                 torch.cuda.synchronize()
-                check_out(r.out.cpu().numpy(), oracle.dense(q, w.K, w.V, ctx))
-                sel_o, nsel_o, z = oracle.selector(q, w.K, ctx, w.budget, w.n_sink, w.recent)
-                sel_g, nsel_g = sel_d.cpu().numpy(), nsel_d.cpu().numpy()
-                check_selection(sel_g, nsel_g, sel_o, nsel_o, z, ctx, w.n_sink, w.recent, w.budget)
-                sel_o, nsel_o = sel_g, nsel_g  # later fast steps are checked on the set the GPU carries
+                ctx = ref["ctx_hist"][t]
+                _, _, z = oracle.selector(q, w.K, ctx, w.budget, w.n_sink, w.recent)
+                check_selection(sel_d.cpu().numpy(), nsel_d.cpu().numpy(), ref["sel_hist"][t], ref["nsel_hist"][t], z, ctx,
+                                w.n_sink, w.recent, w.budget)
+                # the fast steps that follow are compared on the oracle's set: the two must carry the same one
+                assert (sel_d.cpu().numpy() == ref["sel_hist"][t]).all(), "a near-tie at the cut: pick another seed"
             else:
                 sfi.sfi_fast_step(r.ctx.handle, to_dev(q), r.K, r.V, sel_d, nsel_d, w.budget, rs_d, ctx_d, r.out)
                 torch.cuda.synchronize()
-                check_out(r.out.cpu().numpy(), oracle.sparse(q, w.K, w.V, sel_o, nsel_o, rs, ctx, w.n_sink))
+                assert (sel_d.cpu().numpy() == ref["sel_hist"][t]).all()     # Eq. freeze_sel
+            check_out(r.out.cpu().numpy(), ref["out"][t])
             sfi.sfi_advance(r.ctx.handle, ctx_d, rs_d)
         torch.cuda.synchronize()
-        assert (ctx_d.cpu().numpy() == w.ctx_len(w.steps)).all()
+        assert (ctx_d.cpu().numpy() == ref["ctx_len"]).all() and (rs_d.cpu().numpy() == ref["recent_start"]).all()
     finally:
         r.close()
 
@@ -788,3 +795,26 @@ def test_context_shorter_than_the_sink(oracle, n_sink, L):
             check_out(r.fast_compact(q, nsel, sel.shape[2], rt, ct), ref)
     finally:
         r.close()
+
+
+def test_selector_twice_on_the_same_evidence(oracle, tiny):
+    """sfi_slow_attn once, sfi_slow_select twice with two budgets: the second pass must not count into the first
+    pass's histogram and candidate list."""
+    import torch
+    import paper_2603_12038_amd as sfi
+
+    w, r = tiny
+    _step("two Selector passes over one evidence")
+    q, ctx = w.q(0), w.ctx_len(0)
+    ctx_d = i32_dev(ctx)
+    r.out.fill_(float("nan"))
+    sfi.sfi_slow_attn(r.ctx.handle, to_dev(q), r.K, r.V, ctx_d, 0, r.out)
+    for budget in (w.budget, w.budget // 3, w.budget):
+        sel = torch.full((w.B, w.Hkv, budget), -7, dtype=torch.int32, device="cuda")
+        nsel = torch.full((w.B, w.Hkv), -7, dtype=torch.int32, device="cuda")
+        sfi.sfi_slow_select(r.ctx.handle, ctx_d, 0, budget, sel, nsel)
+        torch.cuda.synchronize()
+        sel_ref, nsel_ref, z = oracle.selector(q, w.K, ctx, budget, w.n_sink, w.recent)
+        check_selection(sel.cpu().numpy(), nsel.cpu().numpy(), sel_ref, nsel_ref, z, ctx, w.n_sink, w.recent, budget)
+    check_out(r.out.cpu().numpy(), oracle.dense(q, w.K, w.V, ctx))
+    assert r.sfi.sfi_device_status(r.ctx.handle) == 0

@@ -107,6 +107,27 @@ def test_full_selector_at_llama8b_size(oracle):
     assert n_exact >= (w.B * w.Hkv) // 2
 
 
+def test_full_selector_at_long_context(oracle):
+    """Config 3's slow step (B1, 32/8 heads, ctx 131072, K = 4096, recent 256) with the full Selector: the evidence
+    of a typical position, ~1 / |J|, sits three decades above eps here, the prior's position terms span 64 segments."""
+    sp, d = _params()
+    w = syn.make_long(steps=2)
+    _step("mode 1 at config-3 size")
+    n_exact, _, _ = _run(oracle, w, sp, d)
+    _step(f"  index sets identical to the oracle's: {n_exact}/{w.B * w.Hkv}")
+    assert n_exact >= (w.B * w.Hkv) // 2
+
+
+def test_full_selector_at_serving_shape(oracle):
+    """Config 5's head layout (64/8 heads, G = 8, eight KV heads under the cross-head term), four ragged sequences."""
+    sp, d = _params()
+    w = syn.make_serving(steps=2, B=4)
+    _step(f"mode 1 at config-5 shape, ctx {w.L0.tolist()}")
+    n_exact, _, _ = _run(oracle, w, sp, d)
+    _step(f"  index sets identical to the oracle's: {n_exact}/{w.B * w.Hkv}")
+    assert n_exact >= (w.B * w.Hkv) // 2
+
+
 @pytest.mark.parametrize("alpha", [0.5, 0.25, 0.9])
 @pytest.mark.parametrize("mode", [0, 1])
 def test_power_mean_evidence(oracle, mode, alpha):
@@ -137,7 +158,8 @@ def test_power_mean_single_head_is_alpha_free(oracle):
 
 
 @pytest.mark.parametrize("with_out", [True, False])
-@pytest.mark.parametrize("mode,alpha,W", [(0, 1.0, 5), (0, 0.5, 3), (1, 1.0, 4), (1, 0.5, 2), (0, 1.0, 1)])
+@pytest.mark.parametrize("mode,alpha,W", [(0, 1.0, 5), (0, 0.5, 3), (1, 1.0, 4), (1, 0.5, 2), (0, 1.0, 1),
+                                          (0, 0.5, 16), (1, 0.5, 16)])  # W = 16, alpha < 1: the paper's prefill setting
 def test_windowed_evidence(oracle, mode, alpha, W, with_out):
     """Evidence accumulated over W window queries (Eq. selector_mu with a window): W calls of
     sfi_evidence_add and one sfi_evidence_select against the oracle's Selector on the W * G query vectors
@@ -150,7 +172,7 @@ def test_windowed_evidence(oracle, mode, alpha, W, with_out):
     sp, d = _params(alpha=alpha)
     if mode == 0:
         sp, d = dataclasses.replace(sp, mode=0), None
-    w = syn.make_tiny(L0=3100, steps=8, budget=96, recent=40, n_support=16, B=2, Hq=8, Hkv=2)
+    w = syn.make_tiny(L0=3100, steps=max(8, W), budget=96, recent=40, n_support=16, B=2, Hq=8, Hkv=2)
     w.L0 = np.array([3100, 1500], np.int32)
     G = w.Hq // w.Hkv
     r = Runner(w, selector=d, alpha=alpha)
