@@ -14,6 +14,10 @@ The timed region is captured into one HIP graph and replayed once (inputs reside
 
 Reported value: decode-attention tokens/s of ONE attention layer for the slow+fast mix
 (batch x decode steps x layers / time).
+
+Without --workload the line's value is the default workload above and a "workloads" object carries
+short runs of the other stated configurations (one long stream at 131072, the long-CoT window, the
+ragged serving mix), each with its own roofline object, parity sample and oracle baseline.
 """
 from __future__ import annotations
 
@@ -40,6 +44,31 @@ WORKLOADS = {
     "cot": dict(make="make_cot", ctx=24576, batch=8, seg=24, layers=16,
                 label="long-CoT window (G=5)"),
 }
+
+
+def kernel_source_hash():
+    """First 16 hex digits of the sha256 over the library's kernel sources (what a committed profile was taken on)."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2603_12038_amd", "csrc", "*"))):
+        h.update(open(f, "rb").read())
+    return h.hexdigest()[:16]
+
+
+def committed_traffic(kernel_key):
+    """HBM bytes per launch of a kernel from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE, each scaled
+    by what the counter reads for a plain copy), if that summary was taken on the kernel sources of this tree; it is not
+    measured in this run (counters need the profiler).  Returns (bytes or None, where it comes from)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_llama8b.txt")
+    if not os.path.exists(path):
+        return None, "no committed counter profile"
+    prof = json.load(open(path))
+    if prof.get("kernel_source_sha256_16") != kernel_source_hash():
+        return None, "profiles/hbm_traffic_llama8b.txt was taken on other kernel sources than this tree's: not quoted"
+    if kernel_key not in prof:
+        return None, "kernel not in profiles/hbm_traffic_llama8b.txt"
+    return prof[kernel_key].get("hbm_bytes_per_launch"), "profiles/hbm_traffic_llama8b.txt (rocprofv3 --pmc on these kernel sources; not measured in this run)"
 
 
 def log(msg):
@@ -72,7 +101,7 @@ def bench_serving(args):
 
     import paper_2603_12038_amd as sfi
     import sfi_synth as syn
-    from sfi_check import i32_dev
+    from sfi_check import check_out, check_selection, i32_dev
 
     SEG = 16
     NL = args.layers or 4
@@ -116,6 +145,58 @@ def bench_serving(args):
             sfi.sfi_mixed_step(h, q_all[t, l], Ks[l], Vs[l], flags[t], ctx_d, rs_d, max_ctx, w.budget, outs[l], sels[l],
                                nsels[l])
         sfi.sfi_advance(h, ctx_d, rs_d)
+
+    # ---- parity sample + CPU baseline on layer 0: step 0 (every sequence slow) and a step of fast sequences, each
+    # checked against the oracle on three sequences (the longest, the shortest, one in between) copied back to the host
+    cpu_baseline, parity = None, {}
+    if not args.no_cpu_baseline:
+        from oracle import sfi_oracle as oracle
+
+        order = np.argsort(w.L0)
+        sample = [int(order[-1]), int(order[0]), int(order[B // 2])]
+        bits = lambda t: t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+        Kh = {b: bits(Ks[0][b:b + 1]) for b in sample}
+        Vh = {b: bits(Vs[0][b:b + 1]) for b in sample}
+        all_slow = torch.ones(B, dtype=torch.uint8, device=dev)
+        c0, c1, rs1 = w.ctx_len(0), w.ctx_len(1), w.recent_start(1)
+        sfi.sfi_mixed_step(h, q_all[0, 0], Ks[0], Vs[0], all_slow, ctx_d, rs_d, max_ctx, w.budget, outs[0], sels[0], nsels[0])
+        torch.cuda.synchronize()
+        g_out, g_sel, g_nsel = outs[0].cpu().numpy(), sels[0].cpu().numpy(), nsels[0].cpu().numpy()
+        q0 = bits(q_all[0, 0])
+        t_slow, rows_slow, errs, exact = 0.0, 0, [], 0
+        for b in sample:
+            t1 = time.time()
+            o_d = oracle.dense(q0[b:b + 1], Kh[b], Vh[b], c0[b:b + 1])
+            o_sel, o_nsel, o_z = oracle.selector(q0[b:b + 1], Kh[b], c0[b:b + 1], w.budget, w.n_sink, w.recent)
+            t_slow += time.time() - t1
+            rows_slow += int(c0[b])
+            errs.append(check_out(g_out[b:b + 1], o_d))
+            exact += check_selection(g_sel[b:b + 1], g_nsel[b:b + 1], o_sel, o_nsel, o_z, c0[b:b + 1], w.n_sink, w.recent, w.budget)
+        parity["slow_out_row_rel_err"] = max(errs)
+        parity["selection_sets_exact"] = f"{exact}/{len(sample) * Hkv}"
+        none = torch.zeros(B, dtype=torch.uint8, device=dev)
+        sfi.sfi_mixed_step(h, q_all[1, 0], Ks[0], Vs[0], none, i32_dev(c1), i32_dev(rs1), max_ctx, w.budget, outs[0], sels[0], nsels[0])
+        torch.cuda.synchronize()
+        g_out, q1 = outs[0].cpu().numpy(), bits(q_all[1, 0])
+        t_fast, errs = 0.0, []
+        for b in sample:
+            t1 = time.time()
+            o_s = oracle.sparse(q1[b:b + 1], Kh[b], Vh[b], g_sel[b:b + 1], g_nsel[b:b + 1], rs1[b:b + 1], c1[b:b + 1], w.n_sink)
+            t_fast += time.time() - t1
+            errs.append(check_out(g_out[b:b + 1], o_s))
+        parity["fast_out_row_rel_err"] = max(errs)
+        # the mix as scheduled: a sequence is slow once per 20 steps on average; a slow sequence costs the oracle in
+        # proportion to its context (scaled from the sample's rows to the batch's mean context)
+        s_slow = t_slow / rows_slow * float(w.L0.mean())
+        s_fast = t_fast / len(sample)
+        per_seq_step = s_slow / 20.0 + s_fast * 19.0 / 20.0
+        cpu_baseline = {"value": 1.0 / per_seq_step, "unit": "tokens/s per attention layer", "cores": oracle.num_threads(),
+                        "kind": "oracle",
+                        "sample": f"3 of the {B} sequences (ctx {[int(c0[b]) for b in sample]}): one slow step (dense + Selector) "
+                                  "and one fast step each, scaled to the batch's mean context and to one slow step in 20",
+                        "slow_step_s_per_sequence_at_mean_ctx": s_slow, "fast_step_s_per_sequence": s_fast}
+        log(f"serving parity sample ok {parity}; oracle {s_slow:.2f}s per slow sequence, {s_fast:.4f}s per fast one")
+        del Kh, Vh
 
     for t in range(args.warmup * SEG):
         decode_step(t)
@@ -175,11 +256,15 @@ def bench_serving(args):
         "whole_run_kv_GBps": kv / wall / 1e9, "whole_run_frac_of_8TBps": kv / wall / 1e9 / HBM_PEAK_GBS,
         "all_fast_step_stage_us": {"gather": gather_us, "merge": ms[1] / max(cnt[1], 1) * 1e3},
         "us_per_decode_step_per_layer": wall * 1e6 / (n_t * NL),
+        "parity_sample": parity,
         "device_status": sfi.sfi_device_status(ctx.handle),  # 0: no device-side input had to be clamped
-        "cpu_baseline": None,
+        "cpu_baseline": cpu_baseline,
     }
-    _emit(res)
+    res["roofline"]["traffic_source"] = "not measured in this run (counters need the profiler); no committed counter profile of this workload"
     ctx.close()
+    del Ks, Vs, q_all, graph
+    torch.cuda.empty_cache()
+    return res
 
 
 def bench_retention(args):
@@ -245,8 +330,8 @@ def bench_retention(args):
                      "traffic": None},
         "table": rows, "device_status": sfi.sfi_device_status(ctx.handle), "cpu_baseline": None,
     }
-    _emit(res)
     ctx.close()
+    return res
 
 
 def main():
@@ -254,7 +339,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=8, help="timed refresh segments (16 decode steps each)")
     ap.add_argument("--warmup", type=int, default=2, help="untimed refresh segments")
-    ap.add_argument("--workload", choices=sorted(WORKLOADS) + ["serving", "retention"], default="llama8b",
+    ap.add_argument("--workload", choices=sorted(WORKLOADS) + ["serving", "retention"], default=None,
                     help="llama8b (the baseline's metric workload), long, cot: slow+fast mix on a fixed schedule; "
                          "serving: ragged batch-32 mix with per-sequence modes; retention: sparse vs dense kernel "
                          "latency at KV length 16K")
@@ -294,9 +379,30 @@ def main():
         sys.exit(2)
 
     if args.workload == "serving":
-        return bench_serving(args)
+        return _emit(bench_serving(args))
     if args.workload == "retention":
-        return bench_retention(args)
+        return _emit(bench_retention(args))
+    if args.workload is not None:
+        return _emit(bench_mix(args))
+    # Default run: the metric's workload in full, then short runs of the other stated configurations.
+    import copy
+    args.workload = "llama8b"
+    res = bench_mix(args)
+    others = {}
+    for name in ("long", "cot", "serving"):
+        a = copy.copy(args)
+        a.workload, a.steps, a.warmup, a.layers, a.ctx, a.batch = name, 2, 1, 0, 0, 0
+        log(f"--- workload {name} (short run: {a.steps} timed + {a.warmup} warm-up steps)")
+        r = bench_serving(a) if name == "serving" else bench_mix(a)
+        others[name] = {k: r[k] for k in ("value", "unit", "ms_per_step", "steps", "warmup", "config", "roofline", "kernels",
+                                            "us_per_decode_step_per_layer", "parity_sample", "device_status", "cpu_baseline",
+                                            "whole_run_frac_of_8TBps", "all_fast_step_stage_us") if k in r}
+    res["workloads"] = others
+    _emit(res)
+
+
+def bench_mix(args):
+    """A fixed-schedule slow+fast mix (WORKLOADS): returns the result object."""
     wl = WORKLOADS[args.workload]
     SEG = wl["seg"]
     args.ctx = args.ctx or wl["ctx"]
@@ -575,11 +681,36 @@ def main():
         torch.cuda.synchronize()
         return ea.elapsed_time(eb) / (reps * NL)
 
+    def graph_avg_ms(fn, reps):
+        """The same average with the reps x NL launches captured into one HIP graph and replayed: no host call sits
+        between two launches, so launches shorter than the host's launch rate are timed correctly too."""
+        for l in range(NL):
+            fn(l, step_p)
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            g.capture_begin()
+            for r in range(reps):
+                for l in range(NL):
+                    fn(l, step_p + r)
+            g.capture_end()
+        torch.cuda.current_stream().wait_stream(side)
+        g.replay()
+        torch.cuda.synchronize()
+        ea, eb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ea.record()
+        g.replay()
+        eb.record()
+        torch.cuda.synchronize()
+        return ea.elapsed_time(eb) / (reps * NL)
+
     slow_ms = stage_avg_ms(slow, 2)
     fast_ms = stage_avg_ms(fast, 8)
     fast_bracketed_us = float(fast_ms[0] * 1e3)
     if fast_ms[1] == 0.0:  # the fast step is a single kernel (merge on board): time it without the event pair per launch
-        fast_ms[0] = stream_avg_ms(fast, 8)
+        fast_ms[0] = graph_avg_ms(fast, 8)
     L_mid = L0 + step_p
     dense_bytes = B * Hkv * L_mid * d * 2 * 2
     nsel_mean = float(torch.stack(nsels).float().mean())
@@ -592,21 +723,36 @@ def main():
     seg_fast_ms = fast_ms[0] * (SEG - 1)
     fast_kernel = "compact" if compact else "gather"
     dominant = fast_kernel if seg_fast_ms > seg_dense_ms else "dense"
-    traffic = None  # HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one
-    pmc_path = os.path.join(ROOT, "profiles", "hbm_traffic_llama8b.txt")
-    if os.path.exists(pmc_path) and args.workload == "llama8b" and args.ctx == 32768 and args.batch == 4:
-        prof = json.load(open(pmc_path))
-        for key in (f"attn_{dominant}_stream_kernel", f"attn_{dominant}_kernel"):
-            if key in prof:
-                traffic = prof[key].get("hbm_bytes_per_launch")
-                break
+    # HBM bytes per launch: from the committed counter profile of this workload, if it was taken on these kernel sources
+    traffic, traffic_source = None, "not measured in this run (counters need the profiler); no committed counter profile of this workload"
+    if args.workload == "llama8b" and args.ctx == 32768 and args.batch == 4 and not compact:
+        traffic, traffic_source = committed_traffic("attn_gather_stream_kernel" if dominant != "dense" else "attn_dense_kernel")
+    # The floor of the fast-step launch: its memory skeleton (same grid, scalars, indices and row loads, same record
+    # hand-over, no arithmetic), timed the same way, and the shorter chains underneath it.
+    floor = None
+    if not compact and not args.page_size:
+        def skeleton(variant):
+            return lambda l, step: sfi.sfi_fast_step_floor(h, q_all[step, l], Ks[l], Vs[l], sels[l], nsels[l], w.budget, rs_d,
+                                                            ctx_d, outs[l], variant)
+        floor = {"loads_and_record_handover_us": float(graph_avg_ms(skeleton(1), 8) * 1e3),
+                 "loads_only_us": float(graph_avg_ms(skeleton(0), 8) * 1e3),
+                 "scalars_and_indices_only_us": float(graph_avg_ms(skeleton(4), 8) * 1e3),
+                 "bare_launch_us": float(graph_avg_ms(skeleton(8), 8) * 1e3)}
+        fast(0, step_p)  # leave real outputs behind
     roof = {
         "bound": "hbm", "kernel": f"sfi::attn_{dominant}_kernel",
         "achieved": fast_gbs if dominant != "dense" else dense_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": (fast_gbs if dominant != "dense" else dense_gbs) / HBM_PEAK_GBS, "traffic": traffic,
+        "traffic_source": traffic_source,
         "algorithmic_bytes_per_launch": fast_bytes if dominant != "dense" else dense_bytes,
         "us_per_launch": float((fast_ms[0] if dominant != "dense" else slow_ms[0]) * 1e3),
     }
+    if floor is not None and dominant != "dense":
+        # what the launch shape costs with the matrix and vector units idle, and how close the kernel is to it
+        roof["floor_us"] = floor["loads_and_record_handover_us"]
+        roof["frac_of_floor"] = floor["loads_and_record_handover_us"] / roof["us_per_launch"]
+        roof["floor_frac_of_peak"] = fast_bytes / (floor["loads_and_record_handover_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS
+        roof["floor_without_handover_frac_of_peak"] = fast_bytes / (floor["loads_only_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS
     dsp, fsp = sfi.sfi_query_splits(h)
     # SFI_GUARD_* bits the kernels raised since the contexts were created: 0 = no length, count, stored index
     # or block id of the run had to be clamped
@@ -639,6 +785,7 @@ def main():
             "slow_step_stage_us": {n: float(slow_ms[i] * 1e3) for i, n in enumerate(sfi.binding.STAGE_NAMES)
                                    if i < 6 or (compact and n == "reorg")},
             "fast_step_stage_us": {n: float(fast_ms[i] * 1e3) for i, n in enumerate(sfi.binding.STAGE_NAMES[:2])},
+            "fast_step_floor_us": floor,
         },
         "us_per_decode_step_per_layer": total_s * 1e6 / (K_seg * SEG * NL),
         "gpu_event_ms": gpu_ms,
@@ -647,9 +794,11 @@ def main():
         "device_status": device_status,
         "cpu_baseline": cpu_baseline,
     }
-    print(json.dumps(res))
     for c in ring:
         c.close()
+    del Ks, Vs, K0, V0, q_all
+    torch.cuda.empty_cache()
+    return res
 
 
 if __name__ == "__main__":

@@ -370,6 +370,23 @@ int sfi_plan_splits(const sfi_ctx* ctx, int32_t max_len, int32_t sel_stride, int
 #define SFI_GUARD_BLOCK 8   /* a block-table entry covering rows [0, ctx_len[b]) was outside [0, n_blocks) */
 int sfi_device_status(sfi_ctx* ctx, int32_t* flags, int32_t clear, void* stream);
 
+/*
+ * Memory skeleton of the fast step -- a measurement aid for benchmarks, not part of the path.  Takes the arguments of
+ * sfi_fast_step and launches its grid with its loads but none of its arithmetic; `out` receives no meaningful values.
+ * variant:
+ *   bit 0      also run the record hand-over of the real launch (LDS combine, device-scope record stores, arrival
+ *              counter, merge by the pair's last workgroup);
+ *   bit 1      every wave requests the rows of all its tiles at once, straight into LDS, instead of walking them through
+ *              one register buffer (at most nine tiles per workgroup: the split is made finer if need be, SFI_EUNSUPPORTED
+ *              if that is not enough; not together with bit 0);
+ *   bits 2-3   how far down the chain of dependent loads the launch goes: 0 = all of it (the three per-step scalars and the
+ *              indices, then the K and V rows); 1 = scalars and indices only; 2 = nothing (an empty grid of the same shape).
+ * Flat caches only.  The time of this launch is the floor the fast-step kernel of the same shape is held against.
+ */
+int sfi_fast_step_floor(sfi_ctx* ctx, const void* q, const void* K, const void* V, const int32_t* sel_idx,
+                        const int32_t* n_sel, int32_t sel_stride, const int32_t* recent_start,
+                        const int32_t* ctx_len, void* out, int32_t variant, void* stream);
+
 /* Launch geometry of the last call (for reports): split workgroups per (sequence, KV head). */
 int sfi_query_splits(const sfi_ctx* ctx, int32_t* dense_splits, int32_t* fast_splits);
 

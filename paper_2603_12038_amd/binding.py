@@ -42,7 +42,7 @@ _lib: Optional[C.CDLL] = None
 
 EXPORTS = ("sfi_workspace_bytes", "sfi_create", "sfi_set_block_table", "sfi_destroy", "sfi_strerror", "sfi_slow_step", "sfi_slow_attn",
            "sfi_slow_select", "sfi_evidence_add", "sfi_evidence_select", "sfi_dense_attn",
-           "sfi_fast_step", "sfi_fast_step_static", "sfi_reorg", "sfi_fast_step_compact", "sfi_mixed_step", "sfi_trigger", "sfi_advance", "sfi_set_profiling", "sfi_stage_times",
+           "sfi_fast_step", "sfi_fast_step_static", "sfi_fast_step_floor", "sfi_reorg", "sfi_fast_step_compact", "sfi_mixed_step", "sfi_trigger", "sfi_advance", "sfi_set_profiling", "sfi_stage_times",
            "sfi_set_tuning", "sfi_plan_splits", "sfi_device_status", "sfi_query_splits")
 
 
@@ -81,6 +81,8 @@ def load_library() -> C.CDLL:
     lib.sfi_fast_step.argtypes = [vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
     lib.sfi_fast_step_static.restype = C.c_int
     lib.sfi_fast_step_static.argtypes = [C.POINTER(SfiConfig), vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
+    lib.sfi_fast_step_floor.restype = C.c_int
+    lib.sfi_fast_step_floor.argtypes = [vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, i32, vp]
     lib.sfi_reorg.restype = C.c_int
     lib.sfi_reorg.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, vp, vp, i64, i64, i32, vp]
     lib.sfi_fast_step_compact.restype = C.c_int
@@ -195,6 +197,14 @@ def sfi_fast_step_static(cfg: SfiConfig, q, K, V, sel_idx, n_sel, sel_stride, re
     _check(load_library().sfi_fast_step_static(C.byref(cfg), _ptr(q), _ptr(K), _ptr(V), _ptr(sel_idx), _ptr(n_sel),
                                                sel_stride, _ptr(recent_start), _ptr(ctx_len), _ptr(out),
                                                _stream(stream)), "sfi_fast_step_static")
+
+
+def sfi_fast_step_floor(ctx, q, K, V, sel_idx, n_sel, sel_stride, recent_start, ctx_len, out, variant: int, stream=None) -> None:
+    """Memory skeleton of the fast step (measurement aid): variant bit 0 = with the record hand-over, bit 1 = all of a
+    wave's rows requested at once into LDS, bits 2-3 = 1: scalars and indices only, 2: the bare launch."""
+    _check(load_library().sfi_fast_step_floor(ctx, _ptr(q), _ptr(K), _ptr(V), _ptr(sel_idx), _ptr(n_sel), sel_stride,
+                                              _ptr(recent_start), _ptr(ctx_len), _ptr(out), variant, _stream(stream)),
+           "sfi_fast_step_floor")
 
 
 def sfi_reorg(ctx, K, V, sel_idx, n_sel, sel_stride, ctx_len, is_slow, Kc, Vc, stream=None) -> None:

@@ -624,6 +624,39 @@ int sfi_fast_step(sfi_ctx* x, const void* q, const void* K, const void* V, const
                       x->ws.part, kSlotCap, x->ws.arrive, x->ws.guard, x->ws.guard, kMaxSplits);
 }
 
+// Memory skeleton of the fast step (measurement aid): the launch plan of sfi_fast_step, no arithmetic.
+int sfi_fast_step_floor(sfi_ctx* x, const void* q, const void* K, const void* V, const int32_t* sel_idx,
+                        const int32_t* n_sel, int32_t sel_stride, const int32_t* recent_start,
+                        const int32_t* ctx_len, void* out, int32_t variant, void* stream) {
+  const int rc = check_fast(x, q, K, V, sel_idx, n_sel, sel_stride, recent_start, ctx_len, out);
+  if (rc != SFI_OK) return rc;
+  if (variant < 0 || variant > 15 || x->table != nullptr) return SFI_EUNSUPPORTED;
+  const bool tail = (variant & 1) != 0, burst = (variant & 2) != 0;
+  const int depth = variant >> 2;
+  if ((tail && burst) || depth > 2 || (depth != 0 && (tail || burst))) return SFI_EUNSUPPORTED;
+  AttnArgs a;
+  fill_attn(x, &a, q, K, V, ctx_len);
+  a.recent_start = recent_start;
+  a.sel_idx = sel_stride > 0 ? sel_idx : x->ws.guard;
+  a.n_sel = n_sel;
+  a.sel_stride = sel_stride;
+  a.n_split = fast_splits_for(x, sel_stride, &a.pipelined);
+  const int tiles = (x->cfg.n_sink + sel_stride + x->cfg.recent + kTile - 1) / kTile;
+  int tpw = (tiles + a.n_split - 1) / a.n_split;
+  if (burst) {  // the workgroup's tiles must fit its LDS (nine tiles of 16 KB)
+    while (tpw > 9 && a.n_split < kMaxSplits) {
+      ++a.n_split;
+      tpw = (tiles + a.n_split - 1) / a.n_split;
+    }
+    if (tpw > 9) return SFI_EUNSUPPORTED;
+  }
+  x->last_fast_splits = a.n_split;
+  if (tail && a.n_split == 1) a.out_direct = (float*)out;
+  else if (tail) { a.out_merge = (float*)out; a.arrive = x->ws.arrive; }
+  SFI_TRY(launch_attn_gather_floor(a, x->cfg.batch, a.n_split, tail, burst, tpw, depth, (hipStream_t)stream));
+  return SFI_OK;
+}
+
 // ---- the fast step for callers that cannot allocate ------------------------------------------------------
 // Split records and arrival counters live in a file-scope device array instead of a caller's workspace.
 namespace {

@@ -414,17 +414,29 @@ __device__ __forceinline__ void tile_math(Tile& T, const bf16x8 (&qreg)[4], floa
 }
 
 // Device-scope accesses: visible to / from every compute unit of the device whatever L2 it sits behind,
-// without a fence (records that one workgroup hands to another inside a launch).
-__device__ __forceinline__ void store_device(float* p, float v) {
-  __hip_atomic_store(reinterpret_cast<uint32_t*>(p), __float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+// without a fence (records that one workgroup hands to another inside a launch).  They go through a buffer
+// descriptor, 16 bytes at a time: the records of one (b, h) pair as a raw buffer
+// (byte offsets, out-of-range accesses dropped by the hardware), every access with the device-scope cache policy.
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+constexpr int kScopeDevice = 16;  // cache-policy bit sc1 of the buffer instructions
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t pair_records(float* base, int bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(base, 0, bytes, 0x00020000);
 }
-__device__ __forceinline__ void store_device2(float* p, float v0, float v1) {  // 8-byte aligned
-  const uint64_t u = (uint64_t)__float_as_uint(v0) | ((uint64_t)__float_as_uint(v1) << 32);
-  __hip_atomic_store(reinterpret_cast<uint64_t*>(p), u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+__device__ __forceinline__ void store_device4(__amdgpu_buffer_rsrc_t r, int byte_off, float4 v) {
+  __builtin_amdgcn_raw_buffer_store_b128(u32x4_t{__float_as_uint(v.x), __float_as_uint(v.y), __float_as_uint(v.z), __float_as_uint(v.w)},
+                                         r, byte_off, 0, kScopeDevice);
 }
-__device__ __forceinline__ float2 load_device2(const float* p) {  // 8-byte aligned
-  const uint64_t u = __hip_atomic_load(reinterpret_cast<const uint64_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  return make_float2(__uint_as_float((uint32_t)u), __uint_as_float((uint32_t)(u >> 32)));
+__device__ __forceinline__ void store_device2(__amdgpu_buffer_rsrc_t r, int byte_off, float v0, float v1) {
+  __builtin_amdgcn_raw_buffer_store_b64(u32x2_t{__float_as_uint(v0), __float_as_uint(v1)}, r, byte_off, 0, kScopeDevice);
+}
+__device__ __forceinline__ float4 load_device4(__amdgpu_buffer_rsrc_t r, int byte_off) {
+  const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, kScopeDevice);
+  return make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
+}
+__device__ __forceinline__ float2 load_device2(__amdgpu_buffer_rsrc_t r, int byte_off) {
+  const u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(r, byte_off, 0, kScopeDevice);
+  return make_float2(__uint_as_float(v.x), __uint_as_float(v.y));
 }
 
 // Merge inside the attention kernel.  Called by every thread of every workgroup of a (b, h) pair after
@@ -435,6 +447,7 @@ __device__ __forceinline__ float2 load_device2(const float* p) {  // 8-byte alig
 // and puts the counter back to zero.  Nothing waits on anything, and no cache is written back or
 // invalidated as a whole (a device-scope fence costs tens of microseconds here).
 // One thread per (head, four output dims); records eight at a time, all loads of the eight in flight.
+template <int NW = kWaves>  // waves of the calling workgroup
 __device__ __forceinline__ void finish_pair(const float* part, int64_t head0, int G, int n_wgs, uint32_t* arrive,
                                             float* out, bool out_bf16, int slot_cap) {
   const int tid = threadIdx.x;
@@ -446,19 +459,21 @@ __device__ __forceinline__ void finish_pair(const float* part, int64_t head0, in
   __syncthreads();
   if (s_before != (uint32_t)(n_wgs - 1)) return;
   if (tid == 0) __hip_atomic_store(arrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  for (int idx = tid; idx < G * (kHeadDim / 4); idx += kAttnThreads) {
+  const __amdgpu_buffer_rsrc_t R = pair_records(const_cast<float*>(part) + head0 * slot_cap * kPartStride,
+                                                G * slot_cap * kPartStride * (int)sizeof(float));
+  for (int idx = tid; idx < G * (kHeadDim / 4); idx += NW * 64) {
     const int hh = idx >> 5, c = idx & 31;
-    const float* P = part + (head0 + hh) * slot_cap * kPartStride;
+    const int P = hh * slot_cap * kPartStride * (int)sizeof(float);  // byte offset of the head's records
     float M = kNeg, Z = 0.f;
     float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int s0 = 0; s0 < n_wgs; s0 += 8) {
-      float2 ml[8], ra[8], rb[8];
+      float2 ml[8];
+      float4 r4[8];
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        const float* rec = P + (int64_t)min(s0 + i, n_wgs - 1) * kPartStride;
-        ml[i] = load_device2(rec);
-        ra[i] = load_device2(rec + 4 + 4 * c);
-        rb[i] = load_device2(rec + 6 + 4 * c);
+        const int rec = P + min(s0 + i, n_wgs - 1) * kPartStride * (int)sizeof(float);
+        ml[i] = load_device2(R, rec);
+        r4[i] = load_device4(R, rec + (4 + 4 * c) * (int)sizeof(float));
       }
       float Mn = M;
 #pragma unroll
@@ -473,7 +488,7 @@ __device__ __forceinline__ void finish_pair(const float* part, int64_t head0, in
       for (int i = 0; i < 8; ++i) {
         const float wgt = fast_exp2(ml[i].x - Mn);
         Z += wgt * ml[i].y;
-        o.x += wgt * ra[i].x; o.y += wgt * ra[i].y; o.z += wgt * rb[i].x; o.w += wgt * rb[i].y;
+        o.x += wgt * r4[i].x; o.y += wgt * r4[i].y; o.z += wgt * r4[i].z; o.w += wgt * r4[i].w;
       }
       M = Mn;
     }
@@ -764,20 +779,36 @@ __global__ __launch_bounds__(kAttnThreads, BIG ? 1 : 2) void attn_dense_kernel(c
   report_guard(a.guard, bad);
 }
 
-// With out != nullptr the workgroup is the only one of its (b, h) pair: it writes the normalised
-// attention output O / l straight to out[b, head, :] and no record (no merge kernel follows).
-// With out_merge != nullptr the record goes out in device-scope stores and the pair's last workgroup to
-// finish merges the records into out_merge[b, head, :] (finish_pair; no merge kernel follows).
-__device__ __forceinline__ void write_wg_record(float* part, int64_t head0, int G, int slot, const f32x4 (&acc)[8],
-                                                float m_run, float l_run, float* out, float* out_merge = nullptr,
-                                                uint32_t* arrive = nullptr, int n_split = 1, bool out_bf16 = false,
-                                                int slot_cap = kSlotCap) {
+// Where a fast-step workgroup's result goes.
+struct WgOut {
+  float* out_direct;   // the workgroup is the only one of its (b, h) pair: it writes O / l straight to out[b, head, :]
+  float* out_merge;    // or: records go out in device-scope stores and the pair's last workgroup merges them into this
+  uint32_t* arrive;    //   (finish_pair); arrive counts the pair's workgroups that have sent theirs
+  float* part;         // the records (with neither pointer above: a merge launch follows)
+  int n_split, slot_cap;
+  bool out_bf16;
+};
+__device__ __forceinline__ WgOut wg_out_of(const AttnArgs& a, int bh) {
+  WgOut o;
+  o.out_direct = a.out_direct;
+  o.out_merge = a.out_merge;
+  o.arrive = a.arrive != nullptr ? a.arrive + bh : nullptr;
+  o.part = a.part;
+  o.n_split = a.n_split;
+  o.slot_cap = a.slot_cap;
+  o.out_bf16 = a.out_bf16 != 0;
+  return o;
+}
+// The four waves' partial results combined through LDS, then sent where WgOut says.
+template <int NW = kWaves, int HMAX = 16>  // waves of the workgroup; query heads the reduction buffer has room for (>= G)
+__device__ __forceinline__ void write_wg_record(const WgOut& o, int64_t head0, int G, int slot, const f32x4 (&acc)[8],
+                                                float m_run, float l_run) {
   const int tid = threadIdx.x;
   const int lane = tid & 63, w = tid >> 6;
   const int jg = lane >> 4, n = lane & 15;
-  __shared__ float s_m[kWaves][16];
-  __shared__ float s_l[kWaves][16];
-  __shared__ float s_red[kWaves][16][kHeadDim];
+  __shared__ float s_m[NW][16];
+  __shared__ float s_l[NW][16];
+  __shared__ __align__(16) float s_red[NW][HMAX][kHeadDim];
   if (lane < 16) {
     s_m[w][lane] = m_run;
     s_l[w][lane] = l_run;
@@ -789,7 +820,7 @@ __device__ __forceinline__ void write_wg_record(float* part, int64_t head0, int 
     if (hh < G) {
       float M = s_m[0][hh];
 #pragma unroll
-      for (int ww = 1; ww < kWaves; ++ww) M = fmaxf(M, s_m[ww][hh]);
+      for (int ww = 1; ww < NW; ++ww) M = fmaxf(M, s_m[ww][hh]);
       const float f = fast_exp2(s_m[w][hh] - M);
       float* dst = &s_red[w][hh][n * 8];
       *reinterpret_cast<float4*>(dst) = make_float4(acc[0][i] * f, acc[1][i] * f, acc[2][i] * f, acc[3][i] * f);
@@ -797,49 +828,50 @@ __device__ __forceinline__ void write_wg_record(float* part, int64_t head0, int 
     }
   }
   __syncthreads();
-  if (out != nullptr) {  // block-uniform
-    for (int idx = tid; idx < G * kHeadDim; idx += kAttnThreads) {
+  if (o.out_direct != nullptr) {  // block-uniform
+    for (int idx = tid; idx < G * kHeadDim; idx += NW * 64) {
       const int hh = idx >> 7, dim = idx & 127;
       float M = s_m[0][hh];
 #pragma unroll
-      for (int ww = 1; ww < kWaves; ++ww) M = fmaxf(M, s_m[ww][hh]);
+      for (int ww = 1; ww < NW; ++ww) M = fmaxf(M, s_m[ww][hh]);
       float ls = 0.f, sum = 0.f;
 #pragma unroll
-      for (int ww = 0; ww < kWaves; ++ww) {
+      for (int ww = 0; ww < NW; ++ww) {
         ls += s_l[ww][hh] * fast_exp2(s_m[ww][hh] - M);
         sum += s_red[ww][hh][dim];
       }
-      store_out(out, (head0 + hh) * kHeadDim + dim, ls > 0.f ? sum / ls : 0.f, out_bf16);
+      store_out(o.out_direct, (head0 + hh) * kHeadDim + dim, ls > 0.f ? sum / ls : 0.f, o.out_bf16);
     }
     return;
   }
+  const bool tail = o.out_merge != nullptr;  // block-uniform
   // slot_cap: records each query head has room for (kSlotCap in a caller's workspace, fewer in the static scratch)
-  const int64_t rec0 = (head0 * slot_cap + slot) * kPartStride;
-  const bool tail = out_merge != nullptr;  // block-uniform
-  for (int idx = tid; idx < G * kHeadDim; idx += kAttnThreads) {
-    const int hh = idx >> 7, dim = idx & 127;
-    float s = s_red[0][hh][dim];
+  float* const pair_base = o.part + head0 * o.slot_cap * kPartStride;
+  const __amdgpu_buffer_rsrc_t R = pair_records(pair_base, G * o.slot_cap * kPartStride * (int)sizeof(float));
+  for (int idx = tid; idx < G * (kHeadDim / 4); idx += NW * 64) {  // one thread per (head, four dims): 16-byte stores
+    const int hh = idx >> 5, c = idx & 31;
+    float4 s = *reinterpret_cast<const float4*>(&s_red[0][hh][4 * c]);
 #pragma unroll
-    for (int ww = 1; ww < kWaves; ++ww) s += s_red[ww][hh][dim];
-    float* dst = part + rec0 + (int64_t)hh * slot_cap * kPartStride + 4 + dim;
-    if (tail) store_device(dst, s);
-    else *dst = s;
+    for (int ww = 1; ww < NW; ++ww) {
+      const float4 t = *reinterpret_cast<const float4*>(&s_red[ww][hh][4 * c]);
+      s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+    }
+    const int off = (hh * o.slot_cap + slot) * kPartStride + 4 + 4 * c;  // in floats, from the pair's first record
+    if (tail) store_device4(R, off * (int)sizeof(float), s);
+    else *reinterpret_cast<float4*>(pair_base + off) = s;
   }
   if (tid < G) {
     float M = s_m[0][tid];
 #pragma unroll
-    for (int ww = 1; ww < kWaves; ++ww) M = fmaxf(M, s_m[ww][tid]);
+    for (int ww = 1; ww < NW; ++ww) M = fmaxf(M, s_m[ww][tid]);
     float ls = 0.f;
 #pragma unroll
-    for (int ww = 0; ww < kWaves; ++ww) ls += s_l[ww][tid] * fast_exp2(s_m[ww][tid] - M);
-    float* r = part + rec0 + (int64_t)tid * slot_cap * kPartStride;
-    if (tail) {
-      store_device2(r, M, ls);
-    } else {
-      *reinterpret_cast<float2*>(r) = make_float2(M, ls);
-    }
+    for (int ww = 0; ww < NW; ++ww) ls += s_l[ww][tid] * fast_exp2(s_m[ww][tid] - M);
+    const int off = (tid * o.slot_cap + slot) * kPartStride;
+    if (tail) store_device2(R, off * (int)sizeof(float), M, ls);
+    else *reinterpret_cast<float2*>(pair_base + off) = make_float2(M, ls);
   }
-  if (tail) finish_pair(part, head0, G, n_split, arrive, out_merge, out_bf16, slot_cap);
+  if (tail) finish_pair<NW>(o.part, head0, G, o.n_split, o.arrive, o.out_merge, o.out_bf16, o.slot_cap);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -847,6 +879,7 @@ __device__ __forceinline__ void write_wg_record(float* part, int64_t head0, int 
 // ------------------------------------------------------------------------------------------------
 template <bool PAGED, bool WIDE>
 __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_kernel(const AttnArgs a) {
+  constexpr int NW = kWaves;
   const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   if (a.is_slow != nullptr && a.is_slow[b] != 0) return;
   const int tid = threadIdx.x;
@@ -855,7 +888,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_kernel(const Attn
   const int G = a.G;
   const int bh = b * a.Hkv + h;
   const int64_t head0 = (int64_t)b * a.Hq + h * G;
-  const int first = slot * kWaves + w, step = a.n_split * kWaves;
+  const int first = slot * NW + w, step = a.n_split * NW;
   // The step's three scalars are requested together, ahead of everything else: read one by one where
   // they are used, the wait for the first would hold back the requests for the others (a round trip each).
   const int L_in = a.ctx_len[b], n_sel_in = a.n_sel[bh], rs_in = a.recent_start[b];
@@ -909,8 +942,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_kernel(const Attn
   }
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
-  write_wg_record(a.part, head0, G, slot, acc, m_run, l_run, a.out_direct, a.out_merge,
-                  a.arrive != nullptr ? a.arrive + bh : nullptr, a.n_split, a.out_bf16 != 0, a.slot_cap);
+  write_wg_record(wg_out_of(a, bh), head0, G, slot, acc, m_run, l_run);
   report_guard(a.guard, W.bad);  // last: the way to the record and the merge is the launch's critical path
 }
 
@@ -1050,9 +1082,181 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(con
   }
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
-  write_wg_record(a.part, head0, G, slot, acc, m_run, l_run, a.out_direct, a.out_merge,
-                  a.arrive != nullptr ? a.arrive + bh : nullptr, a.n_split, a.out_bf16 != 0, a.slot_cap);
+  write_wg_record(wg_out_of(a, bh), head0, G, slot, acc, m_run, l_run);
   report_guard(a.guard, W.bad);  // last: the way to the record and the merge is the launch's critical path
+}
+
+// ------------------------------------------------------------------------------------------------
+// Memory skeleton of the fast step -- a measurement aid, not part of the path.  Same grid, same three
+// scalars, same index loads and the same row loads as the gather kernels, but no arithmetic: what
+// arrives is folded into one word per lane.  It answers what a launch of this shape costs when the
+// matrix and vector units do nothing, i.e. the floor the real kernel can be held against.
+//   TAIL   the workgroup's record goes through the same LDS combine, device-scope record stores,
+//          arrival counter and last-workgroup merge as in the real kernel (the numbers are junk);
+//          without it every workgroup ends with one plain 4-byte store.
+//   BURST  instead of walking its tiles with one register buffer (K half and V half refilled as the
+//          real loop does), a wave requests the rows of all its tiles at once, straight into LDS
+//          (global_load_lds, 16 bytes per lane), and waits once: the most requests in flight the
+//          launch shape allows.  The workgroup owns tiles [slot * tpw, (slot + 1) * tpw) of the list,
+//          wave w the tiles w, w + 4, ... of that range; tpw * 16 KB of dynamic LDS.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t fold16(const uint4& v) { return v.x ^ v.y ^ v.z ^ v.w; }
+
+//   depth  1: stop after the scalars and indices; 2: load nothing at all (the cost of the bare launch).
+template <bool WIDE, bool TAIL, bool BURST>
+__global__ __launch_bounds__(kAttnThreads, BURST ? 1 : 3) void attn_gather_floor_kernel(const AttnArgs a, int tpw, int depth) {
+  extern __shared__ uint4 s_rows[];  // BURST: [tpw][16 instructions][64 lanes]
+  const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, w = tid >> 6;
+  const int jg = lane >> 4, n = lane & 15;
+  const int G = a.G;
+  const int bh = b * a.Hkv + h;
+  const int64_t head0 = (int64_t)b * a.Hq + h * G;
+  uint32_t fold = 0u;
+  if (!TAIL && !BURST && depth == 2) {  // wave-uniform: the bare launch
+    if (lane == 0) reinterpret_cast<uint32_t*>(a.part)[((head0 * a.slot_cap + slot) * kPartStride) + w] = (uint32_t)slot;
+    return;
+  }
+  const int L_in = a.ctx_len[b], n_sel_in = a.n_sel[bh], rs_in = a.recent_start[b];
+  ListWalk W;
+  W.sel = a.sel_idx + (int64_t)bh * a.sel_stride;
+  W.sel_cap = max((int)a.sel_stride - 1, 0);
+  W.n_sink = a.n_sink;
+  W.bad = 0;
+  Rows R;
+  R.Kb = reinterpret_cast<const char*>(a.K + b * a.k_sb + h * a.k_sh);
+  R.Vb = reinterpret_cast<const char*>(a.V + b * a.v_sb + h * a.v_sh);
+  R.k_st = (uint32_t)a.k_st * 2u;
+  R.v_st = (uint32_t)a.v_st * 2u;
+  R.k_lane = k_lane_of<WIDE>(jg, n);
+  R.v_lane = n * 16;
+  R.jg = jg;
+  R.n = n;
+  if (!TAIL && !BURST && depth == 1) {  // wave-uniform: scalars and the first tile's indices, nothing else
+    const int first = slot * kWaves + w;
+    const int sA = W.sel_at_nonempty(first * kTile + n), sB = W.sel_at_nonempty(first * kTile + 16 + n);
+    fold = (uint32_t)(L_in ^ n_sel_in ^ rs_in ^ sA ^ sB);
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) fold ^= __shfl_xor(fold, d);
+    if (lane == 0) reinterpret_cast<uint32_t*>(a.part)[((head0 * a.slot_cap + slot) * kPartStride) + w] = fold;
+    return;
+  }
+  if (BURST) {
+    // indices of all of this wave's tiles first (rows n and 16 + n of each), then the scalars
+    constexpr int kMaxT = 4;  // tiles per wave: tpw <= 16
+    int sA[kMaxT], sB[kMaxT];
+#pragma unroll
+    for (int k = 0; k < kMaxT; ++k) {
+      const int p0 = (slot * tpw + w + kWaves * k) * kTile;
+      sA[k] = W.sel_at_nonempty(p0 + n);
+      sB[k] = W.sel_at_nonempty(p0 + 16 + n);
+    }
+    const int L = guarded_len(L_in, a.len_cap, W.bad);
+    W.set_counts(L, n_sel_in, rs_in, (int)a.sel_stride);
+    const int nT = (W.N + kTile - 1) / kTile;
+#pragma unroll
+    for (int k = 0; k < kMaxT; ++k) {
+      const int lt = w + kWaves * k;            // tile within the workgroup's range
+      const int t = slot * tpw + lt;
+      if (lt < tpw && t < nT) {                 // wave-uniform
+        const int p0 = t * kTile;
+        const int ra = W.row_of(p0 + n, sA[k]), rb = W.row_of(p0 + 16 + n, sB[k]);
+        uint4* dst = s_rows + (size_t)lt * 16 * 64;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {           // instruction i: rows 4 i .. 4 i + 3 of the tile, 16 lanes x 16 bytes each
+          const int row = __shfl(i < 4 ? ra : rb, (4 * i + jg) & 15);  // resolved by the lane that holds that position
+          const char* gk = R.Kb + (size_t)((uint32_t)row * R.k_st + (uint32_t)n * 16u);
+          const char* gv = R.Vb + (size_t)((uint32_t)row * R.v_st + (uint32_t)n * 16u);
+          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gk,
+                                           (__attribute__((address_space(3))) void*)(dst + i * 64), 16, 0, 0);
+          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gv,
+                                           (__attribute__((address_space(3))) void*)(dst + (8 + i) * 64), 16, 0, 0);
+        }
+      }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): every row of this wave has landed in LDS
+#pragma unroll
+    for (int k = 0; k < kMaxT; ++k) {
+      const int lt = w + kWaves * k;
+      const int t = slot * tpw + lt;
+      if (lt < tpw && t < nT) {
+        const uint4* src = s_rows + (size_t)lt * 16 * 64;
+        for (int i = 0; i < 16; ++i) fold ^= fold16(src[i * 64 + lane]);
+      }
+    }
+  } else {
+    const int first = slot * kWaves + w, step = a.n_split * kWaves;
+    const int pstep = step * kTile;
+    const int p_first = first * kTile;
+    const int sA = W.sel_at_nonempty(p_first + n), sB = W.sel_at_nonempty(p_first + 16 + n);
+    const int L = guarded_len(L_in, a.len_cap, W.bad);
+    W.set_counts(L, n_sel_in, rs_in, (int)a.sel_stride);
+    Tile T;
+    const int nT = (W.N + kTile - 1) / kTile;
+    const int K = first < nT ? (nT - first + step - 1) / step : 0;
+    int ra = W.row_of(p_first + n, sA), rb = W.row_of(p_first + 16 + n, sB);
+    __builtin_amdgcn_sched_barrier(0);
+    issue_k_rows<uint32_t, WIDE>(T, R, ra, rb);
+    __builtin_amdgcn_sched_barrier(0);
+    int sAn = W.sel_at_nonempty(p_first + pstep + n), sBn = W.sel_at_nonempty(p_first + pstep + 16 + n);
+    __builtin_amdgcn_sched_barrier(0);
+    issue_v_rows<uint32_t, WIDE>(T, R, ra, rb);
+    __builtin_amdgcn_sched_barrier(0);
+    for (int k = 0; k + 1 < K; ++k) {
+      const int pn = p_first + (k + 1) * pstep;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) fold ^= fold16(T.ka[i]) ^ fold16(T.kb[i]);   // the K half is consumed ...
+      ra = W.row_of(pn + n, sAn);
+      rb = W.row_of(pn + 16 + n, sBn);
+      issue_k_rows<uint32_t, WIDE>(T, R, ra, rb);                              // ... and refilled,
+      sAn = W.sel_at_nonempty(pn + pstep + n);
+      sBn = W.sel_at_nonempty(pn + pstep + 16 + n);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) fold ^= fold16(T.v[i]);                      // then the V half
+      issue_v_rows<uint32_t, WIDE>(T, R, ra, rb);
+    }
+    if (K > 0) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) fold ^= fold16(T.ka[i]) ^ fold16(T.kb[i]);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) fold ^= fold16(T.v[i]);
+    }
+  }
+  if (TAIL) {
+    f32x4 acc[8];
+    const float v = (float)(fold & 0xffu);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = f32x4{v, v, v, v};
+    write_wg_record(wg_out_of(a, bh), head0, G, slot, acc, 0.f, 1.f);
+  } else {
+    fold ^= __shfl_xor(fold, 32);
+    if (lane == 0) reinterpret_cast<uint32_t*>(a.part)[((head0 * a.slot_cap + slot) * kPartStride) + w] = fold;
+  }
+  report_guard(a.guard, W.bad);
+}
+
+hipError_t launch_attn_gather_floor(const AttnArgs& a, int B, int n_slots, int tail, int burst, int tpw, int depth, hipStream_t s) {
+  const dim3 grid(n_slots, a.Hkv, B);
+  const size_t lds = burst ? (size_t)tpw * 16 * 64 * sizeof(uint4) : 0;
+#define SFI_FLOOR(WIDE, TAIL, BURST)                                                                                   \
+  do {                                                                                                                 \
+    if (lds > 0 && hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_gather_floor_kernel<WIDE, TAIL, BURST>),   \
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)            \
+      return hipGetLastError();                                                                                        \
+    hipLaunchKernelGGL((attn_gather_floor_kernel<WIDE, TAIL, BURST>), grid, dim3(kAttnThreads), lds, s, a, tpw, depth);       \
+  } while (0)
+  const bool wide = a.G <= 8;
+  if (wide && tail && burst) SFI_FLOOR(true, true, true);
+  else if (wide && tail) SFI_FLOOR(true, true, false);
+  else if (wide && burst) SFI_FLOOR(true, false, true);
+  else if (wide) SFI_FLOOR(true, false, false);
+  else if (tail && burst) SFI_FLOOR(false, true, true);
+  else if (tail) SFI_FLOOR(false, true, false);
+  else if (burst) SFI_FLOOR(false, false, true);
+  else SFI_FLOOR(false, false, false);
+#undef SFI_FLOOR
+  return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1156,8 +1360,7 @@ __global__ __launch_bounds__(kAttnThreads, PAGED ? 2 : 3) void attn_compact_kern
   }
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
-  write_wg_record(a.part, head0, G, slot, acc, m_run, l_run, a.out_direct, a.out_merge,
-                  a.arrive != nullptr ? a.arrive + bh : nullptr, a.n_split, a.out_bf16 != 0, a.slot_cap);
+  write_wg_record(wg_out_of(a, bh), head0, G, slot, acc, m_run, l_run);
   report_guard(a.guard, bad);
 }
 
@@ -1325,10 +1528,10 @@ static void launch_gather_t(const AttnArgs& a, dim3 grid, hipStream_t s) {
   if (a.pipelined) {
     if (a.table != nullptr) hipLaunchKernelGGL((attn_gather_stream_kernel<true, WIDE>), grid, dim3(kAttnThreads), 0, s, a);
     else hipLaunchKernelGGL((attn_gather_stream_kernel<false, WIDE>), grid, dim3(kAttnThreads), 0, s, a);
-  } else {
-    if (a.table != nullptr) hipLaunchKernelGGL((attn_gather_kernel<true, WIDE>), grid, dim3(kAttnThreads), 0, s, a);
-    else hipLaunchKernelGGL((attn_gather_kernel<false, WIDE>), grid, dim3(kAttnThreads), 0, s, a);
+    return;
   }
+  if (a.table != nullptr) hipLaunchKernelGGL((attn_gather_kernel<true, WIDE>), grid, dim3(kAttnThreads), 0, s, a);
+  else hipLaunchKernelGGL((attn_gather_kernel<false, WIDE>), grid, dim3(kAttnThreads), 0, s, a);
 }
 hipError_t launch_attn_gather(const AttnArgs& a, int B, int n_slots, hipStream_t s) {
   const dim3 grid(n_slots, a.Hkv, B);

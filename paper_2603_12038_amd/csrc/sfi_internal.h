@@ -195,6 +195,7 @@ hipError_t launch_attn_dense(const AttnArgs& a, int B, int n_slots, hipStream_t 
 hipError_t launch_attn_compact(const AttnArgs& a, int B, int n_slots, hipStream_t s);
 hipError_t launch_reorg(const ReorgArgs& a, int B, int rows, hipStream_t s);
 hipError_t launch_attn_gather(const AttnArgs& a, int B, int n_slots, hipStream_t s);
+hipError_t launch_attn_gather_floor(const AttnArgs& a, int B, int n_slots, int tail, int burst, int tpw, int depth, hipStream_t s);
 hipError_t launch_merge(const MergeArgs& a, int B, hipStream_t s);
 hipError_t launch_sel_clear(const SelArgs& a, int B, hipStream_t s);
 hipError_t launch_sel_score(const SelArgs& a, int B, int n_seg, hipStream_t s);
