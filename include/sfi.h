@@ -195,13 +195,25 @@ int sfi_slow_select(sfi_ctx* ctx, const int32_t* ctx_len, int32_t max_len, int32
  *   sfi_evidence_select  the Selector on the accumulated evidence mu = (1/W) * sum over the n_added queries:
  *                        mode 0 ranks mu, mode 1 takes f = mu^(1/alpha) through prior, fusion and refinements
  *                        (key norms from the last sfi_evidence_add).  -> sel_idx, n_sel.
- * Every added query must see the same allowed set J, i.e. the same ctx_len[] / max_len in every call (for the
- * tail of a causal prefill block: recent >= W, so that no window query is masked anywhere in J).
+ * Every added query must see the same allowed set J, i.e. the same ctx_len[] / max_len in every call; for window
+ * queries that sit before the end of the context and are masked inside J, see sfi_evidence_add_causal.
  * sfi_evidence_add with out == NULL is the evidence-only pass: V is not read (and may be NULL), no attention
  * output is written -- half the cache traffic, for callers whose prefill kernel has the outputs already.
  */
 int sfi_evidence_add(sfi_ctx* ctx, const void* q, const void* K, const void* V, const int32_t* ctx_len,
                      int32_t max_len, void* out, int32_t first, void* stream);
+/*
+ * The same for a window query under the causal mask ("masked attention logit" of Eq. window_logits): the window's last
+ * W queries of a prefill block sit at rows L - W .. L - 1 of a context of L = ctx_len[b] rows, and query tau sees rows
+ * [0, q_len[b]) only, q_len[b] = L - W + tau + 1 (its own row included).  q_len: DEVICE int32 [B], 0 <= q_len[b] <= ctx_len[b]
+ * (values outside are brought into that range).  ctx_len[] is the same in every call of the window and defines J; this
+ * query's softmax (Eq. selector_pt) runs over the part of J it sees, it adds p = 0 elsewhere, and out (if given) is its
+ * attention over the rows it sees.  The mean of Eq. selector_mu still divides by the n_added given to sfi_evidence_select.
+ * With recent >= W every query sees all of J and the call equals sfi_evidence_add.  In mode 1 the key norms are those
+ * exposed by the last call, so the window's last query (q_len = ctx_len) must be added last.
+ */
+int sfi_evidence_add_causal(sfi_ctx* ctx, const void* q, const void* K, const void* V, const int32_t* ctx_len,
+                            const int32_t* q_len, int32_t max_len, void* out, int32_t first, void* stream);
 int sfi_evidence_select(sfi_ctx* ctx, int32_t n_added, const int32_t* ctx_len, int32_t max_len, int32_t budget,
                         int32_t* sel_idx, int32_t* n_sel, void* stream);
 

@@ -41,7 +41,7 @@ class SfiConfig(C.Structure):
 _lib: Optional[C.CDLL] = None
 
 EXPORTS = ("sfi_workspace_bytes", "sfi_create", "sfi_set_block_table", "sfi_destroy", "sfi_strerror", "sfi_slow_step", "sfi_slow_attn",
-           "sfi_slow_select", "sfi_evidence_add", "sfi_evidence_select", "sfi_dense_attn",
+           "sfi_slow_select", "sfi_evidence_add", "sfi_evidence_add_causal", "sfi_evidence_select", "sfi_dense_attn",
            "sfi_fast_step", "sfi_fast_step_static", "sfi_fast_step_floor", "sfi_reorg", "sfi_fast_step_compact", "sfi_mixed_step", "sfi_trigger", "sfi_advance", "sfi_set_profiling", "sfi_stage_times",
            "sfi_set_tuning", "sfi_plan_splits", "sfi_device_status", "sfi_query_splits")
 
@@ -73,6 +73,8 @@ def load_library() -> C.CDLL:
     lib.sfi_slow_select.argtypes = [vp, vp, i32, i32, vp, vp, vp]
     lib.sfi_evidence_add.restype = C.c_int
     lib.sfi_evidence_add.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, vp]
+    lib.sfi_evidence_add_causal.restype = C.c_int
+    lib.sfi_evidence_add_causal.argtypes = [vp, vp, vp, vp, vp, vp, i32, vp, i32, vp]
     lib.sfi_evidence_select.restype = C.c_int
     lib.sfi_evidence_select.argtypes = [vp, i32, vp, i32, i32, vp, vp, vp]
     lib.sfi_dense_attn.restype = C.c_int
@@ -174,6 +176,11 @@ def sfi_slow_select(ctx, ctx_len, max_len, budget, sel_idx, n_sel, stream=None) 
 def sfi_evidence_add(ctx, q, K, V, ctx_len, max_len, out, first: bool, stream=None) -> None:
     _check(load_library().sfi_evidence_add(ctx, _ptr(q), _ptr(K), _ptr(V), _ptr(ctx_len), max_len, _ptr(out),
                                            1 if first else 0, _stream(stream)), "sfi_evidence_add")
+
+
+def sfi_evidence_add_causal(ctx, q, K, V, ctx_len, q_len, max_len, out, first: bool, stream=None) -> None:
+    _check(load_library().sfi_evidence_add_causal(ctx, _ptr(q), _ptr(K), _ptr(V), _ptr(ctx_len), _ptr(q_len), max_len,
+                                                  _ptr(out), 1 if first else 0, _stream(stream)), "sfi_evidence_add_causal")
 
 
 def sfi_evidence_select(ctx, n_added: int, ctx_len, max_len, budget, sel_idx, n_sel, stream=None) -> None:

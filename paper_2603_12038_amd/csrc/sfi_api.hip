@@ -453,7 +453,7 @@ int sfi_dense_attn(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   set_dense_bounds(x, &a, ml);
   x->last_dense_splits = a.n_split;
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
-  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, a.n_split * kWaves, 0, 0, nullptr, 0, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha, ml, x->cfg.out_bf16};
+  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, a.n_split * kWaves, 0, 0, nullptr, 0, x->G, ctx_len, nullptr, x->cfg.n_sink, x->cfg.recent, x->alpha, ml, x->cfg.out_bf16};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
 }
@@ -462,9 +462,10 @@ namespace {
 // First half of a slow step: dense attention with the evidence (y over J, Selector state cleared,
 // J-only softmax statistics) left in the workspace.
 int slow_attn_impl(sfi_ctx* x, const void* q, const void* K, const void* V, const int32_t* ctx_len, int ml,
-                   float* out, hipStream_t st, bool merge_later = false) {
+                   float* out, hipStream_t st, bool merge_later = false, const int32_t* q_len = nullptr) {
   AttnArgs a;
   fill_attn(x, &a, q, K, V, ctx_len);
+  a.q_len = q_len;
   a.n_split = dense_splits_for(x, ml, false);
   set_dense_bounds(x, &a, ml);
   a.logits = x->ws.logits;
@@ -477,7 +478,7 @@ int slow_attn_impl(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
   x->selector_ran = 0;  // fresh evidence, Selector state cleared by the launch above
   if (merge_later) return SFI_OK;  // the Selector's scoring launch merges
-  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, a.n_split * kWaves, 0, 0, x->ws.jstat, a.n_split * kWaves, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha, ml, x->cfg.out_bf16};
+  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, a.n_split * kWaves, 0, 0, x->ws.jstat, a.n_split * kWaves, x->G, ctx_len, q_len, x->cfg.n_sink, x->cfg.recent, x->alpha, ml, x->cfg.out_bf16};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
 }
@@ -533,31 +534,44 @@ int sfi_slow_select(sfi_ctx* x, const int32_t* ctx_len, int32_t max_len, int32_t
   return run_selector(x, sa, ml, (hipStream_t)stream);
 }
 
-int sfi_evidence_add(sfi_ctx* x, const void* q, const void* K, const void* V, const int32_t* ctx_len,
-                     int32_t max_len, void* out_, int32_t first, void* stream) {
-  float* out = (float*)out_;
+namespace {
+int evidence_add_impl(sfi_ctx* x, const void* q, const void* K, const void* V, const int32_t* ctx_len, const int32_t* q_len,
+                      int32_t max_len, float* out, int32_t first, hipStream_t st) {
   // out == nullptr: evidence only -- V is not read (and may be null), no attention output is produced
   const bool evidence_only = out == nullptr;
   if (x == nullptr || q == nullptr || K == nullptr || ctx_len == nullptr || (!evidence_only && V == nullptr))
     return SFI_EINVAL;
-  if (misaligned(q, 16) || misaligned(K, 16) || misaligned(ctx_len, 4) ||
+  if (misaligned(q, 16) || misaligned(K, 16) || misaligned(ctx_len, 4) || misaligned(q_len, 4) ||
       (!evidence_only && (misaligned(V, 16) || misaligned(out, 16))))
     return SFI_EALIGN;
   if (x->cfg.page_size != 0 && x->table == nullptr) return SFI_EINVAL;  // paged cache without a block table
   int rc;
   int ml;
   if ((rc = resolve_max_len(x, max_len, &ml)) != SFI_OK) return rc;
-  hipStream_t st = (hipStream_t)stream;
   CallRecord call_record(x);
-  if ((rc = slow_attn_impl(x, q, K, V, ctx_len, ml, out, st)) != SFI_OK) return rc;
+  if ((rc = slow_attn_impl(x, q, K, V, ctx_len, ml, out, st, false, q_len)) != SFI_OK) return rc;
   SelArgs sa;
   fill_sel(x, &sa, ctx_len, ml, nullptr, 0, x->last_dense_splits, nullptr, nullptr);
   sa.accum_first = first != 0;
-  const int nJ = ml - x->cfg.recent - x->cfg.n_sink;
+  sa.q_len = q_len;
+  // a query under the causal mask may see up to `recent` more positions of its own, shorter context as allowed set
+  const int nJ = ml - (q_len != nullptr ? 0 : x->cfg.recent) - x->cfg.n_sink;
   int n_seg = nJ > 0 ? (nJ + kSelSeg - 1) / kSelSeg : 1;
   if (n_seg > x->ws.n_seg_cap) n_seg = x->ws.n_seg_cap;
   { StageTimer t(x, st, SFI_STAGE_SCORE); SFI_TRY(launch_sel_accum(sa, x->cfg.batch, n_seg, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
+}
+}  // namespace
+
+int sfi_evidence_add(sfi_ctx* x, const void* q, const void* K, const void* V, const int32_t* ctx_len,
+                     int32_t max_len, void* out, int32_t first, void* stream) {
+  return evidence_add_impl(x, q, K, V, ctx_len, nullptr, max_len, (float*)out, first, (hipStream_t)stream);
+}
+
+int sfi_evidence_add_causal(sfi_ctx* x, const void* q, const void* K, const void* V, const int32_t* ctx_len,
+                            const int32_t* q_len, int32_t max_len, void* out, int32_t first, void* stream) {
+  if (q_len == nullptr) return SFI_EINVAL;
+  return evidence_add_impl(x, q, K, V, ctx_len, q_len, max_len, (float*)out, first, (hipStream_t)stream);
 }
 
 int sfi_evidence_select(sfi_ctx* x, int32_t n_added, const int32_t* ctx_len, int32_t max_len, int32_t budget,
@@ -598,7 +612,7 @@ int fast_step_on(sfi_ctx* x, const void* q, const void* K, const void* V, const 
   else if (x->tail_merge) { a.out_merge = out; a.arrive = arrive; }
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_gather(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
   if (a.n_split == 1 || a.out_merge != nullptr) return SFI_OK;
-  MergeArgs m{part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1, nullptr, 0, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha, x->cfg.max_ctx, x->cfg.out_bf16};
+  MergeArgs m{part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1, nullptr, 0, x->G, ctx_len, nullptr, x->cfg.n_sink, x->cfg.recent, x->alpha, x->cfg.max_ctx, x->cfg.out_bf16};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
 }
@@ -802,7 +816,7 @@ int sfi_fast_step_compact(sfi_ctx* x, const void* q, const void* Kc, const void*
   else if (x->tail_merge) { a.out_merge = out; a.arrive = x->ws.arrive; }
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_compact(a, x->cfg.batch, a.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
   if (a.n_split == 1 || a.out_merge != nullptr) return SFI_OK;
-  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1, nullptr, 0, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha, x->cfg.max_ctx, x->cfg.out_bf16};
+  MergeArgs m{x->ws.part, out, nullptr, x->cfg.n_q_heads, 0, a.n_split, 1, nullptr, 0, x->G, ctx_len, nullptr, x->cfg.n_sink, x->cfg.recent, x->alpha, x->cfg.max_ctx, x->cfg.out_bf16};
   { StageTimer t(x, st, SFI_STAGE_MERGE); SFI_TRY(launch_merge(m, x->cfg.batch, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
 }
@@ -854,7 +868,7 @@ int sfi_mixed_step(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(d, x->cfg.batch, d.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
   x->selector_ran = 0;
   if (!merge_in_score) {
-    MergeArgs m{x->ws.part, out, is_slow, x->cfg.n_q_heads, d.n_split * kWaves, fast_done ? 0 : f.n_split, 2, x->ws.jstat, d.n_split * kWaves, x->G, ctx_len, x->cfg.n_sink, x->cfg.recent, x->alpha, ml, x->cfg.out_bf16};
+    MergeArgs m{x->ws.part, out, is_slow, x->cfg.n_q_heads, d.n_split * kWaves, fast_done ? 0 : f.n_split, 2, x->ws.jstat, d.n_split * kWaves, x->G, ctx_len, nullptr, x->cfg.n_sink, x->cfg.recent, x->alpha, ml, x->cfg.out_bf16};
     StageTimer t(x, st, SFI_STAGE_MERGE);
     SFI_TRY(launch_merge(m, x->cfg.batch, st));
     if (!t.stop()) return SFI_ELAUNCH;

@@ -602,17 +602,18 @@ __global__ __launch_bounds__(kAttnThreads, BIG ? 1 : 2) void attn_dense_kernel(c
   bf16x8 qreg[4];
   load_q(qreg, a.q, head0, G, jg, n);
   int bad = 0;
-  const int L = guarded_len(a.ctx_len[b], a.len_cap, bad);
+  int L, recent;  // a window query under the causal mask sees a shorter context with what is left of the recent window
+  window_view(a.q_len, b, guarded_len(a.ctx_len[b], a.len_cap, bad), a.recent, L, recent);
   if (slot == 0 && a.hist1 != nullptr) {  // fresh Selector state for this (b, h)
     uint32_t* hh = a.hist1 + (int64_t)bh * kHist1Bins;
     for (int i = tid; i < kHist1Bins; i += kAttnThreads) hh[i] = 0u;
     if (tid < kStateWords) a.state[(int64_t)bh * kStateWords + tid] = 0u;
   }
-  const int NJ = max(0, L - a.recent - a.n_sink);
+  const int NJ = max(0, L - recent - a.n_sink);
   const int nTJ = (NJ + kTile - 1) / kTile;
   const int rJ_max = a.n_sink + NJ - 1;
   const int nS = min(a.n_sink, L);
-  const int rs = min(max(a.n_sink, L - a.recent), L);
+  const int rs = min(max(a.n_sink, L - recent), L);
   const int NS = nS + (L - rs);
   const int nTS = (NS + kTile - 1) / kTile;
   const int nT = nTJ + nTS;
@@ -1445,9 +1446,10 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(const MergeArgs a)
   const bool dense = a.mode == 0 || (a.mode == 2 && a.is_slow[b]);
   if (dense) {
     // dense records: slots_slow waves' J records, then one record per wave that owned sink / recent tiles
-    const int L = min(max(a.ctx_len[b], 0), a.len_cap);  // the dense launch's clamp
+    int L, recent;
+    window_view(a.q_len, b, min(max(a.ctx_len[b], 0), a.len_cap), a.recent, L, recent);  // the dense launch's view
     const int nS = min(a.n_sink, L);
-    const int rs = min(max(a.n_sink, L - a.recent), L);
+    const int rs = min(max(a.n_sink, L - recent), L);
     const int nTS = (nS + (L - rs) + kTile - 1) / kTile;
     n_slots = a.slots_slow + min(a.slots_slow, nTS);
   }

@@ -49,6 +49,20 @@ enum SelState { ST_CAND = 0, ST_BIN1 = 1, ST_K1 = 2, ST_TAU = 3, ST_TAKE = 4, ST
 constexpr uint32_t kFlagAll = 1u;   // budget >= |J|: take every position of J
 constexpr uint32_t kFlagNone = 2u;  // nothing to select
 
+// A window query under the causal mask (Eq. window_logits): the query sits at row q_len - 1 of a context that ends
+// at row L_end - 1, sees rows [0, q_len) only, and its evidence covers the part of the allowed set
+// J = [n_sink, L_end - recent) it sees.  For the kernels that is a dense step over a context of q_len rows whose
+// recent window is what is left of the real one in front of the query: rec = max(0, recent - (L_end - q_len)).
+// q_len == nullptr: an ordinary step (L = L_end, rec = recent).
+__device__ __forceinline__ void window_view(const int32_t* q_len, int b, int L_end, int recent, int& L, int& rec) {
+  L = L_end;
+  rec = recent;
+  if (q_len != nullptr) {
+    L = min(max(q_len[b], 0), L_end);
+    rec = max(0, recent - (L_end - L));
+  }
+}
+
 struct Workspace {
   float* part;        // [B*Hq][kSlotCap][kPartStride]
   float* logits;      // [B*Hq][ld_pos]   J-relative positions
@@ -79,6 +93,7 @@ struct AttnArgs {
   const uint16_t* V;
   int64_t k_sb, k_sh, k_st, v_sb, v_sh, v_st;
   const int32_t* ctx_len;
+  const int32_t* q_len;          // dense mode, nullptr or: rows each sequence's query sees (window query under the causal mask)
   const int32_t* recent_start;   // gather mode
   const int32_t* sel_idx;        // gather mode
   const int32_t* n_sel;          // gather mode
@@ -148,6 +163,7 @@ struct MergeArgs {
   float2* jstat;                       // dense records: also leave the J-only softmax statistics here (may be null)
   int32_t n_j, G;                      // records that cover J; query heads per KV head
   const int32_t* ctx_len;              // dense records: the number of sink / recent records follows from it
+  const int32_t* q_len;                // the dense launch's (see window_view)
   int32_t n_sink, recent;
   float alpha;                         // power-mean exponent of the evidence (Eq. selector_mu)
   int32_t len_cap;                     // the clamp the dense launch applied to ctx_len
@@ -163,6 +179,7 @@ struct SelArgs {
   uint32_t* state;
   uint32_t* segcnt;
   const int32_t* ctx_len;
+  const int32_t* q_len;    // accumulation of a window query under the causal mask (see window_view), else nullptr
   const uint8_t* is_slow;
   int32_t* sel_idx;
   int32_t* n_sel;

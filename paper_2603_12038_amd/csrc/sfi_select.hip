@@ -160,7 +160,13 @@ template <bool ACCUM>
 __global__ __launch_bounds__(kSelThreads) void sel_score_kernel(const SelArgs a) {
   const int seg = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
-  const Problem pb = problem_of(a, b);
+  Problem pb = problem_of(a, b);
+  int n_all = pb.nJ;  // ACCUM under the causal mask: |J| of the whole window; pb.nJ becomes the part this query sees
+  if (ACCUM && a.q_len != nullptr) {
+    int Lq, rec;
+    window_view(a.q_len, b, min(max(a.ctx_len[b], 0), a.len_cap), a.recent, Lq, rec);
+    pb.nJ = max(0, Lq - rec - a.n_sink);
+  }
   const int tid = threadIdx.x;
   const int bh = b * a.Hkv + h;
   const int G = a.G;
@@ -170,6 +176,11 @@ __global__ __launch_bounds__(kSelThreads) void sel_score_kernel(const SelArgs a)
     return;
   }
   const int p_lo = seg * kSelSeg;
+  if (ACCUM && a.accum_first && n_all > pb.nJ) {  // the first query of a window starts the accumulator: zero where it sees nothing
+    float* mu0 = a.mu + (int64_t)bh * a.ld_pos;
+    // (from the next whole quad on: the quad that straddles the edge is written by the thread that owns it)
+    for (int p = max(p_lo, (pb.nJ + 3) & ~3) + tid; p < min(p_lo + kSelSeg, n_all); p += kSelThreads) mu0[p] = 0.f;
+  }
   if (p_lo >= pb.nJ) return;
 
   __shared__ float s_jM[16], s_jc[16];
@@ -246,7 +257,10 @@ __global__ __launch_bounds__(kSelThreads) void sel_score_kernel(const SelArgs a)
     if (ACCUM) {
       float4* mp = reinterpret_cast<float4*>(a.mu + (int64_t)bh * a.ld_pos + p);
       float4 m4 = a.accum_first ? make_float4(0.f, 0.f, 0.f, 0.f) : *mp;
-      m4.x += f0; m4.y += f1; m4.z += f2; m4.w += f3;
+      m4.x += f0;                       // positions of the quad past the part this query sees take nothing from it
+      m4.y += p + 1 < pb.nJ ? f1 : 0.f;
+      m4.z += p + 2 < pb.nJ ? f2 : 0.f;
+      m4.w += p + 3 < pb.nJ ? f3 : 0.f;
       *mp = m4;
       continue;
     }

@@ -204,3 +204,59 @@ def test_windowed_evidence(oracle, mode, alpha, W, with_out):
         check_selection(sel.cpu().numpy(), nsel.cpu().numpy(), sel_ref, nsel_ref, z, ctx, w.n_sink, w.recent, w.budget)
     finally:
         r.close()
+
+
+@pytest.mark.parametrize("mode,alpha,W,recent", [(0, 0.5, 16, 4), (1, 0.5, 16, 4), (0, 1.0, 6, 0), (1, 1.0, 5, 2),
+                                                 (0, 0.5, 16, 40), (1, 0.7, 3, 1)])
+def test_windowed_evidence_under_the_causal_mask(oracle, mode, alpha, W, recent):
+    """The tail of a prefill block as the observation window (Eq. window_logits with masked logits): window query
+    tau sits at row L - W + tau and sees rows up to its own.  With recent < W the earlier queries miss the end of J:
+    their softmax runs over the part of J they see.  sfi_evidence_add_causal per query (its `out` is its attention
+    over the rows it sees) and one sfi_evidence_select, against the oracle's Selector on the W * G vectors with
+    their visible lengths.  recent >= W: every query sees all of J (the unmasked case)."""
+    import torch
+    import paper_2603_12038_amd as sfi
+    from helpers import i32_dev, to_dev
+
+    sp, d = _params(alpha=alpha)
+    if mode == 0:
+        sp, d = dataclasses.replace(sp, mode=0), None
+    w = syn.make_tiny(L0=3100, steps=max(8, W), budget=96, recent=recent, n_support=16, B=2, Hq=8, Hkv=2)
+    w.L0 = np.array([3100, 1500], np.int32)
+    G = w.Hq // w.Hkv
+    # high-norm key rows in the stretch of J that only the later window queries see, so that the mask decides what is picked
+    for b in range(w.B):
+        lo, hi = int(w.L0[b]) - W, int(w.L0[b]) - recent
+        if hi > lo:
+            w.K[b, :, lo:hi] = syn.f32_to_bf16_bits(syn.bf16_bits_to_f32(w.K[b, :, lo:hi]) * np.float32(5.0))
+    r = Runner(w, selector=d, alpha=alpha)
+    try:
+        _step(f"causal window mode={mode} alpha={alpha} W={W} recent={recent}")
+        ctx = w.ctx_len(0)
+        ctx_d = i32_dev(ctx)
+        qs = [w.q(t) for t in range(W)]
+        sel = torch.full((w.B, w.Hkv, w.budget), -7, dtype=torch.int32, device="cuda")
+        nsel = torch.full((w.B, w.Hkv), -7, dtype=torch.int32, device="cuda")
+        vis = np.zeros((w.B, w.Hkv * W * G), np.int32)
+        q_cat = np.empty((w.B, w.Hkv * W * G, w.d), np.uint16)
+        for t, q in enumerate(qs):
+            q_len = (ctx - W + t + 1).astype(np.int32)
+            r.out.fill_(float("nan"))
+            sfi.sfi_evidence_add_causal(r.ctx.handle, to_dev(q), r.K, r.V, ctx_d, i32_dev(q_len), 0, r.out, t == 0)
+            torch.cuda.synchronize()
+            check_out(r.out.cpu().numpy(), oracle.dense(q, w.K, w.V, q_len))
+            for h in range(w.Hkv):
+                q_cat[:, h * W * G + t * G:h * W * G + (t + 1) * G] = q[:, h * G:(h + 1) * G]
+                vis[:, h * W * G + t * G:h * W * G + (t + 1) * G] = q_len[:, None]
+        sfi.sfi_evidence_select(r.ctx.handle, W, ctx_d, 0, w.budget, sel, nsel)
+        torch.cuda.synchronize()
+        sel_ref, nsel_ref, z = oracle.selector(q_cat, w.K, ctx, w.budget, w.n_sink, w.recent, sp=sp, vis=vis)
+        n_exact = check_selection(sel.cpu().numpy(), nsel.cpu().numpy(), sel_ref, nsel_ref, z, ctx, w.n_sink, w.recent,
+                                  w.budget)
+        if recent < W - 1:  # the mask matters: without it the oracle ranks differently somewhere
+            sel_nomask, _, _ = oracle.selector(q_cat, w.K, ctx, w.budget, w.n_sink, w.recent, sp=sp)
+            _step(f"  sets identical {n_exact}/{w.B * w.Hkv}")
+            assert not np.array_equal(sel_nomask, sel_ref), "the case is meant to be one where the mask changes the selection"
+        assert r.sfi.sfi_device_status(r.ctx.handle) == 0
+    finally:
+        r.close()
