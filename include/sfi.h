@@ -299,6 +299,19 @@ int sfi_mixed_step(sfi_ctx* ctx, const void* q, const void* K, const void* V, co
                    void* out, int32_t* sel_idx, int32_t* n_sel, void* stream);
 
 /*
+ * The ragged mix over the two-segment layout (paper Sec. "Memory-coalesced Kernel Design and Selector Maintenance" under
+ * per-sequence modes): fast sequences read their sink and selected rows from the compact buffers (as
+ * sfi_fast_step_compact), slow sequences take a slow step and have their buffer rows refilled from the refreshed index
+ * set afterwards (Sel_i -> Reorg_i, as sfi_reorg with is_slow).  Arguments as in sfi_mixed_step and sfi_reorg;
+ * c_rows >= n_sink + budget.  Every sequence's buffers must have been filled for its current index set before its first
+ * fast step here (a step that is slow for it does that).
+ */
+int sfi_mixed_step_compact(sfi_ctx* ctx, const void* q, const void* K, const void* V, const uint8_t* is_slow,
+                           const int32_t* ctx_len, const int32_t* recent_start, int32_t max_len, int32_t budget,
+                           void* out, int32_t* sel_idx, int32_t* n_sel, void* Kc, void* Vc, int64_t c_stride_b,
+                           int64_t c_stride_h, int32_t c_rows, void* stream);
+
+/*
  * Trigger policy on the device (paper Sec. "Training-free trigger policy", Eq. trigger, and the last lines
  * of Algorithm 1), so that a decode loop needs no host decision between steps:
  *   is_slow[b]    = 1 if last_token[b] is in the trigger set, or since_slow[b] >= t_max; else 0

@@ -42,7 +42,7 @@ _lib: Optional[C.CDLL] = None
 
 EXPORTS = ("sfi_workspace_bytes", "sfi_create", "sfi_set_block_table", "sfi_destroy", "sfi_strerror", "sfi_slow_step", "sfi_slow_attn",
            "sfi_slow_select", "sfi_evidence_add", "sfi_evidence_add_causal", "sfi_evidence_select", "sfi_dense_attn",
-           "sfi_fast_step", "sfi_fast_step_static", "sfi_fast_step_floor", "sfi_reorg", "sfi_fast_step_compact", "sfi_mixed_step", "sfi_trigger", "sfi_advance", "sfi_set_profiling", "sfi_stage_times",
+           "sfi_fast_step", "sfi_fast_step_static", "sfi_fast_step_floor", "sfi_reorg", "sfi_fast_step_compact", "sfi_mixed_step", "sfi_mixed_step_compact", "sfi_trigger", "sfi_advance", "sfi_set_profiling", "sfi_stage_times",
            "sfi_set_tuning", "sfi_plan_splits", "sfi_device_status", "sfi_query_splits")
 
 
@@ -91,6 +91,8 @@ def load_library() -> C.CDLL:
     lib.sfi_fast_step_compact.argtypes = [vp, vp, vp, vp, i64, i64, i32, vp, i32, vp, vp, vp, vp, vp, vp]
     lib.sfi_mixed_step.restype = C.c_int
     lib.sfi_mixed_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
+    lib.sfi_mixed_step_compact.restype = C.c_int
+    lib.sfi_mixed_step_compact.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, i64, i64, i32, vp]
     lib.sfi_trigger.restype = C.c_int
     lib.sfi_trigger.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp]
     lib.sfi_advance.restype = C.c_int
@@ -235,6 +237,15 @@ def sfi_mixed_step(ctx, q, K, V, is_slow, ctx_len, recent_start, max_len, budget
     _check(load_library().sfi_mixed_step(ctx, _ptr(q), _ptr(K), _ptr(V), _ptr(is_slow), _ptr(ctx_len),
                                          _ptr(recent_start), max_len, budget, _ptr(out), _ptr(sel_idx),
                                          _ptr(n_sel), _stream(stream)), "sfi_mixed_step")
+
+
+def sfi_mixed_step_compact(ctx, q, K, V, is_slow, ctx_len, recent_start, max_len, budget, out, sel_idx, n_sel, Kc, Vc,
+                           stream=None) -> None:
+    assert Kc.stride() == Vc.stride() and Kc.stride(3) == 1 and Kc.stride(2) == Kc.shape[3]
+    _check(load_library().sfi_mixed_step_compact(ctx, _ptr(q), _ptr(K), _ptr(V), _ptr(is_slow), _ptr(ctx_len),
+                                                 _ptr(recent_start), max_len, budget, _ptr(out), _ptr(sel_idx),
+                                                 _ptr(n_sel), _ptr(Kc), _ptr(Vc), Kc.stride(0), Kc.stride(1), Kc.shape[2],
+                                                 _stream(stream)), "sfi_mixed_step_compact")
 
 
 def sfi_trigger(ctx, last_token, trigger_bitmap, vocab_size, t_max, since_slow, is_slow, stream=None) -> None:

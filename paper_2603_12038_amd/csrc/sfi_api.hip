@@ -764,18 +764,10 @@ int check_compact(const sfi_ctx* x, const void* Kc, const void* Vc, int64_t c_st
 }
 }  // namespace
 
-int sfi_reorg(sfi_ctx* x, const void* K, const void* V, const int32_t* sel_idx, const int32_t* n_sel,
-              int32_t sel_stride, const int32_t* ctx_len, const uint8_t* is_slow, void* Kc, void* Vc,
-              int64_t c_stride_b, int64_t c_stride_h, int32_t c_rows, void* stream) {
-  if (x == nullptr || K == nullptr || V == nullptr || sel_idx == nullptr || n_sel == nullptr || ctx_len == nullptr)
-    return SFI_EINVAL;
-  if (misaligned(K, 16) || misaligned(V, 16) || misaligned(sel_idx, 4) || misaligned(n_sel, 4) || misaligned(ctx_len, 4))
-    return SFI_EALIGN;
-  if (x->cfg.page_size != 0 && x->table == nullptr) return SFI_EINVAL;
-  int rc = check_compact(x, Kc, Vc, c_stride_b, c_stride_h, c_rows, sel_stride);
-  if (rc != SFI_OK) return rc;
-  hipStream_t st = (hipStream_t)stream;
-  CallRecord call_record(x);
+namespace {
+int reorg_on(sfi_ctx* x, const void* K, const void* V, const int32_t* sel_idx, const int32_t* n_sel, int32_t sel_stride,
+             const int32_t* ctx_len, const uint8_t* is_slow, void* Kc, void* Vc, int64_t c_stride_b, int64_t c_stride_h,
+             hipStream_t st) {
   const sfi_config& c = x->cfg;
   ReorgArgs r;
   memset(&r, 0, sizeof(r));
@@ -789,6 +781,21 @@ int sfi_reorg(sfi_ctx* x, const void* K, const void* V, const int32_t* sel_idx, 
   r.len_cap = c.max_ctx; r.n_blocks = x->n_blocks; r.guard = x->ws.guard;
   { StageTimer t(x, st, SFI_STAGE_REORG); SFI_TRY(launch_reorg(r, c.batch, c.n_sink + sel_stride, st)); if (!t.stop()) return SFI_ELAUNCH; }
   return SFI_OK;
+}
+}  // namespace
+
+int sfi_reorg(sfi_ctx* x, const void* K, const void* V, const int32_t* sel_idx, const int32_t* n_sel,
+              int32_t sel_stride, const int32_t* ctx_len, const uint8_t* is_slow, void* Kc, void* Vc,
+              int64_t c_stride_b, int64_t c_stride_h, int32_t c_rows, void* stream) {
+  if (x == nullptr || K == nullptr || V == nullptr || sel_idx == nullptr || n_sel == nullptr || ctx_len == nullptr)
+    return SFI_EINVAL;
+  if (misaligned(K, 16) || misaligned(V, 16) || misaligned(sel_idx, 4) || misaligned(n_sel, 4) || misaligned(ctx_len, 4))
+    return SFI_EALIGN;
+  if (x->cfg.page_size != 0 && x->table == nullptr) return SFI_EINVAL;
+  int rc = check_compact(x, Kc, Vc, c_stride_b, c_stride_h, c_rows, sel_stride);
+  if (rc != SFI_OK) return rc;
+  CallRecord call_record(x);
+  return reorg_on(x, K, V, sel_idx, n_sel, sel_stride, ctx_len, is_slow, Kc, Vc, c_stride_b, c_stride_h, (hipStream_t)stream);
 }
 
 int sfi_fast_step_compact(sfi_ctx* x, const void* q, const void* Kc, const void* Vc, int64_t c_stride_b,
@@ -821,18 +828,27 @@ int sfi_fast_step_compact(sfi_ctx* x, const void* q, const void* Kc, const void*
   return SFI_OK;
 }
 
-int sfi_mixed_step(sfi_ctx* x, const void* q, const void* K, const void* V, const uint8_t* is_slow,
-                   const int32_t* ctx_len, const int32_t* recent_start, int32_t max_len, int32_t budget,
-                   void* out_, int32_t* sel_idx, int32_t* n_sel, void* stream) {
-  float* out = (float*)out_;
+namespace {
+struct CompactBuffers {
+  void* Kc;
+  void* Vc;
+  int64_t stride_b, stride_h;
+  int32_t rows;
+};
+
+// The ragged mix.  cb == nullptr: fast sequences gather their rows through sel_idx; else they read the two-segment
+// layout (compact buffers + recent window in place) and the slow sequences' buffers are refilled after the Selector.
+int mixed_step_on(sfi_ctx* x, const void* q, const void* K, const void* V, const uint8_t* is_slow, const int32_t* ctx_len,
+                  const int32_t* recent_start, int32_t max_len, int32_t budget, float* out, int32_t* sel_idx,
+                  int32_t* n_sel, const CompactBuffers* cb, hipStream_t st) {
   int rc = check_common(x, q, K, V, ctx_len, out);
   if (rc != SFI_OK) return rc;
   if (is_slow == nullptr || sel_idx == nullptr || n_sel == nullptr || recent_start == nullptr) return SFI_EINVAL;
   if (budget < 0 || budget > x->cfg.max_budget) return SFI_EINVAL;
   if (misaligned(sel_idx, 4) || misaligned(n_sel, 4) || misaligned(recent_start, 4)) return SFI_EALIGN;
+  if (cb != nullptr && (rc = check_compact(x, cb->Kc, cb->Vc, cb->stride_b, cb->stride_h, cb->rows, budget)) != SFI_OK) return rc;
   int ml;
   if ((rc = resolve_max_len(x, max_len, &ml)) != SFI_OK) return rc;
-  hipStream_t st = (hipStream_t)stream;
   CallRecord call_record(x);
 
   AttnArgs d;
@@ -853,18 +869,29 @@ int sfi_mixed_step(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   f.n_sel = n_sel;
   f.sel_stride = budget;
   f.len_cap = ml;
-  f.n_split = fast_splits_for(x, budget, &f.pipelined);
+  if (cb != nullptr) {
+    f.Kc = (const uint16_t*)cb->Kc; f.Vc = (const uint16_t*)cb->Vc;
+    f.c_sb = cb->stride_b; f.c_sh = cb->stride_h; f.c_rows = cb->rows;
+    f.n_split = compact_splits_for(x, budget);
+  } else {
+    f.n_split = fast_splits_for(x, budget, &f.pipelined);
+  }
   if (f.n_split == 1) f.out_direct = out;
   else if (x->tail_merge) { f.out_merge = out; f.arrive = x->ws.arrive; }  // slow sequences' workgroups never arrive
   x->last_fast_splits = f.n_split;
-  // Fast sequences finish inside the gather launch unless their split records need the merge launch;
+  // Fast sequences finish inside their launch unless their split records need the merge launch;
   // slow sequences are merged by the first scoring launch (as in sfi_slow_step).  The merge kernel only
   // runs when the in-kernel merge is switched off (for both kinds: it skips what is already done).
   const bool fast_done = f.n_split == 1 || f.out_merge != nullptr;
   const bool merge_in_score = fast_done;
-  // the gather part reads last segment's sel rows of fast sequences; the Selector below only
-  // rewrites rows of slow sequences, so the order of the two attention launches is free.
-  { StageTimer t(x, st, SFI_STAGE_ATTN2); SFI_TRY(launch_attn_gather(f, x->cfg.batch, f.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
+  // the fast part reads last segment's sel rows (or compact rows) of fast sequences; the Selector and Reorg below
+  // only rewrite rows of slow sequences, so the order of the two attention launches is free.
+  {
+    StageTimer t(x, st, SFI_STAGE_ATTN2);
+    if (cb != nullptr) SFI_TRY(launch_attn_compact(f, x->cfg.batch, f.n_split, st));
+    else SFI_TRY(launch_attn_gather(f, x->cfg.batch, f.n_split, st));
+    if (!t.stop()) return SFI_ELAUNCH;
+  }
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(d, x->cfg.batch, d.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
   x->selector_ran = 0;
   if (!merge_in_score) {
@@ -879,7 +906,27 @@ int sfi_mixed_step(sfi_ctx* x, const void* q, const void* K, const void* V, cons
     sa.part = x->ws.part;
     sa.merge_out = out;
   }
-  return run_selector(x, sa, ml, st);
+  if ((rc = run_selector(x, sa, ml, st)) != SFI_OK) return rc;
+  if (cb == nullptr) return SFI_OK;
+  // Reorg_i for the sequences that were refreshed (Sel_i -> Reorg_i)
+  return reorg_on(x, K, V, sel_idx, n_sel, budget, ctx_len, is_slow, cb->Kc, cb->Vc, cb->stride_b, cb->stride_h, st);
+}
+}  // namespace
+
+int sfi_mixed_step(sfi_ctx* x, const void* q, const void* K, const void* V, const uint8_t* is_slow,
+                   const int32_t* ctx_len, const int32_t* recent_start, int32_t max_len, int32_t budget,
+                   void* out, int32_t* sel_idx, int32_t* n_sel, void* stream) {
+  return mixed_step_on(x, q, K, V, is_slow, ctx_len, recent_start, max_len, budget, (float*)out, sel_idx, n_sel, nullptr,
+                       (hipStream_t)stream);
+}
+
+int sfi_mixed_step_compact(sfi_ctx* x, const void* q, const void* K, const void* V, const uint8_t* is_slow,
+                           const int32_t* ctx_len, const int32_t* recent_start, int32_t max_len, int32_t budget,
+                           void* out, int32_t* sel_idx, int32_t* n_sel, void* Kc, void* Vc, int64_t c_stride_b,
+                           int64_t c_stride_h, int32_t c_rows, void* stream) {
+  const CompactBuffers cb{Kc, Vc, c_stride_b, c_stride_h, c_rows};
+  return mixed_step_on(x, q, K, V, is_slow, ctx_len, recent_start, max_len, budget, (float*)out, sel_idx, n_sel, &cb,
+                       (hipStream_t)stream);
 }
 
 int sfi_trigger(sfi_ctx* x, const int32_t* last_token, const uint32_t* trigger_bitmap, int32_t vocab_size,

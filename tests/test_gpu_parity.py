@@ -818,3 +818,48 @@ def test_selector_twice_on_the_same_evidence(oracle, tiny):
         check_selection(sel.cpu().numpy(), nsel.cpu().numpy(), sel_ref, nsel_ref, z, ctx, w.n_sink, w.recent, budget)
     check_out(r.out.cpu().numpy(), oracle.dense(q, w.K, w.V, ctx))
     assert r.sfi.sfi_device_status(r.ctx.handle) == 0
+
+
+@pytest.mark.parametrize("path", ["gather", "compact"])
+def test_ragged_decode_loop_against_the_oracles_driver(oracle, path):
+    """Algorithm 1 for five ragged sequences with their own slow/fast schedules, twelve steps, all state on the device
+    (sfi_mixed_step or sfi_mixed_step_compact + sfi_advance), against the oracle's driver: outputs of every step, the
+    state each step ran on, the index sets after it.  On the compact path the buffers of a sequence are refilled only
+    by its own slow steps; poison in the untouched rows would show in the outputs."""
+    import torch
+    import paper_2603_12038_amd as sfi
+
+    w = syn.make_serving(steps=12, B=5, Hq=16, Hkv=2, len_lo=300, len_hi=1400, budget=64, recent=32, mean_gap=4.0)
+    T = w.steps
+    g = w.slow.astype(np.uint8)
+    assert g[0].all() and 0 < g[1:].sum() < g[1:].size
+    qs = np.stack([w.q(t) for t in range(T)])
+    ref = oracle.decode_loop(qs, w.K, w.V, w.ctx_len(0), w.recent_start(0), g, w.budget, w.n_sink, w.recent)
+    r = Runner(w)
+    try:
+        B = w.B
+        ctx_d, rs_d = i32_dev(w.ctx_len(0)), i32_dev(w.recent_start(0))
+        sel_d = torch.full((B, w.Hkv, w.budget), -7, dtype=torch.int32, device="cuda")
+        nsel_d = torch.zeros((B, w.Hkv), dtype=torch.int32, device="cuda")
+        c_rows = w.n_sink + w.budget
+        Kc = to_dev(np.full((B, w.Hkv, c_rows, w.d), 0x7FC1, np.uint16))
+        Vc = to_dev(np.full((B, w.Hkv, c_rows, w.d), 0x7FC1, np.uint16))
+        for t in range(T):
+            _step(f"ragged decode loop ({path}) step {t}: slow {g[t].tolist()}")
+            flags = torch.from_numpy(g[t]).cuda()
+            assert (ctx_d.cpu().numpy() == ref["ctx_hist"][t]).all() and (rs_d.cpu().numpy() == ref["rs_hist"][t]).all()
+            r.out.fill_(float("nan"))
+            if path == "compact":
+                sfi.sfi_mixed_step_compact(r.ctx.handle, to_dev(qs[t]), r.K, r.V, flags, ctx_d, rs_d, 0, w.budget, r.out, sel_d,
+                                           nsel_d, Kc, Vc)
+            else:
+                sfi.sfi_mixed_step(r.ctx.handle, to_dev(qs[t]), r.K, r.V, flags, ctx_d, rs_d, 0, w.budget, r.out, sel_d, nsel_d)
+            torch.cuda.synchronize()
+            check_out(r.out.cpu().numpy(), ref["out"][t])
+            assert (sel_d.cpu().numpy() == ref["sel_hist"][t]).all() and (nsel_d.cpu().numpy() == ref["nsel_hist"][t]).all()
+            sfi.sfi_advance(r.ctx.handle, ctx_d, rs_d)
+        torch.cuda.synchronize()
+        assert (ctx_d.cpu().numpy() == ref["ctx_len"]).all() and (rs_d.cpu().numpy() == ref["recent_start"]).all()
+        assert r.sfi.sfi_device_status(r.ctx.handle) == 0
+    finally:
+        r.close()
