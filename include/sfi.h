@@ -116,6 +116,20 @@ typedef struct sfi_config {
   int32_t out_bf16;
 } sfi_config;
 
+/*
+ * Packed per-step descriptor (paper Sec. "Memory-coalesced Kernel Design and Selector Maintenance": the small control
+ * state of a decoding step, built once per step and read from device memory by every kernel of every layer): one
+ * 16-byte record per sequence in a DEVICE array [B] the caller owns.  sfi_step_begin fills it for the next step;
+ * sfi_mixed_step_desc runs a layer's step from it.  The caller may also write it directly (it is plain data).
+ * The block table of a paged cache is the context's (sfi_set_block_table); row b of it belongs to desc[b].
+ */
+typedef struct sfi_step_desc {
+  int32_t ctx_len;      /* rows of the sequence in the cache, the current token's included */
+  int32_t recent_start; /* first row of the recent window */
+  int32_t is_slow;      /* 1: the step is a slow step for this sequence, 0: a fast step */
+  int32_t since_slow;   /* fast steps in a row behind the sequence (state of the trigger policy) */
+} sfi_step_desc;
+
 typedef struct sfi_ctx sfi_ctx; /* opaque; host memory owned by the library */
 
 /* Bytes of device workspace a context of this shape needs (256-byte aligned base expected).
@@ -325,6 +339,25 @@ int sfi_mixed_step_compact(sfi_ctx* ctx, const void* q, const void* K, const voi
  */
 int sfi_trigger(sfi_ctx* ctx, const int32_t* last_token, const uint32_t* trigger_bitmap, int32_t vocab_size,
                 int32_t t_max, int32_t* since_slow, uint8_t* is_slow, void* stream);
+
+/*
+ * One launch per decoding step that prepares the packed descriptor for it (the state update and the trigger policy
+ * together, Algorithm 1 "Update I_recent and compute g_{t+1}"): for every sequence b
+ *   advance != 0:  desc[b].ctx_len += 1   (the token generated by the last step has joined the cache)
+ *   desc[b].recent_start = max(n_sink, ctx_len - recent)
+ *   desc[b].is_slow      = 1 if last_token[b] is in the trigger set or desc[b].since_slow >= t_max, else 0
+ *   desc[b].since_slow   = 0 if is_slow, else since_slow + 1
+ * last_token / trigger_bitmap / vocab_size as in sfi_trigger; either may be NULL (no trigger tokens: only the forced
+ * refresh after t_max fast steps).  Before the first step: ctx_len = the prompt's rows, since_slow = t_max (g_0 = 1),
+ * advance = 0.
+ */
+int sfi_step_begin(sfi_ctx* ctx, sfi_step_desc* desc, const int32_t* last_token, const uint32_t* trigger_bitmap,
+                   int32_t vocab_size, int32_t t_max, int32_t advance, void* stream);
+
+/* sfi_mixed_step with the per-sequence state read from the packed descriptor: ctx_len, recent_start and is_slow of
+ * sequence b are desc[b]'s.  Everything else as in sfi_mixed_step. */
+int sfi_mixed_step_desc(sfi_ctx* ctx, const void* q, const void* K, const void* V, const sfi_step_desc* desc,
+                        int32_t max_len, int32_t budget, void* out, int32_t* sel_idx, int32_t* n_sel, void* stream);
 
 /* State update between decode steps, on the device (paper Algorithm 1, "update I_recent"):
  * ctx_len[b] += 1;  recent_start[b] = max(n_sink, ctx_len[b] - recent). */

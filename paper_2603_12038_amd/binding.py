@@ -42,7 +42,7 @@ _lib: Optional[C.CDLL] = None
 
 EXPORTS = ("sfi_workspace_bytes", "sfi_create", "sfi_set_block_table", "sfi_destroy", "sfi_strerror", "sfi_slow_step", "sfi_slow_attn",
            "sfi_slow_select", "sfi_evidence_add", "sfi_evidence_add_causal", "sfi_evidence_select", "sfi_dense_attn",
-           "sfi_fast_step", "sfi_fast_step_static", "sfi_fast_step_floor", "sfi_reorg", "sfi_fast_step_compact", "sfi_mixed_step", "sfi_mixed_step_compact", "sfi_trigger", "sfi_advance", "sfi_set_profiling", "sfi_stage_times",
+           "sfi_fast_step", "sfi_fast_step_static", "sfi_fast_step_floor", "sfi_reorg", "sfi_fast_step_compact", "sfi_mixed_step", "sfi_mixed_step_compact", "sfi_step_begin", "sfi_mixed_step_desc", "sfi_trigger", "sfi_advance", "sfi_set_profiling", "sfi_stage_times",
            "sfi_set_tuning", "sfi_plan_splits", "sfi_device_status", "sfi_query_splits")
 
 
@@ -93,6 +93,10 @@ def load_library() -> C.CDLL:
     lib.sfi_mixed_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
     lib.sfi_mixed_step_compact.restype = C.c_int
     lib.sfi_mixed_step_compact.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, i64, i64, i32, vp]
+    lib.sfi_step_begin.restype = C.c_int
+    lib.sfi_step_begin.argtypes = [vp, vp, vp, vp, i32, i32, i32, vp]
+    lib.sfi_mixed_step_desc.restype = C.c_int
+    lib.sfi_mixed_step_desc.argtypes = [vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
     lib.sfi_trigger.restype = C.c_int
     lib.sfi_trigger.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp]
     lib.sfi_advance.restype = C.c_int
@@ -246,6 +250,17 @@ def sfi_mixed_step_compact(ctx, q, K, V, is_slow, ctx_len, recent_start, max_len
                                                  _ptr(recent_start), max_len, budget, _ptr(out), _ptr(sel_idx),
                                                  _ptr(n_sel), _ptr(Kc), _ptr(Vc), Kc.stride(0), Kc.stride(1), Kc.shape[2],
                                                  _stream(stream)), "sfi_mixed_step_compact")
+
+
+def sfi_step_begin(ctx, desc, last_token, trigger_bitmap, vocab_size, t_max, advance: bool, stream=None) -> None:
+    """desc: int32 device tensor [B, 4] = (ctx_len, recent_start, is_slow, since_slow) per sequence."""
+    _check(load_library().sfi_step_begin(ctx, _ptr(desc), _ptr(last_token), _ptr(trigger_bitmap), vocab_size, t_max,
+                                         1 if advance else 0, _stream(stream)), "sfi_step_begin")
+
+
+def sfi_mixed_step_desc(ctx, q, K, V, desc, max_len, budget, out, sel_idx, n_sel, stream=None) -> None:
+    _check(load_library().sfi_mixed_step_desc(ctx, _ptr(q), _ptr(K), _ptr(V), _ptr(desc), max_len, budget, _ptr(out),
+                                              _ptr(sel_idx), _ptr(n_sel), _stream(stream)), "sfi_mixed_step_desc")
 
 
 def sfi_trigger(ctx, last_token, trigger_bitmap, vocab_size, t_max, since_slow, is_slow, stream=None) -> None:

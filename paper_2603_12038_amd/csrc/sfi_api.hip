@@ -243,6 +243,7 @@ void fill_attn(const sfi_ctx* x, AttnArgs* a, const void* q, const void* K, cons
   a->k_sb = c.k_stride_b; a->k_sh = c.k_stride_h; a->k_st = c.k_stride_t;
   a->v_sb = c.v_stride_b; a->v_sh = c.v_stride_h; a->v_st = c.v_stride_t;
   a->ctx_len = ctx_len;
+  a->ms = 1; a->fs = 1;
   a->part = x->ws.part;
   a->slot_cap = kSlotCap;
   a->ld_pos = x->ws.ld_pos;
@@ -263,6 +264,7 @@ void fill_sel(const sfi_ctx* x, SelArgs* s, const int32_t* ctx_len, int max_len,
   s->jstat = x->ws.jstat; s->logits = x->ws.logits; s->keys = x->ws.keys; s->cand = x->ws.cand;
   s->hist1 = x->ws.hist1; s->state = x->ws.state; s->segcnt = x->ws.segcnt;
   s->ctx_len = ctx_len; s->is_slow = is_slow; s->sel_idx = sel_idx; s->n_sel = n_sel;
+  s->ms = 1; s->fs = 1;
   s->ld_pos = x->ws.ld_pos; s->n_seg_cap = x->ws.n_seg_cap;
   s->Hq = c.n_q_heads; s->Hkv = c.n_kv_heads; s->G = x->G;
   s->n_sink = c.n_sink; s->recent = c.recent; s->n_jrec = n_split * kWaves; s->budget = budget;
@@ -767,7 +769,7 @@ int check_compact(const sfi_ctx* x, const void* Kc, const void* Vc, int64_t c_st
 namespace {
 int reorg_on(sfi_ctx* x, const void* K, const void* V, const int32_t* sel_idx, const int32_t* n_sel, int32_t sel_stride,
              const int32_t* ctx_len, const uint8_t* is_slow, void* Kc, void* Vc, int64_t c_stride_b, int64_t c_stride_h,
-             hipStream_t st) {
+             hipStream_t st, int meta_stride = 1) {
   const sfi_config& c = x->cfg;
   ReorgArgs r;
   memset(&r, 0, sizeof(r));
@@ -775,6 +777,7 @@ int reorg_on(sfi_ctx* x, const void* K, const void* V, const int32_t* sel_idx, c
   r.k_sb = c.k_stride_b; r.k_sh = c.k_stride_h; r.k_st = c.k_stride_t;
   r.v_sb = c.v_stride_b; r.v_sh = c.v_stride_h; r.v_st = c.v_stride_t;
   r.sel_idx = sel_idx; r.n_sel = n_sel; r.ctx_len = ctx_len; r.is_slow = is_slow; r.sel_stride = sel_stride;
+  r.ms = meta_stride; r.fs = meta_stride == 1 ? 1 : 4 * meta_stride;
   r.Kc = (uint16_t*)Kc; r.Vc = (uint16_t*)Vc; r.c_sb = c_stride_b; r.c_sh = c_stride_h;
   r.Hkv = c.n_kv_heads; r.n_sink = c.n_sink;
   r.table = x->table; r.table_stride = x->table_stride; r.page_lg = x->page_lg; r.page_rpb = x->page_rpb;
@@ -840,7 +843,9 @@ struct CompactBuffers {
 // layout (compact buffers + recent window in place) and the slow sequences' buffers are refilled after the Selector.
 int mixed_step_on(sfi_ctx* x, const void* q, const void* K, const void* V, const uint8_t* is_slow, const int32_t* ctx_len,
                   const int32_t* recent_start, int32_t max_len, int32_t budget, float* out, int32_t* sel_idx,
-                  int32_t* n_sel, const CompactBuffers* cb, hipStream_t st) {
+                  int32_t* n_sel, const CompactBuffers* cb, hipStream_t st, int meta_stride = 1) {
+  // meta_stride 4: ctx_len, recent_start, is_slow point at the fields of a packed sfi_step_desc array
+  const int ms = meta_stride, fs = meta_stride == 1 ? 1 : 4 * meta_stride;
   int rc = check_common(x, q, K, V, ctx_len, out);
   if (rc != SFI_OK) return rc;
   if (is_slow == nullptr || sel_idx == nullptr || n_sel == nullptr || recent_start == nullptr) return SFI_EINVAL;
@@ -854,6 +859,7 @@ int mixed_step_on(sfi_ctx* x, const void* q, const void* K, const void* V, const
   AttnArgs d;
   fill_attn(x, &d, q, K, V, ctx_len);
   d.is_slow = is_slow;
+  d.ms = ms; d.fs = fs;
   d.n_split = dense_splits_for(x, ml, true);
   set_dense_bounds(x, &d, ml);
   d.logits = x->ws.logits;
@@ -864,6 +870,7 @@ int mixed_step_on(sfi_ctx* x, const void* q, const void* K, const void* V, const
   AttnArgs f;
   fill_attn(x, &f, q, K, V, ctx_len);
   f.is_slow = is_slow;
+  f.ms = ms; f.fs = fs;
   f.recent_start = recent_start;
   f.sel_idx = budget > 0 ? sel_idx : x->ws.guard;  // as in sfi_fast_step
   f.n_sel = n_sel;
@@ -895,13 +902,14 @@ int mixed_step_on(sfi_ctx* x, const void* q, const void* K, const void* V, const
   { StageTimer t(x, st, SFI_STAGE_ATTN); SFI_TRY(launch_attn_dense(d, x->cfg.batch, d.n_split, st)); if (!t.stop()) return SFI_ELAUNCH; }
   x->selector_ran = 0;
   if (!merge_in_score) {
-    MergeArgs m{x->ws.part, out, is_slow, x->cfg.n_q_heads, d.n_split * kWaves, fast_done ? 0 : f.n_split, 2, x->ws.jstat, d.n_split * kWaves, x->G, ctx_len, nullptr, x->cfg.n_sink, x->cfg.recent, x->alpha, ml, x->cfg.out_bf16};
+    MergeArgs m{x->ws.part, out, is_slow, x->cfg.n_q_heads, d.n_split * kWaves, fast_done ? 0 : f.n_split, 2, x->ws.jstat, d.n_split * kWaves, x->G, ctx_len, nullptr, x->cfg.n_sink, x->cfg.recent, x->alpha, ml, x->cfg.out_bf16, ms, fs};
     StageTimer t(x, st, SFI_STAGE_MERGE);
     SFI_TRY(launch_merge(m, x->cfg.batch, st));
     if (!t.stop()) return SFI_ELAUNCH;
   }
   SelArgs sa;
   fill_sel(x, &sa, ctx_len, ml, is_slow, budget, d.n_split, sel_idx, n_sel);
+  sa.ms = ms; sa.fs = fs;
   if (merge_in_score) {
     sa.part = x->ws.part;
     sa.merge_out = out;
@@ -909,7 +917,7 @@ int mixed_step_on(sfi_ctx* x, const void* q, const void* K, const void* V, const
   if ((rc = run_selector(x, sa, ml, st)) != SFI_OK) return rc;
   if (cb == nullptr) return SFI_OK;
   // Reorg_i for the sequences that were refreshed (Sel_i -> Reorg_i)
-  return reorg_on(x, K, V, sel_idx, n_sel, budget, ctx_len, is_slow, cb->Kc, cb->Vc, cb->stride_b, cb->stride_h, st);
+  return reorg_on(x, K, V, sel_idx, n_sel, budget, ctx_len, is_slow, cb->Kc, cb->Vc, cb->stride_b, cb->stride_h, st, meta_stride);
 }
 }  // namespace
 
@@ -927,6 +935,25 @@ int sfi_mixed_step_compact(sfi_ctx* x, const void* q, const void* K, const void*
   const CompactBuffers cb{Kc, Vc, c_stride_b, c_stride_h, c_rows};
   return mixed_step_on(x, q, K, V, is_slow, ctx_len, recent_start, max_len, budget, (float*)out, sel_idx, n_sel, &cb,
                        (hipStream_t)stream);
+}
+
+int sfi_step_begin(sfi_ctx* x, sfi_step_desc* desc, const int32_t* last_token, const uint32_t* trigger_bitmap,
+                   int32_t vocab_size, int32_t t_max, int32_t advance, void* stream) {
+  if (x == nullptr || desc == nullptr || t_max < 0) return SFI_EINVAL;
+  if (trigger_bitmap != nullptr && vocab_size < 1) return SFI_EINVAL;
+  if (misaligned(desc, 16) || misaligned(last_token, 4) || misaligned(trigger_bitmap, 4)) return SFI_EALIGN;
+  SFI_TRY(launch_step_begin(desc, last_token, trigger_bitmap, vocab_size, t_max, advance != 0, x->cfg.batch, x->cfg.n_sink,
+                            x->cfg.recent, (hipStream_t)stream));
+  return SFI_OK;
+}
+
+int sfi_mixed_step_desc(sfi_ctx* x, const void* q, const void* K, const void* V, const sfi_step_desc* desc,
+                        int32_t max_len, int32_t budget, void* out, int32_t* sel_idx, int32_t* n_sel, void* stream) {
+  if (desc == nullptr) return SFI_EINVAL;
+  if (misaligned(desc, 16)) return SFI_EALIGN;
+  static_assert(sizeof(sfi_step_desc) == 16, "four int32 per sequence");
+  return mixed_step_on(x, q, K, V, reinterpret_cast<const uint8_t*>(&desc->is_slow), &desc->ctx_len, &desc->recent_start,
+                       max_len, budget, (float*)out, sel_idx, n_sel, nullptr, (hipStream_t)stream, 4);
 }
 
 int sfi_trigger(sfi_ctx* x, const int32_t* last_token, const uint32_t* trigger_bitmap, int32_t vocab_size,

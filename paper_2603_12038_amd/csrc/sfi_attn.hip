@@ -566,7 +566,7 @@ __global__ __launch_bounds__(kAttnThreads, BIG ? 1 : 2) void attn_dense_kernel(c
   constexpr int kStash = BIG ? 2 * kStashFloats : kStashFloats;
   __shared__ float s_stash[EXPOSE != 0 ? kWaves : 1][EXPOSE != 0 ? kStash : 1];  // per-wave logits stash
   const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
+  if (a.is_slow != nullptr && a.is_slow[b * a.fs] == 0) return;
   const int tid = threadIdx.x;
   const int lane = tid & 63, w = tid >> 6;
   const int jg = lane >> 4, n = lane & 15;
@@ -603,7 +603,7 @@ __global__ __launch_bounds__(kAttnThreads, BIG ? 1 : 2) void attn_dense_kernel(c
   load_q(qreg, a.q, head0, G, jg, n);
   int bad = 0;
   int L, recent;  // a window query under the causal mask sees a shorter context with what is left of the recent window
-  window_view(a.q_len, b, guarded_len(a.ctx_len[b], a.len_cap, bad), a.recent, L, recent);
+  window_view(a.q_len, b, guarded_len(a.ctx_len[b * a.ms], a.len_cap, bad), a.recent, L, recent);
   if (slot == 0 && a.hist1 != nullptr) {  // fresh Selector state for this (b, h)
     uint32_t* hh = a.hist1 + (int64_t)bh * kHist1Bins;
     for (int i = tid; i < kHist1Bins; i += kAttnThreads) hh[i] = 0u;
@@ -882,7 +882,7 @@ template <bool PAGED, bool WIDE>
 __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_kernel(const AttnArgs a) {
   constexpr int NW = kWaves;
   const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  if (a.is_slow != nullptr && a.is_slow[b] != 0) return;
+  if (a.is_slow != nullptr && a.is_slow[b * a.fs] != 0) return;
   const int tid = threadIdx.x;
   const int lane = tid & 63, w = tid >> 6;
   const int jg = lane >> 4, n = lane & 15;
@@ -892,7 +892,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_kernel(const Attn
   const int first = slot * NW + w, step = a.n_split * NW;
   // The step's three scalars are requested together, ahead of everything else: read one by one where
   // they are used, the wait for the first would hold back the requests for the others (a round trip each).
-  const int L_in = a.ctx_len[b], n_sel_in = a.n_sel[bh], rs_in = a.recent_start[b];
+  const int L_in = a.ctx_len[b * a.ms], n_sel_in = a.n_sel[bh], rs_in = a.recent_start[b * a.ms];
 
   // ---- first round of loads, none depending on another: the selected indices of this wave's first
   // tile (read before the list length is known, clamped to the row of sel_idx), q, the scalars.
@@ -958,7 +958,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_kernel(const Attn
 template <bool PAGED, bool WIDE>
 __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(const AttnArgs a) {
   const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  if (a.is_slow != nullptr && a.is_slow[b] != 0) return;
+  if (a.is_slow != nullptr && a.is_slow[b * a.fs] != 0) return;
   const int tid = threadIdx.x;
   const int lane = tid & 63, w = tid >> 6;
   const int jg = lane >> 4, n = lane & 15;
@@ -969,7 +969,7 @@ __global__ __launch_bounds__(kAttnThreads, 3) void attn_gather_stream_kernel(con
   const int pstep = step * kTile;
   // The step's three scalars are requested together, ahead of everything else: read one by one where
   // they are used, the wait for the first would hold back the requests for the others (a round trip each).
-  const int L_in = a.ctx_len[b], n_sel_in = a.n_sel[bh], rs_in = a.recent_start[b];
+  const int L_in = a.ctx_len[b * a.ms], n_sel_in = a.n_sel[bh], rs_in = a.recent_start[b * a.ms];
 
   ListWalk W;
   W.sel = a.sel_idx + (int64_t)bh * a.sel_stride;
@@ -1119,7 +1119,7 @@ __global__ __launch_bounds__(kAttnThreads, BURST ? 1 : 3) void attn_gather_floor
     if (lane == 0) reinterpret_cast<uint32_t*>(a.part)[((head0 * a.slot_cap + slot) * kPartStride) + w] = (uint32_t)slot;
     return;
   }
-  const int L_in = a.ctx_len[b], n_sel_in = a.n_sel[bh], rs_in = a.recent_start[b];
+  const int L_in = a.ctx_len[b * a.ms], n_sel_in = a.n_sel[bh], rs_in = a.recent_start[b * a.ms];
   ListWalk W;
   W.sel = a.sel_idx + (int64_t)bh * a.sel_stride;
   W.sel_cap = max((int)a.sel_stride - 1, 0);
@@ -1270,7 +1270,7 @@ hipError_t launch_attn_gather_floor(const AttnArgs& a, int B, int n_slots, int t
 template <bool PAGED, bool WIDE>  // PAGED: the recent window is read from a paged cache (the compact buffers are always flat)
 __global__ __launch_bounds__(kAttnThreads, PAGED ? 2 : 3) void attn_compact_kernel(const AttnArgs a) {
   const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  if (a.is_slow != nullptr && a.is_slow[b] != 0) return;
+  if (a.is_slow != nullptr && a.is_slow[b * a.fs] != 0) return;
   const int tid = threadIdx.x;
   const int lane = tid & 63, w = tid >> 6;
   const int jg = lane >> 4, n = lane & 15;
@@ -1299,7 +1299,7 @@ __global__ __launch_bounds__(kAttnThreads, PAGED ? 2 : 3) void attn_compact_kern
   bf16x8 qreg[4];
   load_q<WIDE>(qreg, a.q, head0, G, jg, n);
   int bad = 0;
-  const int L_in = a.ctx_len[b], nSel0 = a.n_sel[bh], rs_in = a.recent_start[b];  // one round trip for the three
+  const int L_in = a.ctx_len[b * a.ms], nSel0 = a.n_sel[bh], rs_in = a.recent_start[b * a.ms];  // one round trip for the three
   const int L = guarded_len(L_in, a.len_cap, bad);
   const int nSel = min(max(nSel0, 0), (int)a.sel_stride);
   bad |= nSel != nSel0 ? kGuardNSel : 0;
@@ -1374,7 +1374,7 @@ __global__ __launch_bounds__(kAttnThreads, PAGED ? 2 : 3) void attn_compact_kern
 template <bool PAGED>
 __global__ __launch_bounds__(kAttnThreads) void reorg_kernel(const ReorgArgs a) {
   const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
+  if (a.is_slow != nullptr && a.is_slow[b * a.fs] == 0) return;
   const int bh = b * a.Hkv + h;
   const int tid = threadIdx.x;
   const int sub = tid & 15, r = tid >> 4;
@@ -1388,7 +1388,7 @@ __global__ __launch_bounds__(kAttnThreads) void reorg_kernel(const ReorgArgs a) 
     src[p] = sel_cap >= 0 ? sel[min(max(i - a.n_sink, 0), sel_cap)] : 0;
   }
   int bad = 0;
-  const int L_in = a.ctx_len[b], nSel0 = a.n_sel[bh];
+  const int L_in = a.ctx_len[b * a.ms], nSel0 = a.n_sel[bh];
   const int L = guarded_len(L_in, a.len_cap, bad);
   const int nSel = min(max(nSel0, 0), (int)a.sel_stride);
   bad |= nSel != nSel0 ? kGuardNSel : 0;
@@ -1439,15 +1439,15 @@ __global__ __launch_bounds__(kMergeThreads) void merge_kernel(const MergeArgs a)
   const int bg = blockIdx.x;
   const int b = bg / a.Hq;
   int n_slots;
-  if (a.mode == 2 && a.slots_fast == 0 && a.is_slow[b] == 0) return;  // fast sequences wrote their output themselves
+  if (a.mode == 2 && a.slots_fast == 0 && a.is_slow[b * a.fs] == 0) return;  // fast sequences wrote their output themselves
   if (a.mode == 0) n_slots = a.slots_slow;
   else if (a.mode == 1) n_slots = a.slots_fast;
-  else n_slots = a.is_slow[b] ? a.slots_slow : a.slots_fast;
-  const bool dense = a.mode == 0 || (a.mode == 2 && a.is_slow[b]);
+  else n_slots = a.is_slow[b * a.fs] ? a.slots_slow : a.slots_fast;
+  const bool dense = a.mode == 0 || (a.mode == 2 && a.is_slow[b * a.fs]);
   if (dense) {
     // dense records: slots_slow waves' J records, then one record per wave that owned sink / recent tiles
     int L, recent;
-    window_view(a.q_len, b, min(max(a.ctx_len[b], 0), a.len_cap), a.recent, L, recent);  // the dense launch's view
+    window_view(a.q_len, b, min(max(a.ctx_len[b * a.ms], 0), a.len_cap), a.recent, L, recent);  // the dense launch's view
     const int nS = min(a.n_sink, L);
     const int rs = min(max(a.n_sink, L - recent), L);
     const int nTS = (nS + (L - rs) + kTile - 1) / kTile;
@@ -1476,6 +1476,30 @@ __global__ void trigger_kernel(const int32_t* last_token, const uint32_t* bitmap
     is_slow[b] = slow ? 1 : 0;
     since_slow[b] = slow ? 0 : c + 1;
   }
+}
+
+// The packed per-step descriptor (Sec. "Memory-coalesced Kernel Design and Selector Maintenance": built once per
+// decoding step, read by every kernel of the step): state update and trigger decision of every sequence in one launch.
+__global__ void step_begin_kernel(sfi_step_desc* desc, const int32_t* last_token, const uint32_t* bitmap, int vocab, int t_max,
+                                  int advance, int B, int n_sink, int recent) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b < B) {
+    sfi_step_desc d = desc[b];
+    if (advance) d.ctx_len += 1;
+    d.recent_start = max(n_sink, d.ctx_len - recent);
+    const int tok = last_token != nullptr ? last_token[b] : -1;
+    const bool hit = bitmap != nullptr && tok >= 0 && tok < vocab && ((bitmap[tok >> 5] >> (tok & 31)) & 1u) != 0u;
+    const bool slow = hit || d.since_slow >= t_max;
+    d.is_slow = slow ? 1 : 0;
+    d.since_slow = slow ? 0 : d.since_slow + 1;
+    desc[b] = d;
+  }
+}
+hipError_t launch_step_begin(sfi_step_desc* desc, const int32_t* last_token, const uint32_t* bitmap, int vocab, int t_max,
+                             int advance, int B, int n_sink, int recent, hipStream_t s) {
+  hipLaunchKernelGGL(step_begin_kernel, dim3((B + 63) / 64), dim3(64), 0, s, desc, last_token, bitmap, vocab, t_max, advance, B,
+                     n_sink, recent);
+  return hipGetLastError();
 }
 
 hipError_t launch_trigger(const int32_t* last_token, const uint32_t* bitmap, int vocab, int t_max, int32_t* since_slow,

@@ -93,6 +93,8 @@ struct AttnArgs {
   const uint16_t* V;
   int64_t k_sb, k_sh, k_st, v_sb, v_sh, v_st;
   const int32_t* ctx_len;
+  int32_t ms, fs;                // strides of the per-sequence entries: ctx_len / recent_start in int32, is_slow in bytes
+                                 //   (1, 1 for plain arrays; 4, 16 when they are fields of a packed sfi_step_desc array)
   const int32_t* q_len;          // dense mode, nullptr or: rows each sequence's query sees (window query under the causal mask)
   const int32_t* recent_start;   // gather mode
   const int32_t* sel_idx;        // gather mode
@@ -141,6 +143,7 @@ struct ReorgArgs {
   const int32_t* n_sel;
   const int32_t* ctx_len;
   const uint8_t* is_slow;        // nullptr: every sequence takes part
+  int32_t ms, fs;                // strides of ctx_len (int32) and is_slow (bytes), see AttnArgs
   int64_t sel_stride;
   uint16_t* Kc;
   uint16_t* Vc;
@@ -168,6 +171,7 @@ struct MergeArgs {
   float alpha;                         // power-mean exponent of the evidence (Eq. selector_mu)
   int32_t len_cap;                     // the clamp the dense launch applied to ctx_len
   int32_t out_bf16;                    // out is bf16
+  int32_t ms = 1, fs = 1;              // strides of ctx_len (int32) and is_slow (bytes), see AttnArgs
 };
 
 struct SelArgs {
@@ -180,6 +184,7 @@ struct SelArgs {
   uint32_t* segcnt;
   const int32_t* ctx_len;
   const int32_t* q_len;    // accumulation of a window query under the causal mask (see window_view), else nullptr
+  int32_t ms, fs;          // strides of ctx_len (int32) and is_slow (bytes), see AttnArgs
   const uint8_t* is_slow;
   int32_t* sel_idx;
   int32_t* n_sel;
@@ -224,5 +229,7 @@ hipError_t launch_sel_write(const SelArgs& a, int B, int n_seg, hipStream_t s);
 hipError_t launch_trigger(const int32_t* last_token, const uint32_t* bitmap, int vocab, int t_max, int32_t* since_slow,
                           uint8_t* is_slow, int B, hipStream_t s);
 hipError_t launch_advance(int32_t* ctx_len, int32_t* recent_start, int B, int n_sink, int recent, hipStream_t s);
+hipError_t launch_step_begin(sfi_step_desc* desc, const int32_t* last_token, const uint32_t* bitmap, int vocab, int t_max,
+                             int advance, int B, int n_sink, int recent, hipStream_t s);
 
 }  // namespace sfi

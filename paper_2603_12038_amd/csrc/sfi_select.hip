@@ -106,7 +106,7 @@ struct Problem {
 
 __device__ __forceinline__ Problem problem_of(const SelArgs& a, int b) {
   Problem p;
-  p.nJ = max(0, min(a.ctx_len[b], a.len_cap) - a.recent - a.n_sink);  // the dense launch's clamp of ctx_len
+  p.nJ = max(0, min(a.ctx_len[b * a.ms], a.len_cap) - a.recent - a.n_sink);  // the dense launch's clamp of ctx_len
   p.ksel = (uint32_t)min(a.budget, p.nJ);
   return p;
 }
@@ -116,7 +116,7 @@ __device__ __forceinline__ Problem problem_of(const SelArgs& a, int b) {
 // query head into the attention output (J records of all waves, then one record per wave that owned
 // sink / recent tiles).
 __device__ __forceinline__ void merge_head(const SelArgs& a, int b, int h, int g) {
-  const int L = min(max(a.ctx_len[b], 0), a.len_cap);
+  const int L = min(max(a.ctx_len[b * a.ms], 0), a.len_cap);
   const int nS = min(a.n_sink, L);
   const int rs = min(max(a.n_sink, L - a.recent), L);
   const int nTS = (nS + (L - rs) + 31) / 32;
@@ -159,12 +159,12 @@ __device__ __forceinline__ void group_jstat(const SelArgs& a, int b, int h, floa
 template <bool ACCUM>
 __global__ __launch_bounds__(kSelThreads) void sel_score_kernel(const SelArgs a) {
   const int seg = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
+  if (a.is_slow != nullptr && a.is_slow[b * a.fs] == 0) return;
   Problem pb = problem_of(a, b);
   int n_all = pb.nJ;  // ACCUM under the causal mask: |J| of the whole window; pb.nJ becomes the part this query sees
   if (ACCUM && a.q_len != nullptr) {
     int Lq, rec;
-    window_view(a.q_len, b, min(max(a.ctx_len[b], 0), a.len_cap), a.recent, Lq, rec);
+    window_view(a.q_len, b, min(max(a.ctx_len[b * a.ms], 0), a.len_cap), a.recent, Lq, rec);
     pb.nJ = max(0, Lq - rec - a.n_sink);
   }
   const int tid = threadIdx.x;
@@ -283,7 +283,7 @@ __global__ __launch_bounds__(kSelThreads) void sel_score_kernel(const SelArgs a)
 // Windowed evidence, mode 0: the accumulated mu times 1 / (number of queries added) is the ranking value.
 __global__ __launch_bounds__(kSelThreads) void sel_finalize_kernel(const SelArgs a) {
   const int seg = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
+  if (a.is_slow != nullptr && a.is_slow[b * a.fs] == 0) return;
   const Problem pb = problem_of(a, b);
   const int p_lo = seg * kSelSeg;
   if (p_lo >= pb.nJ) return;
@@ -344,7 +344,7 @@ __device__ __forceinline__ void block_sums_f64(double (&v)[kSegStats], double (*
 // selector_u, selector_prior_pos) of one segment, and the segment's sums for lambda*.
 __global__ __launch_bounds__(kSelThreads) void sel_prior_kernel(const SelArgs a) {
   const int seg = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
+  if (a.is_slow != nullptr && a.is_slow[b * a.fs] == 0) return;
   const Problem pb = problem_of(a, b);
   const int G = a.G, rows = G + 1;
   const bool fused = a.part != nullptr;  // grid-uniform: no merge launch has run
@@ -439,7 +439,7 @@ __global__ __launch_bounds__(kSelThreads) void sel_prior_kernel(const SelArgs a)
 // then Soft-NMS on the un-updated scores with the neighbourhood clipped to J (Eqs. nms_pool, nms).
 __global__ __launch_bounds__(kSelThreads) void sel_fuse_kernel(const SelArgs a) {
   const int seg = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
+  if (a.is_slow != nullptr && a.is_slow[b * a.fs] == 0) return;
   const Problem pb = problem_of(a, b);
   const int p_lo = seg * kSelSeg;
   if (p_lo >= pb.nJ) return;
@@ -486,7 +486,7 @@ __global__ __launch_bounds__(kSelThreads) void sel_fuse_kernel(const SelArgs a) 
 // head_mutex), then the ranking key and the 12-bit histogram exactly as stage 1 of mode 0.
 __global__ __launch_bounds__(kSelThreads) void sel_cross_kernel(const SelArgs a) {
   const int seg = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
+  if (a.is_slow != nullptr && a.is_slow[b * a.fs] == 0) return;
   const Problem pb = problem_of(a, b);
   const int p_lo = seg * kSelSeg;
   if (p_lo >= pb.nJ) return;
@@ -541,7 +541,7 @@ __global__ __launch_bounds__(kSelThreads) void sel_cross_kernel(const SelArgs a)
 // ---- stage 2: find the threshold bin, collect its keys -----------------------------------------
 __global__ __launch_bounds__(kSelThreads) void sel_cand_kernel(const SelArgs a) {
   const int seg = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
+  if (a.is_slow != nullptr && a.is_slow[b * a.fs] == 0) return;
   const int p_lo = seg * kSelSeg;
   const int tid = threadIdx.x;
   const int bh = b * a.Hkv + h;
@@ -622,7 +622,7 @@ __global__ __launch_bounds__(kSelThreads) void sel_cand_kernel(const SelArgs a) 
 // ---- stage 3: exact threshold among the candidates, index-ordered write of the selected set ------
 __global__ __launch_bounds__(kSelThreads) void sel_write_kernel(const SelArgs a) {
   const int seg = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-  if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
+  if (a.is_slow != nullptr && a.is_slow[b * a.fs] == 0) return;
   const Problem pb = problem_of(a, b);
   const int tid = threadIdx.x;
   const int bh = b * a.Hkv + h;
@@ -733,7 +733,7 @@ __global__ __launch_bounds__(kSelThreads) void sel_write_kernel(const SelArgs a)
 // (another budget, say) starts with this launch instead, or it would count into the first pass's histogram.
 __global__ __launch_bounds__(kSelThreads) void sel_clear_kernel(const SelArgs a) {
   const int h = blockIdx.y, b = blockIdx.z;
-  if (a.is_slow != nullptr && a.is_slow[b] == 0) return;
+  if (a.is_slow != nullptr && a.is_slow[b * a.fs] == 0) return;
   const int bh = b * a.Hkv + h;
   uint32_t* hh = a.hist1 + (int64_t)bh * kHist1Bins;
   for (int i = threadIdx.x; i < kHist1Bins; i += kSelThreads) hh[i] = 0u;

@@ -863,3 +863,50 @@ def test_ragged_decode_loop_against_the_oracles_driver(oracle, path):
         assert r.sfi.sfi_device_status(r.ctx.handle) == 0
     finally:
         r.close()
+
+
+def test_decode_loop_from_the_packed_descriptor(oracle):
+    """Algorithm 1 driven by the packed per-step descriptor alone: sfi_step_begin (state update + trigger policy, one
+    launch per decoding step) and sfi_mixed_step_desc (every kernel reads the descriptor) for three ragged sequences
+    over fourteen steps, no host decision in between.  Expected: the oracle's trigger schedule per sequence fed to the
+    oracle's Algorithm 1 driver."""
+    import torch
+    import paper_2603_12038_amd as sfi
+
+    w = syn.make_serving(steps=14, B=3, Hq=8, Hkv=2, len_lo=400, len_hi=1200, budget=48, recent=24)
+    T, B, t_max, vocab = w.steps, w.B, 4, 300
+    trig = [7, 31, 64, 250]
+    rng = syn.rng_for(5, 4242)
+    tokens = rng.integers(0, 40, size=(T, B)).astype(np.int32)   # tokens[t, b]: generated by step t
+    g = np.stack([oracle.trigger_schedule(tokens[:, b], trig, t_max) for b in range(B)], axis=1)
+    assert g[0].all() and 0 < g[1:].sum() < g[1:].size
+    qs = np.stack([w.q(t) for t in range(T)])
+    ref = oracle.decode_loop(qs, w.K, w.V, w.ctx_len(0), w.recent_start(0), g, w.budget, w.n_sink, w.recent)
+    bitmap = np.zeros((vocab + 31) // 32, np.uint32)
+    for i in trig:
+        bitmap[i >> 5] |= np.uint32(1 << (i & 31))
+    r = Runner(w)
+    try:
+        _step("decode loop from the packed descriptor")
+        desc0 = np.zeros((B, 4), np.int32)
+        desc0[:, 0] = w.ctx_len(0)
+        desc0[:, 1] = -99            # filled in by sfi_step_begin
+        desc0[:, 3] = t_max          # g_0 = 1
+        desc = torch.from_numpy(desc0).cuda()
+        bm = torch.from_numpy(bitmap.view(np.int32)).cuda()
+        sel_d = torch.full((B, w.Hkv, w.budget), -7, dtype=torch.int32, device="cuda")
+        nsel_d = torch.zeros((B, w.Hkv), dtype=torch.int32, device="cuda")
+        last = torch.zeros(B, dtype=torch.int32, device="cuda")
+        for t in range(T):
+            sfi.sfi_step_begin(r.ctx.handle, desc, last if t > 0 else None, bm, vocab, t_max, t > 0)
+            r.out.fill_(float("nan"))
+            sfi.sfi_mixed_step_desc(r.ctx.handle, to_dev(qs[t]), r.K, r.V, desc, 0, w.budget, r.out, sel_d, nsel_d)
+            torch.cuda.synchronize()
+            d = desc.cpu().numpy()
+            assert (d[:, 0] == ref["ctx_hist"][t]).all() and (d[:, 1] == ref["rs_hist"][t]).all() and (d[:, 2] == g[t]).all()
+            check_out(r.out.cpu().numpy(), ref["out"][t])
+            assert (sel_d.cpu().numpy() == ref["sel_hist"][t]).all() and (nsel_d.cpu().numpy() == ref["nsel_hist"][t]).all()
+            last = torch.from_numpy(tokens[t]).cuda()
+        assert r.sfi.sfi_device_status(r.ctx.handle) == 0
+    finally:
+        r.close()
