@@ -739,6 +739,13 @@ def bench_mix(args):
                  "scalars_and_indices_only_us": float(graph_avg_ms(skeleton(4), 8) * 1e3),
                  "bare_launch_us": float(graph_avg_ms(skeleton(8), 8) * 1e3)}
         fast(0, step_p)  # leave real outputs behind
+    # the dense launch's streaming ceiling: its memory skeleton (same grid and tile dealing, loads only, no logits
+    # written), with K rows requested in the kernel's own layout and as whole 128-byte lines
+    dense_floor = None
+    if not args.page_size:
+        dskel = lambda v: (lambda l, step: sfi.sfi_dense_attn_floor(h, Ks[l], Vs[l], ctx_d, max_ctx, v))
+        dense_floor = {"kernel_k_layout_us": float(graph_avg_ms(dskel(0), 2) * 1e3),
+                       "whole_line_k_us": float(graph_avg_ms(dskel(1), 2) * 1e3)}
     roof = {
         "bound": "hbm", "kernel": f"sfi::attn_{dominant}_kernel",
         "achieved": fast_gbs if dominant != "dense" else dense_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -778,7 +785,8 @@ def bench_mix(args):
         "roofline": roof,
         "kernels": {
             "dense_attn": {"us": slow_ms[0] * 1e3, "kv_bytes": dense_bytes, "GBps": dense_gbs,
-                           "frac_of_8TBps": dense_gbs / HBM_PEAK_GBS},
+                           "frac_of_8TBps": dense_gbs / HBM_PEAK_GBS, "us_is": "event pair around the launch (about 2 us above the trace's duration)",
+                           "memory_skeleton_us": dense_floor},
             f"{fast_kernel}_attn": {"us": fast_ms[0] * 1e3, "kv_bytes": fast_bytes, "GBps": fast_gbs,
                             "frac_of_8TBps": fast_gbs / HBM_PEAK_GBS,
                             "us_with_an_event_pair_per_launch": fast_bracketed_us},

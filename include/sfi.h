@@ -445,6 +445,15 @@ int sfi_fast_step_floor(sfi_ctx* ctx, const void* q, const void* K, const void* 
                         const int32_t* n_sel, int32_t sel_stride, const int32_t* recent_start,
                         const int32_t* ctx_len, void* out, int32_t variant, void* stream);
 
+/*
+ * Memory skeleton of the dense launch -- a measurement aid like sfi_fast_step_floor: the grid and tile dealing of
+ * sfi_dense_attn over rows [0, ctx_len[b]) of K and V (two tile buffers per wave, nontemporal 16-byte loads), nothing
+ * computed, no logits written.  variant 0: K rows requested in the dense kernel's own layout (four 64-byte pieces per
+ * row); 1: as whole 128-byte lines.  Flat caches only.  Its time is the streaming ceiling the dense kernel is held against.
+ */
+int sfi_dense_attn_floor(sfi_ctx* ctx, const void* K, const void* V, const int32_t* ctx_len, int32_t max_len,
+                         int32_t variant, void* stream);
+
 /* Launch geometry of the last call (for reports): split workgroups per (sequence, KV head). */
 int sfi_query_splits(const sfi_ctx* ctx, int32_t* dense_splits, int32_t* fast_splits);
 

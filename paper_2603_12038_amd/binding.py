@@ -42,7 +42,7 @@ _lib: Optional[C.CDLL] = None
 
 EXPORTS = ("sfi_workspace_bytes", "sfi_create", "sfi_set_block_table", "sfi_destroy", "sfi_strerror", "sfi_slow_step", "sfi_slow_attn",
            "sfi_slow_select", "sfi_evidence_add", "sfi_evidence_add_causal", "sfi_evidence_select", "sfi_dense_attn",
-           "sfi_fast_step", "sfi_fast_step_static", "sfi_fast_step_floor", "sfi_reorg", "sfi_fast_step_compact", "sfi_mixed_step", "sfi_mixed_step_compact", "sfi_step_begin", "sfi_mixed_step_desc", "sfi_trigger", "sfi_advance", "sfi_set_profiling", "sfi_stage_times",
+           "sfi_fast_step", "sfi_fast_step_static", "sfi_fast_step_floor", "sfi_dense_attn_floor", "sfi_reorg", "sfi_fast_step_compact", "sfi_mixed_step", "sfi_mixed_step_compact", "sfi_step_begin", "sfi_mixed_step_desc", "sfi_trigger", "sfi_advance", "sfi_set_profiling", "sfi_stage_times",
            "sfi_set_tuning", "sfi_plan_splits", "sfi_device_status", "sfi_query_splits")
 
 
@@ -83,6 +83,8 @@ def load_library() -> C.CDLL:
     lib.sfi_fast_step.argtypes = [vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
     lib.sfi_fast_step_static.restype = C.c_int
     lib.sfi_fast_step_static.argtypes = [C.POINTER(SfiConfig), vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
+    lib.sfi_dense_attn_floor.restype = C.c_int
+    lib.sfi_dense_attn_floor.argtypes = [vp, vp, vp, vp, i32, i32, vp]
     lib.sfi_fast_step_floor.restype = C.c_int
     lib.sfi_fast_step_floor.argtypes = [vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, i32, vp]
     lib.sfi_reorg.restype = C.c_int
@@ -210,6 +212,12 @@ def sfi_fast_step_static(cfg: SfiConfig, q, K, V, sel_idx, n_sel, sel_stride, re
     _check(load_library().sfi_fast_step_static(C.byref(cfg), _ptr(q), _ptr(K), _ptr(V), _ptr(sel_idx), _ptr(n_sel),
                                                sel_stride, _ptr(recent_start), _ptr(ctx_len), _ptr(out),
                                                _stream(stream)), "sfi_fast_step_static")
+
+
+def sfi_dense_attn_floor(ctx, K, V, ctx_len, max_len, variant: int, stream=None) -> None:
+    """Memory skeleton of the dense launch (measurement aid): variant 0 = the kernel's K layout, 1 = whole-line K loads."""
+    _check(load_library().sfi_dense_attn_floor(ctx, _ptr(K), _ptr(V), _ptr(ctx_len), max_len, variant, _stream(stream)),
+           "sfi_dense_attn_floor")
 
 
 def sfi_fast_step_floor(ctx, q, K, V, sel_idx, n_sel, sel_stride, recent_start, ctx_len, out, variant: int, stream=None) -> None:

@@ -460,6 +460,24 @@ int sfi_dense_attn(sfi_ctx* x, const void* q, const void* K, const void* V, cons
   return SFI_OK;
 }
 
+// Memory skeleton of the dense launch (measurement aid): the launch plan of sfi_dense_attn, loads only.
+int sfi_dense_attn_floor(sfi_ctx* x, const void* K, const void* V, const int32_t* ctx_len, int32_t max_len, int32_t variant,
+                         void* stream) {
+  if (x == nullptr || K == nullptr || V == nullptr || ctx_len == nullptr) return SFI_EINVAL;
+  if (misaligned(K, 16) || misaligned(V, 16) || misaligned(ctx_len, 4)) return SFI_EALIGN;
+  if (variant < 0 || variant > 1 || x->table != nullptr || x->cfg.page_size != 0) return SFI_EUNSUPPORTED;
+  int ml;
+  const int rc = resolve_max_len(x, max_len, &ml);
+  if (rc != SFI_OK) return rc;
+  AttnArgs a;
+  fill_attn(x, &a, K /* q is not read */, K, V, ctx_len);
+  a.n_split = dense_splits_for(x, ml, false);
+  set_dense_bounds(x, &a, ml);
+  x->last_dense_splits = a.n_split;
+  SFI_TRY(launch_attn_dense_floor(a, x->cfg.batch, a.n_split, variant & 1, (hipStream_t)stream));
+  return SFI_OK;
+}
+
 namespace {
 // First half of a slow step: dense attention with the evidence (y over J, Selector state cleared,
 // J-only softmax statistics) left in the workspace.

@@ -1261,6 +1261,69 @@ hipError_t launch_attn_gather_floor(const AttnArgs& a, int B, int n_slots, int t
 }
 
 // ------------------------------------------------------------------------------------------------
+// Memory skeleton of the dense kernel -- a measurement aid, not part of the path: the dense launch's grid and
+// tile dealing (tiles first, first + step, ... of the prefix per wave, two tile buffers in flight, K half and V
+// half of a buffer refilled separately), nontemporal 16-byte loads, nothing computed: what arrives is folded
+// into one word per wave.  WIDE: K rows requested as whole 128-byte lines (the gather kernels' layout) instead
+// of the four 64-byte pieces the dense kernel's operand layout asks for.  No logits are written.
+// ------------------------------------------------------------------------------------------------
+template <bool WIDE>
+__global__ __launch_bounds__(kAttnThreads, 1) void attn_dense_floor_kernel(const AttnArgs a) {
+  const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, w = tid >> 6;
+  const int jg = lane >> 4, n = lane & 15;
+  Rows R;
+  R.Kb = reinterpret_cast<const char*>(a.K + b * a.k_sb + h * a.k_sh);
+  R.Vb = reinterpret_cast<const char*>(a.V + b * a.v_sb + h * a.v_sh);
+  R.k_st = (uint32_t)a.k_st * 2u;
+  R.v_st = (uint32_t)a.v_st * 2u;
+  R.k_lane = k_lane_of<WIDE>(jg, n);
+  R.v_lane = n * 16;
+  R.jg = jg;
+  R.n = n;
+  const int first = slot * kWaves + w, step = a.n_split * kWaves;
+  Tile T, T2;
+  issue_affine<WIDE>(T, R, first * kTile, a.row_cap);           // before ctx_len arrives, as the kernel does
+  issue_affine<WIDE>(T2, R, (first + step) * kTile, a.row_cap);
+  int bad = 0;
+  const int L = guarded_len(a.ctx_len[b * a.ms], a.len_cap, bad);
+  const int r_last = max(L, 1) - 1;
+  const int nT = (L + kTile - 1) / kTile;
+  const int K = first < nT ? (nT - first + step - 1) / step : 0;
+  uint32_t fold = 0u;
+  auto use = [&](Tile& B, int k) {
+    const int t_next = first + (k + 2) * step;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) fold ^= fold16(B.ka[i]) ^ fold16(B.kb[i]);
+    issue_k_affine<WIDE>(B, R, t_next * kTile, r_last);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) fold ^= fold16(B.v[i]);
+    issue_v_affine<WIDE>(B, R, t_next * kTile, r_last);
+  };
+  int k = 0;
+  for (; k + 1 < K; k += 2) {
+    use(T, k);
+    use(T2, k + 1);
+  }
+  if (k < K) use(T, k);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) fold ^= fold16(T.ka[i]) ^ fold16(T.kb[i]) ^ fold16(T2.ka[i]) ^ fold16(T2.kb[i]);  // the refills past the end
+#pragma unroll
+  for (int i = 0; i < 8; ++i) fold ^= fold16(T.v[i]) ^ fold16(T2.v[i]);
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) fold ^= __shfl_xor(fold, d);
+  const int64_t head0 = (int64_t)b * a.Hq + h * a.G;
+  if (lane == 0) reinterpret_cast<uint32_t*>(a.part)[((head0 * kSlotCap + slot) * kPartStride) + w] = fold;
+}
+hipError_t launch_attn_dense_floor(const AttnArgs& a, int B, int n_slots, int wide, hipStream_t s) {
+  const dim3 grid(n_slots, a.Hkv, B);
+  if (wide) hipLaunchKernelGGL(attn_dense_floor_kernel<true>, grid, dim3(kAttnThreads), 0, s, a);
+  else hipLaunchKernelGGL(attn_dense_floor_kernel<false>, grid, dim3(kAttnThreads), 0, s, a);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
 // compact kernel: the fast step over the two-segment layout (Sec. "Memory-coalesced Kernel Design
 // and Selector Maintenance"): sink ++ selected rows from the compact buffers the Reorg kernel filled,
 // the recent window in place from the cache.  Both segments are runs of consecutive rows, so no
