@@ -367,6 +367,8 @@ def main():
                          "holds k_t then v_t (the library sees two base pointers and a row stride of 2 d either way)")
     ap.add_argument("--out-bf16", action="store_true",
                     help="outputs stored as bf16 (cfg.out_bf16) instead of fp32; slow+fast mix workloads only")
+    ap.add_argument("--dense-k", choices=["pieces", "whole-lines"], default="pieces",
+                    help="A/B of the dense kernel's K loads: four 64-byte pieces per row (default) or whole 128-byte lines")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--dense-wgs", type=int, default=0)
     ap.add_argument("--fast-tpw", type=int, default=0)
@@ -496,6 +498,9 @@ def bench_mix(args):
     if args.dense_wgs or args.fast_tpw or args.fast_merge:
         for c in ring:
             sfi.sfi_set_tuning(c.handle, args.dense_wgs, args.fast_tpw, FAST_MERGE[args.fast_merge])
+    if args.dense_k == "whole-lines":
+        for c in ring:
+            sfi.sfi_set_dense_k_layout(c.handle, True)
     gen = torch.Generator(device=dev)
     gen.manual_seed(1234)
     q_all = torch.randn(n_dec + SEG, NL, B, Hq, d, device=dev, generator=gen).to(torch.bfloat16)

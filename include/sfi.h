@@ -397,6 +397,13 @@ int sfi_stage_times(sfi_ctx* ctx, float* ms_sum /* host, [SFI_N_STAGES] */, int3
  *                      2 in a merge launch of its own.  Other values > 2: SFI_EINVAL. */
 int sfi_set_tuning(sfi_ctx* ctx, int32_t dense_target_wgs, int32_t fast_tiles_per_wave, int32_t fast_merge);
 
+/* A/B knob of the dense kernel's K loads: 0 (default) = a K row leaves the compute unit as four 64-byte requests, the
+ * shape the matrix instruction's operand layout asks for; 1 = as two requests for whole 128-byte lines (the gather
+ * kernels' layout: a row of the product is half a K row, the halves are joined by lane exchanges).  Same results;
+ * applies to flat caches, query groups of at most 8 heads, Selector mode 0 (ignored elsewhere).  The default is the
+ * faster one on MI355X. */
+int sfi_set_dense_k_layout(sfi_ctx* ctx, int32_t whole_lines);
+
 /* Launch geometry the library would choose, without launching anything (host arithmetic only): split
  * workgroups per (sequence, KV head) of a dense launch bounded by max_len rows (0 = cfg.max_ctx) and
  * of a fast step whose index lists are sel_stride wide.  Either output may be NULL.  SFI_EINVAL for a

@@ -43,7 +43,7 @@ _lib: Optional[C.CDLL] = None
 EXPORTS = ("sfi_workspace_bytes", "sfi_create", "sfi_set_block_table", "sfi_destroy", "sfi_strerror", "sfi_slow_step", "sfi_slow_attn",
            "sfi_slow_select", "sfi_evidence_add", "sfi_evidence_add_causal", "sfi_evidence_select", "sfi_dense_attn",
            "sfi_fast_step", "sfi_fast_step_static", "sfi_fast_step_floor", "sfi_dense_attn_floor", "sfi_reorg", "sfi_fast_step_compact", "sfi_mixed_step", "sfi_mixed_step_compact", "sfi_step_begin", "sfi_mixed_step_desc", "sfi_trigger", "sfi_advance", "sfi_set_profiling", "sfi_stage_times",
-           "sfi_set_tuning", "sfi_plan_splits", "sfi_device_status", "sfi_query_splits")
+           "sfi_set_tuning", "sfi_set_dense_k_layout", "sfi_plan_splits", "sfi_device_status", "sfi_query_splits")
 
 
 def load_library() -> C.CDLL:
@@ -109,6 +109,8 @@ def load_library() -> C.CDLL:
     lib.sfi_stage_times.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
     lib.sfi_set_tuning.restype = C.c_int
     lib.sfi_set_tuning.argtypes = [vp, i32, i32, i32]
+    lib.sfi_set_dense_k_layout.restype = C.c_int
+    lib.sfi_set_dense_k_layout.argtypes = [vp, i32]
     lib.sfi_plan_splits.restype = C.c_int
     lib.sfi_plan_splits.argtypes = [vp, i32, i32, C.POINTER(i32), C.POINTER(i32)]
     lib.sfi_device_status.restype = C.c_int
@@ -294,6 +296,10 @@ def sfi_stage_times(ctx):
 
 def sfi_set_tuning(ctx, dense_target_wgs: int = 0, fast_tiles_per_wave: int = 0, fast_merge: int = 0) -> None:
     _check(load_library().sfi_set_tuning(ctx, dense_target_wgs, fast_tiles_per_wave, fast_merge), "sfi_set_tuning")
+
+
+def sfi_set_dense_k_layout(ctx, whole_lines: bool) -> None:
+    _check(load_library().sfi_set_dense_k_layout(ctx, 1 if whole_lines else 0), "sfi_set_dense_k_layout")
 
 
 def sfi_plan_splits(ctx, max_len: int, sel_stride: int) -> Tuple[int, int]:

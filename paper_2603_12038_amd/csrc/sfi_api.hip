@@ -20,6 +20,7 @@ struct sfi_ctx {
   int dense_target_wgs;     // workgroups the dense launch aims for; 0 = decided per launch
   int fast_tiles_per_wave;  // 32-row tiles each wave of the gather launch should get; 0 = decided per launch
   int tail_merge;           // split fast-step launches merge in the attention kernel (no merge launch)
+  int dense_wide;           // dense kernel reads K rows as whole 128-byte lines (A/B knob, sfi_set_dense_k_layout)
   int last_dense_splits, last_fast_splits;
   int selector_ran;         // a Selector pass has used the evidence now in the workspace: its histogram and state
                             // words are no longer the cleared ones the dense kernel left
@@ -244,6 +245,7 @@ void fill_attn(const sfi_ctx* x, AttnArgs* a, const void* q, const void* K, cons
   a->v_sb = c.v_stride_b; a->v_sh = c.v_stride_h; a->v_st = c.v_stride_t;
   a->ctx_len = ctx_len;
   a->ms = 1; a->fs = 1;
+  a->dense_wide = x->dense_wide;
   a->part = x->ws.part;
   a->slot_cap = kSlotCap;
   a->ld_pos = x->ws.ld_pos;
@@ -1051,6 +1053,12 @@ int sfi_set_tuning(sfi_ctx* x, int32_t dense_target_wgs, int32_t fast_tiles_per_
   if (dense_target_wgs != 0) x->dense_target_wgs = dense_target_wgs > 0 ? dense_target_wgs : 0;
   if (fast_tiles_per_wave != 0) x->fast_tiles_per_wave = fast_tiles_per_wave > 0 ? fast_tiles_per_wave : 0;
   if (fast_merge != 0) x->tail_merge = fast_merge != 2;
+  return SFI_OK;
+}
+
+int sfi_set_dense_k_layout(sfi_ctx* x, int32_t whole_lines) {
+  if (x == nullptr || whole_lines < 0 || whole_lines > 1) return SFI_EINVAL;
+  x->dense_wide = whole_lines;
   return SFI_OK;
 }
 

@@ -263,31 +263,40 @@ __device__ __forceinline__ void load_q(bf16x8 (&qreg)[4], const uint16_t* q, int
 // Lanes of heads >= G see q = 0; their state stays finite and is never written out: no mask needed.
 
 // Phase 1: y[i] = logit (log2 domain) of head n, row 4*jg+i of block A (i < 4) / block B (i >= 4).
+// WIDE, first half: the eight products of a tile; after them the K registers are free for the next tile's rows.
+__device__ __forceinline__ void qk_products_wide(const Tile& T, const bf16x8 (&qreg)[4], f32x4 (&s)[4]) {
+#pragma unroll
+  for (int blk = 0; blk < 4; ++blk) {
+    s[blk] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+      s[blk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wide_k(T, blk, kb)), qreg[kb], s[blk], 0, 0, 0);
+  }
+}
+// WIDE, second half: the half-row sums meet.
+// s[blk][i] of lane (jg, n): product row 4 * jg + i, column n.  Lane (jg < 2, n < 8) holds the first-half
+// sums of positions 8 * blk + 4 * jg + i for head n, its mirror 40 lanes up the second-half sums.  The
+// lower lane keeps blocks 0 and 1, the mirror blocks 2 and 3: each sends the other the half it lacks.
+// Then lane (jg >= 2, n < 8) fetches its logits from the mirror (jg, n + 8) in its own row of 16.
+__device__ __forceinline__ void qk_join_wide(const f32x4 (&s)[4], float c2, float (&y)[8]) {
+  const int lane = threadIdx.x & 63, jg = lane >> 4, n = lane & 15;
+  const bool low = jg < 2;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float u0 = (low ? s[0][i] : s[2][i]) + lane_xor40(low ? s[2][i] : s[0][i]);
+    const float u1 = (low ? s[1][i] : s[3][i]) + lane_xor40(low ? s[3][i] : s[1][i]);
+    const float x0 = lane_xor8(u0), x1 = lane_xor8(u1);
+    y[i] = n < 8 ? (low ? u0 : x0) * c2 : 0.f;
+    y[4 + i] = n < 8 ? (low ? u1 : x1) * c2 : 0.f;
+  }
+}
+
 template <bool WIDE = false>
 __device__ __forceinline__ void qk_phase(const Tile& T, const bf16x8 (&qreg)[4], float c2, float (&y)[8]) {
   if (WIDE) {
     f32x4 s[4];
-#pragma unroll
-    for (int blk = 0; blk < 4; ++blk) {
-      s[blk] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-        s[blk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(wide_k(T, blk, kb)), qreg[kb], s[blk], 0, 0, 0);
-    }
-    // s[blk][i] of lane (jg, n): product row 4 * jg + i, column n.  Lane (jg < 2, n < 8) holds the first-half
-    // sums of positions 8 * blk + 4 * jg + i for head n, its mirror 40 lanes up the second-half sums.  The
-    // lower lane keeps blocks 0 and 1, the mirror blocks 2 and 3: each sends the other the half it lacks.
-    // Then lane (jg >= 2, n < 8) fetches its logits from the mirror (jg, n + 8) in its own row of 16.
-    const int lane = threadIdx.x & 63, jg = lane >> 4, n = lane & 15;
-    const bool low = jg < 2;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const float u0 = (low ? s[0][i] : s[2][i]) + lane_xor40(low ? s[2][i] : s[0][i]);
-      const float u1 = (low ? s[1][i] : s[3][i]) + lane_xor40(low ? s[3][i] : s[1][i]);
-      const float x0 = lane_xor8(u0), x1 = lane_xor8(u1);
-      y[i] = n < 8 ? (low ? u0 : x0) * c2 : 0.f;
-      y[4 + i] = n < 8 ? (low ? u1 : x1) * c2 : 0.f;
-    }
+    qk_products_wide(T, qreg, s);
+    qk_join_wide(s, c2, y);
     return;
   }
   f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
@@ -561,7 +570,7 @@ struct ListWalk {
 // BIG: twice the logits stash per wave, which leaves room for one workgroup per compute unit only
 // (launches where every sequence is dense run one per unit anyway; the mixed step keeps two).
 // NOV: evidence only -- no V row is read, no P V product, the records carry the softmax statistics alone.
-template <int EXPOSE, bool PAGED, bool BIG = false, bool NOV = false>
+template <int EXPOSE, bool PAGED, bool BIG = false, bool NOV = false, bool WIDE = false>
 __global__ __launch_bounds__(kAttnThreads, BIG ? 1 : 2) void attn_dense_kernel(const AttnArgs a) {
   constexpr int kStash = BIG ? 2 * kStashFloats : kStashFloats;
   __shared__ float s_stash[EXPOSE != 0 ? kWaves : 1][EXPOSE != 0 ? kStash : 1];  // per-wave logits stash
@@ -578,7 +587,7 @@ __global__ __launch_bounds__(kAttnThreads, BIG ? 1 : 2) void attn_dense_kernel(c
   R.Vb = reinterpret_cast<const char*>(a.V + b * a.v_sb + h * a.v_sh);
   R.k_st = (uint32_t)a.k_st * 2u;
   R.v_st = (uint32_t)a.v_st * 2u;
-  R.k_lane = jg * 16;
+  R.k_lane = k_lane_of<WIDE>(jg, n);
   R.v_lane = n * 16;
   R.jg = jg;
   R.n = n;
@@ -596,11 +605,11 @@ __global__ __launch_bounds__(kAttnThreads, BIG ? 1 : 2) void attn_dense_kernel(c
   Tile T;
   // (a paged cache has valid blocks only up to ctx_len: no load before ctx_len is known)
   if (!PAGED && first < a.max_tiles) {
-    issue_k_affine(T, R, a.n_sink + first * kTile, a.row_cap);
-    if (!NOV) issue_v_affine(T, R, a.n_sink + first * kTile, a.row_cap);
+    issue_k_affine<WIDE>(T, R, a.n_sink + first * kTile, a.row_cap);
+    if (!NOV) issue_v_affine<WIDE>(T, R, a.n_sink + first * kTile, a.row_cap);
   }
   bf16x8 qreg[4];
-  load_q(qreg, a.q, head0, G, jg, n);
+  load_q<WIDE>(qreg, a.q, head0, G, jg, n);
   int bad = 0;
   int L, recent;  // a window query under the causal mask sees a shorter context with what is left of the recent window
   window_view(a.q_len, b, guarded_len(a.ctx_len[b * a.ms], a.len_cap, bad), a.recent, L, recent);
@@ -629,6 +638,15 @@ __global__ __launch_bounds__(kAttnThreads, BIG ? 1 : 2) void attn_dense_kernel(c
     return t < nTJ ? min(xj, rJ_max) : r_s;
   };
   auto issue_k_tile = [&](Tile& T, int t) {
+    if (WIDE) {  // whole 128-byte lines: position 8 * blk + (n & 7), the half of the row this lane's column belongs to
+#pragma unroll
+      for (int blk = 0; blk < 4; ++blk) {
+        const uint32_t o = (uint32_t)row_for(t, 8 * blk + (n & 7)) * R.k_st + R.k_lane;
+        wide_k(T, blk, 0) = load_row16(R.Kb, o);
+        wide_k(T, blk, 1) = load_row16(R.Kb, o + 128u);
+      }
+      return;
+    }
     const uint32_t oa = (uint32_t)row_for(t, n) * R.k_st + R.k_lane;
     const uint32_t ob = (uint32_t)row_for(t, 16 + n) * R.k_st + R.k_lane;
 #pragma unroll
@@ -641,8 +659,8 @@ __global__ __launch_bounds__(kAttnThreads, BIG ? 1 : 2) void attn_dense_kernel(c
     if (NOV) return;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      T.v[i] = load_row16(R.Vb, (uint32_t)row_for(t, 4 * jg + i) * R.v_st + R.v_lane);
-      T.v[4 + i] = load_row16(R.Vb, (uint32_t)row_for(t, 16 + 4 * jg + i) * R.v_st + R.v_lane);
+      T.v[i] = load_row16(R.Vb, (uint32_t)row_for(t, slot_pos<WIDE>(jg, i)) * R.v_st + R.v_lane);
+      T.v[4 + i] = load_row16(R.Vb, (uint32_t)row_for(t, slot_pos<WIDE>(jg, 4 + i)) * R.v_st + R.v_lane);
     }
   };
   Pages P;
@@ -729,7 +747,9 @@ __global__ __launch_bounds__(kAttnThreads, BIG ? 1 : 2) void attn_dense_kernel(c
       l_run = 0.f;
     }
     float y[8];
-    qk_phase(T, qreg, a.scale_log2, y);
+    f32x4 s4[4];
+    if (WIDE) qk_products_wide(T, qreg, s4);  // the refill of the K half below goes out before the lane exchanges
+    else qk_phase(T, qreg, a.scale_log2, y);
     float k2a = 0.f, k2b = 0.f;
     if (EXPOSE == 2) knorm_phase(T, jg, n, k2a, k2b);
     int pra = 0, prb = 0;
@@ -742,9 +762,13 @@ __global__ __launch_bounds__(kAttnThreads, BIG ? 1 : 2) void attn_dense_kernel(c
     } else {
       issue_k_tile(T, t + NB * step);
     }
+    if (WIDE) {
+      __builtin_amdgcn_sched_barrier(0);
+      qk_join_wide(s4, a.scale_log2, y);
+    }
     if (EXPOSE != 0 && inJ) {  // positions past |J| land in the padding of the last tile, never used
       float* st = stash + n_stashed * (rows_exp * kTile);
-      stage_logits(st, y, jg, n, G);
+      stage_logits<WIDE>(st, y, jg, n, G);
       if (EXPOSE == 2 && jg == (n >> 2)) {
         st[G * kTile + n] = k2a;
         st[G * kTile + 16 + n] = k2b;
@@ -753,7 +777,7 @@ __global__ __launch_bounds__(kAttnThreads, BIG ? 1 : 2) void attn_dense_kernel(c
     }
     const int p0 = (inJ ? t : t - nTJ) * kTile;
     const int N = inJ ? NJ : NS;
-    if (p0 + kTile > N) mask_tail<!NOV>(T, y, jg, p0, N);
+    if (p0 + kTile > N) mask_tail<!NOV, WIDE>(T, y, jg, p0, N);
     bf16x8 a_hi, a_lo;
     softmax_phase(y, acc, m_run, l_run, jg, a_hi, a_lo);
     if (!NOV) pv_phase(T, a_hi, a_lo, acc);
@@ -1263,7 +1287,8 @@ hipError_t launch_attn_gather_floor(const AttnArgs& a, int B, int n_slots, int t
 // ------------------------------------------------------------------------------------------------
 // Memory skeleton of the dense kernel -- a measurement aid, not part of the path: the dense launch's grid and
 // tile dealing (tiles first, first + step, ... of the prefix per wave, two tile buffers in flight, K half and V
-// half of a buffer refilled separately), nontemporal 16-byte loads, nothing computed: what arrives is folded
+// half of a buffer refilled separately; tile t starts at row n_sink + 32 t as the kernel's tiles of J do), nontemporal
+// 16-byte loads, nothing computed: what arrives is folded
 // into one word per wave.  WIDE: K rows requested as whole 128-byte lines (the gather kernels' layout) instead
 // of the four 64-byte pieces the dense kernel's operand layout asks for.  No logits are written.
 // ------------------------------------------------------------------------------------------------
@@ -1284,8 +1309,8 @@ __global__ __launch_bounds__(kAttnThreads, 1) void attn_dense_floor_kernel(const
   R.n = n;
   const int first = slot * kWaves + w, step = a.n_split * kWaves;
   Tile T, T2;
-  issue_affine<WIDE>(T, R, first * kTile, a.row_cap);           // before ctx_len arrives, as the kernel does
-  issue_affine<WIDE>(T2, R, (first + step) * kTile, a.row_cap);
+  issue_affine<WIDE>(T, R, a.n_sink + first * kTile, a.row_cap);  // before ctx_len arrives, as the kernel does
+  issue_affine<WIDE>(T2, R, a.n_sink + (first + step) * kTile, a.row_cap);
   int bad = 0;
   const int L = guarded_len(a.ctx_len[b * a.ms], a.len_cap, bad);
   const int r_last = max(L, 1) - 1;
@@ -1296,10 +1321,10 @@ __global__ __launch_bounds__(kAttnThreads, 1) void attn_dense_floor_kernel(const
     const int t_next = first + (k + 2) * step;
 #pragma unroll
     for (int i = 0; i < 4; ++i) fold ^= fold16(B.ka[i]) ^ fold16(B.kb[i]);
-    issue_k_affine<WIDE>(B, R, t_next * kTile, r_last);
+    issue_k_affine<WIDE>(B, R, a.n_sink + t_next * kTile, r_last);
 #pragma unroll
     for (int i = 0; i < 8; ++i) fold ^= fold16(B.v[i]);
-    issue_v_affine<WIDE>(B, R, t_next * kTile, r_last);
+    issue_v_affine<WIDE>(B, R, a.n_sink + t_next * kTile, r_last);
   };
   int k = 0;
   for (; k + 1 < K; k += 2) {
@@ -1574,6 +1599,14 @@ hipError_t launch_trigger(const int32_t* last_token, const uint32_t* bitmap, int
 
 template <bool PAGED>
 static void launch_dense_t(const AttnArgs& a, dim3 grid, hipStream_t s) {
+  if constexpr (!PAGED) {
+    if (a.dense_wide && a.G <= 8 && !a.with_knorm && !a.no_v) {
+      if (a.logits != nullptr && a.big_stash) hipLaunchKernelGGL((attn_dense_kernel<1, false, true, false, true>), grid, dim3(kAttnThreads), 0, s, a);
+      else if (a.logits != nullptr) hipLaunchKernelGGL((attn_dense_kernel<1, false, false, false, true>), grid, dim3(kAttnThreads), 0, s, a);
+      else hipLaunchKernelGGL((attn_dense_kernel<0, false, false, false, true>), grid, dim3(kAttnThreads), 0, s, a);
+      return;
+    }
+  }
   if (a.logits != nullptr && a.no_v && a.with_knorm)  // evidence only (always with the big stash)
     hipLaunchKernelGGL((attn_dense_kernel<2, PAGED, true, true>), grid, dim3(kAttnThreads), 0, s, a);
   else if (a.logits != nullptr && a.no_v)

@@ -107,6 +107,7 @@ struct AttnArgs {
   float* logits;                 // dense mode, nullptr: do not expose logits
   int32_t with_knorm;            // dense mode: also expose the squared key norms (full Selector)
   int32_t no_v;                  // dense mode with logits: evidence only -- V is not read, the records hold no output
+  int32_t dense_wide;            // dense mode: K rows read as whole 128-byte lines (query groups of at most 8 heads, flat cache)
   int32_t big_stash;             // dense mode with logits: the variant with the 32 KB stash per wave (one workgroup per CU)
   int32_t pipelined;             // gather mode: few workgroups per (b, h), each wave walks several tiles
   float* out_direct;             // gather / compact mode with n_split == 1: write the output here, no record

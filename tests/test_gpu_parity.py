@@ -910,3 +910,24 @@ def test_decode_loop_from_the_packed_descriptor(oracle):
         assert r.sfi.sfi_device_status(r.ctx.handle) == 0
     finally:
         r.close()
+
+
+def test_dense_kernel_with_whole_line_k_loads(oracle, tiny):
+    """The dense kernel's other K layout (sfi_set_dense_k_layout: whole 128-byte lines, halves joined by lane
+    exchanges): same outputs within the tolerance, same index sets."""
+    w, r = tiny
+    _step("dense kernel, whole-line K loads")
+    q, ctx = w.q(0), w.ctx_len(0)
+    ref_out, ref_sel, ref_nsel = r.slow(q, ctx, w.budget)
+    r.sfi.sfi_set_dense_k_layout(r.ctx.handle, True)
+    try:
+        out, sel, nsel = r.slow(q, ctx, w.budget)
+        check_out(out, oracle.dense(q, w.K, w.V, ctx))
+        sel_o, nsel_o, z = oracle.selector(q, w.K, ctx, w.budget, w.n_sink, w.recent)
+        check_selection(sel, nsel, sel_o, nsel_o, z, ctx, w.n_sink, w.recent, w.budget)
+        assert (sel == ref_sel).all() and (nsel == ref_nsel).all()
+        for L in (1, 5, 37, 70, 1000):
+            c = np.array([L, max(1, L // 3)], np.int32)
+            check_out(r.dense(q, c), oracle.dense(q, w.K, w.V, c))
+    finally:
+        r.sfi.sfi_set_dense_k_layout(r.ctx.handle, False)
