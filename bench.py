@@ -750,7 +750,15 @@ def bench_mix(args):
     if not args.page_size:
         dskel = lambda v: (lambda l, step: sfi.sfi_dense_attn_floor(h, Ks[l], Vs[l], ctx_d, max_ctx, v))
         dense_floor = {"kernel_k_layout_us": float(graph_avg_ms(dskel(0), 2) * 1e3),
-                       "whole_line_k_us": float(graph_avg_ms(dskel(1), 2) * 1e3)}
+                       "whole_line_k_us": float(graph_avg_ms(dskel(1), 2) * 1e3),
+                       # the same with every wave asleep 2 x 1024 cycles per tile, where the kernel has its arithmetic
+                       "kernel_k_layout_with_2048_idle_cycles_per_tile_us": float(graph_avg_ms(dskel(0 + 16 * 16), 2) * 1e3),
+                       # what exposing the logits to the Selector costs: dense attention + merge launch without them
+                       # (sfi_dense_attn) and with them (sfi_slow_attn), both timed like the skeletons
+                       "attention_and_merge_without_logits_us": float(graph_avg_ms(
+                           lambda l, step: sfi.sfi_dense_attn(h, q_all[step, l], Ks[l], Vs[l], ctx_d, max_ctx, outs[l]), 2) * 1e3),
+                       "attention_and_merge_with_logits_us": float(graph_avg_ms(
+                           lambda l, step: sfi.sfi_slow_attn(h, q_all[step, l], Ks[l], Vs[l], ctx_d, max_ctx, outs[l]), 2) * 1e3)}
     roof = {
         "bound": "hbm", "kernel": f"sfi::attn_{dominant}_kernel",
         "achieved": fast_gbs if dominant != "dense" else dense_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",

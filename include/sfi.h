@@ -455,8 +455,10 @@ int sfi_fast_step_floor(sfi_ctx* ctx, const void* q, const void* K, const void* 
 /*
  * Memory skeleton of the dense launch -- a measurement aid like sfi_fast_step_floor: the grid and tile dealing of
  * sfi_dense_attn over rows [0, ctx_len[b]) of K and V (two tile buffers per wave, nontemporal 16-byte loads), nothing
- * computed, no logits written.  variant 0: K rows requested in the dense kernel's own layout (four 64-byte pieces per
- * row); 1: as whole 128-byte lines.  Flat caches only.  Its time is the streaming ceiling the dense kernel is held against.
+ * computed, no logits written.  variant bits 0-3: 0 = K rows requested in the dense kernel's own layout (four 64-byte
+ * pieces per row), 1 = as whole 128-byte lines.  Bits 4 and up: idle units u (0 .. 64): every wave sleeps u x 64 cycles
+ * after each half of each tile, where the kernel has its arithmetic.  Other values: SFI_EUNSUPPORTED.  Flat caches only.
+ * Its time is the streaming ceiling the dense kernel is held against.
  */
 int sfi_dense_attn_floor(sfi_ctx* ctx, const void* K, const void* V, const int32_t* ctx_len, int32_t max_len,
                          int32_t variant, void* stream);

@@ -1291,9 +1291,16 @@ hipError_t launch_attn_gather_floor(const AttnArgs& a, int B, int n_slots, int t
 // 16-byte loads, nothing computed: what arrives is folded
 // into one word per wave.  WIDE: K rows requested as whole 128-byte lines (the gather kernels' layout) instead
 // of the four 64-byte pieces the dense kernel's operand layout asks for.  No logits are written.
+// The eight loads of a half go out back to back, as the kernel issues them (left to itself the compiler refills
+// register by register as the fold frees them, and that order of requests is 10 % slower).  idle_units > 0: the wave
+// sleeps idle_units x 64 cycles where the kernel has its two blocks of arithmetic (after the K half and after the V
+// half of every tile), to show what time between the waits costs when the memory side is the same.
 // ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ void idle(int units) {
+  for (int i = 0; i < units; ++i) __builtin_amdgcn_s_sleep(1);
+}
 template <bool WIDE>
-__global__ __launch_bounds__(kAttnThreads, 1) void attn_dense_floor_kernel(const AttnArgs a) {
+__global__ __launch_bounds__(kAttnThreads, 1) void attn_dense_floor_kernel(const AttnArgs a, int idle_units) {
   const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x;
   const int lane = tid & 63, w = tid >> 6;
@@ -1321,10 +1328,18 @@ __global__ __launch_bounds__(kAttnThreads, 1) void attn_dense_floor_kernel(const
     const int t_next = first + (k + 2) * step;
 #pragma unroll
     for (int i = 0; i < 4; ++i) fold ^= fold16(B.ka[i]) ^ fold16(B.kb[i]);
+    __builtin_amdgcn_sched_barrier(0);
+    idle(idle_units);
+    __builtin_amdgcn_sched_barrier(0);
     issue_k_affine<WIDE>(B, R, a.n_sink + t_next * kTile, r_last);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < 8; ++i) fold ^= fold16(B.v[i]);
+    __builtin_amdgcn_sched_barrier(0);
+    idle(idle_units);
+    __builtin_amdgcn_sched_barrier(0);
     issue_v_affine<WIDE>(B, R, a.n_sink + t_next * kTile, r_last);
+    __builtin_amdgcn_sched_barrier(0);
   };
   int k = 0;
   for (; k + 1 < K; k += 2) {
@@ -1341,10 +1356,10 @@ __global__ __launch_bounds__(kAttnThreads, 1) void attn_dense_floor_kernel(const
   const int64_t head0 = (int64_t)b * a.Hq + h * a.G;
   if (lane == 0) reinterpret_cast<uint32_t*>(a.part)[((head0 * kSlotCap + slot) * kPartStride) + w] = fold;
 }
-hipError_t launch_attn_dense_floor(const AttnArgs& a, int B, int n_slots, int wide, hipStream_t s) {
+hipError_t launch_attn_dense_floor(const AttnArgs& a, int B, int n_slots, int wide, int idle_units, hipStream_t s) {
   const dim3 grid(n_slots, a.Hkv, B);
-  if (wide) hipLaunchKernelGGL(attn_dense_floor_kernel<true>, grid, dim3(kAttnThreads), 0, s, a);
-  else hipLaunchKernelGGL(attn_dense_floor_kernel<false>, grid, dim3(kAttnThreads), 0, s, a);
+  if (wide) hipLaunchKernelGGL(attn_dense_floor_kernel<true>, grid, dim3(kAttnThreads), 0, s, a, idle_units);
+  else hipLaunchKernelGGL(attn_dense_floor_kernel<false>, grid, dim3(kAttnThreads), 0, s, a, idle_units);
   return hipGetLastError();
 }
 

@@ -931,3 +931,35 @@ def test_dense_kernel_with_whole_line_k_loads(oracle, tiny):
             check_out(r.dense(q, c), oracle.dense(q, w.K, w.V, c))
     finally:
         r.sfi.sfi_set_dense_k_layout(r.ctx.handle, False)
+
+
+def test_measurement_skeletons_run_and_leave_the_path_alone(oracle, tiny):
+    """The memory skeletons bench.py times next to the kernels (sfi_fast_step_floor, sfi_dense_attn_floor) take the same
+    arguments as the launches they mirror, refuse variants that are not defined, and leave nothing behind that a
+    following real step could trip over: a slow step and a fast step after them still match the oracle."""
+    import torch
+    w, r = tiny
+    _step("measurement skeletons")
+    sfi, h = r.sfi, r.ctx.handle
+    q, ctx = w.q(0), w.ctx_len(0)
+    out0, sel, nsel = r.slow(q, ctx, w.budget)
+    q_d, ctx_d, rs_d = to_dev(w.q(1)), i32_dev(w.ctx_len(1)), i32_dev(w.recent_start(1))
+    sel_d, nsel_d = i32_dev(sel), i32_dev(nsel)
+    scratch_out = torch.zeros_like(r.out)
+    for v in (0, 1, 2, 4, 8):
+        sfi.sfi_fast_step_floor(h, q_d, r.K, r.V, sel_d, nsel_d, sel.shape[2], rs_d, ctx_d, scratch_out, v)
+    for v in (0, 1, 16 * 4, 16 * 4 + 1):
+        sfi.sfi_dense_attn_floor(h, r.K, r.V, ctx_d, 0, v)
+    torch.cuda.synchronize()
+    for v in (3, 5, 12, 16, -1):
+        with pytest.raises(sfi.SfiError):
+            sfi.sfi_fast_step_floor(h, q_d, r.K, r.V, sel_d, nsel_d, sel.shape[2], rs_d, ctx_d, scratch_out, v)
+    for v in (2, 15, 16 * 65, -1):
+        with pytest.raises(sfi.SfiError):
+            sfi.sfi_dense_attn_floor(h, r.K, r.V, ctx_d, 0, v)
+    assert sfi.sfi_device_status(h) == 0
+    got = r.fast(w.q(1), sel, nsel, w.recent_start(1), w.ctx_len(1))
+    check_out(got, oracle.sparse(w.q(1), w.K, w.V, sel, nsel, w.recent_start(1), w.ctx_len(1), w.n_sink))
+    out1, sel1, nsel1 = r.slow(q, ctx, w.budget)
+    assert (sel1 == sel).all() and (nsel1 == nsel).all()
+    check_out(out1, oracle.dense(q, w.K, w.V, ctx))
