@@ -963,3 +963,32 @@ def test_measurement_skeletons_run_and_leave_the_path_alone(oracle, tiny):
     out1, sel1, nsel1 = r.slow(q, ctx, w.budget)
     assert (sel1 == sel).all() and (nsel1 == nsel).all()
     check_out(out1, oracle.dense(q, w.K, w.V, ctx))
+
+
+@pytest.mark.parametrize("case", ["random", "ties", "all_equal"])
+def test_top_k_over_several_segments(oracle, case):
+    """Top-K (Eq. topk_out) where a (sequence, KV head) pair spans several 2048-position segments of the Selector's
+    launches, with ragged lengths: random scores, a tie class that spans two segments and is larger than a segment, and
+    all scores equal.  Several budgets on the same evidence, from 1 to more than |J|."""
+    w = syn.make_tiny(L0=9000, steps=1, budget=700, recent=64, n_support=24, B=2)
+    w.L0 = np.array([9000, 4300], np.int32)
+    if case == "ties":
+        for j in range(3000, 5200):
+            w.K[:, :, j] = w.K[:, :, 3000]
+    if case == "all_equal":
+        w.K[:] = 0
+    r = Runner(w, max_budget=9000)
+    try:
+        _step(f"top-k over several segments, {case}")
+        q, ctx = w.q(0), w.ctx_len(0)
+        for budget in (700, 1, 64, 2500, 9000):
+            sel_o, nsel_o, z = oracle.selector(q, w.K, ctx, budget, w.n_sink, w.recent)
+            _, sel, nsel = r.slow(q, ctx, budget)
+            check_selection(sel, nsel, sel_o, nsel_o, z, ctx, w.n_sink, w.recent, budget)
+            if case == "all_equal":
+                for b in range(w.B):
+                    k = int(nsel[b, 0])
+                    assert sel[b, 0, :k].tolist() == list(range(w.n_sink, w.n_sink + k))
+        assert r.sfi.sfi_device_status(r.ctx.handle) == 0
+    finally:
+        r.close()
