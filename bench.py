@@ -753,6 +753,10 @@ def bench_mix(args):
                        "whole_line_k_us": float(graph_avg_ms(dskel(1), 2) * 1e3),
                        # the same with every wave asleep 2 x 1024 cycles per tile, where the kernel has its arithmetic
                        "kernel_k_layout_with_2048_idle_cycles_per_tile_us": float(graph_avg_ms(dskel(0 + 16 * 16), 2) * 1e3),
+                       # the same with a fifth wave per workgroup that stores what the slow step would expose (G x 128
+                       # bytes per tile) while the four waves read; and with all those stores going to the same 2 KB
+                       "kernel_k_layout_with_a_writer_wave_us": float(graph_avg_ms(dskel(2048), 2) * 1e3),
+                       "kernel_k_layout_with_a_writer_wave_on_2KB_us": float(graph_avg_ms(dskel(4096), 2) * 1e3),
                        # what exposing the logits to the Selector costs: dense attention + merge launch without them
                        # (sfi_dense_attn) and with them (sfi_slow_attn), both timed like the skeletons
                        "attention_and_merge_without_logits_us": float(graph_avg_ms(

@@ -456,9 +456,13 @@ int sfi_fast_step_floor(sfi_ctx* ctx, const void* q, const void* K, const void* 
  * Memory skeleton of the dense launch -- a measurement aid like sfi_fast_step_floor: the grid and tile dealing of
  * sfi_dense_attn over rows [0, ctx_len[b]) of K and V (two tile buffers per wave, nontemporal 16-byte loads), nothing
  * computed, no logits written.  variant bits 0-3: 0 = K rows requested in the dense kernel's own layout (four 64-byte
- * pieces per row), 1 = as whole 128-byte lines.  Bits 4 and up: idle units u (0 .. 64): every wave sleeps u x 64 cycles
- * after each half of each tile, where the kernel has its arithmetic.  Other values: SFI_EUNSUPPORTED.  Flat caches only.
- * Its time is the streaming ceiling the dense kernel is held against.
+ * pieces per row), 1 = as whole 128-byte lines.  Bits 4-10: idle units u (0 .. 64): every wave sleeps u x 64 cycles
+ * after each half of each tile, where the kernel has its arithmetic.  Bits 11 and up: 1 = every workgroup gets a fifth
+ * wave that stores what the slow step would expose (G x 128 bytes per tile, into the workspace's logits buffer, junk
+ * values) at about the readers' pace; 2 = the same stores, all to the same 2 KB per (sequence, KV head).  Other values:
+ * SFI_EUNSUPPORTED.  Flat caches only.  Its time is the streaming ceiling the dense kernel is held against; the writer
+ * variants show what store instructions cost a compute unit that is streaming rows.  Overwrites the logits a slow step
+ * left in the workspace.
  */
 int sfi_dense_attn_floor(sfi_ctx* ctx, const void* K, const void* V, const int32_t* ctx_len, int32_t max_len,
                          int32_t variant, void* stream);

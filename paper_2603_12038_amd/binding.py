@@ -218,7 +218,8 @@ def sfi_fast_step_static(cfg: SfiConfig, q, K, V, sel_idx, n_sel, sel_stride, re
 
 def sfi_dense_attn_floor(ctx, K, V, ctx_len, max_len, variant: int, stream=None) -> None:
     """Memory skeleton of the dense launch (measurement aid): variant 0 = the kernel's K layout, 1 = whole-line K loads;
-    + 16 * u: every wave also sleeps u x 64 cycles after each half of each tile."""
+    + 16 * u: every wave also sleeps u x 64 cycles after each half of each tile; + 2048 (4096): a fifth wave per workgroup
+    stores what the slow step would expose while the four read (all to the same 2 KB)."""
     _check(load_library().sfi_dense_attn_floor(ctx, _ptr(K), _ptr(V), _ptr(ctx_len), max_len, variant, _stream(stream)),
            "sfi_dense_attn_floor")
 

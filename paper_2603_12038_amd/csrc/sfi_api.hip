@@ -467,7 +467,8 @@ int sfi_dense_attn_floor(sfi_ctx* x, const void* K, const void* V, const int32_t
                          void* stream) {
   if (x == nullptr || K == nullptr || V == nullptr || ctx_len == nullptr) return SFI_EINVAL;
   if (misaligned(K, 16) || misaligned(V, 16) || misaligned(ctx_len, 4)) return SFI_EALIGN;
-  if (variant < 0 || (variant & 15) > 1 || (variant >> 4) > 64 || x->table != nullptr || x->cfg.page_size != 0) return SFI_EUNSUPPORTED;
+  const int idle_units = (variant >> 4) & 127, writer = variant >> 11;
+  if (variant < 0 || (variant & 15) > 1 || idle_units > 64 || writer > 2 || x->table != nullptr || x->cfg.page_size != 0) return SFI_EUNSUPPORTED;
   int ml;
   const int rc = resolve_max_len(x, max_len, &ml);
   if (rc != SFI_OK) return rc;
@@ -476,7 +477,8 @@ int sfi_dense_attn_floor(sfi_ctx* x, const void* K, const void* V, const int32_t
   a.n_split = dense_splits_for(x, ml, false);
   set_dense_bounds(x, &a, ml);
   x->last_dense_splits = a.n_split;
-  SFI_TRY(launch_attn_dense_floor(a, x->cfg.batch, a.n_split, variant & 1, variant >> 4, (hipStream_t)stream));
+  a.logits = x->ws.logits;  // where the writer wave's stores go (the slow step's logits buffer)
+  SFI_TRY(launch_attn_dense_floor(a, x->cfg.batch, a.n_split, variant & 1, idle_units, writer, (hipStream_t)stream));
   return SFI_OK;
 }
 

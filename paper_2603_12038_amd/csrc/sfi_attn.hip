@@ -1295,16 +1295,37 @@ hipError_t launch_attn_gather_floor(const AttnArgs& a, int B, int n_slots, int t
 // register by register as the fold frees them, and that order of requests is 10 % slower).  idle_units > 0: the wave
 // sleeps idle_units x 64 cycles where the kernel has its two blocks of arithmetic (after the K half and after the V
 // half of every tile), to show what time between the waits costs when the memory side is the same.
+// writer > 0: the workgroup has a fifth wave that does nothing but store what the kernel would expose (G x 128 bytes
+// per tile, the kernel's addresses; writer == 2: always the same 2 KB of them), at about the readers' pace, while the
+// four waves read: what store instructions cost a compute unit that is streaming rows.
 // ------------------------------------------------------------------------------------------------
 __device__ __forceinline__ void idle(int units) {
   for (int i = 0; i < units; ++i) __builtin_amdgcn_s_sleep(1);
 }
 template <bool WIDE>
-__global__ __launch_bounds__(kAttnThreads, 1) void attn_dense_floor_kernel(const AttnArgs a, int idle_units) {
+__global__ __launch_bounds__(kAttnThreads + 64, 1) void attn_dense_floor_kernel(const AttnArgs a, int idle_units, int writer) {
   const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x;
   const int lane = tid & 63, w = tid >> 6;
   const int jg = lane >> 4, n = lane & 15;
+  if (w == kWaves) {  // the writer wave (only launched with writer > 0)
+    int bad0 = 0;
+    const int L0 = guarded_len(a.ctx_len[b * a.ms], a.len_cap, bad0);
+    const int nT0 = (L0 + kTile - 1) / kTile;
+    const int step0 = a.n_split * kWaves;
+    float* lg = a.logits + (int64_t)(b * a.Hkv + h) * a.G * a.ld_pos;
+    const int tile_floats = a.G * kTile;
+    const int k_max = slot * kWaves < nT0 ? (nT0 - slot * kWaves + step0 - 1) / step0 : 0;
+    for (int k = 0; k < k_max; ++k) {
+      __builtin_amdgcn_s_sleep(90);  // 5760 cycles: a little less than the four waves take per tile
+      for (int ww = 0; ww < kWaves; ++ww) {
+        const int t = slot * kWaves + ww + k * step0;
+        if (t < a.max_tiles && lane * 4 < tile_floats)
+          *reinterpret_cast<float4*>(lg + (int64_t)(writer == 2 ? ww : t) * tile_floats + lane * 4) = make_float4((float)lane, 0.f, 0.f, 0.f);
+      }
+    }
+    return;
+  }
   Rows R;
   R.Kb = reinterpret_cast<const char*>(a.K + b * a.k_sb + h * a.k_sh);
   R.Vb = reinterpret_cast<const char*>(a.V + b * a.v_sb + h * a.v_sh);
@@ -1356,10 +1377,11 @@ __global__ __launch_bounds__(kAttnThreads, 1) void attn_dense_floor_kernel(const
   const int64_t head0 = (int64_t)b * a.Hq + h * a.G;
   if (lane == 0) reinterpret_cast<uint32_t*>(a.part)[((head0 * kSlotCap + slot) * kPartStride) + w] = fold;
 }
-hipError_t launch_attn_dense_floor(const AttnArgs& a, int B, int n_slots, int wide, int idle_units, hipStream_t s) {
+hipError_t launch_attn_dense_floor(const AttnArgs& a, int B, int n_slots, int wide, int idle_units, int writer, hipStream_t s) {
   const dim3 grid(n_slots, a.Hkv, B);
-  if (wide) hipLaunchKernelGGL(attn_dense_floor_kernel<true>, grid, dim3(kAttnThreads), 0, s, a, idle_units);
-  else hipLaunchKernelGGL(attn_dense_floor_kernel<false>, grid, dim3(kAttnThreads), 0, s, a, idle_units);
+  const dim3 block(writer != 0 ? kAttnThreads + 64 : kAttnThreads);
+  if (wide) hipLaunchKernelGGL(attn_dense_floor_kernel<true>, grid, block, 0, s, a, idle_units, writer);
+  else hipLaunchKernelGGL(attn_dense_floor_kernel<false>, grid, block, 0, s, a, idle_units, writer);
   return hipGetLastError();
 }
 

@@ -215,7 +215,7 @@ struct SelArgs {
 };
 
 hipError_t launch_attn_dense(const AttnArgs& a, int B, int n_slots, hipStream_t s);
-hipError_t launch_attn_dense_floor(const AttnArgs& a, int B, int n_slots, int wide, int idle_units, hipStream_t s);
+hipError_t launch_attn_dense_floor(const AttnArgs& a, int B, int n_slots, int wide, int idle_units, int writer, hipStream_t s);
 hipError_t launch_attn_compact(const AttnArgs& a, int B, int n_slots, hipStream_t s);
 hipError_t launch_reorg(const ReorgArgs& a, int B, int rows, hipStream_t s);
 hipError_t launch_attn_gather(const AttnArgs& a, int B, int n_slots, hipStream_t s);

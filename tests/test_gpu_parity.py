@@ -948,13 +948,13 @@ def test_measurement_skeletons_run_and_leave_the_path_alone(oracle, tiny):
     scratch_out = torch.zeros_like(r.out)
     for v in (0, 1, 2, 4, 8):
         sfi.sfi_fast_step_floor(h, q_d, r.K, r.V, sel_d, nsel_d, sel.shape[2], rs_d, ctx_d, scratch_out, v)
-    for v in (0, 1, 16 * 4, 16 * 4 + 1):
+    for v in (0, 1, 16 * 4, 16 * 4 + 1, 2048, 4096 + 16 * 2 + 1):
         sfi.sfi_dense_attn_floor(h, r.K, r.V, ctx_d, 0, v)
     torch.cuda.synchronize()
     for v in (3, 5, 12, 16, -1):
         with pytest.raises(sfi.SfiError):
             sfi.sfi_fast_step_floor(h, q_d, r.K, r.V, sel_d, nsel_d, sel.shape[2], rs_d, ctx_d, scratch_out, v)
-    for v in (2, 15, 16 * 65, -1):
+    for v in (2, 15, 16 * 65, 3 * 2048, -1):
         with pytest.raises(sfi.SfiError):
             sfi.sfi_dense_attn_floor(h, r.K, r.V, ctx_d, 0, v)
     assert sfi.sfi_device_status(h) == 0
