@@ -133,6 +133,8 @@ def bench_serving(args):
     h = ctx.handle
     if args.dense_wgs or args.fast_tpw or args.fast_merge:
         sfi.sfi_set_tuning(h, args.dense_wgs, args.fast_tpw, FAST_MERGE[args.fast_merge])
+    if args.mixed_dense == "grid":
+        sfi.sfi_set_mixed_plan(h, False)
     q_all = torch.randn(n_dec + SEG, NL, B, Hq, d, device=dev, generator=gen).to(torch.bfloat16)
     outs = [torch.zeros(B, Hq, d, dtype=torch.float32, device=dev) for _ in range(NL)]
     sels = [torch.full((B, Hkv, w.budget), -1, dtype=torch.int32, device=dev) for _ in range(NL)]
@@ -249,7 +251,7 @@ def bench_serving(args):
         "config": {"workload": f"serving mix: B{B} Hq{Hq} Hkv{Hkv} d{d} ragged ctx {int(w.L0.min())}..{int(w.L0.max())} "
                                f"k{w.budget} R{w.recent} sink{w.n_sink}, per-sequence slow gaps ~ Geometric(1/20)",
                    "step": f"{SEG} decode steps (sfi_mixed_step) x {NL} virtual layers", "virtual_layers": NL,
-                   "launch": "graph", "slow_sequence_steps_in_timed_region": n_slow},
+                   "launch": "graph", "mixed_dense": args.mixed_dense, "slow_sequence_steps_in_timed_region": n_slow},
         "roofline": {"bound": "hbm", "kernel": "sfi::attn_gather_stream_kernel (all-fast step)", "achieved": fast_gbs,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": fast_gbs / HBM_PEAK_GBS, "traffic": None,
                      "algorithmic_bytes_per_launch": fast_bytes, "us_per_launch": gather_us},
@@ -367,6 +369,9 @@ def main():
                          "holds k_t then v_t (the library sees two base pointers and a row stride of 2 d either way)")
     ap.add_argument("--out-bf16", action="store_true",
                     help="outputs stored as bf16 (cfg.out_bf16) instead of fp32; slow+fast mix workloads only")
+    ap.add_argument("--mixed-dense", choices=["planned", "grid"], default="planned",
+                    help="serving workload, A/B of the ragged step's dense launch: planned on the device (one workgroup per "
+                         "compute unit, splits per slow sequence by length; default) or one workgroup per cell of the batch")
     ap.add_argument("--dense-k", choices=["pieces", "whole-lines"], default="pieces",
                     help="A/B of the dense kernel's K loads: four 64-byte pieces per row (default) or whole 128-byte lines")
     ap.add_argument("--no-cpu-baseline", action="store_true")

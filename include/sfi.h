@@ -404,6 +404,15 @@ int sfi_set_tuning(sfi_ctx* ctx, int32_t dense_target_wgs, int32_t fast_tiles_pe
  * faster one on MI355X. */
 int sfi_set_dense_k_layout(sfi_ctx* ctx, int32_t whole_lines);
 
+/* A/B knob of the dense launch inside sfi_mixed_step, sfi_mixed_step_compact and sfi_mixed_step_desc (the ragged step of
+ * Sec. 4.2, where which sequences take a slow step is only known on the device).  on = 1 (default): the launch is one
+ * workgroup per compute unit; every workgroup derives the same plan from the flags and lengths -- the slow sequences
+ * and, for each, a number of splits in proportion to its length -- and takes its share of the cells, so the shares are
+ * equal whatever the mix (batches of up to 1024 sequences, and only where the fast step's merge runs inside its kernel;
+ * otherwise as with on = 0).  on = 0: one workgroup per (split, KV head, sequence) cell of the whole batch with the
+ * finest split; workgroups of fast sequences exit at once.  Same results.  Other values: SFI_EINVAL. */
+int sfi_set_mixed_plan(sfi_ctx* ctx, int32_t on);
+
 /* Launch geometry the library would choose, without launching anything (host arithmetic only): split
  * workgroups per (sequence, KV head) of a dense launch bounded by max_len rows (0 = cfg.max_ctx) and
  * of a fast step whose index lists are sel_stride wide.  Either output may be NULL.  SFI_EINVAL for a

@@ -43,7 +43,7 @@ _lib: Optional[C.CDLL] = None
 EXPORTS = ("sfi_workspace_bytes", "sfi_create", "sfi_set_block_table", "sfi_destroy", "sfi_strerror", "sfi_slow_step", "sfi_slow_attn",
            "sfi_slow_select", "sfi_evidence_add", "sfi_evidence_add_causal", "sfi_evidence_select", "sfi_dense_attn",
            "sfi_fast_step", "sfi_fast_step_static", "sfi_fast_step_floor", "sfi_dense_attn_floor", "sfi_reorg", "sfi_fast_step_compact", "sfi_mixed_step", "sfi_mixed_step_compact", "sfi_step_begin", "sfi_mixed_step_desc", "sfi_trigger", "sfi_advance", "sfi_set_profiling", "sfi_stage_times",
-           "sfi_set_tuning", "sfi_set_dense_k_layout", "sfi_plan_splits", "sfi_device_status", "sfi_query_splits")
+           "sfi_set_tuning", "sfi_set_dense_k_layout", "sfi_set_mixed_plan", "sfi_plan_splits", "sfi_device_status", "sfi_query_splits")
 
 
 def load_library() -> C.CDLL:
@@ -111,6 +111,8 @@ def load_library() -> C.CDLL:
     lib.sfi_set_tuning.argtypes = [vp, i32, i32, i32]
     lib.sfi_set_dense_k_layout.restype = C.c_int
     lib.sfi_set_dense_k_layout.argtypes = [vp, i32]
+    lib.sfi_set_mixed_plan.restype = C.c_int
+    lib.sfi_set_mixed_plan.argtypes = [vp, i32]
     lib.sfi_plan_splits.restype = C.c_int
     lib.sfi_plan_splits.argtypes = [vp, i32, i32, C.POINTER(i32), C.POINTER(i32)]
     lib.sfi_device_status.restype = C.c_int
@@ -298,6 +300,10 @@ def sfi_stage_times(ctx):
 
 def sfi_set_tuning(ctx, dense_target_wgs: int = 0, fast_tiles_per_wave: int = 0, fast_merge: int = 0) -> None:
     _check(load_library().sfi_set_tuning(ctx, dense_target_wgs, fast_tiles_per_wave, fast_merge), "sfi_set_tuning")
+
+
+def sfi_set_mixed_plan(ctx, on: bool) -> None:
+    _check(load_library().sfi_set_mixed_plan(ctx, int(on)), "sfi_set_mixed_plan")
 
 
 def sfi_set_dense_k_layout(ctx, whole_lines: bool) -> None:

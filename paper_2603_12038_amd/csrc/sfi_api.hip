@@ -21,6 +21,7 @@ struct sfi_ctx {
   int fast_tiles_per_wave;  // 32-row tiles each wave of the gather launch should get; 0 = decided per launch
   int tail_merge;           // split fast-step launches merge in the attention kernel (no merge launch)
   int dense_wide;           // dense kernel reads K rows as whole 128-byte lines (A/B knob, sfi_set_dense_k_layout)
+  int mixed_plan;           // the ragged step's dense launch plans itself on the device (default; A/B knob, sfi_set_mixed_plan)
   int last_dense_splits, last_fast_splits;
   int selector_ran;         // a Selector pass has used the evidence now in the workspace: its histogram and state
                             // words are no longer the cleared ones the dense kernel left
@@ -110,6 +111,7 @@ size_t carve(const sfi_config* c, char* base, Workspace* ws) {
   ws->prior = full ? (float*)take((size_t)(B * Hkv) * ld * sizeof(float)) : nullptr;
   ws->znms = full ? (float*)take((size_t)(B * Hkv) * ld * sizeof(float)) : nullptr;
   ws->segstat = full ? (double*)take((size_t)(B * Hkv) * n_seg * kSegStats * sizeof(double)) : nullptr;
+  ws->seq_splits = (int32_t*)take((size_t)B * sizeof(int32_t));
   ws->ld_pos = ld;
   ws->n_seg_cap = n_seg;
   return off;
@@ -379,6 +381,7 @@ int sfi_create(const sfi_config* cfg, void* workspace, size_t workspace_bytes, s
   x->dense_target_wgs = 0;
   x->fast_tiles_per_wave = 0;
   x->tail_merge = 1;
+  x->mixed_plan = 1;
   // The arrival counters of split fast-step launches start at zero (and every launch leaves them there).
   // A workspace the runtime knows (device, managed, pinned) is cleared here and a failure to do so is an error: with stale
   // counters no workgroup would ever take itself for the last one.  (Without a device, or with a
@@ -913,6 +916,14 @@ int mixed_step_on(sfi_ctx* x, const void* q, const void* K, const void* V, const
   // runs when the in-kernel merge is switched off (for both kinds: it skips what is already done).
   const bool fast_done = f.n_split == 1 || f.out_merge != nullptr;
   const bool merge_in_score = fast_done;
+  // The dense launch plans itself on the device (one workgroup per compute unit, splits per slow sequence in proportion to
+  // its length, see slow_list) where its records are merged by the scoring launch, which reads the plan back.
+  const bool planned = x->mixed_plan != 0 && merge_in_score && x->cfg.batch <= kListCap;
+  if (planned) {
+    d.item_batch = x->cfg.batch;
+    d.item_wgs = x->n_cu;
+    d.seq_splits = x->ws.seq_splits;
+  }
   // the fast part reads last segment's sel rows (or compact rows) of fast sequences; the Selector and Reorg below
   // only rewrite rows of slow sequences, so the order of the two attention launches is free.
   {
@@ -936,6 +947,7 @@ int mixed_step_on(sfi_ctx* x, const void* q, const void* K, const void* V, const
     sa.part = x->ws.part;
     sa.merge_out = out;
   }
+  if (planned) sa.seq_splits = x->ws.seq_splits;
   if ((rc = run_selector(x, sa, ml, st)) != SFI_OK) return rc;
   if (cb == nullptr) return SFI_OK;
   // Reorg_i for the sequences that were refreshed (Sel_i -> Reorg_i)
@@ -1055,6 +1067,12 @@ int sfi_set_tuning(sfi_ctx* x, int32_t dense_target_wgs, int32_t fast_tiles_per_
   if (dense_target_wgs != 0) x->dense_target_wgs = dense_target_wgs > 0 ? dense_target_wgs : 0;
   if (fast_tiles_per_wave != 0) x->fast_tiles_per_wave = fast_tiles_per_wave > 0 ? fast_tiles_per_wave : 0;
   if (fast_merge != 0) x->tail_merge = fast_merge != 2;
+  return SFI_OK;
+}
+
+int sfi_set_mixed_plan(sfi_ctx* x, int32_t on) {
+  if (x == nullptr || on < 0 || on > 1) return SFI_EINVAL;
+  x->mixed_plan = on;
   return SFI_OK;
 }
 

@@ -571,12 +571,12 @@ struct ListWalk {
 // (launches where every sequence is dense run one per unit anyway; the mixed step keeps two).
 // NOV: evidence only -- no V row is read, no P V product, the records carry the softmax statistics alone.
 template <int EXPOSE, bool PAGED, bool BIG = false, bool NOV = false, bool WIDE = false>
-__global__ __launch_bounds__(kAttnThreads, BIG ? 1 : 2) void attn_dense_kernel(const AttnArgs a) {
+__device__ __forceinline__ void dense_body(const AttnArgs& a, const int n_split, const int slot, const int h, const int b,
+                                           const int tid_bias = 0) {
   constexpr int kStash = BIG ? 2 * kStashFloats : kStashFloats;
   __shared__ float s_stash[EXPOSE != 0 ? kWaves : 1][EXPOSE != 0 ? kStash : 1];  // per-wave logits stash
-  const int slot = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   if (a.is_slow != nullptr && a.is_slow[b * a.fs] == 0) return;
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x + tid_bias;  // (tid_bias: zero; see attn_dense_items_kernel)
   const int lane = tid & 63, w = tid >> 6;
   const int jg = lane >> 4, n = lane & 15;
   const int G = a.G;
@@ -600,7 +600,7 @@ __global__ __launch_bounds__(kAttnThreads, BIG ? 1 : 2) void attn_dense_kernel(c
   // (the J-only softmax statistics the Selector needs are merged from the J records alone).
   // The rows of the wave's first tile follow from the block index alone (almost always a J tile):
   // their loads go out before ctx_len arrives, clamped to the launch's row bound.
-  const int n_waves = a.n_split * kWaves;
+  const int n_waves = n_split * kWaves;
   const int first = slot * kWaves + w, step = n_waves;
   Tile T;
   // (a paged cache has valid blocks only up to ctx_len: no load before ctx_len is known)
@@ -802,6 +802,138 @@ __global__ __launch_bounds__(kAttnThreads, BIG ? 1 : 2) void attn_dense_kernel(c
   // its sink / recent tiles, slot n_waves + e with e the rank of its first such tile among them
   write_record(K == KJ ? first : n_waves + (first + KJ * step - nTJ));
   report_guard(a.guard, bad);
+}
+// One workgroup per (split, KV head, sequence) cell ...
+template <int EXPOSE, bool PAGED, bool BIG = false, bool NOV = false, bool WIDE = false>
+__global__ __launch_bounds__(kAttnThreads, BIG ? 1 : 2) void attn_dense_kernel(const AttnArgs a) {
+  dense_body<EXPOSE, PAGED, BIG, NOV, WIDE>(a, a.n_split, blockIdx.x, blockIdx.y, blockIdx.z);
+}
+// ... or, in the ragged step (sfi_mixed_step*), one workgroup per compute unit that plans the launch on the device.
+// Which sequences are slow is only known there, so the host cannot size the launch for them: one workgroup per (split,
+// KV head, sequence) cell with the finest split and an early exit for fast sequences leaves the kernel with a handful
+// of tiles per wave (a wave's start and end weigh as much as its tiles), thousands of empty workgroups, and shares
+// that follow the sequences' lengths.  Here every workgroup builds the same plan from the flags and lengths: the slow
+// sequences' ids; for each its tiles T_r (the body's own count: tiles of J plus tiles of sink ++ recent) and its splits
+// s_r = T_r x (grid / Hkv) / sum T rounded down, at least 1 and at most the host's bound a.n_split or one tile per
+// wave, what the rounding left over going one by one to the sequence with the most tiles per split -- so that the cells
+// (r, h, slot < s_r) number one per workgroup and hold the same number of tiles whatever the sequences' lengths (with
+// many slow sequences: about four splits each, dealt round robin).  Workgroup i takes cells i, i + grid, ...; workgroup
+// 0 leaves s_r in a.seq_splits for the launches that merge the records.
+// The waves of a workgroup share no LDS in the body, so a wave may be on the workgroup's next cell while another is
+// still on this one.  A cell's coordinates are made scalars again (they come out of LDS), so that the body's addressing
+// stays on the scalar unit as it is with block indices.
+template <int EXPOSE, bool PAGED>
+__global__ __launch_bounds__(kAttnThreads, 1) void attn_dense_items_kernel(const AttnArgs a) {
+  __shared__ int s_list[kListCap];       // slow sequence ids, ascending
+  __shared__ int s_tiles[kListCap];      // their tiles
+  __shared__ int s_split[kListCap];      // their splits
+  __shared__ int s_first[kListCap + 1];  // cells in front of sequence r (prefix of s_r * Hkv)
+  __shared__ int s_scr[8];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  // flags and lengths of this thread's four sequences, all requested together
+  int flag[4], len[4], c = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int b = min(4 * tid + j, a.item_batch - 1);
+    flag[j] = a.is_slow[(int64_t)b * a.fs];
+    len[j] = a.ctx_len[(int64_t)b * a.ms];
+  }
+  int tiles = 0;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    flag[j] = 4 * tid + j < a.item_batch && flag[j] != 0;
+    const int L = min(max(len[j], 0), a.len_cap);
+    const int NJ = max(0, L - a.recent - a.n_sink);
+    const int nS = min(a.n_sink, L), rs = min(max(a.n_sink, L - a.recent), L);
+    len[j] = (NJ + kTile - 1) / kTile + (nS + (L - rs) + kTile - 1) / kTile;  // from here on: the sequence's tiles
+    c += flag[j];
+    tiles += flag[j] ? len[j] : 0;
+  }
+  int inc = c;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const int t = __shfl_up(inc, d);
+    if (lane >= d) inc += t;
+  }
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) tiles += __shfl_xor(tiles, d);
+  if (lane == 63) s_scr[w] = inc;
+  if (lane == 0) s_scr[4 + w] = tiles;
+  __syncthreads();
+  int base = 0, n_slow = 0;
+#pragma unroll
+  for (int i = 0; i < kWaves; ++i) {
+    const int t = s_scr[i];
+    if (i < w) base += t;
+    n_slow += t;
+  }
+  n_slow = __builtin_amdgcn_readfirstlane(n_slow);
+  if (n_slow == 0) return;
+  const int total = max(1, s_scr[4] + s_scr[5] + s_scr[6] + s_scr[7]);
+  // splits to hand out among the slow sequences: one cell per workgroup, or, with many slow sequences, about four
+  // splits each, so that dealing the cells round robin still balances
+  const int per_head = max(max(1, (int)gridDim.x / a.Hkv), 4 * n_slow);
+  {
+    int o = base + inc - c;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (flag[j]) {
+        s_list[o] = 4 * tid + j;
+        s_tiles[o] = len[j];
+        const int want = (int)((int64_t)len[j] * per_head / total);  // rounded down: the sum must not pass per_head
+        s_split[o] = max(1, min(want, min(a.n_split, (len[j] + kWaves - 1) / kWaves)));
+        ++o;
+      }
+    }
+  }
+  __syncthreads();
+  if (tid == 0) {  // (a few dozen sequences at most in practice; done by one thread, the plan is the same everywhere)
+    int acc = 0;
+    for (int r = 0; r < n_slow; ++r) acc += s_split[r];
+    // what rounding down left over goes, one split at a time, to the sequence with the most tiles per split
+    for (int left = per_head - acc; left > 0 && n_slow <= 64; --left) {
+      int best = -1;
+      float worst = 0.f;
+      for (int r = 0; r < n_slow; ++r) {
+        const int cap = min(a.n_split, (s_tiles[r] + kWaves - 1) / kWaves);
+        const float load = (float)s_tiles[r] / (float)s_split[r];
+        if (s_split[r] < cap && load > worst) {
+          worst = load;
+          best = r;
+        }
+      }
+      if (best < 0) break;
+      ++s_split[best];
+    }
+    acc = 0;
+    for (int r = 0; r < n_slow; ++r) {
+      s_first[r] = acc;
+      acc += s_split[r] * a.Hkv;
+    }
+    s_first[n_slow] = acc;
+  }
+  __syncthreads();
+  if (blockIdx.x == 0)
+    for (int r = tid; r < n_slow; r += kAttnThreads) a.seq_splits[s_list[r]] = s_split[r];
+  const int n_items = __builtin_amdgcn_readfirstlane(s_first[n_slow]);
+  for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+    int lo = 0, hi = n_slow;  // the sequence whose cells include this one: s_first[lo] <= item < s_first[lo + 1]
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (s_first[mid] <= item) lo = mid;
+      else hi = mid;
+    }
+    const int r = lo;
+    const int ns = __builtin_amdgcn_readfirstlane(s_split[r]);
+    const int rem = item - __builtin_amdgcn_readfirstlane(s_first[r]);
+    const int h = rem / ns;
+    const int b = __builtin_amdgcn_readfirstlane(s_list[r]);
+    // A zero the compiler cannot see through: without it everything the body derives from the thread index is
+    // computed once in front of this loop and kept in registers across the body.
+    int zero = 0;
+    asm volatile("" : "+s"(zero));
+    dense_body<EXPOSE, PAGED, true, false, false>(a, ns, rem - h * ns, h, b, zero);
+  }
 }
 
 // Where a fast-step workgroup's result goes.
@@ -1636,6 +1768,11 @@ hipError_t launch_trigger(const int32_t* last_token, const uint32_t* bitmap, int
 
 template <bool PAGED>
 static void launch_dense_t(const AttnArgs& a, dim3 grid, hipStream_t s) {
+  if (a.item_batch > 0) {  // ragged step (logits always exposed, never the big stash, never evidence-only)
+    if (a.with_knorm) hipLaunchKernelGGL((attn_dense_items_kernel<2, PAGED>), grid, dim3(kAttnThreads), 0, s, a);
+    else hipLaunchKernelGGL((attn_dense_items_kernel<1, PAGED>), grid, dim3(kAttnThreads), 0, s, a);
+    return;
+  }
   if constexpr (!PAGED) {
     if (a.dense_wide && a.G <= 8 && !a.with_knorm && !a.no_v) {
       if (a.logits != nullptr && a.big_stash) hipLaunchKernelGGL((attn_dense_kernel<1, false, true, false, true>), grid, dim3(kAttnThreads), 0, s, a);
@@ -1660,7 +1797,8 @@ static void launch_dense_t(const AttnArgs& a, dim3 grid, hipStream_t s) {
     hipLaunchKernelGGL((attn_dense_kernel<0, PAGED>), grid, dim3(kAttnThreads), 0, s, a);
 }
 hipError_t launch_attn_dense(const AttnArgs& a, int B, int n_slots, hipStream_t s) {
-  const dim3 grid(n_slots, a.Hkv, B);
+  // ragged step: a fixed number of workgroups (no more than there are cells)
+  const dim3 grid = a.item_batch > 0 ? dim3((unsigned)min((int64_t)n_slots * a.Hkv * B, (int64_t)a.item_wgs)) : dim3(n_slots, a.Hkv, B);
   if (a.table != nullptr) launch_dense_t<true>(a, grid, s);
   else launch_dense_t<false>(a, grid, s);
   return hipGetLastError();

@@ -63,6 +63,8 @@ __device__ __forceinline__ void window_view(const int32_t* q_len, int b, int L_e
   }
 }
 
+constexpr int kListCap = 1024;  // sequences the ragged step's dense launch can plan for on the device (see attn_dense_items_kernel)
+
 struct Workspace {
   float* part;        // [B*Hq][kSlotCap][kPartStride]
   float* logits;      // [B*Hq][ld_pos]   J-relative positions
@@ -71,6 +73,7 @@ struct Workspace {
   uint32_t* hist1;    // [B*Hkv][kHist1Bins]
   uint32_t* state;    // [B*Hkv][kStateWords]
   uint32_t* segcnt;   // [B*Hkv][n_seg_cap]  keys of each segment above the threshold bin
+  int32_t* seq_splits;  // [B]  ragged step: splits per (sequence, KV head) the dense launch chose for each slow sequence
   float2* jstat;      // [B*Hq]  J-only softmax statistics of each query head (slow step)
   float* prior;       // [B*Hkv][ld]  full Selector: unnormalised prior pi_kn * pi_pos
   float* znms;        // [B*Hkv][ld]  full Selector: log2-domain score after Soft-NMS
@@ -95,6 +98,10 @@ struct AttnArgs {
   const int32_t* ctx_len;
   int32_t ms, fs;                // strides of the per-sequence entries: ctx_len / recent_start in int32, is_slow in bytes
                                  //   (1, 1 for plain arrays; 4, 16 when they are fields of a packed sfi_step_desc array)
+  int32_t item_batch;            // dense mode, ragged step: > 0 = the launch is a fixed number of workgroups that deal the
+                                 //   slow sequences' work items among themselves (see slow_list); the batch size
+  int32_t item_wgs;              //   ... and that number of workgroups
+  int32_t* seq_splits;           //   ... and where the splits chosen for each slow sequence are left, [batch]
   const int32_t* q_len;          // dense mode, nullptr or: rows each sequence's query sees (window query under the causal mask)
   const int32_t* recent_start;   // gather mode
   const int32_t* sel_idx;        // gather mode
@@ -185,6 +192,7 @@ struct SelArgs {
   uint32_t* segcnt;
   const int32_t* ctx_len;
   const int32_t* q_len;    // accumulation of a window query under the causal mask (see window_view), else nullptr
+  const int32_t* seq_splits;  // ragged step: splits the dense launch chose per sequence (n_jrec = 4 x that), else nullptr
   int32_t ms, fs;          // strides of ctx_len (int32) and is_slow (bytes), see AttnArgs
   const uint8_t* is_slow;
   int32_t* sel_idx;

@@ -115,12 +115,18 @@ __device__ __forceinline__ Problem problem_of(const SelArgs& a, int b) {
 // logits first carries G extra workgroups per (b, h); each merges the dense kernel's records of one
 // query head into the attention output (J records of all waves, then one record per wave that owned
 // sink / recent tiles).
+// J records per query head of sequence b: one per wave of the dense launch's workgroups of that sequence (the ragged
+// step's dense launch chooses the splits per sequence on the device and leaves them in the workspace)
+__device__ __forceinline__ int n_jrec_of(const SelArgs& a, int b) {
+  return a.seq_splits != nullptr ? a.seq_splits[b] * kWaves : a.n_jrec;
+}
 __device__ __forceinline__ void merge_head(const SelArgs& a, int b, int h, int g) {
+  const int n_jrec = n_jrec_of(a, b);
   const int L = min(max(a.ctx_len[b * a.ms], 0), a.len_cap);
   const int nS = min(a.n_sink, L);
   const int rs = min(max(a.n_sink, L - a.recent), L);
   const int nTS = (nS + (L - rs) + 31) / 32;
-  const int n_slots = a.n_jrec + min(a.n_jrec, nTS);
+  const int n_slots = n_jrec + min(n_jrec, nTS);
   merge_records(a.part, a.merge_out, b * a.Hq + h * a.G + g, n_slots, nullptr, 0, a.G, a.alpha, a.out_bf16 != 0);
 }
 
@@ -129,13 +135,14 @@ __device__ __forceinline__ void merge_head(const SelArgs& a, int b, int h, int g
 // most kSlotCap = 256).  sM[g] = max of y over J, sc[g] = Z^(-alpha) / G; valid after the next barrier.
 __device__ __forceinline__ void group_jstat(const SelArgs& a, int b, int h, float* sM, float* sc) {
   const int lane = threadIdx.x & 63;
+  const int n_jrec = n_jrec_of(a, b);
   for (int g = threadIdx.x >> 6; g < a.G; g += kSelThreads / 64) {
     const float* P = a.part + (int64_t)(b * a.Hq + h * a.G + g) * kSlotCap * kPartStride;
     float2 ml[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int sl = lane + 64 * i;
-      ml[i] = sl < a.n_jrec ? *reinterpret_cast<const float2*>(P + (int64_t)sl * kPartStride) : make_float2(kNeg, 0.f);
+      ml[i] = sl < n_jrec ? *reinterpret_cast<const float2*>(P + (int64_t)sl * kPartStride) : make_float2(kNeg, 0.f);
     }
     float M = fmaxf(fmaxf(ml[0].x, ml[1].x), fmaxf(ml[2].x, ml[3].x));
 #pragma unroll

@@ -992,3 +992,60 @@ def test_top_k_over_several_segments(oracle, case):
         assert r.sfi.sfi_device_status(r.ctx.handle) == 0
     finally:
         r.close()
+
+
+@pytest.mark.parametrize("paged", [False, True])
+def test_ragged_step_planned_on_the_device(oracle, paged):
+    """sfi_mixed_step's dense launch plans itself on the device (sfi_set_mixed_plan, default): the slow sequences and
+    their splits by length.  Eleven ragged sequences from empty to the whole cache, every kind of mix -- none slow, one (the
+    longest, the shortest, an empty one), several, all -- against the oracle per sequence, and bit for bit against
+    the launch with one workgroup per cell of the batch (same records in other slots, merged in a fixed order: the
+    outputs may differ in the last bits, the index sets may not)."""
+    import torch
+    import paper_2603_12038_amd as sfi
+
+    w = syn.make_serving(steps=2, B=11, Hq=16, Hkv=2, len_lo=300, len_hi=9000, budget=96, recent=32)
+    w.L0 = np.array([int(w.L_alloc) - 4, 0, 33, 4100, 36, 1500, 7000, 5, 610, 0, 2800], np.int32)
+    r = Runner(w, page_size=16 if paged else 0)
+    try:
+        B, h = w.B, r.ctx.handle
+        ctx0, rs0 = w.ctx_len(0), w.recent_start(0)
+        ctx_d, rs_d = i32_dev(ctx0), i32_dev(rs0)
+        q0 = w.q(0)
+        sel_d = torch.full((B, w.Hkv, w.budget), -7, dtype=torch.int32, device="cuda")
+        nsel_d = torch.full((B, w.Hkv), -7, dtype=torch.int32, device="cuda")
+        ones = torch.ones(B, dtype=torch.uint8, device="cuda")
+        _step(f"ragged step planned on the device (paged={paged}): all slow")
+        sfi.sfi_mixed_step(h, to_dev(q0), r.K, r.V, ones, ctx_d, rs_d, 0, w.budget, r.out, sel_d, nsel_d)
+        torch.cuda.synchronize()
+        sel0, nsel0 = sel_d.cpu().numpy().copy(), nsel_d.cpu().numpy().copy()
+        ref_dense = oracle.dense(q0, w.K, w.V, ctx0)
+        check_out(r.out.float().cpu().numpy(), ref_dense)
+        sel_ref, nsel_ref, z = oracle.selector(q0, w.K, ctx0, w.budget, w.n_sink, w.recent)
+        check_selection(sel0, nsel0, sel_ref, nsel_ref, z, ctx0, w.n_sink, w.recent, w.budget)
+        ref_sparse = oracle.sparse(q0, w.K, w.V, sel0, nsel0, rs0, ctx0, w.n_sink)
+        mixes = [[], [0], [2], [1], [7, 9], [0, 6], [3, 5, 8, 10], [0, 1, 2, 3, 4], list(range(B))]
+        for mix in mixes:
+            _step(f"ragged step planned on the device (paged={paged}): slow {mix}")
+            fl = np.zeros(B, np.uint8)
+            fl[mix] = 1
+            got = {}
+            for plan in (1, 0):
+                sfi.sfi_set_mixed_plan(h, plan)
+                sel_d.copy_(torch.from_numpy(sel0)); nsel_d.copy_(torch.from_numpy(nsel0))
+                r.out.fill_(float("nan"))
+                sfi.sfi_mixed_step(h, to_dev(q0), r.K, r.V, torch.from_numpy(fl).cuda(), ctx_d, rs_d, 0, w.budget, r.out, sel_d, nsel_d)
+                torch.cuda.synchronize()
+                got[plan] = (r.out.float().cpu().numpy().copy(), sel_d.cpu().numpy().copy(), nsel_d.cpu().numpy().copy())
+            out, sel, nsel = got[1]
+            for b in range(B):
+                check_out(out[b], ref_dense[b] if fl[b] else ref_sparse[b])
+            assert (sel == got[0][1]).all() and (nsel == got[0][2]).all()
+            assert (sel == sel0).all() and (nsel == nsel0).all()   # the same evidence: the same sets, slow or frozen
+            np.testing.assert_allclose(out, got[0][0], rtol=0, atol=2e-3 * max(1e-30, float(np.abs(ref_dense).max())))
+        assert sfi.sfi_device_status(h) == 0
+        with pytest.raises(sfi.SfiError):
+            sfi.sfi_set_mixed_plan(h, 2)
+    finally:
+        sfi.sfi_set_mixed_plan(r.ctx.handle, 1)
+        r.close()
