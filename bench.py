@@ -244,7 +244,7 @@ def bench_serving(args):
     # pair, about 2 us above the trace's duration) against the rows it has to read
     by_slow = []
     order = np.argsort(w.L0)
-    for which in ([], [order[B // 2]], [order[-1]], [order[3], order[-3]], list(order[::8]), list(order[::4])):
+    for which in ([], [order[B // 2]], [order[-1]], [order[3], order[-3]], list(order[::8]), list(order[::4]), list(order[::2]), list(order)):
         fl = np.zeros(B, np.uint8)
         fl[[int(b) for b in which]] = 1
         fd = torch.from_numpy(fl).to(dev)
