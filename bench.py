@@ -830,7 +830,10 @@ def bench_mix(args):
         "kernels": {
             "dense_attn": {"us": slow_ms[0] * 1e3, "kv_bytes": dense_bytes, "GBps": dense_gbs,
                            "frac_of_8TBps": dense_gbs / HBM_PEAK_GBS, "us_is": "event pair around the launch (about 2 us above the trace's duration)",
-                           "memory_skeleton_us": dense_floor},
+                           "memory_skeleton_us": dense_floor,
+                           # what this machine streams when nothing is computed (the whole-line skeleton), beside the nominal peak
+                           "streaming_read_ceiling_GBps": dense_bytes / (dense_floor["whole_line_k_us"] * 1e-6) / 1e9 if dense_floor else None,
+                           "frac_of_streaming_read_ceiling": dense_gbs / (dense_bytes / (dense_floor["whole_line_k_us"] * 1e-6) / 1e9) if dense_floor else None},
             f"{fast_kernel}_attn": {"us": fast_ms[0] * 1e3, "kv_bytes": fast_bytes, "GBps": fast_gbs,
                             "frac_of_8TBps": fast_gbs / HBM_PEAK_GBS,
                             "us_with_an_event_pair_per_launch": fast_bracketed_us},
