@@ -917,7 +917,7 @@ int mixed_step_on(sfi_ctx* x, const void* q, const void* K, const void* V, const
   const bool fast_done = f.n_split == 1 || f.out_merge != nullptr;
   const bool merge_in_score = fast_done;
   // The dense launch plans itself on the device (one workgroup per compute unit, splits per slow sequence in proportion to
-  // its length, see slow_list) where its records are merged by the scoring launch, which reads the plan back.
+  // its length: attn_dense_items_kernel) where its records are merged by the scoring launch, which reads the plan back.
   const bool planned = x->mixed_plan != 0 && merge_in_score && x->cfg.batch <= kListCap;
   if (planned) {
     d.item_batch = x->cfg.batch;

@@ -4,7 +4,8 @@
 // share it, logits l_g(j) = scale * <q_g, k_j> over a list of positions, and the flash-style
 // partial  (m, sum_j e^{l-m}, sum_j e^{l-m} v_j)  of a share of that list, in the log2 domain
 // (y = log2(e) * l, weights 2^(y - m)).
-//   dense  kernel (slow step): the waves of n_split workgroups share the tiles of the allowed set
+//   dense  kernel (slow step; in the ragged step with the launch planned on the device, attn_dense_items_kernel):
+//          the waves of n_split workgroups share the tiles of the allowed set
 //          J = [n_sink, L - recent), for which y is also exposed to the Selector (Eq. window_logits,
 //          W = 1), followed by the tiles of the sink and recent rows, which the Selector never ranks
 //          (Eq. allowed_set).  A wave keeps the two kinds in separate records, so the J-only softmax
@@ -568,7 +569,8 @@ struct ListWalk {
 // PAGED: K / V are block pools addressed through the sequence's block table.
 // EXPOSE 1: also write y over J for the Selector; 2: y and the squared key norms.
 // BIG: twice the logits stash per wave, which leaves room for one workgroup per compute unit only
-// (launches where every sequence is dense run one per unit anyway; the mixed step keeps two).
+// (launches where every sequence is dense, and the ragged step's planned launch, run one per unit anyway; the ragged
+// step's launch with a workgroup per cell keeps two).
 // NOV: evidence only -- no V row is read, no P V product, the records carry the softmax statistics alone.
 template <int EXPOSE, bool PAGED, bool BIG = false, bool NOV = false, bool WIDE = false>
 __device__ __forceinline__ void dense_body(const AttnArgs& a, const int n_split, const int slot, const int h, const int b,

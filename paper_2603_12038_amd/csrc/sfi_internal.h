@@ -99,7 +99,7 @@ struct AttnArgs {
   int32_t ms, fs;                // strides of the per-sequence entries: ctx_len / recent_start in int32, is_slow in bytes
                                  //   (1, 1 for plain arrays; 4, 16 when they are fields of a packed sfi_step_desc array)
   int32_t item_batch;            // dense mode, ragged step: > 0 = the launch is a fixed number of workgroups that deal the
-                                 //   slow sequences' work items among themselves (see slow_list); the batch size
+                                 //   slow sequences' cells among themselves (attn_dense_items_kernel); the batch size
   int32_t item_wgs;              //   ... and that number of workgroups
   int32_t* seq_splits;           //   ... and where the splits chosen for each slow sequence are left, [batch]
   const int32_t* q_len;          // dense mode, nullptr or: rows each sequence's query sees (window query under the causal mask)
