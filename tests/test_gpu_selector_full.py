@@ -260,3 +260,51 @@ def test_windowed_evidence_under_the_causal_mask(oracle, mode, alpha, W, recent)
         assert r.sfi.sfi_device_status(r.ctx.handle) == 0
     finally:
         r.close()
+
+
+@pytest.mark.parametrize("paged", [False, True])
+def test_full_selector_in_the_ragged_step(oracle, paged):
+    """Mode 1 inside sfi_mixed_step (Sec. 4.2's ragged step: per-sequence modes known only on the device): ragged
+    sequences from empty to the whole cache; for each mix of slow and fast sequences, with the dense launch planned on
+    the device and with one workgroup per cell, the slow sequences' outputs and index sets against the oracle's dense
+    attention and Algorithm 2 (within the band), the fast sequences' outputs against the oracle's sparse attention on
+    the sets they came in with, and their sets untouched."""
+    import torch
+    import paper_2603_12038_amd as sfi
+    from helpers import i32_dev, to_dev
+
+    sp, d = _params()
+    w = syn.make_serving(steps=2, B=7, Hq=16, Hkv=2, len_lo=300, len_hi=6000, budget=96, recent=32)
+    w.L0 = np.array([int(w.L_alloc) - 4, 0, 33, 4100, 1500, 5, 2800], np.int32)
+    r = Runner(w, selector=d, alpha=sp.alpha, page_size=16 if paged else 0)
+    try:
+        B, h = w.B, r.ctx.handle
+        ctx0, rs0, q0 = w.ctx_len(0), w.recent_start(0), w.q(0)
+        ctx_d, rs_d = i32_dev(ctx0), i32_dev(rs0)
+        ref_dense = oracle.dense(q0, w.K, w.V, ctx0)
+        sel_ref, nsel_ref, z = oracle.selector(q0, w.K, ctx0, w.budget, w.n_sink, w.recent, sp=sp)
+        ref_sparse = oracle.sparse(q0, w.K, w.V, sel_ref, nsel_ref, rs0, ctx0, w.n_sink)
+        sel_d = torch.empty((B, w.Hkv, w.budget), dtype=torch.int32, device="cuda")
+        nsel_d = torch.empty((B, w.Hkv), dtype=torch.int32, device="cuda")
+        for plan in (1, 0):
+            sfi.sfi_set_mixed_plan(h, plan)
+            for mix in ([], [0], [1], [3, 5], [0, 2, 4, 6], list(range(B))):
+                _step(f"mode 1 in the ragged step (paged={paged}, planned={plan}): slow {mix}")
+                fl = np.zeros(B, np.uint8)
+                fl[mix] = 1
+                sel_d.copy_(torch.from_numpy(sel_ref)); nsel_d.copy_(torch.from_numpy(nsel_ref))  # what the fast ones read
+                r.out.fill_(float("nan"))
+                sfi.sfi_mixed_step(h, to_dev(q0), r.K, r.V, torch.from_numpy(fl).cuda(), ctx_d, rs_d, 0, w.budget, r.out, sel_d, nsel_d)
+                torch.cuda.synchronize()
+                out, sel, nsel = r.out.float().cpu().numpy(), sel_d.cpu().numpy(), nsel_d.cpu().numpy()
+                for b in range(B):
+                    check_out(out[b], ref_dense[b] if fl[b] else ref_sparse[b])
+                    if not fl[b]:
+                        assert (sel[b] == sel_ref[b]).all() and (nsel[b] == nsel_ref[b]).all()
+                if mix:
+                    check_selection(sel[mix], nsel[mix], sel_ref[mix], nsel_ref[mix], z[mix], ctx0[mix], w.n_sink, w.recent,
+                                    w.budget, band=FULL_BAND)
+        assert sfi.sfi_device_status(h) == 0
+    finally:
+        sfi.sfi_set_mixed_plan(r.ctx.handle, 1)
+        r.close()
