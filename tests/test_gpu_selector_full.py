@@ -262,9 +262,9 @@ def test_windowed_evidence_under_the_causal_mask(oracle, mode, alpha, W, recent)
         r.close()
 
 
-@pytest.mark.parametrize("paged", [False, True])
-def test_full_selector_in_the_ragged_step(oracle, paged):
-    """Mode 1 inside sfi_mixed_step (Sec. 4.2's ragged step: per-sequence modes known only on the device): ragged
+@pytest.mark.parametrize("paged,mode,alpha", [(False, 1, 1.0), (True, 1, 1.0), (False, 1, 0.5), (False, 0, 0.5)])
+def test_full_selector_in_the_ragged_step(oracle, paged, mode, alpha):
+    """Mode 1 (and the power mean with alpha < 1 in either mode) inside sfi_mixed_step (Sec. 4.2's ragged step: per-sequence modes known only on the device): ragged
     sequences from empty to the whole cache; for each mix of slow and fast sequences, with the dense launch planned on
     the device and with one workgroup per cell, the slow sequences' outputs and index sets against the oracle's dense
     attention and Algorithm 2 (within the band), the fast sequences' outputs against the oracle's sparse attention on
@@ -273,7 +273,9 @@ def test_full_selector_in_the_ragged_step(oracle, paged):
     import paper_2603_12038_amd as sfi
     from helpers import i32_dev, to_dev
 
-    sp, d = _params()
+    sp, d = _params(alpha=alpha)
+    if mode == 0:  # the power mean alone (Eq. selector_mu with alpha < 1), ranked without the refinements
+        sp, d = dataclasses.replace(sp, mode=0), None
     w = syn.make_serving(steps=2, B=7, Hq=16, Hkv=2, len_lo=300, len_hi=6000, budget=96, recent=32)
     w.L0 = np.array([int(w.L_alloc) - 4, 0, 33, 4100, 1500, 5, 2800], np.int32)
     r = Runner(w, selector=d, alpha=sp.alpha, page_size=16 if paged else 0)
@@ -289,7 +291,7 @@ def test_full_selector_in_the_ragged_step(oracle, paged):
         for plan in (1, 0):
             sfi.sfi_set_mixed_plan(h, plan)
             for mix in ([], [0], [1], [3, 5], [0, 2, 4, 6], list(range(B))):
-                _step(f"mode 1 in the ragged step (paged={paged}, planned={plan}): slow {mix}")
+                _step(f"mode {mode}, alpha {alpha} in the ragged step (paged={paged}, planned={plan}): slow {mix}")
                 fl = np.zeros(B, np.uint8)
                 fl[mix] = 1
                 sel_d.copy_(torch.from_numpy(sel_ref)); nsel_d.copy_(torch.from_numpy(nsel_ref))  # what the fast ones read
